@@ -1,0 +1,137 @@
+"""CPU oracle for the Picasso decimation path -- TEST INFRASTRUCTURE ONLY.
+
+ctypes front end of ``picasso_oracle.cpp`` (host pointers, numpy arrays).
+Nothing in the product package imports this; only tests, the smoke check and
+the benchmark's cpu_baseline leg do.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "picasso_oracle.cpp")
+_LIB = os.path.join(_HERE, "libpicasso_oracle.so")
+_lib = None
+
+OK = 0
+WARN_BUDGET_UNMET = 1
+ERR_INVALID_ARG = -1
+ERR_BAD_INDEX = -2
+ERR_NONFINITE = -3
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with strict IEEE fp32 semantics (no contraction)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["g++", "-O2", "-std=c++17", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared",
+               "-o", _LIB, _SRC]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.picasso_oracle_cost_key.restype = ctypes.c_uint32
+        _lib.picasso_oracle_cost_key.argtypes = [ctypes.c_float]
+    return _lib
+
+
+def _p(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def facet_quadrics(verts, facets):
+    verts, facets = _f32(verts), _i32(facets)
+    out = np.empty((facets.shape[0], 10), np.float32)
+    lib().picasso_oracle_facet_quadrics(_p(verts), verts.shape[0], _p(facets), facets.shape[0], _p(out))
+    return out
+
+
+def vertex_quadrics(verts, facets):
+    verts, facets = _f32(verts), _i32(facets)
+    out = np.empty((verts.shape[0], 10), np.float32)
+    lib().picasso_oracle_vertex_quadrics(_p(verts), verts.shape[0], _p(facets), facets.shape[0], _p(out))
+    return out
+
+
+def edges(facets):
+    facets = _i32(facets)
+    out = np.empty((max(1, 3 * facets.shape[0]), 2), np.int32)
+    n = ctypes.c_int32(0)
+    lib().picasso_oracle_edges(_p(facets), facets.shape[0], _p(out), ctypes.byref(n))
+    return out[: n.value].copy()
+
+
+def edge_costs(pos, Q, edge_list):
+    pos, Q, edge_list = _f32(pos), _f32(Q), _i32(edge_list)
+    E = edge_list.shape[0]
+    cost = np.empty(E, np.float32)
+    key = np.empty(E, np.uint32)
+    lib().picasso_oracle_edge_costs(_p(pos), _p(Q), _p(edge_list), E, _p(cost), _p(key))
+    return cost, key
+
+
+def cost_key(c: float) -> int:
+    return int(lib().picasso_oracle_cost_key(ctypes.c_float(c)))
+
+
+def select(edge_list, key, n_verts, n_remove):
+    edge_list = _i32(edge_list)
+    key = np.ascontiguousarray(key, dtype=np.uint32)
+    sel = np.zeros(edge_list.shape[0], np.uint8)
+    n = lib().picasso_oracle_select(_p(edge_list), _p(key), edge_list.shape[0], int(n_verts), int(n_remove), _p(sel))
+    return sel.astype(bool), n
+
+
+def decimate(verts, facets, target_nv, max_rounds=-1, return_quadrics=False):
+    """Returns dict(status, verts, facets, cluster_id, rounds[, quadrics])."""
+    verts, facets = _f32(verts), _i32(facets).reshape(-1, 3)
+    N, F = verts.shape[0], facets.shape[0]
+    vo = np.zeros((max(N, 1), 3), np.float32)
+    fo = np.zeros((max(F, 1), 3), np.int32)
+    cid = np.zeros(max(N, 1), np.int32)
+    qo = np.zeros((max(N, 1), 10), np.float32)
+    nv, nf, rounds = ctypes.c_int32(0), ctypes.c_int32(0), ctypes.c_int32(0)
+    st = lib().picasso_oracle_decimate_rounds(
+        _p(verts), N, _p(facets), F, int(target_nv), int(max_rounds), _p(vo), _p(fo), _p(cid),
+        ctypes.byref(nv), ctypes.byref(nf), ctypes.byref(rounds), _p(qo))
+    if st < 0:
+        return dict(status=st)
+    res = dict(status=st, verts=vo[: nv.value].copy(), facets=fo[: nf.value].copy(), cluster_id=cid[:N].copy(),
+               rounds=rounds.value)
+    if return_quadrics:
+        res["quadrics"] = qo[: nv.value].copy()
+    return res
+
+
+def decimate_batch(verts, facets, nv_in, nf_in, target_nv):
+    verts, facets = _f32(verts), _i32(facets).reshape(-1, 3)
+    nv_in, nf_in, target_nv = _i32(nv_in), _i32(nf_in), _i32(target_nv)
+    B = nv_in.shape[0]
+    N, F = verts.shape[0], facets.shape[0]
+    vo = np.zeros((max(N, 1), 3), np.float32)
+    fo = np.zeros((max(F, 1), 3), np.int32)
+    cid = np.zeros(max(N, 1), np.int32)
+    nvo = np.zeros(B, np.int32)
+    nfo = np.zeros(B, np.int32)
+    st = lib().picasso_oracle_decimate_batch(B, _p(verts), _p(facets), _p(nv_in), _p(nf_in), _p(target_nv),
+                                             _p(vo), _p(fo), _p(cid), _p(nvo), _p(nfo))
+    if st < 0:
+        return dict(status=st)
+    return dict(status=st, verts=vo[: int(nvo.sum())].copy(), facets=fo[: int(nfo.sum())].copy(),
+                cluster_id=cid[:N].copy(), nv=nvo, nf=nfo)

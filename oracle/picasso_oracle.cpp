@@ -1,0 +1,405 @@
+// picasso_oracle.cpp -- TEST INFRASTRUCTURE, NOT THE PRODUCT.
+//
+// A plain, slow, single-threaded CPU statement of the round-based QEM mesh
+// decimation of the Picasso paper (Sec. 3, Algorithm 2 "Fast GPU-accelerated
+// mesh simplification"; supplementary section "Quadric error computation").
+// It exists so that the HIP path can be compared against something written
+// directly from the paper.  Only tests, the smoke check and the benchmark's
+// cpu_baseline leg may call it.  It shares no code, header, table or helper
+// with the HIP library.
+//
+// Build:  g++ -O2 -std=c++17 -ffp-contract=off -fPIC -shared
+// (no fast-math, no FMA contraction: every + - * / sqrt below is one IEEE
+//  binary32 operation rounded to nearest-even, in the order written).
+//
+// Readings of the paper taken here (the paper is silent or ambiguous on them):
+//  * Alg. 2 line 11 (absorbing un-paired vertices into a neighbouring cluster)
+//    is not applied: a round contracts disjoint vertex PAIRS only, so that the
+//    vertex budget of lines 4-8 is met exactly.
+//  * Several runs of the core algorithm (Sec. 3: "running the core algorithm
+//    multiple times") carry the accumulated quadrics forward,
+//    Q_C = sum of member vertex quadrics (supplementary, cluster quadric eq.);
+//    facet quadrics are computed once from the input mesh.
+//  * Contraction target = mean of the two current positions (supplementary,
+//    Eq. "average_optimal" with |C| = 2), also used as the point at which the
+//    pair's cost is evaluated.
+//  * Facet quadrics are unweighted with unit normals; a facet with zero area or
+//    a repeated index contributes the zero quadric.
+//  * Ties in cost are broken by edge index; edge index = rank of (lo,hi) in
+//    ascending lexicographic order.  Costs are compared through their
+//    bit patterns mapped to an order-preserving unsigned key (-0 < +0).
+//  * No consistency checks (Sec. 3, last paragraph).
+//  * Facets that collapse (two equal indices) are dropped; of several facets
+//    with the same unordered vertex triple the first in list order survives.
+//  * The representative of a contracted pair is the smaller index; survivors
+//    are renumbered in ascending order; every cluster stays an output vertex.
+//
+// Pins: see tests/test_oracle_*.py (closed forms, brute force, invariants,
+// hand-worked fixtures under tests/golden/).  The whole multi-round pipeline has
+// no printed worked example in the paper (its Fig. 2 carries no numbers):
+// beyond those pins, parity of the full pipeline is "parity unpinned".
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <map>
+#include <set>
+#include <array>
+#include <utility>
+#include <vector>
+
+namespace {
+
+constexpr int OK = 0;
+constexpr int WARN_BUDGET_UNMET = 1;
+constexpr int ERR_INVALID_ARG = -1;
+constexpr int ERR_BAD_INDEX = -2;
+constexpr int ERR_NONFINITE = -3;
+
+// Quadric Q = (A, b, c) stored as a00 a01 a02 a11 a12 a22 b0 b1 b2 c.
+struct Quadric {
+    float q[10];
+};
+
+// Plane quadric of one facet: Q = (n n^T, d n, d^2), plane n.x + d = 0
+// (supplementary, "Quadric error computation", first definition).
+Quadric facet_quadric(const float* V, int i0, int i1, int i2) {
+    Quadric Q;
+    for (float& x : Q.q) x = 0.0f;
+    if (i0 == i1 || i1 == i2 || i0 == i2) return Q;
+    const float* p0 = V + 3 * (int64_t)i0;
+    const float* p1 = V + 3 * (int64_t)i1;
+    const float* p2 = V + 3 * (int64_t)i2;
+    float ax = p1[0] - p0[0], ay = p1[1] - p0[1], az = p1[2] - p0[2];
+    float bx = p2[0] - p0[0], by = p2[1] - p0[1], bz = p2[2] - p0[2];
+    float nx = ay * bz - az * by;
+    float ny = az * bx - ax * bz;
+    float nz = ax * by - ay * bx;
+    float len = std::sqrt((nx * nx + ny * ny) + nz * nz);
+    if (len == 0.0f) return Q;
+    nx = nx / len;
+    ny = ny / len;
+    nz = nz / len;
+    float d = -((nx * p0[0] + ny * p0[1]) + nz * p0[2]);
+    Q.q[0] = nx * nx;
+    Q.q[1] = nx * ny;
+    Q.q[2] = nx * nz;
+    Q.q[3] = ny * ny;
+    Q.q[4] = ny * nz;
+    Q.q[5] = nz * nz;
+    Q.q[6] = d * nx;
+    Q.q[7] = d * ny;
+    Q.q[8] = d * nz;
+    Q.q[9] = d * d;
+    return Q;
+}
+
+// Vertex quadric = sum of the quadrics of adjacent facets (supplementary,
+// vertex quadric eq.), accumulated left to right from +0 in ascending
+// (facet, corner) order.
+void vertex_quadrics(const float* V, int N, const int32_t* F, int nF, std::vector<Quadric>& Qv) {
+    Qv.assign(N, Quadric{});
+    for (int v = 0; v < N; ++v)
+        for (float& x : Qv[v].q) x = 0.0f;
+    for (int f = 0; f < nF; ++f) {
+        Quadric Qf = facet_quadric(V, F[3 * f], F[3 * f + 1], F[3 * f + 2]);
+        for (int c = 0; c < 3; ++c) {
+            Quadric& acc = Qv[F[3 * f + c]];
+            for (int k = 0; k < 10; ++k) acc.q[k] = acc.q[k] + Qf.q[k];
+        }
+    }
+}
+
+// Candidate pairs = mesh edges only (Alg. 2 line 1): the distinct unordered
+// sides of the current facets, ascending by (lo, hi).
+void unique_edges(const int32_t* F, int nF, std::vector<std::pair<int32_t, int32_t>>& E) {
+    E.clear();
+    for (int f = 0; f < nF; ++f) {
+        for (int c = 0; c < 3; ++c) {
+            int32_t a = F[3 * f + c], b = F[3 * f + (c + 1) % 3];
+            if (a == b) continue;
+            E.emplace_back(std::min(a, b), std::max(a, b));
+        }
+    }
+    std::sort(E.begin(), E.end());
+    E.erase(std::unique(E.begin(), E.end()), E.end());
+}
+
+// Quadric error of the pair's summed quadric at the pair's mean position
+// (Alg. 2 line 2; supplementary Q(x) = x^T A x + 2 b^T x + c).
+float pair_cost(const Quadric& Qu, const Quadric& Qv, const float* pu, const float* pv) {
+    float s[10];
+    for (int k = 0; k < 10; ++k) s[k] = Qu.q[k] + Qv.q[k];
+    float mx = (pu[0] + pv[0]) * 0.5f;
+    float my = (pu[1] + pv[1]) * 0.5f;
+    float mz = (pu[2] + pv[2]) * 0.5f;
+    float t0 = (s[0] * mx + s[1] * my) + s[2] * mz;
+    float t1 = (s[1] * mx + s[3] * my) + s[4] * mz;
+    float t2 = (s[2] * mx + s[4] * my) + s[5] * mz;
+    float xAx = (mx * t0 + my * t1) + mz * t2;
+    float bx = (s[6] * mx + s[7] * my) + s[8] * mz;
+    return (xAx + 2.0f * bx) + s[9];
+}
+
+// Unsigned key whose integer order is the numeric order of the floats
+// (negative values: all bits flipped; others: sign bit set).
+uint32_t cost_key(float c) {
+    uint32_t u;
+    std::memcpy(&u, &c, 4);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// Alg. 2 lines 3-10: walk the pairs in ascending (key, index) order; a pair
+// forms a new cluster iff neither end is in a cluster yet and fewer than
+// n_remove pairs have been formed.
+int greedy_pairs(const std::vector<std::pair<int32_t, int32_t>>& E, const std::vector<uint32_t>& key,
+                 int N, int64_t n_remove, std::vector<uint8_t>& selected) {
+    const int nE = (int)E.size();
+    std::vector<int32_t> order(nE);
+    for (int i = 0; i < nE; ++i) order[i] = i;
+    std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return key[a] < key[b]; });
+    std::vector<uint8_t> in_cluster(N, 0);
+    selected.assign(nE, 0);
+    int64_t n_r = 0;
+    for (int r = 0; r < nE; ++r) {
+        int e = order[r];
+        int32_t u = E[e].first, v = E[e].second;
+        if (!in_cluster[u] && !in_cluster[v] && n_r < n_remove) {
+            selected[e] = 1;
+            in_cluster[u] = in_cluster[v] = 1;
+            ++n_r;
+        }
+    }
+    return (int)n_r;
+}
+
+struct Mesh {
+    std::vector<float> pos;       // [nv,3]
+    std::vector<Quadric> Q;       // [nv]
+    std::vector<int32_t> facets;  // [nf,3]
+    int nv() const { return (int)Q.size(); }
+    int nf() const { return (int)(facets.size() / 3); }
+};
+
+// One run of the core algorithm on the current mesh.  Returns the number of
+// contracted pairs; label[] (one entry per ORIGINAL vertex) is updated.
+int one_round(Mesh& M, int target_nv, std::vector<int32_t>& label) {
+    const int nv = M.nv();
+    std::vector<std::pair<int32_t, int32_t>> E;
+    unique_edges(M.facets.data(), M.nf(), E);
+    std::vector<uint32_t> key(E.size());
+    for (size_t e = 0; e < E.size(); ++e) {
+        int32_t u = E[e].first, v = E[e].second;
+        key[e] = cost_key(pair_cost(M.Q[u], M.Q[v], &M.pos[3 * (size_t)u], &M.pos[3 * (size_t)v]));
+    }
+    std::vector<uint8_t> sel;
+    int n_r = greedy_pairs(E, key, nv, (int64_t)nv - target_nv, sel);
+    if (n_r == 0) return 0;
+
+    // Alg. 2 lines 12-16: per cluster, summed quadric, mean position, contract.
+    std::vector<int32_t> remap(nv);
+    for (int w = 0; w < nv; ++w) remap[w] = w;
+    for (size_t e = 0; e < E.size(); ++e) {
+        if (!sel[e]) continue;
+        int32_t u = E[e].first, v = E[e].second;  // u < v, u represents the pair
+        for (int k = 0; k < 3; ++k) M.pos[3 * (size_t)u + k] = (M.pos[3 * (size_t)u + k] + M.pos[3 * (size_t)v + k]) * 0.5f;
+        for (int k = 0; k < 10; ++k) M.Q[u].q[k] = M.Q[u].q[k] + M.Q[v].q[k];
+        remap[v] = u;
+    }
+
+    // facets: re-index, drop collapsed ones and later copies of the same triple
+    std::vector<int32_t> nf;
+    nf.reserve(M.facets.size());
+    std::set<std::array<int32_t, 3>> seen;
+    for (int f = 0; f < M.nf(); ++f) {
+        int32_t a = remap[M.facets[3 * f]], b = remap[M.facets[3 * f + 1]], c = remap[M.facets[3 * f + 2]];
+        if (a == b || b == c || a == c) continue;
+        std::array<int32_t, 3> t{a, b, c};
+        std::sort(t.begin(), t.end());
+        if (!seen.insert(t).second) continue;
+        nf.push_back(a);
+        nf.push_back(b);
+        nf.push_back(c);
+    }
+
+    // survivors renumbered ascending
+    std::vector<int32_t> newid(nv, -1);
+    int cnt = 0;
+    for (int w = 0; w < nv; ++w)
+        if (remap[w] == w) newid[w] = cnt++;
+    Mesh out;
+    out.pos.resize(3 * (size_t)cnt);
+    out.Q.resize(cnt);
+    for (int w = 0; w < nv; ++w) {
+        if (remap[w] != w) continue;
+        for (int k = 0; k < 3; ++k) out.pos[3 * (size_t)newid[w] + k] = M.pos[3 * (size_t)w + k];
+        out.Q[newid[w]] = M.Q[w];
+    }
+    out.facets.resize(nf.size());
+    for (size_t i = 0; i < nf.size(); ++i) out.facets[i] = newid[nf[i]];
+    for (int32_t& l : label) l = newid[remap[l]];
+    M = std::move(out);
+    return n_r;
+}
+
+int check_inputs(const float* verts, int32_t N, const int32_t* facets, int32_t F, int32_t target_nv) {
+    if (!verts || N < 1 || F < 0 || (F > 0 && !facets) || target_nv < 1) return ERR_INVALID_ARG;
+    for (int64_t i = 0; i < 3 * (int64_t)F; ++i)
+        if (facets[i] < 0 || facets[i] >= N) return ERR_BAD_INDEX;
+    for (int64_t i = 0; i < 3 * (int64_t)N; ++i)
+        if (!std::isfinite(verts[i])) return ERR_NONFINITE;
+    return OK;
+}
+
+int decimate(const float* verts, int32_t N, const int32_t* facets, int32_t F, int32_t target_nv, int32_t max_rounds,
+             Mesh& M, std::vector<int32_t>& label, int32_t* rounds_out) {
+    M.pos.assign(verts, verts + 3 * (size_t)N);
+    M.facets.assign(facets, facets + 3 * (size_t)F);
+    vertex_quadrics(verts, N, facets, F, M.Q);
+    label.resize(N);
+    for (int o = 0; o < N; ++o) label[o] = o;
+    int rounds = 0, status = OK;
+    while (M.nv() > target_nv && (max_rounds < 0 || rounds < max_rounds)) {
+        if (one_round(M, target_nv, label) == 0) {
+            status = WARN_BUDGET_UNMET;
+            break;
+        }
+        ++rounds;
+    }
+    if (rounds_out) *rounds_out = rounds;
+    return status;
+}
+
+}  // namespace
+
+extern "C" {
+
+// ---- stage-level entry points (used by the pin tests and by stage parity tests)
+
+int picasso_oracle_facet_quadrics(const float* verts, int32_t N, const int32_t* facets, int32_t F, float* Qf) {
+    (void)N;
+    for (int f = 0; f < F; ++f) {
+        Quadric Q = facet_quadric(verts, facets[3 * f], facets[3 * f + 1], facets[3 * f + 2]);
+        std::memcpy(Qf + 10 * (size_t)f, Q.q, sizeof(Q.q));
+    }
+    return OK;
+}
+
+int picasso_oracle_vertex_quadrics(const float* verts, int32_t N, const int32_t* facets, int32_t F, float* Qv) {
+    std::vector<Quadric> Q;
+    vertex_quadrics(verts, N, facets, F, Q);
+    for (int v = 0; v < N; ++v) std::memcpy(Qv + 10 * (size_t)v, Q[v].q, sizeof(Q[v].q));
+    return OK;
+}
+
+// edges_out has room for 3*F pairs; returns the number of edges in *E.
+int picasso_oracle_edges(const int32_t* facets, int32_t F, int32_t* edges_out, int32_t* E) {
+    std::vector<std::pair<int32_t, int32_t>> Ed;
+    unique_edges(facets, F, Ed);
+    for (size_t e = 0; e < Ed.size(); ++e) {
+        edges_out[2 * e] = Ed[e].first;
+        edges_out[2 * e + 1] = Ed[e].second;
+    }
+    *E = (int32_t)Ed.size();
+    return OK;
+}
+
+int picasso_oracle_edge_costs(const float* pos, const float* Q, const int32_t* edges, int32_t E, float* cost,
+                              uint32_t* key) {
+    for (int e = 0; e < E; ++e) {
+        int32_t u = edges[2 * e], v = edges[2 * e + 1];
+        Quadric Qu, Qv;
+        std::memcpy(Qu.q, Q + 10 * (size_t)u, sizeof(Qu.q));
+        std::memcpy(Qv.q, Q + 10 * (size_t)v, sizeof(Qv.q));
+        float c = pair_cost(Qu, Qv, pos + 3 * (size_t)u, pos + 3 * (size_t)v);
+        if (cost) cost[e] = c;
+        if (key) key[e] = cost_key(c);
+    }
+    return OK;
+}
+
+uint32_t picasso_oracle_cost_key(float c) { return cost_key(c); }
+
+// Greedy grouping of Alg. 2 lines 3-10 on an explicit edge list with explicit keys.
+int picasso_oracle_select(const int32_t* edges, const uint32_t* key, int32_t E, int32_t N, int32_t n_remove,
+                          uint8_t* selected) {
+    std::vector<std::pair<int32_t, int32_t>> Ed(E);
+    for (int e = 0; e < E; ++e) Ed[e] = {edges[2 * e], edges[2 * e + 1]};
+    std::vector<uint32_t> k(key, key + E);
+    std::vector<uint8_t> sel;
+    int n = greedy_pairs(Ed, k, N, n_remove, sel);
+    std::memcpy(selected, sel.data(), E);
+    return n;
+}
+
+// ---- whole path
+
+// max_rounds < 0: run until the budget is met.  All pointers are host memory.
+// verts_out [N,3], facets_out [F,3], cluster_id [N] must have input capacity.
+int picasso_oracle_decimate_rounds(const float* verts, int32_t N, const int32_t* facets, int32_t F, int32_t target_nv,
+                                   int32_t max_rounds, float* verts_out, int32_t* facets_out, int32_t* cluster_id,
+                                   int32_t* nv_out, int32_t* nf_out, int32_t* rounds_out, float* quadrics_out) {
+    int st = check_inputs(verts, N, facets, F, target_nv);
+    if (st < 0) return st;
+    if (!verts_out || !facets_out || !cluster_id || !nv_out || !nf_out) return ERR_INVALID_ARG;
+    Mesh M;
+    std::vector<int32_t> label;
+    st = decimate(verts, N, facets, F, target_nv, max_rounds, M, label, rounds_out);
+    std::memcpy(verts_out, M.pos.data(), M.pos.size() * sizeof(float));
+    std::memcpy(facets_out, M.facets.data(), M.facets.size() * sizeof(int32_t));
+    std::memcpy(cluster_id, label.data(), label.size() * sizeof(int32_t));
+    if (quadrics_out)
+        for (int v = 0; v < M.nv(); ++v) std::memcpy(quadrics_out + 10 * (size_t)v, M.Q[v].q, 40);
+    *nv_out = M.nv();
+    *nf_out = M.nf();
+    return st;
+}
+
+int picasso_oracle_decimate(const float* verts, int32_t N, const int32_t* facets, int32_t F, int32_t target_nv,
+                            float* verts_out, int32_t* facets_out, int32_t* cluster_id, int32_t* nv_out,
+                            int32_t* nf_out) {
+    return picasso_oracle_decimate_rounds(verts, N, facets, F, target_nv, -1, verts_out, facets_out, cluster_id,
+                                          nv_out, nf_out, nullptr, nullptr);
+}
+
+// Concatenated meshes (Sec. 3: "mini-batches of concatenated meshes"): facet
+// indices are global; every mesh is decimated on its own with its own budget.
+// Outputs are concatenated in mesh order with global output indices.
+// Returns the first error, else WARN_BUDGET_UNMET if any mesh fell short.
+int picasso_oracle_decimate_batch(int32_t B, const float* verts, const int32_t* facets, const int32_t* nv_in,
+                                  const int32_t* nf_in, const int32_t* target_nv, float* verts_out,
+                                  int32_t* facets_out, int32_t* cluster_id, int32_t* nv_out, int32_t* nf_out) {
+    if (B < 1 || !nv_in || !nf_in || !target_nv || !nv_out || !nf_out) return ERR_INVALID_ARG;
+    int64_t v0 = 0, f0 = 0, vo = 0, fo = 0;
+    int status = OK;
+    for (int b = 0; b < B; ++b) {
+        const int32_t N = nv_in[b], F = nf_in[b];
+        if (N < 1 || F < 0) return ERR_INVALID_ARG;
+        std::vector<int32_t> loc(3 * (size_t)F);
+        for (int64_t i = 0; i < 3 * (int64_t)F; ++i) {
+            int64_t g = facets[3 * f0 + i];
+            if (g < v0 || g >= v0 + N) return ERR_BAD_INDEX;
+            loc[i] = (int32_t)(g - v0);
+        }
+        std::vector<float> vout(3 * (size_t)N);
+        std::vector<int32_t> fout(3 * (size_t)F), cid(N);
+        int32_t nvo = 0, nfo = 0;
+        int st = picasso_oracle_decimate(verts + 3 * v0, N, loc.data(), F, target_nv[b], vout.data(), fout.data(),
+                                         cid.data(), &nvo, &nfo);
+        if (st < 0) return st;
+        if (st > 0) status = st;
+        std::memcpy(verts_out + 3 * vo, vout.data(), 3 * (size_t)nvo * sizeof(float));
+        for (int64_t i = 0; i < 3 * (int64_t)nfo; ++i) facets_out[3 * fo + i] = (int32_t)(fout[i] + vo);
+        for (int i = 0; i < N; ++i) cluster_id[v0 + i] = (int32_t)(cid[i] + vo);
+        nv_out[b] = nvo;
+        nf_out[b] = nfo;
+        v0 += N;
+        f0 += F;
+        vo += nvo;
+        fo += nfo;
+    }
+    return status;
+}
+
+}  // extern "C"
