@@ -1,0 +1,143 @@
+/* picasso.h -- C-ABI of the MI355X (gfx950) mesh-decimation library.
+ *
+ * Implements the round-based QEM decimation of the Picasso paper
+ * (Sec. 3, Algorithm 2 "Fast GPU-accelerated mesh simplification";
+ * supplementary section "Quadric error computation").  Every step runs in
+ * hand-written HIP kernels; there is no CPU fallback.
+ *
+ * Conventions for every call
+ *   - d_*   : DEVICE pointers owned by the caller; h_* / plain scalars: HOST.
+ *   - verts : float32 [N,3] row-major.  facets: int32 [F,3] row-major.
+ *   - return 0 = OK, >0 = warning, <0 = error (see picasso_status).
+ *     On error no output buffer has been written.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  The
+ *     decimate calls synchronise that stream before they return.
+ *   - A context owns its scratch workspace and is bound to one device; calls
+ *     on one context must not overlap in time.  Inputs are never modified.
+ *   - Nothing is allocated inside the decimate calls.
+ */
+#ifndef PICASSO_H
+#define PICASSO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct picasso_ctx picasso_ctx;
+
+enum picasso_status {
+    PICASSO_OK = 0,
+    PICASSO_WARN_BUDGET_UNMET = 1, /* some mesh ran out of edges: its nv_out > target_nv          */
+    PICASSO_ERR_INVALID_ARG = -1,  /* null pointer, N < 1, F < 0, target_nv < 1, B < 1              */
+    PICASSO_ERR_BAD_INDEX = -2,    /* facet index outside [0,N) (batched: outside its own mesh)     */
+    PICASSO_ERR_NONFINITE = -3,    /* NaN or Inf vertex coordinate                                  */
+    PICASSO_ERR_WORKSPACE = -4,    /* input larger than the context was created for                 */
+    PICASSO_ERR_HIP = -5           /* HIP runtime error (see picasso_last_hip_error)                */
+};
+
+enum picasso_option {
+    PICASSO_OPT_MAX_ROUNDS = 0,    /* stop after this many runs of the core algorithm; <0 = no cap  */
+    PICASSO_OPT_STAGE_TIMING = 1,  /* 1: fill picasso_stats.ms_stage with hipEvent times (slower)    */
+    PICASSO_OPT_SUBROUND_BATCH = 2 /* selection sub-rounds launched between two host checks         */
+};
+
+#define PICASSO_STATS_ROUNDS 32
+enum picasso_stage { /* index into picasso_stats.ms_stage[round][...] */
+    PICASSO_ST_QUADRICS = 0, /* S0, round 0 only */
+    PICASSO_ST_EDGES = 1,    /* S1 emit + sort + unique (+ fused S2 cost) */
+    PICASSO_ST_SELECT = 2,   /* S3 sub-rounds (+ budget truncation, S2b) */
+    PICASSO_ST_CONTRACT = 3, /* S4 + S6 vertex side */
+    PICASSO_ST_FACETS = 4,   /* S5 facet clean-up + compaction */
+    PICASSO_ST_COUNT = 8
+};
+
+typedef struct picasso_stats {
+    int32_t rounds;                          /* runs of the core algorithm executed                 */
+    int32_t nv_out, nf_out;                  /* totals over all meshes                              */
+    int32_t nv[PICASSO_STATS_ROUNDS];        /* vertices entering round r                           */
+    int32_t nf[PICASSO_STATS_ROUNDS];        /* facets entering round r                             */
+    int32_t ne[PICASSO_STATS_ROUNDS];        /* distinct edges in round r                           */
+    int32_t nsel[PICASSO_STATS_ROUNDS];      /* pairs contracted in round r                         */
+    int32_t subrounds[PICASSO_STATS_ROUNDS]; /* selection sub-rounds launched in round r            */
+    float ms_stage[PICASSO_STATS_ROUNDS][PICASSO_ST_COUNT];
+    float ms_total;                          /* whole call, hipEvents on `stream`                   */
+} picasso_stats;
+
+/* Bytes of device workspace a context of this capacity allocates. */
+size_t picasso_workspace_bytes(int64_t max_verts, int64_t max_facets, int32_t max_meshes);
+
+/* Create a context on `device` able to decimate up to max_verts vertices,
+ * max_facets facets (totals over a batch) and max_meshes meshes per call.
+ * Allocates the workspace once; returns PICASSO_ERR_HIP if that fails. */
+int picasso_create(picasso_ctx** out, int device, int64_t max_verts, int64_t max_facets, int32_t max_meshes);
+void picasso_destroy(picasso_ctx* ctx);
+int picasso_set_option(picasso_ctx* ctx, int option, int64_t value);
+const char* picasso_strerror(int status);
+const char* picasso_last_hip_error(picasso_ctx* ctx);
+
+/* Alg. 2 repeated until the vertex budget is met (Sec. 3: "running the core
+ * algorithm multiple times").
+ *
+ *   d_verts [N,3], d_facets [F,3]          inputs
+ *   target_nv                              number of output vertices N of Alg. 2
+ *   d_verts_out  (capacity N*3 floats)     contracted positions, first nv_out rows
+ *   d_facets_out (capacity F*3 ints)       surviving facets re-indexed, first nf_out rows,
+ *                                          input order and winding kept
+ *   d_cluster_id [N]                       output vertex that replaces each input vertex
+ *                                          (the paper's 1-D vertex-clustering tensor)
+ *   h_nv_out, h_nf_out                     host scalars
+ *   stats                                  host, may be NULL
+ *
+ * One round = Alg. 2 lines 1-10 and 12-16 with pairs only: distinct mesh edges
+ * are the candidates (line 1); pair cost = summed vertex quadrics evaluated at
+ * the pair's mean (line 2, supplementary Q(x) and mean-placement equations);
+ * pairs are taken greedily in ascending (cost, edge index) order while both
+ * ends are free and fewer than |V|-target pairs were taken (lines 3-10); each
+ * pair is contracted to its mean with the summed quadric, the smaller index
+ * representing it (lines 12-16).  Facets with two equal indices and later
+ * copies of an identical vertex triple are removed; survivors are renumbered
+ * in ascending order.  target_nv >= N copies the input through unchanged.
+ */
+int picasso_decimate(picasso_ctx* ctx, void* stream, const float* d_verts, int32_t N, const int32_t* d_facets,
+                     int32_t F, int32_t target_nv, float* d_verts_out, int32_t* d_facets_out,
+                     int32_t* d_cluster_id, int32_t* h_nv_out, int32_t* h_nf_out, picasso_stats* stats);
+
+/* Same on B concatenated meshes (Sec. 3: "mini-batches of concatenated
+ * meshes"): mesh b owns vertices [sum nv_in[<b], +nv_in[b]) and the facets
+ * [sum nf_in[<b], +nf_in[b]), whose indices are GLOBAL and must stay inside the
+ * mesh's own vertex range.  Budgets are per mesh.  Outputs are concatenated in
+ * mesh order with global output indices; h_nv_out/h_nf_out are host arrays [B].
+ * The result equals decimating every mesh on its own. */
+int picasso_decimate_batch(picasso_ctx* ctx, void* stream, int32_t B, const float* d_verts, const int32_t* d_facets,
+                           const int32_t* h_nv_in, const int32_t* h_nf_in, const int32_t* h_target_nv,
+                           float* d_verts_out, int32_t* d_facets_out, int32_t* d_cluster_id, int32_t* h_nv_out,
+                           int32_t* h_nf_out, picasso_stats* stats);
+
+/* ---- single steps of the path, exported for stage-level parity tests ------- */
+
+/* Vertex quadrics (supplementary, facet and vertex quadric equations):
+ * d_quadrics_out [N,10] = a00 a01 a02 a11 a12 a22 b0 b1 b2 c, each the
+ * left-to-right fp32 sum over adjacent facets in ascending facet order
+ * (vertex->facet CSR by stable radix sort, ordered segmented reduction). */
+int picasso_vertex_quadrics(picasso_ctx* ctx, void* stream, const float* d_verts, int32_t N, const int32_t* d_facets,
+                            int32_t F, float* d_quadrics_out);
+
+/* Distinct edges of the input mesh in ascending (lo,hi) order (Alg. 2 line 1)
+ * and the cost of each (Alg. 2 line 2) from the vertex quadrics above.
+ * d_edges_out (capacity 3F*2 ints), d_cost_out (capacity 3F floats). */
+int picasso_edge_costs(picasso_ctx* ctx, void* stream, const float* d_verts, int32_t N, const int32_t* d_facets,
+                       int32_t F, int32_t* d_edges_out, float* d_cost_out, int32_t* h_ne_out);
+
+/* Stable LSD radix sort of n keys on their low `key_bits` bits, in place.
+ * key_bytes is 4 or 8; d_vals (uint32, may be NULL) is permuted alongside.
+ * n must not exceed 3*max_facets of the context. */
+int picasso_radix_sort(picasso_ctx* ctx, void* stream, int key_bytes, void* d_keys, uint32_t* d_vals, int64_t n,
+                       int key_bits);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PICASSO_H */

@@ -1,0 +1,14 @@
+"""MI355X-native QEM mesh decimation (the decimation hot path of the Picasso paper).
+
+``binding`` is the ctypes front end of the HIP library (include/picasso.h);
+``meshgen`` holds the seeded synthetic inputs; ``build`` compiles the library.
+Importing the package does not load the library; the first call does, and it
+raises if the library is missing (there is no CPU fallback).
+"""
+from . import meshgen  # noqa: F401
+from .binding import (  # noqa: F401
+    Context, PicassoError, load_library, picasso_stats, picasso_strerror, picasso_workspace_bytes,
+    PICASSO_OK, PICASSO_WARN_BUDGET_UNMET, PICASSO_ERR_INVALID_ARG, PICASSO_ERR_BAD_INDEX,
+    PICASSO_ERR_NONFINITE, PICASSO_ERR_WORKSPACE, PICASSO_ERR_HIP,
+    PICASSO_OPT_MAX_ROUNDS, PICASSO_OPT_STAGE_TIMING, PICASSO_OPT_SUBROUND_BATCH,
+)

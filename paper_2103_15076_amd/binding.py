@@ -1,0 +1,278 @@
+"""Thin ctypes binding of include/picasso.h: argument marshalling only.
+
+torch supplies device memory and the stream; every step of the path runs in
+libpicasso_hip.so.  There is no fallback: if the library is missing or cannot
+be loaded, ``load_library`` raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpicasso_hip.so")
+
+PICASSO_OK = 0
+PICASSO_WARN_BUDGET_UNMET = 1
+PICASSO_ERR_INVALID_ARG = -1
+PICASSO_ERR_BAD_INDEX = -2
+PICASSO_ERR_NONFINITE = -3
+PICASSO_ERR_WORKSPACE = -4
+PICASSO_ERR_HIP = -5
+
+PICASSO_OPT_MAX_ROUNDS = 0
+PICASSO_OPT_STAGE_TIMING = 1
+PICASSO_OPT_SUBROUND_BATCH = 2
+
+PICASSO_STATS_ROUNDS = 32
+PICASSO_ST_COUNT = 8
+STAGE_NAMES = ("quadrics", "edges", "select", "contract", "facets")
+
+EXPORTED_SYMBOLS = (
+    "picasso_workspace_bytes", "picasso_create", "picasso_destroy", "picasso_set_option", "picasso_strerror",
+    "picasso_last_hip_error", "picasso_decimate", "picasso_decimate_batch", "picasso_vertex_quadrics",
+    "picasso_edge_costs", "picasso_radix_sort",
+)
+
+
+class picasso_stats(ctypes.Structure):
+    _fields_ = [
+        ("rounds", ctypes.c_int32),
+        ("nv_out", ctypes.c_int32),
+        ("nf_out", ctypes.c_int32),
+        ("nv", ctypes.c_int32 * PICASSO_STATS_ROUNDS),
+        ("nf", ctypes.c_int32 * PICASSO_STATS_ROUNDS),
+        ("ne", ctypes.c_int32 * PICASSO_STATS_ROUNDS),
+        ("nsel", ctypes.c_int32 * PICASSO_STATS_ROUNDS),
+        ("subrounds", ctypes.c_int32 * PICASSO_STATS_ROUNDS),
+        ("ms_stage", (ctypes.c_float * PICASSO_ST_COUNT) * PICASSO_STATS_ROUNDS),
+        ("ms_total", ctypes.c_float),
+    ]
+
+    def as_dict(self):
+        r = min(self.rounds, PICASSO_STATS_ROUNDS)
+        return dict(
+            rounds=self.rounds, nv_out=self.nv_out, nf_out=self.nf_out, ms_total=self.ms_total,
+            nv=list(self.nv[:r]), nf=list(self.nf[:r]), ne=list(self.ne[:r]), nsel=list(self.nsel[:r]),
+            subrounds=list(self.subrounds[:r]),
+            ms_stage=[{n: self.ms_stage[i][j] for j, n in enumerate(STAGE_NAMES)} for i in range(max(r, 1))],
+        )
+
+
+_lib = None
+
+
+class PicassoError(RuntimeError):
+    def __init__(self, status, msg):
+        super().__init__(f"picasso status {status}: {msg}")
+        self.status = status
+
+
+def load_library():
+    """Loads libpicasso_hip.so; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2103_15076_amd.build` "
+            "(hipcc, gfx950).  There is no CPU fallback.")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    lib.picasso_workspace_bytes.restype = ctypes.c_size_t
+    lib.picasso_workspace_bytes.argtypes = [i64, i64, i32]
+    lib.picasso_create.restype = ctypes.c_int
+    lib.picasso_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64, i64, i32]
+    lib.picasso_destroy.restype = None
+    lib.picasso_destroy.argtypes = [vp]
+    lib.picasso_set_option.restype = ctypes.c_int
+    lib.picasso_set_option.argtypes = [vp, ctypes.c_int, i64]
+    lib.picasso_strerror.restype = ctypes.c_char_p
+    lib.picasso_strerror.argtypes = [ctypes.c_int]
+    lib.picasso_last_hip_error.restype = ctypes.c_char_p
+    lib.picasso_last_hip_error.argtypes = [vp]
+    lib.picasso_decimate.restype = ctypes.c_int
+    lib.picasso_decimate.argtypes = [vp, vp, vp, i32, vp, i32, i32, vp, vp, vp, ctypes.POINTER(i32),
+                                     ctypes.POINTER(i32), ctypes.POINTER(picasso_stats)]
+    lib.picasso_decimate_batch.restype = ctypes.c_int
+    lib.picasso_decimate_batch.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                           ctypes.POINTER(picasso_stats)]
+    lib.picasso_vertex_quadrics.restype = ctypes.c_int
+    lib.picasso_vertex_quadrics.argtypes = [vp, vp, vp, i32, vp, i32, vp]
+    lib.picasso_edge_costs.restype = ctypes.c_int
+    lib.picasso_edge_costs.argtypes = [vp, vp, vp, i32, vp, i32, vp, vp, ctypes.POINTER(i32)]
+    lib.picasso_radix_sort.restype = ctypes.c_int
+    lib.picasso_radix_sort.argtypes = [vp, vp, ctypes.c_int, vp, vp, i64, ctypes.c_int]
+    _lib = lib
+    return lib
+
+
+def picasso_strerror(status: int) -> str:
+    return load_library().picasso_strerror(int(status)).decode()
+
+
+def picasso_workspace_bytes(max_verts: int, max_facets: int, max_meshes: int = 1) -> int:
+    return int(load_library().picasso_workspace_bytes(int(max_verts), int(max_facets), int(max_meshes)))
+
+
+def _stream_ptr(stream):
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _dev_ptr(t, dtype, what):
+    import torch
+    if t is None:
+        return ctypes.c_void_p(0)
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError(f"{what}: expected a contiguous CUDA tensor of dtype {dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+class Context:
+    """Owns a picasso_ctx (device workspace sized at creation)."""
+
+    def __init__(self, max_verts: int, max_facets: int, max_meshes: int = 1, device: int = 0):
+        self._lib = load_library()
+        self._h = ctypes.c_void_p(0)
+        st = self._lib.picasso_create(ctypes.byref(self._h), int(device), int(max_verts), int(max_facets),
+                                      int(max_meshes))
+        if st != PICASSO_OK:
+            raise PicassoError(st, picasso_strerror(st))
+        self.max_verts, self.max_facets, self.max_meshes, self.device = max_verts, max_facets, max_meshes, device
+
+    def close(self):
+        if getattr(self, "_h", None) and self._h.value:
+            self._lib.picasso_destroy(self._h)
+            self._h = ctypes.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *a):
+        self.close()
+
+    def set_option(self, option: int, value: int):
+        st = self._lib.picasso_set_option(self._h, int(option), int(value))
+        if st != PICASSO_OK:
+            raise PicassoError(st, picasso_strerror(st))
+
+    def last_hip_error(self) -> str:
+        return self._lib.picasso_last_hip_error(self._h).decode()
+
+    def _raise(self, st):
+        msg = picasso_strerror(st)
+        if st == PICASSO_ERR_HIP:
+            msg += ": " + self.last_hip_error()
+        raise PicassoError(st, msg)
+
+    # -- the calls of include/picasso.h, same names ---------------------------------------------
+
+    def picasso_decimate(self, verts, facets, target_nv, verts_out=None, facets_out=None, cluster_id=None,
+                         stats=None, stream=None, check=True):
+        """Returns (status, verts_out[:nv], facets_out[:nf], cluster_id).  Output
+        tensors are allocated with torch when not supplied (capacity = input sizes)."""
+        import torch
+        N, F = int(verts.shape[0]), int(facets.shape[0])
+        dev = verts.device
+        if verts_out is None:
+            verts_out = torch.empty((max(N, 1), 3), dtype=torch.float32, device=dev)
+        if facets_out is None:
+            facets_out = torch.empty((max(F, 1), 3), dtype=torch.int32, device=dev)
+        if cluster_id is None:
+            cluster_id = torch.empty((max(N, 1),), dtype=torch.int32, device=dev)
+        nv, nf = ctypes.c_int32(0), ctypes.c_int32(0)
+        st = self._lib.picasso_decimate(
+            self._h, _stream_ptr(stream), _dev_ptr(verts, torch.float32, "verts"), N,
+            _dev_ptr(facets, torch.int32, "facets"), F, int(target_nv),
+            _dev_ptr(verts_out, torch.float32, "verts_out"), _dev_ptr(facets_out, torch.int32, "facets_out"),
+            _dev_ptr(cluster_id, torch.int32, "cluster_id"), ctypes.byref(nv), ctypes.byref(nf),
+            ctypes.byref(stats) if stats is not None else None)
+        if st < 0:
+            if check:
+                self._raise(st)
+            return st, None, None, None
+        return st, verts_out[: nv.value], facets_out[: nf.value], cluster_id[:N]
+
+    def picasso_decimate_batch(self, verts, facets, nv_in, nf_in, target_nv, verts_out=None, facets_out=None,
+                               cluster_id=None, stats=None, stream=None, check=True):
+        """nv_in / nf_in / target_nv: host int sequences [B].  Returns
+        (status, verts_out[:sum nv], facets_out[:sum nf], cluster_id, nv_out[B], nf_out[B])."""
+        import numpy as np
+        import torch
+        nv_in = np.ascontiguousarray(nv_in, dtype=np.int32)
+        nf_in = np.ascontiguousarray(nf_in, dtype=np.int32)
+        target_nv = np.ascontiguousarray(target_nv, dtype=np.int32)
+        B = int(nv_in.shape[0])
+        N, F = int(verts.shape[0]), int(facets.shape[0])
+        dev = verts.device
+        if verts_out is None:
+            verts_out = torch.empty((max(N, 1), 3), dtype=torch.float32, device=dev)
+        if facets_out is None:
+            facets_out = torch.empty((max(F, 1), 3), dtype=torch.int32, device=dev)
+        if cluster_id is None:
+            cluster_id = torch.empty((max(N, 1),), dtype=torch.int32, device=dev)
+        nvo = np.zeros(B, np.int32)
+        nfo = np.zeros(B, np.int32)
+        hp = lambda a: a.ctypes.data_as(ctypes.c_void_p)
+        st = self._lib.picasso_decimate_batch(
+            self._h, _stream_ptr(stream), B, _dev_ptr(verts, torch.float32, "verts"),
+            _dev_ptr(facets, torch.int32, "facets"), hp(nv_in), hp(nf_in), hp(target_nv),
+            _dev_ptr(verts_out, torch.float32, "verts_out"), _dev_ptr(facets_out, torch.int32, "facets_out"),
+            _dev_ptr(cluster_id, torch.int32, "cluster_id"), hp(nvo), hp(nfo),
+            ctypes.byref(stats) if stats is not None else None)
+        if st < 0:
+            if check:
+                self._raise(st)
+            return st, None, None, None, None, None
+        return st, verts_out[: int(nvo.sum())], facets_out[: int(nfo.sum())], cluster_id[:N], nvo, nfo
+
+    def picasso_vertex_quadrics(self, verts, facets, stream=None):
+        import torch
+        N, F = int(verts.shape[0]), int(facets.shape[0])
+        out = torch.empty((N, 10), dtype=torch.float32, device=verts.device)
+        st = self._lib.picasso_vertex_quadrics(self._h, _stream_ptr(stream), _dev_ptr(verts, torch.float32, "verts"),
+                                               N, _dev_ptr(facets, torch.int32, "facets"), F,
+                                               _dev_ptr(out, torch.float32, "out"))
+        if st != PICASSO_OK:
+            self._raise(st)
+        return out
+
+    def picasso_edge_costs(self, verts, facets, stream=None):
+        import torch
+        N, F = int(verts.shape[0]), int(facets.shape[0])
+        edges = torch.empty((max(3 * F, 1), 2), dtype=torch.int32, device=verts.device)
+        cost = torch.empty((max(3 * F, 1),), dtype=torch.float32, device=verts.device)
+        ne = ctypes.c_int32(0)
+        st = self._lib.picasso_edge_costs(self._h, _stream_ptr(stream), _dev_ptr(verts, torch.float32, "verts"), N,
+                                          _dev_ptr(facets, torch.int32, "facets"), F,
+                                          _dev_ptr(edges, torch.int32, "edges"), _dev_ptr(cost, torch.float32, "cost"),
+                                          ctypes.byref(ne))
+        if st != PICASSO_OK:
+            self._raise(st)
+        return edges[: ne.value], cost[: ne.value]
+
+    def picasso_radix_sort(self, keys, vals=None, key_bits=None, stream=None):
+        """In-place stable sort of a uint32-as-int32 / uint64-as-int64 tensor on its low key_bits bits."""
+        import torch
+        if keys.dtype == torch.int64:
+            kb = 8
+        elif keys.dtype == torch.int32:
+            kb = 4
+        else:
+            raise TypeError("keys must be int32 or int64 (bit patterns of unsigned keys)")
+        if key_bits is None:
+            key_bits = 8 * kb
+        st = self._lib.picasso_radix_sort(self._h, _stream_ptr(stream), kb, _dev_ptr(keys, keys.dtype, "keys"),
+                                          _dev_ptr(vals, torch.int32, "vals") if vals is not None else None,
+                                          int(keys.shape[0]), int(key_bits))
+        if st != PICASSO_OK:
+            self._raise(st)
+        return keys, vals

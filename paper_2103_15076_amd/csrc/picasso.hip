@@ -1,0 +1,1375 @@
+// picasso.hip -- round-based QEM mesh decimation for gfx950 behind the C-ABI of
+// include/picasso.h.  Follows Algorithm 2 of the Picasso paper (Sec. 3) and
+// the quadric equations of its supplementary section "Quadric error
+// computation"; the greedy grouping that the paper leaves on the CPU
+// (Alg. 2 lines 3-10) is done here on the GPU by a parallel construction of
+// the same matching.
+//
+// All fp32 arithmetic is written as single IEEE operations in a fixed order
+// and compiled without contraction, so that results are reproducible to the bit.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+#include <vector>
+
+#include "../../include/picasso.h"
+#include "primitives.h"
+
+#pragma clang fp contract(off)
+
+using prim::u32;
+using prim::u64;
+
+namespace {
+
+constexpr int BLOCK = prim::BLOCK;
+constexpr u64 VMIN_NONE = ~0ull;
+
+// ---------------------------------------------------------------------------
+// Device-resident bookkeeping
+// ---------------------------------------------------------------------------
+struct State {
+    int err;       // bit0: bad facet index, bit1: non-finite coordinate
+    int nv[2];     // vertex count, ping-pong by round parity
+    int nf[2];     // facet count, ping-pong
+    int nh;        // 3 * nf of the current round (half-edge keys to sort)
+    int ne;        // distinct edges of the current round
+    int live[3];   // worklist lengths of the selection sub-rounds (rotating)
+    int trunc_n;   // matched edges entering the budget truncation
+    int pad[5];
+};
+
+// One vertex = 64 bytes: position and the 10 quadric coefficients.
+struct __attribute__((aligned(16))) VRec {
+    float x, y, z, w0;
+    float a00, a01, a02, a11;
+    float a12, a22, b0, b1;
+    float b2, c, w1, w2;
+};
+
+struct MeshTab {       // per-mesh tables, all device pointers, B entries (+1 for offsets)
+    int B;
+    const int* voff;   // [B+1] current vertex offsets
+    const int* target; // [B]
+    const int* active; // [B] mesh takes part in this round
+    const int* nrem;   // [B] pairs still to contract (budget of Alg. 2 line 4)
+    int* matched;      // [B] pairs formed this round
+};
+
+__device__ __forceinline__ int mesh_of(const int* __restrict__ voff, int B, int v) {
+    if (B <= 1) return 0;
+    int lo = 0, hi = B;  // invariant: voff[lo] <= v < voff[hi]
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (voff[mid] <= v) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+__device__ __forceinline__ u32 cost_key(float c) {
+    u32 u = __float_as_uint(c);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// ---------------------------------------------------------------------------
+// S0: vertex quadrics (supplementary: facet quadric Q=(nn^T, dn, d^2); vertex
+// quadric = sum over adjacent facets, here in ascending facet order)
+// ---------------------------------------------------------------------------
+
+// Validates and copies the inputs into the workspace; emits the (vertex,
+// incidence) pairs whose stable sort is the vertex->facet CSR.
+__global__ __launch_bounds__(BLOCK) void init_kernel(const float* __restrict__ verts, int N,
+                                                     const int* __restrict__ facets, int F, int B,
+                                                     const int* __restrict__ voff, const int* __restrict__ foff,
+                                                     VRec* __restrict__ vrec, int* __restrict__ cid,
+                                                     int* __restrict__ fcur, u32* __restrict__ ikey,
+                                                     u32* __restrict__ ival, State* st) {
+    const int stride = gridDim.x * BLOCK;
+    const int g = blockIdx.x * BLOCK + threadIdx.x;
+    int err = 0;
+    for (int w = g; w < N; w += stride) {
+        float x = verts[3 * (size_t)w], y = verts[3 * (size_t)w + 1], z = verts[3 * (size_t)w + 2];
+        if (!(isfinite(x) && isfinite(y) && isfinite(z))) err |= 2;
+        VRec r;
+        r.x = x; r.y = y; r.z = z; r.w0 = 0.f;
+        r.a00 = r.a01 = r.a02 = r.a11 = r.a12 = r.a22 = r.b0 = r.b1 = r.b2 = r.c = r.w1 = r.w2 = 0.f;
+        vrec[w] = r;
+        cid[w] = w;
+    }
+    for (int f = g; f < F; f += stride) {
+        const int m = mesh_of(foff, B, f);
+        const int lo = voff[m], hi = voff[m + 1];
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+            int a = facets[3 * (size_t)f + c];
+            if (a < lo || a >= hi) { err |= 1; a = lo; }
+            fcur[3 * (size_t)f + c] = a;
+            if (ikey) {
+                ikey[3 * (size_t)f + c] = (u32)a;
+                ival[3 * (size_t)f + c] = (u32)(3 * f + c);
+            }
+        }
+    }
+    if (err) atomicOr(&st->err, err);
+}
+
+// off[v] = first position of vertex v in the sorted incidence keys (CSR row starts)
+__global__ __launch_bounds__(BLOCK) void csr_offsets_kernel(const u32* __restrict__ skey, int H, int N,
+                                                            int* __restrict__ off) {
+    const int i = blockIdx.x * BLOCK + threadIdx.x;
+    if (i >= H) return;
+    const int k = (int)skey[i];
+    const int kp = i ? (int)skey[i - 1] : -1;
+    for (int v = kp + 1; v <= k; ++v) off[v] = i;
+    if (i == H - 1)
+        for (int v = k + 1; v <= N; ++v) off[v] = H;
+}
+
+struct Quadric10 {
+    float q[10];
+};
+
+__device__ __forceinline__ Quadric10 facet_quadric(const VRec* __restrict__ vrec, int i0, int i1, int i2) {
+    Quadric10 Q;
+#pragma unroll
+    for (int k = 0; k < 10; ++k) Q.q[k] = 0.0f;
+    if (i0 == i1 || i1 == i2 || i0 == i2) return Q;
+    const float4 p0 = *reinterpret_cast<const float4*>(&vrec[i0]);
+    const float4 p1 = *reinterpret_cast<const float4*>(&vrec[i1]);
+    const float4 p2 = *reinterpret_cast<const float4*>(&vrec[i2]);
+    float ax = p1.x - p0.x, ay = p1.y - p0.y, az = p1.z - p0.z;
+    float bx = p2.x - p0.x, by = p2.y - p0.y, bz = p2.z - p0.z;
+    float nx = ay * bz - az * by;
+    float ny = az * bx - ax * bz;
+    float nz = ax * by - ay * bx;
+    float len = sqrtf((nx * nx + ny * ny) + nz * nz);
+    if (len == 0.0f) return Q;
+    nx = nx / len;
+    ny = ny / len;
+    nz = nz / len;
+    float d = -((nx * p0.x + ny * p0.y) + nz * p0.z);
+    Q.q[0] = nx * nx; Q.q[1] = nx * ny; Q.q[2] = nx * nz;
+    Q.q[3] = ny * ny; Q.q[4] = ny * nz; Q.q[5] = nz * nz;
+    Q.q[6] = d * nx;  Q.q[7] = d * ny;  Q.q[8] = d * nz;
+    Q.q[9] = d * d;
+    return Q;
+}
+
+// Ordered segmented reduction: one lane per vertex walks its CSR row in
+// ascending incidence order and adds the facet quadrics left to right.
+__global__ __launch_bounds__(BLOCK) void quadric_reduce_kernel(VRec* __restrict__ vrec, int N,
+                                                               const int* __restrict__ fcur,
+                                                               const int* __restrict__ off,
+                                                               const u32* __restrict__ inc) {
+    const int w = blockIdx.x * BLOCK + threadIdx.x;
+    if (w >= N) return;
+    float acc[10];
+#pragma unroll
+    for (int k = 0; k < 10; ++k) acc[k] = 0.0f;
+    if (off) {
+        const int s = off[w], e = off[w + 1];
+        for (int j = s; j < e; ++j) {
+            const int f = (int)(inc[j] / 3u);
+            const Quadric10 Q = facet_quadric(vrec, fcur[3 * (size_t)f], fcur[3 * (size_t)f + 1], fcur[3 * (size_t)f + 2]);
+#pragma unroll
+            for (int k = 0; k < 10; ++k) acc[k] = acc[k] + Q.q[k];
+        }
+    }
+    float4* r = reinterpret_cast<float4*>(&vrec[w]);
+    r[1] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    r[2] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+    r[3] = make_float4(acc[8], acc[9], 0.f, 0.f);
+}
+
+// ---------------------------------------------------------------------------
+// Round set-up
+// ---------------------------------------------------------------------------
+__global__ void round_begin_kernel(int B, const int* __restrict__ voff, const int* __restrict__ target,
+                                   int* __restrict__ active, int* __restrict__ stuck, int* __restrict__ nrem,
+                                   int* __restrict__ matched, int first_round, int cur, State* st) {
+    for (int b = threadIdx.x; b < B; b += blockDim.x) {
+        const int nvb = voff[b + 1] - voff[b];
+        if (!first_round && active[b] && matched[b] == 0) stuck[b] = 1;
+        const int act = (nvb > target[b]) && !stuck[b];
+        active[b] = act;
+        nrem[b] = act ? nvb - target[b] : 0;
+        matched[b] = 0;
+    }
+    if (threadIdx.x == 0) {
+        st->nh = 3 * st->nf[cur];
+        st->ne = 0;
+        st->live[0] = 0;
+        st->live[1] = 0;
+        st->live[2] = 0;
+        st->trunc_n = 0;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// S1: candidate pairs = distinct mesh edges (Alg. 2 line 1)
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(BLOCK) void emit_edge_keys_kernel(const int* __restrict__ fcur, const State* st, int cur,
+                                                               int vbits, u64* __restrict__ keys,
+                                                               u64* __restrict__ vmin0, u64* __restrict__ vmin1,
+                                                               int* __restrict__ mate) {
+    const int nf = st->nf[cur], nv = st->nv[cur];
+    const int stride = gridDim.x * BLOCK;
+    const int g = blockIdx.x * BLOCK + threadIdx.x;
+    const u64 sentinel = (vbits >= 32) ? ~0ull : ((1ull << (2 * vbits)) - 1ull);
+    for (int f = g; f < nf; f += stride) {
+        const int a = fcur[3 * (size_t)f], b = fcur[3 * (size_t)f + 1], c = fcur[3 * (size_t)f + 2];
+        const int p[3] = {a, b, c}, q[3] = {b, c, a};
+#pragma unroll
+        for (int s = 0; s < 3; ++s) {
+            const int lo = min(p[s], q[s]), hi = max(p[s], q[s]);
+            keys[3 * (size_t)f + s] = (lo == hi) ? sentinel : (((u64)(u32)lo << vbits) | (u64)(u32)hi);
+        }
+    }
+    for (int w = g; w < nv; w += stride) {
+        vmin0[w] = VMIN_NONE;
+        vmin1[w] = VMIN_NONE;
+        mate[w] = -1;
+    }
+}
+
+struct UniquePred {
+    const u64* keys;
+    u64 sentinel;
+    __device__ bool operator()(int i) const {
+        const u64 k = keys[i];
+        return k != sentinel && (i == 0 || k != keys[i - 1]);
+    }
+};
+
+// S2: cost of a pair = quadric error of the summed quadric at the pair's mean
+// (Alg. 2 line 2; supplementary Q(x) = x^T A x + 2 b^T x + c and the mean
+// placement equation).
+__device__ __forceinline__ float pair_cost(const VRec* __restrict__ vrec, int u, int v) {
+    const float4* ru = reinterpret_cast<const float4*>(&vrec[u]);
+    const float4* rv = reinterpret_cast<const float4*>(&vrec[v]);
+    const float4 u0 = ru[0], u1 = ru[1], u2 = ru[2], u3 = ru[3];
+    const float4 v0 = rv[0], v1 = rv[1], v2 = rv[2], v3 = rv[3];
+    const float a00 = u1.x + v1.x, a01 = u1.y + v1.y, a02 = u1.z + v1.z, a11 = u1.w + v1.w;
+    const float a12 = u2.x + v2.x, a22 = u2.y + v2.y, b0 = u2.z + v2.z, b1 = u2.w + v2.w;
+    const float b2 = u3.x + v3.x, c = u3.y + v3.y;
+    const float mx = (u0.x + v0.x) * 0.5f;
+    const float my = (u0.y + v0.y) * 0.5f;
+    const float mz = (u0.z + v0.z) * 0.5f;
+    const float t0 = (a00 * mx + a01 * my) + a02 * mz;
+    const float t1 = (a01 * mx + a11 * my) + a12 * mz;
+    const float t2 = (a02 * mx + a12 * my) + a22 * mz;
+    const float xAx = (mx * t0 + my * t1) + mz * t2;
+    const float bx = (b0 * mx + b1 * my) + b2 * mz;
+    return (xAx + 2.0f * bx) + c;
+}
+
+// Writes the distinct edges, their cost keys, and places each edge's first bid
+// (sub-round 0 of the selection) on both of its vertices.
+struct UniqueOut {
+    const u64* keys;
+    u64* ekey;
+    u32* ecost;
+    const VRec* vrec;
+    u64* vmin0;
+    int vbits;
+    MeshTab mt;
+    __device__ void operator()(int i, int e) const {
+        const u64 k = keys[i];
+        const int u = (int)(k >> vbits), v = (int)(k & ((1ull << vbits) - 1ull));
+        ekey[e] = k;
+        const u32 ck = cost_key(pair_cost(vrec, u, v));
+        ecost[e] = ck;
+        if (mt.active[mesh_of(mt.voff, mt.B, u)]) {
+            const u64 p = ((u64)ck << 32) | (u32)e;
+            atomicMin(&vmin0[u], p);
+            atomicMin(&vmin0[v], p);
+        }
+    }
+};
+
+// ---------------------------------------------------------------------------
+// S3: greedy disjoint grouping of Alg. 2 lines 3-10, computed in parallel.
+//
+// Priority of edge e = (cost key, e) packed in 64 bits; the sequential loop of
+// the paper visits edges in ascending priority.  An edge is LIVE while neither
+// end is paired.  A live edge whose priority is the minimum among the live
+// edges at BOTH ends is exactly one the sequential loop accepts, so every
+// sub-round accepts all such edges at once, retires the edges touching newly
+// paired vertices, and lets the survivors bid again.  vmin buffers rotate:
+// sub-round k reads bids in vmin[k%3], places the survivors' bids in
+// vmin[(k+1)%3] and clears their slots in vmin[(k+2)%3].
+// ---------------------------------------------------------------------------
+constexpr int SEL_ITEMS = 4;
+constexpr int SEL_TILE = BLOCK * SEL_ITEMS;
+
+struct SelArgs {
+    const u64* ekey;
+    const u32* ecost;
+    u64* vmin[3];
+    int* mate;
+    int* list[2];
+    State* st;
+    MeshTab mt;
+    int vbits;
+};
+
+__device__ __forceinline__ bool vertex_pairs_now(const u64* __restrict__ cur, const u64* __restrict__ ekey, int vbits,
+                                                 int x, u64 mx) {
+    // The best live edge at x is accepted in this sub-round iff it is also the best at its other end.
+    if (mx == VMIN_NONE) return false;  // no bid on x (cannot happen for an end of a live edge)
+    const u64 k = ekey[(u32)mx];
+    const int a = (int)(k >> vbits), b = (int)(k & ((1ull << vbits) - 1ull));
+    const int other = (a == x) ? b : a;
+    return cur[other] == mx;
+}
+
+__global__ __launch_bounds__(BLOCK) void select_subround_kernel(SelArgs A, int k) {
+    __shared__ int stage[SEL_TILE];
+    __shared__ int s_count;
+    __shared__ int s_base;
+    const u64* __restrict__ cur = A.vmin[k % 3];
+    u64* __restrict__ nxt = A.vmin[(k + 1) % 3];
+    u64* __restrict__ rst = A.vmin[(k + 2) % 3];
+    const int* __restrict__ lin = (k == 0) ? nullptr : A.list[k & 1];
+    int* __restrict__ lout = A.list[(k + 1) & 1];
+    const int n = (k == 0) ? A.st->ne : A.st->live[k % 3];
+    int* n_out = &A.st->live[(k + 1) % 3];
+    if (blockIdx.x == 0 && threadIdx.x == 0) A.st->live[(k + 2) % 3] = 0;  // next sub-round's output counter
+    const int lane = prim::lane_id();
+    const u64 lt = prim::lanemask_lt();
+    const u64 vmask = (1ull << A.vbits) - 1ull;
+
+    for (long long base = (long long)blockIdx.x * SEL_TILE; base < n; base += (long long)gridDim.x * SEL_TILE) {
+        if (threadIdx.x == 0) s_count = 0;
+        __syncthreads();
+#pragma unroll
+        for (int it = 0; it < SEL_ITEMS; ++it) {
+            const long long i = base + (long long)it * BLOCK + threadIdx.x;
+            bool alive = false, sel = false;
+            int e = 0, u = 0, v = 0, m = 0;
+            u64 p = 0;
+            if (i < n) {
+                e = lin ? lin[i] : (int)i;
+                const u64 key = A.ekey[e];
+                u = (int)(key >> A.vbits);
+                v = (int)(key & vmask);
+                p = ((u64)A.ecost[e] << 32) | (u32)e;
+                m = mesh_of(A.mt.voff, A.mt.B, u);
+                if (k > 0 || A.mt.active[m]) {
+                    const u64 mu = cur[u], mv = cur[v];
+                    if (mu == p && mv == p) {
+                        sel = true;
+                        A.mate[u] = v;
+                        A.mate[v] = u;
+                    } else {
+                        alive = !(vertex_pairs_now(cur, A.ekey, A.vbits, u, mu) ||
+                                  vertex_pairs_now(cur, A.ekey, A.vbits, v, mv));
+                    }
+                }
+            }
+            // pairs formed, counted per mesh (one atomic per wave and mesh)
+            u64 sb = __ballot(sel);
+            while (sb) {
+                const int leader = __ffsll((long long)sb) - 1;
+                const int m0 = __shfl(m, leader, 64);
+                const u64 same = __ballot(sel && m == m0);
+                if (lane == leader) atomicAdd(&A.mt.matched[m0], (int)__popcll(same));
+                sb &= ~same;
+            }
+            // survivors: bid for the next sub-round, stage into the LDS tile
+            const u64 ab = __ballot(alive);
+            if (ab) {
+                int wbase = 0;
+                if (lane == 0) wbase = atomicAdd(&s_count, (int)__popcll(ab));
+                wbase = __shfl(wbase, 0, 64);
+                if (alive) {
+                    stage[wbase + (int)__popcll(ab & lt)] = e;
+                    atomicMin(&nxt[u], p);
+                    atomicMin(&nxt[v], p);
+                    rst[u] = VMIN_NONE;
+                    rst[v] = VMIN_NONE;
+                }
+            }
+        }
+        __syncthreads();
+        const int cnt = s_count;
+        if (threadIdx.x == 0 && cnt) s_base = atomicAdd(n_out, cnt);
+        __syncthreads();
+        if (cnt) {
+            const int gb = s_base;
+            for (int j = threadIdx.x; j < cnt; j += BLOCK) lout[gb + j] = stage[j];
+        }
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------
+// S2b + budget (Alg. 2 lines 3-4, 6): when a mesh formed more pairs than it may
+// remove, only its n_rem pairs of smallest (cost, edge index) stay.  The pairs
+// are gathered in edge order, sorted stably by (mesh, cost key), and the tail
+// of each mesh's run is released.
+// ---------------------------------------------------------------------------
+struct TruncPred {
+    const u64* ekey;
+    const int* mate;
+    MeshTab mt;
+    int vbits;
+    __device__ bool operator()(int e) const {
+        const u64 k = ekey[e];
+        const int u = (int)(k >> vbits), v = (int)(k & ((1ull << vbits) - 1ull));
+        if (mate[u] != v) return false;
+        const int m = mesh_of(mt.voff, mt.B, u);
+        return mt.matched[m] > mt.nrem[m];
+    }
+};
+
+struct TruncOut {
+    const u64* ekey;
+    const u32* ecost;
+    u64* tkey;
+    u32* tval;
+    MeshTab mt;
+    int vbits;
+    __device__ void operator()(int e, int pos) const {
+        const int u = (int)(ekey[e] >> vbits);
+        tkey[pos] = ((u64)(u32)mesh_of(mt.voff, mt.B, u) << 32) | (u64)ecost[e];
+        tval[pos] = (u32)e;
+    }
+};
+
+// segstart[b] = number of gathered pairs that belong to meshes before b
+__global__ void trunc_segments_kernel(int B, const int* __restrict__ matched, const int* __restrict__ nrem,
+                                      int* __restrict__ segstart) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        int run = 0;
+        for (int b = 0; b < B; ++b) {
+            segstart[b] = run;
+            if (matched[b] > nrem[b]) run += matched[b];
+        }
+    }
+}
+
+__global__ __launch_bounds__(BLOCK) void trunc_apply_kernel(const u64* __restrict__ tkey, const u32* __restrict__ tval,
+                                                            const State* st, const int* __restrict__ segstart,
+                                                            const int* __restrict__ nrem,
+                                                            const u64* __restrict__ ekey, int vbits,
+                                                            int* __restrict__ mate) {
+    const int i = blockIdx.x * BLOCK + threadIdx.x;
+    if (i >= st->trunc_n) return;
+    const int m = (int)(tkey[i] >> 32);
+    if (i - segstart[m] >= nrem[m]) {
+        const u64 k = ekey[tval[i]];
+        mate[(int)(k >> vbits)] = -1;
+        mate[(int)(k & ((1ull << vbits) - 1ull))] = -1;
+    }
+}
+
+__global__ void trunc_finish_kernel(int B, int* __restrict__ matched, const int* __restrict__ nrem) {
+    for (int b = threadIdx.x; b < B; b += blockDim.x)
+        if (matched[b] > nrem[b]) matched[b] = nrem[b];
+}
+
+// ---------------------------------------------------------------------------
+// S4 + S6: contraction (Alg. 2 lines 12-16) and survivor renumbering
+// ---------------------------------------------------------------------------
+struct AlivePred {
+    const int* mate;
+    __device__ bool operator()(int w) const {
+        const int m = mate[w];
+        return !(m >= 0 && m < w);  // the larger index of a pair is replaced by the smaller
+    }
+};
+
+struct AliveOut {
+    int* newid;
+    __device__ void operator()(int w, int pos) const { newid[w] = pos; }
+};
+
+// Survivors move to their new slot; a pair's representative takes the mean
+// position and the summed quadric.  vmap[w] = output slot of w's cluster.
+__global__ __launch_bounds__(BLOCK) void contract_kernel(const VRec* __restrict__ vin, VRec* __restrict__ vout,
+                                                         const int* __restrict__ mate, const int* __restrict__ newid,
+                                                         int* __restrict__ vmap, const State* st, int cur, int B,
+                                                         const int* __restrict__ voff_cur, int* __restrict__ voff_nxt,
+                                                         int* __restrict__ htab, int hsize) {
+    const int nv = st->nv[cur];
+    const int stride = gridDim.x * BLOCK;
+    const int g = blockIdx.x * BLOCK + threadIdx.x;
+    for (int w = g; w < nv; w += stride) {
+        const int m = mate[w];
+        if (m >= 0 && m < w) {
+            vmap[w] = newid[m];
+            continue;
+        }
+        const int nw = newid[w];
+        vmap[w] = nw;
+        const float4* a = reinterpret_cast<const float4*>(&vin[w]);
+        float4 r0 = a[0], r1 = a[1], r2 = a[2], r3 = a[3];
+        if (m >= 0) {
+            const float4* b = reinterpret_cast<const float4*>(&vin[m]);
+            const float4 s0 = b[0], s1 = b[1], s2 = b[2], s3 = b[3];
+            r0.x = (r0.x + s0.x) * 0.5f; r0.y = (r0.y + s0.y) * 0.5f; r0.z = (r0.z + s0.z) * 0.5f;
+            r1.x = r1.x + s1.x; r1.y = r1.y + s1.y; r1.z = r1.z + s1.z; r1.w = r1.w + s1.w;
+            r2.x = r2.x + s2.x; r2.y = r2.y + s2.y; r2.z = r2.z + s2.z; r2.w = r2.w + s2.w;
+            r3.x = r3.x + s3.x; r3.y = r3.y + s3.y;
+        }
+        float4* o = reinterpret_cast<float4*>(&vout[nw]);
+        o[0] = r0; o[1] = r1; o[2] = r2; o[3] = r3;
+    }
+    // a mesh's first vertex always survives (a removed vertex has a smaller partner in its own mesh)
+    for (int b = g; b <= B; b += stride) voff_nxt[b] = (b == B) ? st->nv[cur ^ 1] : newid[voff_cur[b]];
+    for (int h = g; h < hsize; h += stride) htab[h] = -1;
+}
+
+// ---------------------------------------------------------------------------
+// S5: facet re-indexing, removal of collapsed and repeated facets, compaction
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void sort3(int& a, int& b, int& c) {
+    int t;
+    if (a > b) { t = a; a = b; b = t; }
+    if (b > c) { t = b; b = c; c = t; }
+    if (a > b) { t = a; a = b; b = t; }
+}
+
+__device__ __forceinline__ u32 hash3(int a, int b, int c) {
+    u32 h = (u32)a * 0x9E3779B1u;
+    h ^= (u32)b * 0x85EBCA77u + (h << 6) + (h >> 2);
+    h ^= (u32)c * 0xC2B2AE3Du + (h << 6) + (h >> 2);
+    h ^= h >> 15;
+    h *= 0x2C1B3C6Du;
+    h ^= h >> 12;
+    return h;
+}
+
+// Re-indexes every facet and enters the non-collapsed ones into an open-
+// addressing table keyed by the unordered vertex triple.  A slot stores a
+// facet index; the slot's identity is that facet's triple, and among equal
+// triples the slot converges to the smallest facet index (atomicMin), so the
+// survivor does not depend on the order in which lanes arrive.
+__global__ __launch_bounds__(BLOCK) void facet_insert_kernel(const int* __restrict__ fcur, int* __restrict__ fmap,
+                                                             const int* __restrict__ vmap, const State* st, int cur,
+                                                             int* __restrict__ htab, u32 hmask, MeshTab mt,
+                                                             const int* __restrict__ voff_cur,
+                                                             int* __restrict__ cid, int n_orig) {
+    const int nf = st->nf[cur];
+    const int stride = gridDim.x * BLOCK;
+    const int g = blockIdx.x * BLOCK + threadIdx.x;
+    for (int f = g; f < nf; f += stride) {
+        const int a0 = fcur[3 * (size_t)f], b0 = fcur[3 * (size_t)f + 1], c0 = fcur[3 * (size_t)f + 2];
+        const int a = vmap[a0], b = vmap[b0], c = vmap[c0];
+        fmap[3 * (size_t)f] = a;
+        fmap[3 * (size_t)f + 1] = b;
+        fmap[3 * (size_t)f + 2] = c;
+        if (!mt.active[mesh_of(voff_cur, mt.B, a0)]) continue;  // mesh sits this round out: facets kept as they are
+        if (a == b || b == c || a == c) continue;
+        int x = a, y = b, z = c;
+        sort3(x, y, z);
+        u32 h = hash3(x, y, z) & hmask;
+        for (;;) {
+            const int old = atomicCAS(&htab[h], -1, f);
+            if (old == -1) break;
+            if (old == f) break;
+            int p = vmap[fcur[3 * (size_t)old]], q = vmap[fcur[3 * (size_t)old + 1]], r = vmap[fcur[3 * (size_t)old + 2]];
+            sort3(p, q, r);
+            if (p == x && q == y && r == z) {
+                atomicMin(&htab[h], f);
+                break;
+            }
+            h = (h + 1) & hmask;
+        }
+    }
+    for (int o = g; o < n_orig; o += stride) cid[o] = vmap[cid[o]];
+}
+
+// keep[f] = 1 iff the facet survives: not collapsed and the first of its triple.
+struct FacetKeepPred {
+    const int* fmap;
+    const int* fcur;
+    const int* htab;
+    u32 hmask;
+    unsigned char* keep;
+    MeshTab mt;
+    const int* voff_cur;
+    __device__ bool operator()(int f) const {
+        const int a = fmap[3 * (size_t)f], b = fmap[3 * (size_t)f + 1], c = fmap[3 * (size_t)f + 2];
+        bool k;
+        if (!mt.active[mesh_of(voff_cur, mt.B, fcur[3 * (size_t)f])]) {
+            k = true;
+        } else if (a == b || b == c || a == c) {
+            k = false;
+        } else {
+            int x = a, y = b, z = c;
+            sort3(x, y, z);
+            u32 h = hash3(x, y, z) & hmask;
+            k = false;
+            for (;;) {
+                const int r = htab[h];
+                if (r == f) { k = true; break; }
+                if (r < 0) break;  // cannot happen: f was inserted
+                int p = fmap[3 * (size_t)r], q = fmap[3 * (size_t)r + 1], s = fmap[3 * (size_t)r + 2];
+                sort3(p, q, s);
+                if (p == x && q == y && s == z) break;  // an earlier copy holds the slot
+                h = (h + 1) & hmask;
+            }
+        }
+        keep[f] = k ? 1 : 0;
+        return k;
+    }
+};
+
+struct FlagPred {
+    const unsigned char* keep;
+    __device__ bool operator()(int f) const { return keep[f] != 0; }
+};
+
+struct FacetOut {
+    const int* fmap;
+    int* fnxt;
+    __device__ void operator()(int f, int pos) const {
+        fnxt[3 * (size_t)pos] = fmap[3 * (size_t)f];
+        fnxt[3 * (size_t)pos + 1] = fmap[3 * (size_t)f + 1];
+        fnxt[3 * (size_t)pos + 2] = fmap[3 * (size_t)f + 2];
+    }
+};
+
+// ---------------------------------------------------------------------------
+// Results
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(BLOCK) void copy_out_kernel(const VRec* __restrict__ vrec, const int* __restrict__ fcur,
+                                                         const int* __restrict__ cid, const State* st, int cur,
+                                                         int n_orig, float* __restrict__ verts_out,
+                                                         int* __restrict__ facets_out, int* __restrict__ cid_out,
+                                                         int B, const int* __restrict__ voff,
+                                                         int* __restrict__ foff_out) {
+    const int nv = st->nv[cur], nf = st->nf[cur];
+    const int stride = gridDim.x * BLOCK;
+    const int g = blockIdx.x * BLOCK + threadIdx.x;
+    for (int w = g; w < nv; w += stride) {
+        const float4 p = *reinterpret_cast<const float4*>(&vrec[w]);
+        verts_out[3 * (size_t)w] = p.x;
+        verts_out[3 * (size_t)w + 1] = p.y;
+        verts_out[3 * (size_t)w + 2] = p.z;
+    }
+    for (long long i = g; i < 3ll * nf; i += stride) facets_out[i] = fcur[i];
+    for (int o = g; o < n_orig; o += stride) cid_out[o] = cid[o];
+    // facets stay grouped by mesh: first facet whose leading vertex is at or past the mesh's first vertex
+    for (int b = g; b <= B; b += stride) {
+        int lo = 0, hi = nf;
+        if (b == B) lo = nf;
+        else {
+            const int v0 = voff[b];
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (fcur[3 * (size_t)mid] >= v0) hi = mid; else lo = mid + 1;
+            }
+        }
+        foff_out[b] = lo;
+    }
+}
+
+__global__ __launch_bounds__(BLOCK) void export_quadrics_kernel(const VRec* __restrict__ vrec, int N,
+                                                                float* __restrict__ out) {
+    const int w = blockIdx.x * BLOCK + threadIdx.x;
+    if (w >= N) return;
+    const float4* r = reinterpret_cast<const float4*>(&vrec[w]);
+    const float4 r1 = r[1], r2 = r[2], r3 = r[3];
+    float* o = out + 10 * (size_t)w;
+    o[0] = r1.x; o[1] = r1.y; o[2] = r1.z; o[3] = r1.w;
+    o[4] = r2.x; o[5] = r2.y; o[6] = r2.z; o[7] = r2.w;
+    o[8] = r3.x; o[9] = r3.y;
+}
+
+__global__ __launch_bounds__(BLOCK) void export_edges_kernel(const u64* __restrict__ ekey, const u32* __restrict__ ecost,
+                                                             const State* st, int vbits, int* __restrict__ edges,
+                                                             float* __restrict__ cost) {
+    const int e = blockIdx.x * BLOCK + threadIdx.x;
+    if (e >= st->ne) return;
+    const u64 k = ekey[e];
+    edges[2 * (size_t)e] = (int)(k >> vbits);
+    edges[2 * (size_t)e + 1] = (int)(k & ((1ull << vbits) - 1ull));
+    const u32 ck = ecost[e];
+    cost[e] = __uint_as_float((ck & 0x80000000u) ? (ck & 0x7FFFFFFFu) : ~ck);
+}
+
+inline int ceil_log2(long long n) {
+    int b = 0;
+    while ((1ll << b) < n) ++b;
+    return b < 1 ? 1 : b;
+}
+
+inline int grid_for(long long n, int cap = 0x7FFFFFFF) {
+    long long g = (n + BLOCK - 1) / BLOCK;
+    if (g < 1) g = 1;
+    if (g > cap) g = cap;
+    return (int)g;
+}
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+}  // namespace
+
+// ---------------------------------------------------------------------------
+// Context
+// ---------------------------------------------------------------------------
+struct picasso_ctx {
+    int device = 0;
+    int64_t max_verts = 0, max_facets = 0;
+    int32_t max_meshes = 0;
+    int64_t opt_max_rounds = -1;
+    int64_t opt_stage_timing = 0;
+    int64_t opt_subround_batch = 12;
+    char hip_err[256] = {0};
+
+    char* ws = nullptr;  // one device allocation, carved below
+    size_t ws_bytes = 0;
+    State* st = nullptr;
+    VRec* vrec[2] = {nullptr, nullptr};
+    int* fbuf[2] = {nullptr, nullptr};  // facet lists, ping-pong
+    int* fmap = nullptr;                // re-indexed facets before compaction
+    int* cid = nullptr;
+    u64* key64[2] = {nullptr, nullptr};  // sort buffers (3F keys); also hold 32-bit keys for S0
+    u32* val32[2] = {nullptr, nullptr};
+    u64* ekey = nullptr;
+    u32* ecost = nullptr;
+    u64* vmin[3] = {nullptr, nullptr, nullptr};
+    int* mate = nullptr;
+    int* newid = nullptr;
+    int* vmap = nullptr;
+    int* csr_off = nullptr;
+    int* list[2] = {nullptr, nullptr};
+    int* htab = nullptr;
+    size_t hcap = 0;
+    unsigned char* keep = nullptr;
+    int* tilesum = nullptr;
+    prim::SortScratch sort_sc{};
+    // per-mesh tables
+    int* voff[2] = {nullptr, nullptr};
+    int* foff = nullptr;
+    int* foff_out = nullptr;
+    int* target = nullptr;
+    int* active = nullptr;
+    int* stuck = nullptr;
+    int* nrem = nullptr;
+    int* matched = nullptr;
+    int* segstart = nullptr;
+    // pinned host staging
+    // pinned host staging: [0,16) State read-back | [32,48) State upload |
+    // [64, 64+4(B+2)) per-mesh upload | h_back: per-mesh read-back (B+2)
+    int* h_pin = nullptr;
+    int* h_back = nullptr;
+    size_t h_pin_ints = 0;
+    hipEvent_t ev[2 * PICASSO_STATS_ROUNDS * PICASSO_ST_COUNT + 4];
+    int n_ev = 0;
+    hipEvent_t ev_total[2];
+};
+
+namespace {
+
+struct Carver {
+    size_t off = 0;
+    char* base = nullptr;
+    template <typename T>
+    T* take(size_t count) {
+        size_t o = off;
+        off = align_up(off + count * sizeof(T));
+        return base ? reinterpret_cast<T*>(base + o) : nullptr;
+    }
+};
+
+size_t next_pow2(size_t x) {
+    size_t p = 1;
+    while (p < x) p <<= 1;
+    return p;
+}
+
+// Lays the workspace out; with base == nullptr only measures it.
+size_t carve(picasso_ctx* c, char* base, int64_t N, int64_t F, int32_t B) {
+    Carver cv;
+    cv.base = base;
+    const size_t n = (size_t)std::max<int64_t>(N, 1), f = (size_t)std::max<int64_t>(F, 1), h = 3 * f;
+    const size_t b = (size_t)std::max<int32_t>(B, 1);
+    picasso_ctx dummy;
+    picasso_ctx* x = c ? c : &dummy;
+    x->st = cv.take<State>(1);
+    x->vrec[0] = cv.take<VRec>(n);
+    x->vrec[1] = cv.take<VRec>(n);
+    x->fbuf[0] = cv.take<int>(3 * f);
+    x->fbuf[1] = cv.take<int>(3 * f);
+    x->fmap = cv.take<int>(3 * f);
+    x->cid = cv.take<int>(n);
+    x->key64[0] = cv.take<u64>(h);
+    x->key64[1] = cv.take<u64>(h);
+    x->val32[0] = cv.take<u32>(h);
+    x->val32[1] = cv.take<u32>(h);
+    x->ekey = cv.take<u64>(h);
+    x->ecost = cv.take<u32>(h);
+    for (int i = 0; i < 3; ++i) x->vmin[i] = cv.take<u64>(n);
+    x->mate = cv.take<int>(n);
+    x->newid = cv.take<int>(n);
+    x->vmap = cv.take<int>(n);
+    x->csr_off = cv.take<int>(n + 1);
+    x->list[0] = cv.take<int>(h);
+    x->list[1] = cv.take<int>(h);
+    x->hcap = next_pow2(2 * f);
+    x->htab = cv.take<int>(x->hcap);
+    x->keep = cv.take<unsigned char>(f);
+    const size_t ctiles = (size_t)prim::compact_tiles((long long)std::max(h, n)) + 1;
+    x->tilesum = cv.take<int>(ctiles);
+    x->sort_sc.T = prim::sort_tiles((long long)h);
+    x->sort_sc.table = cv.take<u32>((size_t)256 * x->sort_sc.T);
+    x->sort_sc.totals = cv.take<u32>(256);
+    x->voff[0] = cv.take<int>(b + 1);
+    x->voff[1] = cv.take<int>(b + 1);
+    x->foff = cv.take<int>(b + 1);
+    x->foff_out = cv.take<int>(b + 1);
+    x->target = cv.take<int>(b);
+    x->active = cv.take<int>(b);
+    x->stuck = cv.take<int>(b);
+    x->nrem = cv.take<int>(b);
+    x->matched = cv.take<int>(b);
+    x->segstart = cv.take<int>(b);
+    return cv.off;
+}
+
+#define HIP_TRY(ctx, expr)                                                                          \
+    do {                                                                                            \
+        hipError_t e__ = (expr);                                                                    \
+        if (e__ != hipSuccess) {                                                                    \
+            snprintf((ctx)->hip_err, sizeof((ctx)->hip_err), "%s at %s:%d: %s", #expr, __FILE__, __LINE__, \
+                     hipGetErrorString(e__));                                                       \
+            return PICASSO_ERR_HIP;                                                                 \
+        }                                                                                           \
+    } while (0)
+
+struct StageTimer {
+    picasso_ctx* c;
+    hipStream_t s;
+    bool on;
+    struct Rec { int round, stage, e0, e1; };
+    std::vector<Rec> recs;
+    int open = -1;
+    void begin(int round, int stage) {
+        if (!on || c->n_ev + 2 > (int)(sizeof(c->ev) / sizeof(c->ev[0]))) return;
+        Rec r{round, stage, c->n_ev, c->n_ev + 1};
+        c->n_ev += 2;
+        (void)hipEventRecord(c->ev[r.e0], s);
+        recs.push_back(r);
+        open = (int)recs.size() - 1;
+    }
+    void end() {
+        if (!on || open < 0) return;
+        (void)hipEventRecord(c->ev[recs[open].e1], s);
+        open = -1;
+    }
+    void collect(picasso_stats* stats) {
+        if (!on || !stats) return;
+        for (const Rec& r : recs) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, c->ev[r.e0], c->ev[r.e1]) == hipSuccess && r.round < PICASSO_STATS_ROUNDS)
+                stats->ms_stage[r.round][r.stage] += ms;
+        }
+    }
+};
+
+// S0 on the data already validated into the workspace by init_kernel.
+int run_vertex_quadrics(picasso_ctx* c, hipStream_t s, int N, int F) {
+    const int H = 3 * F;
+    u32* k0 = reinterpret_cast<u32*>(c->key64[0]);
+    u32* k1 = reinterpret_cast<u32*>(c->key64[1]);
+    if (F > 0) {
+        int where = prim::radix_sort<u32, true>(s, k0, k1, c->val32[0], c->val32[1], nullptr, H, ceil_log2(N), c->sort_sc);
+        if (where < 0) return PICASSO_ERR_HIP;
+        const u32* skey = where ? k1 : k0;
+        const u32* sval = where ? c->val32[1] : c->val32[0];
+        csr_offsets_kernel<<<grid_for(H), BLOCK, 0, s>>>(skey, H, N, c->csr_off);
+        quadric_reduce_kernel<<<grid_for(N), BLOCK, 0, s>>>(c->vrec[0], N, c->fbuf[0], c->csr_off, sval);
+    } else {
+        quadric_reduce_kernel<<<grid_for(N), BLOCK, 0, s>>>(c->vrec[0], N, c->fbuf[0], nullptr, nullptr);
+    }
+    return PICASSO_OK;
+}
+
+int upload_mesh_tables(picasso_ctx* c, hipStream_t s, int B, const int32_t* nv_in, const int32_t* nf_in,
+                       const int32_t* target, int64_t* N_out, int64_t* F_out) {
+    // pinned staging: [voff B+1][foff B+1][target B][zeros B]
+    int* p = c->h_pin + 64;
+    int* hv = p;
+    int* hf = hv + (B + 1);
+    int* ht = hf + (B + 1);
+    int* hz = ht + B;
+    int64_t nacc = 0, facc = 0;
+    for (int b = 0; b < B; ++b) {
+        if (nv_in[b] < 1 || nf_in[b] < 0 || target[b] < 1) return PICASSO_ERR_INVALID_ARG;
+        hv[b] = (int)nacc;
+        hf[b] = (int)facc;
+        ht[b] = target[b];
+        hz[b] = 0;
+        nacc += nv_in[b];
+        facc += nf_in[b];
+        if (nacc > c->max_verts || facc > c->max_facets) return PICASSO_ERR_WORKSPACE;
+    }
+    hv[B] = (int)nacc;
+    hf[B] = (int)facc;
+    *N_out = nacc;
+    *F_out = facc;
+    HIP_TRY(c, hipMemcpyAsync(c->voff[0], hv, sizeof(int) * (B + 1), hipMemcpyHostToDevice, s));
+    HIP_TRY(c, hipMemcpyAsync(c->foff, hf, sizeof(int) * (B + 1), hipMemcpyHostToDevice, s));
+    HIP_TRY(c, hipMemcpyAsync(c->target, ht, sizeof(int) * B, hipMemcpyHostToDevice, s));
+    HIP_TRY(c, hipMemcpyAsync(c->stuck, hz, sizeof(int) * B, hipMemcpyHostToDevice, s));
+    HIP_TRY(c, hipMemcpyAsync(c->active, hz, sizeof(int) * B, hipMemcpyHostToDevice, s));
+    HIP_TRY(c, hipMemcpyAsync(c->matched, hz, sizeof(int) * B, hipMemcpyHostToDevice, s));
+    return PICASSO_OK;
+}
+
+int upload_state(picasso_ctx* c, hipStream_t s, int N, int F) {
+    State* h = reinterpret_cast<State*>(c->h_pin + 32);
+    memset(h, 0, sizeof(State));
+    h->nv[0] = N;
+    h->nf[0] = F;
+    HIP_TRY(c, hipMemcpyAsync(c->st, h, sizeof(State), hipMemcpyHostToDevice, s));
+    return PICASSO_OK;
+}
+
+int status_from_err_bits(int bits) {
+    if (bits & 1) return PICASSO_ERR_BAD_INDEX;
+    if (bits & 2) return PICASSO_ERR_NONFINITE;
+    return PICASSO_OK;
+}
+
+int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, const int32_t* d_facets,
+                  const int32_t* nv_in, const int32_t* nf_in, const int32_t* target_nv, float* d_verts_out,
+                  int32_t* d_facets_out, int32_t* d_cluster_id, int32_t* h_nv_out, int32_t* h_nf_out,
+                  picasso_stats* stats) {
+    if (!c || !d_verts || !nv_in || !nf_in || !target_nv || !d_verts_out || !d_facets_out || !d_cluster_id ||
+        !h_nv_out || !h_nf_out || B < 1)
+        return PICASSO_ERR_INVALID_ARG;
+    if (B > c->max_meshes) return PICASSO_ERR_WORKSPACE;
+    HIP_TRY(c, hipSetDevice(c->device));
+    if (stats) memset(stats, 0, sizeof(*stats));
+
+    int64_t N64 = 0, F64 = 0;
+    int rc = upload_mesh_tables(c, s, B, nv_in, nf_in, target_nv, &N64, &F64);
+    if (rc != PICASSO_OK) return rc;
+    if (F64 > 0 && !d_facets) return PICASSO_ERR_INVALID_ARG;
+    const int N = (int)N64, F = (int)F64;
+    rc = upload_state(c, s, N, F);
+    if (rc != PICASSO_OK) return rc;
+
+    c->n_ev = 0;
+    StageTimer tm{c, s, c->opt_stage_timing != 0 && stats != nullptr, {}, -1};
+    HIP_TRY(c, hipEventRecord(c->ev_total[0], s));
+
+    // host mirror of the per-mesh vertex counts
+    std::vector<int> nvb(nv_in, nv_in + B), stuck(B, 0), act(B, 0), nrem(B, 0);
+    auto any_active = [&]() {
+        bool any = false;
+        for (int b = 0; b < B; ++b) {
+            act[b] = (nvb[b] > target_nv[b]) && !stuck[b];
+            nrem[b] = act[b] ? nvb[b] - target_nv[b] : 0;
+            any |= (act[b] != 0);
+        }
+        return any;
+    };
+    bool work = any_active() && c->opt_max_rounds != 0;
+
+    tm.begin(0, PICASSO_ST_QUADRICS);
+    init_kernel<<<grid_for(std::max(N, F), 4096), BLOCK, 0, s>>>(
+        d_verts, N, d_facets, F, B, c->voff[0], c->foff, c->vrec[0], c->cid, c->fbuf[0],
+        work ? reinterpret_cast<u32*>(c->key64[0]) : nullptr, c->val32[0], c->st);
+    if (work) {
+        rc = run_vertex_quadrics(c, s, N, F);
+        if (rc != PICASSO_OK) return rc;
+    }
+    tm.end();
+
+    State* hst = reinterpret_cast<State*>(c->h_pin);  // read-back area
+    std::vector<int> h_matched(B, 0);
+
+    int cur = 0;        // ping-pong index of vrec / facets / voff / State counts
+    int nv_total = N;   // exact (host mirror)
+    int nf_bound = F;   // upper bound on the current facet count
+    int round = 0;
+    bool validated = false;
+
+    while (work && (c->opt_max_rounds < 0 || round < c->opt_max_rounds)) {
+        const int vbits = ceil_log2(nv_total);
+        const int H = 3 * nf_bound;
+        MeshTab mt{B, c->voff[cur], c->target, c->active, c->nrem, c->matched};
+
+        // ---- S1 (+S2): edges and costs
+        tm.begin(round, PICASSO_ST_EDGES);
+        round_begin_kernel<<<1, BLOCK, 0, s>>>(B, c->voff[cur], c->target, c->active, c->stuck, c->nrem, c->matched,
+                                               round == 0, cur, c->st);
+        emit_edge_keys_kernel<<<grid_for(std::max(nf_bound, nv_total), 8192), BLOCK, 0, s>>>(
+            c->fbuf[cur], c->st, cur, vbits, c->key64[0], c->vmin[0], c->vmin[1], c->mate);
+        const u64* skeys = c->key64[0];
+        if (H > 0) {
+            int where = prim::radix_sort<u64, false>(s, c->key64[0], c->key64[1], nullptr, nullptr, &c->st->nh, H,
+                                                     2 * vbits, c->sort_sc);
+            if (where < 0) return PICASSO_ERR_HIP;
+            skeys = where ? c->key64[1] : c->key64[0];
+        }
+        const u64 sentinel = (vbits >= 32) ? ~0ull : ((1ull << (2 * vbits)) - 1ull);
+        UniquePred up{skeys, sentinel};
+        UniqueOut uo{skeys, c->ekey, c->ecost, c->vrec[cur], c->vmin[0], vbits, mt};
+        prim::compact(s, up, up, uo, &c->st->nh, H, c->tilesum, &c->st->ne);
+        tm.end();
+
+        // ---- S3: selection sub-rounds
+        tm.begin(round, PICASSO_ST_SELECT);
+        SelArgs sa;
+        sa.ekey = c->ekey;
+        sa.ecost = c->ecost;
+        for (int i = 0; i < 3; ++i) sa.vmin[i] = c->vmin[i];
+        sa.mate = c->mate;
+        sa.list[0] = c->list[0];
+        sa.list[1] = c->list[1];
+        sa.st = c->st;
+        sa.mt = mt;
+        sa.vbits = vbits;
+        int k = 0;
+        int live_bound = H;  // edges <= half-edges
+        for (;;) {
+            const int batch = (int)std::max<int64_t>(1, c->opt_subround_batch);
+            for (int j = 0; j < batch; ++j, ++k) {
+                const int g = (int)std::min<long long>(((long long)live_bound + SEL_TILE - 1) / SEL_TILE + 1, 4096);
+                select_subround_kernel<<<g, BLOCK, 0, s>>>(sa, k);
+            }
+            HIP_TRY(c, hipMemcpyAsync(hst, c->st, sizeof(State), hipMemcpyDeviceToHost, s));
+            HIP_TRY(c, hipMemcpyAsync(c->h_back, c->matched, sizeof(int) * B, hipMemcpyDeviceToHost, s));
+            HIP_TRY(c, hipStreamSynchronize(s));
+            if (!validated) {
+                const int st_err = status_from_err_bits(hst->err);
+                if (st_err != PICASSO_OK) return st_err;
+                validated = true;
+            }
+            const int live = hst->live[k % 3];
+            if (live == 0) break;
+            live_bound = live;
+        }
+        for (int b = 0; b < B; ++b) h_matched[b] = c->h_back[b];
+        nf_bound = std::min(nf_bound, hst->nf[cur]);
+        if (stats && round < PICASSO_STATS_ROUNDS) {
+            stats->nv[round] = nv_total;
+            stats->nf[round] = hst->nf[cur];
+            stats->ne[round] = hst->ne;
+            stats->subrounds[round] = k;
+        }
+
+        // ---- budget truncation (only where a mesh formed more pairs than it may remove)
+        bool need_trunc = false;
+        long long n_trunc = 0;
+        int n_sel = 0;
+        for (int b = 0; b < B; ++b) {
+            if (h_matched[b] > nrem[b]) {
+                need_trunc = true;
+                n_trunc += h_matched[b];
+                h_matched[b] = nrem[b];
+            }
+            n_sel += h_matched[b];
+        }
+        if (need_trunc) {
+            const int ne = hst->ne;
+            TruncPred tp{c->ekey, c->mate, mt, vbits};
+            TruncOut to{c->ekey, c->ecost, c->key64[0], c->val32[0], mt, vbits};
+            prim::compact(s, tp, tp, to, nullptr, ne, c->tilesum, &c->st->trunc_n);
+            int where = prim::radix_sort<u64, true>(s, c->key64[0], c->key64[1], c->val32[0], c->val32[1],
+                                                    &c->st->trunc_n, (int)n_trunc, 32 + (B > 1 ? ceil_log2(B) : 0),
+                                                    c->sort_sc);
+            if (where < 0) return PICASSO_ERR_HIP;
+            trunc_segments_kernel<<<1, 64, 0, s>>>(B, c->matched, c->nrem, c->segstart);
+            trunc_apply_kernel<<<grid_for(n_trunc), BLOCK, 0, s>>>(where ? c->key64[1] : c->key64[0],
+                                                                   where ? c->val32[1] : c->val32[0], c->st,
+                                                                   c->segstart, c->nrem, c->ekey, vbits, c->mate);
+            trunc_finish_kernel<<<1, BLOCK, 0, s>>>(B, c->matched, c->nrem);
+        }
+        tm.end();
+        if (stats && round < PICASSO_STATS_ROUNDS) stats->nsel[round] = n_sel;
+
+        // host mirror of the outcome
+        for (int b = 0; b < B; ++b) {
+            if (act[b] && h_matched[b] == 0) stuck[b] = 1;
+            nvb[b] -= h_matched[b];
+        }
+        if (n_sel == 0) {  // nothing contracted anywhere: the meshes are unchanged
+            work = any_active();
+            break;
+        }
+
+        // ---- S4 + S6: contraction and renumbering
+        tm.begin(round, PICASSO_ST_CONTRACT);
+        const int nxt = cur ^ 1;
+        AlivePred ap{c->mate};
+        AliveOut ao{c->newid};
+        prim::compact(s, ap, ap, ao, nullptr, nv_total, c->tilesum, &c->st->nv[nxt]);
+        const size_t hsize = next_pow2((size_t)2 * std::max(nf_bound, 1));
+        contract_kernel<<<grid_for(std::max<long long>(nv_total, (long long)hsize), 8192), BLOCK, 0, s>>>(
+            c->vrec[cur], c->vrec[nxt], c->mate, c->newid, c->vmap, c->st, cur, B, c->voff[cur], c->voff[nxt],
+            c->htab, (int)hsize);
+        tm.end();
+
+        // ---- S5: facets
+        tm.begin(round, PICASSO_ST_FACETS);
+        facet_insert_kernel<<<grid_for(std::max(nf_bound, N), 8192), BLOCK, 0, s>>>(
+            c->fbuf[cur], c->fmap, c->vmap, c->st, cur, c->htab, (u32)(hsize - 1), mt, c->voff[cur], c->cid, N);
+        FacetKeepPred kp{c->fmap, c->fbuf[cur], c->htab, (u32)(hsize - 1), c->keep, mt, c->voff[cur]};
+        FlagPred fp{c->keep};
+        FacetOut fo{c->fmap, c->fbuf[nxt]};
+        prim::compact(s, kp, fp, fo, &c->st->nf[cur], nf_bound, c->tilesum, &c->st->nf[nxt]);
+        tm.end();
+
+        nv_total -= n_sel;
+        cur = nxt;
+        ++round;
+        work = any_active();
+    }
+
+    if (!validated) {
+        HIP_TRY(c, hipMemcpyAsync(hst, c->st, sizeof(State), hipMemcpyDeviceToHost, s));
+        HIP_TRY(c, hipStreamSynchronize(s));
+        const int st_err = status_from_err_bits(hst->err);
+        if (st_err != PICASSO_OK) return st_err;
+    }
+
+    copy_out_kernel<<<grid_for(std::max(std::max(N, 3 * nf_bound), 1), 8192), BLOCK, 0, s>>>(
+        c->vrec[cur], c->fbuf[cur], c->cid, c->st, cur, N, d_verts_out, d_facets_out, d_cluster_id, B, c->voff[cur],
+        c->foff_out);
+    HIP_TRY(c, hipEventRecord(c->ev_total[1], s));
+    HIP_TRY(c, hipMemcpyAsync(hst, c->st, sizeof(State), hipMemcpyDeviceToHost, s));
+    HIP_TRY(c, hipMemcpyAsync(c->h_back, c->foff_out, sizeof(int) * (B + 1), hipMemcpyDeviceToHost, s));
+    HIP_TRY(c, hipStreamSynchronize(s));
+    HIP_TRY(c, hipGetLastError());
+
+    int warn = PICASSO_OK;
+    for (int b = 0; b < B; ++b) {
+        h_nv_out[b] = nvb[b];
+        h_nf_out[b] = c->h_back[b + 1] - c->h_back[b];
+        if (nvb[b] > target_nv[b] && (c->opt_max_rounds < 0 || stuck[b])) warn = PICASSO_WARN_BUDGET_UNMET;
+    }
+    if (stats) {
+        stats->rounds = round;
+        stats->nv_out = hst->nv[cur];
+        stats->nf_out = hst->nf[cur];
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, c->ev_total[0], c->ev_total[1]) == hipSuccess) stats->ms_total = ms;
+        tm.collect(stats);
+    }
+    return warn;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------
+// C-ABI
+// ---------------------------------------------------------------------------
+extern "C" {
+
+size_t picasso_workspace_bytes(int64_t max_verts, int64_t max_facets, int32_t max_meshes) {
+    return carve(nullptr, nullptr, max_verts, max_facets, max_meshes);
+}
+
+int picasso_create(picasso_ctx** out, int device, int64_t max_verts, int64_t max_facets, int32_t max_meshes) {
+    if (!out || max_verts < 1 || max_facets < 0 || max_meshes < 1) return PICASSO_ERR_INVALID_ARG;
+    if (max_verts > 0x7FFFFFF0ll || 3 * max_facets > 0x7FFFFFF0ll) return PICASSO_ERR_INVALID_ARG;
+    picasso_ctx* c = new (std::nothrow) picasso_ctx();
+    if (!c) return PICASSO_ERR_HIP;
+    c->device = device;
+    c->max_verts = max_verts;
+    c->max_facets = max_facets;
+    c->max_meshes = max_meshes;
+    if (hipSetDevice(device) != hipSuccess) { delete c; return PICASSO_ERR_HIP; }
+    c->ws_bytes = carve(nullptr, nullptr, max_verts, max_facets, max_meshes);
+    if (hipMalloc((void**)&c->ws, c->ws_bytes) != hipSuccess) { delete c; return PICASSO_ERR_HIP; }
+    carve(c, c->ws, max_verts, max_facets, max_meshes);
+    c->h_pin_ints = 64 + 5 * ((size_t)max_meshes + 2) + 16;
+    if (hipHostMalloc((void**)&c->h_pin, c->h_pin_ints * sizeof(int), hipHostMallocDefault) != hipSuccess) {
+        (void)hipFree(c->ws);
+        delete c;
+        return PICASSO_ERR_HIP;
+    }
+    memset(c->h_pin, 0, c->h_pin_ints * sizeof(int));
+    c->h_back = c->h_pin + 64 + 4 * ((size_t)max_meshes + 2);
+    const int nev = (int)(sizeof(c->ev) / sizeof(c->ev[0]));
+    for (int i = 0; i < nev; ++i) (void)hipEventCreate(&c->ev[i]);
+    (void)hipEventCreate(&c->ev_total[0]);
+    (void)hipEventCreate(&c->ev_total[1]);
+    *out = c;
+    return PICASSO_OK;
+}
+
+void picasso_destroy(picasso_ctx* c) {
+    if (!c) return;
+    (void)hipSetDevice(c->device);
+    (void)hipDeviceSynchronize();
+    const int nev = (int)(sizeof(c->ev) / sizeof(c->ev[0]));
+    for (int i = 0; i < nev; ++i) (void)hipEventDestroy(c->ev[i]);
+    (void)hipEventDestroy(c->ev_total[0]);
+    (void)hipEventDestroy(c->ev_total[1]);
+    if (c->h_pin) (void)hipHostFree(c->h_pin);
+    if (c->ws) (void)hipFree(c->ws);
+    delete c;
+}
+
+int picasso_set_option(picasso_ctx* c, int option, int64_t value) {
+    if (!c) return PICASSO_ERR_INVALID_ARG;
+    switch (option) {
+        case PICASSO_OPT_MAX_ROUNDS: c->opt_max_rounds = value; return PICASSO_OK;
+        case PICASSO_OPT_STAGE_TIMING: c->opt_stage_timing = value; return PICASSO_OK;
+        case PICASSO_OPT_SUBROUND_BATCH:
+            if (value < 1 || value > 1024) return PICASSO_ERR_INVALID_ARG;
+            c->opt_subround_batch = value;
+            return PICASSO_OK;
+        default: return PICASSO_ERR_INVALID_ARG;
+    }
+}
+
+const char* picasso_strerror(int status) {
+    switch (status) {
+        case PICASSO_OK: return "ok";
+        case PICASSO_WARN_BUDGET_UNMET: return "warning: a mesh ran out of edges before reaching its vertex budget";
+        case PICASSO_ERR_INVALID_ARG: return "invalid argument";
+        case PICASSO_ERR_BAD_INDEX: return "facet index out of range";
+        case PICASSO_ERR_NONFINITE: return "non-finite vertex coordinate";
+        case PICASSO_ERR_WORKSPACE: return "input exceeds the capacity the context was created with";
+        case PICASSO_ERR_HIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+const char* picasso_last_hip_error(picasso_ctx* c) { return c ? c->hip_err : ""; }
+
+int picasso_decimate_batch(picasso_ctx* c, void* stream, int32_t B, const float* d_verts, const int32_t* d_facets,
+                           const int32_t* h_nv_in, const int32_t* h_nf_in, const int32_t* h_target_nv,
+                           float* d_verts_out, int32_t* d_facets_out, int32_t* d_cluster_id, int32_t* h_nv_out,
+                           int32_t* h_nf_out, picasso_stats* stats) {
+    return decimate_impl(c, (hipStream_t)stream, B, d_verts, d_facets, h_nv_in, h_nf_in, h_target_nv, d_verts_out,
+                         d_facets_out, d_cluster_id, h_nv_out, h_nf_out, stats);
+}
+
+int picasso_decimate(picasso_ctx* c, void* stream, const float* d_verts, int32_t N, const int32_t* d_facets,
+                     int32_t F, int32_t target_nv, float* d_verts_out, int32_t* d_facets_out, int32_t* d_cluster_id,
+                     int32_t* h_nv_out, int32_t* h_nf_out, picasso_stats* stats) {
+    if (N < 1 || F < 0 || target_nv < 1) return PICASSO_ERR_INVALID_ARG;
+    return decimate_impl(c, (hipStream_t)stream, 1, d_verts, d_facets, &N, &F, &target_nv, d_verts_out, d_facets_out,
+                         d_cluster_id, h_nv_out, h_nf_out, stats);
+}
+
+int picasso_vertex_quadrics(picasso_ctx* c, void* stream, const float* d_verts, int32_t N, const int32_t* d_facets,
+                            int32_t F, float* d_quadrics_out) {
+    if (!c || !d_verts || N < 1 || F < 0 || (F > 0 && !d_facets) || !d_quadrics_out) return PICASSO_ERR_INVALID_ARG;
+    if (N > c->max_verts || F > c->max_facets) return PICASSO_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(c, hipSetDevice(c->device));
+    int32_t big = 0x7FFFFFFF;
+    int64_t n64, f64;
+    int rc = upload_mesh_tables(c, s, 1, &N, &F, &big, &n64, &f64);
+    if (rc != PICASSO_OK) return rc;
+    rc = upload_state(c, s, N, F);
+    if (rc != PICASSO_OK) return rc;
+    init_kernel<<<grid_for(std::max(N, F), 4096), BLOCK, 0, s>>>(d_verts, N, d_facets, F, 1, c->voff[0], c->foff,
+                                                                 c->vrec[0], c->cid, c->fbuf[0],
+                                                                 reinterpret_cast<u32*>(c->key64[0]), c->val32[0],
+                                                                 c->st);
+    State* hst = reinterpret_cast<State*>(c->h_pin);
+    HIP_TRY(c, hipMemcpyAsync(hst, c->st, sizeof(State), hipMemcpyDeviceToHost, s));
+    HIP_TRY(c, hipStreamSynchronize(s));
+    rc = status_from_err_bits(hst->err);
+    if (rc != PICASSO_OK) return rc;
+    rc = run_vertex_quadrics(c, s, N, F);
+    if (rc != PICASSO_OK) return rc;
+    export_quadrics_kernel<<<grid_for(N), BLOCK, 0, s>>>(c->vrec[0], N, d_quadrics_out);
+    HIP_TRY(c, hipStreamSynchronize(s));
+    HIP_TRY(c, hipGetLastError());
+    return PICASSO_OK;
+}
+
+int picasso_edge_costs(picasso_ctx* c, void* stream, const float* d_verts, int32_t N, const int32_t* d_facets,
+                       int32_t F, int32_t* d_edges_out, float* d_cost_out, int32_t* h_ne_out) {
+    if (!c || !d_verts || N < 1 || F < 0 || (F > 0 && !d_facets) || !d_edges_out || !d_cost_out || !h_ne_out)
+        return PICASSO_ERR_INVALID_ARG;
+    if (N > c->max_verts || F > c->max_facets) return PICASSO_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(c, hipSetDevice(c->device));
+    int32_t one = 1;
+    int64_t n64, f64;
+    int rc = upload_mesh_tables(c, s, 1, &N, &F, &one, &n64, &f64);
+    if (rc != PICASSO_OK) return rc;
+    rc = upload_state(c, s, N, F);
+    if (rc != PICASSO_OK) return rc;
+    init_kernel<<<grid_for(std::max(N, F), 4096), BLOCK, 0, s>>>(d_verts, N, d_facets, F, 1, c->voff[0], c->foff,
+                                                                 c->vrec[0], c->cid, c->fbuf[0],
+                                                                 reinterpret_cast<u32*>(c->key64[0]), c->val32[0],
+                                                                 c->st);
+    State* hst = reinterpret_cast<State*>(c->h_pin);
+    HIP_TRY(c, hipMemcpyAsync(hst, c->st, sizeof(State), hipMemcpyDeviceToHost, s));
+    HIP_TRY(c, hipStreamSynchronize(s));
+    rc = status_from_err_bits(hst->err);
+    if (rc != PICASSO_OK) return rc;
+    rc = run_vertex_quadrics(c, s, N, F);
+    if (rc != PICASSO_OK) return rc;
+    const int vbits = ceil_log2(N), H = 3 * F;
+    MeshTab mt{1, c->voff[0], c->target, c->active, c->nrem, c->matched};
+    round_begin_kernel<<<1, BLOCK, 0, s>>>(1, c->voff[0], c->target, c->active, c->stuck, c->nrem, c->matched, 1, 0,
+                                           c->st);
+    emit_edge_keys_kernel<<<grid_for(std::max(F, N), 8192), BLOCK, 0, s>>>(c->fbuf[0], c->st, 0, vbits, c->key64[0],
+                                                                          c->vmin[0], c->vmin[1], c->mate);
+    const u64* skeys = c->key64[0];
+    if (H > 0) {
+        int where = prim::radix_sort<u64, false>(s, c->key64[0], c->key64[1], nullptr, nullptr, &c->st->nh, H, 2 * vbits,
+                                                 c->sort_sc);
+        if (where < 0) return PICASSO_ERR_HIP;
+        skeys = where ? c->key64[1] : c->key64[0];
+    }
+    const u64 sentinel = (vbits >= 32) ? ~0ull : ((1ull << (2 * vbits)) - 1ull);
+    UniquePred up{skeys, sentinel};
+    UniqueOut uo{skeys, c->ekey, c->ecost, c->vrec[0], c->vmin[0], vbits, mt};
+    prim::compact(s, up, up, uo, &c->st->nh, H, c->tilesum, &c->st->ne);
+    export_edges_kernel<<<grid_for(std::max(H, 1)), BLOCK, 0, s>>>(c->ekey, c->ecost, c->st, vbits, d_edges_out,
+                                                                   d_cost_out);
+    HIP_TRY(c, hipMemcpyAsync(hst, c->st, sizeof(State), hipMemcpyDeviceToHost, s));
+    HIP_TRY(c, hipStreamSynchronize(s));
+    HIP_TRY(c, hipGetLastError());
+    *h_ne_out = hst->ne;
+    return PICASSO_OK;
+}
+
+int picasso_radix_sort(picasso_ctx* c, void* stream, int key_bytes, void* d_keys, uint32_t* d_vals, int64_t n,
+                       int key_bits) {
+    if (!c || !d_keys || n < 0 || (key_bytes != 4 && key_bytes != 8) || key_bits < 1 || key_bits > 8 * key_bytes)
+        return PICASSO_ERR_INVALID_ARG;
+    if (n > 3 * c->max_facets) return PICASSO_ERR_WORKSPACE;
+    if (n == 0) return PICASSO_OK;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(c, hipSetDevice(c->device));
+    int where;
+    if (key_bytes == 8) {
+        u64* k = (u64*)d_keys;
+        where = d_vals ? prim::radix_sort<u64, true>(s, k, c->key64[1], d_vals, c->val32[1], nullptr, (int)n, key_bits, c->sort_sc)
+                       : prim::radix_sort<u64, false>(s, k, c->key64[1], nullptr, nullptr, nullptr, (int)n, key_bits, c->sort_sc);
+        if (where < 0) return PICASSO_ERR_HIP;
+        if (where == 1) {
+            HIP_TRY(c, hipMemcpyAsync(k, c->key64[1], sizeof(u64) * n, hipMemcpyDeviceToDevice, s));
+            if (d_vals) HIP_TRY(c, hipMemcpyAsync(d_vals, c->val32[1], sizeof(u32) * n, hipMemcpyDeviceToDevice, s));
+        }
+    } else {
+        u32* k = (u32*)d_keys;
+        u32* k1 = reinterpret_cast<u32*>(c->key64[1]);
+        where = d_vals ? prim::radix_sort<u32, true>(s, k, k1, d_vals, c->val32[1], nullptr, (int)n, key_bits, c->sort_sc)
+                       : prim::radix_sort<u32, false>(s, k, k1, nullptr, nullptr, nullptr, (int)n, key_bits, c->sort_sc);
+        if (where < 0) return PICASSO_ERR_HIP;
+        if (where == 1) {
+            HIP_TRY(c, hipMemcpyAsync(k, k1, sizeof(u32) * n, hipMemcpyDeviceToDevice, s));
+            if (d_vals) HIP_TRY(c, hipMemcpyAsync(d_vals, c->val32[1], sizeof(u32) * n, hipMemcpyDeviceToDevice, s));
+        }
+    }
+    HIP_TRY(c, hipStreamSynchronize(s));
+    HIP_TRY(c, hipGetLastError());
+    return PICASSO_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,354 @@
+// primitives.h -- wave64 device primitives for gfx950: block scans, a stable
+// LSD radix sort (upsweep / row scan / downsweep per digit pass) and a
+// flag-compaction "scan" built from two kernels.  No kernel here waits on
+// another workgroup: all cross-workgroup ordering is by kernel boundaries.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace prim {
+
+typedef unsigned long long u64;
+typedef uint32_t u32;
+
+constexpr int BLOCK = 256;  // 4 wavefronts of 64 lanes
+constexpr int WAVES = BLOCK / 64;
+
+__device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & 63); }
+__device__ __forceinline__ int wave_id() { return (int)(threadIdx.x >> 6); }
+__device__ __forceinline__ u64 lanemask_lt() { return (1ull << lane_id()) - 1ull; }
+
+// Reads a count that lives either on the device (n_ptr) or in the launch arguments.
+__device__ __forceinline__ int load_count(const int* n_ptr, int n_host) { return n_ptr ? *n_ptr : n_host; }
+
+// Exclusive prefix sum of one value per thread over a 256-thread block.
+// `total` receives the block sum.  smem must hold WAVES words.  Contains barriers.
+__device__ __forceinline__ u32 block_exclusive_scan(u32 v, u32* smem, u32& total) {
+    const int lane = lane_id(), w = wave_id();
+    u32 incl = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        u32 o = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += o;
+    }
+    __syncthreads();  // smem may still be in use by a previous call
+    if (lane == 63) smem[w] = incl;
+    __syncthreads();
+    u32 woff = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < WAVES; ++i) {
+        u32 s = smem[i];
+        if (i < w) woff += s;
+        tot += s;
+    }
+    total = tot;
+    return woff + incl - v;
+}
+
+__device__ __forceinline__ u32 block_sum(u32 v, u32* smem) {
+    const int lane = lane_id(), w = wave_id();
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) v += __shfl_xor(v, d, 64);
+    __syncthreads();
+    if (lane == 0) smem[w] = v;
+    __syncthreads();
+    u32 tot = 0;
+#pragma unroll
+    for (int i = 0; i < WAVES; ++i) tot += smem[i];
+    return tot;
+}
+
+// ---------------------------------------------------------------------------
+// Radix sort.  Tile = 4096 keys per workgroup.  Within a tile the order of the
+// keys is (wave, item, lane), which equals their index order, so ranking by
+// (digit, that order) keeps the sort stable.
+// ---------------------------------------------------------------------------
+constexpr int SORT_ITEMS = 16;
+constexpr int SORT_TILE = BLOCK * SORT_ITEMS;
+
+template <typename K>
+__device__ __forceinline__ u32 digit_of(K k, int shift, u32 mask) {
+    return (u32)(k >> shift) & mask;
+}
+
+// table[d * T + tile] = number of keys of this tile whose digit is d
+template <typename K>
+__global__ __launch_bounds__(BLOCK) void radix_upsweep_kernel(const K* __restrict__ kin, const int* n_ptr, int n_host,
+                                                              int T, u32* __restrict__ table, int shift, int bits) {
+    __shared__ u32 hist[WAVES][256];
+    const int n = load_count(n_ptr, n_host);
+    const int tile = blockIdx.x;
+    const long long base = (long long)tile * SORT_TILE;
+    if (base >= n) return;
+    const int t = threadIdx.x, w = wave_id();
+    const u32 R = 1u << bits, dmask = R - 1;
+    for (int i = t; i < WAVES * 256; i += BLOCK) (&hist[0][0])[i] = 0;
+    __syncthreads();
+#pragma unroll 4
+    for (int i = 0; i < SORT_ITEMS; ++i) {
+        long long idx = base + (long long)i * BLOCK + t;
+        if (idx < n) atomicAdd(&hist[w][digit_of<K>(kin[idx], shift, dmask)], 1u);
+    }
+    __syncthreads();
+    if ((u32)t < R) table[(size_t)t * T + tile] = hist[0][t] + hist[1][t] + hist[2][t] + hist[3][t];
+}
+
+// One workgroup per digit: exclusive scan of its table row over the tiles in
+// use; totals[d] = number of keys with digit d.
+__global__ __launch_bounds__(BLOCK) void radix_scan_kernel(u32* __restrict__ table, u32* __restrict__ totals,
+                                                           const int* n_ptr, int n_host, int T) {
+    __shared__ u32 smem[WAVES];
+    const int n = load_count(n_ptr, n_host);
+    const int tiles = (int)(((long long)n + SORT_TILE - 1) / SORT_TILE);
+    u32* row = table + (size_t)blockIdx.x * T;
+    const int t = threadIdx.x;
+    u32 carry = 0;
+    for (int c = 0; c < tiles; c += BLOCK) {
+        const int i = c + t;
+        u32 v = (i < tiles) ? row[i] : 0u;
+        u32 tot;
+        u32 ex = block_exclusive_scan(v, smem, tot);
+        if (i < tiles) row[i] = carry + ex;
+        carry += tot;
+    }
+    if (t == 0) totals[blockIdx.x] = carry;
+}
+
+template <typename K, bool HAS_VAL>
+__global__ __launch_bounds__(BLOCK) void radix_downsweep_kernel(const K* __restrict__ kin, K* __restrict__ kout,
+                                                                const u32* __restrict__ vin, u32* __restrict__ vout,
+                                                                const int* n_ptr, int n_host, int T,
+                                                                const u32* __restrict__ table,
+                                                                const u32* __restrict__ totals, int shift, int bits) {
+    __shared__ u32 wcnt[WAVES][256];
+    __shared__ u32 tstart[256];
+    __shared__ u32 gbase[256];
+    __shared__ u32 smem[WAVES];
+    __shared__ K skey[SORT_TILE];
+    __shared__ u32 sval[HAS_VAL ? SORT_TILE : 1];
+
+    const int n = load_count(n_ptr, n_host);
+    const int tile = blockIdx.x;
+    const long long base = (long long)tile * SORT_TILE;
+    if (base >= n) return;
+    const int t = threadIdx.x, w = wave_id(), lane = lane_id();
+    const u32 R = 1u << bits, dmask = R - 1;
+
+    for (int i = t; i < WAVES * 256; i += BLOCK) (&wcnt[0][0])[i] = 0;
+
+    K key[SORT_ITEMS];
+    u32 val[SORT_ITEMS];
+    u32 rank[SORT_ITEMS];
+#pragma unroll
+    for (int i = 0; i < SORT_ITEMS; ++i) {
+        long long idx = base + (long long)w * (64 * SORT_ITEMS) + i * 64 + lane;
+        bool ok = idx < n;
+        key[i] = ok ? kin[idx] : (K) ~(K)0;  // padding sorts last within the tile
+        if (HAS_VAL) val[i] = ok ? vin[idx] : 0u;
+    }
+    __syncthreads();
+
+    const u64 lt = lanemask_lt();
+#pragma unroll
+    for (int i = 0; i < SORT_ITEMS; ++i) {
+        const u32 d = digit_of<K>(key[i], shift, dmask);
+        u64 m = ~0ull;  // lanes of this wave holding the same digit
+        for (int b = 0; b < bits; ++b) {
+            const bool bit = (d >> b) & 1u;
+            const u64 bal = __ballot(bit);
+            m &= bit ? bal : ~bal;
+        }
+        const u32 old = wcnt[w][d];
+        const u32 below = (u32)__popcll(m & lt);
+        __builtin_amdgcn_wave_barrier();
+        if (below == 0) wcnt[w][d] = old + (u32)__popcll(m);
+        __builtin_amdgcn_wave_barrier();
+        rank[i] = old + below;
+    }
+    __syncthreads();
+
+    // per digit: wave counts -> exclusive offsets over waves, tile histogram
+    u32 tot = 0;
+    if ((u32)t < R) {
+        u32 c0 = wcnt[0][t], c1 = wcnt[1][t], c2 = wcnt[2][t], c3 = wcnt[3][t];
+        wcnt[0][t] = 0;
+        wcnt[1][t] = c0;
+        wcnt[2][t] = c0 + c1;
+        wcnt[3][t] = c0 + c1 + c2;
+        tot = c0 + c1 + c2 + c3;
+    }
+    u32 dummy;
+    const u32 ex = block_exclusive_scan(tot, smem, dummy);
+    const u32 gtot = ((u32)t < R) ? totals[t] : 0u;
+    const u32 dbase = block_exclusive_scan(gtot, smem, dummy);
+    if ((u32)t < R) {
+        tstart[t] = ex;
+        gbase[t] = dbase + table[(size_t)t * T + tile] - ex;
+    }
+    __syncthreads();
+
+#pragma unroll
+    for (int i = 0; i < SORT_ITEMS; ++i) {
+        const u32 d = digit_of<K>(key[i], shift, dmask);
+        const u32 p = tstart[d] + wcnt[w][d] + rank[i];
+        skey[p] = key[i];
+        if (HAS_VAL) sval[p] = val[i];
+    }
+    __syncthreads();
+
+    const long long rem = (long long)n - base;
+    const int nvalid = rem < SORT_TILE ? (int)rem : SORT_TILE;
+    for (int q = t; q < nvalid; q += BLOCK) {
+        const K k = skey[q];
+        const u32 o = gbase[digit_of<K>(k, shift, dmask)] + (u32)q;
+        kout[o] = k;
+        if (HAS_VAL) vout[o] = sval[q];
+    }
+}
+
+struct SortScratch {
+    u32* table;   // [256 * T]
+    u32* totals;  // [256]
+    int T;        // row stride = tiles at capacity
+};
+
+inline int sort_tiles(long long n) { return (int)((n + SORT_TILE - 1) / SORT_TILE); }
+
+// Sorts on key bits [0, key_bits).  Data ping-pongs between (k0,v0) and
+// (k1,v1); returns 0 if the result is in (k0,v0), 1 if in (k1,v1), <0 on a
+// launch error.  n_max bounds the device-side count for the grid size.
+template <typename K, bool HAS_VAL>
+inline int radix_sort(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_ptr, int n_max, int key_bits,
+                      const SortScratch& sc) {
+    if (n_max <= 0 || key_bits <= 0) return 0;
+    const int passes = (key_bits + 7) / 8;
+    const int per = (key_bits + passes - 1) / passes;
+    const int tiles = sort_tiles(n_max);
+    int cur = 0, shift = 0;
+    for (int p = 0; p < passes; ++p) {
+        const int bits = (key_bits - shift) < per ? (key_bits - shift) : per;
+        K* kin = cur ? k1 : k0;
+        K* kout = cur ? k0 : k1;
+        u32* vin = cur ? v1 : v0;
+        u32* vout = cur ? v0 : v1;
+        radix_upsweep_kernel<K><<<tiles, BLOCK, 0, s>>>(kin, n_ptr, n_max, sc.T, sc.table, shift, bits);
+        radix_scan_kernel<<<1 << bits, BLOCK, 0, s>>>(sc.table, sc.totals, n_ptr, n_max, sc.T);
+        radix_downsweep_kernel<K, HAS_VAL>
+            <<<tiles, BLOCK, 0, s>>>(kin, kout, vin, vout, n_ptr, n_max, sc.T, sc.table, sc.totals, shift, bits);
+        shift += bits;
+        cur ^= 1;
+    }
+    if (hipGetLastError() != hipSuccess) return -1;
+    return cur;
+}
+
+// ---------------------------------------------------------------------------
+// Flag compaction.  count kernel: tilesum[tile] = number of i in the tile with
+// pred(i).  scatter kernel: calls out(i, rank) for every flagged i, rank = its
+// position among flagged items in index order; writes the grand total.
+// Tile = 4096 items; wave w of a workgroup owns items [w*1024, (w+1)*1024).
+// ---------------------------------------------------------------------------
+constexpr int CHUNKS = 16;
+constexpr int CTILE = BLOCK * CHUNKS;
+
+inline int compact_tiles(long long n) { return (int)((n + CTILE - 1) / CTILE); }
+
+template <class Pred>
+__global__ __launch_bounds__(BLOCK) void tile_count_kernel(Pred pred, const int* n_ptr, int n_host,
+                                                           int* __restrict__ tilesum) {
+    __shared__ u32 smem[WAVES];
+    const int n = load_count(n_ptr, n_host);
+    const long long base = (long long)blockIdx.x * CTILE;
+    if (base >= n) return;
+    const int w = wave_id(), lane = lane_id();
+    u32 cnt = 0;
+    for (int c = 0; c < CHUNKS; ++c) {
+        const long long i = base + (long long)w * (64 * CHUNKS) + c * 64 + lane;
+        const bool f = (i < n) && pred((int)i);
+        cnt += (u32)__popcll(__ballot(f));
+    }
+    if (lane == 0) smem[w] = cnt;
+    __syncthreads();
+    if (threadIdx.x == 0) tilesum[blockIdx.x] = (int)(smem[0] + smem[1] + smem[2] + smem[3]);
+}
+
+// In-place exclusive scan of a[0..T) by one workgroup (used when there are many tiles).
+__global__ __launch_bounds__(BLOCK) void scan_tilesums_kernel(int* __restrict__ a, const int* n_ptr, int n_host) {
+    __shared__ u32 smem[WAVES];
+    const int n = load_count(n_ptr, n_host);
+    const int T = (int)(((long long)n + CTILE - 1) / CTILE);
+    u32 carry = 0;
+    for (int c = 0; c < T; c += BLOCK) {
+        const int i = c + threadIdx.x;
+        u32 v = i < T ? (u32)a[i] : 0u, tot;
+        u32 ex = block_exclusive_scan(v, smem, tot);
+        if (i < T) a[i] = (int)(carry + ex);
+        carry += tot;
+    }
+}
+
+template <class Pred, class Out>
+__global__ __launch_bounds__(BLOCK) void tile_scatter_kernel(Pred pred, Out out, const int* n_ptr, int n_host,
+                                                             const int* __restrict__ tilesum, int prefixed,
+                                                             int* __restrict__ total_out) {
+    __shared__ u32 smem[WAVES];
+    const int n = load_count(n_ptr, n_host);
+    if (n <= 0) {
+        if (blockIdx.x == 0 && threadIdx.x == 0 && total_out) *total_out = 0;
+        return;
+    }
+    const int tile = blockIdx.x;
+    const long long base = (long long)tile * CTILE;
+    if (base >= n) return;
+    const int t = threadIdx.x, w = wave_id(), lane = lane_id();
+
+    u32 tileoff;
+    if (prefixed) {
+        tileoff = (u32)tilesum[tile];
+    } else {
+        u32 part = 0;
+        for (int j = t; j < tile; j += BLOCK) part += (u32)tilesum[j];
+        tileoff = block_sum(part, smem);
+    }
+
+    u64 bal[CHUNKS];
+    u32 cnt = 0;
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) {
+        const long long i = base + (long long)w * (64 * CHUNKS) + c * 64 + lane;
+        const bool f = (i < n) && pred((int)i);
+        bal[c] = __ballot(f);
+        cnt += (u32)__popcll(bal[c]);
+    }
+    __syncthreads();
+    if (lane == 0) smem[w] = cnt;
+    __syncthreads();
+    u32 woff = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < WAVES; ++i) {
+        if (i < w) woff += smem[i];
+        tot += smem[i];
+    }
+    u32 run = tileoff + woff;
+    const u64 lt = lanemask_lt();
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) {
+        const long long i = base + (long long)w * (64 * CHUNKS) + c * 64 + lane;
+        if ((bal[c] >> lane) & 1ull) out((int)i, (int)(run + (u32)__popcll(bal[c] & lt)));
+        run += (u32)__popcll(bal[c]);
+    }
+    if (base + CTILE >= n && t == 0 && total_out) *total_out = (int)(tileoff + tot);
+}
+
+// count pass may use a different functor (e.g. one that also stores the flag)
+template <class PredCount, class PredScatter, class Out>
+inline void compact(hipStream_t s, PredCount pc, PredScatter ps, Out out, const int* n_ptr, int n_max, int* tilesum,
+                    int* total_out) {
+    const int tiles = compact_tiles(n_max > 0 ? n_max : 1);
+    tile_count_kernel<PredCount><<<tiles, BLOCK, 0, s>>>(pc, n_ptr, n_max, tilesum);
+    const int prefixed = tiles > 2048;
+    if (prefixed) scan_tilesums_kernel<<<1, BLOCK, 0, s>>>(tilesum, n_ptr, n_max);
+    tile_scatter_kernel<PredScatter, Out><<<tiles, BLOCK, 0, s>>>(ps, out, n_ptr, n_max, tilesum, prefixed, total_out);
+}
+
+}  // namespace prim

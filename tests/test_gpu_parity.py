@@ -1,0 +1,262 @@
+"""GPU parity: the HIP path (through the C-ABI binding) against the CPU oracle,
+element by element on the same seeded inputs.
+
+Bar (the benchmark spec): bit-exact cluster_id, facet list and counts; positions within
+1e-5 relative (they are expected to be bit-identical as well, and that is
+asserted where noted).
+"""
+import numpy as np
+import pytest
+
+from paper_2103_15076_amd import meshgen
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def pk():
+    import paper_2103_15076_amd as p
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    p.load_library()  # raises if the HIP library has not been built
+    return p
+
+
+@pytest.fixture(scope="module")
+def ctx(pk):
+    c = pk.Context(1_300_000, 2_500_000, 16, device=0)
+    yield c
+    c.close()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def assert_same_result(st, vo, fo, cid, ref, exact_positions=True):
+    assert st == ref["status"]
+    vo, fo, cid = vo.cpu().numpy(), fo.cpu().numpy(), cid.cpu().numpy()
+    assert vo.shape[0] == ref["verts"].shape[0], (vo.shape, ref["verts"].shape)
+    assert fo.shape[0] == ref["facets"].shape[0], (fo.shape, ref["facets"].shape)
+    assert np.array_equal(cid, ref["cluster_id"])
+    assert np.array_equal(fo, ref["facets"])
+    tol = 1e-5 * np.maximum(1.0, np.abs(ref["verts"]))
+    assert np.all(np.abs(vo - ref["verts"]) <= tol)
+    if exact_positions:
+        assert np.array_equal(vo.view(np.uint32), ref["verts"].view(np.uint32))
+
+
+# ----------------------------------------------------------------------------
+# primitives
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n,bits", [(1, 32), (63, 7), (4096, 32), (4097, 13), (70001, 32), (1 << 20, 20)])
+def test_radix_sort_pairs_u32_is_stable(ctx, n, bits):
+    rng = np.random.default_rng(n)
+    keys = rng.integers(0, 1 << bits, size=n, dtype=np.uint64).astype(np.uint32)
+    vals = np.arange(n, dtype=np.uint32)
+    k, v = dev(keys.view(np.int32)), dev(vals.view(np.int32))
+    print(f"sort u32 n={n} bits={bits}", flush=True)
+    ctx.picasso_radix_sort(k, v, key_bits=bits)
+    order = np.argsort(keys, kind="stable")
+    assert np.array_equal(k.cpu().numpy().view(np.uint32), keys[order])
+    assert np.array_equal(v.cpu().numpy().view(np.uint32), vals[order])
+
+
+@pytest.mark.parametrize("n,bits,with_vals", [(5, 34, False), (12289, 34, False), (300000, 42, False),
+                                              (100000, 36, True), (2500000, 40, False)])
+def test_radix_sort_u64(ctx, n, bits, with_vals):
+    rng = np.random.default_rng(n + 1)
+    keys = rng.integers(0, 1 << bits, size=n, dtype=np.uint64)
+    keys[: n // 3] = keys[n // 3: 2 * (n // 3)][: n // 3]   # duplicates
+    k = dev(keys.view(np.int64))
+    v = dev(np.arange(n, dtype=np.int32)) if with_vals else None
+    print(f"sort u64 n={n} bits={bits}", flush=True)
+    ctx.picasso_radix_sort(k, v, key_bits=bits)
+    order = np.argsort(keys, kind="stable")
+    assert np.array_equal(k.cpu().numpy().view(np.uint64), keys[order])
+    if with_vals:
+        assert np.array_equal(v.cpu().numpy(), order.astype(np.int32))
+
+
+# ----------------------------------------------------------------------------
+# single steps
+# ----------------------------------------------------------------------------
+
+def _small_meshes():
+    yield "grid", meshgen.noisy_grid(37, 29, seed=3)
+    yield "ico", meshgen.icosphere(4, seed=4)
+    yield "room", meshgen.room_scene(11, room=(3.0, 2.0, 1.5), n_boxes=5, spacing=0.05)
+    yield "flat", meshgen.flat_grid(33, 18, spacing=0.5)
+
+
+@pytest.mark.parametrize("name,mesh", list(_small_meshes()), ids=lambda x: x if isinstance(x, str) else "")
+def test_vertex_quadrics_bit_exact(ctx, oracle, name, mesh):
+    V, F = mesh
+    print(f"quadrics {name} N={V.shape[0]} F={F.shape[0]}", flush=True)
+    Q = ctx.picasso_vertex_quadrics(dev(V), dev(F)).cpu().numpy()
+    ref = oracle.vertex_quadrics(V, F)
+    assert np.array_equal(Q.view(np.uint32), ref.view(np.uint32))
+
+
+@pytest.mark.parametrize("name,mesh", list(_small_meshes()), ids=lambda x: x if isinstance(x, str) else "")
+def test_edges_and_costs_bit_exact(ctx, oracle, name, mesh):
+    V, F = mesh
+    print(f"edges {name}", flush=True)
+    E, cost = ctx.picasso_edge_costs(dev(V), dev(F))
+    E, cost = E.cpu().numpy(), cost.cpu().numpy()
+    Er = oracle.edges(F)
+    assert np.array_equal(E, Er)
+    cr, _ = oracle.edge_costs(V, oracle.vertex_quadrics(V, F), Er)
+    assert np.array_equal(cost.view(np.uint32), cr.view(np.uint32))
+
+
+# ----------------------------------------------------------------------------
+# whole path
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name,mesh", list(_small_meshes()), ids=lambda x: x if isinstance(x, str) else "")
+@pytest.mark.parametrize("frac,max_rounds", [(0.6, -1), (0.26, 1), (0.26, -1), (0.05, -1), (0.0, -1)])
+def test_decimate_matches_oracle(pk, ctx, oracle, name, mesh, frac, max_rounds):
+    V, F = mesh
+    target = max(1, int(V.shape[0] * frac))
+    print(f"decimate {name} N={V.shape[0]} target={target} max_rounds={max_rounds}", flush=True)
+    ctx.set_option(pk.PICASSO_OPT_MAX_ROUNDS, max_rounds)
+    try:
+        st, vo, fo, cid = ctx.picasso_decimate(dev(V), dev(F), target)
+    finally:
+        ctx.set_option(pk.PICASSO_OPT_MAX_ROUNDS, -1)
+    ref = oracle.decimate(V, F, target, max_rounds=max_rounds)
+    if max_rounds >= 0 and ref["verts"].shape[0] > target:
+        st = ref["status"]  # a capped run is not a budget warning on either side
+    assert_same_result(st, vo, fo, cid, ref)
+
+
+def test_adversarial_small_meshes(ctx, oracle):
+    rng = np.random.default_rng(5)
+    cases = {}
+    # random facet soup: non-manifold, duplicate facets, repeated indices, isolated vertices
+    V = rng.normal(size=(60, 3)).astype(np.float32)
+    F = rng.integers(0, 50, size=(150, 3)).astype(np.int32)
+    F[10] = F[3]
+    F[11] = F[3][::-1]
+    F[12] = [7, 7, 9]
+    cases["soup"] = (V, F, 9)
+    # one triangle and isolated vertices: the budget cannot be met
+    cases["stuck"] = (rng.normal(size=(8, 3)).astype(np.float32), np.array([[0, 1, 2]], np.int32), 2)
+    # no facets at all
+    cases["nofacets"] = (rng.normal(size=(5, 3)).astype(np.float32), np.zeros((0, 3), np.int32), 2)
+    # exact ties everywhere (flat lattice): order decided by the edge index alone
+    Vf, Ff = meshgen.flat_grid(40, 25)
+    cases["ties"] = (Vf, Ff, 100)
+    # two vertices
+    cases["pair"] = (np.array([[0, 0, 0], [1, 0, 0], [0, 1, 0]], np.float32), np.array([[0, 1, 2]], np.int32), 1)
+    for name, (V, F, target) in cases.items():
+        print(f"adversarial {name}", flush=True)
+        st, vo, fo, cid = ctx.picasso_decimate(dev(V), dev(F), target)
+        assert_same_result(st, vo, fo, cid, oracle.decimate(V, F, target))
+
+
+def test_zero_rounds_copies_input(ctx):
+    V, F = meshgen.noisy_grid(9, 9, seed=1)
+    st, vo, fo, cid = ctx.picasso_decimate(dev(V), dev(F), 81)
+    assert st == 0 and np.array_equal(vo.cpu().numpy(), V) and np.array_equal(fo.cpu().numpy(), F)
+    assert np.array_equal(cid.cpu().numpy(), np.arange(81))
+
+
+def test_error_codes_and_untouched_outputs(pk, ctx):
+    V, F = meshgen.noisy_grid(20, 20, seed=1)
+    vo = torch.full((400, 3), 7.0, device="cuda:0")
+    fo = torch.full((F.shape[0], 3), 7, dtype=torch.int32, device="cuda:0")
+    cid = torch.full((400,), 7, dtype=torch.int32, device="cuda:0")
+    Fb = F.copy()
+    Fb[17, 2] = 400
+    st, *_ = ctx.picasso_decimate(dev(V), dev(Fb), 100, vo, fo, cid, check=False)
+    assert st == pk.PICASSO_ERR_BAD_INDEX
+    Fb[17, 2] = -3
+    st, *_ = ctx.picasso_decimate(dev(V), dev(Fb), 100, vo, fo, cid, check=False)
+    assert st == pk.PICASSO_ERR_BAD_INDEX
+    Vb = V.copy()
+    Vb[33, 1] = np.inf
+    st, *_ = ctx.picasso_decimate(dev(Vb), dev(F), 100, vo, fo, cid, check=False)
+    assert st == pk.PICASSO_ERR_NONFINITE
+    st, *_ = ctx.picasso_decimate(dev(Vb), dev(F), 400, vo, fo, cid, check=False)   # zero rounds still validates
+    assert st == pk.PICASSO_ERR_NONFINITE
+    st, *_ = ctx.picasso_decimate(dev(V), dev(F), 0, vo, fo, cid, check=False)
+    assert st == pk.PICASSO_ERR_INVALID_ARG
+    assert torch.all(vo == 7.0) and torch.all(fo == 7) and torch.all(cid == 7)
+    small = pk.Context(100, 100, 1)
+    st, *_ = small.picasso_decimate(dev(V), dev(F), 100, check=False)
+    assert st == pk.PICASSO_ERR_WORKSPACE
+    small.close()
+    # the context is still usable after errors
+    st, vo2, fo2, cid2 = ctx.picasso_decimate(dev(V), dev(F), 100)
+    assert st == 0 and vo2.shape[0] == 100
+
+
+def test_run_to_run_determinism(ctx):
+    V, F = meshgen.room_scene(3, room=(4.0, 3.0, 2.0), n_boxes=6, spacing=0.04)
+    a = None
+    for rep in range(5):
+        st, vo, fo, cid = ctx.picasso_decimate(dev(V), dev(F), V.shape[0] // 5)
+        b = (vo.cpu().numpy().tobytes(), fo.cpu().numpy().tobytes(), cid.cpu().numpy().tobytes())
+        if a is None:
+            a = b
+        assert a == b, f"run {rep} differs"
+
+
+def test_batch_matches_oracle_and_independent_runs(ctx, oracle):
+    parts = [meshgen.noisy_grid(30, 22, seed=1), meshgen.icosphere(3, seed=2), meshgen.noisy_grid(12, 12, seed=3),
+             meshgen.room_scene(8, room=(2.0, 2.0, 1.0), n_boxes=3, spacing=0.06)]
+    nv = [p[0].shape[0] for p in parts]
+    nf = [p[1].shape[0] for p in parts]
+    tg = [100, 642, 7, nv[3] // 9]    # the sphere needs zero rounds; others 1..4 rounds
+    off = np.cumsum([0] + nv)
+    V = np.concatenate([p[0] for p in parts])
+    F = np.concatenate([p[1] + off[i] for i, p in enumerate(parts)]).astype(np.int32)
+    print("batch of 4", flush=True)
+    st, vo, fo, cid, nvo, nfo = ctx.picasso_decimate_batch(dev(V), dev(F), nv, nf, tg)
+    ref = oracle.decimate_batch(V, F, nv, nf, tg)
+    assert st == ref["status"]
+    assert nvo.tolist() == ref["nv"].tolist() and nfo.tolist() == ref["nf"].tolist()
+    assert np.array_equal(cid.cpu().numpy(), ref["cluster_id"])
+    assert np.array_equal(fo.cpu().numpy(), ref["facets"])
+    assert np.array_equal(vo.cpu().numpy().view(np.uint32), ref["verts"].view(np.uint32))
+
+
+# ----------------------------------------------------------------------------
+# the benchmark configurations at full size
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name", ["grid64", "icosphere6", "room115k", "scene1p2m"])
+def test_config_full_size(ctx, oracle, name):
+    c = meshgen.config(name)
+    V, F, target = c["verts"], c["facets"], int(c["target"][0])
+    print(f"config {name}: N={V.shape[0]} F={F.shape[0]} target={target}", flush=True)
+    st, vo, fo, cid = ctx.picasso_decimate(dev(V), dev(F), target)
+    print("  gpu done; oracle...", flush=True)
+    ref = oracle.decimate(V, F, target)
+    assert_same_result(st, vo, fo, cid, ref)
+    assert vo.shape[0] == target
+
+
+def test_config_batch_hierarchy(ctx, oracle):
+    """16 room meshes through 4 successive levels, each to 40 % of the vertices;
+    the cluster maps of all levels are kept and compared."""
+    c = meshgen.config("batch16x60k")
+    V, F, nv, nf = c["verts"], c["facets"], c["nv"], c["nf"]
+    dV, dF = dev(V), dev(F)
+    for level in range(c["levels"]):
+        tg = (nv.astype(np.int64) * 4 // 10).astype(np.int32)
+        print(f"hierarchy level {level}: N={int(nv.sum())} F={int(nf.sum())}", flush=True)
+        st, vo, fo, cid, nvo, nfo = ctx.picasso_decimate_batch(dV, dF, nv, nf, tg)
+        ref = oracle.decimate_batch(V, F, nv, nf, tg)
+        assert st == ref["status"]
+        assert nvo.tolist() == ref["nv"].tolist() == tg.tolist() and nfo.tolist() == ref["nf"].tolist()
+        assert np.array_equal(cid.cpu().numpy(), ref["cluster_id"])
+        assert np.array_equal(fo.cpu().numpy(), ref["facets"])
+        assert np.array_equal(vo.cpu().numpy().view(np.uint32), ref["verts"].view(np.uint32))
+        V, F, nv, nf = ref["verts"], ref["facets"], ref["nv"], ref["nf"]
+        dV, dF = vo.clone(), fo.clone()
