@@ -1,0 +1,149 @@
+#!/usr/bin/env python3
+"""Benchmark of the decimation hot path on one MI355X.
+
+One "step" = one whole picasso_decimate call (vertex quadrics, then every
+round: edges, costs, selection, contraction, facet clean-up) on the
+115k-vertex synthetic room mesh, decimated to 41,500 vertices (about 36 %),
+inputs resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload room115k]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="room115k")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true",
+                    help="leave out the per-launch hipEvents of the roofline measurement")
+    ap.add_argument("--stages", action="store_true", help="also print per-stage times to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures ONE GPU only (the path shards by mesh; see DESIGN.md); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2103_15076_amd as pk
+    from paper_2103_15076_amd import meshgen
+
+    pk.load_library()  # fails loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    cfg = meshgen.config(args.workload)
+    V, F = cfg["verts"], cfg["facets"]
+    nv_in, nf_in, target = cfg["nv"], cfg["nf"], cfg["target"]
+    N, NF, B = int(V.shape[0]), int(F.shape[0]), int(nv_in.shape[0])
+    dV, dF = torch.from_numpy(V).to(dev), torch.from_numpy(F).to(dev)
+    vo = torch.empty((N, 3), dtype=torch.float32, device=dev)
+    fo = torch.empty((NF, 3), dtype=torch.int32, device=dev)
+    cid = torch.empty((N,), dtype=torch.int32, device=dev)
+    ctx = pk.Context(N, NF, B, device=0)
+    stream = torch.cuda.current_stream()
+
+    def step(stats=None):
+        if B == 1:
+            return ctx.picasso_decimate(dV, dF, int(target[0]), vo, fo, cid, stats=stats, stream=stream)
+        return ctx.picasso_decimate_batch(dV, dF, nv_in, nf_in, target, vo, fo, cid, stats=stats, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps, hipEvents on the launch stream + wall clock
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ctx.set_option(pk.PICASSO_OPT_KERNEL_TIMING, 0 if args.no_kernel_events else 1)
+    ctx.picasso_kernel_timing(reset=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for _ in range(args.steps):
+        res = step()
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ev_ms = ev0.elapsed_time(ev1)
+    ms_per_step = max(wall_ms, ev_ms) / args.steps
+    nv_out, nf_out = int(res[1].shape[0]), int(res[2].shape[0])
+    kt = ctx.picasso_kernel_timing(reset=True)   # hipEvents around every launch of the dominant kernel, inside the timed region
+
+    # ---- one extra call for the per-round shape and stage times
+    st = pk.picasso_stats()
+    ctx.set_option(pk.PICASSO_OPT_KERNEL_TIMING, 0)
+    ctx.set_option(pk.PICASSO_OPT_STAGE_TIMING, 1)
+    step(st)
+    ctx.set_option(pk.PICASSO_OPT_STAGE_TIMING, 0)
+    sd = st.as_dict()
+    if args.stages:
+        print(json.dumps(sd), file=sys.stderr)
+
+    roofline = None
+    if kt["launches"] > 0:
+        avg_ms = kt["ms_total"] / kt["launches"]
+        bytes_per_launch = kt["bytes_total"] / kt["launches"]
+        achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": kt["kernel"], "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": None,
+                    "launches_per_step": kt["launches"] / args.steps, "avg_launch_us": round(avg_ms * 1e3, 3),
+                    "algorithmic_bytes_per_launch": int(bytes_per_launch)}
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        times = []
+        reps = 5 if N < 500000 else 2
+        for _ in range(reps):
+            c0 = time.perf_counter()
+            if B == 1:
+                ref = oracle.decimate(V, F, int(target[0]))
+            else:
+                ref = oracle.decimate_batch(V, F, nv_in, nf_in, target)
+            times.append(time.perf_counter() - c0)
+        med = float(np.median(times))
+        same = (np.array_equal(res[3].cpu().numpy(), ref["cluster_id"])
+                and np.array_equal(res[2].cpu().numpy(), ref["facets"]))
+        cpu_baseline = {"value": round(NF / med, 1), "unit": "facets/s", "cores": 1, "kind": "oracle",
+                        "sample": f"the full workload, median of {reps} runs ({med * 1e3:.1f} ms per decimation)",
+                        "ms_per_decimation": round(med * 1e3, 2), "gpu_matches_oracle_bit_exact": bool(same)}
+
+    out = {
+        "metric": "input facets/s per decimation (ms per decimation in ms_per_step)",
+        "value": round(NF / (ms_per_step * 1e-3), 1),
+        "unit": "facets/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "n_meshes": B, "verts_in": N, "facets_in": NF,
+                   "target_nv": int(np.sum(target)), "verts_out": nv_out, "facets_out": nf_out,
+                   "rounds": sd["rounds"], "subrounds": sd["subrounds"], "edges": sd["ne"]},
+        "paper_context": {"ms": 65.0, "gpu": "RTX 2080 Ti (paper's machine, its own 115,114-vertex mesh)"},
+        "event_ms_per_step": round(ev_ms / args.steps, 4),
+        "stage_ms": {k: round(sum(r[k] for r in sd["ms_stage"]), 4) for k in pk.binding.STAGE_NAMES},
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+    }
+    print(json.dumps(out))
+    ctx.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -23,6 +23,7 @@ PICASSO_ERR_HIP = -5
 PICASSO_OPT_MAX_ROUNDS = 0
 PICASSO_OPT_STAGE_TIMING = 1
 PICASSO_OPT_SUBROUND_BATCH = 2
+PICASSO_OPT_KERNEL_TIMING = 3
 
 PICASSO_STATS_ROUNDS = 32
 PICASSO_ST_COUNT = 8
@@ -31,7 +32,7 @@ STAGE_NAMES = ("quadrics", "edges", "select", "contract", "facets")
 EXPORTED_SYMBOLS = (
     "picasso_workspace_bytes", "picasso_create", "picasso_destroy", "picasso_set_option", "picasso_strerror",
     "picasso_last_hip_error", "picasso_decimate", "picasso_decimate_batch", "picasso_vertex_quadrics",
-    "picasso_edge_costs", "picasso_radix_sort",
+    "picasso_edge_costs", "picasso_radix_sort", "picasso_kernel_timing",
 )
 
 
@@ -101,6 +102,9 @@ def load_library():
     lib.picasso_vertex_quadrics.argtypes = [vp, vp, vp, i32, vp, i32, vp]
     lib.picasso_edge_costs.restype = ctypes.c_int
     lib.picasso_edge_costs.argtypes = [vp, vp, vp, i32, vp, i32, vp, vp, ctypes.POINTER(i32)]
+    lib.picasso_kernel_timing.restype = ctypes.c_int
+    lib.picasso_kernel_timing.argtypes = [vp, ctypes.c_int, ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double),
+                                          ctypes.POINTER(ctypes.c_double)]
     lib.picasso_radix_sort.restype = ctypes.c_int
     lib.picasso_radix_sort.argtypes = [vp, vp, ctypes.c_int, vp, vp, i64, ctypes.c_int]
     _lib = lib
@@ -163,6 +167,13 @@ class Context:
         st = self._lib.picasso_set_option(self._h, int(option), int(value))
         if st != PICASSO_OK:
             raise PicassoError(st, picasso_strerror(st))
+
+    def picasso_kernel_timing(self, reset=False):
+        """Totals for the edge-key sort's scatter kernel while PICASSO_OPT_KERNEL_TIMING is on."""
+        n, ms, by = ctypes.c_int64(0), ctypes.c_double(0.0), ctypes.c_double(0.0)
+        self._lib.picasso_kernel_timing(self._h, int(bool(reset)), ctypes.byref(n), ctypes.byref(ms), ctypes.byref(by))
+        return dict(kernel="radix_downsweep_kernel<u64> (edge-key sort scatter)", launches=n.value, ms_total=ms.value,
+                    bytes_total=by.value)
 
     def last_hip_error(self) -> str:
         return self._lib.picasso_last_hip_error(self._h).decode()

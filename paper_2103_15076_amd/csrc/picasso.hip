@@ -41,7 +41,8 @@ struct State {
     int ne;        // distinct edges of the current round
     int live[3];   // worklist lengths of the selection sub-rounds (rotating)
     int trunc_n;   // matched edges entering the budget truncation
-    int pad[5];
+    int sel_k;     // sub-round index the selection has reached (buffer rotation phase)
+    int pad[4];
 };
 
 // One vertex = 64 bytes: position and the 10 quadric coefficients.
@@ -52,6 +53,9 @@ struct __attribute__((aligned(16))) VRec {
     float b2, c, w1, w2;
 };
 
+constexpr int MATCH_SLOTS = 32;
+constexpr int MATCH_PAD = 32;  // ints: one 128-byte line per slot
+
 struct MeshTab {       // per-mesh tables, all device pointers, B entries (+1 for offsets)
     int B;
     const int* voff;   // [B+1] current vertex offsets
@@ -59,6 +63,8 @@ struct MeshTab {       // per-mesh tables, all device pointers, B entries (+1 fo
     const int* active; // [B] mesh takes part in this round
     const int* nrem;   // [B] pairs still to contract (budget of Alg. 2 line 4)
     int* matched;      // [B] pairs formed this round
+    int* mslots;       // [B][MATCH_SLOTS][MATCH_PAD] partial pair counts, spread over cache lines so that
+                       // the counting atomics of thousands of waves do not queue on one address
 };
 
 __device__ __forceinline__ int mesh_of(const int* __restrict__ voff, int B, int v) {
@@ -191,7 +197,9 @@ __global__ __launch_bounds__(BLOCK) void quadric_reduce_kernel(VRec* __restrict_
 // ---------------------------------------------------------------------------
 __global__ void round_begin_kernel(int B, const int* __restrict__ voff, const int* __restrict__ target,
                                    int* __restrict__ active, int* __restrict__ stuck, int* __restrict__ nrem,
-                                   int* __restrict__ matched, int first_round, int cur, State* st) {
+                                   int* __restrict__ matched, int* __restrict__ mslots, int first_round, int cur,
+                                   State* st) {
+    for (int i = threadIdx.x; i < B * MATCH_SLOTS; i += blockDim.x) mslots[(size_t)i * MATCH_PAD] = 0;
     for (int b = threadIdx.x; b < B; b += blockDim.x) {
         const int nvb = voff[b + 1] - voff[b];
         if (!first_round && active[b] && matched[b] == 0) stuck[b] = 1;
@@ -207,6 +215,7 @@ __global__ void round_begin_kernel(int B, const int* __restrict__ voff, const in
         st->live[1] = 0;
         st->live[2] = 0;
         st->trunc_n = 0;
+        st->sel_k = 0;
     }
 }
 
@@ -304,8 +313,10 @@ struct UniqueOut {
 // sub-round k reads bids in vmin[k%3], places the survivors' bids in
 // vmin[(k+1)%3] and clears their slots in vmin[(k+2)%3].
 // ---------------------------------------------------------------------------
-constexpr int SEL_ITEMS = 4;
+constexpr int SEL_ITEMS = 1;
 constexpr int SEL_TILE = BLOCK * SEL_ITEMS;
+constexpr int TAIL_THREADS = 1024;
+constexpr int TAIL_MAX = 8192;  // live edges the single-workgroup tail takes over
 
 struct SelArgs {
     const u64* ekey;
@@ -318,6 +329,15 @@ struct SelArgs {
     int vbits;
 };
 
+// Bids are read with device-scope atomic loads where the same kernel also
+// changes them (the tail), with plain loads otherwise.
+template <bool COHERENT>
+__device__ __forceinline__ u64 load_bid(const u64* p) {
+    if (COHERENT) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return *p;
+}
+
+template <bool COHERENT>
 __device__ __forceinline__ bool vertex_pairs_now(const u64* __restrict__ cur, const u64* __restrict__ ekey, int vbits,
                                                  int x, u64 mx) {
     // The best live edge at x is accepted in this sub-round iff it is also the best at its other end.
@@ -325,7 +345,44 @@ __device__ __forceinline__ bool vertex_pairs_now(const u64* __restrict__ cur, co
     const u64 k = ekey[(u32)mx];
     const int a = (int)(k >> vbits), b = (int)(k & ((1ull << vbits) - 1ull));
     const int other = (a == x) ? b : a;
-    return cur[other] == mx;
+    return load_bid<COHERENT>(&cur[other]) == mx;
+}
+
+// One edge of one sub-round.  Returns true if the edge stays live.
+template <bool COHERENT>
+__device__ __forceinline__ bool subround_edge(const SelArgs& A, const u64* __restrict__ cur, int k, int e, int& u,
+                                              int& v, int& m, u64& p, bool& sel) {
+    const u64 key = A.ekey[e];
+    u = (int)(key >> A.vbits);
+    v = (int)(key & ((1ull << A.vbits) - 1ull));
+    p = ((u64)A.ecost[e] << 32) | (u32)e;
+    m = mesh_of(A.mt.voff, A.mt.B, u);
+    sel = false;
+    if (k == 0 && !A.mt.active[m]) return false;
+    const u64 mu = load_bid<COHERENT>(&cur[u]), mv = load_bid<COHERENT>(&cur[v]);
+    if (mu == p && mv == p) {
+        sel = true;
+        A.mate[u] = v;
+        A.mate[v] = u;
+        return false;
+    }
+    return !(vertex_pairs_now<COHERENT>(cur, A.ekey, A.vbits, u, mu) ||
+             vertex_pairs_now<COHERENT>(cur, A.ekey, A.vbits, v, mv));
+}
+
+// pairs formed, counted per mesh: one atomic per wave and mesh
+__device__ __forceinline__ void count_pairs(const SelArgs& A, bool sel, int m) {
+    const int lane = prim::lane_id();
+    u64 sb = __ballot(sel);
+    while (sb) {
+        const int leader = __ffsll((long long)sb) - 1;
+        const int m0 = __shfl(m, leader, 64);
+        const u64 same = __ballot(sel && m == m0);
+        if (lane == leader)
+            atomicAdd(&A.mt.mslots[((size_t)m0 * MATCH_SLOTS + (blockIdx.x & (MATCH_SLOTS - 1))) * MATCH_PAD],
+                      (int)__popcll(same));
+        sb &= ~same;
+    }
 }
 
 __global__ __launch_bounds__(BLOCK) void select_subround_kernel(SelArgs A, int k) {
@@ -339,10 +396,12 @@ __global__ __launch_bounds__(BLOCK) void select_subround_kernel(SelArgs A, int k
     int* __restrict__ lout = A.list[(k + 1) & 1];
     const int n = (k == 0) ? A.st->ne : A.st->live[k % 3];
     int* n_out = &A.st->live[(k + 1) % 3];
-    if (blockIdx.x == 0 && threadIdx.x == 0) A.st->live[(k + 2) % 3] = 0;  // next sub-round's output counter
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        A.st->live[(k + 2) % 3] = 0;  // next sub-round's output counter
+        A.st->sel_k = k + 1;
+    }
     const int lane = prim::lane_id();
     const u64 lt = prim::lanemask_lt();
-    const u64 vmask = (1ull << A.vbits) - 1ull;
 
     for (long long base = (long long)blockIdx.x * SEL_TILE; base < n; base += (long long)gridDim.x * SEL_TILE) {
         if (threadIdx.x == 0) s_count = 0;
@@ -355,32 +414,9 @@ __global__ __launch_bounds__(BLOCK) void select_subround_kernel(SelArgs A, int k
             u64 p = 0;
             if (i < n) {
                 e = lin ? lin[i] : (int)i;
-                const u64 key = A.ekey[e];
-                u = (int)(key >> A.vbits);
-                v = (int)(key & vmask);
-                p = ((u64)A.ecost[e] << 32) | (u32)e;
-                m = mesh_of(A.mt.voff, A.mt.B, u);
-                if (k > 0 || A.mt.active[m]) {
-                    const u64 mu = cur[u], mv = cur[v];
-                    if (mu == p && mv == p) {
-                        sel = true;
-                        A.mate[u] = v;
-                        A.mate[v] = u;
-                    } else {
-                        alive = !(vertex_pairs_now(cur, A.ekey, A.vbits, u, mu) ||
-                                  vertex_pairs_now(cur, A.ekey, A.vbits, v, mv));
-                    }
-                }
+                alive = subround_edge<false>(A, cur, k, e, u, v, m, p, sel);
             }
-            // pairs formed, counted per mesh (one atomic per wave and mesh)
-            u64 sb = __ballot(sel);
-            while (sb) {
-                const int leader = __ffsll((long long)sb) - 1;
-                const int m0 = __shfl(m, leader, 64);
-                const u64 same = __ballot(sel && m == m0);
-                if (lane == leader) atomicAdd(&A.mt.matched[m0], (int)__popcll(same));
-                sb &= ~same;
-            }
+            count_pairs(A, sel, m);
             // survivors: bid for the next sub-round, stage into the LDS tile
             const u64 ab = __ballot(alive);
             if (ab) {
@@ -405,6 +441,80 @@ __global__ __launch_bounds__(BLOCK) void select_subround_kernel(SelArgs A, int k
             for (int j = threadIdx.x; j < cnt; j += BLOCK) lout[gb + j] = stage[j];
         }
         __syncthreads();
+    }
+}
+
+// Tail: once few edges are live, one workgroup runs the remaining sub-rounds
+// back to back with the worklist in LDS, so that they cost a barrier each
+// instead of a kernel launch.  The live count falls in every sub-round (the
+// globally best live edge is always accepted), so the loop ends.
+__global__ __launch_bounds__(TAIL_THREADS) void select_tail_kernel(SelArgs A) {
+    __shared__ int lst[2][TAIL_MAX];
+    __shared__ int s_cnt[2];
+    int k = A.st->sel_k;
+    int n = (k == 0) ? A.st->ne : A.st->live[k % 3];
+    if (n > TAIL_MAX) return;  // too many: the host runs more grid-wide sub-rounds
+    const int tid = threadIdx.x, lane = prim::lane_id();
+    const u64 lt = prim::lanemask_lt();
+    if (k == 0) {
+        for (int i = tid; i < n; i += TAIL_THREADS) lst[0][i] = i;
+    } else {
+        const int* lin = A.list[k & 1];
+        for (int i = tid; i < n; i += TAIL_THREADS) lst[0][i] = lin[i];
+    }
+    int side = 0;
+    __syncthreads();
+    while (n > 0) {
+        const u64* cur = A.vmin[k % 3];
+        u64* nxt = A.vmin[(k + 1) % 3];
+        u64* rst = A.vmin[(k + 2) % 3];
+        if (tid == 0) s_cnt[side ^ 1] = 0;
+        __syncthreads();
+        const int padded = (n + 63) & ~63;  // whole waves run each step so that the ballots are uniform
+        for (int i = tid; i < padded; i += TAIL_THREADS) {
+            bool alive = false, sel = false;
+            int e = 0, u = 0, v = 0, m = 0;
+            u64 p = 0;
+            if (i < n) {
+                e = lst[side][i];
+                alive = subround_edge<true>(A, cur, k, e, u, v, m, p, sel);
+            }
+            count_pairs(A, sel, m);
+            const u64 ab = __ballot(alive);
+            if (ab) {
+                int wbase = 0;
+                if (lane == 0) wbase = atomicAdd(&s_cnt[side ^ 1], (int)__popcll(ab));
+                wbase = __shfl(wbase, 0, 64);
+                if (alive) {
+                    lst[side ^ 1][wbase + (int)__popcll(ab & lt)] = e;
+                    atomicMin(&nxt[u], p);
+                    atomicMin(&nxt[v], p);
+                    __hip_atomic_store(&rst[u], VMIN_NONE, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(&rst[v], VMIN_NONE, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+        }
+        __threadfence();  // this sub-round's bids and clears are at the L2 before anyone reads them
+        __syncthreads();
+        side ^= 1;
+        n = s_cnt[side];
+        ++k;
+        __syncthreads();
+    }
+    __threadfence();
+    __syncthreads();
+    for (int b = tid; b < A.mt.B; b += TAIL_THREADS) {
+        int sum = 0;
+        for (int j = 0; j < MATCH_SLOTS; ++j)
+            sum += __hip_atomic_load(&A.mt.mslots[((size_t)b * MATCH_SLOTS + j) * MATCH_PAD], __ATOMIC_RELAXED,
+                                     __HIP_MEMORY_SCOPE_AGENT);
+        A.mt.matched[b] = sum;
+    }
+    if (tid == 0) {
+        A.st->live[0] = 0;
+        A.st->live[1] = 0;
+        A.st->live[2] = 0;
+        A.st->sel_k = k;
     }
 }
 
@@ -722,11 +832,13 @@ struct picasso_ctx {
     int32_t max_meshes = 0;
     int64_t opt_max_rounds = -1;
     int64_t opt_stage_timing = 0;
-    int64_t opt_subround_batch = 12;
+    int64_t opt_subround_batch = 16;
     char hip_err[256] = {0};
 
     char* ws = nullptr;  // one device allocation, carved below
     size_t ws_bytes = 0;
+    int* hdr = nullptr;  // State followed by the per-mesh tables (see carve)
+    int cap_b = 1;       // per-mesh capacity the header was laid out for
     State* st = nullptr;
     VRec* vrec[2] = {nullptr, nullptr};
     int* fbuf[2] = {nullptr, nullptr};  // facet lists, ping-pong
@@ -757,18 +869,27 @@ struct picasso_ctx {
     int* nrem = nullptr;
     int* matched = nullptr;
     int* segstart = nullptr;
+    int* mslots = nullptr;
     // pinned host staging
-    // pinned host staging: [0,16) State read-back | [32,48) State upload |
-    // [64, 64+4(B+2)) per-mesh upload | h_back: per-mesh read-back (B+2)
+    // pinned host staging: read-back image of the header's front, then the upload image of the whole header
     int* h_pin = nullptr;
-    int* h_back = nullptr;
+    size_t h_up_off = 0;
     size_t h_pin_ints = 0;
     hipEvent_t ev[2 * PICASSO_STATS_ROUNDS * PICASSO_ST_COUNT + 4];
     int n_ev = 0;
     hipEvent_t ev_total[2];
+    // hipEvent brackets around the edge-key sort's downsweep launches (benchmark roofline)
+    int64_t opt_kernel_timing = 0;
+    hipEvent_t kt_pool[512];
+    prim::LaunchTimer::Rec kt_recs[256];
+    prim::LaunchTimer kt;
+    int64_t kt_launches = 0;
+    double kt_ms = 0.0, kt_bytes = 0.0;
 };
 
 namespace {
+
+constexpr int HDR_STATE_INTS = (int)(sizeof(State) / sizeof(int));
 
 struct Carver {
     size_t off = 0;
@@ -795,7 +916,22 @@ size_t carve(picasso_ctx* c, char* base, int64_t N, int64_t F, int32_t B) {
     const size_t b = (size_t)std::max<int32_t>(B, 1);
     picasso_ctx dummy;
     picasso_ctx* x = c ? c : &dummy;
-    x->st = cv.take<State>(1);
+    // header: everything the host uploads or reads back, contiguous so that one copy moves it.
+    //   [State][matched B][foff_out B+1] | [voff0 B+1][foff B+1][target B][stuck B][active B]
+    //   <-------- read back ----------->
+    int* hdr = cv.take<int>(HDR_STATE_INTS + 8 * b + 3);
+    x->hdr = hdr;
+    x->st = reinterpret_cast<State*>(hdr);
+    if (hdr) {
+        int* q = hdr + HDR_STATE_INTS;
+        x->matched = q; q += b;
+        x->foff_out = q; q += b + 1;
+        x->voff[0] = q; q += b + 1;
+        x->foff = q; q += b + 1;
+        x->target = q; q += b;
+        x->stuck = q; q += b;
+        x->active = q; q += b;
+    }
     x->vrec[0] = cv.take<VRec>(n);
     x->vrec[1] = cv.take<VRec>(n);
     x->fbuf[0] = cv.take<int>(3 * f);
@@ -818,21 +954,14 @@ size_t carve(picasso_ctx* c, char* base, int64_t N, int64_t F, int32_t B) {
     x->hcap = next_pow2(2 * f);
     x->htab = cv.take<int>(x->hcap);
     x->keep = cv.take<unsigned char>(f);
-    const size_t ctiles = (size_t)prim::compact_tiles((long long)std::max(h, n)) + 1;
-    x->tilesum = cv.take<int>(ctiles);
-    x->sort_sc.T = prim::sort_tiles((long long)h);
+    x->tilesum = cv.take<int>((size_t)prim::compact_tilesum_capacity((long long)std::max(h, n)));
+    x->sort_sc.T = prim::sort_table_stride((long long)h);
     x->sort_sc.table = cv.take<u32>((size_t)256 * x->sort_sc.T);
     x->sort_sc.totals = cv.take<u32>(256);
-    x->voff[0] = cv.take<int>(b + 1);
     x->voff[1] = cv.take<int>(b + 1);
-    x->foff = cv.take<int>(b + 1);
-    x->foff_out = cv.take<int>(b + 1);
-    x->target = cv.take<int>(b);
-    x->active = cv.take<int>(b);
-    x->stuck = cv.take<int>(b);
     x->nrem = cv.take<int>(b);
-    x->matched = cv.take<int>(b);
     x->segstart = cv.take<int>(b);
+    x->mslots = cv.take<int>(b * MATCH_SLOTS * MATCH_PAD);
     return cv.off;
 }
 
@@ -894,44 +1023,42 @@ int run_vertex_quadrics(picasso_ctx* c, hipStream_t s, int N, int F) {
     return PICASSO_OK;
 }
 
-int upload_mesh_tables(picasso_ctx* c, hipStream_t s, int B, const int32_t* nv_in, const int32_t* nf_in,
-                       const int32_t* target, int64_t* N_out, int64_t* F_out) {
-    // pinned staging: [voff B+1][foff B+1][target B][zeros B]
-    int* p = c->h_pin + 64;
-    int* hv = p;
-    int* hf = hv + (B + 1);
-    int* ht = hf + (B + 1);
-    int* hz = ht + B;
+// Fills the pinned image of the header (State + per-mesh tables) and sends it with one copy.
+int upload_header(picasso_ctx* c, hipStream_t s, int B, const int32_t* nv_in, const int32_t* nf_in,
+                  const int32_t* target, int64_t* N_out, int64_t* F_out) {
+    const int cb = c->cap_b;
+    int* img = c->h_pin + c->h_up_off;
+    const int total = HDR_STATE_INTS + 8 * cb + 3;
+    memset(img, 0, sizeof(int) * total);
+    int* hv = img + (c->voff[0] - c->hdr);
+    int* hf = img + (c->foff - c->hdr);
+    int* ht = img + (c->target - c->hdr);
     int64_t nacc = 0, facc = 0;
     for (int b = 0; b < B; ++b) {
         if (nv_in[b] < 1 || nf_in[b] < 0 || target[b] < 1) return PICASSO_ERR_INVALID_ARG;
         hv[b] = (int)nacc;
         hf[b] = (int)facc;
         ht[b] = target[b];
-        hz[b] = 0;
         nacc += nv_in[b];
         facc += nf_in[b];
         if (nacc > c->max_verts || facc > c->max_facets) return PICASSO_ERR_WORKSPACE;
     }
     hv[B] = (int)nacc;
     hf[B] = (int)facc;
+    State* h = reinterpret_cast<State*>(img);
+    h->nv[0] = (int)nacc;
+    h->nf[0] = (int)facc;
     *N_out = nacc;
     *F_out = facc;
-    HIP_TRY(c, hipMemcpyAsync(c->voff[0], hv, sizeof(int) * (B + 1), hipMemcpyHostToDevice, s));
-    HIP_TRY(c, hipMemcpyAsync(c->foff, hf, sizeof(int) * (B + 1), hipMemcpyHostToDevice, s));
-    HIP_TRY(c, hipMemcpyAsync(c->target, ht, sizeof(int) * B, hipMemcpyHostToDevice, s));
-    HIP_TRY(c, hipMemcpyAsync(c->stuck, hz, sizeof(int) * B, hipMemcpyHostToDevice, s));
-    HIP_TRY(c, hipMemcpyAsync(c->active, hz, sizeof(int) * B, hipMemcpyHostToDevice, s));
-    HIP_TRY(c, hipMemcpyAsync(c->matched, hz, sizeof(int) * B, hipMemcpyHostToDevice, s));
+    HIP_TRY(c, hipMemcpyAsync(c->hdr, img, sizeof(int) * total, hipMemcpyHostToDevice, s));
     return PICASSO_OK;
 }
 
-int upload_state(picasso_ctx* c, hipStream_t s, int N, int F) {
-    State* h = reinterpret_cast<State*>(c->h_pin + 32);
-    memset(h, 0, sizeof(State));
-    h->nv[0] = N;
-    h->nf[0] = F;
-    HIP_TRY(c, hipMemcpyAsync(c->st, h, sizeof(State), hipMemcpyHostToDevice, s));
+// One copy of [State][matched][foff_out] to the pinned read-back area, then waits for the stream.
+int read_header(picasso_ctx* c, hipStream_t s) {
+    const int n = HDR_STATE_INTS + 2 * c->cap_b + 1;
+    HIP_TRY(c, hipMemcpyAsync(c->h_pin, c->hdr, sizeof(int) * n, hipMemcpyDeviceToHost, s));
+    HIP_TRY(c, hipStreamSynchronize(s));
     return PICASSO_OK;
 }
 
@@ -953,14 +1080,18 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
     if (stats) memset(stats, 0, sizeof(*stats));
 
     int64_t N64 = 0, F64 = 0;
-    int rc = upload_mesh_tables(c, s, B, nv_in, nf_in, target_nv, &N64, &F64);
+    int rc = upload_header(c, s, B, nv_in, nf_in, target_nv, &N64, &F64);
     if (rc != PICASSO_OK) return rc;
     if (F64 > 0 && !d_facets) return PICASSO_ERR_INVALID_ARG;
     const int N = (int)N64, F = (int)F64;
-    rc = upload_state(c, s, N, F);
-    if (rc != PICASSO_OK) return rc;
 
     c->n_ev = 0;
+    c->kt.pool = c->kt_pool;
+    c->kt.cap = (int)(sizeof(c->kt_pool) / sizeof(c->kt_pool[0]));
+    c->kt.recs = c->kt_recs;
+    c->kt.used = 0;
+    c->kt.nrec = 0;
+    std::vector<int> nf_round;
     StageTimer tm{c, s, c->opt_stage_timing != 0 && stats != nullptr, {}, -1};
     HIP_TRY(c, hipEventRecord(c->ev_total[0], s));
 
@@ -999,18 +1130,19 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
     while (work && (c->opt_max_rounds < 0 || round < c->opt_max_rounds)) {
         const int vbits = ceil_log2(nv_total);
         const int H = 3 * nf_bound;
-        MeshTab mt{B, c->voff[cur], c->target, c->active, c->nrem, c->matched};
+        MeshTab mt{B, c->voff[cur], c->target, c->active, c->nrem, c->matched, c->mslots};
 
         // ---- S1 (+S2): edges and costs
         tm.begin(round, PICASSO_ST_EDGES);
         round_begin_kernel<<<1, BLOCK, 0, s>>>(B, c->voff[cur], c->target, c->active, c->stuck, c->nrem, c->matched,
-                                               round == 0, cur, c->st);
+                                               c->mslots, round == 0, cur, c->st);
         emit_edge_keys_kernel<<<grid_for(std::max(nf_bound, nv_total), 8192), BLOCK, 0, s>>>(
             c->fbuf[cur], c->st, cur, vbits, c->key64[0], c->vmin[0], c->vmin[1], c->mate);
         const u64* skeys = c->key64[0];
         if (H > 0) {
             int where = prim::radix_sort<u64, false>(s, c->key64[0], c->key64[1], nullptr, nullptr, &c->st->nh, H,
-                                                     2 * vbits, c->sort_sc);
+                                                     2 * vbits, c->sort_sc, c->opt_kernel_timing ? &c->kt : nullptr,
+                                                     round);
             if (where < 0) return PICASSO_ERR_HIP;
             skeys = where ? c->key64[1] : c->key64[0];
         }
@@ -1032,33 +1164,42 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         sa.st = c->st;
         sa.mt = mt;
         sa.vbits = vbits;
-        int k = 0;
-        int live_bound = H;  // edges <= half-edges
+        // Grid-wide sub-rounds while many edges are live (the live count falls about 3x per
+        // sub-round), then the single-workgroup tail; the host looks once per batch.
+        int k = 0, launched = 0;
+        long long live_est = std::max(H / 2, 1);
         for (;;) {
-            const int batch = (int)std::max<int64_t>(1, c->opt_subround_batch);
-            for (int j = 0; j < batch; ++j, ++k) {
-                const int g = (int)std::min<long long>(((long long)live_bound + SEL_TILE - 1) / SEL_TILE + 1, 4096);
+            int wide = 0;
+            for (long long l = live_est; l > TAIL_MAX * 3 / 4; l = l * 10 / 29) ++wide;
+            wide = std::min<int>(wide, (int)std::max<int64_t>(1, c->opt_subround_batch));
+            for (int j = 0; j < wide; ++j, ++k) {
+                const long long lb = std::max<long long>(live_est, 1);
+                const int g = (int)std::min<long long>((lb + SEL_TILE - 1) / SEL_TILE, 16384);
                 select_subround_kernel<<<g, BLOCK, 0, s>>>(sa, k);
+                live_est = std::max<long long>(live_est * 10 / 29, TAIL_MAX / 8);
             }
-            HIP_TRY(c, hipMemcpyAsync(hst, c->st, sizeof(State), hipMemcpyDeviceToHost, s));
-            HIP_TRY(c, hipMemcpyAsync(c->h_back, c->matched, sizeof(int) * B, hipMemcpyDeviceToHost, s));
-            HIP_TRY(c, hipStreamSynchronize(s));
+            select_tail_kernel<<<1, TAIL_THREADS, 0, s>>>(sa);
+            launched += wide + 1;
+            rc = read_header(c, s);
+            if (rc != PICASSO_OK) return rc;
             if (!validated) {
                 const int st_err = status_from_err_bits(hst->err);
                 if (st_err != PICASSO_OK) return st_err;
                 validated = true;
             }
-            const int live = hst->live[k % 3];
+            k = hst->sel_k;
+            const int live = (k == 0) ? hst->ne : hst->live[k % 3];
             if (live == 0) break;
-            live_bound = live;
+            live_est = live;
         }
-        for (int b = 0; b < B; ++b) h_matched[b] = c->h_back[b];
+        for (int b = 0; b < B; ++b) h_matched[b] = c->h_pin[HDR_STATE_INTS + b];
         nf_bound = std::min(nf_bound, hst->nf[cur]);
+        nf_round.push_back(hst->nf[cur]);
         if (stats && round < PICASSO_STATS_ROUNDS) {
             stats->nv[round] = nv_total;
             stats->nf[round] = hst->nf[cur];
             stats->ne[round] = hst->ne;
-            stats->subrounds[round] = k;
+            stats->subrounds[round] = launched;
         }
 
         // ---- budget truncation (only where a mesh formed more pairs than it may remove)
@@ -1130,8 +1271,8 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
     }
 
     if (!validated) {
-        HIP_TRY(c, hipMemcpyAsync(hst, c->st, sizeof(State), hipMemcpyDeviceToHost, s));
-        HIP_TRY(c, hipStreamSynchronize(s));
+        rc = read_header(c, s);
+        if (rc != PICASSO_OK) return rc;
         const int st_err = status_from_err_bits(hst->err);
         if (st_err != PICASSO_OK) return st_err;
     }
@@ -1140,15 +1281,26 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         c->vrec[cur], c->fbuf[cur], c->cid, c->st, cur, N, d_verts_out, d_facets_out, d_cluster_id, B, c->voff[cur],
         c->foff_out);
     HIP_TRY(c, hipEventRecord(c->ev_total[1], s));
-    HIP_TRY(c, hipMemcpyAsync(hst, c->st, sizeof(State), hipMemcpyDeviceToHost, s));
-    HIP_TRY(c, hipMemcpyAsync(c->h_back, c->foff_out, sizeof(int) * (B + 1), hipMemcpyDeviceToHost, s));
-    HIP_TRY(c, hipStreamSynchronize(s));
+    rc = read_header(c, s);
+    if (rc != PICASSO_OK) return rc;
     HIP_TRY(c, hipGetLastError());
+    const int* h_foff = c->h_pin + HDR_STATE_INTS + c->cap_b;
+
+    // edge-key sort downsweep: one read and one write of every 8-byte key per launch
+    for (int i = 0; i < c->kt.nrec; ++i) {
+        const prim::LaunchTimer::Rec& r = c->kt.recs[i];
+        float ms = 0.f;
+        if (r.tag < (int)nf_round.size() && hipEventElapsedTime(&ms, c->kt_pool[r.e0], c->kt_pool[r.e1]) == hipSuccess) {
+            c->kt_launches += 1;
+            c->kt_ms += ms;
+            c->kt_bytes += 16.0 * 3.0 * (double)nf_round[r.tag];
+        }
+    }
 
     int warn = PICASSO_OK;
     for (int b = 0; b < B; ++b) {
         h_nv_out[b] = nvb[b];
-        h_nf_out[b] = c->h_back[b + 1] - c->h_back[b];
+        h_nf_out[b] = h_foff[b + 1] - h_foff[b];
         if (nvb[b] > target_nv[b] && (c->opt_max_rounds < 0 || stuck[b])) warn = PICASSO_WARN_BUDGET_UNMET;
     }
     if (stats) {
@@ -1186,18 +1338,20 @@ int picasso_create(picasso_ctx** out, int device, int64_t max_verts, int64_t max
     c->ws_bytes = carve(nullptr, nullptr, max_verts, max_facets, max_meshes);
     if (hipMalloc((void**)&c->ws, c->ws_bytes) != hipSuccess) { delete c; return PICASSO_ERR_HIP; }
     carve(c, c->ws, max_verts, max_facets, max_meshes);
-    c->h_pin_ints = 64 + 5 * ((size_t)max_meshes + 2) + 16;
+    c->cap_b = max_meshes;
+    c->h_up_off = (size_t)HDR_STATE_INTS + 2 * (size_t)max_meshes + 16;
+    c->h_pin_ints = c->h_up_off + HDR_STATE_INTS + 8 * (size_t)max_meshes + 16;
     if (hipHostMalloc((void**)&c->h_pin, c->h_pin_ints * sizeof(int), hipHostMallocDefault) != hipSuccess) {
         (void)hipFree(c->ws);
         delete c;
         return PICASSO_ERR_HIP;
     }
     memset(c->h_pin, 0, c->h_pin_ints * sizeof(int));
-    c->h_back = c->h_pin + 64 + 4 * ((size_t)max_meshes + 2);
     const int nev = (int)(sizeof(c->ev) / sizeof(c->ev[0]));
     for (int i = 0; i < nev; ++i) (void)hipEventCreate(&c->ev[i]);
     (void)hipEventCreate(&c->ev_total[0]);
     (void)hipEventCreate(&c->ev_total[1]);
+    for (hipEvent_t& e : c->kt_pool) (void)hipEventCreate(&e);
     *out = c;
     return PICASSO_OK;
 }
@@ -1210,6 +1364,7 @@ void picasso_destroy(picasso_ctx* c) {
     for (int i = 0; i < nev; ++i) (void)hipEventDestroy(c->ev[i]);
     (void)hipEventDestroy(c->ev_total[0]);
     (void)hipEventDestroy(c->ev_total[1]);
+    for (hipEvent_t& e : c->kt_pool) (void)hipEventDestroy(e);
     if (c->h_pin) (void)hipHostFree(c->h_pin);
     if (c->ws) (void)hipFree(c->ws);
     delete c;
@@ -1220,6 +1375,7 @@ int picasso_set_option(picasso_ctx* c, int option, int64_t value) {
     switch (option) {
         case PICASSO_OPT_MAX_ROUNDS: c->opt_max_rounds = value; return PICASSO_OK;
         case PICASSO_OPT_STAGE_TIMING: c->opt_stage_timing = value; return PICASSO_OK;
+        case PICASSO_OPT_KERNEL_TIMING: c->opt_kernel_timing = value; return PICASSO_OK;
         case PICASSO_OPT_SUBROUND_BATCH:
             if (value < 1 || value > 1024) return PICASSO_ERR_INVALID_ARG;
             c->opt_subround_batch = value;
@@ -1242,6 +1398,19 @@ const char* picasso_strerror(int status) {
 }
 
 const char* picasso_last_hip_error(picasso_ctx* c) { return c ? c->hip_err : ""; }
+
+int picasso_kernel_timing(picasso_ctx* c, int reset, int64_t* launches, double* ms_total, double* bytes_total) {
+    if (!c) return PICASSO_ERR_INVALID_ARG;
+    if (launches) *launches = c->kt_launches;
+    if (ms_total) *ms_total = c->kt_ms;
+    if (bytes_total) *bytes_total = c->kt_bytes;
+    if (reset) {
+        c->kt_launches = 0;
+        c->kt_ms = 0.0;
+        c->kt_bytes = 0.0;
+    }
+    return PICASSO_OK;
+}
 
 int picasso_decimate_batch(picasso_ctx* c, void* stream, int32_t B, const float* d_verts, const int32_t* d_facets,
                            const int32_t* h_nv_in, const int32_t* h_nf_in, const int32_t* h_target_nv,
@@ -1267,17 +1436,15 @@ int picasso_vertex_quadrics(picasso_ctx* c, void* stream, const float* d_verts, 
     HIP_TRY(c, hipSetDevice(c->device));
     int32_t big = 0x7FFFFFFF;
     int64_t n64, f64;
-    int rc = upload_mesh_tables(c, s, 1, &N, &F, &big, &n64, &f64);
-    if (rc != PICASSO_OK) return rc;
-    rc = upload_state(c, s, N, F);
+    int rc = upload_header(c, s, 1, &N, &F, &big, &n64, &f64);
     if (rc != PICASSO_OK) return rc;
     init_kernel<<<grid_for(std::max(N, F), 4096), BLOCK, 0, s>>>(d_verts, N, d_facets, F, 1, c->voff[0], c->foff,
                                                                  c->vrec[0], c->cid, c->fbuf[0],
                                                                  reinterpret_cast<u32*>(c->key64[0]), c->val32[0],
                                                                  c->st);
     State* hst = reinterpret_cast<State*>(c->h_pin);
-    HIP_TRY(c, hipMemcpyAsync(hst, c->st, sizeof(State), hipMemcpyDeviceToHost, s));
-    HIP_TRY(c, hipStreamSynchronize(s));
+    rc = read_header(c, s);
+    if (rc != PICASSO_OK) return rc;
     rc = status_from_err_bits(hst->err);
     if (rc != PICASSO_OK) return rc;
     rc = run_vertex_quadrics(c, s, N, F);
@@ -1297,25 +1464,23 @@ int picasso_edge_costs(picasso_ctx* c, void* stream, const float* d_verts, int32
     HIP_TRY(c, hipSetDevice(c->device));
     int32_t one = 1;
     int64_t n64, f64;
-    int rc = upload_mesh_tables(c, s, 1, &N, &F, &one, &n64, &f64);
-    if (rc != PICASSO_OK) return rc;
-    rc = upload_state(c, s, N, F);
+    int rc = upload_header(c, s, 1, &N, &F, &one, &n64, &f64);
     if (rc != PICASSO_OK) return rc;
     init_kernel<<<grid_for(std::max(N, F), 4096), BLOCK, 0, s>>>(d_verts, N, d_facets, F, 1, c->voff[0], c->foff,
                                                                  c->vrec[0], c->cid, c->fbuf[0],
                                                                  reinterpret_cast<u32*>(c->key64[0]), c->val32[0],
                                                                  c->st);
     State* hst = reinterpret_cast<State*>(c->h_pin);
-    HIP_TRY(c, hipMemcpyAsync(hst, c->st, sizeof(State), hipMemcpyDeviceToHost, s));
-    HIP_TRY(c, hipStreamSynchronize(s));
+    rc = read_header(c, s);
+    if (rc != PICASSO_OK) return rc;
     rc = status_from_err_bits(hst->err);
     if (rc != PICASSO_OK) return rc;
     rc = run_vertex_quadrics(c, s, N, F);
     if (rc != PICASSO_OK) return rc;
     const int vbits = ceil_log2(N), H = 3 * F;
-    MeshTab mt{1, c->voff[0], c->target, c->active, c->nrem, c->matched};
-    round_begin_kernel<<<1, BLOCK, 0, s>>>(1, c->voff[0], c->target, c->active, c->stuck, c->nrem, c->matched, 1, 0,
-                                           c->st);
+    MeshTab mt{1, c->voff[0], c->target, c->active, c->nrem, c->matched, c->mslots};
+    round_begin_kernel<<<1, BLOCK, 0, s>>>(1, c->voff[0], c->target, c->active, c->stuck, c->nrem, c->matched, c->mslots,
+                                           1, 0, c->st);
     emit_edge_keys_kernel<<<grid_for(std::max(F, N), 8192), BLOCK, 0, s>>>(c->fbuf[0], c->st, 0, vbits, c->key64[0],
                                                                           c->vmin[0], c->vmin[1], c->mate);
     const u64* skeys = c->key64[0];
@@ -1331,8 +1496,8 @@ int picasso_edge_costs(picasso_ctx* c, void* stream, const float* d_verts, int32
     prim::compact(s, up, up, uo, &c->st->nh, H, c->tilesum, &c->st->ne);
     export_edges_kernel<<<grid_for(std::max(H, 1)), BLOCK, 0, s>>>(c->ekey, c->ecost, c->st, vbits, d_edges_out,
                                                                    d_cost_out);
-    HIP_TRY(c, hipMemcpyAsync(hst, c->st, sizeof(State), hipMemcpyDeviceToHost, s));
-    HIP_TRY(c, hipStreamSynchronize(s));
+    rc = read_header(c, s);
+    if (rc != PICASSO_OK) return rc;
     HIP_TRY(c, hipGetLastError());
     *h_ne_out = hst->ne;
     return PICASSO_OK;

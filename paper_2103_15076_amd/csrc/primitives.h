@@ -63,8 +63,11 @@ __device__ __forceinline__ u32 block_sum(u32 v, u32* smem) {
 // keys is (wave, item, lane), which equals their index order, so ranking by
 // (digit, that order) keeps the sort stable.
 // ---------------------------------------------------------------------------
-constexpr int SORT_ITEMS = 16;
-constexpr int SORT_TILE = BLOCK * SORT_ITEMS;
+// Keys per lane: 16 for large inputs, 4 when the input is small enough that
+// 4096-key tiles would leave most compute units without a workgroup.
+constexpr int SORT_ITEMS_BIG = 16;
+constexpr int SORT_ITEMS_SMALL = 4;
+constexpr int SORT_SMALL_MAX_TILES = 2048;
 
 template <typename K>
 __device__ __forceinline__ u32 digit_of(K k, int shift, u32 mask) {
@@ -72,9 +75,10 @@ __device__ __forceinline__ u32 digit_of(K k, int shift, u32 mask) {
 }
 
 // table[d * T + tile] = number of keys of this tile whose digit is d
-template <typename K>
+template <typename K, int SORT_ITEMS>
 __global__ __launch_bounds__(BLOCK) void radix_upsweep_kernel(const K* __restrict__ kin, const int* n_ptr, int n_host,
                                                               int T, u32* __restrict__ table, int shift, int bits) {
+    constexpr int SORT_TILE = BLOCK * SORT_ITEMS;
     __shared__ u32 hist[WAVES][256];
     const int n = load_count(n_ptr, n_host);
     const int tile = blockIdx.x;
@@ -96,10 +100,10 @@ __global__ __launch_bounds__(BLOCK) void radix_upsweep_kernel(const K* __restric
 // One workgroup per digit: exclusive scan of its table row over the tiles in
 // use; totals[d] = number of keys with digit d.
 __global__ __launch_bounds__(BLOCK) void radix_scan_kernel(u32* __restrict__ table, u32* __restrict__ totals,
-                                                           const int* n_ptr, int n_host, int T) {
+                                                           const int* n_ptr, int n_host, int T, int tile_keys) {
     __shared__ u32 smem[WAVES];
     const int n = load_count(n_ptr, n_host);
-    const int tiles = (int)(((long long)n + SORT_TILE - 1) / SORT_TILE);
+    const int tiles = (int)(((long long)n + tile_keys - 1) / tile_keys);
     u32* row = table + (size_t)blockIdx.x * T;
     const int t = threadIdx.x;
     u32 carry = 0;
@@ -114,12 +118,13 @@ __global__ __launch_bounds__(BLOCK) void radix_scan_kernel(u32* __restrict__ tab
     if (t == 0) totals[blockIdx.x] = carry;
 }
 
-template <typename K, bool HAS_VAL>
+template <typename K, bool HAS_VAL, int SORT_ITEMS>
 __global__ __launch_bounds__(BLOCK) void radix_downsweep_kernel(const K* __restrict__ kin, K* __restrict__ kout,
                                                                 const u32* __restrict__ vin, u32* __restrict__ vout,
                                                                 const int* n_ptr, int n_host, int T,
                                                                 const u32* __restrict__ table,
                                                                 const u32* __restrict__ totals, int shift, int bits) {
+    constexpr int SORT_TILE = BLOCK * SORT_ITEMS;
     __shared__ u32 wcnt[WAVES][256];
     __shared__ u32 tstart[256];
     __shared__ u32 gbase[256];
@@ -212,18 +217,44 @@ struct SortScratch {
     int T;        // row stride = tiles at capacity
 };
 
-inline int sort_tiles(long long n) { return (int)((n + SORT_TILE - 1) / SORT_TILE); }
+// Optional hipEvent bracket around every downsweep launch (for the roofline
+// measurement of the benchmark); `tag` travels to the record.
+struct LaunchTimer {
+    hipEvent_t* pool = nullptr;
+    int cap = 0, used = 0;
+    struct Rec { int e0, e1, tag; };
+    Rec* recs = nullptr;
+    int nrec = 0;
+    bool begin(hipStream_t s, int tag) {
+        if (!pool || used + 2 > cap) return false;
+        recs[nrec] = Rec{used, used + 1, tag};
+        (void)hipEventRecord(pool[used], s);
+        used += 2;
+        return true;
+    }
+    void end(hipStream_t s) {
+        (void)hipEventRecord(pool[recs[nrec].e1], s);
+        ++nrec;
+    }
+};
 
-// Sorts on key bits [0, key_bits).  Data ping-pongs between (k0,v0) and
-// (k1,v1); returns 0 if the result is in (k0,v0), 1 if in (k1,v1), <0 on a
-// launch error.  n_max bounds the device-side count for the grid size.
-template <typename K, bool HAS_VAL>
-inline int radix_sort(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_ptr, int n_max, int key_bits,
-                      const SortScratch& sc) {
-    if (n_max <= 0 || key_bits <= 0) return 0;
+inline int sort_items_for(long long n_max) {
+    return (n_max + BLOCK * SORT_ITEMS_SMALL - 1) / (BLOCK * SORT_ITEMS_SMALL) <= SORT_SMALL_MAX_TILES ? SORT_ITEMS_SMALL
+                                                                                                      : SORT_ITEMS_BIG;
+}
+inline int sort_tiles(long long n, int items) { return (int)((n + (long long)BLOCK * items - 1) / ((long long)BLOCK * items)); }
+// row stride of the tile table for inputs of up to n_cap keys
+inline int sort_table_stride(long long n_cap) {
+    const int big = sort_tiles(n_cap, SORT_ITEMS_BIG);
+    return big > SORT_SMALL_MAX_TILES ? big : SORT_SMALL_MAX_TILES;
+}
+
+template <typename K, bool HAS_VAL, int ITEMS>
+inline int radix_sort_impl(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_ptr, int n_max, int key_bits,
+                           const SortScratch& sc, LaunchTimer* lt, int tag) {
     const int passes = (key_bits + 7) / 8;
     const int per = (key_bits + passes - 1) / passes;
-    const int tiles = sort_tiles(n_max);
+    const int tiles = sort_tiles(n_max, ITEMS);
     int cur = 0, shift = 0;
     for (int p = 0; p < passes; ++p) {
         const int bits = (key_bits - shift) < per ? (key_bits - shift) : per;
@@ -231,15 +262,29 @@ inline int radix_sort(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* 
         K* kout = cur ? k0 : k1;
         u32* vin = cur ? v1 : v0;
         u32* vout = cur ? v0 : v1;
-        radix_upsweep_kernel<K><<<tiles, BLOCK, 0, s>>>(kin, n_ptr, n_max, sc.T, sc.table, shift, bits);
-        radix_scan_kernel<<<1 << bits, BLOCK, 0, s>>>(sc.table, sc.totals, n_ptr, n_max, sc.T);
-        radix_downsweep_kernel<K, HAS_VAL>
+        radix_upsweep_kernel<K, ITEMS><<<tiles, BLOCK, 0, s>>>(kin, n_ptr, n_max, sc.T, sc.table, shift, bits);
+        radix_scan_kernel<<<1 << bits, BLOCK, 0, s>>>(sc.table, sc.totals, n_ptr, n_max, sc.T, BLOCK * ITEMS);
+        const bool timed = lt && lt->begin(s, tag);
+        radix_downsweep_kernel<K, HAS_VAL, ITEMS>
             <<<tiles, BLOCK, 0, s>>>(kin, kout, vin, vout, n_ptr, n_max, sc.T, sc.table, sc.totals, shift, bits);
+        if (timed) lt->end(s);
         shift += bits;
         cur ^= 1;
     }
     if (hipGetLastError() != hipSuccess) return -1;
     return cur;
+}
+
+// Sorts on key bits [0, key_bits).  Data ping-pongs between (k0,v0) and
+// (k1,v1); returns 0 if the result is in (k0,v0), 1 if in (k1,v1), <0 on a
+// launch error.  n_max bounds the device-side count for the grid size.
+template <typename K, bool HAS_VAL>
+inline int radix_sort(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_ptr, int n_max, int key_bits,
+                      const SortScratch& sc, LaunchTimer* lt = nullptr, int tag = 0) {
+    if (n_max <= 0 || key_bits <= 0) return 0;
+    if (sort_items_for(n_max) == SORT_ITEMS_SMALL)
+        return radix_sort_impl<K, HAS_VAL, SORT_ITEMS_SMALL>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc, lt, tag);
+    return radix_sort_impl<K, HAS_VAL, SORT_ITEMS_BIG>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc, lt, tag);
 }
 
 // ---------------------------------------------------------------------------
@@ -248,14 +293,26 @@ inline int radix_sort(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* 
 // position among flagged items in index order; writes the grand total.
 // Tile = 4096 items; wave w of a workgroup owns items [w*1024, (w+1)*1024).
 // ---------------------------------------------------------------------------
-constexpr int CHUNKS = 16;
-constexpr int CTILE = BLOCK * CHUNKS;
+constexpr int COMPACT_MAX_SUMMED_TILES = 2048;  // beyond this the tile sums are scanned by a kernel of their own
 
-inline int compact_tiles(long long n) { return (int)((n + CTILE - 1) / CTILE); }
+inline int compact_chunks_for(long long n_max) {
+    if ((n_max + BLOCK - 1) / BLOCK <= COMPACT_MAX_SUMMED_TILES) return 1;
+    if ((n_max + 4 * BLOCK - 1) / (4 * BLOCK) <= COMPACT_MAX_SUMMED_TILES) return 4;
+    return 16;
+}
+inline int compact_tiles(long long n, int chunks) {
+    return (int)((n + (long long)BLOCK * chunks - 1) / ((long long)BLOCK * chunks));
+}
+// capacity of the tile-sum array for inputs of up to n_cap items
+inline int compact_tilesum_capacity(long long n_cap) {
+    const int big = compact_tiles(n_cap, 16);
+    return (big > COMPACT_MAX_SUMMED_TILES ? big : COMPACT_MAX_SUMMED_TILES) + 1;
+}
 
-template <class Pred>
+template <class Pred, int CHUNKS>
 __global__ __launch_bounds__(BLOCK) void tile_count_kernel(Pred pred, const int* n_ptr, int n_host,
                                                            int* __restrict__ tilesum) {
+    constexpr int CTILE = BLOCK * CHUNKS;
     __shared__ u32 smem[WAVES];
     const int n = load_count(n_ptr, n_host);
     const long long base = (long long)blockIdx.x * CTILE;
@@ -273,10 +330,11 @@ __global__ __launch_bounds__(BLOCK) void tile_count_kernel(Pred pred, const int*
 }
 
 // In-place exclusive scan of a[0..T) by one workgroup (used when there are many tiles).
-__global__ __launch_bounds__(BLOCK) void scan_tilesums_kernel(int* __restrict__ a, const int* n_ptr, int n_host) {
+__global__ __launch_bounds__(BLOCK) void scan_tilesums_kernel(int* __restrict__ a, const int* n_ptr, int n_host,
+                                                              int tile_items) {
     __shared__ u32 smem[WAVES];
     const int n = load_count(n_ptr, n_host);
-    const int T = (int)(((long long)n + CTILE - 1) / CTILE);
+    const int T = (int)(((long long)n + tile_items - 1) / tile_items);
     u32 carry = 0;
     for (int c = 0; c < T; c += BLOCK) {
         const int i = c + threadIdx.x;
@@ -287,10 +345,11 @@ __global__ __launch_bounds__(BLOCK) void scan_tilesums_kernel(int* __restrict__ 
     }
 }
 
-template <class Pred, class Out>
+template <class Pred, class Out, int CHUNKS>
 __global__ __launch_bounds__(BLOCK) void tile_scatter_kernel(Pred pred, Out out, const int* n_ptr, int n_host,
                                                              const int* __restrict__ tilesum, int prefixed,
                                                              int* __restrict__ total_out) {
+    constexpr int CTILE = BLOCK * CHUNKS;
     __shared__ u32 smem[WAVES];
     const int n = load_count(n_ptr, n_host);
     if (n <= 0) {
@@ -340,15 +399,26 @@ __global__ __launch_bounds__(BLOCK) void tile_scatter_kernel(Pred pred, Out out,
     if (base + CTILE >= n && t == 0 && total_out) *total_out = (int)(tileoff + tot);
 }
 
+template <class PredCount, class PredScatter, class Out, int CHUNKS>
+inline void compact_impl(hipStream_t s, PredCount pc, PredScatter ps, Out out, const int* n_ptr, int n_max,
+                         int* tilesum, int* total_out) {
+    const int tiles = compact_tiles(n_max > 0 ? n_max : 1, CHUNKS);
+    tile_count_kernel<PredCount, CHUNKS><<<tiles, BLOCK, 0, s>>>(pc, n_ptr, n_max, tilesum);
+    const int prefixed = tiles > COMPACT_MAX_SUMMED_TILES;
+    if (prefixed) scan_tilesums_kernel<<<1, BLOCK, 0, s>>>(tilesum, n_ptr, n_max, BLOCK * CHUNKS);
+    tile_scatter_kernel<PredScatter, Out, CHUNKS>
+        <<<tiles, BLOCK, 0, s>>>(ps, out, n_ptr, n_max, tilesum, prefixed, total_out);
+}
+
 // count pass may use a different functor (e.g. one that also stores the flag)
 template <class PredCount, class PredScatter, class Out>
 inline void compact(hipStream_t s, PredCount pc, PredScatter ps, Out out, const int* n_ptr, int n_max, int* tilesum,
                     int* total_out) {
-    const int tiles = compact_tiles(n_max > 0 ? n_max : 1);
-    tile_count_kernel<PredCount><<<tiles, BLOCK, 0, s>>>(pc, n_ptr, n_max, tilesum);
-    const int prefixed = tiles > 2048;
-    if (prefixed) scan_tilesums_kernel<<<1, BLOCK, 0, s>>>(tilesum, n_ptr, n_max);
-    tile_scatter_kernel<PredScatter, Out><<<tiles, BLOCK, 0, s>>>(ps, out, n_ptr, n_max, tilesum, prefixed, total_out);
+    switch (compact_chunks_for(n_max)) {
+        case 1: compact_impl<PredCount, PredScatter, Out, 1>(s, pc, ps, out, n_ptr, n_max, tilesum, total_out); break;
+        case 4: compact_impl<PredCount, PredScatter, Out, 4>(s, pc, ps, out, n_ptr, n_max, tilesum, total_out); break;
+        default: compact_impl<PredCount, PredScatter, Out, 16>(s, pc, ps, out, n_ptr, n_max, tilesum, total_out);
+    }
 }
 
 }  // namespace prim
