@@ -30,6 +30,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="leave out the per-launch hipEvents of the roofline measurement")
+    ap.add_argument("--copy-calib", action="store_true",
+                    help="only run the plain copy kernel on 1 GiB (HBM yardstick / counter calibration)")
     ap.add_argument("--stages", action="store_true", help="also print per-stage times to stderr")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -46,6 +48,27 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.copy_calib:
+        # plain copy of a known size: achievable HBM rate, and the reference for profiler byte counters
+        nbytes = 1 << 30
+        src = torch.empty(nbytes // 4, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        s = torch.cuda.current_stream()
+        for _ in range(3):
+            pk.picasso_device_copy(dst, src, s)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 10
+        e0.record(s)
+        for _ in range(reps):
+            pk.picasso_device_copy(dst, src, s)
+        e1.record(s)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        print(json.dumps({"copy_kernel": "copy_kernel", "bytes_read": nbytes, "bytes_written": nbytes,
+                          "ms": round(ms, 4), "GBps_read_plus_write": round(2 * nbytes / ms / 1e6, 1),
+                          "frac_of_8TBps": round(2 * nbytes / ms / 1e6 / HBM_PEAK_GBS, 4)}))
+        return
 
     cfg = meshgen.config(args.workload)
     V, F = cfg["verts"], cfg["facets"]

@@ -141,6 +141,11 @@ int picasso_vertex_quadrics(picasso_ctx* ctx, void* stream, const float* d_verts
 int picasso_edge_costs(picasso_ctx* ctx, void* stream, const float* d_verts, int32_t N, const int32_t* d_facets,
                        int32_t F, int32_t* d_edges_out, float* d_cost_out, int32_t* h_ne_out);
 
+/* Plain device-to-device streaming copy kernel (16-byte accesses; nbytes and
+ * both pointers multiples of 16).  Asynchronous on `stream`.  Used by the
+ * benchmark as the HBM yardstick and to calibrate profiler byte counters. */
+int picasso_device_copy(void* stream, void* d_dst, const void* d_src, size_t nbytes);
+
 /* Stable LSD radix sort of n keys on their low `key_bits` bits, in place.
  * key_bytes is 4 or 8; d_vals (uint32, may be NULL) is permuted alongside.
  * n must not exceed 3*max_facets of the context. */

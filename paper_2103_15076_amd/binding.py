@@ -33,6 +33,7 @@ EXPORTED_SYMBOLS = (
     "picasso_workspace_bytes", "picasso_create", "picasso_destroy", "picasso_set_option", "picasso_strerror",
     "picasso_last_hip_error", "picasso_decimate", "picasso_decimate_batch", "picasso_vertex_quadrics",
     "picasso_edge_costs", "picasso_radix_sort", "picasso_kernel_timing",
+    "picasso_device_copy",
 )
 
 
@@ -105,6 +106,8 @@ def load_library():
     lib.picasso_kernel_timing.restype = ctypes.c_int
     lib.picasso_kernel_timing.argtypes = [vp, ctypes.c_int, ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double),
                                           ctypes.POINTER(ctypes.c_double)]
+    lib.picasso_device_copy.restype = ctypes.c_int
+    lib.picasso_device_copy.argtypes = [vp, vp, vp, ctypes.c_size_t]
     lib.picasso_radix_sort.restype = ctypes.c_int
     lib.picasso_radix_sort.argtypes = [vp, vp, ctypes.c_int, vp, vp, i64, ctypes.c_int]
     _lib = lib
@@ -132,6 +135,16 @@ def _dev_ptr(t, dtype, what):
     if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
         raise TypeError(f"{what}: expected a contiguous CUDA tensor of dtype {dtype}")
     return ctypes.c_void_p(t.data_ptr())
+
+
+def picasso_device_copy(dst, src, stream=None):
+    """dst[:] = src with the library's plain copy kernel (both contiguous CUDA tensors of equal byte size)."""
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes and dst.is_cuda and src.is_cuda
+    st = load_library().picasso_device_copy(_stream_ptr(stream), ctypes.c_void_p(dst.data_ptr()),
+                                            ctypes.c_void_p(src.data_ptr()), nbytes)
+    if st != PICASSO_OK:
+        raise PicassoError(st, picasso_strerror(st))
 
 
 class Context:

@@ -285,6 +285,7 @@ struct UniqueOut {
     u32* ecost;
     const VRec* vrec;
     u64* vmin0;
+    unsigned char* estate;
     int vbits;
     MeshTab mt;
     __device__ void operator()(int i, int e) const {
@@ -293,7 +294,9 @@ struct UniqueOut {
         ekey[e] = k;
         const u32 ck = cost_key(pair_cost(vrec, u, v));
         ecost[e] = ck;
-        if (mt.active[mesh_of(mt.voff, mt.B, u)]) {
+        const bool act = mt.active[mesh_of(mt.voff, mt.B, u)] != 0;
+        estate[e] = act ? 0 : 1;
+        if (act) {
             const u64 p = ((u64)ck << 32) | (u32)e;
             atomicMin(&vmin0[u], p);
             atomicMin(&vmin0[v], p);
@@ -323,7 +326,8 @@ struct SelArgs {
     const u32* ecost;
     u64* vmin[3];
     int* mate;
-    int* list[2];
+    int* list;              // live edges gathered for the tail
+    unsigned char* estate;  // per edge: 0 = live, 1 = retired (paired, or an end was paired)
     State* st;
     MeshTab mt;
     int vbits;
@@ -385,64 +389,44 @@ __device__ __forceinline__ void count_pairs(const SelArgs& A, bool sel, int m) {
     }
 }
 
+// Grid-wide sub-round over ALL edges of the round; retired edges are skipped by
+// their state byte.  No worklist is kept here: appending survivors would need
+// one returning atomic per workgroup on a single counter, and thousands of
+// those queue up for longer than the sub-round itself takes.
 __global__ __launch_bounds__(BLOCK) void select_subround_kernel(SelArgs A, int k) {
-    __shared__ int stage[SEL_TILE];
-    __shared__ int s_count;
-    __shared__ int s_base;
     const u64* __restrict__ cur = A.vmin[k % 3];
     u64* __restrict__ nxt = A.vmin[(k + 1) % 3];
     u64* __restrict__ rst = A.vmin[(k + 2) % 3];
-    const int* __restrict__ lin = (k == 0) ? nullptr : A.list[k & 1];
-    int* __restrict__ lout = A.list[(k + 1) & 1];
-    const int n = (k == 0) ? A.st->ne : A.st->live[k % 3];
-    int* n_out = &A.st->live[(k + 1) % 3];
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        A.st->live[(k + 2) % 3] = 0;  // next sub-round's output counter
-        A.st->sel_k = k + 1;
-    }
-    const int lane = prim::lane_id();
-    const u64 lt = prim::lanemask_lt();
-
-    for (long long base = (long long)blockIdx.x * SEL_TILE; base < n; base += (long long)gridDim.x * SEL_TILE) {
-        if (threadIdx.x == 0) s_count = 0;
-        __syncthreads();
-#pragma unroll
-        for (int it = 0; it < SEL_ITEMS; ++it) {
-            const long long i = base + (long long)it * BLOCK + threadIdx.x;
-            bool alive = false, sel = false;
-            int e = 0, u = 0, v = 0, m = 0;
-            u64 p = 0;
-            if (i < n) {
-                e = lin ? lin[i] : (int)i;
-                alive = subround_edge<false>(A, cur, k, e, u, v, m, p, sel);
-            }
-            count_pairs(A, sel, m);
-            // survivors: bid for the next sub-round, stage into the LDS tile
-            const u64 ab = __ballot(alive);
-            if (ab) {
-                int wbase = 0;
-                if (lane == 0) wbase = atomicAdd(&s_count, (int)__popcll(ab));
-                wbase = __shfl(wbase, 0, 64);
-                if (alive) {
-                    stage[wbase + (int)__popcll(ab & lt)] = e;
-                    atomicMin(&nxt[u], p);
-                    atomicMin(&nxt[v], p);
-                    rst[u] = VMIN_NONE;
-                    rst[v] = VMIN_NONE;
-                }
-            }
+    const int n = A.st->ne;
+    if (blockIdx.x == 0 && threadIdx.x == 0) A.st->sel_k = k + 1;
+    for (long long base = (long long)blockIdx.x * BLOCK; base < n; base += (long long)gridDim.x * BLOCK) {
+        const long long i = base + threadIdx.x;
+        bool alive = false, sel = false;
+        int u = 0, v = 0, m = 0;
+        u64 p = 0;
+        const bool live_in = (i < n) && A.estate[i] == 0;
+        if (live_in) alive = subround_edge<false>(A, cur, k, (int)i, u, v, m, p, sel);
+        count_pairs(A, sel, m);
+        if (alive) {
+            atomicMin(&nxt[u], p);
+            atomicMin(&nxt[v], p);
+            rst[u] = VMIN_NONE;
+            rst[v] = VMIN_NONE;
+        } else if (live_in) {
+            A.estate[i] = 1;
         }
-        __syncthreads();
-        const int cnt = s_count;
-        if (threadIdx.x == 0 && cnt) s_base = atomicAdd(n_out, cnt);
-        __syncthreads();
-        if (cnt) {
-            const int gb = s_base;
-            for (int j = threadIdx.x; j < cnt; j += BLOCK) lout[gb + j] = stage[j];
-        }
-        __syncthreads();
     }
 }
+
+struct LivePred {
+    const unsigned char* estate;
+    __device__ bool operator()(int e) const { return estate[e] == 0; }
+};
+
+struct LiveOut {
+    int* list;
+    __device__ void operator()(int e, int pos) const { list[pos] = e; }
+};
 
 // Tail: once few edges are live, one workgroup runs the remaining sub-rounds
 // back to back with the worklist in LDS, so that they cost a barrier each
@@ -452,16 +436,11 @@ __global__ __launch_bounds__(TAIL_THREADS) void select_tail_kernel(SelArgs A) {
     __shared__ int lst[2][TAIL_MAX];
     __shared__ int s_cnt[2];
     int k = A.st->sel_k;
-    int n = (k == 0) ? A.st->ne : A.st->live[k % 3];
+    int n = A.st->live[0];     // live edges, gathered into A.list just before this kernel
     if (n > TAIL_MAX) return;  // too many: the host runs more grid-wide sub-rounds
     const int tid = threadIdx.x, lane = prim::lane_id();
     const u64 lt = prim::lanemask_lt();
-    if (k == 0) {
-        for (int i = tid; i < n; i += TAIL_THREADS) lst[0][i] = i;
-    } else {
-        const int* lin = A.list[k & 1];
-        for (int i = tid; i < n; i += TAIL_THREADS) lst[0][i] = lin[i];
-    }
+    for (int i = tid; i < n; i += TAIL_THREADS) lst[0][i] = A.list[i];
     int side = 0;
     __syncthreads();
     while (n > 0) {
@@ -782,6 +761,14 @@ __global__ __launch_bounds__(BLOCK) void copy_out_kernel(const VRec* __restrict_
     }
 }
 
+// Plain streaming copy, 16 bytes per lane per step: the yardstick for the
+// achievable HBM rate and for calibrating the profiler's byte counters.
+__global__ __launch_bounds__(BLOCK) void copy_kernel(const float4* __restrict__ src, float4* __restrict__ dst,
+                                                     size_t n16) {
+    const size_t stride = (size_t)gridDim.x * BLOCK;
+    for (size_t i = (size_t)blockIdx.x * BLOCK + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
 __global__ __launch_bounds__(BLOCK) void export_quadrics_kernel(const VRec* __restrict__ vrec, int N,
                                                                 float* __restrict__ out) {
     const int w = blockIdx.x * BLOCK + threadIdx.x;
@@ -853,7 +840,8 @@ struct picasso_ctx {
     int* newid = nullptr;
     int* vmap = nullptr;
     int* csr_off = nullptr;
-    int* list[2] = {nullptr, nullptr};
+    int* list = nullptr;
+    unsigned char* estate = nullptr;
     int* htab = nullptr;
     size_t hcap = 0;
     unsigned char* keep = nullptr;
@@ -949,8 +937,8 @@ size_t carve(picasso_ctx* c, char* base, int64_t N, int64_t F, int32_t B) {
     x->newid = cv.take<int>(n);
     x->vmap = cv.take<int>(n);
     x->csr_off = cv.take<int>(n + 1);
-    x->list[0] = cv.take<int>(h);
-    x->list[1] = cv.take<int>(h);
+    x->list = cv.take<int>(h);
+    x->estate = cv.take<unsigned char>(h);
     x->hcap = next_pow2(2 * f);
     x->htab = cv.take<int>(x->hcap);
     x->keep = cv.take<unsigned char>(f);
@@ -1148,7 +1136,7 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         }
         const u64 sentinel = (vbits >= 32) ? ~0ull : ((1ull << (2 * vbits)) - 1ull);
         UniquePred up{skeys, sentinel};
-        UniqueOut uo{skeys, c->ekey, c->ecost, c->vrec[cur], c->vmin[0], vbits, mt};
+        UniqueOut uo{skeys, c->ekey, c->ecost, c->vrec[cur], c->vmin[0], c->estate, vbits, mt};
         prim::compact(s, up, up, uo, &c->st->nh, H, c->tilesum, &c->st->ne);
         tm.end();
 
@@ -1159,27 +1147,30 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         sa.ecost = c->ecost;
         for (int i = 0; i < 3; ++i) sa.vmin[i] = c->vmin[i];
         sa.mate = c->mate;
-        sa.list[0] = c->list[0];
-        sa.list[1] = c->list[1];
+        sa.list = c->list;
+        sa.estate = c->estate;
         sa.st = c->st;
         sa.mt = mt;
         sa.vbits = vbits;
+        int sel_k = 0;
         // Grid-wide sub-rounds while many edges are live (the live count falls about 3x per
-        // sub-round), then the single-workgroup tail; the host looks once per batch.
-        int k = 0, launched = 0;
+        // sub-round), then the live edges are gathered and one workgroup finishes; the host
+        // looks once per batch.
+        int launched = 0;
+        const int ne_bound = H;  // distinct edges <= half-edges
         long long live_est = std::max(H / 2, 1);
         for (;;) {
             int wide = 0;
             for (long long l = live_est; l > TAIL_MAX * 3 / 4; l = l * 10 / 29) ++wide;
             wide = std::min<int>(wide, (int)std::max<int64_t>(1, c->opt_subround_batch));
-            for (int j = 0; j < wide; ++j, ++k) {
-                const long long lb = std::max<long long>(live_est, 1);
-                const int g = (int)std::min<long long>((lb + SEL_TILE - 1) / SEL_TILE, 16384);
-                select_subround_kernel<<<g, BLOCK, 0, s>>>(sa, k);
-                live_est = std::max<long long>(live_est * 10 / 29, TAIL_MAX / 8);
-            }
+            for (int j = 0; j < wide; ++j)
+                select_subround_kernel<<<grid_for(ne_bound, 1 << 16), BLOCK, 0, s>>>(sa, sel_k + j);
+            sel_k += wide;
+            LivePred lp{c->estate};
+            LiveOut lo{c->list};
+            prim::compact(s, lp, lp, lo, &c->st->ne, ne_bound, c->tilesum, &c->st->live[0]);
             select_tail_kernel<<<1, TAIL_THREADS, 0, s>>>(sa);
-            launched += wide + 1;
+            launched += wide + 3;
             rc = read_header(c, s);
             if (rc != PICASSO_OK) return rc;
             if (!validated) {
@@ -1187,8 +1178,8 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
                 if (st_err != PICASSO_OK) return st_err;
                 validated = true;
             }
-            k = hst->sel_k;
-            const int live = (k == 0) ? hst->ne : hst->live[k % 3];
+            sel_k = hst->sel_k;
+            const int live = hst->live[0];
             if (live == 0) break;
             live_est = live;
         }
@@ -1428,6 +1419,16 @@ int picasso_decimate(picasso_ctx* c, void* stream, const float* d_verts, int32_t
                          d_cluster_id, h_nv_out, h_nf_out, stats);
 }
 
+int picasso_device_copy(void* stream, void* d_dst, const void* d_src, size_t nbytes) {
+    if (!d_dst || !d_src || (nbytes & 15) || ((uintptr_t)d_dst & 15) || ((uintptr_t)d_src & 15))
+        return PICASSO_ERR_INVALID_ARG;
+    if (nbytes == 0) return PICASSO_OK;
+    const size_t n16 = nbytes / 16;
+    const int g = (int)std::min<size_t>((n16 + BLOCK - 1) / BLOCK, 256 * 32);
+    copy_kernel<<<g, BLOCK, 0, (hipStream_t)stream>>>((const float4*)d_src, (float4*)d_dst, n16);
+    return hipGetLastError() == hipSuccess ? PICASSO_OK : PICASSO_ERR_HIP;
+}
+
 int picasso_vertex_quadrics(picasso_ctx* c, void* stream, const float* d_verts, int32_t N, const int32_t* d_facets,
                             int32_t F, float* d_quadrics_out) {
     if (!c || !d_verts || N < 1 || F < 0 || (F > 0 && !d_facets) || !d_quadrics_out) return PICASSO_ERR_INVALID_ARG;
@@ -1492,7 +1493,7 @@ int picasso_edge_costs(picasso_ctx* c, void* stream, const float* d_verts, int32
     }
     const u64 sentinel = (vbits >= 32) ? ~0ull : ((1ull << (2 * vbits)) - 1ull);
     UniquePred up{skeys, sentinel};
-    UniqueOut uo{skeys, c->ekey, c->ecost, c->vrec[0], c->vmin[0], vbits, mt};
+    UniqueOut uo{skeys, c->ekey, c->ecost, c->vrec[0], c->vmin[0], c->estate, vbits, mt};
     prim::compact(s, up, up, uo, &c->st->nh, H, c->tilesum, &c->st->ne);
     export_edges_kernel<<<grid_for(std::max(H, 1)), BLOCK, 0, s>>>(c->ekey, c->ecost, c->st, vbits, d_edges_out,
                                                                    d_cost_out);
