@@ -19,6 +19,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# Bytes per launch of the edge-key sort's scatter kernel that crossed the L2-fabric boundary, from two
+# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by the copy-kernel calibration; see
+# profiles/hbm_counters_downsweep.md.  Offline measurements: null for workloads that were not profiled.
+MEASURED_TRAFFIC_BYTES = {"room115k": 12.36e6, "scene1p2m": 77.7e6}
 
 
 def main():
@@ -123,7 +127,8 @@ def main():
         bytes_per_launch = kt["bytes_total"] / kt["launches"]
         achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": kt["kernel"], "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": None,
+                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5),
+                    "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
                     "launches_per_step": kt["launches"] / args.steps, "avg_launch_us": round(avg_ms * 1e3, 3),
                     "algorithmic_bytes_per_launch": int(bytes_per_launch)}
 
