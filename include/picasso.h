@@ -152,6 +152,13 @@ int picasso_device_copy(void* stream, void* d_dst, const void* d_src, size_t nby
 int picasso_radix_sort(picasso_ctx* ctx, void* stream, int key_bytes, void* d_keys, uint32_t* d_vals, int64_t n,
                        int key_bits);
 
+/* Same contract as picasso_radix_sort, by the two-sweep method the path uses for
+ * keys led by vertex ids: a stable partition on the top 8 of the key_bits, then
+ * one workgroup per bucket sorts it in LDS (a bucket too large for LDS takes a
+ * slow global-memory route).  n <= 2^20. */
+int picasso_bucket_sort(picasso_ctx* ctx, void* stream, int key_bytes, void* d_keys, uint32_t* d_vals, int64_t n,
+                        int key_bits);
+
 #ifdef __cplusplus
 }
 #endif

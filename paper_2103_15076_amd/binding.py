@@ -33,7 +33,7 @@ EXPORTED_SYMBOLS = (
     "picasso_workspace_bytes", "picasso_create", "picasso_destroy", "picasso_set_option", "picasso_strerror",
     "picasso_last_hip_error", "picasso_decimate", "picasso_decimate_batch", "picasso_vertex_quadrics",
     "picasso_edge_costs", "picasso_radix_sort", "picasso_kernel_timing",
-    "picasso_device_copy",
+    "picasso_device_copy", "picasso_bucket_sort",
 )
 
 
@@ -110,6 +110,8 @@ def load_library():
     lib.picasso_device_copy.argtypes = [vp, vp, vp, ctypes.c_size_t]
     lib.picasso_radix_sort.restype = ctypes.c_int
     lib.picasso_radix_sort.argtypes = [vp, vp, ctypes.c_int, vp, vp, i64, ctypes.c_int]
+    lib.picasso_bucket_sort.restype = ctypes.c_int
+    lib.picasso_bucket_sort.argtypes = [vp, vp, ctypes.c_int, vp, vp, i64, ctypes.c_int]
     _lib = lib
     return lib
 
@@ -283,7 +285,11 @@ class Context:
             self._raise(st)
         return edges[: ne.value], cost[: ne.value]
 
-    def picasso_radix_sort(self, keys, vals=None, key_bits=None, stream=None):
+    def picasso_bucket_sort(self, keys, vals=None, key_bits=None, stream=None):
+        """Same as picasso_radix_sort, by top-digit partition + per-bucket LDS sort (n <= 2^20)."""
+        return self.picasso_radix_sort(keys, vals, key_bits, stream, _fn="picasso_bucket_sort")
+
+    def picasso_radix_sort(self, keys, vals=None, key_bits=None, stream=None, _fn="picasso_radix_sort"):
         """In-place stable sort of a uint32-as-int32 / uint64-as-int64 tensor on its low key_bits bits."""
         import torch
         if keys.dtype == torch.int64:
@@ -294,7 +300,7 @@ class Context:
             raise TypeError("keys must be int32 or int64 (bit patterns of unsigned keys)")
         if key_bits is None:
             key_bits = 8 * kb
-        st = self._lib.picasso_radix_sort(self._h, _stream_ptr(stream), kb, _dev_ptr(keys, keys.dtype, "keys"),
+        st = getattr(self._lib, _fn)(self._h, _stream_ptr(stream), kb, _dev_ptr(keys, keys.dtype, "keys"),
                                           _dev_ptr(vals, torch.int32, "vals") if vals is not None else None,
                                           int(keys.shape[0]), int(key_bits))
         if st != PICASSO_OK:

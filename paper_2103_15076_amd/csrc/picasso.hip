@@ -319,7 +319,7 @@ struct UniqueOut {
 constexpr int SEL_ITEMS = 1;
 constexpr int SEL_TILE = BLOCK * SEL_ITEMS;
 constexpr int TAIL_THREADS = 1024;
-constexpr int TAIL_MAX = 8192;  // live edges the single-workgroup tail takes over
+constexpr int TAIL_MAX = 3584;  // live edges the single-workgroup tail takes over (sized by its LDS state)
 
 struct SelArgs {
     const u64* ekey;
@@ -428,59 +428,124 @@ struct LiveOut {
     __device__ void operator()(int e, int pos) const { list[pos] = e; }
 };
 
-// Tail: once few edges are live, one workgroup runs the remaining sub-rounds
-// back to back with the worklist in LDS, so that they cost a barrier each
-// instead of a kernel launch.  The live count falls in every sub-round (the
-// globally best live edge is always accepted), so the loop ends.
+// Tail: once few edges are live, one workgroup finishes the matching with all
+// of its state in LDS: the live edges' priorities, a hash map from the (at
+// most 2 x TAIL_MAX) vertices they touch to LDS slots, and one 64-bit bid per
+// slot.  A sub-round then costs four workgroup barriers instead of a kernel
+// launch and several trips to memory.  The live count falls in every
+// sub-round (the best live edge is always accepted), so the loop ends.
+// A slot's bid doubles as its "paired" mark (TAIL_PAIRED is below every real
+// priority: a finite cost never has cost key 0).
+constexpr int TAIL_SLOTS = 8192;  // power of two, >= 2 * TAIL_MAX
+constexpr u64 TAIL_PAIRED = 0ull;
+
+struct TailLds {
+    u64 prio[TAIL_MAX];
+    u64 bid[TAIL_SLOTS];
+    int vkey[TAIL_SLOTS];
+    unsigned short su[TAIL_MAX], sv[TAIL_MAX];
+    unsigned short lst[2][TAIL_MAX];
+    int cnt[2];
+};
+
+__device__ __forceinline__ int tail_slot(int* vkey, int v) {
+    u32 h = ((u32)v * 0x9E3779B1u) >> 19;  // 13 bits
+    for (;;) {
+        const int old = atomicCAS(&vkey[h], -1, v);
+        if (old == -1 || old == v) return (int)h;
+        h = (h + 1) & (TAIL_SLOTS - 1);
+    }
+}
+
 __global__ __launch_bounds__(TAIL_THREADS) void select_tail_kernel(SelArgs A) {
-    __shared__ int lst[2][TAIL_MAX];
-    __shared__ int s_cnt[2];
-    int k = A.st->sel_k;
+    __shared__ TailLds L;
     int n = A.st->live[0];     // live edges, gathered into A.list just before this kernel
     if (n > TAIL_MAX) return;  // too many: the host runs more grid-wide sub-rounds
     const int tid = threadIdx.x, lane = prim::lane_id();
     const u64 lt = prim::lanemask_lt();
-    for (int i = tid; i < n; i += TAIL_THREADS) lst[0][i] = A.list[i];
+    const u64 vmask = (1ull << A.vbits) - 1ull;
+
+    for (int h = tid; h < TAIL_SLOTS; h += TAIL_THREADS) L.vkey[h] = -1;
+    __syncthreads();
+    for (int i = tid; i < n; i += TAIL_THREADS) {
+        const int e = A.list[i];
+        const u64 key = A.ekey[e];
+        L.prio[i] = ((u64)A.ecost[e] << 32) | (u32)e;
+        L.su[i] = (unsigned short)tail_slot(L.vkey, (int)(key >> A.vbits));
+        L.sv[i] = (unsigned short)tail_slot(L.vkey, (int)(key & vmask));
+        L.lst[0][i] = (unsigned short)i;
+    }
     int side = 0;
     __syncthreads();
+
     while (n > 0) {
-        const u64* cur = A.vmin[k % 3];
-        u64* nxt = A.vmin[(k + 1) % 3];
-        u64* rst = A.vmin[(k + 2) % 3];
-        if (tid == 0) s_cnt[side ^ 1] = 0;
-        __syncthreads();
         const int padded = (n + 63) & ~63;  // whole waves run each step so that the ballots are uniform
-        for (int i = tid; i < padded; i += TAIL_THREADS) {
-            bool alive = false, sel = false;
-            int e = 0, u = 0, v = 0, m = 0;
-            u64 p = 0;
-            if (i < n) {
-                e = lst[side][i];
-                alive = subround_edge<true>(A, cur, k, e, u, v, m, p, sel);
+        // clear the bids of every vertex that still has a live edge
+        for (int j = tid; j < n; j += TAIL_THREADS) {
+            const int i = L.lst[side][j];
+            L.bid[L.su[i]] = VMIN_NONE;
+            L.bid[L.sv[i]] = VMIN_NONE;
+        }
+        if (tid == 0) L.cnt[side ^ 1] = 0;
+        __syncthreads();
+        for (int j = tid; j < n; j += TAIL_THREADS) {
+            const int i = L.lst[side][j];
+            atomicMin(&L.bid[L.su[i]], L.prio[i]);
+            atomicMin(&L.bid[L.sv[i]], L.prio[i]);
+        }
+        __syncthreads();
+        // accept the edges that hold the best bid at both ends
+        bool mine[(TAIL_MAX + TAIL_THREADS - 1) / TAIL_THREADS];
+        int q = 0;
+        for (int j = tid; j < padded; j += TAIL_THREADS, ++q) {
+            bool sel = false;
+            int m = 0;
+            if (j < n) {
+                const int i = L.lst[side][j];
+                const u64 p = L.prio[i];
+                sel = (L.bid[L.su[i]] == p) && (L.bid[L.sv[i]] == p);
+                if (sel) {
+                    const int u = L.vkey[L.su[i]], v = L.vkey[L.sv[i]];
+                    A.mate[u] = v;
+                    A.mate[v] = u;
+                    m = mesh_of(A.mt.voff, A.mt.B, u);
+                }
             }
+            mine[q] = sel;
             count_pairs(A, sel, m);
+        }
+        __syncthreads();
+        q = 0;
+        for (int j = tid; j < n; j += TAIL_THREADS, ++q)
+            if (mine[q]) {
+                const int i = L.lst[side][j];
+                L.bid[L.su[i]] = TAIL_PAIRED;
+                L.bid[L.sv[i]] = TAIL_PAIRED;
+            }
+        __syncthreads();
+        // keep the edges whose ends are both still free
+        for (int j = tid; j < padded; j += TAIL_THREADS) {
+            bool alive = false;
+            int i = 0;
+            if (j < n) {
+                i = L.lst[side][j];
+                alive = (L.bid[L.su[i]] != TAIL_PAIRED) && (L.bid[L.sv[i]] != TAIL_PAIRED);
+            }
             const u64 ab = __ballot(alive);
             if (ab) {
                 int wbase = 0;
-                if (lane == 0) wbase = atomicAdd(&s_cnt[side ^ 1], (int)__popcll(ab));
+                if (lane == 0) wbase = atomicAdd(&L.cnt[side ^ 1], (int)__popcll(ab));
                 wbase = __shfl(wbase, 0, 64);
-                if (alive) {
-                    lst[side ^ 1][wbase + (int)__popcll(ab & lt)] = e;
-                    atomicMin(&nxt[u], p);
-                    atomicMin(&nxt[v], p);
-                    __hip_atomic_store(&rst[u], VMIN_NONE, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    __hip_atomic_store(&rst[v], VMIN_NONE, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
+                if (alive) L.lst[side ^ 1][wbase + (int)__popcll(ab & lt)] = (unsigned short)i;
             }
         }
-        __threadfence();  // this sub-round's bids and clears are at the L2 before anyone reads them
         __syncthreads();
         side ^= 1;
-        n = s_cnt[side];
-        ++k;
+        n = L.cnt[side];
         __syncthreads();
     }
-    __threadfence();
+
+    __threadfence();  // the pair counts added above are at the L2 before they are summed
     __syncthreads();
     for (int b = tid; b < A.mt.B; b += TAIL_THREADS) {
         int sum = 0;
@@ -489,12 +554,7 @@ __global__ __launch_bounds__(TAIL_THREADS) void select_tail_kernel(SelArgs A) {
                                      __HIP_MEMORY_SCOPE_AGENT);
         A.mt.matched[b] = sum;
     }
-    if (tid == 0) {
-        A.st->live[0] = 0;
-        A.st->live[1] = 0;
-        A.st->live[2] = 0;
-        A.st->sel_k = k;
-    }
+    if (tid == 0) A.st->live[0] = 0;
 }
 
 // ---------------------------------------------------------------------------
@@ -993,13 +1053,23 @@ struct StageTimer {
     }
 };
 
+// Sort for keys whose leading bits are vertex ids (evenly spread): bucket sort
+// when the input is small enough for it, plain LSD passes otherwise.
+template <typename K, bool HAS_VAL>
+int sort_by_vertex(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_ptr, int n_max, int key_bits,
+                   const prim::SortScratch& sc, prim::LaunchTimer* lt = nullptr, int tag = 0) {
+    if (n_max <= prim::BUCKET_SORT_MAX_KEYS && key_bits > prim::BUCKET_MSD_BITS)
+        return prim::bucket_sort<K, HAS_VAL>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc, lt, tag);
+    return prim::radix_sort<K, HAS_VAL>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc, lt, tag);
+}
+
 // S0 on the data already validated into the workspace by init_kernel.
 int run_vertex_quadrics(picasso_ctx* c, hipStream_t s, int N, int F) {
     const int H = 3 * F;
     u32* k0 = reinterpret_cast<u32*>(c->key64[0]);
     u32* k1 = reinterpret_cast<u32*>(c->key64[1]);
     if (F > 0) {
-        int where = prim::radix_sort<u32, true>(s, k0, k1, c->val32[0], c->val32[1], nullptr, H, ceil_log2(N), c->sort_sc);
+        int where = sort_by_vertex<u32, true>(s, k0, k1, c->val32[0], c->val32[1], nullptr, H, ceil_log2(N), c->sort_sc);
         if (where < 0) return PICASSO_ERR_HIP;
         const u32* skey = where ? k1 : k0;
         const u32* sval = where ? c->val32[1] : c->val32[0];
@@ -1128,9 +1198,9 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
             c->fbuf[cur], c->st, cur, vbits, c->key64[0], c->vmin[0], c->vmin[1], c->mate);
         const u64* skeys = c->key64[0];
         if (H > 0) {
-            int where = prim::radix_sort<u64, false>(s, c->key64[0], c->key64[1], nullptr, nullptr, &c->st->nh, H,
-                                                     2 * vbits, c->sort_sc, c->opt_kernel_timing ? &c->kt : nullptr,
-                                                     round);
+            int where = sort_by_vertex<u64, false>(s, c->key64[0], c->key64[1], nullptr, nullptr, &c->st->nh, H,
+                                                   2 * vbits, c->sort_sc, c->opt_kernel_timing ? &c->kt : nullptr,
+                                                   round);
             if (where < 0) return PICASSO_ERR_HIP;
             skeys = where ? c->key64[1] : c->key64[0];
         }
@@ -1160,8 +1230,10 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         const int ne_bound = H;  // distinct edges <= half-edges
         long long live_est = std::max(H / 2, 1);
         for (;;) {
+            // live edges fall by about 2.8x, 2.7x, 3.2x, 4x, 5x, ... per sub-round on meshes with varied costs
+            static const int decay_x10[] = {28, 27, 32, 40, 50, 60};
             int wide = 0;
-            for (long long l = live_est; l > TAIL_MAX * 3 / 4; l = l * 10 / 29) ++wide;
+            for (long long l = live_est; l > TAIL_MAX; l = l * 10 / decay_x10[std::min(wide, 5)]) ++wide;
             wide = std::min<int>(wide, (int)std::max<int64_t>(1, c->opt_subround_batch));
             for (int j = 0; j < wide; ++j)
                 select_subround_kernel<<<grid_for(ne_bound, 1 << 16), BLOCK, 0, s>>>(sa, sel_k + j);
@@ -1486,8 +1558,8 @@ int picasso_edge_costs(picasso_ctx* c, void* stream, const float* d_verts, int32
                                                                           c->vmin[0], c->vmin[1], c->mate);
     const u64* skeys = c->key64[0];
     if (H > 0) {
-        int where = prim::radix_sort<u64, false>(s, c->key64[0], c->key64[1], nullptr, nullptr, &c->st->nh, H, 2 * vbits,
-                                                 c->sort_sc);
+        int where = sort_by_vertex<u64, false>(s, c->key64[0], c->key64[1], nullptr, nullptr, &c->st->nh, H, 2 * vbits,
+                                               c->sort_sc);
         if (where < 0) return PICASSO_ERR_HIP;
         skeys = where ? c->key64[1] : c->key64[0];
     }
@@ -1501,6 +1573,27 @@ int picasso_edge_costs(picasso_ctx* c, void* stream, const float* d_verts, int32
     if (rc != PICASSO_OK) return rc;
     HIP_TRY(c, hipGetLastError());
     *h_ne_out = hst->ne;
+    return PICASSO_OK;
+}
+
+int picasso_bucket_sort(picasso_ctx* c, void* stream, int key_bytes, void* d_keys, uint32_t* d_vals, int64_t n,
+                        int key_bits) {
+    if (!c || !d_keys || n < 0 || (key_bytes != 4 && key_bytes != 8) || key_bits < 1 || key_bits > 8 * key_bytes)
+        return PICASSO_ERR_INVALID_ARG;
+    if (n > 3 * c->max_facets || n > prim::BUCKET_SORT_MAX_KEYS) return PICASSO_ERR_WORKSPACE;
+    if (n == 0) return PICASSO_OK;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(c, hipSetDevice(c->device));
+    int rc;
+    if (key_bytes == 8)
+        rc = d_vals ? prim::bucket_sort<u64, true>(s, (u64*)d_keys, c->key64[1], d_vals, c->val32[1], nullptr, (int)n, key_bits, c->sort_sc)
+                    : prim::bucket_sort<u64, false>(s, (u64*)d_keys, c->key64[1], nullptr, nullptr, nullptr, (int)n, key_bits, c->sort_sc);
+    else
+        rc = d_vals ? prim::bucket_sort<u32, true>(s, (u32*)d_keys, reinterpret_cast<u32*>(c->key64[1]), d_vals, c->val32[1], nullptr, (int)n, key_bits, c->sort_sc)
+                    : prim::bucket_sort<u32, false>(s, (u32*)d_keys, reinterpret_cast<u32*>(c->key64[1]), nullptr, nullptr, nullptr, (int)n, key_bits, c->sort_sc);
+    if (rc < 0) return PICASSO_ERR_HIP;
+    HIP_TRY(c, hipStreamSynchronize(s));
+    HIP_TRY(c, hipGetLastError());
     return PICASSO_OK;
 }
 

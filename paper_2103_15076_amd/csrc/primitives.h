@@ -288,6 +288,257 @@ inline int radix_sort(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* 
 }
 
 // ---------------------------------------------------------------------------
+// Bucket sort for inputs of up to BUCKET_SORT_MAX_KEYS keys whose leading bits
+// are spread evenly (vertex ids): one stable radix pass on the TOP 8 bits
+// splits the keys into 256 buckets, then each bucket is sorted on the
+// remaining bits by one workgroup entirely in LDS (register-staged LSD passes
+// over a single LDS array).  Two sweeps over memory instead of one per 8 bits,
+// and 4 launches instead of 3 per 8 bits.  A bucket that does not fit in LDS
+// (a very uneven key distribution) is sorted by the same workgroup with a slow
+// pass-by-pass LSD over global memory, so the result is always correct.
+// ---------------------------------------------------------------------------
+constexpr int BUCKET_THREADS = 1024;
+constexpr int BUCKET_WAVES = BUCKET_THREADS / 64;
+constexpr int BUCKET_ITEMS = 8;
+constexpr int BUCKET_CAP = BUCKET_THREADS * BUCKET_ITEMS;  // keys of one bucket held in LDS
+constexpr int BUCKET_MSD_BITS = 8;
+constexpr long long BUCKET_SORT_MAX_KEYS = 1ll << 20;  // average bucket <= half of BUCKET_CAP
+
+template <int NW>
+__device__ __forceinline__ u32 wide_block_exclusive_scan(u32 v, u32* smem, u32& total) {
+    const int lane = lane_id(), w = wave_id();
+    u32 incl = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        u32 o = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += o;
+    }
+    __syncthreads();
+    if (lane == 63) smem[w] = incl;
+    __syncthreads();
+    u32 woff = 0, tot = 0;
+    for (int i = 0; i < NW; ++i) {
+        u32 x = smem[i];
+        if (i < w) woff += x;
+        tot += x;
+    }
+    total = tot;
+    return woff + incl - v;
+}
+
+template <typename K>
+__device__ __forceinline__ K coherent_load(const K* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Slow path for a bucket larger than BUCKET_CAP: stable LSD over global memory
+// by this workgroup alone; wave 0 places the keys 64 at a time in order.
+template <typename K, bool HAS_VAL>
+__device__ void bucket_sort_oversize(K* a, K* b, u32* va, u32* vb, int cnt, int low_bits, u32* hist /*[256]*/,
+                                     u32* smem) {
+    // data starts in b (the partition pass wrote it there) and must end in a
+    K* src = b;
+    K* dst = a;
+    u32* vsrc = vb;
+    u32* vdst = va;
+    const int passes = (low_bits + 7) / 8;
+    const int per = (low_bits + passes - 1) / passes;
+    const int t = threadIdx.x, lane = lane_id();
+    int shift = 0;
+    for (int p = 0; p < passes; ++p) {
+        const int bits = (low_bits - shift) < per ? (low_bits - shift) : per;
+        const u32 R = 1u << bits, dmask = R - 1;
+        if (t < 256) hist[t] = 0;
+        __syncthreads();
+        for (int i = t; i < cnt; i += BUCKET_THREADS) atomicAdd(&hist[digit_of<K>(coherent_load(&src[i]), shift, dmask)], 1u);
+        __syncthreads();
+        u32 tot;
+        const u32 c = (t < 256 && (u32)t < R) ? hist[t] : 0u;
+        const u32 ex = wide_block_exclusive_scan<BUCKET_WAVES>(c, smem, tot);
+        __syncthreads();
+        if (t < 256) hist[t] = ex;  // running output position of each digit
+        __syncthreads();
+        if (t < 64) {
+            for (int base = 0; base < cnt; base += 64) {
+                const int i = base + lane;
+                const bool ok = i < cnt;
+                const K k = ok ? coherent_load(&src[i]) : (K)0;
+                const u32 d = ok ? digit_of<K>(k, shift, dmask) : 0xFFFFFFFFu;
+                u64 m = __ballot(ok);
+                for (int bb = 0; bb < bits; ++bb) {
+                    const bool bit = (d >> bb) & 1u;
+                    const u64 bal = __ballot(bit);
+                    m &= bit ? bal : ~bal;
+                }
+                if (ok) {
+                    const u32 below = (u32)__popcll(m & lanemask_lt());
+                    const u32 old = hist[d];
+                    __builtin_amdgcn_wave_barrier();
+                    if (below == 0) hist[d] = old + (u32)__popcll(m);
+                    __builtin_amdgcn_wave_barrier();
+                    dst[old + below] = k;
+                    if (HAS_VAL) vdst[old + below] = coherent_load(&vsrc[i]);
+                }
+            }
+        }
+        __threadfence();
+        __syncthreads();
+        K* tk = src; src = dst; dst = tk;
+        u32* tv = vsrc; vsrc = vdst; vdst = tv;
+        shift += bits;
+    }
+    if (src != a) {  // an even number of passes left the result in b
+        for (int i = t; i < cnt; i += BUCKET_THREADS) {
+            a[i] = coherent_load(&src[i]);
+            if (HAS_VAL) va[i] = coherent_load(&vsrc[i]);
+        }
+    }
+}
+
+// One workgroup per bucket.  kin/vin hold the keys partitioned by their top
+// digit (bucket d occupies [start_d, start_d + totals[d])); the sorted bucket is
+// written to the same range of kout/vout.  low_bits = key bits below the digit.
+template <typename K, bool HAS_VAL>
+__global__ __launch_bounds__(BUCKET_THREADS) void bucket_sort_kernel(K* __restrict__ kin, K* __restrict__ kout,
+                                                                     u32* __restrict__ vin, u32* __restrict__ vout,
+                                                                     const u32* __restrict__ totals, int nbuckets,
+                                                                     int low_bits) {
+    __shared__ K skey[BUCKET_CAP];
+    __shared__ u32 sval[HAS_VAL ? BUCKET_CAP : 1];
+    __shared__ u32 wcnt[BUCKET_WAVES][256];
+    __shared__ u32 tstart[256];
+    __shared__ u32 smem[BUCKET_WAVES];
+    const int t = threadIdx.x, w = wave_id(), lane = lane_id();
+    const int bkt = blockIdx.x;
+
+    // start of this bucket = sum of the counts of the buckets before it
+    u32 tot;
+    const u32 mine = (t < nbuckets) ? totals[t] : 0u;
+    const u32 ex = wide_block_exclusive_scan<BUCKET_WAVES>(mine, smem, tot);
+    if (t == bkt) {
+        tstart[0] = ex;
+        tstart[1] = mine;
+    }
+    __syncthreads();
+    const u32 start = tstart[0];
+    const int cnt = (int)tstart[1];
+    __syncthreads();
+    if (cnt == 0) return;
+    if (cnt > BUCKET_CAP) {
+        bucket_sort_oversize<K, HAS_VAL>(kout + start, kin + start, HAS_VAL ? vout + start : nullptr,
+                                         HAS_VAL ? vin + start : nullptr, cnt, low_bits, tstart, smem);
+        return;
+    }
+    if (low_bits <= 0) {
+        for (int i = t; i < cnt; i += BUCKET_THREADS) {
+            kout[start + i] = kin[start + i];
+            if (HAS_VAL) vout[start + i] = vin[start + i];
+        }
+        return;
+    }
+
+    const int items = (cnt + BUCKET_THREADS - 1) / BUCKET_THREADS;  // <= BUCKET_ITEMS, same for the whole workgroup
+    for (int i = t; i < cnt; i += BUCKET_THREADS) {
+        skey[i] = kin[start + i];
+        if (HAS_VAL) sval[i] = vin[start + i];
+    }
+    __syncthreads();
+
+    const int passes = (low_bits + 7) / 8;
+    const int per = (low_bits + passes - 1) / passes;
+    const u64 lt = lanemask_lt();
+    int shift = 0;
+    for (int p = 0; p < passes; ++p) {
+        const int bits = (low_bits - shift) < per ? (low_bits - shift) : per;
+        const u32 R = 1u << bits, dmask = R - 1;
+        for (int i = t; i < BUCKET_WAVES * 256; i += BUCKET_THREADS) (&wcnt[0][0])[i] = 0;
+        K key[BUCKET_ITEMS];
+        u32 val[BUCKET_ITEMS];
+        u32 rank[BUCKET_ITEMS];
+#pragma unroll
+        for (int i = 0; i < BUCKET_ITEMS; ++i) {
+            if (i < items) {
+                const int idx = w * (64 * items) + i * 64 + lane;  // index order = (wave, item, lane)
+                const bool ok = idx < cnt;
+                key[i] = ok ? skey[idx] : (K) ~(K)0;
+                if (HAS_VAL) val[i] = ok ? sval[idx] : 0u;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < BUCKET_ITEMS; ++i) {
+            if (i < items) {
+                const u32 d = digit_of<K>(key[i], shift, dmask);
+                u64 m = ~0ull;
+                for (int b = 0; b < bits; ++b) {
+                    const bool bit = (d >> b) & 1u;
+                    const u64 bal = __ballot(bit);
+                    m &= bit ? bal : ~bal;
+                }
+                const u32 old = wcnt[w][d];
+                const u32 below = (u32)__popcll(m & lt);
+                __builtin_amdgcn_wave_barrier();
+                if (below == 0) wcnt[w][d] = old + (u32)__popcll(m);
+                __builtin_amdgcn_wave_barrier();
+                rank[i] = old + below;
+            }
+        }
+        __syncthreads();
+        u32 dtot = 0;
+        if ((u32)t < R) {
+            u32 run = 0;
+            for (int ww = 0; ww < BUCKET_WAVES; ++ww) {
+                const u32 c = wcnt[ww][t];
+                wcnt[ww][t] = run;
+                run += c;
+            }
+            dtot = run;
+        }
+        u32 dummy;
+        const u32 dex = wide_block_exclusive_scan<BUCKET_WAVES>(dtot, smem, dummy);
+        if ((u32)t < R) tstart[t] = dex;
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < BUCKET_ITEMS; ++i) {
+            if (i < items) {
+                const u32 d = digit_of<K>(key[i], shift, dmask);
+                const u32 pos = tstart[d] + wcnt[w][d] + rank[i];
+                if (pos < (u32)cnt) {  // padding (all-ones keys) ranks last and is dropped
+                    skey[pos] = key[i];
+                    if (HAS_VAL) sval[pos] = val[i];
+                }
+            }
+        }
+        __syncthreads();
+        shift += bits;
+    }
+    for (int i = t; i < cnt; i += BUCKET_THREADS) {
+        kout[start + i] = skey[i];
+        if (HAS_VAL) vout[start + i] = sval[i];
+    }
+}
+
+// Stable sort on key bits [0, key_bits) for n <= BUCKET_SORT_MAX_KEYS keys with
+// evenly spread leading bits.  The result is always in (k0, v0): returns 0, or <0 on a launch error.
+template <typename K, bool HAS_VAL>
+inline int bucket_sort(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_ptr, int n_max, int key_bits,
+                       const SortScratch& sc, LaunchTimer* lt = nullptr, int tag = 0) {
+    if (n_max <= 0 || key_bits <= 0) return 0;
+    const int msd = key_bits < BUCKET_MSD_BITS ? key_bits : BUCKET_MSD_BITS;
+    const int low = key_bits - msd;
+    const int tiles = sort_tiles(n_max, SORT_ITEMS_SMALL);
+    radix_upsweep_kernel<K, SORT_ITEMS_SMALL><<<tiles, BLOCK, 0, s>>>(k0, n_ptr, n_max, sc.T, sc.table, low, msd);
+    radix_scan_kernel<<<1 << msd, BLOCK, 0, s>>>(sc.table, sc.totals, n_ptr, n_max, sc.T, BLOCK * SORT_ITEMS_SMALL);
+    const bool timed = lt && lt->begin(s, tag);
+    radix_downsweep_kernel<K, HAS_VAL, SORT_ITEMS_SMALL>
+        <<<tiles, BLOCK, 0, s>>>(k0, k1, v0, v1, n_ptr, n_max, sc.T, sc.table, sc.totals, low, msd);
+    if (timed) lt->end(s);
+    bucket_sort_kernel<K, HAS_VAL><<<1 << msd, BUCKET_THREADS, 0, s>>>(k1, k0, v1, v0, sc.totals, 1 << msd, low);
+    if (hipGetLastError() != hipSuccess) return -1;
+    return 0;
+}
+
+// ---------------------------------------------------------------------------
 // Flag compaction.  count kernel: tilesum[tile] = number of i in the tile with
 // pred(i).  scatter kernel: calls out(i, rank) for every flagged i, rank = its
 // position among flagged items in index order; writes the grand total.

@@ -81,6 +81,43 @@ def test_radix_sort_u64(ctx, n, bits, with_vals):
         assert np.array_equal(v.cpu().numpy(), order.astype(np.int32))
 
 
+def _bucket_cases():
+    rng = np.random.default_rng(99)
+    # (name, keys, bits): evenly spread, ragged, empty buckets, one bucket far beyond the LDS capacity
+    yield "uniform34", rng.integers(0, 1 << 34, size=300001, dtype=np.uint64), 34
+    yield "tiny", rng.integers(0, 1 << 20, size=37, dtype=np.uint64), 20
+    yield "few_bits", rng.integers(0, 1 << 6, size=5000, dtype=np.uint64), 6
+    yield "nine_bits", rng.integers(0, 1 << 9, size=70000, dtype=np.uint64), 9
+    k = rng.integers(0, 1 << 32, size=200000, dtype=np.uint64)
+    k[:120000] = (np.uint64(5) << np.uint64(24)) | (k[:120000] & np.uint64(0xFFFFFF))   # 120k keys share the top byte
+    rng.shuffle(k)
+    yield "skewed_oversize", k, 32
+    k = np.full(30000, (7 << 20) | 12345, np.uint64)   # all equal: one oversize bucket, stability only
+    yield "all_equal", k, 28
+    yield "full", rng.integers(0, 1 << 40, size=1 << 20, dtype=np.uint64), 40
+
+
+@pytest.mark.parametrize("name,keys,bits", list(_bucket_cases()), ids=lambda x: x if isinstance(x, str) else "")
+@pytest.mark.parametrize("width", [32, 64])
+def test_bucket_sort_is_stable_and_handles_uneven_buckets(ctx, name, keys, bits, width):
+    if width == 32 and bits > 32:
+        keys, bits = keys & np.uint64(0xFFFFFFFF), 32
+    n = keys.shape[0]
+    vals = np.arange(n, dtype=np.int32)
+    k = dev(keys.astype(np.uint32).view(np.int32)) if width == 32 else dev(keys.view(np.int64))
+    v = dev(vals)
+    print(f"bucket sort {name} n={n} bits={bits} width={width}", flush=True)
+    ctx.picasso_bucket_sort(k, v, key_bits=bits)
+    order = np.argsort(keys, kind="stable")
+    got = k.cpu().numpy().view(np.uint32 if width == 32 else np.uint64)
+    assert np.array_equal(got.astype(np.uint64), keys[order])
+    assert np.array_equal(v.cpu().numpy(), order.astype(np.int32))
+    # keys only
+    k2 = dev(keys.astype(np.uint32).view(np.int32)) if width == 32 else dev(keys.view(np.int64))
+    ctx.picasso_bucket_sort(k2, None, key_bits=bits)
+    assert np.array_equal(k2.cpu().numpy().view(np.uint32 if width == 32 else np.uint64).astype(np.uint64), keys[order])
+
+
 # ----------------------------------------------------------------------------
 # single steps
 # ----------------------------------------------------------------------------
