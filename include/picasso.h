@@ -155,7 +155,8 @@ int picasso_radix_sort(picasso_ctx* ctx, void* stream, int key_bytes, void* d_ke
 /* Same contract as picasso_radix_sort, by the two-sweep method the path uses for
  * keys led by vertex ids: a stable partition on the top 8 of the key_bits, then
  * one workgroup per bucket sorts it in LDS (a bucket too large for LDS takes a
- * slow global-memory route).  n <= 2^20. */
+ * slow global-memory route).  2^20 < n <= 2^23 uses 4096 buckets on the top 12
+ * bits (two 6-bit partition passes; needs key_bits > 12). */
 int picasso_bucket_sort(picasso_ctx* ctx, void* stream, int key_bytes, void* d_keys, uint32_t* d_vals, int64_t n,
                         int key_bits);
 

@@ -907,6 +907,7 @@ struct picasso_ctx {
     unsigned char* keep = nullptr;
     int* tilesum = nullptr;
     prim::SortScratch sort_sc{};
+    u32* hist12 = nullptr;  // bucket sizes of the 4096-bucket sort
     // per-mesh tables
     int* voff[2] = {nullptr, nullptr};
     int* foff = nullptr;
@@ -1006,6 +1007,7 @@ size_t carve(picasso_ctx* c, char* base, int64_t N, int64_t F, int32_t B) {
     x->sort_sc.T = prim::sort_table_stride((long long)h);
     x->sort_sc.table = cv.take<u32>((size_t)256 * x->sort_sc.T);
     x->sort_sc.totals = cv.take<u32>(256);
+    x->hist12 = cv.take<u32>(4096);
     x->voff[1] = cv.take<int>(b + 1);
     x->nrem = cv.take<int>(b);
     x->segstart = cv.take<int>(b);
@@ -1057,9 +1059,11 @@ struct StageTimer {
 // when the input is small enough for it, plain LSD passes otherwise.
 template <typename K, bool HAS_VAL>
 int sort_by_vertex(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_ptr, int n_max, int key_bits,
-                   const prim::SortScratch& sc, prim::LaunchTimer* lt = nullptr, int tag = 0) {
+                   const prim::SortScratch& sc, u32* hist12, prim::LaunchTimer* lt = nullptr, int tag = 0) {
     if (n_max <= prim::BUCKET_SORT_MAX_KEYS && key_bits > prim::BUCKET_MSD_BITS)
         return prim::bucket_sort<K, HAS_VAL>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc, lt, tag);
+    if (n_max <= prim::BUCKET_SORT_LARGE_MAX_KEYS && key_bits > prim::BUCKET_LARGE_MSD_BITS)
+        return prim::bucket_sort_large<K, HAS_VAL>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc, hist12, lt, tag);
     return prim::radix_sort<K, HAS_VAL>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc, lt, tag);
 }
 
@@ -1069,7 +1073,7 @@ int run_vertex_quadrics(picasso_ctx* c, hipStream_t s, int N, int F) {
     u32* k0 = reinterpret_cast<u32*>(c->key64[0]);
     u32* k1 = reinterpret_cast<u32*>(c->key64[1]);
     if (F > 0) {
-        int where = sort_by_vertex<u32, true>(s, k0, k1, c->val32[0], c->val32[1], nullptr, H, ceil_log2(N), c->sort_sc);
+        int where = sort_by_vertex<u32, true>(s, k0, k1, c->val32[0], c->val32[1], nullptr, H, ceil_log2(N), c->sort_sc, c->hist12);
         if (where < 0) return PICASSO_ERR_HIP;
         const u32* skey = where ? k1 : k0;
         const u32* sval = where ? c->val32[1] : c->val32[0];
@@ -1199,8 +1203,8 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         const u64* skeys = c->key64[0];
         if (H > 0) {
             int where = sort_by_vertex<u64, false>(s, c->key64[0], c->key64[1], nullptr, nullptr, &c->st->nh, H,
-                                                   2 * vbits, c->sort_sc, c->opt_kernel_timing ? &c->kt : nullptr,
-                                                   round);
+                                                   2 * vbits, c->sort_sc, c->hist12,
+                                                   c->opt_kernel_timing ? &c->kt : nullptr, round);
             if (where < 0) return PICASSO_ERR_HIP;
             skeys = where ? c->key64[1] : c->key64[0];
         }
@@ -1559,7 +1563,7 @@ int picasso_edge_costs(picasso_ctx* c, void* stream, const float* d_verts, int32
     const u64* skeys = c->key64[0];
     if (H > 0) {
         int where = sort_by_vertex<u64, false>(s, c->key64[0], c->key64[1], nullptr, nullptr, &c->st->nh, H, 2 * vbits,
-                                               c->sort_sc);
+                                               c->sort_sc, c->hist12);
         if (where < 0) return PICASSO_ERR_HIP;
         skeys = where ? c->key64[1] : c->key64[0];
     }
@@ -1580,18 +1584,34 @@ int picasso_bucket_sort(picasso_ctx* c, void* stream, int key_bytes, void* d_key
                         int key_bits) {
     if (!c || !d_keys || n < 0 || (key_bytes != 4 && key_bytes != 8) || key_bits < 1 || key_bits > 8 * key_bytes)
         return PICASSO_ERR_INVALID_ARG;
-    if (n > 3 * c->max_facets || n > prim::BUCKET_SORT_MAX_KEYS) return PICASSO_ERR_WORKSPACE;
+    if (n > 3 * c->max_facets || n > prim::BUCKET_SORT_LARGE_MAX_KEYS) return PICASSO_ERR_WORKSPACE;
     if (n == 0) return PICASSO_OK;
     hipStream_t s = (hipStream_t)stream;
     HIP_TRY(c, hipSetDevice(c->device));
     int rc;
-    if (key_bytes == 8)
-        rc = d_vals ? prim::bucket_sort<u64, true>(s, (u64*)d_keys, c->key64[1], d_vals, c->val32[1], nullptr, (int)n, key_bits, c->sort_sc)
-                    : prim::bucket_sort<u64, false>(s, (u64*)d_keys, c->key64[1], nullptr, nullptr, nullptr, (int)n, key_bits, c->sort_sc);
-    else
-        rc = d_vals ? prim::bucket_sort<u32, true>(s, (u32*)d_keys, reinterpret_cast<u32*>(c->key64[1]), d_vals, c->val32[1], nullptr, (int)n, key_bits, c->sort_sc)
-                    : prim::bucket_sort<u32, false>(s, (u32*)d_keys, reinterpret_cast<u32*>(c->key64[1]), nullptr, nullptr, nullptr, (int)n, key_bits, c->sort_sc);
+    const bool large = n > prim::BUCKET_SORT_MAX_KEYS;
+    if (large && key_bits <= prim::BUCKET_LARGE_MSD_BITS) return PICASSO_ERR_INVALID_ARG;
+    if (key_bytes == 8) {
+        u64* k1 = c->key64[1];
+        if (large)
+            rc = d_vals ? prim::bucket_sort_large<u64, true>(s, (u64*)d_keys, k1, d_vals, c->val32[1], nullptr, (int)n, key_bits, c->sort_sc, c->hist12)
+                        : prim::bucket_sort_large<u64, false>(s, (u64*)d_keys, k1, nullptr, nullptr, nullptr, (int)n, key_bits, c->sort_sc, c->hist12);
+        else
+            rc = d_vals ? prim::bucket_sort<u64, true>(s, (u64*)d_keys, k1, d_vals, c->val32[1], nullptr, (int)n, key_bits, c->sort_sc)
+                        : prim::bucket_sort<u64, false>(s, (u64*)d_keys, k1, nullptr, nullptr, nullptr, (int)n, key_bits, c->sort_sc);
+        if (rc == 1) HIP_TRY(c, hipMemcpyAsync(d_keys, k1, sizeof(u64) * n, hipMemcpyDeviceToDevice, s));
+    } else {
+        u32* k1 = reinterpret_cast<u32*>(c->key64[1]);
+        if (large)
+            rc = d_vals ? prim::bucket_sort_large<u32, true>(s, (u32*)d_keys, k1, d_vals, c->val32[1], nullptr, (int)n, key_bits, c->sort_sc, c->hist12)
+                        : prim::bucket_sort_large<u32, false>(s, (u32*)d_keys, k1, nullptr, nullptr, nullptr, (int)n, key_bits, c->sort_sc, c->hist12);
+        else
+            rc = d_vals ? prim::bucket_sort<u32, true>(s, (u32*)d_keys, k1, d_vals, c->val32[1], nullptr, (int)n, key_bits, c->sort_sc)
+                        : prim::bucket_sort<u32, false>(s, (u32*)d_keys, k1, nullptr, nullptr, nullptr, (int)n, key_bits, c->sort_sc);
+        if (rc == 1) HIP_TRY(c, hipMemcpyAsync(d_keys, k1, sizeof(u32) * n, hipMemcpyDeviceToDevice, s));
+    }
     if (rc < 0) return PICASSO_ERR_HIP;
+    if (rc == 1 && d_vals) HIP_TRY(c, hipMemcpyAsync(d_vals, c->val32[1], sizeof(u32) * n, hipMemcpyDeviceToDevice, s));
     HIP_TRY(c, hipStreamSynchronize(s));
     HIP_TRY(c, hipGetLastError());
     return PICASSO_OK;

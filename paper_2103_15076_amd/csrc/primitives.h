@@ -88,13 +88,20 @@ __global__ __launch_bounds__(BLOCK) void radix_upsweep_kernel(const K* __restric
     const u32 R = 1u << bits, dmask = R - 1;
     for (int i = t; i < WAVES * 256; i += BLOCK) (&hist[0][0])[i] = 0;
     __syncthreads();
+    // a digit narrower than 8 bits leaves room for 256/R copies of the histogram per wave:
+    // lanes spread over the copies, so fewer of them meet on one LDS word
+    const u32 copy = ((u32)lane_id() & ((256u >> bits) - 1u)) << bits;
 #pragma unroll 4
     for (int i = 0; i < SORT_ITEMS; ++i) {
         long long idx = base + (long long)i * BLOCK + t;
-        if (idx < n) atomicAdd(&hist[w][digit_of<K>(kin[idx], shift, dmask)], 1u);
+        if (idx < n) atomicAdd(&hist[w][copy | digit_of<K>(kin[idx], shift, dmask)], 1u);
     }
     __syncthreads();
-    if ((u32)t < R) table[(size_t)t * T + tile] = hist[0][t] + hist[1][t] + hist[2][t] + hist[3][t];
+    if ((u32)t < R) {
+        u32 sum = 0;
+        for (u32 c = (u32)t; c < 256u; c += R) sum += hist[0][c] + hist[1][c] + hist[2][c] + hist[3][c];
+        table[(size_t)t * T + tile] = sum;
+    }
 }
 
 // One workgroup per digit: exclusive scan of its table row over the tiles in
@@ -297,12 +304,11 @@ inline int radix_sort(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* 
 // (a very uneven key distribution) is sorted by the same workgroup with a slow
 // pass-by-pass LSD over global memory, so the result is always correct.
 // ---------------------------------------------------------------------------
-constexpr int BUCKET_THREADS = 1024;
-constexpr int BUCKET_WAVES = BUCKET_THREADS / 64;
 constexpr int BUCKET_ITEMS = 8;
-constexpr int BUCKET_CAP = BUCKET_THREADS * BUCKET_ITEMS;  // keys of one bucket held in LDS
+constexpr int BUCKET_THREADS_256 = 1024;  // 256 buckets: up to 8192 keys of a bucket held in LDS
+constexpr int BUCKET_THREADS_4096 = 512;  // 4096 buckets: up to 4096 keys
 constexpr int BUCKET_MSD_BITS = 8;
-constexpr long long BUCKET_SORT_MAX_KEYS = 1ll << 20;  // average bucket <= half of BUCKET_CAP
+constexpr long long BUCKET_SORT_MAX_KEYS = 1ll << 20;  // average bucket <= half of what LDS holds
 
 template <int NW>
 __device__ __forceinline__ u32 wide_block_exclusive_scan(u32 v, u32* smem, u32& total) {
@@ -333,9 +339,10 @@ __device__ __forceinline__ K coherent_load(const K* p) {
 
 // Slow path for a bucket larger than BUCKET_CAP: stable LSD over global memory
 // by this workgroup alone; wave 0 places the keys 64 at a time in order.
-template <typename K, bool HAS_VAL>
+template <typename K, bool HAS_VAL, int BUCKET_THREADS>
 __device__ void bucket_sort_oversize(K* a, K* b, u32* va, u32* vb, int cnt, int low_bits, u32* hist /*[256]*/,
                                      u32* smem) {
+    constexpr int BUCKET_WAVES = BUCKET_THREADS / 64;
     // data starts in b (the partition pass wrote it there) and must end in a
     K* src = b;
     K* dst = a;
@@ -398,11 +405,13 @@ __device__ void bucket_sort_oversize(K* a, K* b, u32* va, u32* vb, int cnt, int 
 // One workgroup per bucket.  kin/vin hold the keys partitioned by their top
 // digit (bucket d occupies [start_d, start_d + totals[d])); the sorted bucket is
 // written to the same range of kout/vout.  low_bits = key bits below the digit.
-template <typename K, bool HAS_VAL>
+template <typename K, bool HAS_VAL, int BUCKET_THREADS>
 __global__ __launch_bounds__(BUCKET_THREADS) void bucket_sort_kernel(K* __restrict__ kin, K* __restrict__ kout,
                                                                      u32* __restrict__ vin, u32* __restrict__ vout,
                                                                      const u32* __restrict__ totals, int nbuckets,
                                                                      int low_bits) {
+    constexpr int BUCKET_WAVES = BUCKET_THREADS / 64;
+    constexpr int BUCKET_CAP = BUCKET_THREADS * BUCKET_ITEMS;  // keys of one bucket held in LDS
     __shared__ K skey[BUCKET_CAP];
     __shared__ u32 sval[HAS_VAL ? BUCKET_CAP : 1];
     __shared__ u32 wcnt[BUCKET_WAVES][256];
@@ -412,20 +421,17 @@ __global__ __launch_bounds__(BUCKET_THREADS) void bucket_sort_kernel(K* __restri
     const int bkt = blockIdx.x;
 
     // start of this bucket = sum of the counts of the buckets before it
-    u32 tot;
-    const u32 mine = (t < nbuckets) ? totals[t] : 0u;
-    const u32 ex = wide_block_exclusive_scan<BUCKET_WAVES>(mine, smem, tot);
-    if (t == bkt) {
-        tstart[0] = ex;
-        tstart[1] = mine;
-    }
-    __syncthreads();
-    const u32 start = tstart[0];
-    const int cnt = (int)tstart[1];
-    __syncthreads();
+    (void)nbuckets;
+    const int cnt = (int)totals[bkt];
     if (cnt == 0) return;
+    u32 part = 0;
+    for (int j = t; j < bkt; j += BUCKET_THREADS) part += totals[j];
+    u32 tot;
+    (void)wide_block_exclusive_scan<BUCKET_WAVES>(part, smem, tot);
+    const u32 start = tot;
+    __syncthreads();
     if (cnt > BUCKET_CAP) {
-        bucket_sort_oversize<K, HAS_VAL>(kout + start, kin + start, HAS_VAL ? vout + start : nullptr,
+        bucket_sort_oversize<K, HAS_VAL, BUCKET_THREADS>(kout + start, kin + start, HAS_VAL ? vout + start : nullptr,
                                          HAS_VAL ? vin + start : nullptr, cnt, low_bits, tstart, smem);
         return;
     }
@@ -451,7 +457,8 @@ __global__ __launch_bounds__(BUCKET_THREADS) void bucket_sort_kernel(K* __restri
     for (int p = 0; p < passes; ++p) {
         const int bits = (low_bits - shift) < per ? (low_bits - shift) : per;
         const u32 R = 1u << bits, dmask = R - 1;
-        for (int i = t; i < BUCKET_WAVES * 256; i += BUCKET_THREADS) (&wcnt[0][0])[i] = 0;
+        for (int i = t; i < BUCKET_WAVES * 256; i += BUCKET_THREADS)
+            if ((u32)(i & 255) < R) (&wcnt[0][0])[i] = 0;
         K key[BUCKET_ITEMS];
         u32 val[BUCKET_ITEMS];
         u32 rank[BUCKET_ITEMS];
@@ -533,9 +540,76 @@ inline int bucket_sort(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int*
     radix_downsweep_kernel<K, HAS_VAL, SORT_ITEMS_SMALL>
         <<<tiles, BLOCK, 0, s>>>(k0, k1, v0, v1, n_ptr, n_max, sc.T, sc.table, sc.totals, low, msd);
     if (timed) lt->end(s);
-    bucket_sort_kernel<K, HAS_VAL><<<1 << msd, BUCKET_THREADS, 0, s>>>(k1, k0, v1, v0, sc.totals, 1 << msd, low);
+    bucket_sort_kernel<K, HAS_VAL, BUCKET_THREADS_256>
+        <<<1 << msd, BUCKET_THREADS_256, 0, s>>>(k1, k0, v1, v0, sc.totals, 1 << msd, low);
     if (hipGetLastError() != hipSuccess) return -1;
     return 0;
+}
+
+// Larger inputs (up to BUCKET_SORT_LARGE_MAX_KEYS): 4096 buckets on the top 12
+// bits.  A single 12-bit partition pass would scatter about one key per digit
+// and tile, so the partition is done as two stable 6-bit passes (low half
+// first), and the bucket sizes come from a 12-bit histogram taken up front.
+constexpr int BUCKET_LARGE_MSD_BITS = 12;
+constexpr long long BUCKET_SORT_LARGE_MAX_KEYS = 1ll << 23;
+
+template <typename K>
+__global__ __launch_bounds__(BLOCK) void top_digit_histogram_kernel(const K* __restrict__ kin, const int* n_ptr,
+                                                                    int n_host, u32* __restrict__ hist, int shift) {
+    constexpr int R = 1 << BUCKET_LARGE_MSD_BITS;
+    constexpr int TILE = BLOCK * SORT_ITEMS_BIG;
+    __shared__ u32 h[R];
+    const int n = load_count(n_ptr, n_host);
+    const long long base = (long long)blockIdx.x * TILE;
+    if (base >= n) return;
+    const int t = threadIdx.x;
+    for (int i = t; i < R; i += BLOCK) h[i] = 0;
+    __syncthreads();
+#pragma unroll 4
+    for (int i = 0; i < SORT_ITEMS_BIG; ++i) {
+        const long long idx = base + (long long)i * BLOCK + t;
+        if (idx < n) atomicAdd(&h[digit_of<K>(kin[idx], shift, R - 1)], 1u);
+    }
+    __syncthreads();
+    for (int i = t; i < R; i += BLOCK) {
+        const u32 c = h[i];
+        if (c) atomicAdd(&hist[i], c);
+    }
+}
+
+__global__ __launch_bounds__(BLOCK) void fill_u32_kernel(u32* __restrict__ p, int n, u32 v) {
+    const int i = blockIdx.x * BLOCK + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// Result is in (k1, v1): returns 1, or <0 on a launch error.  hist12 holds 4096 words.
+template <typename K, bool HAS_VAL>
+inline int bucket_sort_large(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_ptr, int n_max, int key_bits,
+                             const SortScratch& sc, u32* hist12, LaunchTimer* lt = nullptr, int tag = 0) {
+    constexpr int R = 1 << BUCKET_LARGE_MSD_BITS;
+    const int low = key_bits - BUCKET_LARGE_MSD_BITS;
+    const int tiles = sort_tiles(n_max, SORT_ITEMS_BIG);
+    fill_u32_kernel<<<R / BLOCK, BLOCK, 0, s>>>(hist12, R, 0u);
+    top_digit_histogram_kernel<K><<<tiles, BLOCK, 0, s>>>(k0, n_ptr, n_max, hist12, low);
+    K* kin = k0;
+    K* kout = k1;
+    u32* vin = v0;
+    u32* vout = v1;
+    for (int half = 0; half < 2; ++half) {
+        const int shift = low + 6 * half;
+        radix_upsweep_kernel<K, SORT_ITEMS_BIG><<<tiles, BLOCK, 0, s>>>(kin, n_ptr, n_max, sc.T, sc.table, shift, 6);
+        radix_scan_kernel<<<64, BLOCK, 0, s>>>(sc.table, sc.totals, n_ptr, n_max, sc.T, BLOCK * SORT_ITEMS_BIG);
+        const bool timed = lt && lt->begin(s, tag);
+        radix_downsweep_kernel<K, HAS_VAL, SORT_ITEMS_BIG>
+            <<<tiles, BLOCK, 0, s>>>(kin, kout, vin, vout, n_ptr, n_max, sc.T, sc.table, sc.totals, shift, 6);
+        if (timed) lt->end(s);
+        K* tk = kin; kin = kout; kout = tk;
+        u32* tv = vin; vin = vout; vout = tv;
+    }
+    // after two passes the partitioned keys are back in (k0, v0)
+    bucket_sort_kernel<K, HAS_VAL, BUCKET_THREADS_4096><<<R, BUCKET_THREADS_4096, 0, s>>>(k0, k1, v0, v1, hist12, R, low);
+    if (hipGetLastError() != hipSuccess) return -1;
+    return 1;
 }
 
 // ---------------------------------------------------------------------------

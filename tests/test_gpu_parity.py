@@ -95,6 +95,11 @@ def _bucket_cases():
     k = np.full(30000, (7 << 20) | 12345, np.uint64)   # all equal: one oversize bucket, stability only
     yield "all_equal", k, 28
     yield "full", rng.integers(0, 1 << 40, size=1 << 20, dtype=np.uint64), 40
+    yield "large4096", rng.integers(0, 1 << 42, size=3000001, dtype=np.uint64), 42
+    k = rng.integers(0, 1 << 30, size=1500000, dtype=np.uint64)
+    k[:200000] &= np.uint64((1 << 18) - 1)     # 200k keys in bucket 0 of 4096: far beyond the LDS capacity
+    rng.shuffle(k)
+    yield "large_skewed", k, 30
 
 
 @pytest.mark.parametrize("name,keys,bits", list(_bucket_cases()), ids=lambda x: x if isinstance(x, str) else "")
