@@ -42,7 +42,7 @@ enum picasso_option {
     PICASSO_OPT_MAX_ROUNDS = 0,    /* stop after this many runs of the core algorithm; <0 = no cap  */
     PICASSO_OPT_STAGE_TIMING = 1,  /* 1: fill picasso_stats.ms_stage with hipEvent times (slower)    */
     PICASSO_OPT_SUBROUND_BATCH = 2,/* selection sub-rounds launched between two host checks         */
-    PICASSO_OPT_KERNEL_TIMING = 3  /* 1: bracket every launch of the edge-key sort's scatter kernel
+    PICASSO_OPT_KERNEL_TIMING = 3  /* 1: bracket the launches of the edge-key sort's main kernel
                                       with hipEvents on `stream` (see picasso_kernel_timing)       */
 };
 
@@ -81,11 +81,12 @@ const char* picasso_strerror(int status);
 const char* picasso_last_hip_error(picasso_ctx* ctx);
 
 /* Totals gathered while PICASSO_OPT_KERNEL_TIMING is on, over all decimate
- * calls since the last reset: launches of the scatter ("downsweep") kernel of
- * the 64-bit edge-key radix sort (Alg. 2 line 1), their summed hipEvent time,
- * and their summed algorithmic bytes (each launch reads and writes every
- * 8-byte key once: 16 bytes x 3 x facets of that round).  Host pointers, may
- * be NULL.  reset != 0 clears the totals after reading. */
+ * calls since the last reset: launches of the main streaming kernel of the
+ * 64-bit edge-key sort (Alg. 2 line 1) -- the per-bucket sort kernel, or the
+ * scatter passes when an input beyond 2^23 keys falls back to plain LSD --,
+ * their summed hipEvent time, and their summed algorithmic bytes (each launch
+ * reads and writes every 8-byte key once: 16 bytes x 3 x facets of that
+ * round).  Host pointers, may be NULL.  reset != 0 clears the totals. */
 int picasso_kernel_timing(picasso_ctx* ctx, int reset, int64_t* launches, double* ms_total, double* bytes_total);
 
 /* Alg. 2 repeated until the vertex budget is met (Sec. 3: "running the core

@@ -184,10 +184,10 @@ class Context:
             raise PicassoError(st, picasso_strerror(st))
 
     def picasso_kernel_timing(self, reset=False):
-        """Totals for the edge-key sort's scatter kernel while PICASSO_OPT_KERNEL_TIMING is on."""
+        """Totals for the edge-key sort's main kernel while PICASSO_OPT_KERNEL_TIMING is on."""
         n, ms, by = ctypes.c_int64(0), ctypes.c_double(0.0), ctypes.c_double(0.0)
         self._lib.picasso_kernel_timing(self._h, int(bool(reset)), ctypes.byref(n), ctypes.byref(ms), ctypes.byref(by))
-        return dict(kernel="radix_downsweep_kernel<u64> (edge-key sort scatter)", launches=n.value, ms_total=ms.value,
+        return dict(kernel="bucket_sort_kernel<u64> (edge-key sort, per-bucket LDS sort)", launches=n.value, ms_total=ms.value,
                     bytes_total=by.value)
 
     def last_hip_error(self) -> str:

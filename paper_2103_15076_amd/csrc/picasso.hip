@@ -11,6 +11,7 @@
 #include <math.h>
 #include <stdint.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <algorithm>
@@ -927,7 +928,7 @@ struct picasso_ctx {
     hipEvent_t ev[2 * PICASSO_STATS_ROUNDS * PICASSO_ST_COUNT + 4];
     int n_ev = 0;
     hipEvent_t ev_total[2];
-    // hipEvent brackets around the edge-key sort's downsweep launches (benchmark roofline)
+    // hipEvent brackets around the edge-key sort's main kernel (benchmark roofline)
     int64_t opt_kernel_timing = 0;
     hipEvent_t kt_pool[512];
     prim::LaunchTimer::Rec kt_recs[256];
@@ -1187,6 +1188,7 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
     int nv_total = N;   // exact (host mirror)
     int nf_bound = F;   // upper bound on the current facet count
     int round = 0;
+    int ne_prev = 0, nv_prev = 0;  // edge and vertex counts of the round before
     bool validated = false;
 
     while (work && (c->opt_max_rounds < 0 || round < c->opt_max_rounds)) {
@@ -1232,12 +1234,16 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         // looks once per batch.
         int launched = 0;
         const int ne_bound = H;  // distinct edges <= half-edges
+        // edges of this round: about half the half-edges at first, later the previous round's
+        // count scaled by the drop in vertices (the facet bound lags one round behind)
         long long live_est = std::max(H / 2, 1);
+        if (round > 0 && ne_prev > 0 && nv_prev > 0)
+            live_est = std::max<long long>(1, std::min<long long>(H, (long long)ne_prev * nv_total / nv_prev * 21 / 20));
         for (;;) {
             // live edges fall by about 2.8x, 2.7x, 3.2x, 4x, 5x, ... per sub-round on meshes with varied costs
             static const int decay_x10[] = {28, 27, 32, 40, 50, 60};
             int wide = 0;
-            for (long long l = live_est; l > TAIL_MAX; l = l * 10 / decay_x10[std::min(wide, 5)]) ++wide;
+            for (long long l = live_est; l > TAIL_MAX; ++wide) l = l * 10 / decay_x10[std::min(wide, 5)];
             wide = std::min<int>(wide, (int)std::max<int64_t>(1, c->opt_subround_batch));
             for (int j = 0; j < wide; ++j)
                 select_subround_kernel<<<grid_for(ne_bound, 1 << 16), BLOCK, 0, s>>>(sa, sel_k + j);
@@ -1256,12 +1262,17 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
             }
             sel_k = hst->sel_k;
             const int live = hst->live[0];
+            if (getenv("PICASSO_DEBUG"))
+                fprintf(stderr, "[picasso] round %d: wide=%d sel_k=%d live=%d ne=%d est=%lld\n", round, wide, sel_k, live,
+                        hst->ne, live_est);
             if (live == 0) break;
             live_est = live;
         }
         for (int b = 0; b < B; ++b) h_matched[b] = c->h_pin[HDR_STATE_INTS + b];
         nf_bound = std::min(nf_bound, hst->nf[cur]);
         nf_round.push_back(hst->nf[cur]);
+        ne_prev = hst->ne;
+        nv_prev = nv_total;
         if (stats && round < PICASSO_STATS_ROUNDS) {
             stats->nv[round] = nv_total;
             stats->nf[round] = hst->nf[cur];
@@ -1353,7 +1364,7 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
     HIP_TRY(c, hipGetLastError());
     const int* h_foff = c->h_pin + HDR_STATE_INTS + c->cap_b;
 
-    // edge-key sort downsweep: one read and one write of every 8-byte key per launch
+    // edge-key sort, main kernel: one read and one write of every 8-byte key per launch
     for (int i = 0; i < c->kt.nrec; ++i) {
         const prim::LaunchTimer::Rec& r = c->kt.recs[i];
         float ms = 0.f;

@@ -224,8 +224,9 @@ struct SortScratch {
     int T;        // row stride = tiles at capacity
 };
 
-// Optional hipEvent bracket around every downsweep launch (for the roofline
-// measurement of the benchmark); `tag` travels to the record.
+// Optional hipEvent bracket around the launches of the sort's main streaming
+// kernel (the per-bucket sort; the scatter passes when plain LSD is used), for
+// the roofline measurement of the benchmark; `tag` travels to the record.
 struct LaunchTimer {
     hipEvent_t* pool = nullptr;
     int cap = 0, used = 0;
@@ -536,12 +537,12 @@ inline int bucket_sort(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int*
     const int tiles = sort_tiles(n_max, SORT_ITEMS_SMALL);
     radix_upsweep_kernel<K, SORT_ITEMS_SMALL><<<tiles, BLOCK, 0, s>>>(k0, n_ptr, n_max, sc.T, sc.table, low, msd);
     radix_scan_kernel<<<1 << msd, BLOCK, 0, s>>>(sc.table, sc.totals, n_ptr, n_max, sc.T, BLOCK * SORT_ITEMS_SMALL);
-    const bool timed = lt && lt->begin(s, tag);
     radix_downsweep_kernel<K, HAS_VAL, SORT_ITEMS_SMALL>
         <<<tiles, BLOCK, 0, s>>>(k0, k1, v0, v1, n_ptr, n_max, sc.T, sc.table, sc.totals, low, msd);
-    if (timed) lt->end(s);
+    const bool timed = lt && lt->begin(s, tag);
     bucket_sort_kernel<K, HAS_VAL, BUCKET_THREADS_256>
         <<<1 << msd, BUCKET_THREADS_256, 0, s>>>(k1, k0, v1, v0, sc.totals, 1 << msd, low);
+    if (timed) lt->end(s);
     if (hipGetLastError() != hipSuccess) return -1;
     return 0;
 }
@@ -599,15 +600,15 @@ inline int bucket_sort_large(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, cons
         const int shift = low + 6 * half;
         radix_upsweep_kernel<K, SORT_ITEMS_BIG><<<tiles, BLOCK, 0, s>>>(kin, n_ptr, n_max, sc.T, sc.table, shift, 6);
         radix_scan_kernel<<<64, BLOCK, 0, s>>>(sc.table, sc.totals, n_ptr, n_max, sc.T, BLOCK * SORT_ITEMS_BIG);
-        const bool timed = lt && lt->begin(s, tag);
         radix_downsweep_kernel<K, HAS_VAL, SORT_ITEMS_BIG>
             <<<tiles, BLOCK, 0, s>>>(kin, kout, vin, vout, n_ptr, n_max, sc.T, sc.table, sc.totals, shift, 6);
-        if (timed) lt->end(s);
         K* tk = kin; kin = kout; kout = tk;
         u32* tv = vin; vin = vout; vout = tv;
     }
     // after two passes the partitioned keys are back in (k0, v0)
+    const bool timed = lt && lt->begin(s, tag);
     bucket_sort_kernel<K, HAS_VAL, BUCKET_THREADS_4096><<<R, BUCKET_THREADS_4096, 0, s>>>(k0, k1, v0, v1, hist12, R, low);
+    if (timed) lt->end(s);
     if (hipGetLastError() != hipSuccess) return -1;
     return 1;
 }
