@@ -13,7 +13,7 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "picasso_oracle.cpp")
+_SRCS = [os.path.join(_HERE, "picasso_oracle.cpp"), os.path.join(_HERE, "picasso_pool_oracle.cpp")]
 _LIB = os.path.join(_HERE, "libpicasso_oracle.so")
 _lib = None
 
@@ -26,9 +26,9 @@ ERR_NONFINITE = -3
 
 def build(force: bool = False) -> str:
     """Compile the oracle with strict IEEE fp32 semantics (no contraction)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(os.path.getmtime(p) for p in _SRCS):
         cmd = ["g++", "-O2", "-std=c++17", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared",
-               "-o", _LIB, _SRC]
+               "-o", _LIB] + _SRCS
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -135,3 +135,55 @@ def decimate_batch(verts, facets, nv_in, nf_in, target_nv):
         return dict(status=st)
     return dict(status=st, verts=vo[: int(nvo.sum())].copy(), facets=fo[: int(nfo.sum())].copy(),
                 cluster_id=cid[:N].copy(), nv=nvo, nf=nfo)
+
+
+# ---- pooling / unpooling over the recorded clusters (Sec. 3, "Pooling and unpooling")
+
+POOL_AVG, POOL_MAX, POOL_WEIGHTED, POOL_SUM = 0, 1, 2, 3
+
+
+def pool_forward(mode, x, cluster_id, n_out, weight=None):
+    """Returns y[n_out, C] (and argmax[n_out, C] for max pooling)."""
+    x, cluster_id = _f32(x), _i32(cluster_id)
+    n_in, C = x.shape
+    y = np.zeros((n_out, C), np.float32)
+    arg = np.full((n_out, C), -1, np.int32)
+    w = _f32(weight) if weight is not None else None
+    st = lib().picasso_oracle_pool_forward(int(mode), _p(x), n_in, C, _p(cluster_id), int(n_out),
+                                           _p(w) if w is not None else None, _p(y), _p(arg))
+    if st != 0:
+        raise ValueError(f"oracle status {st}")
+    return (y, arg) if mode == POOL_MAX else y
+
+
+def pool_backward(mode, gy, cluster_id, n_in, weight=None, argmax=None):
+    gy, cluster_id = _f32(gy), _i32(cluster_id)
+    n_out, C = gy.shape
+    gx = np.zeros((n_in, C), np.float32)
+    w = _f32(weight) if weight is not None else None
+    a = _i32(argmax) if argmax is not None else None
+    st = lib().picasso_oracle_pool_backward(int(mode), _p(gy), int(n_in), C, _p(cluster_id), n_out,
+                                            _p(w) if w is not None else None, _p(a) if a is not None else None, _p(gx))
+    if st != 0:
+        raise ValueError(f"oracle status {st}")
+    return gx
+
+
+def unpool_forward(y, cluster_id):
+    y, cluster_id = _f32(y), _i32(cluster_id)
+    n_out, C = y.shape
+    x = np.zeros((cluster_id.shape[0], C), np.float32)
+    st = lib().picasso_oracle_unpool_forward(_p(y), cluster_id.shape[0], C, _p(cluster_id), n_out, _p(x))
+    if st != 0:
+        raise ValueError(f"oracle status {st}")
+    return x
+
+
+def unpool_backward(gx, cluster_id, n_out):
+    gx, cluster_id = _f32(gx), _i32(cluster_id)
+    n_in, C = gx.shape
+    gy = np.zeros((n_out, C), np.float32)
+    st = lib().picasso_oracle_unpool_backward(_p(gx), n_in, C, _p(cluster_id), int(n_out), _p(gy))
+    if st != 0:
+        raise ValueError(f"oracle status {st}")
+    return gy
