@@ -127,6 +127,50 @@ int picasso_decimate_batch(picasso_ctx* ctx, void* stream, int32_t B, const floa
                            float* d_verts_out, int32_t* d_facets_out, int32_t* d_cluster_id, int32_t* h_nv_out,
                            int32_t* h_nf_out, picasso_stats* stats);
 
+/* ---- pooling / unpooling over the clusters (Sec. 3, "Pooling and unpooling") ----
+ *
+ * The clusters recorded in cluster_id are the pooling neighbourhoods.  Features
+ * are float32 [N, C] row-major device arrays.  Sums run over a cluster's members
+ * in ascending vertex order, left to right in fp32, without fp atomics, so the
+ * results are reproducible to the bit. */
+
+enum picasso_pool_mode {
+    PICASSO_POOL_AVG = 0,      /* y_c = (sum_v x_v) / |c|                                          */
+    PICASSO_POOL_MAX = 1,      /* y_c = max_v x_v per channel; argmax = first member attaining it   */
+    PICASSO_POOL_WEIGHTED = 2, /* y_c = (sum_v w_v x_v) / (sum_v w_v), 0 if the weights sum to 0    */
+    PICASSO_POOL_SUM = 3       /* y_c = sum_v x_v                                                   */
+};
+
+/* Member lists of the clusters: d_offsets [n_out+1], d_members [n_in] (members of
+ * cluster c = d_members[d_offsets[c] .. d_offsets[c+1]), ascending).  Built with a
+ * stable radix sort of (cluster_id, vertex).  Synchronises the stream; returns
+ * PICASSO_ERR_BAD_INDEX if an id lies outside [0, n_out).  n_in <= 3*max_facets
+ * and n_out <= max_verts of the context. */
+int picasso_cluster_csr(picasso_ctx* ctx, void* stream, const int32_t* d_cluster_id, int32_t n_in, int32_t n_out,
+                        int32_t* d_offsets, int32_t* d_members);
+
+/* d_y [n_out, C] = pooled features.  d_weight [n_in] for PICASSO_POOL_WEIGHTED,
+ * else may be NULL.  d_argmax [n_out, C] (vertex index, -1 for an empty cluster)
+ * is written for PICASSO_POOL_MAX when not NULL.  Asynchronous on `stream`. */
+int picasso_pool_forward(picasso_ctx* ctx, void* stream, int mode, const float* d_x, int32_t n_in, int32_t C,
+                         const int32_t* d_offsets, const int32_t* d_members, int32_t n_out, const float* d_weight,
+                         float* d_y, int32_t* d_argmax);
+
+/* d_gx [n_in, C] = gradient with respect to the input features given d_gy
+ * [n_out, C] (the adjoint of the forward pass; weights are constants).
+ * PICASSO_POOL_MAX needs the d_argmax of the forward pass.  Asynchronous. */
+int picasso_pool_backward(picasso_ctx* ctx, void* stream, int mode, const float* d_gy, int32_t n_in, int32_t C,
+                          const int32_t* d_cluster_id, const int32_t* d_offsets, const int32_t* d_members,
+                          int32_t n_out, const float* d_weight, const int32_t* d_argmax, float* d_gx);
+
+/* Unpooling: d_x [n_in, C]: every vertex takes the feature of its cluster
+ * (d_y [n_out, C]).  Its backward pass adds up the gradients of a cluster's
+ * vertices (= PICASSO_POOL_SUM).  Asynchronous. */
+int picasso_unpool_forward(picasso_ctx* ctx, void* stream, const float* d_y, int32_t n_in, int32_t C,
+                           const int32_t* d_cluster_id, float* d_x);
+int picasso_unpool_backward(picasso_ctx* ctx, void* stream, const float* d_gx, int32_t n_in, int32_t C,
+                            const int32_t* d_offsets, const int32_t* d_members, int32_t n_out, float* d_gy);
+
 /* ---- single steps of the path, exported for stage-level parity tests ------- */
 
 /* Vertex quadrics (supplementary, facet and vertex quadric equations):

@@ -33,8 +33,11 @@ EXPORTED_SYMBOLS = (
     "picasso_workspace_bytes", "picasso_create", "picasso_destroy", "picasso_set_option", "picasso_strerror",
     "picasso_last_hip_error", "picasso_decimate", "picasso_decimate_batch", "picasso_vertex_quadrics",
     "picasso_edge_costs", "picasso_radix_sort", "picasso_kernel_timing",
-    "picasso_device_copy", "picasso_bucket_sort",
+    "picasso_device_copy", "picasso_bucket_sort", "picasso_cluster_csr", "picasso_pool_forward",
+    "picasso_pool_backward", "picasso_unpool_forward", "picasso_unpool_backward",
 )
+
+PICASSO_POOL_AVG, PICASSO_POOL_MAX, PICASSO_POOL_WEIGHTED, PICASSO_POOL_SUM = 0, 1, 2, 3
 
 
 class picasso_stats(ctypes.Structure):
@@ -110,6 +113,16 @@ def load_library():
     lib.picasso_device_copy.argtypes = [vp, vp, vp, ctypes.c_size_t]
     lib.picasso_radix_sort.restype = ctypes.c_int
     lib.picasso_radix_sort.argtypes = [vp, vp, ctypes.c_int, vp, vp, i64, ctypes.c_int]
+    lib.picasso_cluster_csr.restype = ctypes.c_int
+    lib.picasso_cluster_csr.argtypes = [vp, vp, vp, i32, i32, vp, vp]
+    lib.picasso_pool_forward.restype = ctypes.c_int
+    lib.picasso_pool_forward.argtypes = [vp, vp, ctypes.c_int, vp, i32, i32, vp, vp, i32, vp, vp, vp]
+    lib.picasso_pool_backward.restype = ctypes.c_int
+    lib.picasso_pool_backward.argtypes = [vp, vp, ctypes.c_int, vp, i32, i32, vp, vp, vp, i32, vp, vp, vp]
+    lib.picasso_unpool_forward.restype = ctypes.c_int
+    lib.picasso_unpool_forward.argtypes = [vp, vp, vp, i32, i32, vp, vp]
+    lib.picasso_unpool_backward.restype = ctypes.c_int
+    lib.picasso_unpool_backward.argtypes = [vp, vp, vp, i32, i32, vp, vp, i32, vp]
     lib.picasso_bucket_sort.restype = ctypes.c_int
     lib.picasso_bucket_sort.argtypes = [vp, vp, ctypes.c_int, vp, vp, i64, ctypes.c_int]
     _lib = lib
@@ -284,6 +297,78 @@ class Context:
         if st != PICASSO_OK:
             self._raise(st)
         return edges[: ne.value], cost[: ne.value]
+
+    # -- pooling / unpooling over cluster_id ------------------------------------------------------
+
+    def picasso_cluster_csr(self, cluster_id, n_out, stream=None):
+        """Returns (offsets int32[n_out+1], members int32[n_in]) device tensors."""
+        import torch
+        n_in = int(cluster_id.shape[0])
+        off = torch.empty((n_out + 1,), dtype=torch.int32, device=cluster_id.device)
+        mem = torch.empty((n_in,), dtype=torch.int32, device=cluster_id.device)
+        st = self._lib.picasso_cluster_csr(self._h, _stream_ptr(stream), _dev_ptr(cluster_id, torch.int32, "cluster_id"),
+                                           n_in, int(n_out), _dev_ptr(off, torch.int32, "off"),
+                                           _dev_ptr(mem, torch.int32, "mem"))
+        if st != PICASSO_OK:
+            self._raise(st)
+        return off, mem
+
+    def picasso_pool_forward(self, mode, x, offsets, members, weight=None, want_argmax=None, stream=None):
+        """Returns y[n_out, C]; for PICASSO_POOL_MAX returns (y, argmax)."""
+        import torch
+        n_in, C = int(x.shape[0]), int(x.shape[1])
+        n_out = int(offsets.shape[0]) - 1
+        y = torch.empty((n_out, C), dtype=torch.float32, device=x.device)
+        if want_argmax is None:
+            want_argmax = mode == PICASSO_POOL_MAX
+        arg = torch.empty((n_out, C), dtype=torch.int32, device=x.device) if want_argmax else None
+        st = self._lib.picasso_pool_forward(self._h, _stream_ptr(stream), int(mode), _dev_ptr(x, torch.float32, "x"),
+                                            n_in, C, _dev_ptr(offsets, torch.int32, "offsets"),
+                                            _dev_ptr(members, torch.int32, "members"), n_out,
+                                            _dev_ptr(weight, torch.float32, "weight"), _dev_ptr(y, torch.float32, "y"),
+                                            _dev_ptr(arg, torch.int32, "argmax"))
+        if st != PICASSO_OK:
+            self._raise(st)
+        return (y, arg) if want_argmax else y
+
+    def picasso_pool_backward(self, mode, gy, cluster_id, offsets, members, weight=None, argmax=None, stream=None):
+        import torch
+        n_in, C = int(cluster_id.shape[0]), int(gy.shape[1])
+        n_out = int(offsets.shape[0]) - 1
+        gx = torch.empty((n_in, C), dtype=torch.float32, device=gy.device)
+        st = self._lib.picasso_pool_backward(self._h, _stream_ptr(stream), int(mode), _dev_ptr(gy, torch.float32, "gy"),
+                                             n_in, C, _dev_ptr(cluster_id, torch.int32, "cluster_id"),
+                                             _dev_ptr(offsets, torch.int32, "offsets"),
+                                             _dev_ptr(members, torch.int32, "members"), n_out,
+                                             _dev_ptr(weight, torch.float32, "weight"),
+                                             _dev_ptr(argmax, torch.int32, "argmax"), _dev_ptr(gx, torch.float32, "gx"))
+        if st != PICASSO_OK:
+            self._raise(st)
+        return gx
+
+    def picasso_unpool_forward(self, y, cluster_id, stream=None):
+        import torch
+        n_in, C = int(cluster_id.shape[0]), int(y.shape[1])
+        x = torch.empty((n_in, C), dtype=torch.float32, device=y.device)
+        st = self._lib.picasso_unpool_forward(self._h, _stream_ptr(stream), _dev_ptr(y, torch.float32, "y"), n_in, C,
+                                              _dev_ptr(cluster_id, torch.int32, "cluster_id"),
+                                              _dev_ptr(x, torch.float32, "x"))
+        if st != PICASSO_OK:
+            self._raise(st)
+        return x
+
+    def picasso_unpool_backward(self, gx, offsets, members, stream=None):
+        import torch
+        n_in, C = int(gx.shape[0]), int(gx.shape[1])
+        n_out = int(offsets.shape[0]) - 1
+        gy = torch.empty((n_out, C), dtype=torch.float32, device=gx.device)
+        st = self._lib.picasso_unpool_backward(self._h, _stream_ptr(stream), _dev_ptr(gx, torch.float32, "gx"), n_in, C,
+                                               _dev_ptr(offsets, torch.int32, "offsets"),
+                                               _dev_ptr(members, torch.int32, "members"), n_out,
+                                               _dev_ptr(gy, torch.float32, "gy"))
+        if st != PICASSO_OK:
+            self._raise(st)
+        return gy
 
     def picasso_bucket_sort(self, keys, vals=None, key_bits=None, stream=None):
         """Same as picasso_radix_sort, by top-digit partition + per-bucket LDS sort (n <= 2^20)."""

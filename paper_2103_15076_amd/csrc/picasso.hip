@@ -20,6 +20,7 @@
 
 #include "../../include/picasso.h"
 #include "primitives.h"
+#include "pooling.h"
 
 #pragma clang fp contract(off)
 
@@ -1589,6 +1590,82 @@ int picasso_edge_costs(picasso_ctx* c, void* stream, const float* d_verts, int32
     HIP_TRY(c, hipGetLastError());
     *h_ne_out = hst->ne;
     return PICASSO_OK;
+}
+
+// ---- pooling / unpooling over cluster_id (Sec. 3, "Pooling and unpooling")
+
+int picasso_cluster_csr(picasso_ctx* c, void* stream, const int32_t* d_cluster_id, int32_t n_in, int32_t n_out,
+                        int32_t* d_offsets, int32_t* d_members) {
+    if (!c || !d_cluster_id || n_in < 1 || n_out < 1 || !d_offsets || !d_members) return PICASSO_ERR_INVALID_ARG;
+    if (n_in > 3 * c->max_facets || n_out > c->max_verts) return PICASSO_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(c, hipSetDevice(c->device));
+    u32* k0 = reinterpret_cast<u32*>(c->key64[0]);
+    u32* k1 = reinterpret_cast<u32*>(c->key64[1]);
+    prim::fill_u32_kernel<<<1, BLOCK, 0, s>>>(reinterpret_cast<u32*>(&c->st->err), 1, 0u);
+    pool::emit_cluster_pairs_kernel<<<pool::grid_for(n_in), pool::BLOCK, 0, s>>>(d_cluster_id, n_in, n_out, k0,
+                                                                                 c->val32[0], &c->st->err);
+    const int where = sort_by_vertex<u32, true>(s, k0, k1, c->val32[0], c->val32[1], nullptr, n_in, ceil_log2(n_out),
+                                                c->sort_sc, c->hist12);
+    if (where < 0) return PICASSO_ERR_HIP;
+    csr_offsets_kernel<<<grid_for(n_in), BLOCK, 0, s>>>(where ? k1 : k0, n_in, n_out, d_offsets);
+    HIP_TRY(c, hipMemcpyAsync(d_members, where ? c->val32[1] : c->val32[0], sizeof(int32_t) * (size_t)n_in,
+                              hipMemcpyDeviceToDevice, s));
+    int rc = read_header(c, s);
+    if (rc != PICASSO_OK) return rc;
+    HIP_TRY(c, hipGetLastError());
+    return (reinterpret_cast<State*>(c->h_pin)->err & 1) ? PICASSO_ERR_BAD_INDEX : PICASSO_OK;
+}
+
+int picasso_pool_forward(picasso_ctx* c, void* stream, int mode, const float* d_x, int32_t n_in, int32_t C,
+                         const int32_t* d_offsets, const int32_t* d_members, int32_t n_out, const float* d_weight,
+                         float* d_y, int32_t* d_argmax) {
+    if (!c || !d_x || !d_offsets || !d_members || !d_y || n_in < 1 || n_out < 1 || C < 1 || mode < 0 || mode > 3 ||
+        (mode == pool::WEIGHTED && !d_weight))
+        return PICASSO_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(c, hipSetDevice(c->device));
+    const bool vec4 = (C % 4 == 0) && (((uintptr_t)d_x | (uintptr_t)d_y) % 16 == 0);
+    if (vec4) pool::launch_pool_forward<4>(s, mode, d_x, C, d_offsets, d_members, n_out, d_weight, d_y, d_argmax);
+    else pool::launch_pool_forward<1>(s, mode, d_x, C, d_offsets, d_members, n_out, d_weight, d_y, d_argmax);
+    HIP_TRY(c, hipGetLastError());
+    return PICASSO_OK;
+}
+
+int picasso_pool_backward(picasso_ctx* c, void* stream, int mode, const float* d_gy, int32_t n_in, int32_t C,
+                          const int32_t* d_cluster_id, const int32_t* d_offsets, const int32_t* d_members,
+                          int32_t n_out, const float* d_weight, const int32_t* d_argmax, float* d_gx) {
+    if (!c || !d_gy || !d_cluster_id || !d_offsets || !d_members || !d_gx || n_in < 1 || n_out < 1 || C < 1 ||
+        mode < 0 || mode > 3 || (mode == pool::WEIGHTED && !d_weight) || (mode == pool::MAX && !d_argmax))
+        return PICASSO_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(c, hipSetDevice(c->device));
+    const bool vec4 = (C % 4 == 0) && (((uintptr_t)d_gy | (uintptr_t)d_gx) % 16 == 0);
+    if (vec4)
+        pool::launch_pool_backward<4>(s, mode, d_gy, n_in, C, d_cluster_id, d_offsets, d_members, d_weight, d_argmax, d_gx);
+    else
+        pool::launch_pool_backward<1>(s, mode, d_gy, n_in, C, d_cluster_id, d_offsets, d_members, d_weight, d_argmax, d_gx);
+    HIP_TRY(c, hipGetLastError());
+    return PICASSO_OK;
+}
+
+int picasso_unpool_forward(picasso_ctx* c, void* stream, const float* d_y, int32_t n_in, int32_t C,
+                           const int32_t* d_cluster_id, float* d_x) {
+    if (!c || !d_y || !d_cluster_id || !d_x || n_in < 1 || C < 1) return PICASSO_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(c, hipSetDevice(c->device));
+    const bool vec4 = (C % 4 == 0) && (((uintptr_t)d_y | (uintptr_t)d_x) % 16 == 0);
+    if (vec4)
+        pool::unpool_forward_kernel<4><<<pool::grid_for((long long)n_in * (C / 4)), pool::BLOCK, 0, s>>>(d_y, n_in, C, d_cluster_id, d_x);
+    else
+        pool::unpool_forward_kernel<1><<<pool::grid_for((long long)n_in * C), pool::BLOCK, 0, s>>>(d_y, n_in, C, d_cluster_id, d_x);
+    HIP_TRY(c, hipGetLastError());
+    return PICASSO_OK;
+}
+
+int picasso_unpool_backward(picasso_ctx* c, void* stream, const float* d_gx, int32_t n_in, int32_t C,
+                            const int32_t* d_offsets, const int32_t* d_members, int32_t n_out, float* d_gy) {
+    return picasso_pool_forward(c, stream, pool::SUM, d_gx, n_in, C, d_offsets, d_members, n_out, nullptr, d_gy, nullptr);
 }
 
 int picasso_bucket_sort(picasso_ctx* c, void* stream, int key_bytes, void* d_keys, uint32_t* d_vals, int64_t n,

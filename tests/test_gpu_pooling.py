@@ -1,0 +1,160 @@
+"""GPU parity of pooling / unpooling over cluster_id (Sec. 3, "Pooling and
+unpooling") against the fp64 oracle.
+
+Bar: max pooling, its argmax, unpooling and every index array bit-exact.  Sums and
+averages: the HIP path adds a cluster's members left to right in fp32, the oracle in
+fp64, so |diff| <= (n + 2) * 2^-24 * sum|terms| / |divisor| for a cluster of n
+members (n - 1 additions, one product per term for weighted pooling, one division);
+the tests compute that bound from the data.
+"""
+import numpy as np
+import pytest
+
+from paper_2103_15076_amd import meshgen
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+U = 2.0 ** -24
+
+
+@pytest.fixture(scope="module")
+def pk():
+    import paper_2103_15076_amd as p
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    p.load_library()
+    return p
+
+
+@pytest.fixture(scope="module")
+def ctx(pk):
+    c = pk.Context(1_300_000, 2_500_000, 16, device=0)
+    yield c
+    c.close()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def _clusters(rng, n_in, n_out, empty=False):
+    cid = rng.integers(0, n_out, size=n_in).astype(np.int32)
+    if not empty:
+        cid[:n_out] = np.arange(n_out)
+        rng.shuffle(cid)
+    return cid
+
+
+def _sum_bound(absx, cid, n_out, divisor):
+    """(n+2) u * sum|x| / |divisor| per cluster and channel."""
+    s = np.zeros((n_out, absx.shape[1]))
+    np.add.at(s, cid, absx.astype(np.float64))
+    n = np.bincount(cid, minlength=n_out).astype(np.float64)
+    d = np.maximum(np.abs(divisor), 1e-30)
+    return (n[:, None] + 2) * U * s / d[:, None] + 1e-45
+
+
+@pytest.mark.parametrize("n_in,n_out,C", [(1, 1, 1), (257, 100, 3), (5000, 1200, 128), (70001, 23456, 20), (4096, 4096, 64)])
+def test_cluster_csr_and_all_ops(pk, ctx, oracle, n_in, n_out, C):
+    rng = np.random.default_rng(n_in + C)
+    cid = _clusters(rng, n_in, n_out)
+    x = (rng.normal(size=(n_in, C)) * 3).astype(np.float32)
+    w = rng.uniform(0.1, 2.0, size=n_in).astype(np.float32)
+    g = rng.normal(size=(n_out, C)).astype(np.float32)
+    dcid, dx, dw, dg = dev(cid), dev(x), dev(w), dev(g)
+    print(f"pool n_in={n_in} n_out={n_out} C={C}", flush=True)
+    off, mem = ctx.picasso_cluster_csr(dcid, n_out)
+    off_h, mem_h = off.cpu().numpy(), mem.cpu().numpy()
+    # CSR: exact
+    order = np.argsort(cid, kind="stable")
+    assert np.array_equal(mem_h, order.astype(np.int32))
+    assert np.array_equal(off_h, np.concatenate([[0], np.cumsum(np.bincount(cid, minlength=n_out))]).astype(np.int32))
+    sizes = np.bincount(cid, minlength=n_out).astype(np.float64)
+
+    # forward
+    y_avg = ctx.picasso_pool_forward(pk.PICASSO_POOL_AVG, dx, off, mem).cpu().numpy()
+    ref = oracle.pool_forward(oracle.POOL_AVG, x, cid, n_out)
+    assert np.all(np.abs(y_avg.astype(np.float64) - ref) <= _sum_bound(np.abs(x), cid, n_out, sizes) + U * np.abs(ref))
+    y_sum = ctx.picasso_pool_forward(pk.PICASSO_POOL_SUM, dx, off, mem).cpu().numpy()
+    ref = oracle.pool_forward(oracle.POOL_SUM, x, cid, n_out)
+    assert np.all(np.abs(y_sum.astype(np.float64) - ref) <= _sum_bound(np.abs(x), cid, n_out, np.ones(n_out)) + U * np.abs(ref))
+    y_w = ctx.picasso_pool_forward(pk.PICASSO_POOL_WEIGHTED, dx, off, mem, weight=dw).cpu().numpy()
+    ref = oracle.pool_forward(oracle.POOL_WEIGHTED, x, cid, n_out, w)
+    wsum = np.zeros(n_out)
+    np.add.at(wsum, cid, w.astype(np.float64))
+    assert np.all(np.abs(y_w.astype(np.float64) - ref) <= 2 * _sum_bound(np.abs(x * w[:, None]), cid, n_out, wsum) + 4 * U * np.abs(ref))
+    y_max, arg = ctx.picasso_pool_forward(pk.PICASSO_POOL_MAX, dx, off, mem)
+    rmax, rarg = oracle.pool_forward(oracle.POOL_MAX, x, cid, n_out)
+    assert np.array_equal(y_max.cpu().numpy().view(np.uint32), rmax.view(np.uint32))
+    assert np.array_equal(arg.cpu().numpy(), rarg)
+
+    # unpool forward / backward
+    up = ctx.picasso_unpool_forward(dg, dcid).cpu().numpy()
+    assert np.array_equal(up.view(np.uint32), oracle.unpool_forward(g, cid).view(np.uint32))
+    ub = ctx.picasso_unpool_backward(dx, off, mem).cpu().numpy()
+    assert np.array_equal(ub.view(np.uint32), y_sum.view(np.uint32))       # same kernel as sum pooling
+
+    # backward
+    gx = ctx.picasso_pool_backward(pk.PICASSO_POOL_AVG, dg, dcid, off, mem).cpu().numpy()
+    ref = oracle.pool_backward(oracle.POOL_AVG, g, cid, n_in)
+    assert np.all(np.abs(gx.astype(np.float64) - ref) <= 2 * U * np.abs(ref) + 1e-45)
+    gx = ctx.picasso_pool_backward(pk.PICASSO_POOL_MAX, dg, dcid, off, mem, argmax=arg).cpu().numpy()
+    assert np.array_equal(gx.view(np.uint32), oracle.pool_backward(oracle.POOL_MAX, g, cid, n_in, argmax=rarg).view(np.uint32))
+    gx = ctx.picasso_pool_backward(pk.PICASSO_POOL_WEIGHTED, dg, dcid, off, mem, weight=dw).cpu().numpy()
+    ref = oracle.pool_backward(oracle.POOL_WEIGHTED, g, cid, n_in, weight=w)
+    nmax = sizes.max()
+    assert np.all(np.abs(gx.astype(np.float64) - ref) <= (nmax + 4) * U * np.abs(ref) + 1e-45)
+
+
+def test_empty_clusters_ties_and_unaligned_channels(pk, ctx, oracle):
+    rng = np.random.default_rng(9)
+    n_in, n_out, C = 300, 200, 5            # C not a multiple of 4: scalar path; many empty clusters
+    cid = _clusters(rng, n_in, n_out, empty=True)
+    x = rng.integers(-2, 3, size=(n_in, C)).astype(np.float32)   # many exact ties for the argmax rule
+    off, mem = ctx.picasso_cluster_csr(dev(cid), n_out)
+    y, arg = ctx.picasso_pool_forward(pk.PICASSO_POOL_MAX, dev(x), off, mem)
+    ry, rarg = oracle.pool_forward(oracle.POOL_MAX, x, cid, n_out)
+    assert np.array_equal(y.cpu().numpy(), ry) and np.array_equal(arg.cpu().numpy(), rarg)
+    ya = ctx.picasso_pool_forward(pk.PICASSO_POOL_AVG, dev(x), off, mem).cpu().numpy()
+    np.testing.assert_allclose(ya, oracle.pool_forward(oracle.POOL_AVG, x, cid, n_out), rtol=1e-6, atol=1e-6)
+    w = np.zeros(n_in, np.float32)          # all weights zero: defined as 0
+    yw = ctx.picasso_pool_forward(pk.PICASSO_POOL_WEIGHTED, dev(x), off, mem, weight=dev(w)).cpu().numpy()
+    assert not yw.any()
+
+
+def test_bad_cluster_ids_are_rejected(pk, ctx):
+    cid = np.array([0, 1, 5, 2], np.int32)
+    with pytest.raises(pk.PicassoError) as e:
+        ctx.picasso_cluster_csr(dev(cid), 3)
+    assert e.value.status == pk.PICASSO_ERR_BAD_INDEX
+    off, mem = ctx.picasso_cluster_csr(dev(np.array([0, 1, 2, 2], np.int32)), 3)   # context still usable
+    assert off.cpu().numpy().tolist() == [0, 1, 2, 4]
+
+
+def test_pooling_after_decimation_room_mesh(pk, ctx, oracle):
+    """The real pipeline: decimate, then pool 128-channel features over the recorded clusters."""
+    c = meshgen.config("room115k")
+    V, F = c["verts"], c["facets"]
+    st, vo, fo, cid = ctx.picasso_decimate(dev(V), dev(F), int(c["target"][0]))
+    n_out = vo.shape[0]
+    rng = np.random.default_rng(1)
+    x = rng.normal(size=(V.shape[0], 128)).astype(np.float32)
+    off, mem = ctx.picasso_cluster_csr(cid.contiguous(), n_out)
+    cid_h = cid.cpu().numpy()
+    y, arg = ctx.picasso_pool_forward(pk.PICASSO_POOL_MAX, dev(x), off, mem)
+    ry, rarg = oracle.pool_forward(oracle.POOL_MAX, x, cid_h, n_out)
+    assert np.array_equal(y.cpu().numpy(), ry) and np.array_equal(arg.cpu().numpy(), rarg)
+    ya = ctx.picasso_pool_forward(pk.PICASSO_POOL_AVG, dev(x), off, mem).cpu().numpy()
+    sizes = np.bincount(cid_h, minlength=n_out).astype(np.float64)
+    ref = oracle.pool_forward(oracle.POOL_AVG, x, cid_h, n_out)
+    assert np.all(np.abs(ya.astype(np.float64) - ref) <= _sum_bound(np.abs(x), cid_h, n_out, sizes) + U * np.abs(ref))
+    # average pooling of the positions over ONE round's clusters is the contraction itself
+    ctx.set_option(pk.PICASSO_OPT_MAX_ROUNDS, 1)
+    try:
+        st, vo1, fo1, cid1 = ctx.picasso_decimate(dev(V), dev(F), 1)
+    finally:
+        ctx.set_option(pk.PICASSO_OPT_MAX_ROUNDS, -1)
+    off1, mem1 = ctx.picasso_cluster_csr(cid1.contiguous(), vo1.shape[0])
+    Vp = np.concatenate([V, np.zeros((V.shape[0], 1), np.float32)], axis=1)      # 4 channels
+    pos = ctx.picasso_pool_forward(pk.PICASSO_POOL_AVG, dev(Vp), off1, mem1).cpu().numpy()[:, :3]
+    np.testing.assert_allclose(pos, vo1.cpu().numpy(), rtol=0, atol=2e-6)
