@@ -36,6 +36,8 @@ def main():
                     help="leave out the per-launch hipEvents of the roofline measurement")
     ap.add_argument("--copy-calib", action="store_true",
                     help="only run the plain copy kernel on 1 GiB (HBM yardstick / counter calibration)")
+    ap.add_argument("--pool", type=int, default=0, metavar="C",
+                    help="also time pooling/unpooling of C-channel features over the recorded clusters")
     ap.add_argument("--stages", action="store_true", help="also print per-stage times to stderr")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -152,6 +154,42 @@ def main():
                         "sample": f"the full workload, median of {reps} runs ({med * 1e3:.1f} ms per decimation)",
                         "ms_per_decimation": round(med * 1e3, 2), "gpu_matches_oracle_bit_exact": bool(same)}
 
+    pooling = None
+    if args.pool:
+        # pooling / unpooling of C-channel features over the clusters just recorded (network-style use)
+        C = args.pool
+        n_out = nv_out
+        x = torch.randn((N, C), device=dev, dtype=torch.float32)
+        g = torch.randn((n_out, C), device=dev, dtype=torch.float32)
+        cid_c = res[3].contiguous()
+
+        def timed(fn, reps=20):
+            for _ in range(3):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(reps):
+                fn()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+
+        t_csr = timed(lambda: ctx.picasso_cluster_csr(cid_c, n_out))
+        off, mem = ctx.picasso_cluster_csr(cid_c, n_out)
+        _, arg = ctx.picasso_pool_forward(pk.PICASSO_POOL_MAX, x, off, mem)
+        rows = {
+            "max_forward": (lambda: ctx.picasso_pool_forward(pk.PICASSO_POOL_MAX, x, off, mem), 4 * C * (N + 2 * n_out) + 8 * N),
+            "avg_forward": (lambda: ctx.picasso_pool_forward(pk.PICASSO_POOL_AVG, x, off, mem), 4 * C * (N + n_out) + 8 * N),
+            "max_backward": (lambda: ctx.picasso_pool_backward(pk.PICASSO_POOL_MAX, g, cid_c, off, mem, argmax=arg), 4 * C * (N + 2 * n_out) + 4 * N),
+            "unpool_forward": (lambda: ctx.picasso_unpool_forward(g, cid_c), 4 * C * (N + n_out) + 4 * N),
+            "unpool_backward": (lambda: ctx.picasso_unpool_backward(x, off, mem), 4 * C * (N + n_out) + 8 * N),
+        }
+        pooling = {"channels": C, "n_in": N, "n_out": n_out, "cluster_csr_ms": round(t_csr, 4)}
+        for name, (fn, nbytes) in rows.items():
+            ms = timed(fn)
+            pooling[name] = {"ms": round(ms, 4), "algorithmic_MB": round(nbytes / 1e6, 2),
+                             "GBps": round(nbytes / ms / 1e6, 1), "frac_of_8TBps": round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 4)}
+
     out = {
         "metric": "input facets/s per decimation (ms per decimation in ms_per_step)",
         "value": round(NF / (ms_per_step * 1e-3), 1),
@@ -169,6 +207,8 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
     }
+    if pooling is not None:
+        out["pooling"] = pooling
     print(json.dumps(out))
     ctx.close()
 
