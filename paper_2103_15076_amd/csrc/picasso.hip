@@ -142,14 +142,16 @@ struct Quadric10 {
     float q[10];
 };
 
-__device__ __forceinline__ Quadric10 facet_quadric(const VRec* __restrict__ vrec, int i0, int i1, int i2) {
+// Positions come from the caller's packed [N,3] array (12-byte stride), not from the 64-byte
+// vertex records: the three gathers per incidence then touch five times fewer cache lines.
+__device__ __forceinline__ Quadric10 facet_quadric(const float* __restrict__ verts, int i0, int i1, int i2) {
     Quadric10 Q;
 #pragma unroll
     for (int k = 0; k < 10; ++k) Q.q[k] = 0.0f;
     if (i0 == i1 || i1 == i2 || i0 == i2) return Q;
-    const float4 p0 = *reinterpret_cast<const float4*>(&vrec[i0]);
-    const float4 p1 = *reinterpret_cast<const float4*>(&vrec[i1]);
-    const float4 p2 = *reinterpret_cast<const float4*>(&vrec[i2]);
+    const float3 p0 = make_float3(verts[3 * (size_t)i0], verts[3 * (size_t)i0 + 1], verts[3 * (size_t)i0 + 2]);
+    const float3 p1 = make_float3(verts[3 * (size_t)i1], verts[3 * (size_t)i1 + 1], verts[3 * (size_t)i1 + 2]);
+    const float3 p2 = make_float3(verts[3 * (size_t)i2], verts[3 * (size_t)i2 + 1], verts[3 * (size_t)i2 + 2]);
     float ax = p1.x - p0.x, ay = p1.y - p0.y, az = p1.z - p0.z;
     float bx = p2.x - p0.x, by = p2.y - p0.y, bz = p2.z - p0.z;
     float nx = ay * bz - az * by;
@@ -170,7 +172,8 @@ __device__ __forceinline__ Quadric10 facet_quadric(const VRec* __restrict__ vrec
 
 // Ordered segmented reduction: one lane per vertex walks its CSR row in
 // ascending incidence order and adds the facet quadrics left to right.
-__global__ __launch_bounds__(BLOCK) void quadric_reduce_kernel(VRec* __restrict__ vrec, int N,
+__global__ __launch_bounds__(BLOCK) void quadric_reduce_kernel(VRec* __restrict__ vrec,
+                                                               const float* __restrict__ verts, int N,
                                                                const int* __restrict__ fcur,
                                                                const int* __restrict__ off,
                                                                const u32* __restrict__ inc) {
@@ -183,7 +186,7 @@ __global__ __launch_bounds__(BLOCK) void quadric_reduce_kernel(VRec* __restrict_
         const int s = off[w], e = off[w + 1];
         for (int j = s; j < e; ++j) {
             const int f = (int)(inc[j] / 3u);
-            const Quadric10 Q = facet_quadric(vrec, fcur[3 * (size_t)f], fcur[3 * (size_t)f + 1], fcur[3 * (size_t)f + 2]);
+            const Quadric10 Q = facet_quadric(verts, fcur[3 * (size_t)f], fcur[3 * (size_t)f + 1], fcur[3 * (size_t)f + 2]);
 #pragma unroll
             for (int k = 0; k < 10; ++k) acc[k] = acc[k] + Q.q[k];
         }
@@ -1070,7 +1073,7 @@ int sort_by_vertex(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_p
 }
 
 // S0 on the data already validated into the workspace by init_kernel.
-int run_vertex_quadrics(picasso_ctx* c, hipStream_t s, int N, int F) {
+int run_vertex_quadrics(picasso_ctx* c, hipStream_t s, const float* d_verts, int N, int F) {
     const int H = 3 * F;
     u32* k0 = reinterpret_cast<u32*>(c->key64[0]);
     u32* k1 = reinterpret_cast<u32*>(c->key64[1]);
@@ -1080,9 +1083,9 @@ int run_vertex_quadrics(picasso_ctx* c, hipStream_t s, int N, int F) {
         const u32* skey = where ? k1 : k0;
         const u32* sval = where ? c->val32[1] : c->val32[0];
         csr_offsets_kernel<<<grid_for(H), BLOCK, 0, s>>>(skey, H, N, c->csr_off);
-        quadric_reduce_kernel<<<grid_for(N), BLOCK, 0, s>>>(c->vrec[0], N, c->fbuf[0], c->csr_off, sval);
+        quadric_reduce_kernel<<<grid_for(N), BLOCK, 0, s>>>(c->vrec[0], d_verts, N, c->fbuf[0], c->csr_off, sval);
     } else {
-        quadric_reduce_kernel<<<grid_for(N), BLOCK, 0, s>>>(c->vrec[0], N, c->fbuf[0], nullptr, nullptr);
+        quadric_reduce_kernel<<<grid_for(N), BLOCK, 0, s>>>(c->vrec[0], d_verts, N, c->fbuf[0], nullptr, nullptr);
     }
     return PICASSO_OK;
 }
@@ -1177,7 +1180,7 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         d_verts, N, d_facets, F, B, c->voff[0], c->foff, c->vrec[0], c->cid, c->fbuf[0],
         work ? reinterpret_cast<u32*>(c->key64[0]) : nullptr, c->val32[0], c->st);
     if (work) {
-        rc = run_vertex_quadrics(c, s, N, F);
+        rc = run_vertex_quadrics(c, s, d_verts, N, F);
         if (rc != PICASSO_OK) return rc;
     }
     tm.end();
@@ -1536,7 +1539,7 @@ int picasso_vertex_quadrics(picasso_ctx* c, void* stream, const float* d_verts, 
     if (rc != PICASSO_OK) return rc;
     rc = status_from_err_bits(hst->err);
     if (rc != PICASSO_OK) return rc;
-    rc = run_vertex_quadrics(c, s, N, F);
+    rc = run_vertex_quadrics(c, s, d_verts, N, F);
     if (rc != PICASSO_OK) return rc;
     export_quadrics_kernel<<<grid_for(N), BLOCK, 0, s>>>(c->vrec[0], N, d_quadrics_out);
     HIP_TRY(c, hipStreamSynchronize(s));
@@ -1564,7 +1567,7 @@ int picasso_edge_costs(picasso_ctx* c, void* stream, const float* d_verts, int32
     if (rc != PICASSO_OK) return rc;
     rc = status_from_err_bits(hst->err);
     if (rc != PICASSO_OK) return rc;
-    rc = run_vertex_quadrics(c, s, N, F);
+    rc = run_vertex_quadrics(c, s, d_verts, N, F);
     if (rc != PICASSO_OK) return rc;
     const int vbits = ceil_log2(N), H = 3 * F;
     MeshTab mt{1, c->voff[0], c->target, c->active, c->nrem, c->matched, c->mslots};

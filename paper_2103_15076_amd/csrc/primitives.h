@@ -305,9 +305,10 @@ inline int radix_sort(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* 
 // (a very uneven key distribution) is sorted by the same workgroup with a slow
 // pass-by-pass LSD over global memory, so the result is always correct.
 // ---------------------------------------------------------------------------
-constexpr int BUCKET_ITEMS = 8;
-constexpr int BUCKET_THREADS_256 = 1024;  // 256 buckets: up to 8192 keys of a bucket held in LDS
-constexpr int BUCKET_THREADS_4096 = 512;  // 4096 buckets: up to 4096 keys
+constexpr int BUCKET_THREADS_256 = 1024;  // 256 buckets: 8 keys per lane, up to 8192 keys of a bucket held in LDS
+constexpr int BUCKET_THREADS_4096 = 512;  // 4096 buckets: up to 4096 keys (8 per lane), or 8192 key-value
+                                          // pairs (16 per lane: vertex incidences run to ~6 per vertex and
+                                          // vertex ids need not fill their bit range, so those buckets run fuller)
 constexpr int BUCKET_MSD_BITS = 8;
 constexpr long long BUCKET_SORT_MAX_KEYS = 1ll << 20;  // average bucket <= half of what LDS holds
 
@@ -406,7 +407,7 @@ __device__ void bucket_sort_oversize(K* a, K* b, u32* va, u32* vb, int cnt, int 
 // One workgroup per bucket.  kin/vin hold the keys partitioned by their top
 // digit (bucket d occupies [start_d, start_d + totals[d])); the sorted bucket is
 // written to the same range of kout/vout.  low_bits = key bits below the digit.
-template <typename K, bool HAS_VAL, int BUCKET_THREADS>
+template <typename K, bool HAS_VAL, int BUCKET_THREADS, int BUCKET_ITEMS>
 __global__ __launch_bounds__(BUCKET_THREADS) void bucket_sort_kernel(K* __restrict__ kin, K* __restrict__ kout,
                                                                      u32* __restrict__ vin, u32* __restrict__ vout,
                                                                      const u32* __restrict__ totals, int nbuckets,
@@ -540,7 +541,7 @@ inline int bucket_sort(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int*
     radix_downsweep_kernel<K, HAS_VAL, SORT_ITEMS_SMALL>
         <<<tiles, BLOCK, 0, s>>>(k0, k1, v0, v1, n_ptr, n_max, sc.T, sc.table, sc.totals, low, msd);
     const bool timed = lt && lt->begin(s, tag);
-    bucket_sort_kernel<K, HAS_VAL, BUCKET_THREADS_256>
+    bucket_sort_kernel<K, HAS_VAL, BUCKET_THREADS_256, 8>
         <<<1 << msd, BUCKET_THREADS_256, 0, s>>>(k1, k0, v1, v0, sc.totals, 1 << msd, low);
     if (timed) lt->end(s);
     if (hipGetLastError() != hipSuccess) return -1;
@@ -607,7 +608,8 @@ inline int bucket_sort_large(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, cons
     }
     // after two passes the partitioned keys are back in (k0, v0)
     const bool timed = lt && lt->begin(s, tag);
-    bucket_sort_kernel<K, HAS_VAL, BUCKET_THREADS_4096><<<R, BUCKET_THREADS_4096, 0, s>>>(k0, k1, v0, v1, hist12, R, low);
+    bucket_sort_kernel<K, HAS_VAL, BUCKET_THREADS_4096, (HAS_VAL ? 16 : 8)>
+        <<<R, BUCKET_THREADS_4096, 0, s>>>(k0, k1, v0, v1, hist12, R, low);
     if (timed) lt->end(s);
     if (hipGetLastError() != hipSuccess) return -1;
     return 1;
