@@ -96,6 +96,12 @@ def main():
         step()
     torch.cuda.synchronize()
 
+    # The collector is held off while timing (as timeit does): a full collection of this process
+    # (torch, numpy and the mesh arrays alive) takes ~40 ms, two orders above one step.
+    import gc
+    gc.collect()
+    gc.disable()
+
     # ---- timed region: exactly K steps, hipEvents on the launch stream + wall clock
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     ctx.set_option(pk.PICASSO_OPT_KERNEL_TIMING, 0 if args.no_kernel_events else 1)
@@ -111,6 +117,7 @@ def main():
     ev_ms = ev0.elapsed_time(ev1)
     ms_per_step = max(wall_ms, ev_ms) / args.steps
     nv_out, nf_out = int(res[1].shape[0]), int(res[2].shape[0])
+    gc.enable()
     kt = ctx.picasso_kernel_timing(reset=True)   # hipEvents around every launch of the dominant kernel, inside the timed region
 
     # ---- one extra call for the per-round shape and stage times
