@@ -31,6 +31,13 @@ def ctx(pk):
     c.close()
 
 
+@pytest.fixture(scope="module")
+def ctx16k(pk):
+    c = pk.Context(200_000, 400_000, 64, device=0)
+    yield c
+    c.close()
+
+
 def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
 
@@ -199,6 +206,68 @@ def test_adversarial_small_meshes(ctx, oracle):
         print(f"adversarial {name}", flush=True)
         st, vo, fo, cid = ctx.picasso_decimate(dev(V), dev(F), target)
         assert_same_result(st, vo, fo, cid, oracle.decimate(V, F, target))
+
+
+def test_hub_vertices_and_uneven_buckets_in_the_pipeline(ctx, oracle):
+    """Meshes whose keys are NOT evenly spread: a fan around one hub vertex (its incidences and
+    edges all fall into one sort bucket, far more than LDS holds) and a mesh whose vertex count
+    is just above a power of two (half of the id range empty)."""
+    rng = np.random.default_rng(21)
+    # fan: hub 0 joined to a ring of 30000 vertices, plus a noisy grid glued on
+    n = 30000
+    ang = np.linspace(0, 2 * np.pi, n, endpoint=False)
+    ring = np.stack([np.cos(ang), np.sin(ang), 0.05 * rng.normal(size=n)], 1)
+    V = np.concatenate([[[0, 0, 0.3]], ring]).astype(np.float32)
+    F = np.stack([np.zeros(n, np.int64), 1 + np.arange(n), 1 + (np.arange(n) + 1) % n], 1).astype(np.int32)
+    Vg, Fg = meshgen.noisy_grid(40, 40, seed=6)
+    V2 = np.concatenate([V, Vg + np.float32([3, 0, 0])]).astype(np.float32)
+    F2 = np.concatenate([F, Fg + V.shape[0]]).astype(np.int32)
+    for target in (V2.shape[0] // 2, V2.shape[0] // 7):
+        print(f"hub fan N={V2.shape[0]} target={target}", flush=True)
+        st, vo, fo, cid = ctx.picasso_decimate(dev(V2), dev(F2), target)
+        assert_same_result(st, vo, fo, cid, oracle.decimate(V2, F2, target))
+    # hub as the LAST vertex (it is the larger end of every edge)
+    perm = np.arange(V.shape[0])[::-1].copy()
+    inv = np.empty_like(perm)
+    inv[perm] = np.arange(perm.size)
+    V3, F3 = V[perm], inv[F].astype(np.int32)
+    st, vo, fo, cid = ctx.picasso_decimate(dev(V3), dev(F3), 5000)
+    assert_same_result(st, vo, fo, cid, oracle.decimate(V3, F3, 5000))
+    # vertex count just above a power of two
+    Vp, Fp = meshgen.noisy_grid(257, 256, seed=8)     # 65792 = 2^16 + 256
+    st, vo, fo, cid = ctx.picasso_decimate(dev(Vp), dev(Fp), 20000)
+    assert_same_result(st, vo, fo, cid, oracle.decimate(Vp, Fp, 20000))
+
+
+def test_batch_of_many_small_meshes(ctx16k, oracle):
+    """64 meshes of different kinds and sizes in one call, budgets from 'nothing to do' to 'to one vertex'."""
+    rng = np.random.default_rng(33)
+    parts, tg = [], []
+    for b in range(64):
+        kind = b % 4
+        if kind == 0:
+            p = meshgen.noisy_grid(int(rng.integers(3, 30)), int(rng.integers(3, 30)), seed=100 + b)
+        elif kind == 1:
+            p = meshgen.icosphere(int(rng.integers(0, 4)), seed=100 + b)
+        elif kind == 2:
+            p = meshgen.flat_grid(int(rng.integers(2, 20)), int(rng.integers(2, 20)))
+        else:
+            p = meshgen.room_scene(100 + b, room=(1.0, 1.0, 0.5), n_boxes=1, spacing=0.1)
+        parts.append(p)
+        n = p[0].shape[0]
+        tg.append(int(max(1, [n, n - 1, n // 2, n // 5, 1][b % 5])))
+    nv = [p[0].shape[0] for p in parts]
+    nf = [p[1].shape[0] for p in parts]
+    off = np.cumsum([0] + nv)
+    V = np.concatenate([p[0] for p in parts])
+    F = np.concatenate([p[1] + off[i] for i, p in enumerate(parts)]).astype(np.int32)
+    st, vo, fo, cid, nvo, nfo = ctx16k.picasso_decimate_batch(dev(V), dev(F), nv, nf, tg)
+    ref = oracle.decimate_batch(V, F, nv, nf, tg)
+    assert st == ref["status"]
+    assert nvo.tolist() == ref["nv"].tolist() and nfo.tolist() == ref["nf"].tolist()
+    assert np.array_equal(cid.cpu().numpy(), ref["cluster_id"])
+    assert np.array_equal(fo.cpu().numpy(), ref["facets"])
+    assert np.array_equal(vo.cpu().numpy().view(np.uint32), ref["verts"].view(np.uint32))
 
 
 def test_zero_rounds_copies_input(ctx):
