@@ -39,6 +39,8 @@ def main():
     ap.add_argument("--pool", type=int, default=0, metavar="C",
                     help="also time pooling/unpooling of C-channel features over the recorded clusters")
     ap.add_argument("--stages", action="store_true", help="also print per-stage times to stderr")
+    ap.add_argument("--single-stream", action="store_true",
+                    help="keep the first round's edge sort on the caller's stream (PICASSO_OPT_OVERLAP = 0)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures ONE GPU only (the path shards by mesh; see DESIGN.md); "
@@ -105,6 +107,8 @@ def main():
     # ---- timed region: exactly K steps, hipEvents on the launch stream + wall clock
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     ctx.set_option(pk.PICASSO_OPT_KERNEL_TIMING, 0 if args.no_kernel_events else 1)
+    if args.single_stream:
+        ctx.set_option(pk.PICASSO_OPT_OVERLAP, 0)
     ctx.picasso_kernel_timing(reset=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()

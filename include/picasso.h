@@ -12,7 +12,8 @@
  *     On error no output buffer has been written.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  The
  *     decimate calls synchronise that stream before they return.
- *   - A context owns its scratch workspace and is bound to one device; calls
+ *   - A context owns its scratch workspace (and one internal stream of default
+ *     priority) and is bound to one device, which the calls make current; calls
  *     on one context must not overlap in time.  Inputs are never modified.
  *   - Nothing is allocated inside the decimate calls.
  */
@@ -42,8 +43,12 @@ enum picasso_option {
     PICASSO_OPT_MAX_ROUNDS = 0,    /* stop after this many runs of the core algorithm; <0 = no cap  */
     PICASSO_OPT_STAGE_TIMING = 1,  /* 1: fill picasso_stats.ms_stage with hipEvent times (slower)    */
     PICASSO_OPT_SUBROUND_BATCH = 2,/* selection sub-rounds launched between two host checks         */
-    PICASSO_OPT_KERNEL_TIMING = 3  /* 1: bracket the launches of the edge-key sort's main kernel
-                                      with hipEvents on `stream` (see picasso_kernel_timing)       */
+    PICASSO_OPT_KERNEL_TIMING = 3, /* 1: bracket the launches of the edge-key sort's main kernel
+                                      with hipEvents (see picasso_kernel_timing)                   */
+    PICASSO_OPT_OVERLAP = 4        /* 1 (default): for inputs of 2^18 facets or more, the first
+                                      round's edge-key sort runs on a stream of the context's own
+                                      beside the vertex quadrics and joins `stream` before costs
+                                      are computed; 0: everything on `stream`                      */
 };
 
 #define PICASSO_STATS_ROUNDS 32

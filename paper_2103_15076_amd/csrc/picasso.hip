@@ -913,6 +913,15 @@ struct picasso_ctx {
     int* tilesum = nullptr;
     prim::SortScratch sort_sc{};
     u32* hist12 = nullptr;  // bucket sizes of the 4096-bucket sort
+    // The vertex->facet sort has buffers and scratch of its own, so that in the first round it can
+    // run beside the edge-key sort (neither depends on the other) on a second stream.
+    u32* s0_key[2] = {nullptr, nullptr};
+    u32* s0_val[2] = {nullptr, nullptr};
+    prim::SortScratch sort_sc_s0{};
+    u32* hist12_s0 = nullptr;
+    hipStream_t side = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    int64_t opt_overlap = 1;
     // per-mesh tables
     int* voff[2] = {nullptr, nullptr};
     int* foff = nullptr;
@@ -1013,6 +1022,14 @@ size_t carve(picasso_ctx* c, char* base, int64_t N, int64_t F, int32_t B) {
     x->sort_sc.table = cv.take<u32>((size_t)256 * x->sort_sc.T);
     x->sort_sc.totals = cv.take<u32>(256);
     x->hist12 = cv.take<u32>(4096);
+    for (int i = 0; i < 2; ++i) {
+        x->s0_key[i] = cv.take<u32>(h);
+        x->s0_val[i] = cv.take<u32>(h);
+    }
+    x->sort_sc_s0.T = x->sort_sc.T;
+    x->sort_sc_s0.table = cv.take<u32>((size_t)256 * x->sort_sc_s0.T);
+    x->sort_sc_s0.totals = cv.take<u32>(256);
+    x->hist12_s0 = cv.take<u32>(4096);
     x->voff[1] = cv.take<int>(b + 1);
     x->nrem = cv.take<int>(b);
     x->segstart = cv.take<int>(b);
@@ -1073,15 +1090,18 @@ int sort_by_vertex(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_p
 }
 
 // S0 on the data already validated into the workspace by init_kernel.
+constexpr int64_t OVERLAP_MIN_FACETS = 1 << 18;
+
 int run_vertex_quadrics(picasso_ctx* c, hipStream_t s, const float* d_verts, int N, int F) {
     const int H = 3 * F;
-    u32* k0 = reinterpret_cast<u32*>(c->key64[0]);
-    u32* k1 = reinterpret_cast<u32*>(c->key64[1]);
+    u32* k0 = c->s0_key[0];
+    u32* k1 = c->s0_key[1];
     if (F > 0) {
-        int where = sort_by_vertex<u32, true>(s, k0, k1, c->val32[0], c->val32[1], nullptr, H, ceil_log2(N), c->sort_sc, c->hist12);
+        int where = sort_by_vertex<u32, true>(s, k0, k1, c->s0_val[0], c->s0_val[1], nullptr, H, ceil_log2(N),
+                                              c->sort_sc_s0, c->hist12_s0);
         if (where < 0) return PICASSO_ERR_HIP;
         const u32* skey = where ? k1 : k0;
-        const u32* sval = where ? c->val32[1] : c->val32[0];
+        const u32* sval = where ? c->s0_val[1] : c->s0_val[0];
         csr_offsets_kernel<<<grid_for(H), BLOCK, 0, s>>>(skey, H, N, c->csr_off);
         quadric_reduce_kernel<<<grid_for(N), BLOCK, 0, s>>>(c->vrec[0], d_verts, N, c->fbuf[0], c->csr_off, sval);
     } else {
@@ -1175,14 +1195,51 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
     };
     bool work = any_active() && c->opt_max_rounds != 0;
 
+    // Edge keys, their sort and the count half of the unique step (S1 up to where costs are needed)
+    // for the round that starts with `nvt` vertices, at most `nfb` facets, on stream `st_`.
+    const u64* skeys = nullptr;
+    auto issue_edge_prefix = [&](hipStream_t st_, int round_, int cur_, int nvt, int nfb) -> int {
+        const int vbits_ = ceil_log2(nvt);
+        const int H_ = 3 * nfb;
+        round_begin_kernel<<<1, BLOCK, 0, st_>>>(B, c->voff[cur_], c->target, c->active, c->stuck, c->nrem, c->matched,
+                                                 c->mslots, round_ == 0, cur_, c->st);
+        emit_edge_keys_kernel<<<grid_for(std::max(nfb, nvt), 8192), BLOCK, 0, st_>>>(
+            c->fbuf[cur_], c->st, cur_, vbits_, c->key64[0], c->vmin[0], c->vmin[1], c->mate);
+        skeys = c->key64[0];
+        if (H_ > 0) {
+            int where = sort_by_vertex<u64, false>(st_, c->key64[0], c->key64[1], nullptr, nullptr, &c->st->nh, H_,
+                                                   2 * vbits_, c->sort_sc, c->hist12,
+                                                   c->opt_kernel_timing ? &c->kt : nullptr, round_);
+            if (where < 0) return PICASSO_ERR_HIP;
+            skeys = where ? c->key64[1] : c->key64[0];
+        }
+        const u64 sentinel_ = (vbits_ >= 32) ? ~0ull : ((1ull << (2 * vbits_)) - 1ull);
+        UniquePred up_{skeys, sentinel_};
+        prim::compact_count(st_, up_, &c->st->nh, H_, c->tilesum);
+        return PICASSO_OK;
+    };
+
+    // In the first round the vertex quadrics (S0) and the edge keys (S1) depend only on the validated
+    // input, not on each other: S1's prefix goes to the context's side stream and joins before the
+    // costs are computed.  (Serial when stage times are being recorded, to keep them attributable.)
+    // The fork and join cost about as much as a few small kernels, so small inputs stay on one stream.
+    const bool overlap = work && c->opt_overlap && c->side && !tm.on && F >= OVERLAP_MIN_FACETS;
     tm.begin(0, PICASSO_ST_QUADRICS);
     init_kernel<<<grid_for(std::max(N, F), 4096), BLOCK, 0, s>>>(
         d_verts, N, d_facets, F, B, c->voff[0], c->foff, c->vrec[0], c->cid, c->fbuf[0],
-        work ? reinterpret_cast<u32*>(c->key64[0]) : nullptr, c->val32[0], c->st);
+        work ? c->s0_key[0] : nullptr, c->s0_val[0], c->st);
+    if (overlap) {
+        HIP_TRY(c, hipEventRecord(c->ev_fork, s));
+        HIP_TRY(c, hipStreamWaitEvent(c->side, c->ev_fork, 0));
+        rc = issue_edge_prefix(c->side, 0, 0, N, F);
+        if (rc != PICASSO_OK) return rc;
+        HIP_TRY(c, hipEventRecord(c->ev_join, c->side));
+    }
     if (work) {
         rc = run_vertex_quadrics(c, s, d_verts, N, F);
         if (rc != PICASSO_OK) return rc;
     }
+    if (overlap) HIP_TRY(c, hipStreamWaitEvent(s, c->ev_join, 0));
     tm.end();
 
     State* hst = reinterpret_cast<State*>(c->h_pin);  // read-back area
@@ -1202,22 +1259,14 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
 
         // ---- S1 (+S2): edges and costs
         tm.begin(round, PICASSO_ST_EDGES);
-        round_begin_kernel<<<1, BLOCK, 0, s>>>(B, c->voff[cur], c->target, c->active, c->stuck, c->nrem, c->matched,
-                                               c->mslots, round == 0, cur, c->st);
-        emit_edge_keys_kernel<<<grid_for(std::max(nf_bound, nv_total), 8192), BLOCK, 0, s>>>(
-            c->fbuf[cur], c->st, cur, vbits, c->key64[0], c->vmin[0], c->vmin[1], c->mate);
-        const u64* skeys = c->key64[0];
-        if (H > 0) {
-            int where = sort_by_vertex<u64, false>(s, c->key64[0], c->key64[1], nullptr, nullptr, &c->st->nh, H,
-                                                   2 * vbits, c->sort_sc, c->hist12,
-                                                   c->opt_kernel_timing ? &c->kt : nullptr, round);
-            if (where < 0) return PICASSO_ERR_HIP;
-            skeys = where ? c->key64[1] : c->key64[0];
+        if (!(round == 0 && overlap)) {
+            rc = issue_edge_prefix(s, round, cur, nv_total, nf_bound);
+            if (rc != PICASSO_OK) return rc;
         }
         const u64 sentinel = (vbits >= 32) ? ~0ull : ((1ull << (2 * vbits)) - 1ull);
         UniquePred up{skeys, sentinel};
         UniqueOut uo{skeys, c->ekey, c->ecost, c->vrec[cur], c->vmin[0], c->estate, vbits, mt};
-        prim::compact(s, up, up, uo, &c->st->nh, H, c->tilesum, &c->st->ne);
+        prim::compact_scatter(s, up, uo, &c->st->nh, H, c->tilesum, &c->st->ne);
         tm.end();
 
         // ---- S3: selection sub-rounds
@@ -1434,6 +1483,9 @@ int picasso_create(picasso_ctx** out, int device, int64_t max_verts, int64_t max
     (void)hipEventCreate(&c->ev_total[0]);
     (void)hipEventCreate(&c->ev_total[1]);
     for (hipEvent_t& e : c->kt_pool) (void)hipEventCreate(&e);
+    if (hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess) c->side = nullptr;
+    (void)hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming);
+    (void)hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming);
     *out = c;
     return PICASSO_OK;
 }
@@ -1447,6 +1499,9 @@ void picasso_destroy(picasso_ctx* c) {
     (void)hipEventDestroy(c->ev_total[0]);
     (void)hipEventDestroy(c->ev_total[1]);
     for (hipEvent_t& e : c->kt_pool) (void)hipEventDestroy(e);
+    if (c->side) (void)hipStreamDestroy(c->side);
+    if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+    if (c->ev_join) (void)hipEventDestroy(c->ev_join);
     if (c->h_pin) (void)hipHostFree(c->h_pin);
     if (c->ws) (void)hipFree(c->ws);
     delete c;
@@ -1458,6 +1513,7 @@ int picasso_set_option(picasso_ctx* c, int option, int64_t value) {
         case PICASSO_OPT_MAX_ROUNDS: c->opt_max_rounds = value; return PICASSO_OK;
         case PICASSO_OPT_STAGE_TIMING: c->opt_stage_timing = value; return PICASSO_OK;
         case PICASSO_OPT_KERNEL_TIMING: c->opt_kernel_timing = value; return PICASSO_OK;
+        case PICASSO_OPT_OVERLAP: c->opt_overlap = value; return PICASSO_OK;
         case PICASSO_OPT_SUBROUND_BATCH:
             if (value < 1 || value > 1024) return PICASSO_ERR_INVALID_ARG;
             c->opt_subround_batch = value;
@@ -1531,8 +1587,7 @@ int picasso_vertex_quadrics(picasso_ctx* c, void* stream, const float* d_verts, 
     int rc = upload_header(c, s, 1, &N, &F, &big, &n64, &f64);
     if (rc != PICASSO_OK) return rc;
     init_kernel<<<grid_for(std::max(N, F), 4096), BLOCK, 0, s>>>(d_verts, N, d_facets, F, 1, c->voff[0], c->foff,
-                                                                 c->vrec[0], c->cid, c->fbuf[0],
-                                                                 reinterpret_cast<u32*>(c->key64[0]), c->val32[0],
+                                                                 c->vrec[0], c->cid, c->fbuf[0], c->s0_key[0], c->s0_val[0],
                                                                  c->st);
     State* hst = reinterpret_cast<State*>(c->h_pin);
     rc = read_header(c, s);
@@ -1559,8 +1614,7 @@ int picasso_edge_costs(picasso_ctx* c, void* stream, const float* d_verts, int32
     int rc = upload_header(c, s, 1, &N, &F, &one, &n64, &f64);
     if (rc != PICASSO_OK) return rc;
     init_kernel<<<grid_for(std::max(N, F), 4096), BLOCK, 0, s>>>(d_verts, N, d_facets, F, 1, c->voff[0], c->foff,
-                                                                 c->vrec[0], c->cid, c->fbuf[0],
-                                                                 reinterpret_cast<u32*>(c->key64[0]), c->val32[0],
+                                                                 c->vrec[0], c->cid, c->fbuf[0], c->s0_key[0], c->s0_val[0],
                                                                  c->st);
     State* hst = reinterpret_cast<State*>(c->h_pin);
     rc = read_header(c, s);

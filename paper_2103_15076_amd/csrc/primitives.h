@@ -738,6 +738,33 @@ inline void compact_impl(hipStream_t s, PredCount pc, PredScatter ps, Out out, c
         <<<tiles, BLOCK, 0, s>>>(ps, out, n_ptr, n_max, tilesum, prefixed, total_out);
 }
 
+// The two halves of compact() on their own, for callers that put other work between them
+// (or launch them on different streams).  Both must be given the same n_max.
+template <class PredCount>
+inline void compact_count(hipStream_t s, PredCount pc, const int* n_ptr, int n_max, int* tilesum) {
+    const int tiles = compact_tiles(n_max > 0 ? n_max : 1, compact_chunks_for(n_max));
+    switch (compact_chunks_for(n_max)) {
+        case 1: tile_count_kernel<PredCount, 1><<<tiles, BLOCK, 0, s>>>(pc, n_ptr, n_max, tilesum); break;
+        case 4: tile_count_kernel<PredCount, 4><<<tiles, BLOCK, 0, s>>>(pc, n_ptr, n_max, tilesum); break;
+        default: tile_count_kernel<PredCount, 16><<<tiles, BLOCK, 0, s>>>(pc, n_ptr, n_max, tilesum);
+    }
+    if (tiles > COMPACT_MAX_SUMMED_TILES)
+        scan_tilesums_kernel<<<1, BLOCK, 0, s>>>(tilesum, n_ptr, n_max, BLOCK * compact_chunks_for(n_max));
+}
+
+template <class PredScatter, class Out>
+inline void compact_scatter(hipStream_t s, PredScatter ps, Out out, const int* n_ptr, int n_max, const int* tilesum,
+                            int* total_out) {
+    const int chunks = compact_chunks_for(n_max);
+    const int tiles = compact_tiles(n_max > 0 ? n_max : 1, chunks);
+    const int prefixed = tiles > COMPACT_MAX_SUMMED_TILES;
+    switch (chunks) {
+        case 1: tile_scatter_kernel<PredScatter, Out, 1><<<tiles, BLOCK, 0, s>>>(ps, out, n_ptr, n_max, tilesum, prefixed, total_out); break;
+        case 4: tile_scatter_kernel<PredScatter, Out, 4><<<tiles, BLOCK, 0, s>>>(ps, out, n_ptr, n_max, tilesum, prefixed, total_out); break;
+        default: tile_scatter_kernel<PredScatter, Out, 16><<<tiles, BLOCK, 0, s>>>(ps, out, n_ptr, n_max, tilesum, prefixed, total_out);
+    }
+}
+
 // count pass may use a different functor (e.g. one that also stores the flag)
 template <class PredCount, class PredScatter, class Out>
 inline void compact(hipStream_t s, PredCount pc, PredScatter ps, Out out, const int* n_ptr, int n_max, int* tilesum,

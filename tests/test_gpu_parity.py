@@ -353,6 +353,24 @@ def test_config_full_size(ctx, oracle, name):
     assert vo.shape[0] == target
 
 
+def test_single_stream_and_two_stream_first_round_agree(pk, ctx):
+    """Above 2^18 facets the first round's edge sort runs beside the quadric sums on a second
+    stream; both schedules must give the same bytes, call after call."""
+    c = meshgen.config("scene1p2m")
+    V, F, target = dev(c["verts"]), dev(c["facets"]), int(c["target"][0])
+    res = []
+    try:
+        for overlap in (1, 0, 1, 1):
+            ctx.set_option(pk.PICASSO_OPT_OVERLAP, overlap)
+            print(f"overlap={overlap}", flush=True)
+            st, vo, fo, cid = ctx.picasso_decimate(V, F, target)
+            torch.cuda.synchronize()
+            res.append((st, vo.cpu().numpy().tobytes(), fo.cpu().numpy().tobytes(), cid.cpu().numpy().tobytes()))
+    finally:
+        ctx.set_option(pk.PICASSO_OPT_OVERLAP, 1)
+    assert all(r == res[0] for r in res[1:])
+
+
 def test_config_batch_hierarchy(ctx, oracle):
     """16 room meshes through 4 successive levels, each to 40 % of the vertices;
     the cluster maps of all levels are kept and compared."""
