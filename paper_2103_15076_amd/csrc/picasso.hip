@@ -282,9 +282,38 @@ __device__ __forceinline__ float pair_cost(const VRec* __restrict__ vrec, int u,
     return (xAx + 2.0f * bx) + c;
 }
 
+// Bids of the lanes of one wave on their vertices x, where lanes with equal x are neighbours among
+// the lanes that bid (edges are sorted by their lower vertex, so that end of consecutive edges is
+// often the same vertex).  Atomics of one wave on one address are served one after the other, so
+// each such group first takes the minimum of its priorities across lanes and its last lane issues
+// the group's single atomicMin.  Every lane of the wave must call this.
+__device__ __forceinline__ void bid_grouped(u64* __restrict__ vmin, bool on, int x, u64 p) {
+    const int lane = prim::lane_id();
+    const u64 ab = __ballot(on);
+    if (ab == 0) return;
+    const u64 lt = prim::lanemask_lt();
+    const u64 below = ab & lt;
+    const int prev = below ? 63 - __clzll((long long)below) : lane;
+    const int xprev = __shfl(x, prev, 64);
+    const bool head = on && (below == 0 || xprev != x);
+    const u64 hb = __ballot(head);
+    const u64 hle = hb & (lt | (1ull << lane));
+    const int dist = hle ? lane - (63 - __clzll((long long)hle)) : 0;  // lanes back to the group's head
+    u64 q = on ? p : ~0ull;
+    for (int d = 1; d < 64; d <<= 1) {
+        if (!__any(dist >= d)) break;
+        const u64 o = __shfl_up(q, d, 64);
+        if (dist >= d) q = (o < q) ? o : q;
+    }
+    const u64 above = ab & ~(lt | (1ull << lane));
+    const bool tail = on && (above == 0 || ((hb >> (__ffsll((long long)above) - 1)) & 1ull));
+    if (tail) atomicMin(&vmin[x], q);
+}
+
 // Writes the distinct edges, their cost keys, and places each edge's first bid
 // (sub-round 0 of the selection) on both of its vertices.
 struct UniqueOut {
+    static constexpr bool WAVE_WIDE = true;
     const u64* keys;
     u64* ekey;
     u32* ecost;
@@ -293,19 +322,24 @@ struct UniqueOut {
     unsigned char* estate;
     int vbits;
     MeshTab mt;
-    __device__ void operator()(int i, int e) const {
-        const u64 k = keys[i];
-        const int u = (int)(k >> vbits), v = (int)(k & ((1ull << vbits) - 1ull));
-        ekey[e] = k;
-        const u32 ck = cost_key(pair_cost(vrec, u, v));
-        ecost[e] = ck;
-        const bool act = mt.active[mesh_of(mt.voff, mt.B, u)] != 0;
-        estate[e] = act ? 0 : 1;
-        if (act) {
-            const u64 p = ((u64)ck << 32) | (u32)e;
-            atomicMin(&vmin0[u], p);
-            atomicMin(&vmin0[v], p);
+    __device__ void wave(int i, bool in_range, bool flagged, int e) const {
+        bool act = false;
+        int u = 0;
+        u64 p = 0;
+        if (flagged) {
+            const u64 k = keys[i];
+            u = (int)(k >> vbits);
+            const int v = (int)(k & ((1ull << vbits) - 1ull));
+            ekey[e] = k;
+            const u32 ck = cost_key(pair_cost(vrec, u, v));
+            ecost[e] = ck;
+            act = mt.active[mesh_of(mt.voff, mt.B, u)] != 0;
+            estate[e] = act ? 0 : 1;
+            p = ((u64)ck << 32) | (u32)e;
+            if (act) atomicMin(&vmin0[v], p);
         }
+        (void)in_range;
+        bid_grouped(vmin0, act, u, p);
     }
 };
 
@@ -413,13 +447,13 @@ __global__ __launch_bounds__(BLOCK) void select_subround_kernel(SelArgs A, int k
         if (live_in) alive = subround_edge<false>(A, cur, k, (int)i, u, v, m, p, sel);
         count_pairs(A, sel, m);
         if (alive) {
-            atomicMin(&nxt[u], p);
             atomicMin(&nxt[v], p);
             rst[u] = VMIN_NONE;
             rst[v] = VMIN_NONE;
         } else if (live_in) {
             A.estate[i] = 1;
         }
+        bid_grouped(nxt, alive, u, p);
     }
 }
 

@@ -4,6 +4,7 @@
 // another workgroup: all cross-workgroup ordering is by kernel boundaries.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <type_traits>
 #include <stdint.h>
 
 namespace prim {
@@ -673,6 +674,14 @@ __global__ __launch_bounds__(BLOCK) void scan_tilesums_kernel(int* __restrict__ 
     }
 }
 
+// An output functor may declare `static constexpr bool WAVE_WIDE = true` and provide
+// wave(i, in_range, flagged, pos), which all 64 lanes of a wave call together (so it may use
+// cross-lane operations), in place of operator()(i, pos) called by the flagged lanes only.
+template <class Out, class = void>
+struct out_is_wave_wide : std::false_type {};
+template <class Out>
+struct out_is_wave_wide<Out, std::enable_if_t<Out::WAVE_WIDE>> : std::true_type {};
+
 template <class Pred, class Out, int CHUNKS>
 __global__ __launch_bounds__(BLOCK) void tile_scatter_kernel(Pred pred, Out out, const int* n_ptr, int n_host,
                                                              const int* __restrict__ tilesum, int prefixed,
@@ -721,7 +730,13 @@ __global__ __launch_bounds__(BLOCK) void tile_scatter_kernel(Pred pred, Out out,
 #pragma unroll
     for (int c = 0; c < CHUNKS; ++c) {
         const long long i = base + (long long)w * (64 * CHUNKS) + c * 64 + lane;
-        if ((bal[c] >> lane) & 1ull) out((int)i, (int)(run + (u32)__popcll(bal[c] & lt)));
+        const bool f = ((bal[c] >> lane) & 1ull) != 0;
+        const int pos = (int)(run + (u32)__popcll(bal[c] & lt));
+        if constexpr (out_is_wave_wide<Out>::value) {
+            out.wave((int)i, i < n, f, pos);  // every lane of the wave calls it
+        } else {
+            if (f) out((int)i, pos);
+        }
         run += (u32)__popcll(bal[c]);
     }
     if (base + CTILE >= n && t == 0 && total_out) *total_out = (int)(tileoff + tot);
