@@ -45,10 +45,16 @@ enum picasso_option {
     PICASSO_OPT_SUBROUND_BATCH = 2,/* selection sub-rounds launched between two host checks         */
     PICASSO_OPT_KERNEL_TIMING = 3, /* 1: bracket the launches of the edge-key sort's main kernel
                                       with hipEvents (see picasso_kernel_timing)                   */
-    PICASSO_OPT_OVERLAP = 4        /* 1 (default): for inputs of 2^18 facets or more, the first
+    PICASSO_OPT_OVERLAP = 4,       /* 1 (default): for inputs of 2^18 facets or more, the first
                                       round's edge-key sort runs on a stream of the context's own
                                       beside the vertex quadrics and joins `stream` before costs
                                       are computed; 0: everything on `stream`                      */
+    PICASSO_OPT_TRUNC_BLOCK_MAX = 5 /* budget step (Alg. 2 lines 3-4 and 6): a mesh that formed more
+                                      pairs than it may remove keeps its cheapest ones; while no
+                                      such mesh formed more than this many pairs (default and
+                                      largest value 32768) one workgroup per mesh selects them,
+                                      above it the pairs of all such meshes are sorted.  Same
+                                      result either way.                                           */
 };
 
 #define PICASSO_STATS_ROUNDS 32

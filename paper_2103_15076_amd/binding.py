@@ -25,6 +25,7 @@ PICASSO_OPT_STAGE_TIMING = 1
 PICASSO_OPT_SUBROUND_BATCH = 2
 PICASSO_OPT_KERNEL_TIMING = 3
 PICASSO_OPT_OVERLAP = 4
+PICASSO_OPT_TRUNC_BLOCK_MAX = 5
 
 PICASSO_STATS_ROUNDS = 32
 PICASSO_ST_COUNT = 8

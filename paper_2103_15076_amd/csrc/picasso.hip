@@ -630,6 +630,137 @@ struct TruncOut {
     }
 };
 
+// The same gather for the one-workgroup-per-mesh selection below: cost keys and edges apart.
+struct TruncOutSplit {
+    const u32* ecost;
+    u32* tcost;
+    u32* tval;
+    __device__ void operator()(int e, int pos) const {
+        tcost[pos] = ecost[e];
+        tval[pos] = (u32)e;
+    }
+};
+
+// Budget for meshes with a moderate number of pairs: no sort.  The gathered pairs of a mesh are a
+// contiguous run in edge order; one workgroup per mesh reads the run's cost keys once, into
+// registers (item r * TRUNC_THREADS + t sits in register r of thread t), finds the cost key of the
+// nrem-th smallest (cost key, edge) by a bitwise search on "how many keys are <= x" (a compare
+// and an add per key and bit), and flags every pair above that key and, among the pairs with
+// exactly that key, all but the first ones in edge order.  A wide kernel then releases the
+// flagged pairs.  One compute unit does the whole search, so runs longer than TRUNC_BLOCK_CAP go
+// to the sort instead.
+constexpr int TRUNC_THREADS = 1024;
+constexpr int TRUNC_REGS_MAX = 32;
+constexpr int TRUNC_BLOCK_CAP = TRUNC_THREADS * TRUNC_REGS_MAX;
+
+// Sum over the 64 lanes of a wave (all active), the same value returned to every lane.
+__device__ __forceinline__ u32 wave_sum_u32(u32 x) {
+    int v = (int)x;
+    v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, true);   // quad_perm [1,0,3,2]
+    v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, true);   // quad_perm [2,3,0,1]
+    v += __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, true);  // row_half_mirror
+    v += __builtin_amdgcn_update_dpp(0, v, 0x140, 0xF, 0xF, true);  // row_mirror: each row of 16 holds its sum
+    return (u32)(__builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) +
+                 __builtin_amdgcn_readlane(v, 32) + __builtin_amdgcn_readlane(v, 48));
+}
+
+template <int R>
+__global__ __launch_bounds__(TRUNC_THREADS) void trunc_block_kernel(u32* __restrict__ tcost,
+                                                                    const int* __restrict__ matched,
+                                                                    const int* __restrict__ nrem) {
+    constexpr int NW = TRUNC_THREADS / 64;
+    __shared__ u32 wsum[NW];
+    __shared__ u32 wsum2[2][NW];
+    __shared__ u32 cnt[R * NW];
+    const int b = blockIdx.x;
+    const int n = matched[b], keep = nrem[b];
+    if (n <= keep) return;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const u64 lt = prim::lanemask_lt();
+
+    u32 before = 0, s0;  // pairs gathered for meshes in front of this one
+    for (int j = tid; j < b; j += TRUNC_THREADS)
+        if (matched[j] > nrem[j]) before += (u32)matched[j];
+    prim::wide_block_exclusive_scan<NW>(before, wsum, s0);
+    tcost += s0;
+    if (n > R * TRUNC_THREADS) {  // not for this kernel (the host does not launch it so): release nothing
+        for (int i = tid; i < n; i += TRUNC_THREADS) tcost[i] = 0u;
+        return;
+    }
+
+    u32 key[R];  // empty slots hold the largest key
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int i = r * TRUNC_THREADS + tid;
+        key[r] = i < n ? tcost[i] : 0xFFFFFFFFu;
+    }
+
+    // Number of the run's keys <= x, known to every thread after one barrier (`slot` alternates so
+    // that the next count does not overwrite sums that are still being read).
+    auto count_le = [&](u32 x, int slot) -> u32 {
+        u32 c = 0;
+#pragma unroll
+        for (int r = 0; r < R; ++r) c += (key[r] <= x) ? 1u : 0u;
+        c = wave_sum_u32(c);
+        if (lane == 0) wsum2[slot][w] = c;
+        __syncthreads();
+        u32 tot = 0;
+#pragma unroll
+        for (int j = 0; j < NW; ++j) tot += wsum2[slot][j];
+        return tot < (u32)n ? tot : (u32)n;  // (empty slots count when x is the largest key)
+    };
+
+    // prefix = smallest key x with at least `keep` keys <= x, found bit by bit from the top
+    u32 prefix = 0, kk = 0;
+    if (keep > 0) {
+        for (int bit = 31; bit >= 0; --bit)
+            if (count_le(prefix | ((1u << bit) - 1u), bit & 1) < (u32)keep) prefix |= 1u << bit;
+        __syncthreads();
+        kk = (u32)keep - (prefix ? count_le(prefix - 1u, 0) : 0u);
+    }
+    // kk = how many pairs with exactly the key `prefix` stay (the first kk in edge order)
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const bool eq = (r * TRUNC_THREADS + tid < n) && key[r] == prefix;
+        const u64 eb = __ballot(eq);
+        if (lane == 0) cnt[r * NW + w] = (u32)__popcll(eb);
+    }
+    __syncthreads();
+    {
+        const u32 v = tid < R * NW ? cnt[tid] : 0u;
+        u32 tot;
+        const u32 ex = prim::wide_block_exclusive_scan<NW>(v, wsum, tot);
+        if (tid < R * NW) cnt[tid] = ex;  // equal keys in front of wave w's part of row r
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int i = r * TRUNC_THREADS + tid;
+        const bool valid = i < n;
+        const bool eq = valid && key[r] == prefix, gt = valid && key[r] > prefix;
+        const u64 eb = __ballot(eq);
+        const u32 rank = cnt[r * NW + w] + (u32)__popcll(eb & lt);
+        if (valid) tcost[i] = (gt || (eq && rank >= kk)) ? 1u : 0u;  // the key's slot now holds the flag
+    }
+}
+
+// Releases the flagged pairs; block 0 also clamps the pair counts of the meshes to their budgets.
+__global__ __launch_bounds__(BLOCK) void trunc_release_kernel(const u32* __restrict__ tflag,
+                                                              const u32* __restrict__ tval, const State* st,
+                                                              const u64* __restrict__ ekey, int vbits,
+                                                              int* __restrict__ mate, int B, int* __restrict__ matched,
+                                                              const int* __restrict__ nrem) {
+    const int i = blockIdx.x * BLOCK + threadIdx.x;
+    if (i < st->trunc_n && tflag[i]) {
+        const u64 k = ekey[tval[i]];
+        mate[(int)(k >> vbits)] = -1;
+        mate[(int)(k & ((1ull << vbits) - 1ull))] = -1;
+    }
+    if (blockIdx.x == 0)
+        for (int b = threadIdx.x; b < B; b += BLOCK)
+            if (matched[b] > nrem[b]) matched[b] = nrem[b];
+}
+
 // segstart[b] = number of gathered pairs that belong to meshes before b
 __global__ void trunc_segments_kernel(int B, const int* __restrict__ matched, const int* __restrict__ nrem,
                                       int* __restrict__ segstart) {
@@ -956,6 +1087,7 @@ struct picasso_ctx {
     hipStream_t side = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     int64_t opt_overlap = 1;
+    int64_t opt_trunc_block_max = TRUNC_BLOCK_CAP;
     // per-mesh tables
     int* voff[2] = {nullptr, nullptr};
     int* foff = nullptr;
@@ -1370,16 +1502,33 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         // ---- budget truncation (only where a mesh formed more pairs than it may remove)
         bool need_trunc = false;
         long long n_trunc = 0;
-        int n_sel = 0;
+        int n_sel = 0, seg_max = 0;
         for (int b = 0; b < B; ++b) {
             if (h_matched[b] > nrem[b]) {
                 need_trunc = true;
                 n_trunc += h_matched[b];
+                seg_max = std::max(seg_max, h_matched[b]);
                 h_matched[b] = nrem[b];
             }
             n_sel += h_matched[b];
         }
-        if (need_trunc) {
+        if (need_trunc && seg_max <= c->opt_trunc_block_max) {
+            const int ne = hst->ne;
+            TruncPred tp{c->ekey, c->mate, mt, vbits};
+            u32* tcost = reinterpret_cast<u32*>(c->key64[0]);
+            TruncOutSplit to{c->ecost, tcost, c->val32[0]};
+            prim::compact(s, tp, tp, to, nullptr, ne, c->tilesum, &c->st->trunc_n);
+            if (seg_max <= 4 * TRUNC_THREADS)
+                trunc_block_kernel<4><<<B, TRUNC_THREADS, 0, s>>>(tcost, c->matched, c->nrem);
+            else if (seg_max <= 8 * TRUNC_THREADS)
+                trunc_block_kernel<8><<<B, TRUNC_THREADS, 0, s>>>(tcost, c->matched, c->nrem);
+            else if (seg_max <= 16 * TRUNC_THREADS)
+                trunc_block_kernel<16><<<B, TRUNC_THREADS, 0, s>>>(tcost, c->matched, c->nrem);
+            else
+                trunc_block_kernel<32><<<B, TRUNC_THREADS, 0, s>>>(tcost, c->matched, c->nrem);
+            trunc_release_kernel<<<grid_for(n_trunc), BLOCK, 0, s>>>(tcost, c->val32[0], c->st, c->ekey, vbits,
+                                                                     c->mate, B, c->matched, c->nrem);
+        } else if (need_trunc) {
             const int ne = hst->ne;
             TruncPred tp{c->ekey, c->mate, mt, vbits};
             TruncOut to{c->ekey, c->ecost, c->key64[0], c->val32[0], mt, vbits};
@@ -1548,6 +1697,10 @@ int picasso_set_option(picasso_ctx* c, int option, int64_t value) {
         case PICASSO_OPT_STAGE_TIMING: c->opt_stage_timing = value; return PICASSO_OK;
         case PICASSO_OPT_KERNEL_TIMING: c->opt_kernel_timing = value; return PICASSO_OK;
         case PICASSO_OPT_OVERLAP: c->opt_overlap = value; return PICASSO_OK;
+        case PICASSO_OPT_TRUNC_BLOCK_MAX:
+            if (value < 0) return PICASSO_ERR_INVALID_ARG;
+            c->opt_trunc_block_max = std::min<int64_t>(value, TRUNC_BLOCK_CAP);
+            return PICASSO_OK;
         case PICASSO_OPT_SUBROUND_BATCH:
             if (value < 1 || value > 1024) return PICASSO_ERR_INVALID_ARG;
             c->opt_subround_batch = value;

@@ -183,6 +183,40 @@ def test_decimate_matches_oracle(pk, ctx, oracle, name, mesh, frac, max_rounds):
     assert_same_result(st, vo, fo, cid, ref)
 
 
+@pytest.mark.parametrize("block_max", [0, 1 << 15], ids=["sorted", "per_mesh_select"])
+def test_budget_step_both_ways(pk, ctx, oracle, block_max):
+    """The last round keeps a mesh's cheapest pairs either by a sort of all gathered pairs or by a
+    per-mesh selection; both against the oracle, on meshes with distinct costs and with nothing but ties,
+    alone and in a batch (budgets of 1 pair, of all but 1 pair, and in between)."""
+    ctx.set_option(pk.PICASSO_OPT_TRUNC_BLOCK_MAX, block_max)
+    try:
+        for name, (V, F) in _small_meshes():
+            for frac in (0.9, 0.55):
+                target = int(V.shape[0] * frac)
+                print(f"budget {name} target={target} block_max={block_max}", flush=True)
+                st, vo, fo, cid = ctx.picasso_decimate(dev(V), dev(F), target)
+                assert_same_result(st, vo, fo, cid, oracle.decimate(V, F, target))
+        parts = [meshgen.noisy_grid(30, 22, seed=1), meshgen.flat_grid(21, 17, spacing=0.25),
+                 meshgen.icosphere(3, seed=2), meshgen.noisy_grid(12, 12, seed=3)]
+        nv = [p[0].shape[0] for p in parts]
+        nf = [p[1].shape[0] for p in parts]
+        off = np.cumsum([0] + nv)
+        V = np.concatenate([p[0] for p in parts])
+        F = np.concatenate([p[1] + off[i] for i, p in enumerate(parts)]).astype(np.int32)
+        for tg in ([nv[0] - 1, nv[1] - 1, nv[2], nv[3] - 1],          # one pair each (one mesh untouched)
+                   [nv[0] - 100, nv[1] // 2, nv[2] - 7, nv[3] - 30]):
+            print(f"budget batch targets={tg} block_max={block_max}", flush=True)
+            st, vo, fo, cid, nvo, nfo = ctx.picasso_decimate_batch(dev(V), dev(F), nv, nf, tg)
+            ref = oracle.decimate_batch(V, F, nv, nf, tg)
+            assert st == ref["status"]
+            assert nvo.tolist() == ref["nv"].tolist() and nfo.tolist() == ref["nf"].tolist()
+            assert np.array_equal(cid.cpu().numpy(), ref["cluster_id"])
+            assert np.array_equal(fo.cpu().numpy(), ref["facets"])
+            assert np.array_equal(vo.cpu().numpy().view(np.uint32), ref["verts"].view(np.uint32))
+    finally:
+        ctx.set_option(pk.PICASSO_OPT_TRUNC_BLOCK_MAX, 1 << 15)
+
+
 def test_adversarial_small_meshes(ctx, oracle):
     rng = np.random.default_rng(5)
     cases = {}
