@@ -370,6 +370,8 @@ struct SelArgs {
     State* st;
     MeshTab mt;
     int vbits;
+    int* host_img;     // pinned host memory, device view: the tail leaves [State][matched] there
+    int publish_ints;  // for the host, which then needs no copy of its own before it looks
 };
 
 // Bids are read with device-scope atomic loads where the same kernel also
@@ -496,11 +498,22 @@ __device__ __forceinline__ int tail_slot(int* vkey, int v) {
     }
 }
 
+// The round's counters and pair counts, written straight into the host's pinned memory (read at
+// the L2, where this kernel's own stores to them already are).
+__device__ __forceinline__ void tail_publish(const SelArgs& A, int tid) {
+    const int* hdr = reinterpret_cast<const int*>(A.st);
+    for (int i = tid; i < A.publish_ints; i += TAIL_THREADS)
+        A.host_img[i] = __hip_atomic_load(&hdr[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 __global__ __launch_bounds__(TAIL_THREADS) void select_tail_kernel(SelArgs A) {
     __shared__ TailLds L;
     int n = A.st->live[0];     // live edges, gathered into A.list just before this kernel
-    if (n > TAIL_MAX) return;  // too many: the host runs more grid-wide sub-rounds
     const int tid = threadIdx.x, lane = prim::lane_id();
+    if (n > TAIL_MAX) {        // too many: the host runs more grid-wide sub-rounds
+        tail_publish(A, tid);
+        return;
+    }
     const u64 lt = prim::lanemask_lt();
     const u64 vmask = (1ull << A.vbits) - 1ull;
 
@@ -594,6 +607,9 @@ __global__ __launch_bounds__(TAIL_THREADS) void select_tail_kernel(SelArgs A) {
         A.mt.matched[b] = sum;
     }
     if (tid == 0) A.st->live[0] = 0;
+    __threadfence();
+    __syncthreads();
+    tail_publish(A, tid);
 }
 
 // ---------------------------------------------------------------------------
@@ -1102,6 +1118,7 @@ struct picasso_ctx {
     // pinned host staging
     // pinned host staging: read-back image of the header's front, then the upload image of the whole header
     int* h_pin = nullptr;
+    int* h_pin_dev = nullptr;  // the same memory as the device addresses it
     size_t h_up_off = 0;
     size_t h_pin_ints = 0;
     hipEvent_t ev[2 * PICASSO_STATS_ROUNDS * PICASSO_ST_COUNT + 4];
@@ -1447,6 +1464,8 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         sa.st = c->st;
         sa.mt = mt;
         sa.vbits = vbits;
+        sa.host_img = c->h_pin_dev;
+        sa.publish_ints = HDR_STATE_INTS + B;
         int sel_k = 0;
         // Grid-wide sub-rounds while many edges are live (the live count falls about 3x per
         // sub-round), then the live edges are gathered and one workgroup finishes; the host
@@ -1472,8 +1491,7 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
             prim::compact(s, lp, lp, lo, &c->st->ne, ne_bound, c->tilesum, &c->st->live[0]);
             select_tail_kernel<<<1, TAIL_THREADS, 0, s>>>(sa);
             launched += wide + 3;
-            rc = read_header(c, s);
-            if (rc != PICASSO_OK) return rc;
+            HIP_TRY(c, hipStreamSynchronize(s));  // the tail has left [State][matched] in the read-back area
             if (!validated) {
                 const int st_err = status_from_err_bits(hst->err);
                 if (st_err != PICASSO_OK) return st_err;
@@ -1661,6 +1679,12 @@ int picasso_create(picasso_ctx** out, int device, int64_t max_verts, int64_t max
         return PICASSO_ERR_HIP;
     }
     memset(c->h_pin, 0, c->h_pin_ints * sizeof(int));
+    if (hipHostGetDevicePointer((void**)&c->h_pin_dev, c->h_pin, 0) != hipSuccess) {
+        (void)hipHostFree(c->h_pin);
+        (void)hipFree(c->ws);
+        delete c;
+        return PICASSO_ERR_HIP;
+    }
     const int nev = (int)(sizeof(c->ev) / sizeof(c->ev[0]));
     for (int i = 0; i < nev; ++i) (void)hipEventCreate(&c->ev[i]);
     (void)hipEventCreate(&c->ev_total[0]);
