@@ -200,18 +200,28 @@ __global__ __launch_bounds__(BLOCK) void quadric_reduce_kernel(VRec* __restrict_
 // ---------------------------------------------------------------------------
 // Round set-up
 // ---------------------------------------------------------------------------
-__global__ void round_begin_kernel(int B, const int* __restrict__ voff, const int* __restrict__ target,
-                                   int* __restrict__ active, int* __restrict__ stuck, int* __restrict__ nrem,
-                                   int* __restrict__ matched, int* __restrict__ mslots, int first_round, int cur,
-                                   State* st) {
-    for (int i = threadIdx.x; i < B * MATCH_SLOTS; i += blockDim.x) mslots[(size_t)i * MATCH_PAD] = 0;
-    for (int b = threadIdx.x; b < B; b += blockDim.x) {
-        const int nvb = voff[b + 1] - voff[b];
-        if (!first_round && active[b] && matched[b] == 0) stuck[b] = 1;
-        const int act = (nvb > target[b]) && !stuck[b];
-        active[b] = act;
-        nrem[b] = act ? nvb - target[b] : 0;
-        matched[b] = 0;
+struct RoundTab {
+    int B;
+    const int* voff;
+    const int* target;
+    int* active;
+    int* stuck;
+    int* nrem;
+    int* matched;
+    int* mslots;
+    int first_round;
+};
+
+// Per-mesh budgets and the round's counters, by one workgroup.
+__device__ __forceinline__ void round_begin_block(const RoundTab& R, int cur, State* st) {
+    for (int i = threadIdx.x; i < R.B * MATCH_SLOTS; i += blockDim.x) R.mslots[(size_t)i * MATCH_PAD] = 0;
+    for (int b = threadIdx.x; b < R.B; b += blockDim.x) {
+        const int nvb = R.voff[b + 1] - R.voff[b];
+        if (!R.first_round && R.active[b] && R.matched[b] == 0) R.stuck[b] = 1;
+        const int act = (nvb > R.target[b]) && !R.stuck[b];
+        R.active[b] = act;
+        R.nrem[b] = act ? nvb - R.target[b] : 0;
+        R.matched[b] = 0;
     }
     if (threadIdx.x == 0) {
         st->nh = 3 * st->nf[cur];
@@ -226,28 +236,63 @@ __global__ void round_begin_kernel(int B, const int* __restrict__ voff, const in
 
 // ---------------------------------------------------------------------------
 // S1: candidate pairs = distinct mesh edges (Alg. 2 line 1)
+//
+// First kernel of a round: the round's set-up (block 0), the per-vertex selection state, and one
+// 64-bit key (lower vertex, higher vertex) per half-edge, key i for corner i of the facet array.
+// With COUNT the workgroups walk the keys in the tiles of the sort that follows and also leave
+// that sort's first per-tile digit counts in `table` (the layout of prim::radix_upsweep_kernel),
+// which saves the sort its first pass over the keys.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(BLOCK) void emit_edge_keys_kernel(const int* __restrict__ fcur, const State* st, int cur,
-                                                               int vbits, u64* __restrict__ keys,
-                                                               u64* __restrict__ vmin0, u64* __restrict__ vmin1,
-                                                               int* __restrict__ mate) {
+template <bool COUNT>
+__global__ __launch_bounds__(BLOCK) void edge_keys_kernel(const int* __restrict__ fcur, State* st, int cur, int vbits,
+                                                          u64* __restrict__ keys, u64* __restrict__ vmin0,
+                                                          u64* __restrict__ vmin1, int* __restrict__ mate,
+                                                          RoundTab R, int T, u32* __restrict__ table, int shift,
+                                                          int bits) {
+    constexpr int ITEMS = prim::SORT_ITEMS_SMALL;
+    constexpr int TILE = BLOCK * ITEMS;
+    __shared__ u32 hist[COUNT ? prim::WAVES : 1][256];
     const int nf = st->nf[cur], nv = st->nv[cur];
+    const long long n = 3ll * nf;
     const int stride = gridDim.x * BLOCK;
-    const int g = blockIdx.x * BLOCK + threadIdx.x;
+    const int t = threadIdx.x, g = blockIdx.x * BLOCK + t;
     const u64 sentinel = (vbits >= 32) ? ~0ull : ((1ull << (2 * vbits)) - 1ull);
-    for (int f = g; f < nf; f += stride) {
-        const int a = fcur[3 * (size_t)f], b = fcur[3 * (size_t)f + 1], c = fcur[3 * (size_t)f + 2];
-        const int p[3] = {a, b, c}, q[3] = {b, c, a};
-#pragma unroll
-        for (int s = 0; s < 3; ++s) {
-            const int lo = min(p[s], q[s]), hi = max(p[s], q[s]);
-            keys[3 * (size_t)f + s] = (lo == hi) ? sentinel : (((u64)(u32)lo << vbits) | (u64)(u32)hi);
-        }
-    }
     for (int w = g; w < nv; w += stride) {
         vmin0[w] = VMIN_NONE;
         vmin1[w] = VMIN_NONE;
         mate[w] = -1;
+    }
+    if (blockIdx.x == 0) round_begin_block(R, cur, st);
+    const u32 dmask = (1u << bits) - 1u;
+    const u32 copy = COUNT ? (((u32)prim::lane_id() & ((256u >> bits) - 1u)) << bits) : 0u;
+    for (long long tile = blockIdx.x; tile * TILE < n; tile += gridDim.x) {
+        if constexpr (COUNT) {
+            for (int i = t; i < prim::WAVES * 256; i += BLOCK) (&hist[0][0])[i] = 0;
+            __syncthreads();
+        }
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            const long long idx = tile * TILE + (long long)i * BLOCK + t;
+            if (idx < n) {
+                const int f = (int)(idx / 3), sl = (int)(idx - 3ll * f);
+                const int a = fcur[idx], b = fcur[3 * (size_t)f + (sl == 2 ? 0 : sl + 1)];
+                const int lo = min(a, b), hi = max(a, b);
+                const u64 k = (lo == hi) ? sentinel : (((u64)(u32)lo << vbits) | (u64)(u32)hi);
+                keys[idx] = k;
+                if constexpr (COUNT) atomicAdd(&hist[prim::wave_id()][copy | ((u32)(k >> shift) & dmask)], 1u);
+            }
+        }
+        if constexpr (COUNT) {
+            static_assert(prim::WAVES == 4, "four per-wave histograms are summed below");
+            __syncthreads();
+            const u32 radix = 1u << bits;
+            if ((u32)t < radix) {
+                u32 sum = 0;
+                for (u32 c = (u32)t; c < 256u; c += radix) sum += hist[0][c] + hist[1][c] + hist[2][c] + hist[3][c];
+                table[(size_t)t * T + tile] = sum;
+            }
+            __syncthreads();
+        }
     }
 }
 
@@ -1264,12 +1309,46 @@ struct StageTimer {
 // when the input is small enough for it, plain LSD passes otherwise.
 template <typename K, bool HAS_VAL>
 int sort_by_vertex(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_ptr, int n_max, int key_bits,
-                   const prim::SortScratch& sc, u32* hist12, prim::LaunchTimer* lt = nullptr, int tag = 0) {
+                   const prim::SortScratch& sc, u32* hist12, prim::LaunchTimer* lt = nullptr, int tag = 0,
+                   bool counted = false) {
     if (n_max <= prim::BUCKET_SORT_MAX_KEYS && key_bits > prim::BUCKET_MSD_BITS)
-        return prim::bucket_sort<K, HAS_VAL>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc, lt, tag);
+        return prim::bucket_sort<K, HAS_VAL>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc, lt, tag, counted);
     if (n_max <= prim::BUCKET_SORT_LARGE_MAX_KEYS && key_bits > prim::BUCKET_LARGE_MSD_BITS)
         return prim::bucket_sort_large<K, HAS_VAL>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc, hist12, lt, tag);
     return prim::radix_sort<K, HAS_VAL>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc, lt, tag);
+}
+
+// Edge keys, their sort and the count half of the unique step (S1 up to where costs are needed)
+// for the round that starts with `nvt` vertices and at most `nfb` facets, on stream `st_`.
+// *skeys_out = the sorted keys.
+int issue_edge_prefix(picasso_ctx* c, hipStream_t st_, int B, int round_, int cur_, int nvt, int nfb,
+                      const u64** skeys_out) {
+    const u64* skeys = nullptr;
+    const int vbits_ = ceil_log2(nvt);
+    const int H_ = 3 * nfb;
+    const RoundTab rt{B, c->voff[cur_], c->target, c->active, c->stuck, c->nrem, c->matched, c->mslots, round_ == 0};
+    // inputs that go to the bucket sort get its first digit counts from the kernel that writes the keys
+    const bool counted = H_ > 0 && H_ <= prim::BUCKET_SORT_MAX_KEYS && 2 * vbits_ > prim::BUCKET_MSD_BITS;
+    if (counted)
+        edge_keys_kernel<true><<<prim::sort_tiles(H_, prim::SORT_ITEMS_SMALL), BLOCK, 0, st_>>>(
+            c->fbuf[cur_], c->st, cur_, vbits_, c->key64[0], c->vmin[0], c->vmin[1], c->mate, rt, c->sort_sc.T,
+            c->sort_sc.table, prim::bucket_sort_low_bits(2 * vbits_), prim::bucket_sort_msd_bits(2 * vbits_));
+    else
+        edge_keys_kernel<false><<<grid_for(std::max(3 * nfb, nvt), 8192), BLOCK, 0, st_>>>(
+            c->fbuf[cur_], c->st, cur_, vbits_, c->key64[0], c->vmin[0], c->vmin[1], c->mate, rt, 0, nullptr, 0, 8);
+    skeys = c->key64[0];
+    if (H_ > 0) {
+        int where = sort_by_vertex<u64, false>(st_, c->key64[0], c->key64[1], nullptr, nullptr, &c->st->nh, H_,
+                                               2 * vbits_, c->sort_sc, c->hist12,
+                                               c->opt_kernel_timing ? &c->kt : nullptr, round_, counted);
+        if (where < 0) return PICASSO_ERR_HIP;
+        skeys = where ? c->key64[1] : c->key64[0];
+    }
+    const u64 sentinel_ = (vbits_ >= 32) ? ~0ull : ((1ull << (2 * vbits_)) - 1ull);
+    UniquePred up_{skeys, sentinel_};
+    prim::compact_count(st_, up_, &c->st->nh, H_, c->tilesum);
+    *skeys_out = skeys;
+    return PICASSO_OK;
 }
 
 // S0 on the data already validated into the workspace by init_kernel.
@@ -1378,34 +1457,11 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
     };
     bool work = any_active() && c->opt_max_rounds != 0;
 
-    // Edge keys, their sort and the count half of the unique step (S1 up to where costs are needed)
-    // for the round that starts with `nvt` vertices, at most `nfb` facets, on stream `st_`.
-    const u64* skeys = nullptr;
-    auto issue_edge_prefix = [&](hipStream_t st_, int round_, int cur_, int nvt, int nfb) -> int {
-        const int vbits_ = ceil_log2(nvt);
-        const int H_ = 3 * nfb;
-        round_begin_kernel<<<1, BLOCK, 0, st_>>>(B, c->voff[cur_], c->target, c->active, c->stuck, c->nrem, c->matched,
-                                                 c->mslots, round_ == 0, cur_, c->st);
-        emit_edge_keys_kernel<<<grid_for(std::max(nfb, nvt), 8192), BLOCK, 0, st_>>>(
-            c->fbuf[cur_], c->st, cur_, vbits_, c->key64[0], c->vmin[0], c->vmin[1], c->mate);
-        skeys = c->key64[0];
-        if (H_ > 0) {
-            int where = sort_by_vertex<u64, false>(st_, c->key64[0], c->key64[1], nullptr, nullptr, &c->st->nh, H_,
-                                                   2 * vbits_, c->sort_sc, c->hist12,
-                                                   c->opt_kernel_timing ? &c->kt : nullptr, round_);
-            if (where < 0) return PICASSO_ERR_HIP;
-            skeys = where ? c->key64[1] : c->key64[0];
-        }
-        const u64 sentinel_ = (vbits_ >= 32) ? ~0ull : ((1ull << (2 * vbits_)) - 1ull);
-        UniquePred up_{skeys, sentinel_};
-        prim::compact_count(st_, up_, &c->st->nh, H_, c->tilesum);
-        return PICASSO_OK;
-    };
-
     // In the first round the vertex quadrics (S0) and the edge keys (S1) depend only on the validated
     // input, not on each other: S1's prefix goes to the context's side stream and joins before the
     // costs are computed.  (Serial when stage times are being recorded, to keep them attributable.)
     // The fork and join cost about as much as a few small kernels, so small inputs stay on one stream.
+    const u64* skeys = nullptr;
     const bool overlap = work && c->opt_overlap && c->side && !tm.on && F >= OVERLAP_MIN_FACETS;
     tm.begin(0, PICASSO_ST_QUADRICS);
     init_kernel<<<grid_for(std::max(N, F), 4096), BLOCK, 0, s>>>(
@@ -1414,7 +1470,7 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
     if (overlap) {
         HIP_TRY(c, hipEventRecord(c->ev_fork, s));
         HIP_TRY(c, hipStreamWaitEvent(c->side, c->ev_fork, 0));
-        rc = issue_edge_prefix(c->side, 0, 0, N, F);
+        rc = issue_edge_prefix(c, c->side, B, 0, 0, N, F, &skeys);
         if (rc != PICASSO_OK) return rc;
         HIP_TRY(c, hipEventRecord(c->ev_join, c->side));
     }
@@ -1443,7 +1499,7 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         // ---- S1 (+S2): edges and costs
         tm.begin(round, PICASSO_ST_EDGES);
         if (!(round == 0 && overlap)) {
-            rc = issue_edge_prefix(s, round, cur, nv_total, nf_bound);
+            rc = issue_edge_prefix(c, s, B, round, cur, nv_total, nf_bound, &skeys);
             if (rc != PICASSO_OK) return rc;
         }
         const u64 sentinel = (vbits >= 32) ? ~0ull : ((1ull << (2 * vbits)) - 1ull);
@@ -1836,21 +1892,13 @@ int picasso_edge_costs(picasso_ctx* c, void* stream, const float* d_verts, int32
     if (rc != PICASSO_OK) return rc;
     const int vbits = ceil_log2(N), H = 3 * F;
     MeshTab mt{1, c->voff[0], c->target, c->active, c->nrem, c->matched, c->mslots};
-    round_begin_kernel<<<1, BLOCK, 0, s>>>(1, c->voff[0], c->target, c->active, c->stuck, c->nrem, c->matched, c->mslots,
-                                           1, 0, c->st);
-    emit_edge_keys_kernel<<<grid_for(std::max(F, N), 8192), BLOCK, 0, s>>>(c->fbuf[0], c->st, 0, vbits, c->key64[0],
-                                                                          c->vmin[0], c->vmin[1], c->mate);
-    const u64* skeys = c->key64[0];
-    if (H > 0) {
-        int where = sort_by_vertex<u64, false>(s, c->key64[0], c->key64[1], nullptr, nullptr, &c->st->nh, H, 2 * vbits,
-                                               c->sort_sc, c->hist12);
-        if (where < 0) return PICASSO_ERR_HIP;
-        skeys = where ? c->key64[1] : c->key64[0];
-    }
+    const u64* skeys = nullptr;
+    rc = issue_edge_prefix(c, s, 1, 0, 0, N, F, &skeys);
+    if (rc != PICASSO_OK) return rc;
     const u64 sentinel = (vbits >= 32) ? ~0ull : ((1ull << (2 * vbits)) - 1ull);
     UniquePred up{skeys, sentinel};
     UniqueOut uo{skeys, c->ekey, c->ecost, c->vrec[0], c->vmin[0], c->estate, vbits, mt};
-    prim::compact(s, up, up, uo, &c->st->nh, H, c->tilesum, &c->st->ne);
+    prim::compact_scatter(s, up, uo, &c->st->nh, H, c->tilesum, &c->st->ne);
     export_edges_kernel<<<grid_for(std::max(H, 1)), BLOCK, 0, s>>>(c->ekey, c->ecost, c->st, vbits, d_edges_out,
                                                                    d_cost_out);
     rc = read_header(c, s);

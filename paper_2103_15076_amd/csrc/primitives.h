@@ -530,14 +530,21 @@ __global__ __launch_bounds__(BUCKET_THREADS) void bucket_sort_kernel(K* __restri
 
 // Stable sort on key bits [0, key_bits) for n <= BUCKET_SORT_MAX_KEYS keys with
 // evenly spread leading bits.  The result is always in (k0, v0): returns 0, or <0 on a launch error.
+// `counted`: the producer of the keys has already filled sc.table with the per-tile counts of the
+// top digit (tiles of BLOCK * SORT_ITEMS_SMALL keys, digit = bits [bucket_sort_low_bits, key_bits)),
+// as radix_upsweep_kernel would, so that pass over the keys is skipped.
+inline int bucket_sort_msd_bits(int key_bits) { return key_bits < BUCKET_MSD_BITS ? key_bits : BUCKET_MSD_BITS; }
+inline int bucket_sort_low_bits(int key_bits) { return key_bits - bucket_sort_msd_bits(key_bits); }
+
 template <typename K, bool HAS_VAL>
 inline int bucket_sort(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_ptr, int n_max, int key_bits,
-                       const SortScratch& sc, LaunchTimer* lt = nullptr, int tag = 0) {
+                       const SortScratch& sc, LaunchTimer* lt = nullptr, int tag = 0, bool counted = false) {
     if (n_max <= 0 || key_bits <= 0) return 0;
-    const int msd = key_bits < BUCKET_MSD_BITS ? key_bits : BUCKET_MSD_BITS;
+    const int msd = bucket_sort_msd_bits(key_bits);
     const int low = key_bits - msd;
     const int tiles = sort_tiles(n_max, SORT_ITEMS_SMALL);
-    radix_upsweep_kernel<K, SORT_ITEMS_SMALL><<<tiles, BLOCK, 0, s>>>(k0, n_ptr, n_max, sc.T, sc.table, low, msd);
+    if (!counted)
+        radix_upsweep_kernel<K, SORT_ITEMS_SMALL><<<tiles, BLOCK, 0, s>>>(k0, n_ptr, n_max, sc.T, sc.table, low, msd);
     radix_scan_kernel<<<1 << msd, BLOCK, 0, s>>>(sc.table, sc.totals, n_ptr, n_max, sc.T, BLOCK * SORT_ITEMS_SMALL);
     radix_downsweep_kernel<K, HAS_VAL, SORT_ITEMS_SMALL>
         <<<tiles, BLOCK, 0, s>>>(k0, k1, v0, v1, n_ptr, n_max, sc.T, sc.table, sc.totals, low, msd);
