@@ -75,6 +75,45 @@ __device__ __forceinline__ u32 digit_of(K k, int shift, u32 mask) {
     return (u32)(k >> shift) & mask;
 }
 
+// Stable ranks of a wave's keys among the wave's keys with the same digit.  digit[i] is the
+// digit of the lane's i-th key (keys are ordered by (item, lane)); wrow[d] accumulates this
+// wave's count of digit d and must be zero on entry.  On return rank[i] = number of the wave's
+// earlier keys with the same digit.  Lanes that hold one digit are found with ballots; the first
+// of them adds their number to wrow[d] with one LDS atomic, whose return value (the count left by
+// the earlier items: LDS operations of a wave complete in order) it then hands to the others.
+// Four items go through together so that four atomics are in flight instead of one.
+template <int ITEMS>
+__device__ __forceinline__ void wave_rank_digits(const u32 (&digit)[ITEMS], int items, int bits, u32* wrow,
+                                                 u32 (&rank)[ITEMS]) {
+    constexpr int GROUP = ITEMS < 4 ? ITEMS : 4;
+    const u64 lt = lanemask_lt();
+#pragma unroll
+    for (int i0 = 0; i0 < ITEMS; i0 += GROUP) {
+        if (i0 >= items) break;
+        u32 below[GROUP], old[GROUP];
+        int leader[GROUP];
+#pragma unroll
+        for (int j = 0; j < GROUP; ++j) {
+            old[j] = 0;
+            if (i0 + j < items) {
+                const u32 d = digit[i0 + j];
+                u64 m = ~0ull;  // lanes of this wave holding the same digit
+                for (int b = 0; b < bits; ++b) {
+                    const bool bit = (d >> b) & 1u;
+                    const u64 bal = __ballot(bit);
+                    m &= bit ? bal : ~bal;
+                }
+                below[j] = (u32)__popcll(m & lt);
+                leader[j] = __ffsll((long long)m) - 1;
+                if (below[j] == 0) old[j] = atomicAdd(&wrow[d], (u32)__popcll(m));
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < GROUP; ++j)
+            if (i0 + j < items) rank[i0 + j] = (u32)__shfl((int)old[j], leader[j], 64) + below[j];
+    }
+}
+
 // table[d * T + tile] = number of keys of this tile whose digit is d
 template <typename K, int SORT_ITEMS>
 __global__ __launch_bounds__(BLOCK) void radix_upsweep_kernel(const K* __restrict__ kin, const int* n_ptr, int n_host,
@@ -161,22 +200,11 @@ __global__ __launch_bounds__(BLOCK) void radix_downsweep_kernel(const K* __restr
     }
     __syncthreads();
 
-    const u64 lt = lanemask_lt();
+    {
+        u32 digit[SORT_ITEMS];
 #pragma unroll
-    for (int i = 0; i < SORT_ITEMS; ++i) {
-        const u32 d = digit_of<K>(key[i], shift, dmask);
-        u64 m = ~0ull;  // lanes of this wave holding the same digit
-        for (int b = 0; b < bits; ++b) {
-            const bool bit = (d >> b) & 1u;
-            const u64 bal = __ballot(bit);
-            m &= bit ? bal : ~bal;
-        }
-        const u32 old = wcnt[w][d];
-        const u32 below = (u32)__popcll(m & lt);
-        __builtin_amdgcn_wave_barrier();
-        if (below == 0) wcnt[w][d] = old + (u32)__popcll(m);
-        __builtin_amdgcn_wave_barrier();
-        rank[i] = old + below;
+        for (int i = 0; i < SORT_ITEMS; ++i) digit[i] = digit_of<K>(key[i], shift, dmask);
+        wave_rank_digits<SORT_ITEMS>(digit, SORT_ITEMS, bits, wcnt[w], rank);
     }
     __syncthreads();
 
@@ -408,6 +436,19 @@ __device__ void bucket_sort_oversize(K* a, K* b, u32* va, u32* vb, int cnt, int 
 // One workgroup per bucket.  kin/vin hold the keys partitioned by their top
 // digit (bucket d occupies [start_d, start_d + totals[d])); the sorted bucket is
 // written to the same range of kout/vout.  low_bits = key bits below the digit.
+//
+// The bucket is held in LDS.  One stable radix pass on the TOP (up to) 9 of the
+// low bits splits it into up to 512 groups of keys that agree on all bits
+// sorted so far; with vertex-pair keys a group is the handful of half-edges of
+// one lower vertex.  Each group is then finished by one lane with a stable
+// insertion sort on the whole key, which for such groups costs far less than
+// the two or three more radix passes over every key that the remaining bits
+// would take (a radix pass spends one wave-wide ballot per key and bit).  If
+// some group is long (keys crowded on few values of those 9 bits), the
+// workgroup runs plain LSD radix passes over all the low bits instead.
+constexpr int BUCKET_GROUP_BITS = 9;
+constexpr int BUCKET_GROUP_MAX = 64;  // longest group the insertion sort is allowed
+
 template <typename K, bool HAS_VAL, int BUCKET_THREADS, int BUCKET_ITEMS>
 __global__ __launch_bounds__(BUCKET_THREADS) void bucket_sort_kernel(K* __restrict__ kin, K* __restrict__ kout,
                                                                      u32* __restrict__ vin, u32* __restrict__ vout,
@@ -415,10 +456,12 @@ __global__ __launch_bounds__(BUCKET_THREADS) void bucket_sort_kernel(K* __restri
                                                                      int low_bits) {
     constexpr int BUCKET_WAVES = BUCKET_THREADS / 64;
     constexpr int BUCKET_CAP = BUCKET_THREADS * BUCKET_ITEMS;  // keys of one bucket held in LDS
+    constexpr int RMAX = 1 << BUCKET_GROUP_BITS;
+    static_assert(RMAX <= BUCKET_THREADS, "one thread per digit in the scans below");
     __shared__ K skey[BUCKET_CAP];
     __shared__ u32 sval[HAS_VAL ? BUCKET_CAP : 1];
-    __shared__ u32 wcnt[BUCKET_WAVES][256];
-    __shared__ u32 tstart[256];
+    __shared__ u32 wcnt[BUCKET_WAVES][RMAX];
+    __shared__ u32 tstart[RMAX];
     __shared__ u32 smem[BUCKET_WAVES];
     const int t = threadIdx.x, w = wave_id(), lane = lane_id();
     const int bkt = blockIdx.x;
@@ -445,54 +488,42 @@ __global__ __launch_bounds__(BUCKET_THREADS) void bucket_sort_kernel(K* __restri
         }
         return;
     }
+    kin += start;
+    kout += start;
+    if (HAS_VAL) {
+        vin += start;
+        vout += start;
+    }
 
     const int items = (cnt + BUCKET_THREADS - 1) / BUCKET_THREADS;  // <= BUCKET_ITEMS, same for the whole workgroup
-    for (int i = t; i < cnt; i += BUCKET_THREADS) {
-        skey[i] = kin[start + i];
-        if (HAS_VAL) sval[i] = vin[start + i];
-    }
-    __syncthreads();
 
-    const int passes = (low_bits + 7) / 8;
-    const int per = (low_bits + passes - 1) / passes;
-    const u64 lt = lanemask_lt();
-    int shift = 0;
-    for (int p = 0; p < passes; ++p) {
-        const int bits = (low_bits - shift) < per ? (low_bits - shift) : per;
+    // One stable pass on key bits [shift, shift + bits): the keys come from memory (FROM_MEMORY) or
+    // from skey, in index order = (wave, item, lane), and land in skey/sval; tstart[d] = first
+    // position of digit d afterwards.
+    auto radix_pass = [&](auto from_memory, int shift, int bits) {
+        constexpr bool FROM_MEMORY = decltype(from_memory)::value;
         const u32 R = 1u << bits, dmask = R - 1;
-        for (int i = t; i < BUCKET_WAVES * 256; i += BUCKET_THREADS)
-            if ((u32)(i & 255) < R) (&wcnt[0][0])[i] = 0;
+        for (int i = t; i < BUCKET_WAVES * RMAX; i += BUCKET_THREADS)
+            if ((u32)(i & (RMAX - 1)) < R) (&wcnt[0][0])[i] = 0;
         K key[BUCKET_ITEMS];
         u32 val[BUCKET_ITEMS];
         u32 rank[BUCKET_ITEMS];
+        u32 digit[BUCKET_ITEMS];
 #pragma unroll
         for (int i = 0; i < BUCKET_ITEMS; ++i) {
+            key[i] = (K) ~(K)0;  // padding ranks last and is dropped
+            val[i] = 0u;
             if (i < items) {
-                const int idx = w * (64 * items) + i * 64 + lane;  // index order = (wave, item, lane)
-                const bool ok = idx < cnt;
-                key[i] = ok ? skey[idx] : (K) ~(K)0;
-                if (HAS_VAL) val[i] = ok ? sval[idx] : 0u;
+                const int idx = w * (64 * items) + i * 64 + lane;
+                if (idx < cnt) {
+                    key[i] = FROM_MEMORY ? kin[idx] : skey[idx];
+                    if (HAS_VAL) val[i] = FROM_MEMORY ? vin[idx] : sval[idx];
+                }
             }
+            digit[i] = digit_of<K>(key[i], shift, dmask);
         }
         __syncthreads();
-#pragma unroll
-        for (int i = 0; i < BUCKET_ITEMS; ++i) {
-            if (i < items) {
-                const u32 d = digit_of<K>(key[i], shift, dmask);
-                u64 m = ~0ull;
-                for (int b = 0; b < bits; ++b) {
-                    const bool bit = (d >> b) & 1u;
-                    const u64 bal = __ballot(bit);
-                    m &= bit ? bal : ~bal;
-                }
-                const u32 old = wcnt[w][d];
-                const u32 below = (u32)__popcll(m & lt);
-                __builtin_amdgcn_wave_barrier();
-                if (below == 0) wcnt[w][d] = old + (u32)__popcll(m);
-                __builtin_amdgcn_wave_barrier();
-                rank[i] = old + below;
-            }
-        }
+        wave_rank_digits<BUCKET_ITEMS>(digit, items, bits, wcnt[w], rank);
         __syncthreads();
         u32 dtot = 0;
         if ((u32)t < R) {
@@ -511,25 +542,59 @@ __global__ __launch_bounds__(BUCKET_THREADS) void bucket_sort_kernel(K* __restri
 #pragma unroll
         for (int i = 0; i < BUCKET_ITEMS; ++i) {
             if (i < items) {
-                const u32 d = digit_of<K>(key[i], shift, dmask);
-                const u32 pos = tstart[d] + wcnt[w][d] + rank[i];
-                if (pos < (u32)cnt) {  // padding (all-ones keys) ranks last and is dropped
+                const u32 pos = tstart[digit[i]] + wcnt[w][digit[i]] + rank[i];
+                if (pos < (u32)cnt) {
                     skey[pos] = key[i];
                     if (HAS_VAL) sval[pos] = val[i];
                 }
             }
         }
         __syncthreads();
-        shift += bits;
+    };
+
+    const int gbits = low_bits < BUCKET_GROUP_BITS ? low_bits : BUCKET_GROUP_BITS;
+    const int rest = low_bits - gbits;
+    radix_pass(std::true_type{}, rest, gbits);
+    if (rest > 0) {
+        // groups: positions [tstart[d], tstart[d + 1]) (the last one ends at cnt)
+        const int ngroups = 1 << gbits;
+        int gs = 0, ge = 0;
+        if (t < ngroups) {
+            gs = (int)tstart[t];
+            ge = t + 1 < ngroups ? (int)tstart[t + 1] : cnt;
+            if (ge > cnt) ge = cnt;
+        }
+        if (!__syncthreads_or(ge - gs > BUCKET_GROUP_MAX)) {
+            for (int i = gs + 1; i < ge; ++i) {
+                const K k = skey[i];
+                const u32 v = HAS_VAL ? sval[i] : 0u;
+                int j = i;
+                while (j > gs && skey[j - 1] > k) {
+                    skey[j] = skey[j - 1];
+                    if (HAS_VAL) sval[j] = sval[j - 1];
+                    --j;
+                }
+                skey[j] = k;
+                if (HAS_VAL) sval[j] = v;
+            }
+            __syncthreads();
+        } else {
+            const int passes = (low_bits + 7) / 8;
+            const int per = (low_bits + passes - 1) / passes;
+            int shift = 0;
+            for (int p = 0; p < passes; ++p) {
+                const int bits = (low_bits - shift) < per ? (low_bits - shift) : per;
+                radix_pass(std::false_type{}, shift, bits);
+                shift += bits;
+            }
+        }
     }
     for (int i = t; i < cnt; i += BUCKET_THREADS) {
-        kout[start + i] = skey[i];
-        if (HAS_VAL) vout[start + i] = sval[i];
+        kout[i] = skey[i];
+        if (HAS_VAL) vout[i] = sval[i];
     }
 }
 
-// Stable sort on key bits [0, key_bits) for n <= BUCKET_SORT_MAX_KEYS keys with
-// evenly spread leading bits.  The result is always in (k0, v0): returns 0, or <0 on a launch error.
 // `counted`: the producer of the keys has already filled sc.table with the per-tile counts of the
 // top digit (tiles of BLOCK * SORT_ITEMS_SMALL keys, digit = bits [bucket_sort_low_bits, key_bits)),
 // as radix_upsweep_kernel would, so that pass over the keys is skipped.
