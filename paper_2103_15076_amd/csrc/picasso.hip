@@ -504,6 +504,80 @@ __global__ __launch_bounds__(BLOCK) void select_subround_kernel(SelArgs A, int k
     }
 }
 
+// The same sub-round for large rounds once most edges are retired (every sub-round but the
+// first).  One lane per edge would then spend a wave, and a trip to memory, on every 64 state
+// bytes; here a lane reads the state of 16 consecutive edges at once, the wave lists its live
+// edges in LDS in ascending order (1024 edges per wave), and the lanes then work through that
+// list 64 edges at a time exactly as above.
+constexpr int SPARSE_MIN_EDGES = 1 << 20;  // below this the one-lane-per-edge kernel is at its launch floor anyway
+
+template <int SPARSE_EDGES_PER_LANE>  // 4 while about a third of the edges are live, 16 later
+__global__ __launch_bounds__(BLOCK) void select_subround_sparse_kernel(SelArgs A, int k) {
+    static_assert(SPARSE_EDGES_PER_LANE == 4 || SPARSE_EDGES_PER_LANE == 16, "one 4- or 16-byte load per lane");
+    constexpr int PER_WAVE = 64 * SPARSE_EDGES_PER_LANE;
+    __shared__ int slist[prim::WAVES][PER_WAVE];
+    const u64* __restrict__ cur = A.vmin[k % 3];
+    u64* __restrict__ nxt = A.vmin[(k + 1) % 3];
+    u64* __restrict__ rst = A.vmin[(k + 2) % 3];
+    const int n = A.st->ne;
+    if (blockIdx.x == 0 && threadIdx.x == 0) A.st->sel_k = k + 1;
+    const int lane = prim::lane_id(), w = prim::wave_id();
+    int* list = slist[w];
+    for (long long cbase = ((long long)blockIdx.x * prim::WAVES + w) * PER_WAVE; cbase < n;
+         cbase += (long long)gridDim.x * prim::WAVES * PER_WAVE) {
+        const long long b0 = cbase + (long long)lane * SPARSE_EDGES_PER_LANE;
+        u32 sw[4] = {0x01010101u, 0x01010101u, 0x01010101u, 0x01010101u};  // "retired" beyond the end
+        if (b0 + SPARSE_EDGES_PER_LANE <= n) {
+            if constexpr (SPARSE_EDGES_PER_LANE == 16) {
+                const uint4 q = *reinterpret_cast<const uint4*>(A.estate + b0);
+                sw[0] = q.x; sw[1] = q.y; sw[2] = q.z; sw[3] = q.w;
+            } else {
+                sw[0] = *reinterpret_cast<const u32*>(A.estate + b0);
+            }
+        } else {
+            for (int j = 0; j < SPARSE_EDGES_PER_LANE; ++j)
+                if (b0 + j < n && A.estate[b0 + j] == 0) sw[j >> 2] &= ~(0xFFu << (8 * (j & 3)));
+        }
+        u32 livebits = 0;
+#pragma unroll
+        for (int j = 0; j < SPARSE_EDGES_PER_LANE; ++j)
+            if (((sw[j >> 2] >> (8 * (j & 3))) & 0xFFu) == 0) livebits |= 1u << j;
+        const int c = __popc(livebits);
+        int incl = c;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int o = __shfl_up(incl, d, 64);
+            if (lane >= d) incl += o;
+        }
+        const int total = __shfl(incl, 63, 64);
+        int pos = incl - c;
+        while (livebits) {
+            const int j = __ffs((int)livebits) - 1;
+            livebits &= livebits - 1;
+            list[pos++] = (int)(b0 + j);
+        }
+        __builtin_amdgcn_wave_barrier();  // (a wave's LDS operations complete in order)
+        for (int q = 0; q < total; q += 64) {
+            const bool has = q + lane < total;
+            const int i = has ? list[q + lane] : 0;
+            bool alive = false, sel = false;
+            int u = 0, v = 0, m = 0;
+            u64 p = 0;
+            if (has) alive = subround_edge<false>(A, cur, k, i, u, v, m, p, sel);
+            count_pairs(A, sel, m);
+            if (alive) {
+                atomicMin(&nxt[v], p);
+                rst[u] = VMIN_NONE;
+                rst[v] = VMIN_NONE;
+            } else if (has) {
+                A.estate[i] = 1;
+            }
+            bid_grouped(nxt, alive, u, p);
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
 struct LivePred {
     const unsigned char* estate;
     __device__ bool operator()(int e) const { return estate[e] == 0; }
@@ -1539,8 +1613,14 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
             int wide = 0;
             for (long long l = live_est; l > TAIL_MAX; ++wide) l = l * 10 / decay_x10[std::min(wide, 5)];
             wide = std::min<int>(wide, (int)std::max<int64_t>(1, c->opt_subround_batch));
-            for (int j = 0; j < wide; ++j)
-                select_subround_kernel<<<grid_for(ne_bound, 1 << 16), BLOCK, 0, s>>>(sa, sel_k + j);
+            for (int j = 0; j < wide; ++j) {
+                if (sel_k + j == 1 && ne_bound >= SPARSE_MIN_EDGES)
+                    select_subround_sparse_kernel<4><<<(ne_bound + BLOCK * 4 - 1) / (BLOCK * 4), BLOCK, 0, s>>>(sa, sel_k + j);
+                else if (sel_k + j > 1 && ne_bound >= SPARSE_MIN_EDGES)
+                    select_subround_sparse_kernel<16><<<(ne_bound + BLOCK * 16 - 1) / (BLOCK * 16), BLOCK, 0, s>>>(sa, sel_k + j);
+                else
+                    select_subround_kernel<<<grid_for(ne_bound, 1 << 16), BLOCK, 0, s>>>(sa, sel_k + j);
+            }
             sel_k += wide;
             LivePred lp{c->estate};
             LiveOut lo{c->list};
