@@ -628,9 +628,15 @@ inline int bucket_sort(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int*
 constexpr int BUCKET_LARGE_MSD_BITS = 12;
 constexpr long long BUCKET_SORT_LARGE_MAX_KEYS = 1ll << 23;
 
+// Histogram of the top 12-bit digit over the whole input (added to `hist`, which starts at zero),
+// and from the same read of the keys the first partition pass's per-tile counts of the digit's
+// low 6 bits (table[d6 * T + tile], what radix_upsweep_kernel would compute for bits
+// [shift, shift + 6)).  Keys made from mesh indices often share their leading bits across a
+// whole wave; such a wave counts itself with a single LDS atomic.
 template <typename K>
 __global__ __launch_bounds__(BLOCK) void top_digit_histogram_kernel(const K* __restrict__ kin, const int* n_ptr,
-                                                                    int n_host, u32* __restrict__ hist, int shift) {
+                                                                    int n_host, u32* __restrict__ hist, int shift, int T,
+                                                                    u32* __restrict__ table) {
     constexpr int R = 1 << BUCKET_LARGE_MSD_BITS;
     constexpr int TILE = BLOCK * SORT_ITEMS_BIG;
     __shared__ u32 h[R];
@@ -643,12 +649,26 @@ __global__ __launch_bounds__(BLOCK) void top_digit_histogram_kernel(const K* __r
 #pragma unroll 4
     for (int i = 0; i < SORT_ITEMS_BIG; ++i) {
         const long long idx = base + (long long)i * BLOCK + t;
-        if (idx < n) atomicAdd(&h[digit_of<K>(kin[idx], shift, R - 1)], 1u);
+        const bool ok = idx < n;
+        const u32 d = ok ? digit_of<K>(kin[idx], shift, R - 1) : 0u;
+        const u64 on = __ballot(ok);
+        if (on == 0) continue;
+        const u32 d0 = (u32)__builtin_amdgcn_readfirstlane((int)d);  // (of the first lane with a key)
+        if (__ballot(ok && d == d0) == on) {
+            if (ok && (on & lanemask_lt()) == 0) atomicAdd(&h[d0], (u32)__popcll(on));
+        } else if (ok) {
+            atomicAdd(&h[d], 1u);
+        }
     }
     __syncthreads();
     for (int i = t; i < R; i += BLOCK) {
         const u32 c = h[i];
         if (c) atomicAdd(&hist[i], c);
+    }
+    if (t < 64) {
+        u32 sum = 0;
+        for (int hi = 0; hi < 64; ++hi) sum += h[(hi << 6) | t];
+        table[(size_t)t * T + blockIdx.x] = sum;
     }
 }
 
@@ -665,14 +685,15 @@ inline int bucket_sort_large(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, cons
     const int low = key_bits - BUCKET_LARGE_MSD_BITS;
     const int tiles = sort_tiles(n_max, SORT_ITEMS_BIG);
     fill_u32_kernel<<<R / BLOCK, BLOCK, 0, s>>>(hist12, R, 0u);
-    top_digit_histogram_kernel<K><<<tiles, BLOCK, 0, s>>>(k0, n_ptr, n_max, hist12, low);
+    top_digit_histogram_kernel<K><<<tiles, BLOCK, 0, s>>>(k0, n_ptr, n_max, hist12, low, sc.T, sc.table);
     K* kin = k0;
     K* kout = k1;
     u32* vin = v0;
     u32* vout = v1;
     for (int half = 0; half < 2; ++half) {
         const int shift = low + 6 * half;
-        radix_upsweep_kernel<K, SORT_ITEMS_BIG><<<tiles, BLOCK, 0, s>>>(kin, n_ptr, n_max, sc.T, sc.table, shift, 6);
+        if (half == 1)  // (the histogram kernel has left the first pass's counts)
+            radix_upsweep_kernel<K, SORT_ITEMS_BIG><<<tiles, BLOCK, 0, s>>>(kin, n_ptr, n_max, sc.T, sc.table, shift, 6);
         radix_scan_kernel<<<64, BLOCK, 0, s>>>(sc.table, sc.totals, n_ptr, n_max, sc.T, BLOCK * SORT_ITEMS_BIG);
         radix_downsweep_kernel<K, HAS_VAL, SORT_ITEMS_BIG>
             <<<tiles, BLOCK, 0, s>>>(kin, kout, vin, vout, n_ptr, n_max, sc.T, sc.table, sc.totals, shift, 6);
