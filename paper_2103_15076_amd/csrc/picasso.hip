@@ -239,19 +239,26 @@ __device__ __forceinline__ void round_begin_block(const RoundTab& R, int cur, St
 //
 // First kernel of a round: the round's set-up (block 0), the per-vertex selection state, and one
 // 64-bit key (lower vertex, higher vertex) per half-edge, key i for corner i of the facet array.
-// With COUNT the workgroups walk the keys in the tiles of the sort that follows and also leave
-// that sort's first per-tile digit counts in `table` (the layout of prim::radix_upsweep_kernel),
-// which saves the sort its first pass over the keys.
+// The workgroups walk the keys in the tiles of the sort that follows and leave what that sort's
+// first pass over the keys would compute, so the sort starts without it:
+//   COUNT_SMALL  per-tile counts of the top digit (prim::radix_upsweep_kernel's table), for
+//                prim::bucket_sort;
+//   COUNT_LARGE  the 12-bit histogram and the per-tile counts of its low 6 bits
+//                (prim::top_digit_histogram_kernel's outputs; hist12 zeroed beforehand), for
+//                prim::bucket_sort_large.
 // ---------------------------------------------------------------------------
-template <bool COUNT>
+enum { COUNT_NONE = 0, COUNT_SMALL = 1, COUNT_LARGE = 2 };
+
+template <int COUNT>
 __global__ __launch_bounds__(BLOCK) void edge_keys_kernel(const int* __restrict__ fcur, State* st, int cur, int vbits,
                                                           u64* __restrict__ keys, u64* __restrict__ vmin0,
                                                           u64* __restrict__ vmin1, int* __restrict__ mate,
                                                           RoundTab R, int T, u32* __restrict__ table, int shift,
-                                                          int bits) {
-    constexpr int ITEMS = prim::SORT_ITEMS_SMALL;
+                                                          int bits, u32* __restrict__ hist12) {
+    constexpr int ITEMS = COUNT == COUNT_LARGE ? prim::SORT_ITEMS_BIG : prim::SORT_ITEMS_SMALL;
     constexpr int TILE = BLOCK * ITEMS;
-    __shared__ u32 hist[COUNT ? prim::WAVES : 1][256];
+    constexpr int R12 = 1 << prim::BUCKET_LARGE_MSD_BITS;
+    __shared__ u32 hist[COUNT == COUNT_LARGE ? R12 : (COUNT == COUNT_SMALL ? prim::WAVES * 256 : 1)];
     const int nf = st->nf[cur], nv = st->nv[cur];
     const long long n = 3ll * nf;
     const int stride = gridDim.x * BLOCK;
@@ -264,31 +271,63 @@ __global__ __launch_bounds__(BLOCK) void edge_keys_kernel(const int* __restrict_
     }
     if (blockIdx.x == 0) round_begin_block(R, cur, st);
     const u32 dmask = (1u << bits) - 1u;
-    const u32 copy = COUNT ? (((u32)prim::lane_id() & ((256u >> bits) - 1u)) << bits) : 0u;
+    const u32 copy = COUNT == COUNT_SMALL ? (((u32)prim::lane_id() & ((256u >> bits) - 1u)) << bits) : 0u;
     for (long long tile = blockIdx.x; tile * TILE < n; tile += gridDim.x) {
-        if constexpr (COUNT) {
-            for (int i = t; i < prim::WAVES * 256; i += BLOCK) (&hist[0][0])[i] = 0;
+        if constexpr (COUNT != COUNT_NONE) {
+            constexpr int HN = COUNT == COUNT_LARGE ? R12 : prim::WAVES * 256;
+            for (int i = t; i < HN; i += BLOCK) hist[i] = 0;
             __syncthreads();
         }
-#pragma unroll
+#pragma unroll 4
         for (int i = 0; i < ITEMS; ++i) {
             const long long idx = tile * TILE + (long long)i * BLOCK + t;
-            if (idx < n) {
+            const bool ok = idx < n;
+            u64 k = 0;
+            if (ok) {
                 const int f = (int)(idx / 3), sl = (int)(idx - 3ll * f);
                 const int a = fcur[idx], b = fcur[3 * (size_t)f + (sl == 2 ? 0 : sl + 1)];
                 const int lo = min(a, b), hi = max(a, b);
-                const u64 k = (lo == hi) ? sentinel : (((u64)(u32)lo << vbits) | (u64)(u32)hi);
+                k = (lo == hi) ? sentinel : (((u64)(u32)lo << vbits) | (u64)(u32)hi);
                 keys[idx] = k;
-                if constexpr (COUNT) atomicAdd(&hist[prim::wave_id()][copy | ((u32)(k >> shift) & dmask)], 1u);
+            }
+            if constexpr (COUNT == COUNT_SMALL) {
+                if (ok) atomicAdd(&hist[prim::wave_id() * 256 + (copy | ((u32)(k >> shift) & dmask))], 1u);
+            }
+            if constexpr (COUNT == COUNT_LARGE) {
+                // the lower vertices of neighbouring corners mostly share their leading bits: a wave
+                // whose keys all have one digit counts itself with a single LDS atomic
+                const u32 d = (u32)(k >> shift) & (u32)(R12 - 1);
+                const u64 on = __ballot(ok);
+                if (on != 0) {
+                    const u32 d0 = (u32)__builtin_amdgcn_readfirstlane((int)d);
+                    if (__ballot(ok && d == d0) == on) {
+                        if (ok && (on & prim::lanemask_lt()) == 0) atomicAdd(&hist[d0], (u32)__popcll(on));
+                    } else if (ok) {
+                        atomicAdd(&hist[d], 1u);
+                    }
+                }
             }
         }
-        if constexpr (COUNT) {
+        if constexpr (COUNT == COUNT_SMALL) {
             static_assert(prim::WAVES == 4, "four per-wave histograms are summed below");
             __syncthreads();
             const u32 radix = 1u << bits;
             if ((u32)t < radix) {
                 u32 sum = 0;
-                for (u32 c = (u32)t; c < 256u; c += radix) sum += hist[0][c] + hist[1][c] + hist[2][c] + hist[3][c];
+                for (u32 c = (u32)t; c < 256u; c += radix) sum += hist[c] + hist[256 + c] + hist[512 + c] + hist[768 + c];
+                table[(size_t)t * T + tile] = sum;
+            }
+            __syncthreads();
+        }
+        if constexpr (COUNT == COUNT_LARGE) {
+            __syncthreads();
+            for (int i = t; i < R12; i += BLOCK) {
+                const u32 c = hist[i];
+                if (c) atomicAdd(&hist12[i], c);
+            }
+            if (t < 64) {
+                u32 sum = 0;
+                for (int hi6 = 0; hi6 < 64; ++hi6) sum += hist[(hi6 << 6) | t];
                 table[(size_t)t * T + tile] = sum;
             }
             __syncthreads();
@@ -1381,14 +1420,24 @@ struct StageTimer {
 
 // Sort for keys whose leading bits are vertex ids (evenly spread): bucket sort
 // when the input is small enough for it, plain LSD passes otherwise.
+// which sort sort_by_vertex takes, named by the counting a producer of the keys may do for it
+inline int sort_by_vertex_path(long long n_max, int key_bits) {
+    if (n_max <= 0) return COUNT_NONE;
+    if (n_max <= prim::BUCKET_SORT_MAX_KEYS && key_bits > prim::BUCKET_MSD_BITS) return COUNT_SMALL;
+    if (n_max <= prim::BUCKET_SORT_LARGE_MAX_KEYS && key_bits > prim::BUCKET_LARGE_MSD_BITS) return COUNT_LARGE;
+    return COUNT_NONE;
+}
+
 template <typename K, bool HAS_VAL>
 int sort_by_vertex(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_ptr, int n_max, int key_bits,
                    const prim::SortScratch& sc, u32* hist12, prim::LaunchTimer* lt = nullptr, int tag = 0,
                    bool counted = false) {
-    if (n_max <= prim::BUCKET_SORT_MAX_KEYS && key_bits > prim::BUCKET_MSD_BITS)
+    const int how = sort_by_vertex_path(n_max, key_bits);
+    if (how == COUNT_SMALL)
         return prim::bucket_sort<K, HAS_VAL>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc, lt, tag, counted);
-    if (n_max <= prim::BUCKET_SORT_LARGE_MAX_KEYS && key_bits > prim::BUCKET_LARGE_MSD_BITS)
-        return prim::bucket_sort_large<K, HAS_VAL>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc, hist12, lt, tag);
+    if (how == COUNT_LARGE)
+        return prim::bucket_sort_large<K, HAS_VAL>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc, hist12, lt, tag,
+                                                   counted);
     return prim::radix_sort<K, HAS_VAL>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc, lt, tag);
 }
 
@@ -1401,15 +1450,25 @@ int issue_edge_prefix(picasso_ctx* c, hipStream_t st_, int B, int round_, int cu
     const int vbits_ = ceil_log2(nvt);
     const int H_ = 3 * nfb;
     const RoundTab rt{B, c->voff[cur_], c->target, c->active, c->stuck, c->nrem, c->matched, c->mslots, round_ == 0};
-    // inputs that go to the bucket sort get its first digit counts from the kernel that writes the keys
-    const bool counted = H_ > 0 && H_ <= prim::BUCKET_SORT_MAX_KEYS && 2 * vbits_ > prim::BUCKET_MSD_BITS;
-    if (counted)
-        edge_keys_kernel<true><<<prim::sort_tiles(H_, prim::SORT_ITEMS_SMALL), BLOCK, 0, st_>>>(
+    // the kernel that writes the keys also does the first counting pass of the sort they go to
+    const int kb = 2 * vbits_;
+    const int how = sort_by_vertex_path(H_, kb);
+    const bool counted = how != COUNT_NONE;
+    if (how == COUNT_SMALL) {
+        edge_keys_kernel<COUNT_SMALL><<<prim::sort_tiles(H_, prim::SORT_ITEMS_SMALL), BLOCK, 0, st_>>>(
             c->fbuf[cur_], c->st, cur_, vbits_, c->key64[0], c->vmin[0], c->vmin[1], c->mate, rt, c->sort_sc.T,
-            c->sort_sc.table, prim::bucket_sort_low_bits(2 * vbits_), prim::bucket_sort_msd_bits(2 * vbits_));
-    else
-        edge_keys_kernel<false><<<grid_for(std::max(3 * nfb, nvt), 8192), BLOCK, 0, st_>>>(
-            c->fbuf[cur_], c->st, cur_, vbits_, c->key64[0], c->vmin[0], c->vmin[1], c->mate, rt, 0, nullptr, 0, 8);
+            c->sort_sc.table, prim::bucket_sort_low_bits(kb), prim::bucket_sort_msd_bits(kb), nullptr);
+    } else if (how == COUNT_LARGE) {
+        prim::fill_u32_kernel<<<(1 << prim::BUCKET_LARGE_MSD_BITS) / BLOCK, BLOCK, 0, st_>>>(
+            c->hist12, 1 << prim::BUCKET_LARGE_MSD_BITS, 0u);
+        edge_keys_kernel<COUNT_LARGE><<<prim::sort_tiles(H_, prim::SORT_ITEMS_BIG), BLOCK, 0, st_>>>(
+            c->fbuf[cur_], c->st, cur_, vbits_, c->key64[0], c->vmin[0], c->vmin[1], c->mate, rt, c->sort_sc.T,
+            c->sort_sc.table, kb - prim::BUCKET_LARGE_MSD_BITS, prim::BUCKET_LARGE_MSD_BITS, c->hist12);
+    } else {
+        edge_keys_kernel<COUNT_NONE><<<grid_for(std::max(3 * nfb, nvt), 8192), BLOCK, 0, st_>>>(
+            c->fbuf[cur_], c->st, cur_, vbits_, c->key64[0], c->vmin[0], c->vmin[1], c->mate, rt, 0, nullptr, 0, 8,
+            nullptr);
+    }
     skeys = c->key64[0];
     if (H_ > 0) {
         int where = sort_by_vertex<u64, false>(st_, c->key64[0], c->key64[1], nullptr, nullptr, &c->st->nh, H_,

@@ -680,12 +680,15 @@ __global__ __launch_bounds__(BLOCK) void fill_u32_kernel(u32* __restrict__ p, in
 // Result is in (k1, v1): returns 1, or <0 on a launch error.  hist12 holds 4096 words.
 template <typename K, bool HAS_VAL>
 inline int bucket_sort_large(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_ptr, int n_max, int key_bits,
-                             const SortScratch& sc, u32* hist12, LaunchTimer* lt = nullptr, int tag = 0) {
+                             const SortScratch& sc, u32* hist12, LaunchTimer* lt = nullptr, int tag = 0,
+                             bool counted = false) {
     constexpr int R = 1 << BUCKET_LARGE_MSD_BITS;
     const int low = key_bits - BUCKET_LARGE_MSD_BITS;
     const int tiles = sort_tiles(n_max, SORT_ITEMS_BIG);
-    fill_u32_kernel<<<R / BLOCK, BLOCK, 0, s>>>(hist12, R, 0u);
-    top_digit_histogram_kernel<K><<<tiles, BLOCK, 0, s>>>(k0, n_ptr, n_max, hist12, low, sc.T, sc.table);
+    if (!counted) {  // (else the producer of the keys has left what these two kernels compute)
+        fill_u32_kernel<<<R / BLOCK, BLOCK, 0, s>>>(hist12, R, 0u);
+        top_digit_histogram_kernel<K><<<tiles, BLOCK, 0, s>>>(k0, n_ptr, n_max, hist12, low, sc.T, sc.table);
+    }
     K* kin = k0;
     K* kout = k1;
     u32* vin = v0;
