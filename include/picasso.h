@@ -84,7 +84,9 @@ size_t picasso_workspace_bytes(int64_t max_verts, int64_t max_facets, int32_t ma
 
 /* Create a context on `device` able to decimate up to max_verts vertices,
  * max_facets facets (totals over a batch) and max_meshes meshes per call.
- * Allocates the workspace once; returns PICASSO_ERR_HIP if that fails. */
+ * Limits (32-bit indices): max_verts < 2^31 - 16, max_facets <= 2^29, else
+ * PICASSO_ERR_INVALID_ARG.  Allocates the workspace and a small pinned host
+ * buffer once; returns PICASSO_ERR_HIP if that fails. */
 int picasso_create(picasso_ctx** out, int device, int64_t max_verts, int64_t max_facets, int32_t max_meshes);
 void picasso_destroy(picasso_ctx* ctx);
 int picasso_set_option(picasso_ctx* ctx, int option, int64_t value);

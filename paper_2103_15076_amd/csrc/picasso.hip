@@ -1854,7 +1854,9 @@ size_t picasso_workspace_bytes(int64_t max_verts, int64_t max_facets, int32_t ma
 
 int picasso_create(picasso_ctx** out, int device, int64_t max_verts, int64_t max_facets, int32_t max_meshes) {
     if (!out || max_verts < 1 || max_facets < 0 || max_meshes < 1) return PICASSO_ERR_INVALID_ARG;
-    if (max_verts > 0x7FFFFFF0ll || 3 * max_facets > 0x7FFFFFF0ll) return PICASSO_ERR_INVALID_ARG;
+    // 32-bit indices throughout: half-edge slots (3 per facet) and the facet hash table
+    // (next power of two above 2 * facets) must fit an int
+    if (max_verts > 0x7FFFFFF0ll || max_facets > (1ll << 29)) return PICASSO_ERR_INVALID_ARG;
     picasso_ctx* c = new (std::nothrow) picasso_ctx();
     if (!c) return PICASSO_ERR_HIP;
     c->device = device;

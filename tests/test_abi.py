@@ -64,6 +64,9 @@ def test_host_side_argument_checks_need_no_device(lib):
     assert lib.picasso_create(ctypes.byref(h), 0, 0, 10, 1) == pk.PICASSO_ERR_INVALID_ARG
     assert lib.picasso_create(ctypes.byref(h), 0, 10, 10, 0) == pk.PICASSO_ERR_INVALID_ARG
     assert lib.picasso_create(None, 0, 10, 10, 1) == pk.PICASSO_ERR_INVALID_ARG
+    # capacities beyond what 32-bit indices address are refused before anything is allocated
+    assert lib.picasso_create(ctypes.byref(h), 0, 10, (1 << 29) + 1, 1) == pk.PICASSO_ERR_INVALID_ARG
+    assert lib.picasso_create(ctypes.byref(h), 0, 1 << 31, 10, 1) == pk.PICASSO_ERR_INVALID_ARG
     assert lib.picasso_device_copy(None, None, None, 16) == pk.PICASSO_ERR_INVALID_ARG
 
 
