@@ -243,9 +243,9 @@ __device__ __forceinline__ void round_begin_block(const RoundTab& R, int cur, St
 // first pass over the keys would compute, so the sort starts without it:
 //   COUNT_SMALL  per-tile counts of the top digit (prim::radix_upsweep_kernel's table), for
 //                prim::bucket_sort;
-//   COUNT_LARGE  the 12-bit histogram and the per-tile counts of its low 6 bits
-//                (prim::top_digit_histogram_kernel's outputs; hist12 zeroed beforehand), for
-//                prim::bucket_sort_large.
+//   COUNT_LARGE  the 12-bit histogram and, if `table` is given, the per-tile counts of its low
+//                6 bits (prim::top_digit_histogram_kernel's outputs; hist12 zeroed beforehand),
+//                for prim::bucket_sort_large.
 // ---------------------------------------------------------------------------
 enum { COUNT_NONE = 0, COUNT_SMALL = 1, COUNT_LARGE = 2 };
 
@@ -325,7 +325,7 @@ __global__ __launch_bounds__(BLOCK) void edge_keys_kernel(const int* __restrict_
                 const u32 c = hist[i];
                 if (c) atomicAdd(&hist12[i], c);
             }
-            if (t < 64) {
+            if (table && t < 64) {
                 u32 sum = 0;
                 for (int hi6 = 0; hi6 < 64; ++hi6) sum += hist[(hi6 << 6) | t];
                 table[(size_t)t * T + tile] = sum;
@@ -1251,7 +1251,7 @@ struct picasso_ctx {
     unsigned char* keep = nullptr;
     int* tilesum = nullptr;
     prim::SortScratch sort_sc{};
-    u32* hist12 = nullptr;  // bucket sizes of the 4096-bucket sort
+    u32* hist12 = nullptr;  // the 4096-bucket sort's bucket sizes, first positions and cursors (3 x 4096)
     // The vertex->facet sort has buffers and scratch of its own, so that in the first round it can
     // run beside the edge-key sort (neither depends on the other) on a second stream.
     u32* s0_key[2] = {nullptr, nullptr};
@@ -1362,7 +1362,7 @@ size_t carve(picasso_ctx* c, char* base, int64_t N, int64_t F, int32_t B) {
     x->sort_sc.T = prim::sort_table_stride((long long)h);
     x->sort_sc.table = cv.take<u32>((size_t)256 * x->sort_sc.T);
     x->sort_sc.totals = cv.take<u32>(256);
-    x->hist12 = cv.take<u32>(4096);
+    x->hist12 = cv.take<u32>(3 * 4096);
     for (int i = 0; i < 2; ++i) {
         x->s0_key[i] = cv.take<u32>(h);
         x->s0_val[i] = cv.take<u32>(h);
@@ -1370,7 +1370,7 @@ size_t carve(picasso_ctx* c, char* base, int64_t N, int64_t F, int32_t B) {
     x->sort_sc_s0.T = x->sort_sc.T;
     x->sort_sc_s0.table = cv.take<u32>((size_t)256 * x->sort_sc_s0.T);
     x->sort_sc_s0.totals = cv.take<u32>(256);
-    x->hist12_s0 = cv.take<u32>(4096);
+    x->hist12_s0 = cv.take<u32>(3 * 4096);
     x->voff[1] = cv.take<int>(b + 1);
     x->nrem = cv.take<int>(b);
     x->segstart = cv.take<int>(b);
@@ -1463,7 +1463,8 @@ int issue_edge_prefix(picasso_ctx* c, hipStream_t st_, int B, int round_, int cu
             c->hist12, 1 << prim::BUCKET_LARGE_MSD_BITS, 0u);
         edge_keys_kernel<COUNT_LARGE><<<prim::sort_tiles(H_, prim::SORT_ITEMS_BIG), BLOCK, 0, st_>>>(
             c->fbuf[cur_], c->st, cur_, vbits_, c->key64[0], c->vmin[0], c->vmin[1], c->mate, rt, c->sort_sc.T,
-            c->sort_sc.table, kb - prim::BUCKET_LARGE_MSD_BITS, prim::BUCKET_LARGE_MSD_BITS, c->hist12);
+            nullptr /* keys without values: the sort needs the histogram only */, kb - prim::BUCKET_LARGE_MSD_BITS,
+            prim::BUCKET_LARGE_MSD_BITS, c->hist12);
     } else {
         edge_keys_kernel<COUNT_NONE><<<grid_for(std::max(3 * nfb, nvt), 8192), BLOCK, 0, st_>>>(
             c->fbuf[cur_], c->st, cur_, vbits_, c->key64[0], c->vmin[0], c->vmin[1], c->mate, rt, 0, nullptr, 0, 8,

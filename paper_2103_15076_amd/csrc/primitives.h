@@ -453,7 +453,8 @@ template <typename K, bool HAS_VAL, int BUCKET_THREADS, int BUCKET_ITEMS>
 __global__ __launch_bounds__(BUCKET_THREADS) void bucket_sort_kernel(K* __restrict__ kin, K* __restrict__ kout,
                                                                      u32* __restrict__ vin, u32* __restrict__ vout,
                                                                      const u32* __restrict__ totals, int nbuckets,
-                                                                     int low_bits) {
+                                                                     int low_bits,
+                                                                     const u32* __restrict__ starts = nullptr) {
     constexpr int BUCKET_WAVES = BUCKET_THREADS / 64;
     constexpr int BUCKET_CAP = BUCKET_THREADS * BUCKET_ITEMS;  // keys of one bucket held in LDS
     constexpr int RMAX = 1 << BUCKET_GROUP_BITS;
@@ -466,16 +467,19 @@ __global__ __launch_bounds__(BUCKET_THREADS) void bucket_sort_kernel(K* __restri
     const int t = threadIdx.x, w = wave_id(), lane = lane_id();
     const int bkt = blockIdx.x;
 
-    // start of this bucket = sum of the counts of the buckets before it
+    // start of this bucket = sum of the counts of the buckets before it (given, or summed here)
     (void)nbuckets;
     const int cnt = (int)totals[bkt];
     if (cnt == 0) return;
-    u32 part = 0;
-    for (int j = t; j < bkt; j += BUCKET_THREADS) part += totals[j];
-    u32 tot;
-    (void)wide_block_exclusive_scan<BUCKET_WAVES>(part, smem, tot);
-    const u32 start = tot;
-    __syncthreads();
+    u32 start;
+    if (starts) {
+        start = starts[bkt];
+    } else {
+        u32 part = 0;
+        for (int j = t; j < bkt; j += BUCKET_THREADS) part += totals[j];
+        (void)wide_block_exclusive_scan<BUCKET_WAVES>(part, smem, start);
+        __syncthreads();
+    }
     if (cnt > BUCKET_CAP) {
         bucket_sort_oversize<K, HAS_VAL, BUCKET_THREADS>(kout + start, kin + start, HAS_VAL ? vout + start : nullptr,
                                          HAS_VAL ? vin + start : nullptr, cnt, low_bits, tstart, smem);
@@ -677,7 +681,92 @@ __global__ __launch_bounds__(BLOCK) void fill_u32_kernel(u32* __restrict__ p, in
     if (i < n) p[i] = v;
 }
 
-// Result is in (k1, v1): returns 1, or <0 on a launch error.  hist12 holds 4096 words.
+// starts[d] = cursor[d] = number of keys whose 12-bit digit is below d (one workgroup).
+__global__ __launch_bounds__(1024) void digit_starts_kernel(const u32* __restrict__ hist, u32* __restrict__ starts,
+                                                            u32* __restrict__ cursor) {
+    constexpr int R = 1 << BUCKET_LARGE_MSD_BITS;
+    constexpr int PER = R / 1024;
+    __shared__ u32 smem[16];
+    const int t = threadIdx.x;
+    u32 c[PER], sum = 0;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+        c[j] = hist[t * PER + j];
+        sum += c[j];
+    }
+    u32 tot;
+    u32 run = wide_block_exclusive_scan<16>(sum, smem, tot);
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+        starts[t * PER + j] = run;
+        cursor[t * PER + j] = run;
+        run += c[j];
+    }
+}
+
+// Partition of keys WITHOUT values by their 12-bit digit (bits [shift, shift + 12)) in one pass:
+// every tile counts its keys per digit in LDS, reserves room for them in each digit's range with
+// one returning atomic per digit it holds (cursor[d] starts at the digit's first position), and
+// writes its keys there.  The order of the keys inside a digit's range depends on the order in
+// which tiles arrive, so this is for sorts that then order each range on the whole key; with
+// equal keys indistinguishable the final result does not depend on it.  A wave whose keys share
+// one digit (the common case for keys led by mesh indices) ranks itself with one LDS atomic and
+// writes one contiguous run.
+template <typename K>
+__global__ __launch_bounds__(BLOCK) void msd_scatter_kernel(const K* __restrict__ kin, K* __restrict__ kout,
+                                                            const int* n_ptr, int n_host, int shift,
+                                                            u32* __restrict__ cursor) {
+    constexpr int R = 1 << BUCKET_LARGE_MSD_BITS;
+    constexpr int ITEMS = SORT_ITEMS_BIG;
+    constexpr int TILE = BLOCK * ITEMS;
+    __shared__ u32 h[R];  // per digit: this tile's count, then where the tile's keys of that digit go
+    const int n = load_count(n_ptr, n_host);
+    const long long base = (long long)blockIdx.x * TILE;
+    if (base >= n) return;
+    const int t = threadIdx.x, w = wave_id(), lane = lane_id();
+    const u64 lt = lanemask_lt();
+    for (int i = t; i < R; i += BLOCK) h[i] = 0;
+    __syncthreads();
+    K key[ITEMS];
+    u32 rk[ITEMS];
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        const long long idx = base + (long long)w * (64 * ITEMS) + i * 64 + lane;
+        key[i] = idx < n ? kin[idx] : (K)0;
+    }
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        const long long idx = base + (long long)w * (64 * ITEMS) + i * 64 + lane;
+        const bool ok = idx < n;
+        const u32 d = digit_of<K>(key[i], shift, R - 1);
+        const u64 on = __ballot(ok);
+        rk[i] = 0;
+        if (on == 0) continue;
+        const int first = __ffsll((long long)on) - 1;
+        const u32 d0 = (u32)__shfl((int)d, first, 64);
+        if (__ballot(ok && d == d0) == on) {
+            u32 b = 0;
+            if (lane == first) b = atomicAdd(&h[d0], (u32)__popcll(on));
+            rk[i] = (u32)__shfl((int)b, first, 64) + (u32)__popcll(on & lt);
+        } else if (ok) {
+            rk[i] = atomicAdd(&h[d], 1u);
+        }
+    }
+    __syncthreads();
+    for (int d = t; d < R; d += BLOCK) {
+        const u32 c = h[d];
+        if (c) h[d] = atomicAdd(&cursor[d], c);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        const long long idx = base + (long long)w * (64 * ITEMS) + i * 64 + lane;
+        if (idx < n) kout[h[digit_of<K>(key[i], shift, R - 1)] + rk[i]] = key[i];
+    }
+}
+
+// Result is in (k1, v1): returns 1 (keys with values), or in k0: returns 0 (keys only); <0 on a
+// launch error.  hist12 holds 3 x 4096 words (counts, first positions, cursors).
 template <typename K, bool HAS_VAL>
 inline int bucket_sort_large(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_ptr, int n_max, int key_bits,
                              const SortScratch& sc, u32* hist12, LaunchTimer* lt = nullptr, int tag = 0,
@@ -688,6 +777,19 @@ inline int bucket_sort_large(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, cons
     if (!counted) {  // (else the producer of the keys has left what these two kernels compute)
         fill_u32_kernel<<<R / BLOCK, BLOCK, 0, s>>>(hist12, R, 0u);
         top_digit_histogram_kernel<K><<<tiles, BLOCK, 0, s>>>(k0, n_ptr, n_max, hist12, low, sc.T, sc.table);
+    }
+    if constexpr (!HAS_VAL) {
+        // keys only: one unordered partition pass, then each bucket is ordered on the whole key
+        u32* starts = hist12 + R;
+        u32* cursor = hist12 + 2 * R;
+        digit_starts_kernel<<<1, 1024, 0, s>>>(hist12, starts, cursor);
+        msd_scatter_kernel<K><<<tiles, BLOCK, 0, s>>>(k0, k1, n_ptr, n_max, low, cursor);
+        const bool timed = lt && lt->begin(s, tag);
+        bucket_sort_kernel<K, false, BUCKET_THREADS_4096, 8>
+            <<<R, BUCKET_THREADS_4096, 0, s>>>(k1, k0, nullptr, nullptr, hist12, R, low, starts);
+        if (timed) lt->end(s);
+        if (hipGetLastError() != hipSuccess) return -1;
+        return 0;
     }
     K* kin = k0;
     K* kout = k1;

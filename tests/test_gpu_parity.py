@@ -405,6 +405,23 @@ def test_single_stream_and_two_stream_first_round_agree(pk, ctx):
     assert all(r == res[0] for r in res[1:])
 
 
+def test_large_mesh_with_scrambled_numbering(ctx, oracle):
+    """Vertex ids and facet order of a 400k-vertex scene are permuted at random, so neighbouring corners
+    of the facet array share no leading index bits: the sorts lose the locality their fast paths use
+    (waves whose keys fall into one bucket) and must give the same mesh all the same."""
+    V, F, _ = meshgen.room_scene_sized(77, 400_000)
+    rng = np.random.default_rng(123)
+    perm = rng.permutation(V.shape[0])          # new id of old vertex i
+    V2 = np.empty_like(V)
+    V2[perm] = V
+    F2 = perm[F].astype(np.int32)[rng.permutation(F.shape[0])]
+    target = V.shape[0] // 3
+    print(f"scrambled: N={V2.shape[0]} F={F2.shape[0]} target={target}", flush=True)
+    st, vo, fo, cid = ctx.picasso_decimate(dev(V2), dev(F2), target)
+    print("  gpu done; oracle...", flush=True)
+    assert_same_result(st, vo, fo, cid, oracle.decimate(V2, F2, target))
+
+
 def test_config_batch_hierarchy(ctx, oracle):
     """16 room meshes through 4 successive levels, each to 40 % of the vertices;
     the cluster maps of all levels are kept and compared."""
