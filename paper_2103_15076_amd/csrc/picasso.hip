@@ -96,9 +96,12 @@ __global__ __launch_bounds__(BLOCK) void init_kernel(const float* __restrict__ v
                                                      const int* __restrict__ voff, const int* __restrict__ foff,
                                                      VRec* __restrict__ vrec, int* __restrict__ cid,
                                                      int* __restrict__ fcur, u32* __restrict__ ikey,
-                                                     u32* __restrict__ ival, State* st) {
+                                                     u32* __restrict__ ival, State* st,
+                                                     u32* __restrict__ msd_hist) {
     const int stride = gridDim.x * BLOCK;
     const int g = blockIdx.x * BLOCK + threadIdx.x;
+    // the edge-key sort's digit counts and cursors start every round at zero (see edge_keys_kernel)
+    for (int i = g; i < 2 * prim::MSD_HIST_WORDS; i += stride) msd_hist[i] = 0;
     int err = 0;
     for (int w = g; w < N; w += stride) {
         float x = verts[3 * (size_t)w], y = verts[3 * (size_t)w + 1], z = verts[3 * (size_t)w + 2];
@@ -239,13 +242,9 @@ __device__ __forceinline__ void round_begin_block(const RoundTab& R, int cur, St
 //
 // First kernel of a round: the round's set-up (block 0), the per-vertex selection state, and one
 // 64-bit key (lower vertex, higher vertex) per half-edge, key i for corner i of the facet array.
-// The workgroups walk the keys in the tiles of the sort that follows and leave what that sort's
-// first pass over the keys would compute, so the sort starts without it:
-//   COUNT_SMALL  per-tile counts of the top digit (prim::radix_upsweep_kernel's table), for
-//                prim::bucket_sort;
-//   COUNT_LARGE  the 12-bit histogram and, if `table` is given, the per-tile counts of its low
-//                6 bits (prim::top_digit_histogram_kernel's outputs; hist12 zeroed beforehand),
-//                for prim::bucket_sort_large.
+// With COUNT_SMALL / COUNT_LARGE the kernel also adds the keys' top 8- / 12-bit digits to the
+// histogram that the sort of the keys starts from (prim::bucket_sort / prim::bucket_sort_large
+// with `counted`; zeroed beforehand), so the sort needs no counting pass of its own.
 // ---------------------------------------------------------------------------
 enum { COUNT_NONE = 0, COUNT_SMALL = 1, COUNT_LARGE = 2 };
 
@@ -253,12 +252,11 @@ template <int COUNT>
 __global__ __launch_bounds__(BLOCK) void edge_keys_kernel(const int* __restrict__ fcur, State* st, int cur, int vbits,
                                                           u64* __restrict__ keys, u64* __restrict__ vmin0,
                                                           u64* __restrict__ vmin1, int* __restrict__ mate,
-                                                          RoundTab R, int T, u32* __restrict__ table, int shift,
-                                                          int bits, u32* __restrict__ hist12) {
+                                                          RoundTab R, int shift, u32* __restrict__ msd_hist) {
     constexpr int ITEMS = COUNT == COUNT_LARGE ? prim::SORT_ITEMS_BIG : prim::SORT_ITEMS_SMALL;
     constexpr int TILE = BLOCK * ITEMS;
-    constexpr int R12 = 1 << prim::BUCKET_LARGE_MSD_BITS;
-    __shared__ u32 hist[COUNT == COUNT_LARGE ? R12 : (COUNT == COUNT_SMALL ? prim::WAVES * 256 : 1)];
+    constexpr int RADIX = COUNT == COUNT_LARGE ? (1 << prim::BUCKET_LARGE_MSD_BITS) : (1 << prim::BUCKET_MSD_BITS);
+    __shared__ u32 hist[COUNT != COUNT_NONE ? RADIX : 1];
     const int nf = st->nf[cur], nv = st->nv[cur];
     const long long n = 3ll * nf;
     const int stride = gridDim.x * BLOCK;
@@ -270,12 +268,9 @@ __global__ __launch_bounds__(BLOCK) void edge_keys_kernel(const int* __restrict_
         mate[w] = -1;
     }
     if (blockIdx.x == 0) round_begin_block(R, cur, st);
-    const u32 dmask = (1u << bits) - 1u;
-    const u32 copy = COUNT == COUNT_SMALL ? (((u32)prim::lane_id() & ((256u >> bits) - 1u)) << bits) : 0u;
     for (long long tile = blockIdx.x; tile * TILE < n; tile += gridDim.x) {
         if constexpr (COUNT != COUNT_NONE) {
-            constexpr int HN = COUNT == COUNT_LARGE ? R12 : prim::WAVES * 256;
-            for (int i = t; i < HN; i += BLOCK) hist[i] = 0;
+            for (int i = t; i < RADIX; i += BLOCK) hist[i] = 0;
             __syncthreads();
         }
 #pragma unroll 4
@@ -290,13 +285,10 @@ __global__ __launch_bounds__(BLOCK) void edge_keys_kernel(const int* __restrict_
                 k = (lo == hi) ? sentinel : (((u64)(u32)lo << vbits) | (u64)(u32)hi);
                 keys[idx] = k;
             }
-            if constexpr (COUNT == COUNT_SMALL) {
-                if (ok) atomicAdd(&hist[prim::wave_id() * 256 + (copy | ((u32)(k >> shift) & dmask))], 1u);
-            }
-            if constexpr (COUNT == COUNT_LARGE) {
+            if constexpr (COUNT != COUNT_NONE) {
                 // the lower vertices of neighbouring corners mostly share their leading bits: a wave
                 // whose keys all have one digit counts itself with a single LDS atomic
-                const u32 d = (u32)(k >> shift) & (u32)(R12 - 1);
+                const u32 d = (u32)(k >> shift) & (u32)(RADIX - 1);
                 const u64 on = __ballot(ok);
                 if (on != 0) {
                     const u32 d0 = (u32)__builtin_amdgcn_readfirstlane((int)d);
@@ -308,27 +300,11 @@ __global__ __launch_bounds__(BLOCK) void edge_keys_kernel(const int* __restrict_
                 }
             }
         }
-        if constexpr (COUNT == COUNT_SMALL) {
-            static_assert(prim::WAVES == 4, "four per-wave histograms are summed below");
+        if constexpr (COUNT != COUNT_NONE) {
             __syncthreads();
-            const u32 radix = 1u << bits;
-            if ((u32)t < radix) {
-                u32 sum = 0;
-                for (u32 c = (u32)t; c < 256u; c += radix) sum += hist[c] + hist[256 + c] + hist[512 + c] + hist[768 + c];
-                table[(size_t)t * T + tile] = sum;
-            }
-            __syncthreads();
-        }
-        if constexpr (COUNT == COUNT_LARGE) {
-            __syncthreads();
-            for (int i = t; i < R12; i += BLOCK) {
+            for (int i = t; i < RADIX; i += BLOCK) {
                 const u32 c = hist[i];
-                if (c) atomicAdd(&hist12[i], c);
-            }
-            if (table && t < 64) {
-                u32 sum = 0;
-                for (int hi6 = 0; hi6 < 64; ++hi6) sum += hist[(hi6 << 6) | t];
-                table[(size_t)t * T + tile] = sum;
+                if (c) atomicAdd(&msd_hist[i], c);
             }
             __syncthreads();
         }
@@ -989,10 +965,13 @@ __global__ __launch_bounds__(BLOCK) void contract_kernel(const VRec* __restrict_
                                                          const int* __restrict__ mate, const int* __restrict__ newid,
                                                          int* __restrict__ vmap, const State* st, int cur, int B,
                                                          const int* __restrict__ voff_cur, int* __restrict__ voff_nxt,
-                                                         int* __restrict__ htab, int hsize) {
+                                                         int* __restrict__ htab, int hsize,
+                                                         u32* __restrict__ msd_hist) {
     const int nv = st->nv[cur];
     const int stride = gridDim.x * BLOCK;
     const int g = blockIdx.x * BLOCK + threadIdx.x;
+    // this round's edge keys are long sorted: their digit counts and cursors go back to zero for the next round
+    for (int i = g; i < 2 * prim::MSD_HIST_WORDS; i += stride) msd_hist[i] = 0;
     for (int w = g; w < nv; w += stride) {
         const int m = mate[w];
         if (m >= 0 && m < w) {
@@ -1251,7 +1230,7 @@ struct picasso_ctx {
     unsigned char* keep = nullptr;
     int* tilesum = nullptr;
     prim::SortScratch sort_sc{};
-    u32* hist12 = nullptr;  // the 4096-bucket sort's bucket sizes, first positions and cursors (3 x 4096)
+    u32* hist12 = nullptr;  // the bucket sorts' top-digit counts and cursors (2 x prim::MSD_HIST_WORDS)
     // The vertex->facet sort has buffers and scratch of its own, so that in the first round it can
     // run beside the edge-key sort (neither depends on the other) on a second stream.
     u32* s0_key[2] = {nullptr, nullptr};
@@ -1362,7 +1341,7 @@ size_t carve(picasso_ctx* c, char* base, int64_t N, int64_t F, int32_t B) {
     x->sort_sc.T = prim::sort_table_stride((long long)h);
     x->sort_sc.table = cv.take<u32>((size_t)256 * x->sort_sc.T);
     x->sort_sc.totals = cv.take<u32>(256);
-    x->hist12 = cv.take<u32>(3 * 4096);
+    x->hist12 = cv.take<u32>(2 * prim::MSD_HIST_WORDS);
     for (int i = 0; i < 2; ++i) {
         x->s0_key[i] = cv.take<u32>(h);
         x->s0_val[i] = cv.take<u32>(h);
@@ -1370,7 +1349,7 @@ size_t carve(picasso_ctx* c, char* base, int64_t N, int64_t F, int32_t B) {
     x->sort_sc_s0.T = x->sort_sc.T;
     x->sort_sc_s0.table = cv.take<u32>((size_t)256 * x->sort_sc_s0.T);
     x->sort_sc_s0.totals = cv.take<u32>(256);
-    x->hist12_s0 = cv.take<u32>(3 * 4096);
+    x->hist12_s0 = cv.take<u32>(2 * prim::MSD_HIST_WORDS);
     x->voff[1] = cv.take<int>(b + 1);
     x->nrem = cv.take<int>(b);
     x->segstart = cv.take<int>(b);
@@ -1434,7 +1413,7 @@ int sort_by_vertex(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_p
                    bool counted = false) {
     const int how = sort_by_vertex_path(n_max, key_bits);
     if (how == COUNT_SMALL)
-        return prim::bucket_sort<K, HAS_VAL>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc, lt, tag, counted);
+        return prim::bucket_sort<K, HAS_VAL>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc, lt, tag, counted, hist12);
     if (how == COUNT_LARGE)
         return prim::bucket_sort_large<K, HAS_VAL>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc, hist12, lt, tag,
                                                    counted);
@@ -1450,26 +1429,22 @@ int issue_edge_prefix(picasso_ctx* c, hipStream_t st_, int B, int round_, int cu
     const int vbits_ = ceil_log2(nvt);
     const int H_ = 3 * nfb;
     const RoundTab rt{B, c->voff[cur_], c->target, c->active, c->stuck, c->nrem, c->matched, c->mslots, round_ == 0};
-    // the kernel that writes the keys also does the first counting pass of the sort they go to
+    // the kernel that writes the keys also counts their top digits for the sort they go to (the
+    // histogram and the cursors were zeroed by init_kernel, or by the contraction of the round before)
     const int kb = 2 * vbits_;
     const int how = sort_by_vertex_path(H_, kb);
     const bool counted = how != COUNT_NONE;
-    if (how == COUNT_SMALL) {
+    if (how == COUNT_SMALL)
         edge_keys_kernel<COUNT_SMALL><<<prim::sort_tiles(H_, prim::SORT_ITEMS_SMALL), BLOCK, 0, st_>>>(
-            c->fbuf[cur_], c->st, cur_, vbits_, c->key64[0], c->vmin[0], c->vmin[1], c->mate, rt, c->sort_sc.T,
-            c->sort_sc.table, prim::bucket_sort_low_bits(kb), prim::bucket_sort_msd_bits(kb), nullptr);
-    } else if (how == COUNT_LARGE) {
-        prim::fill_u32_kernel<<<(1 << prim::BUCKET_LARGE_MSD_BITS) / BLOCK, BLOCK, 0, st_>>>(
-            c->hist12, 1 << prim::BUCKET_LARGE_MSD_BITS, 0u);
+            c->fbuf[cur_], c->st, cur_, vbits_, c->key64[0], c->vmin[0], c->vmin[1], c->mate, rt,
+            prim::bucket_sort_low_bits(kb), c->hist12);
+    else if (how == COUNT_LARGE)
         edge_keys_kernel<COUNT_LARGE><<<prim::sort_tiles(H_, prim::SORT_ITEMS_BIG), BLOCK, 0, st_>>>(
-            c->fbuf[cur_], c->st, cur_, vbits_, c->key64[0], c->vmin[0], c->vmin[1], c->mate, rt, c->sort_sc.T,
-            nullptr /* keys without values: the sort needs the histogram only */, kb - prim::BUCKET_LARGE_MSD_BITS,
-            prim::BUCKET_LARGE_MSD_BITS, c->hist12);
-    } else {
+            c->fbuf[cur_], c->st, cur_, vbits_, c->key64[0], c->vmin[0], c->vmin[1], c->mate, rt,
+            kb - prim::BUCKET_LARGE_MSD_BITS, c->hist12);
+    else
         edge_keys_kernel<COUNT_NONE><<<grid_for(std::max(3 * nfb, nvt), 8192), BLOCK, 0, st_>>>(
-            c->fbuf[cur_], c->st, cur_, vbits_, c->key64[0], c->vmin[0], c->vmin[1], c->mate, rt, 0, nullptr, 0, 8,
-            nullptr);
-    }
+            c->fbuf[cur_], c->st, cur_, vbits_, c->key64[0], c->vmin[0], c->vmin[1], c->mate, rt, 0, nullptr);
     skeys = c->key64[0];
     if (H_ > 0) {
         int where = sort_by_vertex<u64, false>(st_, c->key64[0], c->key64[1], nullptr, nullptr, &c->st->nh, H_,
@@ -1600,7 +1575,7 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
     tm.begin(0, PICASSO_ST_QUADRICS);
     init_kernel<<<grid_for(std::max(N, F), 4096), BLOCK, 0, s>>>(
         d_verts, N, d_facets, F, B, c->voff[0], c->foff, c->vrec[0], c->cid, c->fbuf[0],
-        work ? c->s0_key[0] : nullptr, c->s0_val[0], c->st);
+        work ? c->s0_key[0] : nullptr, c->s0_val[0], c->st, c->hist12);
     if (overlap) {
         HIP_TRY(c, hipEventRecord(c->ev_fork, s));
         HIP_TRY(c, hipStreamWaitEvent(c->side, c->ev_fork, 0));
@@ -1779,7 +1754,7 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         const size_t hsize = next_pow2((size_t)2 * std::max(nf_bound, 1));
         contract_kernel<<<grid_for(std::max<long long>(nv_total, (long long)hsize), 8192), BLOCK, 0, s>>>(
             c->vrec[cur], c->vrec[nxt], c->mate, c->newid, c->vmap, c->st, cur, B, c->voff[cur], c->voff[nxt],
-            c->htab, (int)hsize);
+            c->htab, (int)hsize, c->hist12);
         tm.end();
 
         // ---- S5: facets
@@ -1997,7 +1972,7 @@ int picasso_vertex_quadrics(picasso_ctx* c, void* stream, const float* d_verts, 
     if (rc != PICASSO_OK) return rc;
     init_kernel<<<grid_for(std::max(N, F), 4096), BLOCK, 0, s>>>(d_verts, N, d_facets, F, 1, c->voff[0], c->foff,
                                                                  c->vrec[0], c->cid, c->fbuf[0], c->s0_key[0], c->s0_val[0],
-                                                                 c->st);
+                                                                 c->st, c->hist12);
     State* hst = reinterpret_cast<State*>(c->h_pin);
     rc = read_header(c, s);
     if (rc != PICASSO_OK) return rc;
@@ -2024,7 +1999,7 @@ int picasso_edge_costs(picasso_ctx* c, void* stream, const float* d_verts, int32
     if (rc != PICASSO_OK) return rc;
     init_kernel<<<grid_for(std::max(N, F), 4096), BLOCK, 0, s>>>(d_verts, N, d_facets, F, 1, c->voff[0], c->foff,
                                                                  c->vrec[0], c->cid, c->fbuf[0], c->s0_key[0], c->s0_val[0],
-                                                                 c->st);
+                                                                 c->st, c->hist12);
     State* hst = reinterpret_cast<State*>(c->h_pin);
     rc = read_header(c, s);
     if (rc != PICASSO_OK) return rc;

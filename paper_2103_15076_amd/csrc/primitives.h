@@ -453,8 +453,7 @@ template <typename K, bool HAS_VAL, int BUCKET_THREADS, int BUCKET_ITEMS>
 __global__ __launch_bounds__(BUCKET_THREADS) void bucket_sort_kernel(K* __restrict__ kin, K* __restrict__ kout,
                                                                      u32* __restrict__ vin, u32* __restrict__ vout,
                                                                      const u32* __restrict__ totals, int nbuckets,
-                                                                     int low_bits,
-                                                                     const u32* __restrict__ starts = nullptr) {
+                                                                     int low_bits) {
     constexpr int BUCKET_WAVES = BUCKET_THREADS / 64;
     constexpr int BUCKET_CAP = BUCKET_THREADS * BUCKET_ITEMS;  // keys of one bucket held in LDS
     constexpr int RMAX = 1 << BUCKET_GROUP_BITS;
@@ -467,19 +466,14 @@ __global__ __launch_bounds__(BUCKET_THREADS) void bucket_sort_kernel(K* __restri
     const int t = threadIdx.x, w = wave_id(), lane = lane_id();
     const int bkt = blockIdx.x;
 
-    // start of this bucket = sum of the counts of the buckets before it (given, or summed here)
+    // start of this bucket = sum of the counts of the buckets before it
     (void)nbuckets;
     const int cnt = (int)totals[bkt];
     if (cnt == 0) return;
-    u32 start;
-    if (starts) {
-        start = starts[bkt];
-    } else {
-        u32 part = 0;
-        for (int j = t; j < bkt; j += BUCKET_THREADS) part += totals[j];
-        (void)wide_block_exclusive_scan<BUCKET_WAVES>(part, smem, start);
-        __syncthreads();
-    }
+    u32 part = 0, start;
+    for (int j = t; j < bkt; j += BUCKET_THREADS) part += totals[j];
+    (void)wide_block_exclusive_scan<BUCKET_WAVES>(part, smem, start);
+    __syncthreads();
     if (cnt > BUCKET_CAP) {
         bucket_sort_oversize<K, HAS_VAL, BUCKET_THREADS>(kout + start, kin + start, HAS_VAL ? vout + start : nullptr,
                                          HAS_VAL ? vin + start : nullptr, cnt, low_bits, tstart, smem);
@@ -599,21 +593,155 @@ __global__ __launch_bounds__(BUCKET_THREADS) void bucket_sort_kernel(K* __restri
     }
 }
 
-// `counted`: the producer of the keys has already filled sc.table with the per-tile counts of the
-// top digit (tiles of BLOCK * SORT_ITEMS_SMALL keys, digit = bits [bucket_sort_low_bits, key_bits)),
-// as radix_upsweep_kernel would, so that pass over the keys is skipped.
+// Histogram of the top RBITS-bit digit (bits [shift, shift + RBITS)) over the whole input, added
+// to `hist` (which starts at zero); tiles of BLOCK * ITEMS keys.
+template <typename K, int RBITS, int ITEMS>
+__global__ __launch_bounds__(BLOCK) void msd_histogram_kernel(const K* __restrict__ kin, const int* n_ptr, int n_host,
+                                                              u32* __restrict__ hist, int shift) {
+    constexpr int R = 1 << RBITS;
+    constexpr int TILE = BLOCK * ITEMS;
+    __shared__ u32 h[R];
+    const int n = load_count(n_ptr, n_host);
+    const long long base = (long long)blockIdx.x * TILE;
+    if (base >= n) return;
+    const int t = threadIdx.x;
+    for (int i = t; i < R; i += BLOCK) h[i] = 0;
+    __syncthreads();
+#pragma unroll 4
+    for (int i = 0; i < ITEMS; ++i) {
+        const long long idx = base + (long long)i * BLOCK + t;
+        if (idx < n) atomicAdd(&h[digit_of<K>(kin[idx], shift, R - 1)], 1u);
+    }
+    __syncthreads();
+    for (int i = t; i < R; i += BLOCK) {
+        const u32 c = h[i];
+        if (c) atomicAdd(&hist[i], c);
+    }
+}
+
+// Partition of keys WITHOUT values by their top digit (bits [shift, shift + RBITS)) in one pass.
+// hist[d] = number of keys with digit d over the whole input (so digit d owns the output range
+// that starts at the sum of the counts before it); cursor[d] = how much of that range is taken,
+// zero at the start.  Every tile counts its keys per digit in LDS, takes its share of each
+// digit's range with one returning atomic per digit it holds, and writes its keys there.  The
+// order of the keys inside a digit's range depends on the order in which tiles arrive, so this is
+// for sorts that then order each range on the whole key; with equal keys indistinguishable the
+// final result does not depend on it.  A wave whose keys share one digit (the common case for
+// keys led by mesh indices) ranks itself with one LDS atomic and writes one contiguous run.
+template <typename K, int RBITS, int ITEMS>
+__global__ __launch_bounds__(BLOCK) void msd_scatter_kernel(const K* __restrict__ kin, K* __restrict__ kout,
+                                                            const int* n_ptr, int n_host, int shift,
+                                                            const u32* __restrict__ hist, u32* __restrict__ cursor) {
+    constexpr int R = 1 << RBITS;
+    constexpr int PER = R / BLOCK;  // digits per thread in the scan of the ranges' first positions
+    static_assert(R % BLOCK == 0, "whole digits per thread");
+    constexpr int TILE = BLOCK * ITEMS;
+    __shared__ u32 h[R];  // per digit: this tile's count, then where the tile's keys of that digit go
+    __shared__ u32 first[R];
+    __shared__ u32 smem[WAVES];
+    const int n = load_count(n_ptr, n_host);
+    const long long base = (long long)blockIdx.x * TILE;
+    if (base >= n) return;
+    const int t = threadIdx.x, w = wave_id(), lane = lane_id();
+    const u64 lt = lanemask_lt();
+    for (int i = t; i < R; i += BLOCK) h[i] = 0;
+    K key[ITEMS];
+    u32 rk[ITEMS];
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        const long long idx = base + (long long)w * (64 * ITEMS) + i * 64 + lane;
+        key[i] = idx < n ? kin[idx] : (K)0;
+    }
+    {   // first position of every digit's range
+        u32 c[PER], sum = 0, tot;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            c[j] = hist[t * PER + j];
+            sum += c[j];
+        }
+        u32 run = block_exclusive_scan(sum, smem, tot);
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            first[t * PER + j] = run;
+            run += c[j];
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        const long long idx = base + (long long)w * (64 * ITEMS) + i * 64 + lane;
+        const bool ok = idx < n;
+        const u32 d = digit_of<K>(key[i], shift, R - 1);
+        const u64 on = __ballot(ok);
+        rk[i] = 0;
+        if (on == 0) continue;
+        const int lead = __ffsll((long long)on) - 1;
+        const u32 d0 = (u32)__shfl((int)d, lead, 64);
+        if (__ballot(ok && d == d0) == on) {
+            u32 b = 0;
+            if (lane == lead) b = atomicAdd(&h[d0], (u32)__popcll(on));
+            rk[i] = (u32)__shfl((int)b, lead, 64) + (u32)__popcll(on & lt);
+        } else if (ok) {
+            rk[i] = atomicAdd(&h[d], 1u);
+        }
+    }
+    __syncthreads();
+    for (int d = t; d < R; d += BLOCK) {
+        const u32 c = h[d];
+        if (c) h[d] = first[d] + atomicAdd(&cursor[d], c);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        const long long idx = base + (long long)w * (64 * ITEMS) + i * 64 + lane;
+        if (idx < n) {
+            const u32 pos = h[digit_of<K>(key[i], shift, R - 1)] + rk[i];
+            if (pos < (u32)n) kout[pos] = key[i];  // (always, when hist and cursor are as described)
+        }
+    }
+}
+
+// Keys without values are partitioned by msd_scatter_kernel, which works from a histogram of the
+// top digit in msd_hist[0, R) and cursors in msd_hist[MSD_HIST_WORDS, MSD_HIST_WORDS + R), both
+// zeroed beforehand (msd_hist holds 2 * MSD_HIST_WORDS words).  `counted`: the producer of the
+// keys has already added the keys' digits to that (zeroed) histogram and left the cursors zero,
+// so the histogram pass over the keys is skipped.
+constexpr int MSD_HIST_WORDS = 4096;
 inline int bucket_sort_msd_bits(int key_bits) { return key_bits < BUCKET_MSD_BITS ? key_bits : BUCKET_MSD_BITS; }
 inline int bucket_sort_low_bits(int key_bits) { return key_bits - bucket_sort_msd_bits(key_bits); }
 
+__global__ __launch_bounds__(BLOCK) void fill_u32_kernel(u32* __restrict__ p, int n, u32 v) {
+    const int i = blockIdx.x * BLOCK + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
 template <typename K, bool HAS_VAL>
 inline int bucket_sort(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_ptr, int n_max, int key_bits,
-                       const SortScratch& sc, LaunchTimer* lt = nullptr, int tag = 0, bool counted = false) {
+                       const SortScratch& sc, LaunchTimer* lt = nullptr, int tag = 0, bool counted = false,
+                       u32* msd_hist = nullptr) {
     if (n_max <= 0 || key_bits <= 0) return 0;
     const int msd = bucket_sort_msd_bits(key_bits);
     const int low = key_bits - msd;
     const int tiles = sort_tiles(n_max, SORT_ITEMS_SMALL);
-    if (!counted)
-        radix_upsweep_kernel<K, SORT_ITEMS_SMALL><<<tiles, BLOCK, 0, s>>>(k0, n_ptr, n_max, sc.T, sc.table, low, msd);
+    if constexpr (!HAS_VAL) {
+        if (msd == BUCKET_MSD_BITS && msd_hist) {
+            // keys only: one unordered partition pass (msd_scatter_kernel), then each bucket is ordered on the whole key
+            u32* cursor = msd_hist + MSD_HIST_WORDS;
+            if (!counted) {
+                fill_u32_kernel<<<2 * MSD_HIST_WORDS / BLOCK, BLOCK, 0, s>>>(msd_hist, 2 * MSD_HIST_WORDS, 0u);
+                msd_histogram_kernel<K, BUCKET_MSD_BITS, SORT_ITEMS_SMALL><<<tiles, BLOCK, 0, s>>>(k0, n_ptr, n_max, msd_hist, low);
+            }
+            msd_scatter_kernel<K, BUCKET_MSD_BITS, SORT_ITEMS_SMALL><<<tiles, BLOCK, 0, s>>>(k0, k1, n_ptr, n_max, low, msd_hist, cursor);
+            const bool timed = lt && lt->begin(s, tag);
+            bucket_sort_kernel<K, false, BUCKET_THREADS_256, 8>
+                <<<1 << msd, BUCKET_THREADS_256, 0, s>>>(k1, k0, nullptr, nullptr, msd_hist, 1 << msd, low);
+            if (timed) lt->end(s);
+            if (hipGetLastError() != hipSuccess) return -1;
+            return 0;
+        }
+    }
+    (void)counted;
+    radix_upsweep_kernel<K, SORT_ITEMS_SMALL><<<tiles, BLOCK, 0, s>>>(k0, n_ptr, n_max, sc.T, sc.table, low, msd);
     radix_scan_kernel<<<1 << msd, BLOCK, 0, s>>>(sc.table, sc.totals, n_ptr, n_max, sc.T, BLOCK * SORT_ITEMS_SMALL);
     radix_downsweep_kernel<K, HAS_VAL, SORT_ITEMS_SMALL>
         <<<tiles, BLOCK, 0, s>>>(k0, k1, v0, v1, n_ptr, n_max, sc.T, sc.table, sc.totals, low, msd);
@@ -676,97 +804,8 @@ __global__ __launch_bounds__(BLOCK) void top_digit_histogram_kernel(const K* __r
     }
 }
 
-__global__ __launch_bounds__(BLOCK) void fill_u32_kernel(u32* __restrict__ p, int n, u32 v) {
-    const int i = blockIdx.x * BLOCK + threadIdx.x;
-    if (i < n) p[i] = v;
-}
-
-// starts[d] = cursor[d] = number of keys whose 12-bit digit is below d (one workgroup).
-__global__ __launch_bounds__(1024) void digit_starts_kernel(const u32* __restrict__ hist, u32* __restrict__ starts,
-                                                            u32* __restrict__ cursor) {
-    constexpr int R = 1 << BUCKET_LARGE_MSD_BITS;
-    constexpr int PER = R / 1024;
-    __shared__ u32 smem[16];
-    const int t = threadIdx.x;
-    u32 c[PER], sum = 0;
-#pragma unroll
-    for (int j = 0; j < PER; ++j) {
-        c[j] = hist[t * PER + j];
-        sum += c[j];
-    }
-    u32 tot;
-    u32 run = wide_block_exclusive_scan<16>(sum, smem, tot);
-#pragma unroll
-    for (int j = 0; j < PER; ++j) {
-        starts[t * PER + j] = run;
-        cursor[t * PER + j] = run;
-        run += c[j];
-    }
-}
-
-// Partition of keys WITHOUT values by their 12-bit digit (bits [shift, shift + 12)) in one pass:
-// every tile counts its keys per digit in LDS, reserves room for them in each digit's range with
-// one returning atomic per digit it holds (cursor[d] starts at the digit's first position), and
-// writes its keys there.  The order of the keys inside a digit's range depends on the order in
-// which tiles arrive, so this is for sorts that then order each range on the whole key; with
-// equal keys indistinguishable the final result does not depend on it.  A wave whose keys share
-// one digit (the common case for keys led by mesh indices) ranks itself with one LDS atomic and
-// writes one contiguous run.
-template <typename K>
-__global__ __launch_bounds__(BLOCK) void msd_scatter_kernel(const K* __restrict__ kin, K* __restrict__ kout,
-                                                            const int* n_ptr, int n_host, int shift,
-                                                            u32* __restrict__ cursor) {
-    constexpr int R = 1 << BUCKET_LARGE_MSD_BITS;
-    constexpr int ITEMS = SORT_ITEMS_BIG;
-    constexpr int TILE = BLOCK * ITEMS;
-    __shared__ u32 h[R];  // per digit: this tile's count, then where the tile's keys of that digit go
-    const int n = load_count(n_ptr, n_host);
-    const long long base = (long long)blockIdx.x * TILE;
-    if (base >= n) return;
-    const int t = threadIdx.x, w = wave_id(), lane = lane_id();
-    const u64 lt = lanemask_lt();
-    for (int i = t; i < R; i += BLOCK) h[i] = 0;
-    __syncthreads();
-    K key[ITEMS];
-    u32 rk[ITEMS];
-#pragma unroll
-    for (int i = 0; i < ITEMS; ++i) {
-        const long long idx = base + (long long)w * (64 * ITEMS) + i * 64 + lane;
-        key[i] = idx < n ? kin[idx] : (K)0;
-    }
-#pragma unroll
-    for (int i = 0; i < ITEMS; ++i) {
-        const long long idx = base + (long long)w * (64 * ITEMS) + i * 64 + lane;
-        const bool ok = idx < n;
-        const u32 d = digit_of<K>(key[i], shift, R - 1);
-        const u64 on = __ballot(ok);
-        rk[i] = 0;
-        if (on == 0) continue;
-        const int first = __ffsll((long long)on) - 1;
-        const u32 d0 = (u32)__shfl((int)d, first, 64);
-        if (__ballot(ok && d == d0) == on) {
-            u32 b = 0;
-            if (lane == first) b = atomicAdd(&h[d0], (u32)__popcll(on));
-            rk[i] = (u32)__shfl((int)b, first, 64) + (u32)__popcll(on & lt);
-        } else if (ok) {
-            rk[i] = atomicAdd(&h[d], 1u);
-        }
-    }
-    __syncthreads();
-    for (int d = t; d < R; d += BLOCK) {
-        const u32 c = h[d];
-        if (c) h[d] = atomicAdd(&cursor[d], c);
-    }
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < ITEMS; ++i) {
-        const long long idx = base + (long long)w * (64 * ITEMS) + i * 64 + lane;
-        if (idx < n) kout[h[digit_of<K>(key[i], shift, R - 1)] + rk[i]] = key[i];
-    }
-}
-
 // Result is in (k1, v1): returns 1 (keys with values), or in k0: returns 0 (keys only); <0 on a
-// launch error.  hist12 holds 3 x 4096 words (counts, first positions, cursors).
+// launch error.  hist12 holds 2 * MSD_HIST_WORDS words (counts, cursors).
 template <typename K, bool HAS_VAL>
 inline int bucket_sort_large(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_ptr, int n_max, int key_bits,
                              const SortScratch& sc, u32* hist12, LaunchTimer* lt = nullptr, int tag = 0,
@@ -774,23 +813,23 @@ inline int bucket_sort_large(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, cons
     constexpr int R = 1 << BUCKET_LARGE_MSD_BITS;
     const int low = key_bits - BUCKET_LARGE_MSD_BITS;
     const int tiles = sort_tiles(n_max, SORT_ITEMS_BIG);
-    if (!counted) {  // (else the producer of the keys has left what these two kernels compute)
-        fill_u32_kernel<<<R / BLOCK, BLOCK, 0, s>>>(hist12, R, 0u);
-        top_digit_histogram_kernel<K><<<tiles, BLOCK, 0, s>>>(k0, n_ptr, n_max, hist12, low, sc.T, sc.table);
-    }
     if constexpr (!HAS_VAL) {
-        // keys only: one unordered partition pass, then each bucket is ordered on the whole key
-        u32* starts = hist12 + R;
-        u32* cursor = hist12 + 2 * R;
-        digit_starts_kernel<<<1, 1024, 0, s>>>(hist12, starts, cursor);
-        msd_scatter_kernel<K><<<tiles, BLOCK, 0, s>>>(k0, k1, n_ptr, n_max, low, cursor);
+        // keys only: one unordered partition pass (msd_scatter_kernel), then each bucket is ordered on the whole key
+        u32* cursor = hist12 + MSD_HIST_WORDS;
+        if (!counted) {
+            fill_u32_kernel<<<2 * MSD_HIST_WORDS / BLOCK, BLOCK, 0, s>>>(hist12, 2 * MSD_HIST_WORDS, 0u);
+            msd_histogram_kernel<K, BUCKET_LARGE_MSD_BITS, SORT_ITEMS_BIG><<<tiles, BLOCK, 0, s>>>(k0, n_ptr, n_max, hist12, low);
+        }
+        msd_scatter_kernel<K, BUCKET_LARGE_MSD_BITS, SORT_ITEMS_BIG><<<tiles, BLOCK, 0, s>>>(k0, k1, n_ptr, n_max, low, hist12, cursor);
         const bool timed = lt && lt->begin(s, tag);
-        bucket_sort_kernel<K, false, BUCKET_THREADS_4096, 8>
-            <<<R, BUCKET_THREADS_4096, 0, s>>>(k1, k0, nullptr, nullptr, hist12, R, low, starts);
+        bucket_sort_kernel<K, false, BUCKET_THREADS_4096, 8><<<R, BUCKET_THREADS_4096, 0, s>>>(k1, k0, nullptr, nullptr, hist12, R, low);
         if (timed) lt->end(s);
         if (hipGetLastError() != hipSuccess) return -1;
         return 0;
     }
+    (void)counted;
+    fill_u32_kernel<<<R / BLOCK, BLOCK, 0, s>>>(hist12, R, 0u);
+    top_digit_histogram_kernel<K><<<tiles, BLOCK, 0, s>>>(k0, n_ptr, n_max, hist12, low, sc.T, sc.table);
     K* kin = k0;
     K* kout = k1;
     u32* vin = v0;
