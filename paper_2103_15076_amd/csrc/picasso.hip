@@ -91,17 +91,30 @@ __device__ __forceinline__ u32 cost_key(float c) {
 
 // Validates and copies the inputs into the workspace; emits the (vertex,
 // incidence) pairs whose stable sort is the vertex->facet CSR.
+enum { COUNT_NONE = 0, COUNT_SMALL = 1, COUNT_LARGE = 2 };
+
+// Incidence keys for S0: (vertex << fbits) | facet, one per facet corner, so that sorting the keys
+// alone lists every vertex's facets in ascending facet order.  With COUNT_SMALL / COUNT_LARGE the
+// kernel also adds the keys' top 8- / 12-bit digits (bits [ishift, ...)) to ihist, the histogram
+// that the sort of the keys starts from (zero on entry; see quadric_reduce_kernel).
+template <int COUNT>
 __global__ __launch_bounds__(BLOCK) void init_kernel(const float* __restrict__ verts, int N,
                                                      const int* __restrict__ facets, int F, int B,
                                                      const int* __restrict__ voff, const int* __restrict__ foff,
                                                      VRec* __restrict__ vrec, int* __restrict__ cid,
-                                                     int* __restrict__ fcur, u32* __restrict__ ikey,
-                                                     u32* __restrict__ ival, State* st,
+                                                     int* __restrict__ fcur, u64* __restrict__ ikey, int fbits,
+                                                     int ishift, u32* __restrict__ ihist, State* st,
                                                      u32* __restrict__ msd_hist) {
+    constexpr int RADIX = COUNT == COUNT_LARGE ? (1 << prim::BUCKET_LARGE_MSD_BITS) : (1 << prim::BUCKET_MSD_BITS);
+    __shared__ u32 hist[COUNT != COUNT_NONE ? RADIX : 1];
     const int stride = gridDim.x * BLOCK;
     const int g = blockIdx.x * BLOCK + threadIdx.x;
     // the edge-key sort's digit counts and cursors start every round at zero (see edge_keys_kernel)
     for (int i = g; i < 2 * prim::MSD_HIST_WORDS; i += stride) msd_hist[i] = 0;
+    if constexpr (COUNT != COUNT_NONE) {
+        for (int i = threadIdx.x; i < RADIX; i += BLOCK) hist[i] = 0;
+        __syncthreads();
+    }
     int err = 0;
     for (int w = g; w < N; w += stride) {
         float x = verts[3 * (size_t)w], y = verts[3 * (size_t)w + 1], z = verts[3 * (size_t)w + 2];
@@ -112,30 +125,59 @@ __global__ __launch_bounds__(BLOCK) void init_kernel(const float* __restrict__ v
         vrec[w] = r;
         cid[w] = w;
     }
-    for (int f = g; f < F; f += stride) {
-        const int m = mesh_of(foff, B, f);
-        const int lo = voff[m], hi = voff[m + 1];
+    for (int f0 = blockIdx.x * BLOCK; f0 < F; f0 += stride) {  // (whole waves, for the ballots below)
+        const int f = f0 + threadIdx.x;
+        const bool ok = f < F;
+        int lo = 0, hi = 0;
+        if (ok) {
+            const int m = mesh_of(foff, B, f);
+            lo = voff[m];
+            hi = voff[m + 1];
+        }
 #pragma unroll
         for (int c = 0; c < 3; ++c) {
-            int a = facets[3 * (size_t)f + c];
-            if (a < lo || a >= hi) { err |= 1; a = lo; }
-            fcur[3 * (size_t)f + c] = a;
-            if (ikey) {
-                ikey[3 * (size_t)f + c] = (u32)a;
-                ival[3 * (size_t)f + c] = (u32)(3 * f + c);
+            u64 k = 0;
+            if (ok) {
+                int a = facets[3 * (size_t)f + c];
+                if (a < lo || a >= hi) { err |= 1; a = lo; }
+                fcur[3 * (size_t)f + c] = a;
+                k = ((u64)(u32)a << fbits) | (u64)(u32)f;
+                if (ikey) ikey[3 * (size_t)f + c] = k;
             }
+            if constexpr (COUNT != COUNT_NONE) {
+                // neighbouring facets mostly refer to vertices with the same leading bits: a wave
+                // whose keys all have one digit counts itself with a single LDS atomic
+                const u32 d = (u32)(k >> ishift) & (u32)(RADIX - 1);
+                const u64 on = __ballot(ok);
+                if (on != 0) {
+                    const u32 d0 = (u32)__builtin_amdgcn_readfirstlane((int)d);
+                    if (__ballot(ok && d == d0) == on) {
+                        if (ok && (on & prim::lanemask_lt()) == 0) atomicAdd(&hist[d0], (u32)__popcll(on));
+                    } else if (ok) {
+                        atomicAdd(&hist[d], 1u);
+                    }
+                }
+            }
+        }
+    }
+    if constexpr (COUNT != COUNT_NONE) {
+        __syncthreads();
+        for (int i = threadIdx.x; i < RADIX; i += BLOCK) {
+            const u32 c = hist[i];
+            if (c) atomicAdd(&ihist[i], c);
         }
     }
     if (err) atomicOr(&st->err, err);
 }
 
-// off[v] = first position of vertex v in the sorted incidence keys (CSR row starts)
-__global__ __launch_bounds__(BLOCK) void csr_offsets_kernel(const u32* __restrict__ skey, int H, int N,
+// off[v] = first position of row v = key >> fbits in the sorted keys (CSR row starts)
+template <typename K>
+__global__ __launch_bounds__(BLOCK) void csr_offsets_kernel(const K* __restrict__ skey, int fbits, int H, int N,
                                                             int* __restrict__ off) {
     const int i = blockIdx.x * BLOCK + threadIdx.x;
     if (i >= H) return;
-    const int k = (int)skey[i];
-    const int kp = i ? (int)skey[i - 1] : -1;
+    const int k = (int)(skey[i] >> fbits);
+    const int kp = i ? (int)(skey[i - 1] >> fbits) : -1;
     for (int v = kp + 1; v <= k; ++v) off[v] = i;
     if (i == H - 1)
         for (int v = k + 1; v <= N; ++v) off[v] = H;
@@ -179,8 +221,11 @@ __global__ __launch_bounds__(BLOCK) void quadric_reduce_kernel(VRec* __restrict_
                                                                const float* __restrict__ verts, int N,
                                                                const int* __restrict__ fcur,
                                                                const int* __restrict__ off,
-                                                               const u32* __restrict__ inc) {
+                                                               const u64* __restrict__ inc, int fbits,
+                                                               u32* __restrict__ ihist) {
     const int w = blockIdx.x * BLOCK + threadIdx.x;
+    // last kernel of S0: the incidence sort's digit counts and cursors go back to zero for the next call
+    for (int i = w; i < 2 * prim::MSD_HIST_WORDS; i += gridDim.x * BLOCK) ihist[i] = 0;
     if (w >= N) return;
     float acc[10];
 #pragma unroll
@@ -188,7 +233,7 @@ __global__ __launch_bounds__(BLOCK) void quadric_reduce_kernel(VRec* __restrict_
     if (off) {
         const int s = off[w], e = off[w + 1];
         for (int j = s; j < e; ++j) {
-            const int f = (int)(inc[j] / 3u);
+            const int f = (int)(inc[j] & ((1ull << fbits) - 1ull));
             const Quadric10 Q = facet_quadric(verts, fcur[3 * (size_t)f], fcur[3 * (size_t)f + 1], fcur[3 * (size_t)f + 2]);
 #pragma unroll
             for (int k = 0; k < 10; ++k) acc[k] = acc[k] + Q.q[k];
@@ -246,8 +291,6 @@ __device__ __forceinline__ void round_begin_block(const RoundTab& R, int cur, St
 // histogram that the sort of the keys starts from (prim::bucket_sort / prim::bucket_sort_large
 // with `counted`; zeroed beforehand), so the sort needs no counting pass of its own.
 // ---------------------------------------------------------------------------
-enum { COUNT_NONE = 0, COUNT_SMALL = 1, COUNT_LARGE = 2 };
-
 template <int COUNT>
 __global__ __launch_bounds__(BLOCK) void edge_keys_kernel(const int* __restrict__ fcur, State* st, int cur, int vbits,
                                                           u64* __restrict__ keys, u64* __restrict__ vmin0,
@@ -1233,8 +1276,7 @@ struct picasso_ctx {
     u32* hist12 = nullptr;  // the bucket sorts' top-digit counts and cursors (2 x prim::MSD_HIST_WORDS)
     // The vertex->facet sort has buffers and scratch of its own, so that in the first round it can
     // run beside the edge-key sort (neither depends on the other) on a second stream.
-    u32* s0_key[2] = {nullptr, nullptr};
-    u32* s0_val[2] = {nullptr, nullptr};
+    u64* s0_key[2] = {nullptr, nullptr};  // incidence keys (vertex, facet) of S0 and their sort's second buffer
     prim::SortScratch sort_sc_s0{};
     u32* hist12_s0 = nullptr;
     hipStream_t side = nullptr;
@@ -1343,8 +1385,7 @@ size_t carve(picasso_ctx* c, char* base, int64_t N, int64_t F, int32_t B) {
     x->sort_sc.totals = cv.take<u32>(256);
     x->hist12 = cv.take<u32>(2 * prim::MSD_HIST_WORDS);
     for (int i = 0; i < 2; ++i) {
-        x->s0_key[i] = cv.take<u32>(h);
-        x->s0_val[i] = cv.take<u32>(h);
+        x->s0_key[i] = cv.take<u64>(h);
     }
     x->sort_sc_s0.T = x->sort_sc.T;
     x->sort_sc_s0.table = cv.take<u32>((size_t)256 * x->sort_sc_s0.T);
@@ -1407,7 +1448,7 @@ inline int sort_by_vertex_path(long long n_max, int key_bits) {
     return COUNT_NONE;
 }
 
-template <typename K, bool HAS_VAL>
+template <typename K, bool HAS_VAL, int LARGE_KEYS_ONLY_ITEMS = 8>
 int sort_by_vertex(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_ptr, int n_max, int key_bits,
                    const prim::SortScratch& sc, u32* hist12, prim::LaunchTimer* lt = nullptr, int tag = 0,
                    bool counted = false) {
@@ -1415,8 +1456,8 @@ int sort_by_vertex(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_p
     if (how == COUNT_SMALL)
         return prim::bucket_sort<K, HAS_VAL>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc, lt, tag, counted, hist12);
     if (how == COUNT_LARGE)
-        return prim::bucket_sort_large<K, HAS_VAL>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc, hist12, lt, tag,
-                                                   counted);
+        return prim::bucket_sort_large<K, HAS_VAL, LARGE_KEYS_ONLY_ITEMS>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc,
+                                                                          hist12, lt, tag, counted);
     return prim::radix_sort<K, HAS_VAL>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc, lt, tag);
 }
 
@@ -1460,23 +1501,49 @@ int issue_edge_prefix(picasso_ctx* c, hipStream_t st_, int B, int round_, int cu
     return PICASSO_OK;
 }
 
-// S0 on the data already validated into the workspace by init_kernel.
 constexpr int64_t OVERLAP_MIN_FACETS = 1 << 18;
 
+// Bits of the incidence keys: vertex id above, facet id below.
+inline int incidence_fbits(int F) { return ceil_log2(std::max(F, 1)); }
+inline int incidence_key_bits(int N, int F) { return ceil_log2(N) + incidence_fbits(F); }
+
+// The validating kernel, instantiated for the sort the incidence keys go to.
+int launch_init(picasso_ctx* c, hipStream_t s, const float* d_verts, int N, const int32_t* d_facets, int F, int B,
+                bool with_keys) {
+    const int fbits = incidence_fbits(F), kb = incidence_key_bits(N, F);
+    const int how = with_keys ? sort_by_vertex_path(3ll * F, kb) : COUNT_NONE;
+    u64* ikey = with_keys ? c->s0_key[0] : nullptr;
+    const int grid = grid_for(std::max(N, F), 4096);
+    if (how == COUNT_SMALL)
+        init_kernel<COUNT_SMALL><<<grid, BLOCK, 0, s>>>(d_verts, N, d_facets, F, B, c->voff[0], c->foff, c->vrec[0],
+                                                        c->cid, c->fbuf[0], ikey, fbits, prim::bucket_sort_low_bits(kb),
+                                                        c->hist12_s0, c->st, c->hist12);
+    else if (how == COUNT_LARGE)
+        init_kernel<COUNT_LARGE><<<grid, BLOCK, 0, s>>>(d_verts, N, d_facets, F, B, c->voff[0], c->foff, c->vrec[0],
+                                                        c->cid, c->fbuf[0], ikey, fbits,
+                                                        kb - prim::BUCKET_LARGE_MSD_BITS, c->hist12_s0, c->st, c->hist12);
+    else
+        init_kernel<COUNT_NONE><<<grid, BLOCK, 0, s>>>(d_verts, N, d_facets, F, B, c->voff[0], c->foff, c->vrec[0],
+                                                       c->cid, c->fbuf[0], ikey, fbits, 0, nullptr, c->st, c->hist12);
+    return hipGetLastError() == hipSuccess ? PICASSO_OK : PICASSO_ERR_HIP;
+}
+
+// S0 on the incidence keys written by init_kernel (whose digit counts are in hist12_s0).
 int run_vertex_quadrics(picasso_ctx* c, hipStream_t s, const float* d_verts, int N, int F) {
     const int H = 3 * F;
-    u32* k0 = c->s0_key[0];
-    u32* k1 = c->s0_key[1];
+    const int fbits = incidence_fbits(F), kb = incidence_key_bits(N, F);
     if (F > 0) {
-        int where = sort_by_vertex<u32, true>(s, k0, k1, c->s0_val[0], c->s0_val[1], nullptr, H, ceil_log2(N),
-                                              c->sort_sc_s0, c->hist12_s0);
+        const bool counted = sort_by_vertex_path(H, kb) != COUNT_NONE;
+        int where = sort_by_vertex<u64, false, 16>(s, c->s0_key[0], c->s0_key[1], nullptr, nullptr, nullptr, H, kb,
+                                                   c->sort_sc_s0, c->hist12_s0, nullptr, 0, counted);
         if (where < 0) return PICASSO_ERR_HIP;
-        const u32* skey = where ? k1 : k0;
-        const u32* sval = where ? c->s0_val[1] : c->s0_val[0];
-        csr_offsets_kernel<<<grid_for(H), BLOCK, 0, s>>>(skey, H, N, c->csr_off);
-        quadric_reduce_kernel<<<grid_for(N), BLOCK, 0, s>>>(c->vrec[0], d_verts, N, c->fbuf[0], c->csr_off, sval);
+        const u64* skey = where ? c->s0_key[1] : c->s0_key[0];
+        csr_offsets_kernel<u64><<<grid_for(H), BLOCK, 0, s>>>(skey, fbits, H, N, c->csr_off);
+        quadric_reduce_kernel<<<grid_for(N), BLOCK, 0, s>>>(c->vrec[0], d_verts, N, c->fbuf[0], c->csr_off, skey, fbits,
+                                                            c->hist12_s0);
     } else {
-        quadric_reduce_kernel<<<grid_for(N), BLOCK, 0, s>>>(c->vrec[0], d_verts, N, c->fbuf[0], nullptr, nullptr);
+        quadric_reduce_kernel<<<grid_for(N), BLOCK, 0, s>>>(c->vrec[0], d_verts, N, c->fbuf[0], nullptr, nullptr, 0,
+                                                            c->hist12_s0);
     }
     return PICASSO_OK;
 }
@@ -1573,9 +1640,8 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
     const u64* skeys = nullptr;
     const bool overlap = work && c->opt_overlap && c->side && !tm.on && F >= OVERLAP_MIN_FACETS;
     tm.begin(0, PICASSO_ST_QUADRICS);
-    init_kernel<<<grid_for(std::max(N, F), 4096), BLOCK, 0, s>>>(
-        d_verts, N, d_facets, F, B, c->voff[0], c->foff, c->vrec[0], c->cid, c->fbuf[0],
-        work ? c->s0_key[0] : nullptr, c->s0_val[0], c->st, c->hist12);
+    rc = launch_init(c, s, d_verts, N, d_facets, F, B, work);
+    if (rc != PICASSO_OK) return rc;
     if (overlap) {
         HIP_TRY(c, hipEventRecord(c->ev_fork, s));
         HIP_TRY(c, hipStreamWaitEvent(c->side, c->ev_fork, 0));
@@ -1852,6 +1918,13 @@ int picasso_create(picasso_ctx** out, int device, int64_t max_verts, int64_t max
         return PICASSO_ERR_HIP;
     }
     memset(c->h_pin, 0, c->h_pin_ints * sizeof(int));
+    // the incidence sort's digit counts start at zero; every S0 leaves them at zero again
+    if (hipMemset(c->hist12_s0, 0, sizeof(u32) * 2 * prim::MSD_HIST_WORDS) != hipSuccess) {
+        (void)hipHostFree(c->h_pin);
+        (void)hipFree(c->ws);
+        delete c;
+        return PICASSO_ERR_HIP;
+    }
     if (hipHostGetDevicePointer((void**)&c->h_pin_dev, c->h_pin, 0) != hipSuccess) {
         (void)hipHostFree(c->h_pin);
         (void)hipFree(c->ws);
@@ -1970,14 +2043,16 @@ int picasso_vertex_quadrics(picasso_ctx* c, void* stream, const float* d_verts, 
     int64_t n64, f64;
     int rc = upload_header(c, s, 1, &N, &F, &big, &n64, &f64);
     if (rc != PICASSO_OK) return rc;
-    init_kernel<<<grid_for(std::max(N, F), 4096), BLOCK, 0, s>>>(d_verts, N, d_facets, F, 1, c->voff[0], c->foff,
-                                                                 c->vrec[0], c->cid, c->fbuf[0], c->s0_key[0], c->s0_val[0],
-                                                                 c->st, c->hist12);
+    rc = launch_init(c, s, d_verts, N, d_facets, F, 1, true);
+    if (rc != PICASSO_OK) return rc;
     State* hst = reinterpret_cast<State*>(c->h_pin);
     rc = read_header(c, s);
     if (rc != PICASSO_OK) return rc;
     rc = status_from_err_bits(hst->err);
-    if (rc != PICASSO_OK) return rc;
+    if (rc != PICASSO_OK) {  // S0 will not run: take back the digit counts the validating kernel has added
+        prim::fill_u32_kernel<<<2 * prim::MSD_HIST_WORDS / BLOCK, BLOCK, 0, s>>>(c->hist12_s0, 2 * prim::MSD_HIST_WORDS, 0u);
+        return rc;
+    }
     rc = run_vertex_quadrics(c, s, d_verts, N, F);
     if (rc != PICASSO_OK) return rc;
     export_quadrics_kernel<<<grid_for(N), BLOCK, 0, s>>>(c->vrec[0], N, d_quadrics_out);
@@ -1997,14 +2072,16 @@ int picasso_edge_costs(picasso_ctx* c, void* stream, const float* d_verts, int32
     int64_t n64, f64;
     int rc = upload_header(c, s, 1, &N, &F, &one, &n64, &f64);
     if (rc != PICASSO_OK) return rc;
-    init_kernel<<<grid_for(std::max(N, F), 4096), BLOCK, 0, s>>>(d_verts, N, d_facets, F, 1, c->voff[0], c->foff,
-                                                                 c->vrec[0], c->cid, c->fbuf[0], c->s0_key[0], c->s0_val[0],
-                                                                 c->st, c->hist12);
+    rc = launch_init(c, s, d_verts, N, d_facets, F, 1, true);
+    if (rc != PICASSO_OK) return rc;
     State* hst = reinterpret_cast<State*>(c->h_pin);
     rc = read_header(c, s);
     if (rc != PICASSO_OK) return rc;
     rc = status_from_err_bits(hst->err);
-    if (rc != PICASSO_OK) return rc;
+    if (rc != PICASSO_OK) {  // S0 will not run: take back the digit counts the validating kernel has added
+        prim::fill_u32_kernel<<<2 * prim::MSD_HIST_WORDS / BLOCK, BLOCK, 0, s>>>(c->hist12_s0, 2 * prim::MSD_HIST_WORDS, 0u);
+        return rc;
+    }
     rc = run_vertex_quadrics(c, s, d_verts, N, F);
     if (rc != PICASSO_OK) return rc;
     const int vbits = ceil_log2(N), H = 3 * F;
@@ -2041,7 +2118,7 @@ int picasso_cluster_csr(picasso_ctx* c, void* stream, const int32_t* d_cluster_i
     const int where = sort_by_vertex<u32, true>(s, k0, k1, c->val32[0], c->val32[1], nullptr, n_in, ceil_log2(n_out),
                                                 c->sort_sc, c->hist12);
     if (where < 0) return PICASSO_ERR_HIP;
-    csr_offsets_kernel<<<grid_for(n_in), BLOCK, 0, s>>>(where ? k1 : k0, n_in, n_out, d_offsets);
+    csr_offsets_kernel<u32><<<grid_for(n_in), BLOCK, 0, s>>>(where ? k1 : k0, 0, n_in, n_out, d_offsets);
     HIP_TRY(c, hipMemcpyAsync(d_members, where ? c->val32[1] : c->val32[0], sizeof(int32_t) * (size_t)n_in,
                               hipMemcpyDeviceToDevice, s));
     int rc = read_header(c, s);

@@ -806,7 +806,7 @@ __global__ __launch_bounds__(BLOCK) void top_digit_histogram_kernel(const K* __r
 
 // Result is in (k1, v1): returns 1 (keys with values), or in k0: returns 0 (keys only); <0 on a
 // launch error.  hist12 holds 2 * MSD_HIST_WORDS words (counts, cursors).
-template <typename K, bool HAS_VAL>
+template <typename K, bool HAS_VAL, int KEYS_ONLY_ITEMS = 8>  // keys per lane of the bucket kernel without values
 inline int bucket_sort_large(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_ptr, int n_max, int key_bits,
                              const SortScratch& sc, u32* hist12, LaunchTimer* lt = nullptr, int tag = 0,
                              bool counted = false) {
@@ -822,7 +822,8 @@ inline int bucket_sort_large(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, cons
         }
         msd_scatter_kernel<K, BUCKET_LARGE_MSD_BITS, SORT_ITEMS_BIG><<<tiles, BLOCK, 0, s>>>(k0, k1, n_ptr, n_max, low, hist12, cursor);
         const bool timed = lt && lt->begin(s, tag);
-        bucket_sort_kernel<K, false, BUCKET_THREADS_4096, 8><<<R, BUCKET_THREADS_4096, 0, s>>>(k1, k0, nullptr, nullptr, hist12, R, low);
+        bucket_sort_kernel<K, false, BUCKET_THREADS_4096, KEYS_ONLY_ITEMS>
+            <<<R, BUCKET_THREADS_4096, 0, s>>>(k1, k0, nullptr, nullptr, hist12, R, low);
         if (timed) lt->end(s);
         if (hipGetLastError() != hipSuccess) return -1;
         return 0;
