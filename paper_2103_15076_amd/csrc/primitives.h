@@ -450,10 +450,10 @@ constexpr int BUCKET_GROUP_BITS = 9;
 constexpr int BUCKET_GROUP_MAX = 64;  // longest group the insertion sort is allowed
 
 template <typename K, bool HAS_VAL, int BUCKET_THREADS, int BUCKET_ITEMS>
-__global__ __launch_bounds__(BUCKET_THREADS) void bucket_sort_kernel(K* __restrict__ kin, K* __restrict__ kout,
-                                                                     u32* __restrict__ vin, u32* __restrict__ vout,
-                                                                     const u32* __restrict__ totals, int nbuckets,
-                                                                     int low_bits) {
+__device__ __forceinline__ void bucket_sort_one(const int bkt, K* __restrict__ kin, K* __restrict__ kout,
+                                                u32* __restrict__ vin, u32* __restrict__ vout,
+                                                const u32* __restrict__ totals, int low_bits, int only_above,
+                                                int leave_above) {
     constexpr int BUCKET_WAVES = BUCKET_THREADS / 64;
     constexpr int BUCKET_CAP = BUCKET_THREADS * BUCKET_ITEMS;  // keys of one bucket held in LDS
     constexpr int RMAX = 1 << BUCKET_GROUP_BITS;
@@ -464,12 +464,11 @@ __global__ __launch_bounds__(BUCKET_THREADS) void bucket_sort_kernel(K* __restri
     __shared__ u32 tstart[RMAX];
     __shared__ u32 smem[BUCKET_WAVES];
     const int t = threadIdx.x, w = wave_id(), lane = lane_id();
-    const int bkt = blockIdx.x;
 
     // start of this bucket = sum of the counts of the buckets before it
-    (void)nbuckets;
     const int cnt = (int)totals[bkt];
-    if (cnt == 0) return;
+    // (a second launch with more keys per lane, hence fewer workgroups per compute unit, may take the long buckets)
+    if (cnt == 0 || cnt <= only_above || cnt > leave_above) return;
     u32 part = 0, start;
     for (int j = t; j < bkt; j += BUCKET_THREADS) part += totals[j];
     (void)wide_block_exclusive_scan<BUCKET_WAVES>(part, smem, start);
@@ -590,6 +589,27 @@ __global__ __launch_bounds__(BUCKET_THREADS) void bucket_sort_kernel(K* __restri
     for (int i = t; i < cnt; i += BUCKET_THREADS) {
         kout[i] = skey[i];
         if (HAS_VAL) vout[i] = sval[i];
+    }
+}
+
+// A launch with one workgroup per bucket takes every bucket; a smaller grid walks over the buckets
+// (used for the few long buckets, selected by only_above, whose variant fits one workgroup per
+// compute unit: a full grid of workgroups that only look and leave would queue up behind that).
+template <typename K, bool HAS_VAL, int BUCKET_THREADS, int BUCKET_ITEMS, bool WALK = false>
+__global__ __launch_bounds__(BUCKET_THREADS) void bucket_sort_kernel(K* __restrict__ kin, K* __restrict__ kout,
+                                                                     u32* __restrict__ vin, u32* __restrict__ vout,
+                                                                     const u32* __restrict__ totals, int nbuckets,
+                                                                     int low_bits, int only_above = 0,
+                                                                     int leave_above = 0x7FFFFFFF) {
+    if constexpr (WALK) {
+        for (int bkt = blockIdx.x; bkt < nbuckets; bkt += gridDim.x) {
+            bucket_sort_one<K, HAS_VAL, BUCKET_THREADS, BUCKET_ITEMS>(bkt, kin, kout, vin, vout, totals, low_bits,
+                                                                      only_above, leave_above);
+            __syncthreads();
+        }
+    } else {
+        bucket_sort_one<K, HAS_VAL, BUCKET_THREADS, BUCKET_ITEMS>((int)blockIdx.x, kin, kout, vin, vout, totals,
+                                                                  low_bits, only_above, leave_above);
     }
 }
 
@@ -822,8 +842,17 @@ inline int bucket_sort_large(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, cons
         }
         msd_scatter_kernel<K, BUCKET_LARGE_MSD_BITS, SORT_ITEMS_BIG><<<tiles, BLOCK, 0, s>>>(k0, k1, n_ptr, n_max, low, hist12, cursor);
         const bool timed = lt && lt->begin(s, tag);
-        bucket_sort_kernel<K, false, BUCKET_THREADS_4096, KEYS_ONLY_ITEMS>
-            <<<R, BUCKET_THREADS_4096, 0, s>>>(k1, k0, nullptr, nullptr, hist12, R, low);
+        if constexpr (KEYS_ONLY_ITEMS > 8) {
+            // buckets of up to 4096 keys at three workgroups per compute unit, longer ones separately
+            constexpr int CAP8 = BUCKET_THREADS_4096 * 8;
+            bucket_sort_kernel<K, false, BUCKET_THREADS_4096, 8>
+                <<<R, BUCKET_THREADS_4096, 0, s>>>(k1, k0, nullptr, nullptr, hist12, R, low, 0, CAP8);
+            bucket_sort_kernel<K, false, BUCKET_THREADS_4096, KEYS_ONLY_ITEMS, true>
+                <<<256, BUCKET_THREADS_4096, 0, s>>>(k1, k0, nullptr, nullptr, hist12, R, low, CAP8);
+        } else {
+            bucket_sort_kernel<K, false, BUCKET_THREADS_4096, KEYS_ONLY_ITEMS>
+                <<<R, BUCKET_THREADS_4096, 0, s>>>(k1, k0, nullptr, nullptr, hist12, R, low);
+        }
         if (timed) lt->end(s);
         if (hipGetLastError() != hipSuccess) return -1;
         return 0;
