@@ -1273,7 +1273,7 @@ struct picasso_ctx {
     unsigned char* keep = nullptr;
     int* tilesum = nullptr;
     prim::SortScratch sort_sc{};
-    u32* hist12 = nullptr;  // the bucket sorts' top-digit counts and cursors (2 x prim::MSD_HIST_WORDS)
+    u32* hist12 = nullptr;  // the bucket sorts' top-digit counts, cursors and first positions (3 x prim::MSD_HIST_WORDS)
     // The vertex->facet sort has buffers and scratch of its own, so that in the first round it can
     // run beside the edge-key sort (neither depends on the other) on a second stream.
     u64* s0_key[2] = {nullptr, nullptr};  // incidence keys (vertex, facet) of S0 and their sort's second buffer
@@ -1383,14 +1383,14 @@ size_t carve(picasso_ctx* c, char* base, int64_t N, int64_t F, int32_t B) {
     x->sort_sc.T = prim::sort_table_stride((long long)h);
     x->sort_sc.table = cv.take<u32>((size_t)256 * x->sort_sc.T);
     x->sort_sc.totals = cv.take<u32>(256);
-    x->hist12 = cv.take<u32>(2 * prim::MSD_HIST_WORDS);
+    x->hist12 = cv.take<u32>(3 * prim::MSD_HIST_WORDS);
     for (int i = 0; i < 2; ++i) {
         x->s0_key[i] = cv.take<u64>(h);
     }
     x->sort_sc_s0.T = x->sort_sc.T;
     x->sort_sc_s0.table = cv.take<u32>((size_t)256 * x->sort_sc_s0.T);
     x->sort_sc_s0.totals = cv.take<u32>(256);
-    x->hist12_s0 = cv.take<u32>(2 * prim::MSD_HIST_WORDS);
+    x->hist12_s0 = cv.take<u32>(3 * prim::MSD_HIST_WORDS);
     x->voff[1] = cv.take<int>(b + 1);
     x->nrem = cv.take<int>(b);
     x->segstart = cv.take<int>(b);

@@ -452,8 +452,8 @@ constexpr int BUCKET_GROUP_MAX = 64;  // longest group the insertion sort is all
 template <typename K, bool HAS_VAL, int BUCKET_THREADS, int BUCKET_ITEMS>
 __device__ __forceinline__ void bucket_sort_one(const int bkt, K* __restrict__ kin, K* __restrict__ kout,
                                                 u32* __restrict__ vin, u32* __restrict__ vout,
-                                                const u32* __restrict__ totals, int low_bits, int only_above,
-                                                int leave_above) {
+                                                const u32* __restrict__ totals, const u32* __restrict__ starts,
+                                                int low_bits, int only_above, int leave_above) {
     constexpr int BUCKET_WAVES = BUCKET_THREADS / 64;
     constexpr int BUCKET_CAP = BUCKET_THREADS * BUCKET_ITEMS;  // keys of one bucket held in LDS
     constexpr int RMAX = 1 << BUCKET_GROUP_BITS;
@@ -465,14 +465,19 @@ __device__ __forceinline__ void bucket_sort_one(const int bkt, K* __restrict__ k
     __shared__ u32 smem[BUCKET_WAVES];
     const int t = threadIdx.x, w = wave_id(), lane = lane_id();
 
-    // start of this bucket = sum of the counts of the buckets before it
+    // start of this bucket = sum of the counts of the buckets before it (given, or summed here)
     const int cnt = (int)totals[bkt];
     // (a second launch with more keys per lane, hence fewer workgroups per compute unit, may take the long buckets)
     if (cnt == 0 || cnt <= only_above || cnt > leave_above) return;
-    u32 part = 0, start;
-    for (int j = t; j < bkt; j += BUCKET_THREADS) part += totals[j];
-    (void)wide_block_exclusive_scan<BUCKET_WAVES>(part, smem, start);
-    __syncthreads();
+    u32 start;
+    if (starts) {  // (the partition kernel has left them)
+        start = starts[bkt];
+    } else {
+        u32 part = 0;
+        for (int j = t; j < bkt; j += BUCKET_THREADS) part += totals[j];
+        (void)wide_block_exclusive_scan<BUCKET_WAVES>(part, smem, start);
+        __syncthreads();
+    }
     if (cnt > BUCKET_CAP) {
         bucket_sort_oversize<K, HAS_VAL, BUCKET_THREADS>(kout + start, kin + start, HAS_VAL ? vout + start : nullptr,
                                          HAS_VAL ? vin + start : nullptr, cnt, low_bits, tstart, smem);
@@ -599,17 +604,17 @@ template <typename K, bool HAS_VAL, int BUCKET_THREADS, int BUCKET_ITEMS, bool W
 __global__ __launch_bounds__(BUCKET_THREADS) void bucket_sort_kernel(K* __restrict__ kin, K* __restrict__ kout,
                                                                      u32* __restrict__ vin, u32* __restrict__ vout,
                                                                      const u32* __restrict__ totals, int nbuckets,
-                                                                     int low_bits, int only_above = 0,
-                                                                     int leave_above = 0x7FFFFFFF) {
+                                                                     int low_bits, const u32* __restrict__ starts = nullptr,
+                                                                     int only_above = 0, int leave_above = 0x7FFFFFFF) {
     if constexpr (WALK) {
         for (int bkt = blockIdx.x; bkt < nbuckets; bkt += gridDim.x) {
-            bucket_sort_one<K, HAS_VAL, BUCKET_THREADS, BUCKET_ITEMS>(bkt, kin, kout, vin, vout, totals, low_bits,
-                                                                      only_above, leave_above);
+            bucket_sort_one<K, HAS_VAL, BUCKET_THREADS, BUCKET_ITEMS>(bkt, kin, kout, vin, vout, totals, starts,
+                                                                      low_bits, only_above, leave_above);
             __syncthreads();
         }
     } else {
         bucket_sort_one<K, HAS_VAL, BUCKET_THREADS, BUCKET_ITEMS>((int)blockIdx.x, kin, kout, vin, vout, totals,
-                                                                  low_bits, only_above, leave_above);
+                                                                  starts, low_bits, only_above, leave_above);
     }
 }
 
@@ -641,8 +646,8 @@ __global__ __launch_bounds__(BLOCK) void msd_histogram_kernel(const K* __restric
 
 // Partition of keys WITHOUT values by their top digit (bits [shift, shift + RBITS)) in one pass.
 // hist[d] = number of keys with digit d over the whole input (so digit d owns the output range
-// that starts at the sum of the counts before it); cursor[d] = how much of that range is taken,
-// zero at the start.  Every tile counts its keys per digit in LDS, takes its share of each
+// that starts at the sum of the counts before it; the first tile also writes these first
+// positions to `starts`); cursor[d] = how much of that range is taken, zero at the start.  Every tile counts its keys per digit in LDS, takes its share of each
 // digit's range with one returning atomic per digit it holds, and writes its keys there.  The
 // order of the keys inside a digit's range depends on the order in which tiles arrive, so this is
 // for sorts that then order each range on the whole key; with equal keys indistinguishable the
@@ -651,7 +656,8 @@ __global__ __launch_bounds__(BLOCK) void msd_histogram_kernel(const K* __restric
 template <typename K, int RBITS, int ITEMS>
 __global__ __launch_bounds__(BLOCK) void msd_scatter_kernel(const K* __restrict__ kin, K* __restrict__ kout,
                                                             const int* n_ptr, int n_host, int shift,
-                                                            const u32* __restrict__ hist, u32* __restrict__ cursor) {
+                                                            const u32* __restrict__ hist, u32* __restrict__ cursor,
+                                                            u32* __restrict__ starts) {
     constexpr int R = 1 << RBITS;
     constexpr int PER = R / BLOCK;  // digits per thread in the scan of the ranges' first positions
     static_assert(R % BLOCK == 0, "whole digits per thread");
@@ -683,6 +689,7 @@ __global__ __launch_bounds__(BLOCK) void msd_scatter_kernel(const K* __restrict_
 #pragma unroll
         for (int j = 0; j < PER; ++j) {
             first[t * PER + j] = run;
+            if (blockIdx.x == 0) starts[t * PER + j] = run;  // for the kernel that sorts the ranges
             run += c[j];
         }
     }
@@ -723,7 +730,8 @@ __global__ __launch_bounds__(BLOCK) void msd_scatter_kernel(const K* __restrict_
 
 // Keys without values are partitioned by msd_scatter_kernel, which works from a histogram of the
 // top digit in msd_hist[0, R) and cursors in msd_hist[MSD_HIST_WORDS, MSD_HIST_WORDS + R), both
-// zeroed beforehand (msd_hist holds 2 * MSD_HIST_WORDS words).  `counted`: the producer of the
+// zeroed beforehand; the ranges' first positions go to msd_hist[2 * MSD_HIST_WORDS, ...) (msd_hist
+// holds 3 * MSD_HIST_WORDS words).  `counted`: the producer of the
 // keys has already added the keys' digits to that (zeroed) histogram and left the cursors zero,
 // so the histogram pass over the keys is skipped.
 constexpr int MSD_HIST_WORDS = 4096;
@@ -751,10 +759,11 @@ inline int bucket_sort(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int*
                 fill_u32_kernel<<<2 * MSD_HIST_WORDS / BLOCK, BLOCK, 0, s>>>(msd_hist, 2 * MSD_HIST_WORDS, 0u);
                 msd_histogram_kernel<K, BUCKET_MSD_BITS, SORT_ITEMS_SMALL><<<tiles, BLOCK, 0, s>>>(k0, n_ptr, n_max, msd_hist, low);
             }
-            msd_scatter_kernel<K, BUCKET_MSD_BITS, SORT_ITEMS_SMALL><<<tiles, BLOCK, 0, s>>>(k0, k1, n_ptr, n_max, low, msd_hist, cursor);
+            u32* starts = msd_hist + 2 * MSD_HIST_WORDS;
+            msd_scatter_kernel<K, BUCKET_MSD_BITS, SORT_ITEMS_SMALL><<<tiles, BLOCK, 0, s>>>(k0, k1, n_ptr, n_max, low, msd_hist, cursor, starts);
             const bool timed = lt && lt->begin(s, tag);
             bucket_sort_kernel<K, false, BUCKET_THREADS_256, 8>
-                <<<1 << msd, BUCKET_THREADS_256, 0, s>>>(k1, k0, nullptr, nullptr, msd_hist, 1 << msd, low);
+                <<<1 << msd, BUCKET_THREADS_256, 0, s>>>(k1, k0, nullptr, nullptr, msd_hist, 1 << msd, low, starts);
             if (timed) lt->end(s);
             if (hipGetLastError() != hipSuccess) return -1;
             return 0;
@@ -825,7 +834,7 @@ __global__ __launch_bounds__(BLOCK) void top_digit_histogram_kernel(const K* __r
 }
 
 // Result is in (k1, v1): returns 1 (keys with values), or in k0: returns 0 (keys only); <0 on a
-// launch error.  hist12 holds 2 * MSD_HIST_WORDS words (counts, cursors).
+// launch error.  hist12 holds 3 * MSD_HIST_WORDS words (counts, cursors, first positions).
 template <typename K, bool HAS_VAL, int KEYS_ONLY_ITEMS = 8>  // keys per lane of the bucket kernel without values
 inline int bucket_sort_large(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_ptr, int n_max, int key_bits,
                              const SortScratch& sc, u32* hist12, LaunchTimer* lt = nullptr, int tag = 0,
@@ -840,18 +849,19 @@ inline int bucket_sort_large(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, cons
             fill_u32_kernel<<<2 * MSD_HIST_WORDS / BLOCK, BLOCK, 0, s>>>(hist12, 2 * MSD_HIST_WORDS, 0u);
             msd_histogram_kernel<K, BUCKET_LARGE_MSD_BITS, SORT_ITEMS_BIG><<<tiles, BLOCK, 0, s>>>(k0, n_ptr, n_max, hist12, low);
         }
-        msd_scatter_kernel<K, BUCKET_LARGE_MSD_BITS, SORT_ITEMS_BIG><<<tiles, BLOCK, 0, s>>>(k0, k1, n_ptr, n_max, low, hist12, cursor);
+        u32* starts = hist12 + 2 * MSD_HIST_WORDS;
+        msd_scatter_kernel<K, BUCKET_LARGE_MSD_BITS, SORT_ITEMS_BIG><<<tiles, BLOCK, 0, s>>>(k0, k1, n_ptr, n_max, low, hist12, cursor, starts);
         const bool timed = lt && lt->begin(s, tag);
         if constexpr (KEYS_ONLY_ITEMS > 8) {
             // buckets of up to 4096 keys at three workgroups per compute unit, longer ones separately
             constexpr int CAP8 = BUCKET_THREADS_4096 * 8;
             bucket_sort_kernel<K, false, BUCKET_THREADS_4096, 8>
-                <<<R, BUCKET_THREADS_4096, 0, s>>>(k1, k0, nullptr, nullptr, hist12, R, low, 0, CAP8);
+                <<<R, BUCKET_THREADS_4096, 0, s>>>(k1, k0, nullptr, nullptr, hist12, R, low, starts, 0, CAP8);
             bucket_sort_kernel<K, false, BUCKET_THREADS_4096, KEYS_ONLY_ITEMS, true>
-                <<<256, BUCKET_THREADS_4096, 0, s>>>(k1, k0, nullptr, nullptr, hist12, R, low, CAP8);
+                <<<256, BUCKET_THREADS_4096, 0, s>>>(k1, k0, nullptr, nullptr, hist12, R, low, starts, CAP8);
         } else {
             bucket_sort_kernel<K, false, BUCKET_THREADS_4096, KEYS_ONLY_ITEMS>
-                <<<R, BUCKET_THREADS_4096, 0, s>>>(k1, k0, nullptr, nullptr, hist12, R, low);
+                <<<R, BUCKET_THREADS_4096, 0, s>>>(k1, k0, nullptr, nullptr, hist12, R, low, starts);
         }
         if (timed) lt->end(s);
         if (hipGetLastError() != hipSuccess) return -1;
