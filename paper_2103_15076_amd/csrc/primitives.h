@@ -82,6 +82,8 @@ __device__ __forceinline__ u32 digit_of(K k, int shift, u32 mask) {
 // of them adds their number to wrow[d] with one LDS atomic, whose return value (the count left by
 // the earlier items: LDS operations of a wave complete in order) it then hands to the others.
 // Four items go through together so that four atomics are in flight instead of one.
+constexpr int WAVE_RANK_MAX_BITS = 9;  // widest digit wave_rank_digits takes
+
 template <int ITEMS>
 __device__ __forceinline__ void wave_rank_digits(const u32 (&digit)[ITEMS], int items, int bits, u32* wrow,
                                                  u32 (&rank)[ITEMS]) {
@@ -97,12 +99,19 @@ __device__ __forceinline__ void wave_rank_digits(const u32 (&digit)[ITEMS], int 
             old[j] = 0;
             if (i0 + j < items) {
                 const u32 d = digit[i0 + j];
-                u64 m = ~0ull;  // lanes of this wave holding the same digit
-                for (int b = 0; b < bits; ++b) {
-                    const bool bit = (d >> b) & 1u;
-                    const u64 bal = __ballot(bit);
-                    m &= bit ? bal : ~bal;
+                // lanes whose digit differs from this lane's in some bit: per bit, the ballot of the
+                // bit XOR this lane's own bit spread over a word (unrolled; `bits` is wave-uniform)
+                u32 dlo = 0, dhi = 0;
+#pragma unroll
+                for (int b = 0; b < WAVE_RANK_MAX_BITS; ++b) {
+                    if (b < bits) {
+                        const int own = (int)(d << (31 - b)) >> 31;  // 0 or -1
+                        const u64 bal = __ballot(own != 0);
+                        dlo |= (u32)bal ^ (u32)own;
+                        dhi |= (u32)(bal >> 32) ^ (u32)own;
+                    }
                 }
+                const u64 m = ~(((u64)dhi << 32) | dlo);  // lanes of this wave holding the same digit
                 below[j] = (u32)__popcll(m & lt);
                 leader[j] = __ffsll((long long)m) - 1;
                 if (below[j] == 0) old[j] = atomicAdd(&wrow[d], (u32)__popcll(m));
@@ -441,7 +450,8 @@ __device__ void bucket_sort_oversize(K* a, K* b, u32* va, u32* vb, int cnt, int 
 // low bits splits it into up to 512 groups of keys that agree on all bits
 // sorted so far; with vertex-pair keys a group is the handful of half-edges of
 // one lower vertex.  Each group is then finished by one lane with a stable
-// insertion sort on the whole key, which for such groups costs far less than
+// sort on the whole key (by counting ranks in registers for up to 16 keys,
+// by insertion in place beyond), which for such groups costs far less than
 // the two or three more radix passes over every key that the remaining bits
 // would take (a radix pass spends one wave-wide ballot per key and bit).  If
 // some group is long (keys crowded on few values of those 9 bits), the
@@ -449,7 +459,64 @@ __device__ void bucket_sort_oversize(K* a, K* b, u32* va, u32* vb, int cnt, int 
 constexpr int BUCKET_GROUP_BITS = 9;
 constexpr int BUCKET_GROUP_MAX = 64;  // longest group the insertion sort is allowed
 
-template <typename K, bool HAS_VAL, int BUCKET_THREADS, int BUCKET_ITEMS>
+// Stable sort of the g <= G keys at [gs, gs + g) of an LDS array by one lane: the keys are read into
+// registers together, each key's place is the number of keys that must precede it (G x G
+// comparisons, none of which waits for memory), and the keys are written back to their places.
+template <typename K, bool HAS_VAL, int G>
+__device__ __forceinline__ void group_rank_sort(K* skey, u32* sval, int gs, int g) {
+    K k[G];
+    u32 v[G];
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+        k[j] = j < g ? skey[gs + j] : (K)0;
+        v[j] = (HAS_VAL && j < g) ? sval[gs + j] : 0u;
+    }
+#pragma unroll
+    for (int i = 0; i < G; ++i) {
+        if (i < g) {
+            int r = 0;
+#pragma unroll
+            for (int j = 0; j < G; ++j) r += (j < g && (k[j] < k[i] || (k[j] == k[i] && j < i))) ? 1 : 0;
+            skey[gs + r] = k[i];
+            if (HAS_VAL) sval[gs + r] = v[i];
+        }
+    }
+}
+
+// The same for keys without values (so that equal keys need no order among themselves): a bitonic
+// sorting network over G registers, G a power of two, empty places filled with the largest key.
+template <typename K, int G>
+__device__ __forceinline__ void group_network_sort(K* skey, int gs, int g) {
+    K k[G];
+#pragma unroll
+    for (int j = 0; j < G; ++j) k[j] = j < g ? skey[gs + j] : (K) ~(K)0;
+#pragma unroll
+    for (int size = 2; size <= G; size <<= 1) {
+#pragma unroll
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+#pragma unroll
+            for (int i = 0; i < G; ++i) {
+                const int l = i ^ stride;
+                if (l > i) {
+                    const bool up = (i & size) == 0;
+                    const K a = k[i], b = k[l];
+                    const bool swap = up ? (a > b) : (a < b);
+                    k[i] = swap ? b : a;
+                    k[l] = swap ? a : b;
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < G; ++j)
+        if (j < g) skey[gs + j] = k[j];
+}
+
+// LK = type of the keys while they are in LDS and registers.  All keys of a bucket agree above
+// their low_bits bits, so 64-bit keys with low_bits <= 32 are kept as their low 32 bits (LK = u32:
+// half the LDS, registers and comparison work) and get their common upper part back, bucket <<
+// low_bits, on the way out.
+template <typename K, bool HAS_VAL, int BUCKET_THREADS, int BUCKET_ITEMS, typename LK = K>
 __device__ __forceinline__ void bucket_sort_one(const int bkt, K* __restrict__ kin, K* __restrict__ kout,
                                                 u32* __restrict__ vin, u32* __restrict__ vout,
                                                 const u32* __restrict__ totals, const u32* __restrict__ starts,
@@ -458,7 +525,7 @@ __device__ __forceinline__ void bucket_sort_one(const int bkt, K* __restrict__ k
     constexpr int BUCKET_CAP = BUCKET_THREADS * BUCKET_ITEMS;  // keys of one bucket held in LDS
     constexpr int RMAX = 1 << BUCKET_GROUP_BITS;
     static_assert(RMAX <= BUCKET_THREADS, "one thread per digit in the scans below");
-    __shared__ K skey[BUCKET_CAP];
+    __shared__ LK skey[BUCKET_CAP];
     __shared__ u32 sval[HAS_VAL ? BUCKET_CAP : 1];
     __shared__ u32 wcnt[BUCKET_WAVES][RMAX];
     __shared__ u32 tstart[RMAX];
@@ -507,22 +574,22 @@ __device__ __forceinline__ void bucket_sort_one(const int bkt, K* __restrict__ k
         const u32 R = 1u << bits, dmask = R - 1;
         for (int i = t; i < BUCKET_WAVES * RMAX; i += BUCKET_THREADS)
             if ((u32)(i & (RMAX - 1)) < R) (&wcnt[0][0])[i] = 0;
-        K key[BUCKET_ITEMS];
+        LK key[BUCKET_ITEMS];
         u32 val[BUCKET_ITEMS];
         u32 rank[BUCKET_ITEMS];
         u32 digit[BUCKET_ITEMS];
 #pragma unroll
         for (int i = 0; i < BUCKET_ITEMS; ++i) {
-            key[i] = (K) ~(K)0;  // padding ranks last and is dropped
+            key[i] = (LK) ~(LK)0;  // padding ranks last and is dropped
             val[i] = 0u;
             if (i < items) {
                 const int idx = w * (64 * items) + i * 64 + lane;
                 if (idx < cnt) {
-                    key[i] = FROM_MEMORY ? kin[idx] : skey[idx];
+                    key[i] = FROM_MEMORY ? (LK)kin[idx] : skey[idx];
                     if (HAS_VAL) val[i] = FROM_MEMORY ? vin[idx] : sval[idx];
                 }
             }
-            digit[i] = digit_of<K>(key[i], shift, dmask);
+            digit[i] = digit_of<LK>(key[i], shift, dmask);
         }
         __syncthreads();
         wave_rank_digits<BUCKET_ITEMS>(digit, items, bits, wcnt[w], rank);
@@ -567,17 +634,29 @@ __device__ __forceinline__ void bucket_sort_one(const int bkt, K* __restrict__ k
             if (ge > cnt) ge = cnt;
         }
         if (!__syncthreads_or(ge - gs > BUCKET_GROUP_MAX)) {
-            for (int i = gs + 1; i < ge; ++i) {
-                const K k = skey[i];
-                const u32 v = HAS_VAL ? sval[i] : 0u;
-                int j = i;
-                while (j > gs && skey[j - 1] > k) {
-                    skey[j] = skey[j - 1];
-                    if (HAS_VAL) sval[j] = sval[j - 1];
-                    --j;
+            const int g = ge - gs;
+            if (g > 16) {  // one lane, in place: every step waits for LDS, so only for the rare long group
+                for (int i = gs + 1; i < ge; ++i) {
+                    const LK k = skey[i];
+                    const u32 v = HAS_VAL ? sval[i] : 0u;
+                    int j = i;
+                    while (j > gs && skey[j - 1] > k) {
+                        skey[j] = skey[j - 1];
+                        if (HAS_VAL) sval[j] = sval[j - 1];
+                        --j;
+                    }
+                    skey[j] = k;
+                    if (HAS_VAL) sval[j] = v;
                 }
-                skey[j] = k;
-                if (HAS_VAL) sval[j] = v;
+            } else if (g > 8) {
+                if constexpr (HAS_VAL) group_rank_sort<LK, true, 16>(skey, sval, gs, g);
+                else group_network_sort<LK, 16>(skey, gs, g);
+            } else if (g > 4) {
+                if constexpr (HAS_VAL) group_rank_sort<LK, true, 8>(skey, sval, gs, g);
+                else group_network_sort<LK, 8>(skey, gs, g);
+            } else if (g > 1) {
+                if constexpr (HAS_VAL) group_rank_sort<LK, true, 4>(skey, sval, gs, g);
+                else group_network_sort<LK, 4>(skey, gs, g);
             }
             __syncthreads();
         } else {
@@ -591,8 +670,10 @@ __device__ __forceinline__ void bucket_sort_one(const int bkt, K* __restrict__ k
             }
         }
     }
+    K upper = 0;
+    if constexpr (sizeof(LK) < sizeof(K)) upper = (K)(u32)bkt << low_bits;
     for (int i = t; i < cnt; i += BUCKET_THREADS) {
-        kout[i] = skey[i];
+        kout[i] = upper | (K)skey[i];
         if (HAS_VAL) vout[i] = sval[i];
     }
 }
@@ -600,22 +681,44 @@ __device__ __forceinline__ void bucket_sort_one(const int bkt, K* __restrict__ k
 // A launch with one workgroup per bucket takes every bucket; a smaller grid walks over the buckets
 // (used for the few long buckets, selected by only_above, whose variant fits one workgroup per
 // compute unit: a full grid of workgroups that only look and leave would queue up behind that).
-template <typename K, bool HAS_VAL, int BUCKET_THREADS, int BUCKET_ITEMS, bool WALK = false>
+template <typename K, bool HAS_VAL, int BUCKET_THREADS, int BUCKET_ITEMS, bool WALK = false, typename LK = K>
 __global__ __launch_bounds__(BUCKET_THREADS) void bucket_sort_kernel(K* __restrict__ kin, K* __restrict__ kout,
                                                                      u32* __restrict__ vin, u32* __restrict__ vout,
                                                                      const u32* __restrict__ totals, int nbuckets,
                                                                      int low_bits, const u32* __restrict__ starts = nullptr,
                                                                      int only_above = 0, int leave_above = 0x7FFFFFFF) {
     if constexpr (WALK) {
-        for (int bkt = blockIdx.x; bkt < nbuckets; bkt += gridDim.x) {
-            bucket_sort_one<K, HAS_VAL, BUCKET_THREADS, BUCKET_ITEMS>(bkt, kin, kout, vin, vout, totals, starts,
-                                                                      low_bits, only_above, leave_above);
-            __syncthreads();
+        // every wave looks at the sizes of the workgroup's next 64 buckets at once (same loads, same
+        // ballot in every wave), and the workgroup then visits only those it has to sort
+        for (int base = blockIdx.x; base < nbuckets; base += 64 * gridDim.x) {
+            const int mine = base + lane_id() * (int)gridDim.x;
+            const int c = mine < nbuckets ? (int)totals[mine] : 0;
+            u64 todo = __ballot(c > 0 && c > only_above && c <= leave_above);
+            while (todo) {
+                const int j = __ffsll((long long)todo) - 1;
+                todo &= todo - 1;
+                bucket_sort_one<K, HAS_VAL, BUCKET_THREADS, BUCKET_ITEMS, LK>(base + j * (int)gridDim.x, kin, kout, vin,
+                                                                              vout, totals, starts, low_bits,
+                                                                              only_above, leave_above);
+                __syncthreads();
+            }
         }
     } else {
-        bucket_sort_one<K, HAS_VAL, BUCKET_THREADS, BUCKET_ITEMS>((int)blockIdx.x, kin, kout, vin, vout, totals,
-                                                                  starts, low_bits, only_above, leave_above);
+        bucket_sort_one<K, HAS_VAL, BUCKET_THREADS, BUCKET_ITEMS, LK>((int)blockIdx.x, kin, kout, vin, vout, totals,
+                                                                      starts, low_bits, only_above, leave_above);
     }
+}
+
+// Launch of the keys-only bucket kernel with the narrowest in-LDS key type that holds low_bits bits.
+template <typename K, int BUCKET_THREADS, int BUCKET_ITEMS, bool WALK>
+inline void launch_bucket_keys(int grid, hipStream_t s, K* kin, K* kout, const u32* totals, int nbuckets, int low_bits,
+                               const u32* starts, int only_above = 0, int leave_above = 0x7FFFFFFF) {
+    if (sizeof(K) == 8 && low_bits <= 32)
+        bucket_sort_kernel<K, false, BUCKET_THREADS, BUCKET_ITEMS, WALK, u32><<<grid, BUCKET_THREADS, 0, s>>>(
+            kin, kout, nullptr, nullptr, totals, nbuckets, low_bits, starts, only_above, leave_above);
+    else
+        bucket_sort_kernel<K, false, BUCKET_THREADS, BUCKET_ITEMS, WALK, K><<<grid, BUCKET_THREADS, 0, s>>>(
+            kin, kout, nullptr, nullptr, totals, nbuckets, low_bits, starts, only_above, leave_above);
 }
 
 // Histogram of the top RBITS-bit digit (bits [shift, shift + RBITS)) over the whole input, added
@@ -762,8 +865,7 @@ inline int bucket_sort(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int*
             u32* starts = msd_hist + 2 * MSD_HIST_WORDS;
             msd_scatter_kernel<K, BUCKET_MSD_BITS, SORT_ITEMS_SMALL><<<tiles, BLOCK, 0, s>>>(k0, k1, n_ptr, n_max, low, msd_hist, cursor, starts);
             const bool timed = lt && lt->begin(s, tag);
-            bucket_sort_kernel<K, false, BUCKET_THREADS_256, 8>
-                <<<1 << msd, BUCKET_THREADS_256, 0, s>>>(k1, k0, nullptr, nullptr, msd_hist, 1 << msd, low, starts);
+            launch_bucket_keys<K, BUCKET_THREADS_256, 8, false>(1 << msd, s, k1, k0, msd_hist, 1 << msd, low, starts);
             if (timed) lt->end(s);
             if (hipGetLastError() != hipSuccess) return -1;
             return 0;
@@ -855,13 +957,10 @@ inline int bucket_sort_large(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, cons
         if constexpr (KEYS_ONLY_ITEMS > 8) {
             // buckets of up to 4096 keys at three workgroups per compute unit, longer ones separately
             constexpr int CAP8 = BUCKET_THREADS_4096 * 8;
-            bucket_sort_kernel<K, false, BUCKET_THREADS_4096, 8>
-                <<<R, BUCKET_THREADS_4096, 0, s>>>(k1, k0, nullptr, nullptr, hist12, R, low, starts, 0, CAP8);
-            bucket_sort_kernel<K, false, BUCKET_THREADS_4096, KEYS_ONLY_ITEMS, true>
-                <<<256, BUCKET_THREADS_4096, 0, s>>>(k1, k0, nullptr, nullptr, hist12, R, low, starts, CAP8);
+            launch_bucket_keys<K, BUCKET_THREADS_4096, 8, false>(R, s, k1, k0, hist12, R, low, starts, 0, CAP8);
+            launch_bucket_keys<K, BUCKET_THREADS_4096, KEYS_ONLY_ITEMS, true>(256, s, k1, k0, hist12, R, low, starts, CAP8);
         } else {
-            bucket_sort_kernel<K, false, BUCKET_THREADS_4096, KEYS_ONLY_ITEMS>
-                <<<R, BUCKET_THREADS_4096, 0, s>>>(k1, k0, nullptr, nullptr, hist12, R, low, starts);
+            launch_bucket_keys<K, BUCKET_THREADS_4096, KEYS_ONLY_ITEMS, false>(R, s, k1, k0, hist12, R, low, starts);
         }
         if (timed) lt->end(s);
         if (hipGetLastError() != hipSuccess) return -1;
