@@ -533,6 +533,19 @@ __device__ __forceinline__ void count_pairs(const SelArgs& A, bool sel, int m) {
     }
 }
 
+// The same into an LDS array (one workgroup's own tally).
+__device__ __forceinline__ void count_pairs_lds(int* pairs, bool sel, int m) {
+    const int lane = prim::lane_id();
+    u64 sb = __ballot(sel);
+    while (sb) {
+        const int leader = __ffsll((long long)sb) - 1;
+        const int m0 = __shfl(m, leader, 64);
+        const u64 same = __ballot(sel && m == m0);
+        if (lane == leader) atomicAdd(&pairs[m0], (int)__popcll(same));
+        sb &= ~same;
+    }
+}
+
 // Grid-wide sub-round over ALL edges of the round; retired edges are skipped by
 // their state byte.  No worklist is kept here: appending survivors would need
 // one returning atomic per workgroup on a single counter, and thousands of
@@ -655,6 +668,7 @@ struct LiveOut {
 // A slot's bid doubles as its "paired" mark (TAIL_PAIRED is below every real
 // priority: a finite cost never has cost key 0).
 constexpr int TAIL_SLOTS = 8192;  // power of two, >= 2 * TAIL_MAX
+constexpr int TAIL_LDS_MESHES = 1024;
 constexpr u64 TAIL_PAIRED = 0ull;
 
 struct TailLds {
@@ -664,6 +678,7 @@ struct TailLds {
     unsigned short su[TAIL_MAX], sv[TAIL_MAX];
     unsigned short lst[2][TAIL_MAX];
     int cnt[2];
+    int pairs[TAIL_LDS_MESHES];  // pairs this kernel formed, per mesh (batches of up to this many meshes)
 };
 
 __device__ __forceinline__ int tail_slot(int* vkey, int v) {
@@ -694,6 +709,12 @@ __global__ __launch_bounds__(TAIL_THREADS) void select_tail_kernel(SelArgs A) {
     const u64 lt = prim::lanemask_lt();
     const u64 vmask = (1ull << A.vbits) - 1ull;
 
+    // Up to TAIL_LDS_MESHES meshes, the pairs formed here are tallied in LDS and added to the earlier
+    // kernels' counters at the end; that way nothing this kernel writes to memory is read back by
+    // it, and it needs no device-wide fence (which costs several microseconds here).
+    const bool lds_pairs = A.mt.B <= TAIL_LDS_MESHES;
+    if (lds_pairs)
+        for (int b = tid; b < A.mt.B; b += TAIL_THREADS) L.pairs[b] = 0;
     for (int h = tid; h < TAIL_SLOTS; h += TAIL_THREADS) L.vkey[h] = -1;
     __syncthreads();
     for (int i = tid; i < n; i += TAIL_THREADS) {
@@ -741,7 +762,8 @@ __global__ __launch_bounds__(TAIL_THREADS) void select_tail_kernel(SelArgs A) {
                 }
             }
             mine[q] = sel;
-            count_pairs(A, sel, m);
+            if (lds_pairs) count_pairs_lds(L.pairs, sel, m);
+            else count_pairs(A, sel, m);
         }
         __syncthreads();
         q = 0;
@@ -774,19 +796,39 @@ __global__ __launch_bounds__(TAIL_THREADS) void select_tail_kernel(SelArgs A) {
         __syncthreads();
     }
 
-    __threadfence();  // the pair counts added above are at the L2 before they are summed
-    __syncthreads();
-    for (int b = tid; b < A.mt.B; b += TAIL_THREADS) {
+    static_assert(MATCH_SLOTS == 32, "a mesh's slots fill half a wave");
+    constexpr int STATE_INTS = (int)(sizeof(State) / sizeof(int));
+    if (!lds_pairs) {
+        __threadfence();  // the pair counts added above are at the L2 before they are summed
+        __syncthreads();
+    }
+    // one lane per counter slot (a mesh's MATCH_SLOTS slots sit in neighbouring lanes), so that the
+    // loads are in flight together; whole waves run each step for the shuffles
+    for (int base = 0; base < A.mt.B * MATCH_SLOTS; base += TAIL_THREADS) {
+        const int idx = base + tid;
+        const bool ok = idx < A.mt.B * MATCH_SLOTS;
         int sum = 0;
-        for (int j = 0; j < MATCH_SLOTS; ++j)
-            sum += __hip_atomic_load(&A.mt.mslots[((size_t)b * MATCH_SLOTS + j) * MATCH_PAD], __ATOMIC_RELAXED,
-                                     __HIP_MEMORY_SCOPE_AGENT);
-        A.mt.matched[b] = sum;
+        if (ok) sum = __hip_atomic_load(&A.mt.mslots[(size_t)idx * MATCH_PAD], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int d = MATCH_SLOTS / 2; d > 0; d >>= 1) sum += __shfl_xor(sum, d, 64);
+        if (ok && (idx & (MATCH_SLOTS - 1)) == 0) {
+            const int b = idx / MATCH_SLOTS;
+            if (lds_pairs) sum += L.pairs[b];
+            A.mt.matched[b] = sum;
+            if (lds_pairs && STATE_INTS + b < A.publish_ints) A.host_img[STATE_INTS + b] = sum;
+        }
     }
     if (tid == 0) A.st->live[0] = 0;
-    __threadfence();
-    __syncthreads();
-    tail_publish(A, tid);
+    if (lds_pairs) {
+        // the host's copy of the counters: everything but live[0] was written by earlier kernels
+        constexpr int LIVE0 = (int)(offsetof(State, live) / sizeof(int));
+        const int* hdr = reinterpret_cast<const int*>(A.st);
+        if (tid < STATE_INTS && tid < A.publish_ints) A.host_img[tid] = (tid == LIVE0) ? 0 : hdr[tid];
+    } else {
+        __threadfence();
+        __syncthreads();
+        tail_publish(A, tid);
+    }
 }
 
 // ---------------------------------------------------------------------------
