@@ -405,6 +405,21 @@ def test_single_stream_and_two_stream_first_round_agree(pk, ctx):
     assert all(r == res[0] for r in res[1:])
 
 
+def test_room115k_with_scrambled_numbering(ctx, oracle):
+    """The headline mesh with vertex ids and facet order permuted at random (the 256-bucket sorts with
+    no locality in their keys)."""
+    c = meshgen.config("room115k")
+    V, F, target = c["verts"], c["facets"], int(c["target"][0])
+    rng = np.random.default_rng(321)
+    perm = rng.permutation(V.shape[0])
+    V2 = np.empty_like(V)
+    V2[perm] = V
+    F2 = perm[F].astype(np.int32)[rng.permutation(F.shape[0])]
+    print(f"scrambled room115k: N={V2.shape[0]} F={F2.shape[0]} target={target}", flush=True)
+    st, vo, fo, cid = ctx.picasso_decimate(dev(V2), dev(F2), target)
+    assert_same_result(st, vo, fo, cid, oracle.decimate(V2, F2, target))
+
+
 def test_large_mesh_with_scrambled_numbering(ctx, oracle):
     """Vertex ids and facet order of a 400k-vertex scene are permuted at random, so neighbouring corners
     of the facet array share no leading index bits: the sorts lose the locality their fast paths use
