@@ -12,9 +12,10 @@
  *     On error no output buffer has been written.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  The
  *     decimate calls synchronise that stream before they return.
- *   - A context owns its scratch workspace (and one internal stream of default
- *     priority) and is bound to one device, which the calls make current; calls
- *     on one context must not overlap in time.  Inputs are never modified.
+ *   - A context owns its scratch workspace, a small pinned host buffer that its
+ *     kernels write counters into, and one internal stream of default priority;
+ *     it is bound to one device, which the calls make current; calls on one
+ *     context must not overlap in time.  Inputs are never modified.
  *   - Nothing is allocated inside the decimate calls.
  */
 #ifndef PICASSO_H
@@ -189,13 +190,15 @@ int picasso_unpool_backward(picasso_ctx* ctx, void* stream, const float* d_gx, i
 /* Vertex quadrics (supplementary, facet and vertex quadric equations):
  * d_quadrics_out [N,10] = a00 a01 a02 a11 a12 a22 b0 b1 b2 c, each the
  * left-to-right fp32 sum over adjacent facets in ascending facet order
- * (vertex->facet CSR by stable radix sort, ordered segmented reduction). */
+ * (vertex->facet lists by a sort of packed (vertex, facet) keys, then an
+ * ordered segmented reduction).  Synchronises the stream. */
 int picasso_vertex_quadrics(picasso_ctx* ctx, void* stream, const float* d_verts, int32_t N, const int32_t* d_facets,
                             int32_t F, float* d_quadrics_out);
 
 /* Distinct edges of the input mesh in ascending (lo,hi) order (Alg. 2 line 1)
  * and the cost of each (Alg. 2 line 2) from the vertex quadrics above.
- * d_edges_out (capacity 3F*2 ints), d_cost_out (capacity 3F floats). */
+ * d_edges_out (capacity 3F*2 ints), d_cost_out (capacity 3F floats); the number
+ * of edges goes to the host scalar h_ne_out.  Synchronises the stream. */
 int picasso_edge_costs(picasso_ctx* ctx, void* stream, const float* d_verts, int32_t N, const int32_t* d_facets,
                        int32_t F, int32_t* d_edges_out, float* d_cost_out, int32_t* h_ne_out);
 
@@ -211,10 +214,12 @@ int picasso_radix_sort(picasso_ctx* ctx, void* stream, int key_bytes, void* d_ke
                        int key_bits);
 
 /* Same contract as picasso_radix_sort, by the two-sweep method the path uses for
- * keys led by vertex ids: a stable partition on the top 8 of the key_bits, then
- * one workgroup per bucket sorts it in LDS (a bucket too large for LDS takes a
- * slow global-memory route).  2^20 < n <= 2^23 uses 4096 buckets on the top 12
- * bits (two 6-bit partition passes; needs key_bits > 12). */
+ * keys led by vertex ids: a partition on the top 8 of the key_bits, then one
+ * workgroup per bucket sorts it in LDS (a bucket too large for LDS takes a slow
+ * global-memory route).  2^20 < n <= 2^23 uses 4096 buckets on the top 12 bits
+ * (needs key_bits > 12).  With values the partition is ordered (stable: per-tile
+ * counts, row scans, ordered scatter; two 6-bit passes for 12 bits); without
+ * values it is a single unordered pass, equal keys being indistinguishable. */
 int picasso_bucket_sort(picasso_ctx* ctx, void* stream, int key_bytes, void* d_keys, uint32_t* d_vals, int64_t n,
                         int key_bits);
 
