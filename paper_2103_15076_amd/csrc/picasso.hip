@@ -119,10 +119,12 @@ __global__ __launch_bounds__(BLOCK) void init_kernel(const float* __restrict__ v
     for (int w = g; w < N; w += stride) {
         float x = verts[3 * (size_t)w], y = verts[3 * (size_t)w + 1], z = verts[3 * (size_t)w + 2];
         if (!(isfinite(x) && isfinite(y) && isfinite(z))) err |= 2;
-        VRec r;
-        r.x = x; r.y = y; r.z = z; r.w0 = 0.f;
-        r.a00 = r.a01 = r.a02 = r.a11 = r.a12 = r.a22 = r.b0 = r.b1 = r.b2 = r.c = r.w1 = r.w2 = 0.f;
-        vrec[w] = r;
+        if (!ikey) {  // (with incidence keys S0 follows, and quadric_reduce_kernel writes the whole record)
+            VRec r;
+            r.x = x; r.y = y; r.z = z; r.w0 = 0.f;
+            r.a00 = r.a01 = r.a02 = r.a11 = r.a12 = r.a22 = r.b0 = r.b1 = r.b2 = r.c = r.w1 = r.w2 = 0.f;
+            vrec[w] = r;
+        }
         cid[w] = w;
     }
     for (int f0 = blockIdx.x * BLOCK; f0 < F; f0 += stride) {  // (whole waves, for the ballots below)
@@ -240,6 +242,7 @@ __global__ __launch_bounds__(BLOCK) void quadric_reduce_kernel(VRec* __restrict_
         }
     }
     float4* r = reinterpret_cast<float4*>(&vrec[w]);
+    r[0] = make_float4(verts[3 * (size_t)w], verts[3 * (size_t)w + 1], verts[3 * (size_t)w + 2], 0.f);
     r[1] = make_float4(acc[0], acc[1], acc[2], acc[3]);
     r[2] = make_float4(acc[4], acc[5], acc[6], acc[7]);
     r[3] = make_float4(acc[8], acc[9], 0.f, 0.f);
