@@ -44,8 +44,10 @@ enum picasso_option {
     PICASSO_OPT_MAX_ROUNDS = 0,    /* stop after this many runs of the core algorithm; <0 = no cap  */
     PICASSO_OPT_STAGE_TIMING = 1,  /* 1: fill picasso_stats.ms_stage with hipEvent times (slower)    */
     PICASSO_OPT_SUBROUND_BATCH = 2,/* selection sub-rounds launched between two host checks         */
-    PICASSO_OPT_KERNEL_TIMING = 3, /* 1: bracket the launches of the edge-key sort's main kernel
-                                      with hipEvents (see picasso_kernel_timing)                   */
+    PICASSO_OPT_KERNEL_TIMING = 3, /* N > 0: in every N-th decimate call from now on, bracket the
+                                      launches of the edge-key sort's main kernel with hipEvents
+                                      (see picasso_kernel_timing); an event pair costs several
+                                      microseconds of queue time per launch; 0: off                */
     PICASSO_OPT_OVERLAP = 4,       /* 1 (default): for inputs of 2^18 facets or more, the first
                                       round's edge-key sort runs on a stream of the context's own
                                       beside the vertex quadrics and joins `stream` before costs

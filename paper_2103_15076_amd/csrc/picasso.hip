@@ -1349,7 +1349,9 @@ struct picasso_ctx {
     int n_ev = 0;
     hipEvent_t ev_total[2];
     // hipEvent brackets around the edge-key sort's main kernel (benchmark roofline)
-    int64_t opt_kernel_timing = 0;
+    int64_t opt_kernel_timing = 0;  // N > 0: events around the kernel in every N-th decimate call
+    int64_t kt_calls = 0;           // decimate calls since the option was set
+    bool kt_this_call = false;
     hipEvent_t kt_pool[512];
     prim::LaunchTimer::Rec kt_recs[256];
     prim::LaunchTimer kt;
@@ -1535,7 +1537,7 @@ int issue_edge_prefix(picasso_ctx* c, hipStream_t st_, int B, int round_, int cu
     if (H_ > 0) {
         int where = sort_by_vertex<u64, false>(st_, c->key64[0], c->key64[1], nullptr, nullptr, &c->st->nh, H_,
                                                2 * vbits_, c->sort_sc, c->hist12,
-                                               c->opt_kernel_timing ? &c->kt : nullptr, round_, counted);
+                                               c->kt_this_call ? &c->kt : nullptr, round_, counted);
         if (where < 0) return PICASSO_ERR_HIP;
         skeys = where ? c->key64[1] : c->key64[0];
     }
@@ -1661,9 +1663,10 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
     c->kt.recs = c->kt_recs;
     c->kt.used = 0;
     c->kt.nrec = 0;
+    c->kt_this_call = c->opt_kernel_timing > 0 && (c->kt_calls++ % c->opt_kernel_timing) == 0;
     std::vector<int> nf_round;
     StageTimer tm{c, s, c->opt_stage_timing != 0 && stats != nullptr, {}, -1};
-    HIP_TRY(c, hipEventRecord(c->ev_total[0], s));
+    if (stats) HIP_TRY(c, hipEventRecord(c->ev_total[0], s));  // (an event costs queue time: only when asked for)
 
     // host mirror of the per-mesh vertex counts
     std::vector<int> nvb(nv_in, nv_in + B), stuck(B, 0), act(B, 0), nrem(B, 0);
@@ -1894,7 +1897,7 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
     copy_out_kernel<<<grid_for(std::max(std::max(N, 3 * nf_bound), 1), 8192), BLOCK, 0, s>>>(
         c->vrec[cur], c->fbuf[cur], c->cid, c->st, cur, N, d_verts_out, d_facets_out, d_cluster_id, B, c->voff[cur],
         c->foff_out);
-    HIP_TRY(c, hipEventRecord(c->ev_total[1], s));
+    if (stats) HIP_TRY(c, hipEventRecord(c->ev_total[1], s));
     rc = read_header(c, s);
     if (rc != PICASSO_OK) return rc;
     HIP_TRY(c, hipGetLastError());
@@ -2010,7 +2013,11 @@ int picasso_set_option(picasso_ctx* c, int option, int64_t value) {
     switch (option) {
         case PICASSO_OPT_MAX_ROUNDS: c->opt_max_rounds = value; return PICASSO_OK;
         case PICASSO_OPT_STAGE_TIMING: c->opt_stage_timing = value; return PICASSO_OK;
-        case PICASSO_OPT_KERNEL_TIMING: c->opt_kernel_timing = value; return PICASSO_OK;
+        case PICASSO_OPT_KERNEL_TIMING:
+            if (value < 0) return PICASSO_ERR_INVALID_ARG;
+            c->opt_kernel_timing = value;
+            c->kt_calls = 0;
+            return PICASSO_OK;
         case PICASSO_OPT_OVERLAP: c->opt_overlap = value; return PICASSO_OK;
         case PICASSO_OPT_TRUNC_BLOCK_MAX:
             if (value < 0) return PICASSO_ERR_INVALID_ARG;
