@@ -1111,11 +1111,14 @@ __device__ __forceinline__ u32 hash3(int a, int b, int c) {
 // facet index; the slot's identity is that facet's triple, and among equal
 // triples the slot converges to the smallest facet index (atomicMin), so the
 // survivor does not depend on the order in which lanes arrive.
+constexpr int FSLOT_KEEP = -1, FSLOT_DROP = -2;
+
 __global__ __launch_bounds__(BLOCK) void facet_insert_kernel(const int* __restrict__ fcur, int* __restrict__ fmap,
                                                              const int* __restrict__ vmap, const State* st, int cur,
                                                              int* __restrict__ htab, u32 hmask, MeshTab mt,
                                                              const int* __restrict__ voff_cur,
-                                                             int* __restrict__ cid, int n_orig) {
+                                                             int* __restrict__ cid, int n_orig,
+                                                             int* __restrict__ fslot) {
     const int nf = st->nf[cur];
     const int stride = gridDim.x * BLOCK;
     const int g = blockIdx.x * BLOCK + threadIdx.x;
@@ -1125,8 +1128,16 @@ __global__ __launch_bounds__(BLOCK) void facet_insert_kernel(const int* __restri
         fmap[3 * (size_t)f] = a;
         fmap[3 * (size_t)f + 1] = b;
         fmap[3 * (size_t)f + 2] = c;
-        if (!mt.active[mesh_of(voff_cur, mt.B, a0)]) continue;  // mesh sits this round out: facets kept as they are
-        if (a == b || b == c || a == c) continue;
+        // fslot[f]: the table slot that decides about the facet (it survives iff the slot ends up
+        // holding f), or FSLOT_KEEP / FSLOT_DROP where no slot is involved
+        if (!mt.active[mesh_of(voff_cur, mt.B, a0)]) {  // mesh sits this round out: facets kept as they are
+            fslot[f] = FSLOT_KEEP;
+            continue;
+        }
+        if (a == b || b == c || a == c) {
+            fslot[f] = FSLOT_DROP;
+            continue;
+        }
         int x = a, y = b, z = c;
         sort3(x, y, z);
         u32 h = hash3(x, y, z) & hmask;
@@ -1142,41 +1153,20 @@ __global__ __launch_bounds__(BLOCK) void facet_insert_kernel(const int* __restri
             }
             h = (h + 1) & hmask;
         }
+        fslot[f] = (int)h;
     }
     for (int o = g; o < n_orig; o += stride) cid[o] = vmap[cid[o]];
 }
 
-// keep[f] = 1 iff the facet survives: not collapsed and the first of its triple.
+// keep[f] = 1 iff the facet survives: not collapsed and the first of its triple (the slot that
+// facet_insert_kernel left for it holds the smallest facet index of the triple).
 struct FacetKeepPred {
-    const int* fmap;
-    const int* fcur;
+    const int* fslot;
     const int* htab;
-    u32 hmask;
     unsigned char* keep;
-    MeshTab mt;
-    const int* voff_cur;
     __device__ bool operator()(int f) const {
-        const int a = fmap[3 * (size_t)f], b = fmap[3 * (size_t)f + 1], c = fmap[3 * (size_t)f + 2];
-        bool k;
-        if (!mt.active[mesh_of(voff_cur, mt.B, fcur[3 * (size_t)f])]) {
-            k = true;
-        } else if (a == b || b == c || a == c) {
-            k = false;
-        } else {
-            int x = a, y = b, z = c;
-            sort3(x, y, z);
-            u32 h = hash3(x, y, z) & hmask;
-            k = false;
-            for (;;) {
-                const int r = htab[h];
-                if (r == f) { k = true; break; }
-                if (r < 0) break;  // cannot happen: f was inserted
-                int p = fmap[3 * (size_t)r], q = fmap[3 * (size_t)r + 1], s = fmap[3 * (size_t)r + 2];
-                sort3(p, q, s);
-                if (p == x && q == y && s == z) break;  // an earlier copy holds the slot
-                h = (h + 1) & hmask;
-            }
-        }
+        const int h = fslot[f];
+        const bool k = h >= 0 ? htab[h] == f : h == FSLOT_KEEP;
         keep[f] = k ? 1 : 0;
         return k;
     }
@@ -1316,6 +1306,7 @@ struct picasso_ctx {
     int* htab = nullptr;
     size_t hcap = 0;
     unsigned char* keep = nullptr;
+    int* fslot = nullptr;  // per facet: the hash-table slot that decides about it
     int* tilesum = nullptr;
     prim::SortScratch sort_sc{};
     u32* hist12 = nullptr;  // the bucket sorts' top-digit counts, cursors and first positions (3 x prim::MSD_HIST_WORDS)
@@ -1426,6 +1417,7 @@ size_t carve(picasso_ctx* c, char* base, int64_t N, int64_t F, int32_t B) {
     x->hcap = next_pow2(2 * f);
     x->htab = cv.take<int>(x->hcap);
     x->keep = cv.take<unsigned char>(f);
+    x->fslot = cv.take<int>(f);
     x->tilesum = cv.take<int>((size_t)prim::compact_tilesum_capacity((long long)std::max(h, n)));
     x->sort_sc.T = prim::sort_table_stride((long long)h);
     x->sort_sc.table = cv.take<u32>((size_t)256 * x->sort_sc.T);
@@ -1874,8 +1866,9 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         // ---- S5: facets
         tm.begin(round, PICASSO_ST_FACETS);
         facet_insert_kernel<<<grid_for(std::max(nf_bound, N), 8192), BLOCK, 0, s>>>(
-            c->fbuf[cur], c->fmap, c->vmap, c->st, cur, c->htab, (u32)(hsize - 1), mt, c->voff[cur], c->cid, N);
-        FacetKeepPred kp{c->fmap, c->fbuf[cur], c->htab, (u32)(hsize - 1), c->keep, mt, c->voff[cur]};
+            c->fbuf[cur], c->fmap, c->vmap, c->st, cur, c->htab, (u32)(hsize - 1), mt, c->voff[cur], c->cid, N,
+            c->fslot);
+        FacetKeepPred kp{c->fslot, c->htab, c->keep};
         FlagPred fp{c->keep};
         FacetOut fo{c->fmap, c->fbuf[nxt]};
         prim::compact(s, kp, fp, fo, &c->st->nf[cur], nf_bound, c->tilesum, &c->st->nf[nxt]);
