@@ -93,10 +93,36 @@ __device__ __forceinline__ u32 cost_key(float c) {
 // incidence) pairs whose stable sort is the vertex->facet CSR.
 enum { COUNT_NONE = 0, COUNT_SMALL = 1, COUNT_LARGE = 2 };
 
+// Incidence key of corner i of the facet array: (vertex << fbits) | facet.
+struct IncidenceKeys {
+    const int* fcur;
+    int fbits;
+    __device__ __forceinline__ u64 operator()(long long i) const {
+        return ((u64)(u32)fcur[i] << fbits) | (u64)(u32)(i / 3);
+    }
+};
+
+// Edge key of corner i of the facet array: the side from corner i to the facet's next corner as
+// (lower vertex << vbits) | higher vertex; a side with equal ends gets the all-ones key.
+struct EdgeKeys {
+    const int* fcur;
+    int vbits;
+    u64 sentinel;
+    __device__ __forceinline__ u64 operator()(long long i) const {
+        const long long f = i / 3;
+        const int sl = (int)(i - 3 * f);
+        const int a = fcur[i], b = fcur[3 * f + (sl == 2 ? 0 : sl + 1)];
+        const int lo = min(a, b), hi = max(a, b);
+        return (lo == hi) ? sentinel : (((u64)(u32)lo << vbits) | (u64)(u32)hi);
+    }
+};
+
 // Incidence keys for S0: (vertex << fbits) | facet, one per facet corner, so that sorting the keys
 // alone lists every vertex's facets in ascending facet order.  With COUNT_SMALL / COUNT_LARGE the
 // kernel also adds the keys' top 8- / 12-bit digits (bits [ishift, ...)) to ihist, the histogram
-// that the sort of the keys starts from (zero on entry; see quadric_reduce_kernel).
+// that the sort of the keys starts from (zero on entry; see quadric_reduce_kernel); that sort makes
+// the keys again from the validated facet array (IncidenceKeys), so they are written out (ikey)
+// only for a sort that needs them in memory.
 template <int COUNT>
 __global__ __launch_bounds__(BLOCK) void init_kernel(const float* __restrict__ verts, int N,
                                                      const int* __restrict__ facets, int F, int B,
@@ -104,7 +130,7 @@ __global__ __launch_bounds__(BLOCK) void init_kernel(const float* __restrict__ v
                                                      VRec* __restrict__ vrec, int* __restrict__ cid,
                                                      int* __restrict__ fcur, u64* __restrict__ ikey, int fbits,
                                                      int ishift, u32* __restrict__ ihist, State* st,
-                                                     u32* __restrict__ msd_hist) {
+                                                     u32* __restrict__ msd_hist, int s0_follows) {
     constexpr int RADIX = COUNT == COUNT_LARGE ? (1 << prim::BUCKET_LARGE_MSD_BITS) : (1 << prim::BUCKET_MSD_BITS);
     __shared__ u32 hist[COUNT != COUNT_NONE ? RADIX : 1];
     const int stride = gridDim.x * BLOCK;
@@ -119,7 +145,7 @@ __global__ __launch_bounds__(BLOCK) void init_kernel(const float* __restrict__ v
     for (int w = g; w < N; w += stride) {
         float x = verts[3 * (size_t)w], y = verts[3 * (size_t)w + 1], z = verts[3 * (size_t)w + 2];
         if (!(isfinite(x) && isfinite(y) && isfinite(z))) err |= 2;
-        if (!ikey) {  // (with incidence keys S0 follows, and quadric_reduce_kernel writes the whole record)
+        if (!s0_follows) {  // (else quadric_reduce_kernel writes the whole record)
             VRec r;
             r.x = x; r.y = y; r.z = z; r.w0 = 0.f;
             r.a00 = r.a01 = r.a02 = r.a11 = r.a12 = r.a22 = r.b0 = r.b1 = r.b2 = r.c = r.w1 = r.w2 = 0.f;
@@ -325,11 +351,8 @@ __global__ __launch_bounds__(BLOCK) void edge_keys_kernel(const int* __restrict_
             const bool ok = idx < n;
             u64 k = 0;
             if (ok) {
-                const int f = (int)(idx / 3), sl = (int)(idx - 3ll * f);
-                const int a = fcur[idx], b = fcur[3 * (size_t)f + (sl == 2 ? 0 : sl + 1)];
-                const int lo = min(a, b), hi = max(a, b);
-                k = (lo == hi) ? sentinel : (((u64)(u32)lo << vbits) | (u64)(u32)hi);
-                keys[idx] = k;
+                k = EdgeKeys{fcur, vbits, sentinel}(idx);
+                if (keys) keys[idx] = k;  // (the counted sorts make the keys again from fcur)
             }
             if constexpr (COUNT != COUNT_NONE) {
                 // the lower vertices of neighbouring corners mostly share their leading bits: a wave
@@ -1487,16 +1510,17 @@ inline int sort_by_vertex_path(long long n_max, int key_bits) {
     return COUNT_NONE;
 }
 
-template <typename K, bool HAS_VAL, int LARGE_KEYS_ONLY_ITEMS = 8>
+template <typename K, bool HAS_VAL, int LARGE_KEYS_ONLY_ITEMS = 8, class Src = prim::ArrayKeys<K>>
 int sort_by_vertex(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_ptr, int n_max, int key_bits,
                    const prim::SortScratch& sc, u32* hist12, prim::LaunchTimer* lt = nullptr, int tag = 0,
-                   bool counted = false) {
+                   bool counted = false, const Src* src = nullptr) {
     const int how = sort_by_vertex_path(n_max, key_bits);
     if (how == COUNT_SMALL)
-        return prim::bucket_sort<K, HAS_VAL>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc, lt, tag, counted, hist12);
+        return prim::bucket_sort<K, HAS_VAL, Src>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc, lt, tag, counted,
+                                                  hist12, src);
     if (how == COUNT_LARGE)
-        return prim::bucket_sort_large<K, HAS_VAL, LARGE_KEYS_ONLY_ITEMS>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc,
-                                                                          hist12, lt, tag, counted);
+        return prim::bucket_sort_large<K, HAS_VAL, LARGE_KEYS_ONLY_ITEMS, Src>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits,
+                                                                               sc, hist12, lt, tag, counted, src);
     return prim::radix_sort<K, HAS_VAL>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc, lt, tag);
 }
 
@@ -1516,24 +1540,25 @@ int issue_edge_prefix(picasso_ctx* c, hipStream_t st_, int B, int round_, int cu
     const bool counted = how != COUNT_NONE;
     if (how == COUNT_SMALL)
         edge_keys_kernel<COUNT_SMALL><<<prim::sort_tiles(H_, prim::SORT_ITEMS_SMALL), BLOCK, 0, st_>>>(
-            c->fbuf[cur_], c->st, cur_, vbits_, c->key64[0], c->vmin[0], c->vmin[1], c->mate, rt,
+            c->fbuf[cur_], c->st, cur_, vbits_, nullptr, c->vmin[0], c->vmin[1], c->mate, rt,
             prim::bucket_sort_low_bits(kb), c->hist12);
     else if (how == COUNT_LARGE)
         edge_keys_kernel<COUNT_LARGE><<<prim::sort_tiles(H_, prim::SORT_ITEMS_BIG), BLOCK, 0, st_>>>(
-            c->fbuf[cur_], c->st, cur_, vbits_, c->key64[0], c->vmin[0], c->vmin[1], c->mate, rt,
+            c->fbuf[cur_], c->st, cur_, vbits_, nullptr, c->vmin[0], c->vmin[1], c->mate, rt,
             kb - prim::BUCKET_LARGE_MSD_BITS, c->hist12);
     else
         edge_keys_kernel<COUNT_NONE><<<grid_for(std::max(3 * nfb, nvt), 8192), BLOCK, 0, st_>>>(
             c->fbuf[cur_], c->st, cur_, vbits_, c->key64[0], c->vmin[0], c->vmin[1], c->mate, rt, 0, nullptr);
     skeys = c->key64[0];
+    const u64 sentinel_ = (vbits_ >= 32) ? ~0ull : ((1ull << (2 * vbits_)) - 1ull);
     if (H_ > 0) {
-        int where = sort_by_vertex<u64, false>(st_, c->key64[0], c->key64[1], nullptr, nullptr, &c->st->nh, H_,
-                                               2 * vbits_, c->sort_sc, c->hist12,
-                                               c->kt_this_call ? &c->kt : nullptr, round_, counted);
+        const EdgeKeys src{c->fbuf[cur_], vbits_, sentinel_};  // (the counted sorts read the keys from here)
+        int where = sort_by_vertex<u64, false, 8, EdgeKeys>(st_, c->key64[0], c->key64[1], nullptr, nullptr, &c->st->nh,
+                                                            H_, 2 * vbits_, c->sort_sc, c->hist12,
+                                                            c->kt_this_call ? &c->kt : nullptr, round_, counted, &src);
         if (where < 0) return PICASSO_ERR_HIP;
         skeys = where ? c->key64[1] : c->key64[0];
     }
-    const u64 sentinel_ = (vbits_ >= 32) ? ~0ull : ((1ull << (2 * vbits_)) - 1ull);
     UniquePred up_{skeys, sentinel_};
     prim::compact_count(st_, up_, &c->st->nh, H_, c->tilesum);
     *skeys_out = skeys;
@@ -1551,19 +1576,23 @@ int launch_init(picasso_ctx* c, hipStream_t s, const float* d_verts, int N, cons
                 bool with_keys) {
     const int fbits = incidence_fbits(F), kb = incidence_key_bits(N, F);
     const int how = with_keys ? sort_by_vertex_path(3ll * F, kb) : COUNT_NONE;
-    u64* ikey = with_keys ? c->s0_key[0] : nullptr;
+    // only a sort that cannot make the keys itself (the plain LSD fallback) needs them written out
+    u64* ikey = (with_keys && how == COUNT_NONE) ? c->s0_key[0] : nullptr;
+    const int s0 = with_keys ? 1 : 0;
     const int grid = grid_for(std::max(N, F), 4096);
     if (how == COUNT_SMALL)
         init_kernel<COUNT_SMALL><<<grid, BLOCK, 0, s>>>(d_verts, N, d_facets, F, B, c->voff[0], c->foff, c->vrec[0],
                                                         c->cid, c->fbuf[0], ikey, fbits, prim::bucket_sort_low_bits(kb),
-                                                        c->hist12_s0, c->st, c->hist12);
+                                                        c->hist12_s0, c->st, c->hist12, s0);
     else if (how == COUNT_LARGE)
         init_kernel<COUNT_LARGE><<<grid, BLOCK, 0, s>>>(d_verts, N, d_facets, F, B, c->voff[0], c->foff, c->vrec[0],
                                                         c->cid, c->fbuf[0], ikey, fbits,
-                                                        kb - prim::BUCKET_LARGE_MSD_BITS, c->hist12_s0, c->st, c->hist12);
+                                                        kb - prim::BUCKET_LARGE_MSD_BITS, c->hist12_s0, c->st, c->hist12,
+                                                        s0);
     else
         init_kernel<COUNT_NONE><<<grid, BLOCK, 0, s>>>(d_verts, N, d_facets, F, B, c->voff[0], c->foff, c->vrec[0],
-                                                       c->cid, c->fbuf[0], ikey, fbits, 0, nullptr, c->st, c->hist12);
+                                                       c->cid, c->fbuf[0], ikey, fbits, 0, nullptr, c->st, c->hist12,
+                                                       s0);
     return hipGetLastError() == hipSuccess ? PICASSO_OK : PICASSO_ERR_HIP;
 }
 
@@ -1573,8 +1602,10 @@ int run_vertex_quadrics(picasso_ctx* c, hipStream_t s, const float* d_verts, int
     const int fbits = incidence_fbits(F), kb = incidence_key_bits(N, F);
     if (F > 0) {
         const bool counted = sort_by_vertex_path(H, kb) != COUNT_NONE;
-        int where = sort_by_vertex<u64, false, 16>(s, c->s0_key[0], c->s0_key[1], nullptr, nullptr, nullptr, H, kb,
-                                                   c->sort_sc_s0, c->hist12_s0, nullptr, 0, counted);
+        const IncidenceKeys src{c->fbuf[0], fbits};  // (the counted sorts read the keys from here)
+        int where = sort_by_vertex<u64, false, 16, IncidenceKeys>(s, c->s0_key[0], c->s0_key[1], nullptr, nullptr,
+                                                                  nullptr, H, kb, c->sort_sc_s0, c->hist12_s0, nullptr,
+                                                                  0, counted, &src);
         if (where < 0) return PICASSO_ERR_HIP;
         const u64* skey = where ? c->s0_key[1] : c->s0_key[0];
         csr_offsets_kernel<u64><<<grid_for(H), BLOCK, 0, s>>>(skey, fbits, H, N, c->csr_off);

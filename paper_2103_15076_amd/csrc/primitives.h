@@ -756,8 +756,16 @@ __global__ __launch_bounds__(BLOCK) void msd_histogram_kernel(const K* __restric
 // for sorts that then order each range on the whole key; with equal keys indistinguishable the
 // final result does not depend on it.  A wave whose keys share one digit (the common case for
 // keys led by mesh indices) ranks itself with one LDS atomic and writes one contiguous run.
-template <typename K, int RBITS, int ITEMS>
-__global__ __launch_bounds__(BLOCK) void msd_scatter_kernel(const K* __restrict__ kin, K* __restrict__ kout,
+// A key source gives key i of the input: an array, or a functor that makes the key on the fly (so
+// that keys which are a cheap function of other data need not be written out and read back).
+template <typename K>
+struct ArrayKeys {
+    const K* p;
+    __device__ __forceinline__ K operator()(long long i) const { return p[i]; }
+};
+
+template <typename K, int RBITS, int ITEMS, class Src>
+__global__ __launch_bounds__(BLOCK) void msd_scatter_kernel(Src kin, K* __restrict__ kout,
                                                             const int* n_ptr, int n_host, int shift,
                                                             const u32* __restrict__ hist, u32* __restrict__ cursor,
                                                             u32* __restrict__ starts) {
@@ -779,7 +787,7 @@ __global__ __launch_bounds__(BLOCK) void msd_scatter_kernel(const K* __restrict_
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) {
         const long long idx = base + (long long)w * (64 * ITEMS) + i * 64 + lane;
-        key[i] = idx < n ? kin[idx] : (K)0;
+        key[i] = idx < n ? kin(idx) : (K)0;
     }
     {   // first position of every digit's range
         u32 c[PER], sum = 0, tot;
@@ -846,10 +854,12 @@ __global__ __launch_bounds__(BLOCK) void fill_u32_kernel(u32* __restrict__ p, in
     if (i < n) p[i] = v;
 }
 
-template <typename K, bool HAS_VAL>
+// `src`: where the keys come from when not from k0 (keys without values, `counted`); k0 then only
+// receives the result.
+template <typename K, bool HAS_VAL, class Src = ArrayKeys<K>>
 inline int bucket_sort(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_ptr, int n_max, int key_bits,
                        const SortScratch& sc, LaunchTimer* lt = nullptr, int tag = 0, bool counted = false,
-                       u32* msd_hist = nullptr) {
+                       u32* msd_hist = nullptr, const Src* src = nullptr) {
     if (n_max <= 0 || key_bits <= 0) return 0;
     const int msd = bucket_sort_msd_bits(key_bits);
     const int low = key_bits - msd;
@@ -863,7 +873,10 @@ inline int bucket_sort(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int*
                 msd_histogram_kernel<K, BUCKET_MSD_BITS, SORT_ITEMS_SMALL><<<tiles, BLOCK, 0, s>>>(k0, n_ptr, n_max, msd_hist, low);
             }
             u32* starts = msd_hist + 2 * MSD_HIST_WORDS;
-            msd_scatter_kernel<K, BUCKET_MSD_BITS, SORT_ITEMS_SMALL><<<tiles, BLOCK, 0, s>>>(k0, k1, n_ptr, n_max, low, msd_hist, cursor, starts);
+            if (src && counted)
+                msd_scatter_kernel<K, BUCKET_MSD_BITS, SORT_ITEMS_SMALL, Src><<<tiles, BLOCK, 0, s>>>(*src, k1, n_ptr, n_max, low, msd_hist, cursor, starts);
+            else
+                msd_scatter_kernel<K, BUCKET_MSD_BITS, SORT_ITEMS_SMALL, ArrayKeys<K>><<<tiles, BLOCK, 0, s>>>(ArrayKeys<K>{k0}, k1, n_ptr, n_max, low, msd_hist, cursor, starts);
             const bool timed = lt && lt->begin(s, tag);
             launch_bucket_keys<K, BUCKET_THREADS_256, 8, false>(1 << msd, s, k1, k0, msd_hist, 1 << msd, low, starts);
             if (timed) lt->end(s);
@@ -937,10 +950,11 @@ __global__ __launch_bounds__(BLOCK) void top_digit_histogram_kernel(const K* __r
 
 // Result is in (k1, v1): returns 1 (keys with values), or in k0: returns 0 (keys only); <0 on a
 // launch error.  hist12 holds 3 * MSD_HIST_WORDS words (counts, cursors, first positions).
-template <typename K, bool HAS_VAL, int KEYS_ONLY_ITEMS = 8>  // keys per lane of the bucket kernel without values
+template <typename K, bool HAS_VAL, int KEYS_ONLY_ITEMS = 8,  // keys per lane of the bucket kernel without values
+          class Src = ArrayKeys<K>>
 inline int bucket_sort_large(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_ptr, int n_max, int key_bits,
                              const SortScratch& sc, u32* hist12, LaunchTimer* lt = nullptr, int tag = 0,
-                             bool counted = false) {
+                             bool counted = false, const Src* src = nullptr) {
     constexpr int R = 1 << BUCKET_LARGE_MSD_BITS;
     const int low = key_bits - BUCKET_LARGE_MSD_BITS;
     const int tiles = sort_tiles(n_max, SORT_ITEMS_BIG);
@@ -952,7 +966,10 @@ inline int bucket_sort_large(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, cons
             msd_histogram_kernel<K, BUCKET_LARGE_MSD_BITS, SORT_ITEMS_BIG><<<tiles, BLOCK, 0, s>>>(k0, n_ptr, n_max, hist12, low);
         }
         u32* starts = hist12 + 2 * MSD_HIST_WORDS;
-        msd_scatter_kernel<K, BUCKET_LARGE_MSD_BITS, SORT_ITEMS_BIG><<<tiles, BLOCK, 0, s>>>(k0, k1, n_ptr, n_max, low, hist12, cursor, starts);
+        if (src && counted)
+            msd_scatter_kernel<K, BUCKET_LARGE_MSD_BITS, SORT_ITEMS_BIG, Src><<<tiles, BLOCK, 0, s>>>(*src, k1, n_ptr, n_max, low, hist12, cursor, starts);
+        else
+            msd_scatter_kernel<K, BUCKET_LARGE_MSD_BITS, SORT_ITEMS_BIG, ArrayKeys<K>><<<tiles, BLOCK, 0, s>>>(ArrayKeys<K>{k0}, k1, n_ptr, n_max, low, hist12, cursor, starts);
         const bool timed = lt && lt->begin(s, tag);
         if constexpr (KEYS_ONLY_ITEMS > 8) {
             // buckets of up to 4096 keys at three workgroups per compute unit, longer ones separately
