@@ -437,6 +437,23 @@ def test_large_mesh_with_scrambled_numbering(ctx, oracle):
     assert_same_result(st, vo, fo, cid, oracle.decimate(V2, F2, target))
 
 
+def test_beyond_the_bucket_sorts(pk, oracle):
+    """2.85 M facets = 8.5 M half-edges, more than the bucket sorts take (2^23 keys): the first round's
+    incidence and edge keys are written out and sorted by plain LSD passes, the later rounds drop
+    back into the bucket sorts.  Own context (the shared one is smaller)."""
+    V, F, _ = meshgen.room_scene_sized(31, 1_500_000, room=(30.0, 20.0, 3.0), n_boxes=300)
+    assert 3 * F.shape[0] > (1 << 23)
+    target = V.shape[0] // 2
+    c = pk.Context(V.shape[0], F.shape[0], 1, device=0)
+    try:
+        print(f"huge: N={V.shape[0]} F={F.shape[0]} target={target}", flush=True)
+        st, vo, fo, cid = c.picasso_decimate(dev(V), dev(F), target)
+        print("  gpu done; oracle...", flush=True)
+        assert_same_result(st, vo, fo, cid, oracle.decimate(V, F, target))
+    finally:
+        c.close()
+
+
 def test_config_batch_hierarchy(ctx, oracle):
     """16 room meshes through 4 successive levels, each to 40 % of the vertices;
     the cluster maps of all levels are kept and compared."""
