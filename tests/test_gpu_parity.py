@@ -437,6 +437,34 @@ def test_large_mesh_with_scrambled_numbering(ctx, oracle):
     assert_same_result(st, vo, fo, cid, oracle.decimate(V2, F2, target))
 
 
+def test_batch_of_more_meshes_than_the_tail_tallies_in_lds(pk, oracle):
+    """1,100 tiny meshes in one call: above 1,024 meshes the selection tail counts pairs through
+    memory instead of LDS; budgets bind in many meshes at once (one budget workgroup per mesh)."""
+    rng = np.random.default_rng(9)
+    parts = []
+    for k in range(1100):
+        nx, ny = int(rng.integers(3, 7)), int(rng.integers(3, 7))
+        parts.append(meshgen.noisy_grid(nx, ny, seed=1000 + k))
+    nv = [p[0].shape[0] for p in parts]
+    nf = [p[1].shape[0] for p in parts]
+    off = np.cumsum([0] + nv)
+    V = np.concatenate([p[0] for p in parts])
+    F = np.concatenate([p[1] + off[i] for i, p in enumerate(parts)]).astype(np.int32)
+    tg = [max(2, int(n * f)) for n, f in zip(nv, rng.uniform(0.3, 1.0, size=len(nv)))]
+    c = pk.Context(V.shape[0], F.shape[0], len(parts), device=0)
+    try:
+        print(f"batch of {len(parts)}: N={V.shape[0]} F={F.shape[0]}", flush=True)
+        st, vo, fo, cid, nvo, nfo = c.picasso_decimate_batch(dev(V), dev(F), nv, nf, tg)
+        ref = oracle.decimate_batch(V, F, nv, nf, tg)
+        assert st == ref["status"]
+        assert nvo.tolist() == ref["nv"].tolist() and nfo.tolist() == ref["nf"].tolist()
+        assert np.array_equal(cid.cpu().numpy(), ref["cluster_id"])
+        assert np.array_equal(fo.cpu().numpy(), ref["facets"])
+        assert np.array_equal(vo.cpu().numpy().view(np.uint32), ref["verts"].view(np.uint32))
+    finally:
+        c.close()
+
+
 def test_beyond_the_bucket_sorts(pk, oracle):
     """2.85 M facets = 8.5 M half-edges, more than the bucket sorts take (2^23 keys): the first round's
     incidence and edge keys are written out and sorted by plain LSD passes, the later rounds drop
