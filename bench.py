@@ -22,7 +22,7 @@ HBM_PEAK_GBS = 8000.0
 # Bytes per launch of the edge-key sort's main kernel (bucket_sort_kernel<u64>) that crossed the L2-fabric boundary, from two
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by the copy-kernel calibration; see
 # profiles/hbm_counters_edge_sort.md.  Offline measurements: null for workloads that were not profiled.
-MEASURED_TRAFFIC_BYTES = {"room115k": 8.05e6, "scene1p2m": 66.3e6}
+MEASURED_TRAFFIC_BYTES = {"room115k": 8.07e6, "scene1p2m": 66.3e6}
 
 
 def main():
