@@ -23,6 +23,8 @@ ERR_INVALID_ARG = -1
 ERR_BAD_INDEX = -2
 ERR_NONFINITE = -3
 
+PLACE_MEAN, PLACE_INVERSE = 0, 1
+
 
 def build(force: bool = False) -> str:
     """Compile the oracle with strict IEEE fp32 semantics (no contraction)."""
@@ -77,13 +79,28 @@ def edges(facets):
     return out[: n.value].copy()
 
 
-def edge_costs(pos, Q, edge_list):
+def edge_costs(pos, Q, edge_list, placement=PLACE_MEAN, rcond_min=0.0):
     pos, Q, edge_list = _f32(pos), _f32(Q), _i32(edge_list)
     E = edge_list.shape[0]
     cost = np.empty(E, np.float32)
     key = np.empty(E, np.uint32)
-    lib().picasso_oracle_edge_costs(_p(pos), _p(Q), _p(edge_list), E, _p(cost), _p(key))
+    if placement == PLACE_MEAN:
+        lib().picasso_oracle_edge_costs(_p(pos), _p(Q), _p(edge_list), E, _p(cost), _p(key))
+    else:
+        lib().picasso_oracle_edge_costs_opts(_p(pos), _p(Q), _p(edge_list), E, int(placement),
+                                             ctypes.c_float(rcond_min), _p(cost), _p(key))
     return cost, key
+
+
+def pair_target(quadric_sum, pu, pv, placement, rcond_min):
+    """Contraction target of one pair: returns (target[3], rcond, used_inverse)."""
+    q, pu, pv = _f32(quadric_sum), _f32(pu), _f32(pv)
+    t = np.zeros(3, np.float32)
+    rc = ctypes.c_float(0.0)
+    used = ctypes.c_int32(0)
+    lib().picasso_oracle_pair_target(_p(q), _p(pu), _p(pv), int(placement), ctypes.c_float(rcond_min), _p(t),
+                                     ctypes.byref(rc), ctypes.byref(used))
+    return t, float(rc.value), bool(used.value)
 
 
 def cost_key(c: float) -> int:
@@ -98,7 +115,7 @@ def select(edge_list, key, n_verts, n_remove):
     return sel.astype(bool), n
 
 
-def decimate(verts, facets, target_nv, max_rounds=-1, return_quadrics=False):
+def decimate(verts, facets, target_nv, max_rounds=-1, return_quadrics=False, placement=PLACE_MEAN, rcond_min=0.0):
     """Returns dict(status, verts, facets, cluster_id, rounds[, quadrics])."""
     verts, facets = _f32(verts), _i32(facets).reshape(-1, 3)
     N, F = verts.shape[0], facets.shape[0]
@@ -107,9 +124,15 @@ def decimate(verts, facets, target_nv, max_rounds=-1, return_quadrics=False):
     cid = np.zeros(max(N, 1), np.int32)
     qo = np.zeros((max(N, 1), 10), np.float32)
     nv, nf, rounds = ctypes.c_int32(0), ctypes.c_int32(0), ctypes.c_int32(0)
-    st = lib().picasso_oracle_decimate_rounds(
-        _p(verts), N, _p(facets), F, int(target_nv), int(max_rounds), _p(vo), _p(fo), _p(cid),
-        ctypes.byref(nv), ctypes.byref(nf), ctypes.byref(rounds), _p(qo))
+    if placement != PLACE_MEAN:
+        assert not return_quadrics
+        st = lib().picasso_oracle_decimate_opts(
+            _p(verts), N, _p(facets), F, int(target_nv), int(max_rounds), int(placement), ctypes.c_float(rcond_min),
+            _p(vo), _p(fo), _p(cid), ctypes.byref(nv), ctypes.byref(nf), ctypes.byref(rounds))
+    else:
+        st = lib().picasso_oracle_decimate_rounds(
+            _p(verts), N, _p(facets), F, int(target_nv), int(max_rounds), _p(vo), _p(fo), _p(cid),
+            ctypes.byref(nv), ctypes.byref(nf), ctypes.byref(rounds), _p(qo))
     if st < 0:
         return dict(status=st)
     res = dict(status=st, verts=vo[: nv.value].copy(), facets=fo[: nf.value].copy(), cluster_id=cid[:N].copy(),

@@ -34,6 +34,19 @@
 //  * The representative of a contracted pair is the smaller index; survivors
 //    are renumbered in ascending order; every cluster stays an output vertex.
 //
+// Variant (off by default), entry points with the suffix _opts:
+//  * placement = 1: the contraction target of a pair is the minimiser of its
+//    summed quadric, -A^-1 b (supplementary, Eq. "inverse_optimal"), when A is
+//    judged to have full rank by the reciprocal of its condition number, else the
+//    mean as above.  The paper gives neither the way that number is computed
+//    nor the threshold: taken here as the ratio of the smallest to the largest
+//    pivot of A's L D L^T factorisation with diagonal pivoting (A is positive
+//    semi-definite; a determinant-and-cofactor formula loses all accuracy on
+//    the rank-1 matrices of flat regions), and a threshold the caller passes
+//    (full rank iff ratio > threshold).  The system is solved with the same
+//    factors.  The pair's cost (Alg. 2 line 2) is the quadric error at that
+//    same target.
+//
 // Pins: see tests/test_oracle_*.py (closed forms, brute force, invariants,
 // hand-worked fixtures under tests/golden/).  The whole multi-round pipeline has
 // no printed worked example in the paper (its Fig. 2 carries no numbers):
@@ -126,20 +139,95 @@ void unique_edges(const int32_t* F, int nF, std::vector<std::pair<int32_t, int32
     E.erase(std::unique(E.begin(), E.end()), E.end());
 }
 
-// Quadric error of the pair's summed quadric at the pair's mean position
-// (Alg. 2 line 2; supplementary Q(x) = x^T A x + 2 b^T x + c).
-float pair_cost(const Quadric& Qu, const Quadric& Qv, const float* pu, const float* pv) {
-    float s[10];
-    for (int k = 0; k < 10; ++k) s[k] = Qu.q[k] + Qv.q[k];
-    float mx = (pu[0] + pv[0]) * 0.5f;
-    float my = (pu[1] + pv[1]) * 0.5f;
-    float mz = (pu[2] + pv[2]) * 0.5f;
+// Choices among the variants; the defaults are the path described at the top.
+struct Opts {
+    int placement = 0;        // 0: mean of the pair; 1: -A^-1 b where A has full rank, else the mean
+    float rcond_min = 0.0f;   // full rank iff rcond > rcond_min
+};
+
+// Minimiser of the quadric s = (A, b, c): the solution of A x = -b
+// (supplementary, Eq. "inverse_optimal").  A is a sum of plane quadrics n n^T,
+// symmetric positive semi-definite, and is factored as P A P^T = L D L^T with
+// diagonal pivoting (the largest remaining diagonal entry is eliminated
+// next), so the pivots come out as d1 >= d2 >= d3 up to rounding.  The
+// reciprocal condition number is estimated by d3 / d1 (for such a 3x3 matrix
+// between 1 and 27 times lambda_min / lambda_max); A is taken to have full
+// rank iff all pivots are positive and d3 > rcond_min * d1.  Returns false (x
+// untouched) otherwise, or when a coordinate of x is not finite.
+bool inverse_placement(const float* s, float rcond_min, float* x, float* rcond_out) {
+    float a00 = s[0], a01 = s[1], a02 = s[2], a11 = s[3], a12 = s[4], a22 = s[5];
+    float r0 = -s[6], r1 = -s[7], r2 = -s[8];
+    if (rcond_out) *rcond_out = 0.0f;
+    // first pivot: largest diagonal entry (the first of equal ones), moved to position 0
+    int p = 0;
+    float m = a00;
+    if (a11 > m) { p = 1; m = a11; }
+    if (a22 > m) { p = 2; m = a22; }
+    if (p == 1) { std::swap(a00, a11); std::swap(a02, a12); std::swap(r0, r1); }
+    if (p == 2) { std::swap(a00, a22); std::swap(a01, a12); std::swap(r0, r2); }
+    const float d1 = a00;
+    if (!(d1 > 0.0f)) return false;
+    float l1 = a01 / d1, l2 = a02 / d1;
+    // remaining 2x2 block, written so that it does not depend on which of the two axes comes first
+    float s11 = a11 - (a01 * a01) / d1;
+    float s12 = a12 - (a01 * a02) / d1;
+    float s22 = a22 - (a02 * a02) / d1;
+    // second pivot: larger diagonal entry of the remaining 2x2 block
+    const bool swap12 = s22 > s11;
+    if (swap12) { std::swap(s11, s22); std::swap(l1, l2); std::swap(r1, r2); }
+    const float d2 = s11;
+    if (!(d2 > 0.0f)) return false;
+    const float l3 = s12 / d2;
+    const float d3 = s22 - l3 * s12;
+    if (!(d3 > 0.0f)) return false;
+    if (rcond_out) *rcond_out = d3 / d1;
+    if (!(d3 > rcond_min * d1)) return false;
+    // L y = r, D z = y, L^T w = z
+    const float y0 = r0;
+    const float y1 = r1 - l1 * y0;
+    const float y2 = (r2 - l2 * y0) - l3 * y1;
+    float w2 = y2 / d3;
+    float w1 = y1 / d2 - l3 * w2;
+    float w0 = (y0 / d1 - l1 * w1) - l2 * w2;
+    // undo the two exchanges, last one first
+    if (swap12) std::swap(w1, w2);
+    if (p == 1) std::swap(w0, w1);
+    if (p == 2) std::swap(w0, w2);
+    if (!std::isfinite(w0) || !std::isfinite(w1) || !std::isfinite(w2)) return false;
+    x[0] = w0;
+    x[1] = w1;
+    x[2] = w2;
+    return true;
+}
+
+// Contraction target of the pair (u, v) whose summed quadric is s: the mean of
+// the two positions (supplementary, Eq. "average_optimal" with |C| = 2), or
+// with placement = 1 the minimiser above wherever it is accepted.
+void pair_target(const float* s, const float* pu, const float* pv, const Opts& o, float* t) {
+    t[0] = (pu[0] + pv[0]) * 0.5f;
+    t[1] = (pu[1] + pv[1]) * 0.5f;
+    t[2] = (pu[2] + pv[2]) * 0.5f;
+    if (o.placement == 1) inverse_placement(s, o.rcond_min, t, nullptr);
+}
+
+// Q(x) = x^T A x + 2 b^T x + c (supplementary, quadric error).
+float quadric_error(const float* s, const float* x) {
+    float mx = x[0], my = x[1], mz = x[2];
     float t0 = (s[0] * mx + s[1] * my) + s[2] * mz;
     float t1 = (s[1] * mx + s[3] * my) + s[4] * mz;
     float t2 = (s[2] * mx + s[4] * my) + s[5] * mz;
     float xAx = (mx * t0 + my * t1) + mz * t2;
     float bx = (s[6] * mx + s[7] * my) + s[8] * mz;
     return (xAx + 2.0f * bx) + s[9];
+}
+
+// Quadric error of the pair's summed quadric at the pair's contraction target
+// (Alg. 2 line 2).
+float pair_cost(const Quadric& Qu, const Quadric& Qv, const float* pu, const float* pv, const Opts& o = Opts()) {
+    float s[10], t[3];
+    for (int k = 0; k < 10; ++k) s[k] = Qu.q[k] + Qv.q[k];
+    pair_target(s, pu, pv, o, t);
+    return quadric_error(s, t);
 }
 
 // Unsigned key whose integer order is the numeric order of the floats
@@ -184,27 +272,29 @@ struct Mesh {
 
 // One run of the core algorithm on the current mesh.  Returns the number of
 // contracted pairs; label[] (one entry per ORIGINAL vertex) is updated.
-int one_round(Mesh& M, int target_nv, std::vector<int32_t>& label) {
+int one_round(Mesh& M, int target_nv, std::vector<int32_t>& label, const Opts& o) {
     const int nv = M.nv();
     std::vector<std::pair<int32_t, int32_t>> E;
     unique_edges(M.facets.data(), M.nf(), E);
     std::vector<uint32_t> key(E.size());
     for (size_t e = 0; e < E.size(); ++e) {
         int32_t u = E[e].first, v = E[e].second;
-        key[e] = cost_key(pair_cost(M.Q[u], M.Q[v], &M.pos[3 * (size_t)u], &M.pos[3 * (size_t)v]));
+        key[e] = cost_key(pair_cost(M.Q[u], M.Q[v], &M.pos[3 * (size_t)u], &M.pos[3 * (size_t)v], o));
     }
     std::vector<uint8_t> sel;
     int n_r = greedy_pairs(E, key, nv, (int64_t)nv - target_nv, sel);
     if (n_r == 0) return 0;
 
-    // Alg. 2 lines 12-16: per cluster, summed quadric, mean position, contract.
+    // Alg. 2 lines 12-16: per cluster, summed quadric, target position, contract.
     std::vector<int32_t> remap(nv);
     for (int w = 0; w < nv; ++w) remap[w] = w;
     for (size_t e = 0; e < E.size(); ++e) {
         if (!sel[e]) continue;
         int32_t u = E[e].first, v = E[e].second;  // u < v, u represents the pair
-        for (int k = 0; k < 3; ++k) M.pos[3 * (size_t)u + k] = (M.pos[3 * (size_t)u + k] + M.pos[3 * (size_t)v + k]) * 0.5f;
+        float t[3];
         for (int k = 0; k < 10; ++k) M.Q[u].q[k] = M.Q[u].q[k] + M.Q[v].q[k];
+        pair_target(M.Q[u].q, &M.pos[3 * (size_t)u], &M.pos[3 * (size_t)v], o, t);
+        for (int k = 0; k < 3; ++k) M.pos[3 * (size_t)u + k] = t[k];
         remap[v] = u;
     }
 
@@ -253,7 +343,7 @@ int check_inputs(const float* verts, int32_t N, const int32_t* facets, int32_t F
 }
 
 int decimate(const float* verts, int32_t N, const int32_t* facets, int32_t F, int32_t target_nv, int32_t max_rounds,
-             Mesh& M, std::vector<int32_t>& label, int32_t* rounds_out) {
+             Mesh& M, std::vector<int32_t>& label, int32_t* rounds_out, const Opts& o = Opts()) {
     M.pos.assign(verts, verts + 3 * (size_t)N);
     M.facets.assign(facets, facets + 3 * (size_t)F);
     vertex_quadrics(verts, N, facets, F, M.Q);
@@ -261,7 +351,7 @@ int decimate(const float* verts, int32_t N, const int32_t* facets, int32_t F, in
     for (int o = 0; o < N; ++o) label[o] = o;
     int rounds = 0, status = OK;
     while (M.nv() > target_nv && (max_rounds < 0 || rounds < max_rounds)) {
-        if (one_round(M, target_nv, label) == 0) {
+        if (one_round(M, target_nv, label, o) == 0) {
             status = WARN_BUDGET_UNMET;
             break;
         }
@@ -351,6 +441,59 @@ int picasso_oracle_decimate_rounds(const float* verts, int32_t N, const int32_t*
     std::memcpy(cluster_id, label.data(), label.size() * sizeof(int32_t));
     if (quadrics_out)
         for (int v = 0; v < M.nv(); ++v) std::memcpy(quadrics_out + 10 * (size_t)v, M.Q[v].q, 40);
+    *nv_out = M.nv();
+    *nf_out = M.nf();
+    return st;
+}
+
+// ---- variants: placement (0 mean, 1 inverse with fallback) and its threshold
+
+int picasso_oracle_pair_target(const float* quadric_sum, const float* pu, const float* pv, int32_t placement,
+                               float rcond_min, float* target, float* rcond, int32_t* used_inverse) {
+    Opts o;
+    o.placement = placement;
+    o.rcond_min = rcond_min;
+    pair_target(quadric_sum, pu, pv, o, target);
+    float x[3] = {0.0f, 0.0f, 0.0f};
+    const bool ok = inverse_placement(quadric_sum, rcond_min, x, rcond);
+    if (used_inverse) *used_inverse = (placement == 1 && ok) ? 1 : 0;
+    return OK;
+}
+
+int picasso_oracle_edge_costs_opts(const float* pos, const float* Q, const int32_t* edges, int32_t E,
+                                   int32_t placement, float rcond_min, float* cost, uint32_t* key) {
+    Opts o;
+    o.placement = placement;
+    o.rcond_min = rcond_min;
+    for (int e = 0; e < E; ++e) {
+        int32_t u = edges[2 * e], v = edges[2 * e + 1];
+        Quadric Qu, Qv;
+        std::memcpy(Qu.q, Q + 10 * (size_t)u, sizeof(Qu.q));
+        std::memcpy(Qv.q, Q + 10 * (size_t)v, sizeof(Qv.q));
+        float c = pair_cost(Qu, Qv, pos + 3 * (size_t)u, pos + 3 * (size_t)v, o);
+        if (cost) cost[e] = c;
+        if (key) key[e] = cost_key(c);
+    }
+    return OK;
+}
+
+int picasso_oracle_decimate_opts(const float* verts, int32_t N, const int32_t* facets, int32_t F, int32_t target_nv,
+                                 int32_t max_rounds, int32_t placement, float rcond_min, float* verts_out,
+                                 int32_t* facets_out, int32_t* cluster_id, int32_t* nv_out, int32_t* nf_out,
+                                 int32_t* rounds_out) {
+    int st = check_inputs(verts, N, facets, F, target_nv);
+    if (st < 0) return st;
+    if (!verts_out || !facets_out || !cluster_id || !nv_out || !nf_out) return ERR_INVALID_ARG;
+    if (placement != 0 && placement != 1) return ERR_INVALID_ARG;
+    Opts o;
+    o.placement = placement;
+    o.rcond_min = rcond_min;
+    Mesh M;
+    std::vector<int32_t> label;
+    st = decimate(verts, N, facets, F, target_nv, max_rounds, M, label, rounds_out, o);
+    std::memcpy(verts_out, M.pos.data(), M.pos.size() * sizeof(float));
+    std::memcpy(facets_out, M.facets.data(), M.facets.size() * sizeof(int32_t));
+    std::memcpy(cluster_id, label.data(), label.size() * sizeof(int32_t));
     *nv_out = M.nv();
     *nf_out = M.nf();
     return st;
