@@ -52,12 +52,24 @@ enum picasso_option {
                                       round's edge-key sort runs on a stream of the context's own
                                       beside the vertex quadrics and joins `stream` before costs
                                       are computed; 0: everything on `stream`                      */
-    PICASSO_OPT_TRUNC_BLOCK_MAX = 5 /* budget step (Alg. 2 lines 3-4 and 6): a mesh that formed more
+    PICASSO_OPT_TRUNC_BLOCK_MAX = 5,/* budget step (Alg. 2 lines 3-4 and 6): a mesh that formed more
                                       pairs than it may remove keeps its cheapest ones; while no
                                       such mesh formed more than this many pairs (default and
                                       largest value 32768) one workgroup per mesh selects them,
                                       above it the pairs of all such meshes are sorted.  Same
                                       result either way.                                           */
+    PICASSO_OPT_PLACEMENT = 6,     /* where a pair is contracted to, and where its cost is taken
+                                      (Alg. 2 lines 2 and 14; supplementary, the two placement
+                                      equations).  0 (default): the mean of the two positions.
+                                      1: the point of least quadric error, the solution of
+                                      A x = -b for the pair's summed quadric, wherever A is of
+                                      full rank, else the mean.  A (positive semi-definite) is
+                                      factored with diagonal pivoting; it counts as of full rank
+                                      when its three pivots are positive and smallest / largest
+                                      exceeds the threshold below (the paper tests the reciprocal
+                                      condition number without saying how or against what).      */
+    PICASSO_OPT_RCOND_MIN_BITS = 7 /* that threshold, passed as the bit pattern of a binary32
+                                      value (finite, >= 0; default 1e-3)                          */
 };
 
 #define PICASSO_STATS_ROUNDS 32

@@ -26,6 +26,9 @@ PICASSO_OPT_SUBROUND_BATCH = 2
 PICASSO_OPT_KERNEL_TIMING = 3
 PICASSO_OPT_OVERLAP = 4
 PICASSO_OPT_TRUNC_BLOCK_MAX = 5
+PICASSO_OPT_PLACEMENT = 6
+PICASSO_OPT_RCOND_MIN_BITS = 7
+PICASSO_PLACE_MEAN, PICASSO_PLACE_INVERSE = 0, 1
 
 PICASSO_STATS_ROUNDS = 32
 PICASSO_ST_COUNT = 8
@@ -197,6 +200,12 @@ class Context:
         st = self._lib.picasso_set_option(self._h, int(option), int(value))
         if st != PICASSO_OK:
             raise PicassoError(st, picasso_strerror(st))
+
+    def set_placement(self, placement: int, rcond_min: float = 1e-3):
+        """PICASSO_OPT_PLACEMENT and its binary32 threshold (passed on as a bit pattern)."""
+        import struct
+        self.set_option(PICASSO_OPT_RCOND_MIN_BITS, struct.unpack("<I", struct.pack("<f", float(rcond_min)))[0])
+        self.set_option(PICASSO_OPT_PLACEMENT, placement)
 
     def picasso_kernel_timing(self, reset=False):
         """Totals for the edge-key sort's main kernel while PICASSO_OPT_KERNEL_TIMING is on."""

@@ -389,10 +389,69 @@ struct UniquePred {
     }
 };
 
-// S2: cost of a pair = quadric error of the summed quadric at the pair's mean
-// (Alg. 2 line 2; supplementary Q(x) = x^T A x + 2 b^T x + c and the mean
-// placement equation).
-__device__ __forceinline__ float pair_cost(const VRec* __restrict__ vrec, int u, int v) {
+// Where a pair is contracted to.
+enum { PLACE_MEAN = 0, PLACE_INVERSE = 1 };
+
+// Point of least quadric error, the solution of A x = -b (supplementary,
+// inverse placement equation), for a positive semi-definite A = sum of n n^T.
+// The three axes are eliminated in the order of the largest remaining diagonal
+// entry (P A P^T = L D L^T); A counts as of full rank when all three pivots are
+// positive and the last exceeds rcond_min times the first, their ratio standing
+// for the reciprocal condition number.  Returns false, leaving (x, y, z) as
+// they are, when A is not of full rank or the solution is not finite.
+__device__ __forceinline__ bool quadric_minimiser(float a00, float a01, float a02, float a11, float a12, float a22,
+                                                  float b0, float b1, float b2, float rcond_min, float& x, float& y,
+                                                  float& z) {
+    float r0 = -b0, r1 = -b1, r2 = -b2, t;
+    int first = 0;
+    float top = a00;
+    if (a11 > top) { first = 1; top = a11; }
+    if (a22 > top) { first = 2; top = a22; }
+    if (first == 1) {  // axes 0 and 1 change places
+        t = a00; a00 = a11; a11 = t;
+        t = a02; a02 = a12; a12 = t;
+        t = r0; r0 = r1; r1 = t;
+    } else if (first == 2) {  // axes 0 and 2 change places
+        t = a00; a00 = a22; a22 = t;
+        t = a01; a01 = a12; a12 = t;
+        t = r0; r0 = r2; r2 = t;
+    }
+    const float d1 = a00;
+    if (!(d1 > 0.0f)) return false;
+    float l1 = a01 / d1, l2 = a02 / d1;
+    float s11 = a11 - (a01 * a01) / d1;
+    const float s12 = a12 - (a01 * a02) / d1;
+    float s22 = a22 - (a02 * a02) / d1;
+    const bool flip = s22 > s11;  // the larger entry of the remaining block goes next
+    if (flip) {
+        t = s11; s11 = s22; s22 = t;
+        t = l1; l1 = l2; l2 = t;
+        t = r1; r1 = r2; r2 = t;
+    }
+    const float d2 = s11;
+    if (!(d2 > 0.0f)) return false;
+    const float l3 = s12 / d2;
+    const float d3 = s22 - l3 * s12;
+    if (!(d3 > 0.0f) || !(d3 > rcond_min * d1)) return false;
+    const float y1 = r1 - l1 * r0;
+    const float y2 = (r2 - l2 * r0) - l3 * y1;
+    float w2 = y2 / d3;
+    float w1 = y1 / d2 - l3 * w2;
+    float w0 = (r0 / d1 - l1 * w1) - l2 * w2;
+    if (flip) { t = w1; w1 = w2; w2 = t; }
+    if (first == 1) { t = w0; w0 = w1; w1 = t; }
+    else if (first == 2) { t = w0; w0 = w2; w2 = t; }
+    if (!isfinite(w0) || !isfinite(w1) || !isfinite(w2)) return false;
+    x = w0; y = w1; z = w2;
+    return true;
+}
+
+// S2: cost of a pair = quadric error of the summed quadric at the point the
+// pair would be contracted to: the pair's mean, or with PLACE_INVERSE the point
+// of least error where the quadric has one (Alg. 2 line 2; supplementary
+// Q(x) = x^T A x + 2 b^T x + c and the two placement equations).
+template <int PLACE>
+__device__ __forceinline__ float pair_cost(const VRec* __restrict__ vrec, int u, int v, float rcond_min) {
     const float4* ru = reinterpret_cast<const float4*>(&vrec[u]);
     const float4* rv = reinterpret_cast<const float4*>(&vrec[v]);
     const float4 u0 = ru[0], u1 = ru[1], u2 = ru[2], u3 = ru[3];
@@ -400,9 +459,10 @@ __device__ __forceinline__ float pair_cost(const VRec* __restrict__ vrec, int u,
     const float a00 = u1.x + v1.x, a01 = u1.y + v1.y, a02 = u1.z + v1.z, a11 = u1.w + v1.w;
     const float a12 = u2.x + v2.x, a22 = u2.y + v2.y, b0 = u2.z + v2.z, b1 = u2.w + v2.w;
     const float b2 = u3.x + v3.x, c = u3.y + v3.y;
-    const float mx = (u0.x + v0.x) * 0.5f;
-    const float my = (u0.y + v0.y) * 0.5f;
-    const float mz = (u0.z + v0.z) * 0.5f;
+    float mx = (u0.x + v0.x) * 0.5f;
+    float my = (u0.y + v0.y) * 0.5f;
+    float mz = (u0.z + v0.z) * 0.5f;
+    if (PLACE == PLACE_INVERSE) quadric_minimiser(a00, a01, a02, a11, a12, a22, b0, b1, b2, rcond_min, mx, my, mz);
     const float t0 = (a00 * mx + a01 * my) + a02 * mz;
     const float t1 = (a01 * mx + a11 * my) + a12 * mz;
     const float t2 = (a02 * mx + a12 * my) + a22 * mz;
@@ -441,7 +501,8 @@ __device__ __forceinline__ void bid_grouped(u64* __restrict__ vmin, bool on, int
 
 // Writes the distinct edges, their cost keys, and places each edge's first bid
 // (sub-round 0 of the selection) on both of its vertices.
-struct UniqueOut {
+template <int PLACE>
+struct UniqueOutT {
     static constexpr bool WAVE_WIDE = true;
     const u64* keys;
     u64* ekey;
@@ -451,6 +512,7 @@ struct UniqueOut {
     unsigned char* estate;
     int vbits;
     MeshTab mt;
+    float rcond_min;
     __device__ void wave(int i, bool in_range, bool flagged, int e) const {
         bool act = false;
         int u = 0;
@@ -460,7 +522,7 @@ struct UniqueOut {
             u = (int)(k >> vbits);
             const int v = (int)(k & ((1ull << vbits) - 1ull));
             ekey[e] = k;
-            const u32 ck = cost_key(pair_cost(vrec, u, v));
+            const u32 ck = cost_key(pair_cost<PLACE>(vrec, u, v, rcond_min));
             ecost[e] = ck;
             act = mt.active[mesh_of(mt.voff, mt.B, u)] != 0;
             estate[e] = act ? 0 : 1;
@@ -1070,14 +1132,16 @@ struct AliveOut {
     __device__ void operator()(int w, int pos) const { newid[w] = pos; }
 };
 
-// Survivors move to their new slot; a pair's representative takes the mean
-// position and the summed quadric.  vmap[w] = output slot of w's cluster.
+// Survivors move to their new slot; a pair's representative takes the summed
+// quadric and the pair's target position (the mean; with PLACE_INVERSE the
+// point of least error where there is one).  vmap[w] = output slot of w's cluster.
+template <int PLACE>
 __global__ __launch_bounds__(BLOCK) void contract_kernel(const VRec* __restrict__ vin, VRec* __restrict__ vout,
                                                          const int* __restrict__ mate, const int* __restrict__ newid,
                                                          int* __restrict__ vmap, const State* st, int cur, int B,
                                                          const int* __restrict__ voff_cur, int* __restrict__ voff_nxt,
                                                          int* __restrict__ htab, int hsize,
-                                                         u32* __restrict__ msd_hist) {
+                                                         u32* __restrict__ msd_hist, float rcond_min) {
     const int nv = st->nv[cur];
     const int stride = gridDim.x * BLOCK;
     const int g = blockIdx.x * BLOCK + threadIdx.x;
@@ -1100,6 +1164,8 @@ __global__ __launch_bounds__(BLOCK) void contract_kernel(const VRec* __restrict_
             r1.x = r1.x + s1.x; r1.y = r1.y + s1.y; r1.z = r1.z + s1.z; r1.w = r1.w + s1.w;
             r2.x = r2.x + s2.x; r2.y = r2.y + s2.y; r2.z = r2.z + s2.z; r2.w = r2.w + s2.w;
             r3.x = r3.x + s3.x; r3.y = r3.y + s3.y;
+            if (PLACE == PLACE_INVERSE)
+                quadric_minimiser(r1.x, r1.y, r1.z, r1.w, r2.x, r2.y, r2.z, r2.w, r3.x, rcond_min, r0.x, r0.y, r0.z);
         }
         float4* o = reinterpret_cast<float4*>(&vout[nw]);
         o[0] = r0; o[1] = r1; o[2] = r2; o[3] = r3;
@@ -1364,6 +1430,8 @@ struct picasso_ctx {
     hipEvent_t ev_total[2];
     // hipEvent brackets around the edge-key sort's main kernel (benchmark roofline)
     int64_t opt_kernel_timing = 0;  // N > 0: events around the kernel in every N-th decimate call
+    int opt_placement = PLACE_MEAN;
+    float opt_rcond_min = 1e-3f;
     int64_t kt_calls = 0;           // decimate calls since the option was set
     bool kt_this_call = false;
     hipEvent_t kt_pool[512];
@@ -1750,8 +1818,14 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         }
         const u64 sentinel = (vbits >= 32) ? ~0ull : ((1ull << (2 * vbits)) - 1ull);
         UniquePred up{skeys, sentinel};
-        UniqueOut uo{skeys, c->ekey, c->ecost, c->vrec[cur], c->vmin[0], c->estate, vbits, mt};
-        prim::compact_scatter(s, up, uo, &c->st->nh, H, c->tilesum, &c->st->ne);
+        if (c->opt_placement == PLACE_INVERSE) {
+            UniqueOutT<PLACE_INVERSE> uo{skeys, c->ekey, c->ecost, c->vrec[cur], c->vmin[0], c->estate, vbits, mt,
+                                         c->opt_rcond_min};
+            prim::compact_scatter(s, up, uo, &c->st->nh, H, c->tilesum, &c->st->ne);
+        } else {
+            UniqueOutT<PLACE_MEAN> uo{skeys, c->ekey, c->ecost, c->vrec[cur], c->vmin[0], c->estate, vbits, mt, 0.0f};
+            prim::compact_scatter(s, up, uo, &c->st->nh, H, c->tilesum, &c->st->ne);
+        }
         tm.end();
 
         // ---- S3: selection sub-rounds
@@ -1889,9 +1963,15 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         AliveOut ao{c->newid};
         prim::compact(s, ap, ap, ao, nullptr, nv_total, c->tilesum, &c->st->nv[nxt]);
         const size_t hsize = next_pow2((size_t)2 * std::max(nf_bound, 1));
-        contract_kernel<<<grid_for(std::max<long long>(nv_total, (long long)hsize), 8192), BLOCK, 0, s>>>(
-            c->vrec[cur], c->vrec[nxt], c->mate, c->newid, c->vmap, c->st, cur, B, c->voff[cur], c->voff[nxt],
-            c->htab, (int)hsize, c->hist12);
+        const int cgrid = grid_for(std::max<long long>(nv_total, (long long)hsize), 8192);
+        if (c->opt_placement == PLACE_INVERSE)
+            contract_kernel<PLACE_INVERSE><<<cgrid, BLOCK, 0, s>>>(
+                c->vrec[cur], c->vrec[nxt], c->mate, c->newid, c->vmap, c->st, cur, B, c->voff[cur], c->voff[nxt],
+                c->htab, (int)hsize, c->hist12, c->opt_rcond_min);
+        else
+            contract_kernel<PLACE_MEAN><<<cgrid, BLOCK, 0, s>>>(
+                c->vrec[cur], c->vrec[nxt], c->mate, c->newid, c->vmap, c->st, cur, B, c->voff[cur], c->voff[nxt],
+                c->htab, (int)hsize, c->hist12, 0.0f);
         tm.end();
 
         // ---- S5: facets
@@ -2047,6 +2127,19 @@ int picasso_set_option(picasso_ctx* c, int option, int64_t value) {
             if (value < 0) return PICASSO_ERR_INVALID_ARG;
             c->opt_trunc_block_max = std::min<int64_t>(value, TRUNC_BLOCK_CAP);
             return PICASSO_OK;
+        case PICASSO_OPT_PLACEMENT:
+            if (value != PLACE_MEAN && value != PLACE_INVERSE) return PICASSO_ERR_INVALID_ARG;
+            c->opt_placement = (int)value;
+            return PICASSO_OK;
+        case PICASSO_OPT_RCOND_MIN_BITS: {
+            if (value < 0 || value > 0xFFFFFFFFll) return PICASSO_ERR_INVALID_ARG;
+            const u32 bits = (u32)value;
+            float f;
+            memcpy(&f, &bits, sizeof f);
+            if (!(f >= 0.0f) || !std::isfinite(f)) return PICASSO_ERR_INVALID_ARG;
+            c->opt_rcond_min = f;
+            return PICASSO_OK;
+        }
         case PICASSO_OPT_SUBROUND_BATCH:
             if (value < 1 || value > 1024) return PICASSO_ERR_INVALID_ARG;
             c->opt_subround_batch = value;
@@ -2167,8 +2260,14 @@ int picasso_edge_costs(picasso_ctx* c, void* stream, const float* d_verts, int32
     if (rc != PICASSO_OK) return rc;
     const u64 sentinel = (vbits >= 32) ? ~0ull : ((1ull << (2 * vbits)) - 1ull);
     UniquePred up{skeys, sentinel};
-    UniqueOut uo{skeys, c->ekey, c->ecost, c->vrec[0], c->vmin[0], c->estate, vbits, mt};
-    prim::compact_scatter(s, up, uo, &c->st->nh, H, c->tilesum, &c->st->ne);
+    if (c->opt_placement == PLACE_INVERSE) {
+        UniqueOutT<PLACE_INVERSE> uo{skeys, c->ekey, c->ecost, c->vrec[0], c->vmin[0], c->estate, vbits, mt,
+                                     c->opt_rcond_min};
+        prim::compact_scatter(s, up, uo, &c->st->nh, H, c->tilesum, &c->st->ne);
+    } else {
+        UniqueOutT<PLACE_MEAN> uo{skeys, c->ekey, c->ecost, c->vrec[0], c->vmin[0], c->estate, vbits, mt, 0.0f};
+        prim::compact_scatter(s, up, uo, &c->st->nh, H, c->tilesum, &c->st->ne);
+    }
     export_edges_kernel<<<grid_for(std::max(H, 1)), BLOCK, 0, s>>>(c->ekey, c->ecost, c->st, vbits, d_edges_out,
                                                                    d_cost_out);
     rc = read_header(c, s);
