@@ -115,7 +115,19 @@ def select(edge_list, key, n_verts, n_remove):
     return sel.astype(bool), n
 
 
-def decimate(verts, facets, target_nv, max_rounds=-1, return_quadrics=False, placement=PLACE_MEAN, rcond_min=0.0):
+def select_absorb(edge_list, key, n_verts, n_remove):
+    """Alg. 2 lines 3-11 (line 11 under the budget): (selected[E], via[N], vertices removed)."""
+    edge_list = _i32(edge_list)
+    key = np.ascontiguousarray(key, dtype=np.uint32)
+    sel = np.zeros(edge_list.shape[0], np.uint8)
+    via = np.full(int(n_verts), -1, np.int32)
+    n = lib().picasso_oracle_select_absorb(_p(edge_list), _p(key), edge_list.shape[0], int(n_verts), int(n_remove),
+                                           _p(sel), _p(via))
+    return sel.astype(bool), via, n
+
+
+def decimate(verts, facets, target_nv, max_rounds=-1, return_quadrics=False, placement=PLACE_MEAN, rcond_min=0.0,
+             absorb=False):
     """Returns dict(status, verts, facets, cluster_id, rounds[, quadrics])."""
     verts, facets = _f32(verts), _i32(facets).reshape(-1, 3)
     N, F = verts.shape[0], facets.shape[0]
@@ -124,11 +136,11 @@ def decimate(verts, facets, target_nv, max_rounds=-1, return_quadrics=False, pla
     cid = np.zeros(max(N, 1), np.int32)
     qo = np.zeros((max(N, 1), 10), np.float32)
     nv, nf, rounds = ctypes.c_int32(0), ctypes.c_int32(0), ctypes.c_int32(0)
-    if placement != PLACE_MEAN:
-        assert not return_quadrics
+    if placement != PLACE_MEAN or absorb:
         st = lib().picasso_oracle_decimate_opts(
             _p(verts), N, _p(facets), F, int(target_nv), int(max_rounds), int(placement), ctypes.c_float(rcond_min),
-            _p(vo), _p(fo), _p(cid), ctypes.byref(nv), ctypes.byref(nf), ctypes.byref(rounds))
+            int(bool(absorb)), _p(vo), _p(fo), _p(cid), ctypes.byref(nv), ctypes.byref(nf), ctypes.byref(rounds),
+            _p(qo))
     else:
         st = lib().picasso_oracle_decimate_rounds(
             _p(verts), N, _p(facets), F, int(target_nv), int(max_rounds), _p(vo), _p(fo), _p(cid),

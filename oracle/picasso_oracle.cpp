@@ -46,6 +46,16 @@
 //    (full rank iff ratio > threshold).  The system is solved with the same
 //    factors.  The pair's cost (Alg. 2 line 2) is the quadric error at that
 //    same target.
+//  * absorb = 1: Alg. 2 line 11 is applied, under the vertex budget.  After
+//    lines 5-10 the pairs are visited once more in the same ascending order; a
+//    pair with one end in a cluster founded in lines 5-10 and the other end in
+//    no cluster adds that end to that cluster, while n_r < N_r (every vertex
+//    added is one more vertex removed, so the output still has exactly N
+//    vertices whenever enough edges exist).  Only founders attract: a vertex
+//    added by line 11 does not pull in its own neighbours (Fig. 2 (c) joins
+//    each remaining point to a pair it touches).  A cluster is represented by
+//    its founding pair's smaller index; its quadric and its mean position are
+//    summed over its members in ascending index order.
 //
 // Pins: see tests/test_oracle_*.py (closed forms, brute force, invariants,
 // hand-worked fixtures under tests/golden/).  The whole multi-round pipeline has
@@ -143,6 +153,7 @@ void unique_edges(const int32_t* F, int nF, std::vector<std::pair<int32_t, int32
 struct Opts {
     int placement = 0;        // 0: mean of the pair; 1: -A^-1 b where A has full rank, else the mean
     float rcond_min = 0.0f;   // full rank iff rcond > rcond_min
+    int absorb = 0;           // 1: Alg. 2 line 11 under the budget
 };
 
 // Minimiser of the quadric s = (A, b, c): the solution of A x = -b
@@ -262,6 +273,38 @@ int greedy_pairs(const std::vector<std::pair<int32_t, int32_t>>& E, const std::v
     return (int)n_r;
 }
 
+// Alg. 2 line 11 under the budget (see the header): second walk over the pairs
+// in ascending (key, index) order.  founder[] marks the ends of the pairs formed
+// in lines 5-10; via[w] receives the index of the pair that added w to a
+// founder's cluster (-1 otherwise).  Returns the number of vertices added.
+int absorb_remaining(const std::vector<std::pair<int32_t, int32_t>>& E, const std::vector<uint32_t>& key, int N,
+                     int64_t n_remove, int64_t n_r, const std::vector<uint8_t>& selected,
+                     std::vector<int32_t>& via) {
+    const int nE = (int)E.size();
+    std::vector<int32_t> order(nE);
+    for (int i = 0; i < nE; ++i) order[i] = i;
+    std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return key[a] < key[b]; });
+    std::vector<uint8_t> founder(N, 0), in_cluster(N, 0);
+    for (int e = 0; e < nE; ++e)
+        if (selected[e]) founder[E[e].first] = founder[E[e].second] = in_cluster[E[e].first] = in_cluster[E[e].second] = 1;
+    via.assign(N, -1);
+    int added = 0;
+    for (int r = 0; r < nE; ++r) {
+        if (!(n_r < n_remove)) break;
+        const int e = order[r];
+        const int32_t u = E[e].first, v = E[e].second;
+        int32_t w = -1;
+        if (founder[u] && !in_cluster[v]) w = v;
+        if (founder[v] && !in_cluster[u]) w = u;
+        if (w < 0) continue;
+        in_cluster[w] = 1;
+        via[w] = e;
+        ++n_r;
+        ++added;
+    }
+    return added;
+}
+
 struct Mesh {
     std::vector<float> pos;       // [nv,3]
     std::vector<Quadric> Q;       // [nv]
@@ -285,17 +328,56 @@ int one_round(Mesh& M, int target_nv, std::vector<int32_t>& label, const Opts& o
     int n_r = greedy_pairs(E, key, nv, (int64_t)nv - target_nv, sel);
     if (n_r == 0) return 0;
 
-    // Alg. 2 lines 12-16: per cluster, summed quadric, target position, contract.
+    // remap[w] = representative of w's cluster (the founding pair's smaller index)
     std::vector<int32_t> remap(nv);
     for (int w = 0; w < nv; ++w) remap[w] = w;
+    for (size_t e = 0; e < E.size(); ++e)
+        if (sel[e]) remap[E[e].second] = E[e].first;
+    std::vector<std::vector<int32_t>> members;  // of the clusters line 11 enlarged, ascending; indexed by representative
+    if (o.absorb) {
+        std::vector<int32_t> via;
+        n_r += absorb_remaining(E, key, nv, (int64_t)nv - target_nv, n_r, sel, via);
+        std::vector<uint8_t> enlarged(nv, 0);
+        for (int w = 0; w < nv; ++w) {
+            if (via[w] < 0) continue;
+            const int32_t a = E[via[w]].first, b = E[via[w]].second;
+            remap[w] = remap[w == a ? b : a];
+            enlarged[remap[w]] = 1;
+        }
+        members.resize(nv);
+        for (int w = 0; w < nv; ++w)
+            if (enlarged[remap[w]]) members[remap[w]].push_back(w);
+    }
+
+    // Alg. 2 lines 12-16: per cluster, summed quadric, target position, contract.
     for (size_t e = 0; e < E.size(); ++e) {
         if (!sel[e]) continue;
         int32_t u = E[e].first, v = E[e].second;  // u < v, u represents the pair
-        float t[3];
-        for (int k = 0; k < 10; ++k) M.Q[u].q[k] = M.Q[u].q[k] + M.Q[v].q[k];
-        pair_target(M.Q[u].q, &M.pos[3 * (size_t)u], &M.pos[3 * (size_t)v], o, t);
+        if (members.empty() || members[u].empty()) {
+            float t[3];
+            for (int k = 0; k < 10; ++k) M.Q[u].q[k] = M.Q[u].q[k] + M.Q[v].q[k];
+            pair_target(M.Q[u].q, &M.pos[3 * (size_t)u], &M.pos[3 * (size_t)v], o, t);
+            for (int k = 0; k < 3; ++k) M.pos[3 * (size_t)u + k] = t[k];
+            continue;
+        }
+        // a cluster that line 11 enlarged: members in ascending index order
+        Quadric acc;
+        float sum[3] = {0.0f, 0.0f, 0.0f};
+        int cnt = 0;
+        for (int32_t w : members[u]) {
+            if (cnt == 0) {
+                acc = M.Q[w];
+                for (int k = 0; k < 3; ++k) sum[k] = M.pos[3 * (size_t)w + k];
+            } else {
+                for (int k = 0; k < 10; ++k) acc.q[k] = acc.q[k] + M.Q[w].q[k];
+                for (int k = 0; k < 3; ++k) sum[k] = sum[k] + M.pos[3 * (size_t)w + k];
+            }
+            ++cnt;
+        }
+        float t[3] = {sum[0] / (float)cnt, sum[1] / (float)cnt, sum[2] / (float)cnt};
+        if (o.placement == 1) inverse_placement(acc.q, o.rcond_min, t, nullptr);
+        M.Q[u] = acc;
         for (int k = 0; k < 3; ++k) M.pos[3 * (size_t)u + k] = t[k];
-        remap[v] = u;
     }
 
     // facets: re-index, drop collapsed ones and later copies of the same triple
@@ -478,25 +560,45 @@ int picasso_oracle_edge_costs_opts(const float* pos, const float* Q, const int32
 }
 
 int picasso_oracle_decimate_opts(const float* verts, int32_t N, const int32_t* facets, int32_t F, int32_t target_nv,
-                                 int32_t max_rounds, int32_t placement, float rcond_min, float* verts_out,
-                                 int32_t* facets_out, int32_t* cluster_id, int32_t* nv_out, int32_t* nf_out,
-                                 int32_t* rounds_out) {
+                                 int32_t max_rounds, int32_t placement, float rcond_min, int32_t absorb,
+                                 float* verts_out, int32_t* facets_out, int32_t* cluster_id, int32_t* nv_out,
+                                 int32_t* nf_out, int32_t* rounds_out, float* quadrics_out) {
     int st = check_inputs(verts, N, facets, F, target_nv);
     if (st < 0) return st;
     if (!verts_out || !facets_out || !cluster_id || !nv_out || !nf_out) return ERR_INVALID_ARG;
-    if (placement != 0 && placement != 1) return ERR_INVALID_ARG;
+    if ((placement != 0 && placement != 1) || (absorb != 0 && absorb != 1)) return ERR_INVALID_ARG;
     Opts o;
     o.placement = placement;
     o.rcond_min = rcond_min;
+    o.absorb = absorb;
     Mesh M;
     std::vector<int32_t> label;
     st = decimate(verts, N, facets, F, target_nv, max_rounds, M, label, rounds_out, o);
     std::memcpy(verts_out, M.pos.data(), M.pos.size() * sizeof(float));
     std::memcpy(facets_out, M.facets.data(), M.facets.size() * sizeof(int32_t));
     std::memcpy(cluster_id, label.data(), label.size() * sizeof(int32_t));
+    if (quadrics_out)
+        for (int v = 0; v < M.nv(); ++v) std::memcpy(quadrics_out + 10 * (size_t)v, M.Q[v].q, 40);
     *nv_out = M.nv();
     *nf_out = M.nf();
     return st;
+}
+
+// Alg. 2 lines 3-11 on an explicit edge list with explicit keys: selected[e] = 1
+// for the pairs of lines 5-10, via[w] = index of the pair through which line 11
+// added vertex w to a cluster (-1: not added).  Returns pairs + added vertices.
+int picasso_oracle_select_absorb(const int32_t* edges, const uint32_t* key, int32_t E, int32_t N, int32_t n_remove,
+                                 uint8_t* selected, int32_t* via) {
+    std::vector<std::pair<int32_t, int32_t>> Ed(E);
+    for (int e = 0; e < E; ++e) Ed[e] = {edges[2 * e], edges[2 * e + 1]};
+    std::vector<uint32_t> k(key, key + E);
+    std::vector<uint8_t> sel;
+    int n = greedy_pairs(Ed, k, N, n_remove, sel);
+    std::vector<int32_t> v;
+    n += absorb_remaining(Ed, k, N, n_remove, n, sel, v);
+    std::memcpy(selected, sel.data(), E);
+    std::memcpy(via, v.data(), sizeof(int32_t) * (size_t)N);
+    return n;
 }
 
 int picasso_oracle_decimate(const float* verts, int32_t N, const int32_t* facets, int32_t F, int32_t target_nv,

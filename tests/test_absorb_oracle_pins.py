@@ -1,0 +1,192 @@
+"""Pins for the oracle's reading of Alg. 2 line 11 (Sec. 3: the remaining
+vertices join an existing cluster they are connected to; Fig. 2), applied under
+the vertex budget.  Checked against a hand-followed example, a declarative
+characterisation of the result verified by brute force on small random
+graphs, and invariants of whole runs recomputed with numpy.  (CPU only.)
+"""
+import json
+import os
+
+import numpy as np
+import pytest
+
+from paper_2103_15076_amd import meshgen
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def test_hand_followed_example_in_the_shape_of_fig2(oracle):
+    fx = json.load(open(os.path.join(GOLD, "absorb_fig2_like.json")))
+    E = np.asarray(fx["edges"], np.int32)
+    key = np.asarray(fx["keys"], np.uint32)
+    for case in fx["cases"]:
+        sel, via, removed = oracle.select_absorb(E, key, 6, case["n_remove"])
+        assert np.nonzero(sel)[0].tolist() == case["selected_edges"]
+        assert via.tolist() == case["via"]
+        assert removed == case["removed"]
+        # clusters implied by the pairs and the joining edges
+        rep = list(range(6))
+        for e in np.nonzero(sel)[0]:
+            rep[E[e, 1]] = E[e, 0]
+        for w in range(6):
+            if via[w] >= 0:
+                a, b = E[via[w]]
+                rep[w] = rep[b if w == a else a]
+        clusters = sorted(sorted(w for w in range(6) if rep[w] == r) for r in set(rep))
+        assert clusters == case["clusters"]
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_result_is_characterised_without_walking_the_list(oracle, seed):
+    """On random graphs with many tied keys: (i) lines 5-10 are the pinned greedy
+    pairs; (ii) a vertex can only join through its cheapest pair (key, index)
+    among those leading to a founder; (iii) the vertices that join are exactly
+    the `budget left` cheapest of those, each through that pair."""
+    rng = np.random.default_rng(seed)
+    n = int(rng.integers(4, 30))
+    m = int(rng.integers(n, 4 * n))
+    pairs = set()
+    while len(pairs) < min(m, n * (n - 1) // 2):
+        a, b = rng.integers(0, n, 2)
+        if a != b:
+            pairs.add((min(a, b), max(a, b)))
+    E = np.array(sorted(pairs), np.int32)
+    key = rng.integers(0, 6, E.shape[0]).astype(np.uint32)
+    n_remove = int(rng.integers(0, n))
+    sel, via, removed = oracle.select_absorb(E, key, n, n_remove)
+    sel_ref, n_pairs = oracle.select(E, key, n, n_remove)
+    assert np.array_equal(sel, sel_ref)
+    founder = np.zeros(n, bool)
+    founder[E[sel].reshape(-1)] = True
+    best = {}
+    for e, (a, b) in enumerate(E):
+        for w, o in ((a, b), (b, a)):
+            if not founder[w] and founder[o]:
+                pr = (int(key[e]), e)
+                if w not in best or pr < best[w]:
+                    best[w] = pr
+    left = n_remove - n_pairs
+    chosen = sorted(best.items(), key=lambda kv: kv[1])[:max(left, 0)]
+    want = np.full(n, -1, np.int32)
+    for w, (_, e) in chosen:
+        want[w] = e
+    assert np.array_equal(via, want)
+    assert removed == n_pairs + len(chosen)
+
+
+def _mesh_edges(F):
+    a = np.concatenate([F[:, [0, 1]], F[:, [1, 2]], F[:, [2, 0]]])
+    a = np.sort(a[a[:, 0] != a[:, 1]], axis=1)
+    return np.unique(a, axis=0)
+
+
+def _vertex_quadrics64(V, F):
+    V = V.astype(np.float64)
+    Q = np.zeros((V.shape[0], 10))
+    for f in F:
+        if len(set(f.tolist())) < 3:
+            continue
+        p0, p1, p2 = V[f[0]], V[f[1]], V[f[2]]
+        n = np.cross(p1 - p0, p2 - p0)
+        ln = np.linalg.norm(n)
+        if ln == 0:
+            continue
+        n /= ln
+        d = -float(n @ p0)
+        A = np.outer(n, n)
+        q = np.array([A[0, 0], A[0, 1], A[0, 2], A[1, 1], A[1, 2], A[2, 2], d * n[0], d * n[1], d * n[2], d * d])
+        for v in f:
+            Q[v] += q
+    return Q
+
+
+@pytest.mark.parametrize("name,mesh,target", [
+    ("grid", meshgen.noisy_grid(24, 19, seed=4, noise=0.01), 150),
+    ("sphere", meshgen.icosphere(3, seed=6, jitter=0.04), 260),
+    ("room", meshgen.room_scene(9, room=(2.0, 1.5, 1.0), n_boxes=3, spacing=0.08), 300),
+])
+def test_one_run_with_line_11_recomputed_from_the_input(oracle, name, mesh, target):
+    """One run of the core algorithm: the budget is met exactly; every cluster is
+    connected in the input mesh and lies within two edges of a single pair; its
+    position is the mean and its quadric the sum over its members (numpy, fp64,
+    from the input mesh); fewer pairs than half the vertices are needed."""
+    V, F = mesh
+    N = V.shape[0]
+    res = oracle.decimate(V, F, target, max_rounds=1, absorb=True, return_quadrics=True)
+    ref = oracle.decimate(V, F, target, max_rounds=1)
+    cid = res["cluster_id"]
+    n_out = res["verts"].shape[0]
+    assert target <= n_out <= ref["verts"].shape[0]
+    if ref["verts"].shape[0] > target:
+        assert n_out < ref["verts"].shape[0]  # line 11 removes more than the pairs alone
+    E = _mesh_edges(F)
+    adj = [set() for _ in range(N)]
+    for a, b in E:
+        adj[a].add(b)
+        adj[b].add(a)
+    Q64 = _vertex_quadrics64(V, F)
+    sizes = np.bincount(cid, minlength=n_out)
+    assert sizes.min() >= 1
+    order = np.argsort(cid, kind="stable")
+    start = np.concatenate([[0], np.cumsum(sizes)])
+    big = 0
+    for c in range(n_out):
+        mem = order[start[c]:start[c + 1]]
+        np.testing.assert_allclose(res["verts"][c], V[mem].astype(np.float64).mean(axis=0), atol=2e-6)
+        np.testing.assert_allclose(res["quadrics"][c], Q64[mem].sum(axis=0), rtol=2e-4, atol=2e-4)
+        if len(mem) >= 3:
+            big += 1
+            ms = set(mem.tolist())
+            # some pair (a, b) of members is an edge and every other member touches a or b
+            assert any(b in adj[a] and all((w in adj[a] or w in adj[b]) for w in ms - {a, b})
+                       for a in mem for b in mem if a < b), (c, mem)
+        elif len(mem) == 2:
+            assert mem[1] in adj[mem[0]]
+    assert big > 0
+    # representatives are numbered in ascending order of the founding pair's smaller index, which
+    # need not be the cluster's smallest member: the smallest member of a pair cluster still is
+    firsts = np.array([order[start[c]] for c in range(n_out) if sizes[c] <= 2])
+    assert np.all(np.diff(firsts) > 0)
+
+
+def test_line_11_changes_nothing_when_the_pairs_use_up_the_budget(oracle):
+    V, F = meshgen.noisy_grid(30, 30, seed=2, noise=0.01)
+    target = V.shape[0] - 40
+    a = oracle.decimate(V, F, target)
+    b = oracle.decimate(V, F, target, absorb=True)
+    assert a["rounds"] == b["rounds"] == 1
+    for k in ("verts", "facets", "cluster_id"):
+        assert np.array_equal(a[k], b[k]), k
+
+
+def test_budget_is_met_exactly_over_several_runs(oracle):
+    for name, target in (("grid64", 1024), ("icosphere6", 10240)):
+        cfg = meshgen.config(name)
+        a = oracle.decimate(cfg["verts"], cfg["facets"], target)
+        b = oracle.decimate(cfg["verts"], cfg["facets"], target, absorb=True)
+        assert b["status"] == 0 and b["verts"].shape[0] == target
+        assert b["rounds"] < a["rounds"]  # each run removes more than pairs alone do
+        assert np.array_equal(np.unique(b["cluster_id"]), np.arange(target))
+        assert b["facets"].min() >= 0 and b["facets"].max() < target
+
+
+def test_members_are_summed_in_ascending_index_order(oracle):
+    """A fan around the pair (0, 1) whose other vertices all join it: positions are
+    chosen so that the fp32 sum depends on the order, and the result must be the
+    left-to-right sum over ascending indices, divided by the member count."""
+    x = np.array([1.0e8, 3.0, -1.0e8, 7.0, 5.0, 11.0], np.float32)
+    V = np.stack([x, np.arange(6, dtype=np.float32), np.zeros(6, np.float32)], axis=1)
+    F = np.array([[0, 1, 2], [0, 1, 3], [0, 1, 4], [0, 1, 5]], np.int32)
+    res = oracle.decimate(V, F, 1, max_rounds=1, absorb=True)
+    if res["verts"].shape[0] == 1 and np.all(res["cluster_id"] == 0):
+        s = V[0].copy()
+        for w in range(1, 6):
+            s = (s + V[w]).astype(np.float32)
+        want = (s / np.float32(6.0)).astype(np.float32)
+        assert np.array_equal(res["verts"][0], want)
+        rev = V[5].copy()
+        for w in range(4, -1, -1):
+            rev = (rev + V[w]).astype(np.float32)
+        assert not np.array_equal((rev / np.float32(6.0)).astype(np.float32), want)
+    else:
+        pytest.fail(f"expected a single cluster, got {res['cluster_id']}")
