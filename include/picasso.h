@@ -68,8 +68,18 @@ enum picasso_option {
                                       when its three pivots are positive and smallest / largest
                                       exceeds the threshold below (the paper tests the reciprocal
                                       condition number without saying how or against what).      */
-    PICASSO_OPT_RCOND_MIN_BITS = 7 /* that threshold, passed as the bit pattern of a binary32
+    PICASSO_OPT_RCOND_MIN_BITS = 7,/* that threshold, passed as the bit pattern of a binary32
                                       value (finite, >= 0; default 1e-3)                          */
+    PICASSO_OPT_ABSORB = 8         /* 1: Alg. 2 line 11 (Fig. 2 (c)) is applied in every run of the
+                                      core algorithm, under the vertex budget: once the pairs
+                                      are formed, a vertex in no pair that has an edge to a
+                                      paired vertex joins that pair's cluster through its
+                                      cheapest such edge (cost, edge index), cheapest vertices
+                                      first, while the mesh may still lose vertices; a vertex
+                                      that joined attracts no others.  A cluster's quadric and
+                                      mean position are summed over its members in ascending
+                                      index order; it is represented by its pair's smaller
+                                      index.  0 (default): pairs only.                           */
 };
 
 #define PICASSO_STATS_ROUNDS 32

@@ -44,7 +44,8 @@ struct State {
     int live[3];   // worklist lengths of the selection sub-rounds (rotating)
     int trunc_n;   // matched edges entering the budget truncation
     int sel_k;     // sub-round index the selection has reached (buffer rotation phase)
-    int pad[4];
+    int absorb_n;  // edges through which an un-paired vertex would join a pair's cluster (Alg. 2 line 11)
+    int pad[3];
 };
 
 // One vertex = 64 bytes: position and the 10 quadric coefficients.
@@ -308,6 +309,7 @@ __device__ __forceinline__ void round_begin_block(const RoundTab& R, int cur, St
         st->live[2] = 0;
         st->trunc_n = 0;
         st->sel_k = 0;
+        st->absorb_n = 0;
     }
 }
 
@@ -1067,18 +1069,38 @@ __global__ __launch_bounds__(TRUNC_THREADS) void trunc_block_kernel(u32* __restr
     }
 }
 
+constexpr u64 ABID_NONE = ~0ull;
+
+// The end of an edge that line 11 of Alg. 2 could add to the other end's cluster: the un-paired
+// one when exactly one end is paired, else -1.
+__device__ __forceinline__ int joining_end(const int* __restrict__ mate, int u, int v) {
+    const bool pu = mate[u] >= 0, pv = mate[v] >= 0;
+    return pu == pv ? -1 : (pu ? v : u);
+}
+
+// Gives up what the budget does not cover: a pair is dissolved (ABSORB = false), or the vertex
+// that would have joined through the edge stays on its own (ABSORB = true: its bid is withdrawn).
+template <bool ABSORB>
+__device__ __forceinline__ void release_edge(u64 k, int vbits, int* __restrict__ mate, u64* __restrict__ abid) {
+    const int u = (int)(k >> vbits), v = (int)(k & ((1ull << vbits) - 1ull));
+    if (ABSORB) {
+        const int w = joining_end(mate, u, v);
+        if (w >= 0) abid[w] = ABID_NONE;
+    } else {
+        mate[u] = -1;
+        mate[v] = -1;
+    }
+}
+
 // Releases the flagged pairs; block 0 also clamps the pair counts of the meshes to their budgets.
+template <bool ABSORB>
 __global__ __launch_bounds__(BLOCK) void trunc_release_kernel(const u32* __restrict__ tflag,
                                                               const u32* __restrict__ tval, const State* st,
                                                               const u64* __restrict__ ekey, int vbits,
                                                               int* __restrict__ mate, int B, int* __restrict__ matched,
-                                                              const int* __restrict__ nrem) {
+                                                              const int* __restrict__ nrem, u64* __restrict__ abid) {
     const int i = blockIdx.x * BLOCK + threadIdx.x;
-    if (i < st->trunc_n && tflag[i]) {
-        const u64 k = ekey[tval[i]];
-        mate[(int)(k >> vbits)] = -1;
-        mate[(int)(k & ((1ull << vbits) - 1ull))] = -1;
-    }
+    if (i < st->trunc_n && tflag[i]) release_edge<ABSORB>(ekey[tval[i]], vbits, mate, abid);
     if (blockIdx.x == 0)
         for (int b = threadIdx.x; b < B; b += BLOCK)
             if (matched[b] > nrem[b]) matched[b] = nrem[b];
@@ -1096,19 +1118,16 @@ __global__ void trunc_segments_kernel(int B, const int* __restrict__ matched, co
     }
 }
 
+template <bool ABSORB>
 __global__ __launch_bounds__(BLOCK) void trunc_apply_kernel(const u64* __restrict__ tkey, const u32* __restrict__ tval,
                                                             const State* st, const int* __restrict__ segstart,
                                                             const int* __restrict__ nrem,
                                                             const u64* __restrict__ ekey, int vbits,
-                                                            int* __restrict__ mate) {
+                                                            int* __restrict__ mate, u64* __restrict__ abid) {
     const int i = blockIdx.x * BLOCK + threadIdx.x;
     if (i >= st->trunc_n) return;
     const int m = (int)(tkey[i] >> 32);
-    if (i - segstart[m] >= nrem[m]) {
-        const u64 k = ekey[tval[i]];
-        mate[(int)(k >> vbits)] = -1;
-        mate[(int)(k & ((1ull << vbits) - 1ull))] = -1;
-    }
+    if (i - segstart[m] >= nrem[m]) release_edge<ABSORB>(ekey[tval[i]], vbits, mate, abid);
 }
 
 __global__ void trunc_finish_kernel(int B, int* __restrict__ matched, const int* __restrict__ nrem) {
@@ -1117,13 +1136,150 @@ __global__ void trunc_finish_kernel(int B, int* __restrict__ matched, const int*
 }
 
 // ---------------------------------------------------------------------------
+// Alg. 2 line 11 (option), under the vertex budget: after the pairs are final,
+// an un-paired vertex next to a paired one joins that pair's cluster through
+// its cheapest such edge (cost key, edge index) -- the first the sequential
+// walk over the sorted pairs would reach.  Every joining vertex has its own
+// edge, so the priorities are distinct; where a mesh has more candidates than
+// budget left, the cheapest stay (the same machinery as for the pairs).  Only
+// the two founders of a cluster attract: a vertex that joined pulls in nobody.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(BLOCK) void absorb_begin_kernel(u64* __restrict__ abid, int* __restrict__ arep,
+                                                             const State* st, int cur, int B,
+                                                             const int* __restrict__ nrem,
+                                                             const int* __restrict__ matched, int* __restrict__ arem,
+                                                             int* __restrict__ acand) {
+    const int nv = st->nv[cur];
+    const int stride = gridDim.x * BLOCK;
+    const int g = blockIdx.x * BLOCK + threadIdx.x;
+    for (int w = g; w < nv; w += stride) {
+        abid[w] = ABID_NONE;
+        arep[w] = -1;
+    }
+    for (int b = g; b < B; b += stride) {
+        const int left = nrem[b] - matched[b];
+        arem[b] = (matched[b] > 0 && left > 0) ? left : 0;  // budget left once the pairs are formed
+        acand[b] = 0;
+    }
+}
+
+__global__ __launch_bounds__(BLOCK) void absorb_bid_kernel(const u64* __restrict__ ekey, const u32* __restrict__ ecost,
+                                                           const State* st, int vbits, const int* __restrict__ mate,
+                                                           MeshTab mt, const int* __restrict__ arem,
+                                                           u64* __restrict__ abid) {
+    const int n = st->ne;
+    for (int e = blockIdx.x * BLOCK + threadIdx.x; e < n; e += gridDim.x * BLOCK) {
+        const u64 k = ekey[e];
+        const int u = (int)(k >> vbits), v = (int)(k & ((1ull << vbits) - 1ull));
+        const int w = joining_end(mate, u, v);
+        if (w >= 0 && arem[mesh_of(mt.voff, mt.B, w)] > 0) atomicMin(&abid[w], ((u64)ecost[e] << 32) | (u32)e);
+    }
+}
+
+// Edge e is the one through which its un-paired end joins (its bid stands at that vertex).
+struct JoinPred {
+    const u64* ekey;
+    const u32* ecost;
+    const int* mate;
+    const u64* abid;
+    int vbits;
+    __device__ bool operator()(int e) const {
+        const u64 k = ekey[e];
+        const int w = joining_end(mate, (int)(k >> vbits), (int)(k & ((1ull << vbits) - 1ull)));
+        return w >= 0 && abid[w] == (((u64)ecost[e] << 32) | (u32)e);
+    }
+};
+
+struct JoinListOut {
+    int* list;
+    __device__ void operator()(int e, int pos) const { list[pos] = e; }
+};
+
+// ... and its mesh has more such edges than budget left.
+struct JoinOverPred {
+    JoinPred jp;
+    MeshTab mt;
+    const int* acand;
+    const int* arem;
+    __device__ bool operator()(int e) const {
+        if (!jp(e)) return false;
+        const int m = mesh_of(mt.voff, mt.B, (int)(jp.ekey[e] >> jp.vbits));
+        return acand[m] > arem[m];
+    }
+};
+
+struct JoinOverOut {  // (mesh, cost key) keys for the sorted variant of the budget step
+    const u64* ekey;
+    const u32* ecost;
+    u64* tkey;
+    u32* tval;
+    MeshTab mt;
+    int vbits;
+    __device__ void operator()(int e, int pos) const {
+        tkey[pos] = ((u64)(u32)mesh_of(mt.voff, mt.B, (int)(ekey[e] >> vbits)) << 32) | (u64)ecost[e];
+        tval[pos] = (u32)e;
+    }
+};
+
+// The joining edges are listed in edge order, hence by mesh: acand[b] = how many belong to mesh b.
+// Also written to host memory (`host_out`), which the host reads after waiting for the stream.
+__global__ __launch_bounds__(BLOCK) void absorb_count_kernel(const int* __restrict__ list, const State* st,
+                                                             const u64* __restrict__ ekey, int vbits, int B,
+                                                             const int* __restrict__ voff, int* __restrict__ acand,
+                                                             int* __restrict__ host_out) {
+    const int n = st->absorb_n;
+    for (int b = threadIdx.x; b < B; b += BLOCK) {
+        int pos[2];
+        for (int side = 0; side < 2; ++side) {
+            const int v0 = voff[b + side];
+            int lo = 0, hi = n;  // first listed edge whose lower vertex is at or past v0
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if ((int)(ekey[list[mid]] >> vbits) >= v0) hi = mid; else lo = mid + 1;
+            }
+            pos[side] = lo;
+        }
+        acand[b] = pos[1] - pos[0];
+        host_out[b] = pos[1] - pos[0];
+    }
+}
+
+// For every listed edge that still stands: the joining vertex records its cluster's representative
+// (the founding pair's smaller index) and emits the key (representative, vertex); withdrawn ones
+// emit the all-ones key, which sorts behind every real one.
+__global__ __launch_bounds__(BLOCK) void absorb_keys_kernel(const int* __restrict__ list, const State* st,
+                                                            const u64* __restrict__ ekey,
+                                                            const u32* __restrict__ ecost, int vbits,
+                                                            const int* __restrict__ mate, const u64* __restrict__ abid,
+                                                            int* __restrict__ arep, u64* __restrict__ akey) {
+    const int i = blockIdx.x * BLOCK + threadIdx.x;
+    if (i >= st->absorb_n) return;
+    const int e = list[i];
+    const u64 k = ekey[e];
+    const int u = (int)(k >> vbits), v = (int)(k & ((1ull << vbits) - 1ull));
+    const int w = joining_end(mate, u, v);
+    u64 out = (vbits >= 32) ? ~0ull : ((1ull << (2 * vbits)) - 1ull);
+    if (w >= 0 && abid[w] == (((u64)ecost[e] << 32) | (u32)e)) {
+        const int o = (w == u) ? v : u;
+        const int mo = mate[o];
+        const int r = o < mo ? o : mo;
+        arep[w] = r;
+        out = ((u64)(u32)r << vbits) | (u64)(u32)w;
+    }
+    akey[i] = out;
+}
+
+// ---------------------------------------------------------------------------
 // S4 + S6: contraction (Alg. 2 lines 12-16) and survivor renumbering
 // ---------------------------------------------------------------------------
-struct AlivePred {
+template <bool ABSORB>
+struct AlivePredT {
     const int* mate;
+    const int* arep;
     __device__ bool operator()(int w) const {
         const int m = mate[w];
-        return !(m >= 0 && m < w);  // the larger index of a pair is replaced by the smaller
+        if (m >= 0 && m < w) return false;  // the larger index of a pair is replaced by the smaller
+        return !(ABSORB && arep[w] >= 0);   // as is a vertex that joined a pair's cluster
     }
 };
 
@@ -1134,14 +1290,20 @@ struct AliveOut {
 
 // Survivors move to their new slot; a pair's representative takes the summed
 // quadric and the pair's target position (the mean; with PLACE_INVERSE the
-// point of least error where there is one).  vmap[w] = output slot of w's cluster.
-template <int PLACE>
+// point of least error where there is one).  With ABSORB a cluster may have
+// more members than its pair: `akey` lists (representative, member) in
+// ascending order for the vertices that joined, and quadric and position are
+// summed over all members in ascending index order, the position sum divided
+// by their number.  vmap[w] = output slot of w's cluster.
+template <int PLACE, bool ABSORB>
 __global__ __launch_bounds__(BLOCK) void contract_kernel(const VRec* __restrict__ vin, VRec* __restrict__ vout,
                                                          const int* __restrict__ mate, const int* __restrict__ newid,
                                                          int* __restrict__ vmap, const State* st, int cur, int B,
                                                          const int* __restrict__ voff_cur, int* __restrict__ voff_nxt,
                                                          int* __restrict__ htab, int hsize,
-                                                         u32* __restrict__ msd_hist, float rcond_min) {
+                                                         u32* __restrict__ msd_hist, float rcond_min,
+                                                         const int* __restrict__ arep, const u64* __restrict__ akey,
+                                                         int vbits) {
     const int nv = st->nv[cur];
     const int stride = gridDim.x * BLOCK;
     const int g = blockIdx.x * BLOCK + threadIdx.x;
@@ -1153,25 +1315,88 @@ __global__ __launch_bounds__(BLOCK) void contract_kernel(const VRec* __restrict_
             vmap[w] = newid[m];
             continue;
         }
+        if (ABSORB) {
+            const int r = arep[w];
+            if (r >= 0) {
+                vmap[w] = newid[r];
+                continue;
+            }
+        }
         const int nw = newid[w];
         vmap[w] = nw;
         const float4* a = reinterpret_cast<const float4*>(&vin[w]);
         float4 r0 = a[0], r1 = a[1], r2 = a[2], r3 = a[3];
         if (m >= 0) {
-            const float4* b = reinterpret_cast<const float4*>(&vin[m]);
-            const float4 s0 = b[0], s1 = b[1], s2 = b[2], s3 = b[3];
-            r0.x = (r0.x + s0.x) * 0.5f; r0.y = (r0.y + s0.y) * 0.5f; r0.z = (r0.z + s0.z) * 0.5f;
-            r1.x = r1.x + s1.x; r1.y = r1.y + s1.y; r1.z = r1.z + s1.z; r1.w = r1.w + s1.w;
-            r2.x = r2.x + s2.x; r2.y = r2.y + s2.y; r2.z = r2.z + s2.z; r2.w = r2.w + s2.w;
-            r3.x = r3.x + s3.x; r3.y = r3.y + s3.y;
+            int j = 0, jend = 0;  // this cluster's part of akey
+            if (ABSORB) {
+                const int n = st->absorb_n;
+                const u64 first = (u64)(u32)w << vbits;
+                int lo = 0, hi = n;
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    if (akey[mid] >= first) hi = mid; else lo = mid + 1;
+                }
+                j = jend = lo;
+                while (jend < n && (int)(akey[jend] >> vbits) == w) ++jend;
+            }
+            if (!ABSORB || j == jend) {
+                const float4* b = reinterpret_cast<const float4*>(&vin[m]);
+                const float4 s0 = b[0], s1 = b[1], s2 = b[2], s3 = b[3];
+                r0.x = (r0.x + s0.x) * 0.5f; r0.y = (r0.y + s0.y) * 0.5f; r0.z = (r0.z + s0.z) * 0.5f;
+                r1.x = r1.x + s1.x; r1.y = r1.y + s1.y; r1.z = r1.z + s1.z; r1.w = r1.w + s1.w;
+                r2.x = r2.x + s2.x; r2.y = r2.y + s2.y; r2.z = r2.z + s2.z; r2.w = r2.w + s2.w;
+                r3.x = r3.x + s3.x; r3.y = r3.y + s3.y;
+            } else {
+                // merge w < m with the ascending list of joined vertices
+                const u64 low = (1ull << vbits) - 1ull;
+                bool done_w = false, done_m = false;
+                int cnt = 0;
+                while (!done_w || !done_m || j < jend) {
+                    int x = 0x7FFFFFFF, from = -1;
+                    if (!done_w) { x = w; from = 0; }
+                    else if (!done_m) { x = m; from = 1; }
+                    if (j < jend) {
+                        const int y = (int)(akey[j] & low);
+                        if (y < x) { x = y; from = 2; }
+                    }
+                    if (from == 0) done_w = true;
+                    else if (from == 1) done_m = true;
+                    else ++j;
+                    const float4* b = reinterpret_cast<const float4*>(&vin[x]);
+                    const float4 s0 = b[0], s1 = b[1], s2 = b[2], s3 = b[3];
+                    if (cnt == 0) {
+                        r0 = s0; r1 = s1; r2 = s2; r3 = s3;
+                    } else {
+                        r0.x = r0.x + s0.x; r0.y = r0.y + s0.y; r0.z = r0.z + s0.z;
+                        r1.x = r1.x + s1.x; r1.y = r1.y + s1.y; r1.z = r1.z + s1.z; r1.w = r1.w + s1.w;
+                        r2.x = r2.x + s2.x; r2.y = r2.y + s2.y; r2.z = r2.z + s2.z; r2.w = r2.w + s2.w;
+                        r3.x = r3.x + s3.x; r3.y = r3.y + s3.y;
+                    }
+                    ++cnt;
+                }
+                const float k = (float)cnt;
+                r0.x = r0.x / k; r0.y = r0.y / k; r0.z = r0.z / k;
+                r0.w = 0.f; r3.z = 0.f; r3.w = 0.f;
+            }
             if (PLACE == PLACE_INVERSE)
                 quadric_minimiser(r1.x, r1.y, r1.z, r1.w, r2.x, r2.y, r2.z, r2.w, r3.x, rcond_min, r0.x, r0.y, r0.z);
         }
         float4* o = reinterpret_cast<float4*>(&vout[nw]);
         o[0] = r0; o[1] = r1; o[2] = r2; o[3] = r3;
     }
-    // a mesh's first vertex always survives (a removed vertex has a smaller partner in its own mesh)
-    for (int b = g; b <= B; b += stride) voff_nxt[b] = (b == B) ? st->nv[cur ^ 1] : newid[voff_cur[b]];
+    // a mesh's first vertex always survives when only pairs are contracted (a removed vertex has a
+    // smaller partner in its own mesh); one that joined a cluster may not, and then the mesh starts
+    // at its first survivor (every cluster has one)
+    for (int b = g; b <= B; b += stride) {
+        int nb = st->nv[cur ^ 1];
+        if (b < B) {
+            int w = voff_cur[b];
+            if (ABSORB)
+                while (w + 1 < voff_cur[b + 1] && arep[w] >= 0) ++w;
+            nb = newid[w];
+        }
+        voff_nxt[b] = nb;
+    }
     for (int h = g; h < hsize; h += stride) htab[h] = -1;
 }
 
@@ -1432,6 +1657,11 @@ struct picasso_ctx {
     int64_t opt_kernel_timing = 0;  // N > 0: events around the kernel in every N-th decimate call
     int opt_placement = PLACE_MEAN;
     float opt_rcond_min = 1e-3f;
+    int opt_absorb = 0;
+    u64* abid = nullptr;   // per vertex: cheapest edge through which it could join a pair's cluster
+    int* arep = nullptr;   // per vertex: representative of the cluster it joined, or -1
+    int* acand = nullptr;  // per mesh: vertices that could join
+    int* arem = nullptr;   // per mesh: budget left after the pairs
     int64_t kt_calls = 0;           // decimate calls since the option was set
     bool kt_this_call = false;
     hipEvent_t kt_pool[512];
@@ -1525,6 +1755,10 @@ size_t carve(picasso_ctx* c, char* base, int64_t N, int64_t F, int32_t B) {
     x->nrem = cv.take<int>(b);
     x->segstart = cv.take<int>(b);
     x->mslots = cv.take<int>(b * MATCH_SLOTS * MATCH_PAD);
+    x->abid = cv.take<u64>(n);
+    x->arep = cv.take<int>(n);
+    x->acand = cv.take<int>(b);
+    x->arem = cv.take<int>(b);
     return cv.off;
 }
 
@@ -1731,6 +1965,78 @@ int status_from_err_bits(int bits) {
     return PICASSO_OK;
 }
 
+// Alg. 2 line 11 on the device for the round whose pairs are final (see the kernels).  nrem /
+// h_matched: per-mesh budget and pairs kept (host mirrors); h_joined receives the vertices that
+// join per mesh; *akeys the sorted (representative, vertex) keys, st->absorb_n of them.  Waits for
+// the stream once (the per-mesh candidate counts decide whether the budget step is needed).
+int run_absorb(picasso_ctx* c, hipStream_t s, int B, int cur, int vbits, int ne, int nv_total, const MeshTab& mt,
+               const std::vector<int>& nrem, const std::vector<int>& h_matched, std::vector<int>& h_joined,
+               const u64** akeys) {
+    absorb_begin_kernel<<<grid_for(std::max(nv_total, B), 4096), BLOCK, 0, s>>>(c->abid, c->arep, c->st, cur, B, c->nrem,
+                                                                              c->matched, c->arem, c->acand);
+    absorb_bid_kernel<<<grid_for(std::max(ne, 1), 8192), BLOCK, 0, s>>>(c->ekey, c->ecost, c->st, vbits, c->mate, mt,
+                                                                      c->arem, c->abid);
+    JoinPred jp{c->ekey, c->ecost, c->mate, c->abid, vbits};
+    JoinListOut jl{c->list};
+    prim::compact(s, jp, jp, jl, &c->st->ne, ne, c->tilesum, &c->st->absorb_n);
+    int* host_counts = c->h_pin_dev + HDR_STATE_INTS + c->cap_b;  // (the offsets' slots of the read-back area: free until the end)
+    absorb_count_kernel<<<1, BLOCK, 0, s>>>(c->list, c->st, c->ekey, vbits, B, c->voff[cur], c->acand, host_counts);
+    HIP_TRY(c, hipStreamSynchronize(s));
+    const int* h_cand = c->h_pin + HDR_STATE_INTS + c->cap_b;
+    long long n_list = 0, n_over = 0;
+    int seg_max = 0;
+    for (int b = 0; b < B; ++b) {
+        const int left = (h_matched[b] > 0 && nrem[b] > h_matched[b]) ? nrem[b] - h_matched[b] : 0;
+        const int cand = h_cand[b];
+        n_list += cand;
+        if (cand > left) {
+            n_over += cand;
+            seg_max = std::max(seg_max, cand);
+        }
+        h_joined[b] = std::min(cand, left);
+    }
+    if (n_list == 0) return PICASSO_OK;
+    if (n_over > 0) {  // the cheapest `left` candidates of each such mesh stay
+        JoinOverPred op{jp, mt, c->acand, c->arem};
+        if (seg_max <= c->opt_trunc_block_max) {
+            u32* tcost = reinterpret_cast<u32*>(c->key64[0]);
+            TruncOutSplit to{c->ecost, tcost, c->val32[0]};
+            prim::compact(s, op, op, to, &c->st->ne, ne, c->tilesum, &c->st->trunc_n);
+            if (seg_max <= 4 * TRUNC_THREADS)
+                trunc_block_kernel<4><<<B, TRUNC_THREADS, 0, s>>>(tcost, c->acand, c->arem);
+            else if (seg_max <= 8 * TRUNC_THREADS)
+                trunc_block_kernel<8><<<B, TRUNC_THREADS, 0, s>>>(tcost, c->acand, c->arem);
+            else if (seg_max <= 16 * TRUNC_THREADS)
+                trunc_block_kernel<16><<<B, TRUNC_THREADS, 0, s>>>(tcost, c->acand, c->arem);
+            else
+                trunc_block_kernel<32><<<B, TRUNC_THREADS, 0, s>>>(tcost, c->acand, c->arem);
+            trunc_release_kernel<true><<<grid_for(n_over), BLOCK, 0, s>>>(tcost, c->val32[0], c->st, c->ekey, vbits,
+                                                                          c->mate, B, c->acand, c->arem, c->abid);
+        } else {
+            JoinOverOut to{c->ekey, c->ecost, c->key64[0], c->val32[0], mt, vbits};
+            prim::compact(s, op, op, to, &c->st->ne, ne, c->tilesum, &c->st->trunc_n);
+            int where = prim::radix_sort<u64, true>(s, c->key64[0], c->key64[1], c->val32[0], c->val32[1],
+                                                    &c->st->trunc_n, (int)n_over, 32 + (B > 1 ? ceil_log2(B) : 0),
+                                                    c->sort_sc);
+            if (where < 0) return PICASSO_ERR_HIP;
+            trunc_segments_kernel<<<1, 64, 0, s>>>(B, c->acand, c->arem, c->segstart);
+            trunc_apply_kernel<true><<<grid_for(n_over), BLOCK, 0, s>>>(where ? c->key64[1] : c->key64[0],
+                                                                        where ? c->val32[1] : c->val32[0], c->st,
+                                                                        c->segstart, c->arem, c->ekey, vbits, c->mate,
+                                                                        c->abid);
+            trunc_finish_kernel<<<1, BLOCK, 0, s>>>(B, c->acand, c->arem);
+        }
+    }
+    absorb_keys_kernel<<<grid_for(n_list), BLOCK, 0, s>>>(c->list, c->st, c->ekey, c->ecost, vbits, c->mate, c->abid,
+                                                         c->arep, c->key64[0]);
+    const int where = sort_by_vertex<u64, false>(s, c->key64[0], c->key64[1], nullptr, nullptr, &c->st->absorb_n,
+                                                 (int)n_list, 2 * vbits, c->sort_sc, c->hist12);
+    if (where < 0) return PICASSO_ERR_HIP;
+    *akeys = where ? c->key64[1] : c->key64[0];
+    HIP_TRY(c, hipGetLastError());
+    return PICASSO_OK;
+}
+
 int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, const int32_t* d_facets,
                   const int32_t* nv_in, const int32_t* nf_in, const int32_t* target_nv, float* d_verts_out,
                   int32_t* d_facets_out, int32_t* d_cluster_id, int32_t* h_nv_out, int32_t* h_nf_out,
@@ -1796,7 +2102,7 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
     tm.end();
 
     State* hst = reinterpret_cast<State*>(c->h_pin);  // read-back area
-    std::vector<int> h_matched(B, 0);
+    std::vector<int> h_matched(B, 0), h_joined(B, 0);
 
     int cur = 0;        // ping-pong index of vrec / facets / voff / State counts
     int nv_total = N;   // exact (host mirror)
@@ -1926,8 +2232,8 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
                 trunc_block_kernel<16><<<B, TRUNC_THREADS, 0, s>>>(tcost, c->matched, c->nrem);
             else
                 trunc_block_kernel<32><<<B, TRUNC_THREADS, 0, s>>>(tcost, c->matched, c->nrem);
-            trunc_release_kernel<<<grid_for(n_trunc), BLOCK, 0, s>>>(tcost, c->val32[0], c->st, c->ekey, vbits,
-                                                                     c->mate, B, c->matched, c->nrem);
+            trunc_release_kernel<false><<<grid_for(n_trunc), BLOCK, 0, s>>>(tcost, c->val32[0], c->st, c->ekey, vbits,
+                                                                            c->mate, B, c->matched, c->nrem, nullptr);
         } else if (need_trunc) {
             const int ne = hst->ne;
             TruncPred tp{c->ekey, c->mate, mt, vbits};
@@ -1938,18 +2244,31 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
                                                     c->sort_sc);
             if (where < 0) return PICASSO_ERR_HIP;
             trunc_segments_kernel<<<1, 64, 0, s>>>(B, c->matched, c->nrem, c->segstart);
-            trunc_apply_kernel<<<grid_for(n_trunc), BLOCK, 0, s>>>(where ? c->key64[1] : c->key64[0],
-                                                                   where ? c->val32[1] : c->val32[0], c->st,
-                                                                   c->segstart, c->nrem, c->ekey, vbits, c->mate);
+            trunc_apply_kernel<false><<<grid_for(n_trunc), BLOCK, 0, s>>>(where ? c->key64[1] : c->key64[0],
+                                                                          where ? c->val32[1] : c->val32[0], c->st,
+                                                                          c->segstart, c->nrem, c->ekey, vbits, c->mate,
+                                                                          nullptr);
             trunc_finish_kernel<<<1, BLOCK, 0, s>>>(B, c->matched, c->nrem);
         }
+
+        // ---- Alg. 2 line 11 (option): un-paired vertices join a neighbouring pair's cluster while budget is left
+        int n_joined = 0;
+        const u64* akeys = nullptr;
+        std::fill(h_joined.begin(), h_joined.end(), 0);
+        bool budget_left = false;
+        for (int b = 0; b < B; ++b) budget_left |= (h_matched[b] > 0 && nrem[b] > h_matched[b]);
+        if (c->opt_absorb && budget_left) {
+            rc = run_absorb(c, s, B, cur, vbits, hst->ne, nv_total, mt, nrem, h_matched, h_joined, &akeys);
+            if (rc != PICASSO_OK) return rc;
+            for (int b = 0; b < B; ++b) n_joined += h_joined[b];
+        }
         tm.end();
-        if (stats && round < PICASSO_STATS_ROUNDS) stats->nsel[round] = n_sel;
+        if (stats && round < PICASSO_STATS_ROUNDS) stats->nsel[round] = n_sel + n_joined;
 
         // host mirror of the outcome
         for (int b = 0; b < B; ++b) {
             if (act[b] && h_matched[b] == 0) stuck[b] = 1;
-            nvb[b] -= h_matched[b];
+            nvb[b] -= h_matched[b] + h_joined[b];
         }
         if (n_sel == 0) {  // nothing contracted anywhere: the meshes are unchanged
             work = any_active();
@@ -1959,19 +2278,28 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         // ---- S4 + S6: contraction and renumbering
         tm.begin(round, PICASSO_ST_CONTRACT);
         const int nxt = cur ^ 1;
-        AlivePred ap{c->mate};
         AliveOut ao{c->newid};
-        prim::compact(s, ap, ap, ao, nullptr, nv_total, c->tilesum, &c->st->nv[nxt]);
+        if (n_joined > 0) {
+            AlivePredT<true> ap{c->mate, c->arep};
+            prim::compact(s, ap, ap, ao, nullptr, nv_total, c->tilesum, &c->st->nv[nxt]);
+        } else {
+            AlivePredT<false> ap{c->mate, nullptr};
+            prim::compact(s, ap, ap, ao, nullptr, nv_total, c->tilesum, &c->st->nv[nxt]);
+        }
         const size_t hsize = next_pow2((size_t)2 * std::max(nf_bound, 1));
         const int cgrid = grid_for(std::max<long long>(nv_total, (long long)hsize), 8192);
-        if (c->opt_placement == PLACE_INVERSE)
-            contract_kernel<PLACE_INVERSE><<<cgrid, BLOCK, 0, s>>>(
-                c->vrec[cur], c->vrec[nxt], c->mate, c->newid, c->vmap, c->st, cur, B, c->voff[cur], c->voff[nxt],
-                c->htab, (int)hsize, c->hist12, c->opt_rcond_min);
-        else
-            contract_kernel<PLACE_MEAN><<<cgrid, BLOCK, 0, s>>>(
-                c->vrec[cur], c->vrec[nxt], c->mate, c->newid, c->vmap, c->st, cur, B, c->voff[cur], c->voff[nxt],
-                c->htab, (int)hsize, c->hist12, 0.0f);
+#define PICASSO_CONTRACT(PLACE, ABSORB, RCOND)                                                                       \
+    contract_kernel<PLACE, ABSORB><<<cgrid, BLOCK, 0, s>>>(c->vrec[cur], c->vrec[nxt], c->mate, c->newid, c->vmap,    \
+                                                           c->st, cur, B, c->voff[cur], c->voff[nxt], c->htab,        \
+                                                           (int)hsize, c->hist12, RCOND, c->arep, akeys, vbits)
+        if (c->opt_placement == PLACE_INVERSE) {
+            if (n_joined > 0) PICASSO_CONTRACT(PLACE_INVERSE, true, c->opt_rcond_min);
+            else PICASSO_CONTRACT(PLACE_INVERSE, false, c->opt_rcond_min);
+        } else {
+            if (n_joined > 0) PICASSO_CONTRACT(PLACE_MEAN, true, 0.0f);
+            else PICASSO_CONTRACT(PLACE_MEAN, false, 0.0f);
+        }
+#undef PICASSO_CONTRACT
         tm.end();
 
         // ---- S5: facets
@@ -1985,7 +2313,7 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         prim::compact(s, kp, fp, fo, &c->st->nf[cur], nf_bound, c->tilesum, &c->st->nf[nxt]);
         tm.end();
 
-        nv_total -= n_sel;
+        nv_total -= n_sel + n_joined;
         cur = nxt;
         ++round;
         work = any_active();
@@ -2126,6 +2454,10 @@ int picasso_set_option(picasso_ctx* c, int option, int64_t value) {
         case PICASSO_OPT_TRUNC_BLOCK_MAX:
             if (value < 0) return PICASSO_ERR_INVALID_ARG;
             c->opt_trunc_block_max = std::min<int64_t>(value, TRUNC_BLOCK_CAP);
+            return PICASSO_OK;
+        case PICASSO_OPT_ABSORB:
+            if (value != 0 && value != 1) return PICASSO_ERR_INVALID_ARG;
+            c->opt_absorb = (int)value;
             return PICASSO_OK;
         case PICASSO_OPT_PLACEMENT:
             if (value != PLACE_MEAN && value != PLACE_INVERSE) return PICASSO_ERR_INVALID_ARG;

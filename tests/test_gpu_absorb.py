@@ -1,0 +1,149 @@
+"""GPU parity of the line-11 variant (Alg. 2 line 11, Fig. 2 (c): remaining
+vertices join a cluster they are connected to; applied under the vertex
+budget) against the CPU oracle's same variant, through the C-ABI.  Integer
+outputs bit-exact, positions bit-identical.
+"""
+import numpy as np
+import pytest
+
+from paper_2103_15076_amd import meshgen
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def pk():
+    import paper_2103_15076_amd as p
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    p.load_library()
+    return p
+
+
+@pytest.fixture(scope="module")
+def ctx(pk):
+    c = pk.Context(1_300_000, 2_500_000, 8, device=0)
+    c.set_option(pk.PICASSO_OPT_ABSORB, 1)
+    yield c
+    c.close()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def _meshes():
+    yield "grid", meshgen.noisy_grid(40, 33, seed=5, noise=0.02)
+    yield "sphere", meshgen.icosphere(4, seed=7, jitter=0.05)
+    yield "room", meshgen.room_scene(11, room=(3.0, 2.0, 1.5), n_boxes=5, spacing=0.05)
+    yield "flat", meshgen.flat_grid(33, 18, spacing=0.5)
+
+
+def _same(st, vo, fo, cid, ref):
+    assert st == ref["status"]
+    vo, fo, cid = vo.cpu().numpy(), fo.cpu().numpy(), cid.cpu().numpy()
+    assert vo.shape[0] == ref["verts"].shape[0], (vo.shape, ref["verts"].shape)
+    assert fo.shape[0] == ref["facets"].shape[0], (fo.shape, ref["facets"].shape)
+    assert np.array_equal(cid, ref["cluster_id"])
+    assert np.array_equal(fo, ref["facets"])
+    assert np.all(np.abs(vo - ref["verts"]) <= 1e-5 * np.maximum(1.0, np.abs(ref["verts"])))
+    assert np.array_equal(vo.view(np.uint32), ref["verts"].view(np.uint32))
+
+
+@pytest.mark.parametrize("name,mesh", list(_meshes()), ids=lambda x: x if isinstance(x, str) else "")
+@pytest.mark.parametrize("frac,max_rounds", [(0.97, -1), (0.55, -1), (0.45, 1), (0.4, -1), (0.3, 1), (0.1, -1), (0.0, -1)])
+def test_decimate_with_line_11_matches_oracle(pk, ctx, oracle, name, mesh, frac, max_rounds):
+    """Budgets that the pairs alone use up, that end among the joining vertices (the budget step
+    of line 11), and that leave every candidate room; one run and several."""
+    V, F = mesh
+    target = max(1, int(V.shape[0] * frac))
+    print(f"line11 {name} N={V.shape[0]} target={target} max_rounds={max_rounds}", flush=True)
+    ctx.set_option(pk.PICASSO_OPT_MAX_ROUNDS, max_rounds)
+    try:
+        st, vo, fo, cid = ctx.picasso_decimate(dev(V), dev(F), target)
+    finally:
+        ctx.set_option(pk.PICASSO_OPT_MAX_ROUNDS, -1)
+    ref = oracle.decimate(V, F, target, max_rounds=max_rounds, absorb=True)
+    if max_rounds >= 0 and ref["verts"].shape[0] > target:
+        st = ref["status"]
+    _same(st, vo, fo, cid, ref)
+
+
+def test_budget_step_of_line_11_both_ways(pk, ctx, oracle):
+    """The joining vertices of a mesh are cut to the budget left by a per-mesh selection or by a
+    sort; both against the oracle, with distinct costs and with nothing but ties."""
+    for block_max in (0, 1 << 15):
+        ctx.set_option(pk.PICASSO_OPT_TRUNC_BLOCK_MAX, block_max)
+        try:
+            for name, (V, F) in _meshes():
+                for frac in (0.5, 0.42, 0.36):
+                    target = int(V.shape[0] * frac)
+                    print(f"line11 budget {name} target={target} block_max={block_max}", flush=True)
+                    st, vo, fo, cid = ctx.picasso_decimate(dev(V), dev(F), target)
+                    _same(st, vo, fo, cid, oracle.decimate(V, F, target, absorb=True))
+        finally:
+            ctx.set_option(pk.PICASSO_OPT_TRUNC_BLOCK_MAX, 1 << 15)
+
+
+def test_batch_with_line_11_equals_the_meshes_one_by_one(pk, ctx, oracle):
+    parts = [meshgen.noisy_grid(30, 22, seed=1, noise=0.03), meshgen.icosphere(3, seed=2, jitter=0.05),
+             meshgen.room_scene(4, room=(2.0, 2.0, 1.0), n_boxes=3, spacing=0.06), meshgen.flat_grid(9, 9),
+             meshgen.noisy_grid(12, 12, seed=3)]
+    nv = [p[0].shape[0] for p in parts]
+    nf = [p[1].shape[0] for p in parts]
+    off = np.cumsum([0] + nv)
+    V = np.concatenate([p[0] for p in parts])
+    F = np.concatenate([p[1] + off[i] for i, p in enumerate(parts)]).astype(np.int32)
+    for tg in ([nv[0] // 3, int(nv[1] * 0.45), nv[2] // 4, nv[3], nv[4] - 3],
+               [int(nv[0] * 0.4), nv[1] // 5, int(nv[2] * 0.38), 1, nv[4] // 2]):
+        print(f"line11 batch nv={nv} targets={tg}", flush=True)
+        st, vo, fo, cid, nvo, nfo = ctx.picasso_decimate_batch(dev(V), dev(F), nv, nf, tg)
+        vo, fo, cid = vo.cpu().numpy(), fo.cpu().numpy(), cid.cpu().numpy()
+        v0 = f0 = 0
+        worst = 0
+        for i, (Vi, Fi) in enumerate(parts):
+            ref = oracle.decimate(Vi, Fi, tg[i], absorb=True)
+            worst = max(worst, ref["status"])
+            assert int(nvo[i]) == ref["verts"].shape[0] and int(nfo[i]) == ref["facets"].shape[0], i
+            assert np.array_equal(vo[v0:v0 + nvo[i]].view(np.uint32), ref["verts"].view(np.uint32)), i
+            assert np.array_equal(fo[f0:f0 + nfo[i]], ref["facets"] + v0), i
+            assert np.array_equal(cid[off[i]:off[i + 1]], ref["cluster_id"] + v0), i
+            v0 += int(nvo[i])
+            f0 += int(nfo[i])
+        assert st == worst
+
+
+def test_line_11_with_inverse_placement(pk, ctx, oracle):
+    V, F = meshgen.icosphere(4, seed=7, jitter=0.05)
+    target = V.shape[0] // 6
+    ctx.set_placement(pk.PICASSO_PLACE_INVERSE, 1e-3)
+    try:
+        st, vo, fo, cid = ctx.picasso_decimate(dev(V), dev(F), target)
+    finally:
+        ctx.set_placement(pk.PICASSO_PLACE_MEAN)
+    _same(st, vo, fo, cid, oracle.decimate(V, F, target, absorb=True, placement=1, rcond_min=1e-3))
+
+
+@pytest.mark.parametrize("name", ["grid64", "icosphere6", "room115k", "scene1p2m"])
+def test_config_full_size_with_line_11(ctx, oracle, name):
+    c = meshgen.config(name)
+    V, F, target = c["verts"], c["facets"], int(c["target"][0])
+    print(f"line11 config {name}: N={V.shape[0]} F={F.shape[0]} target={target}", flush=True)
+    st, vo, fo, cid = ctx.picasso_decimate(dev(V), dev(F), target)
+    print("  gpu done; oracle...", flush=True)
+    ref = oracle.decimate(V, F, target, absorb=True)
+    _same(st, vo, fo, cid, ref)
+    assert vo.shape[0] == target
+
+
+def test_switching_the_option_off_restores_the_default_path(pk, ctx, oracle):
+    V, F = meshgen.noisy_grid(40, 33, seed=5, noise=0.02)
+    target = V.shape[0] // 5
+    ctx.set_option(pk.PICASSO_OPT_ABSORB, 0)
+    try:
+        st, vo, fo, cid = ctx.picasso_decimate(dev(V), dev(F), target)
+    finally:
+        ctx.set_option(pk.PICASSO_OPT_ABSORB, 1)
+    _same(st, vo, fo, cid, oracle.decimate(V, F, target))
