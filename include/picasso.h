@@ -179,6 +179,19 @@ enum picasso_pool_mode {
     PICASSO_POOL_SUM = 3       /* y_c = sum_v x_v                                                   */
 };
 
+/* The two 1-D tensors of input-vertex length in Alg. 2's output list (Sec. 3,
+ * "Pooling and unpooling": clustering and degenerated-vertex information; the
+ * paper leaves their definition to code it does not print), derived from a
+ * decimate call's d_cluster_id: d_replace[v] = representative of v's cluster as
+ * an input vertex index (the cluster's smallest member), d_mapping[v] = output
+ * index of v if v is that representative, else -1, so that
+ * d_cluster_id[v] == d_mapping[d_replace[v]].  Device pointers of n_in ints
+ * each, owned by the caller.  Synchronises the stream; returns
+ * PICASSO_ERR_BAD_INDEX (outputs then unspecified) if an id lies outside
+ * [0, n_out).  n_out <= max_verts of the context. */
+int picasso_replace_mapping(picasso_ctx* ctx, void* stream, const int32_t* d_cluster_id, int32_t n_in, int32_t n_out,
+                            int32_t* d_replace, int32_t* d_mapping);
+
 /* Member lists of the clusters: d_offsets [n_out+1], d_members [n_in] (members of
  * cluster c = d_members[d_offsets[c] .. d_offsets[c+1]), ascending).  Built with a
  * stable radix sort of (cluster_id, vertex).  Synchronises the stream; returns

@@ -154,6 +154,18 @@ def decimate(verts, facets, target_nv, max_rounds=-1, return_quadrics=False, pla
     return res
 
 
+def replace_mapping(cluster_id, n_out):
+    """(replace[n_in], mapping[n_in]) of Alg. 2's output list, from cluster_id."""
+    cluster_id = _i32(cluster_id)
+    n_in = cluster_id.shape[0]
+    rep = np.zeros(n_in, np.int32)
+    mp = np.zeros(n_in, np.int32)
+    st = lib().picasso_oracle_replace_mapping(_p(cluster_id), n_in, int(n_out), _p(rep), _p(mp))
+    if st != 0:
+        raise ValueError(f"oracle status {st}")
+    return rep, mp
+
+
 def decimate_batch(verts, facets, nv_in, nf_in, target_nv):
     verts, facets = _f32(verts), _i32(facets).reshape(-1, 3)
     nv_in, nf_in, target_nv = _i32(nv_in), _i32(nf_in), _i32(target_nv)

@@ -601,6 +601,28 @@ int picasso_oracle_select_absorb(const int32_t* edges, const uint32_t* key, int3
     return n;
 }
 
+// The two 1-D tensors of input-vertex length that Alg. 2 returns beside the mesh
+// (Sec. 3, "Pooling and unpooling": the clustering and the degenerated-vertex
+// information), derived from cluster_id.  The paper defers their definition to
+// code it does not print; reading taken here: replace[v] = the representative of
+// v's cluster as an INPUT vertex index, the cluster's smallest member;
+// mapping[v] = the output index of v if v is that representative, -1 if v has
+// degenerated into another vertex.  So cluster_id[v] == mapping[replace[v]].
+int picasso_oracle_replace_mapping(const int32_t* cluster_id, int32_t n_in, int32_t n_out, int32_t* replace,
+                                   int32_t* mapping) {
+    if (!cluster_id || n_in < 1 || n_out < 1 || !replace || !mapping) return ERR_INVALID_ARG;
+    for (int v = 0; v < n_in; ++v)
+        if (cluster_id[v] < 0 || cluster_id[v] >= n_out) return ERR_BAD_INDEX;
+    std::vector<int32_t> first(n_out, -1);
+    for (int v = 0; v < n_in; ++v)
+        if (first[cluster_id[v]] < 0) first[cluster_id[v]] = v;
+    for (int v = 0; v < n_in; ++v) {
+        replace[v] = first[cluster_id[v]];
+        mapping[v] = (replace[v] == v) ? cluster_id[v] : -1;
+    }
+    return OK;
+}
+
 int picasso_oracle_decimate(const float* verts, int32_t N, const int32_t* facets, int32_t F, int32_t target_nv,
                             float* verts_out, int32_t* facets_out, int32_t* cluster_id, int32_t* nv_out,
                             int32_t* nf_out) {

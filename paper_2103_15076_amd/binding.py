@@ -39,7 +39,7 @@ EXPORTED_SYMBOLS = (
     "picasso_workspace_bytes", "picasso_create", "picasso_destroy", "picasso_set_option", "picasso_strerror",
     "picasso_last_hip_error", "picasso_decimate", "picasso_decimate_batch", "picasso_vertex_quadrics",
     "picasso_edge_costs", "picasso_radix_sort", "picasso_kernel_timing",
-    "picasso_device_copy", "picasso_bucket_sort", "picasso_cluster_csr", "picasso_pool_forward",
+    "picasso_device_copy", "picasso_bucket_sort", "picasso_cluster_csr", "picasso_replace_mapping", "picasso_pool_forward",
     "picasso_pool_backward", "picasso_unpool_forward", "picasso_unpool_backward",
 )
 
@@ -121,6 +121,8 @@ def load_library():
     lib.picasso_radix_sort.argtypes = [vp, vp, ctypes.c_int, vp, vp, i64, ctypes.c_int]
     lib.picasso_cluster_csr.restype = ctypes.c_int
     lib.picasso_cluster_csr.argtypes = [vp, vp, vp, i32, i32, vp, vp]
+    lib.picasso_replace_mapping.restype = ctypes.c_int
+    lib.picasso_replace_mapping.argtypes = [vp, vp, vp, i32, i32, vp, vp]
     lib.picasso_pool_forward.restype = ctypes.c_int
     lib.picasso_pool_forward.argtypes = [vp, vp, ctypes.c_int, vp, i32, i32, vp, vp, i32, vp, vp, vp]
     lib.picasso_pool_backward.restype = ctypes.c_int
@@ -311,6 +313,19 @@ class Context:
         return edges[: ne.value], cost[: ne.value]
 
     # -- pooling / unpooling over cluster_id ------------------------------------------------------
+
+    def picasso_replace_mapping(self, cluster_id, n_out, stream=None):
+        """Returns (replace int32[n_in], mapping int32[n_in]) device tensors."""
+        import torch
+        n_in = int(cluster_id.shape[0])
+        rep = torch.empty((n_in,), dtype=torch.int32, device=cluster_id.device)
+        mp = torch.empty((n_in,), dtype=torch.int32, device=cluster_id.device)
+        st = self._lib.picasso_replace_mapping(self._h, _stream_ptr(stream),
+                                               _dev_ptr(cluster_id, torch.int32, "cluster_id"), n_in, int(n_out),
+                                               _dev_ptr(rep, torch.int32, "replace"), _dev_ptr(mp, torch.int32, "mapping"))
+        if st != PICASSO_OK:
+            self._raise(st)
+        return rep, mp
 
     def picasso_cluster_csr(self, cluster_id, n_out, stream=None):
         """Returns (offsets int32[n_out+1], members int32[n_in]) device tensors."""

@@ -2634,6 +2634,24 @@ int picasso_cluster_csr(picasso_ctx* c, void* stream, const int32_t* d_cluster_i
     return (reinterpret_cast<State*>(c->h_pin)->err & 1) ? PICASSO_ERR_BAD_INDEX : PICASSO_OK;
 }
 
+int picasso_replace_mapping(picasso_ctx* c, void* stream, const int32_t* d_cluster_id, int32_t n_in, int32_t n_out,
+                            int32_t* d_replace, int32_t* d_mapping) {
+    if (!c || !d_cluster_id || n_in < 1 || n_out < 1 || !d_replace || !d_mapping) return PICASSO_ERR_INVALID_ARG;
+    if (n_out > c->max_verts) return PICASSO_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(c, hipSetDevice(c->device));
+    prim::fill_u32_kernel<<<1, BLOCK, 0, s>>>(reinterpret_cast<u32*>(&c->st->err), 1, 0u);
+    prim::fill_u32_kernel<<<grid_for(n_out), BLOCK, 0, s>>>(reinterpret_cast<u32*>(c->newid), n_out, 0x7FFFFFFFu);
+    pool::cluster_first_kernel<<<pool::grid_for(n_in), pool::BLOCK, 0, s>>>(d_cluster_id, n_in, n_out, c->newid,
+                                                                            &c->st->err);
+    pool::replace_mapping_kernel<<<pool::grid_for(n_in), pool::BLOCK, 0, s>>>(d_cluster_id, n_in, n_out, c->newid,
+                                                                              d_replace, d_mapping);
+    int rc = read_header(c, s);
+    if (rc != PICASSO_OK) return rc;
+    HIP_TRY(c, hipGetLastError());
+    return (reinterpret_cast<State*>(c->h_pin)->err & 1) ? PICASSO_ERR_BAD_INDEX : PICASSO_OK;
+}
+
 int picasso_pool_forward(picasso_ctx* c, void* stream, int mode, const float* d_x, int32_t n_in, int32_t C,
                          const int32_t* d_offsets, const int32_t* d_members, int32_t n_out, const float* d_weight,
                          float* d_y, int32_t* d_argmax) {

@@ -161,6 +161,33 @@ __global__ __launch_bounds__(BLOCK) void emit_cluster_pairs_kernel(const int* __
     val[v] = (uint32_t)v;
 }
 
+// The two per-input-vertex tensors of Alg. 2's output list from cluster_id: first[c] = smallest
+// member of cluster c (first pass, atomicMin: the result does not depend on order), then
+// replace[v] = first[cluster_id[v]] and mapping[v] = cluster_id[v] for that member, -1 otherwise.
+__global__ __launch_bounds__(BLOCK) void cluster_first_kernel(const int* __restrict__ cid, int n_in, int n_out,
+                                                              int* __restrict__ first, int* __restrict__ err) {
+    const int v = blockIdx.x * BLOCK + threadIdx.x;
+    if (v >= n_in) return;
+    const int c = cid[v];
+    if (c < 0 || c >= n_out) {
+        atomicOr(err, 1);
+        return;
+    }
+    atomicMin(&first[c], v);
+}
+
+__global__ __launch_bounds__(BLOCK) void replace_mapping_kernel(const int* __restrict__ cid, int n_in, int n_out,
+                                                                const int* __restrict__ first,
+                                                                int* __restrict__ replace, int* __restrict__ mapping) {
+    const int v = blockIdx.x * BLOCK + threadIdx.x;
+    if (v >= n_in) return;
+    const int c = cid[v];
+    if (c < 0 || c >= n_out) return;  // (flagged by the first pass; the call reports it)
+    const int r = first[c];
+    replace[v] = r;
+    mapping[v] = (r == v) ? c : -1;
+}
+
 inline int grid_for(long long n) { return (int)((n + BLOCK - 1) / BLOCK > 0 ? (n + BLOCK - 1) / BLOCK : 1); }
 
 template <int VEC>

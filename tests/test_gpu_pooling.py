@@ -158,3 +158,27 @@ def test_pooling_after_decimation_room_mesh(pk, ctx, oracle):
     Vp = np.concatenate([V, np.zeros((V.shape[0], 1), np.float32)], axis=1)      # 4 channels
     pos = ctx.picasso_pool_forward(pk.PICASSO_POOL_AVG, dev(Vp), off1, mem1).cpu().numpy()[:, :3]
     np.testing.assert_allclose(pos, vo1.cpu().numpy(), rtol=0, atol=2e-6)
+
+
+def test_replace_and_mapping_match_oracle(pk, oracle):
+    """The two per-input-vertex tensors of Alg. 2's output list, from the cluster_id of real
+    decimations (pairs only, and with line 11) and from an adversarial labelling; bit-exact."""
+    ctx = pk.Context(50_000, 100_000, 1, device=0)
+    try:
+        V, F = meshgen.icosphere(5, seed=3)
+        for absorb in (0, 1):
+            ctx.set_option(pk.PICASSO_OPT_ABSORB, absorb)
+            st, vo, fo, cid = ctx.picasso_decimate(dev(V), dev(F), V.shape[0] // 9)
+            rep, mp = ctx.picasso_replace_mapping(cid, int(vo.shape[0]))
+            r_ref, m_ref = oracle.replace_mapping(cid.cpu().numpy(), int(vo.shape[0]))
+            assert np.array_equal(rep.cpu().numpy(), r_ref) and np.array_equal(mp.cpu().numpy(), m_ref)
+        rng = np.random.default_rng(0)
+        for n_in, n_out in ((1, 1), (5, 5), (70_000, 3), (70_000, 50_000)):
+            lab = rng.integers(0, n_out, n_in).astype(np.int32)
+            rep, mp = ctx.picasso_replace_mapping(dev(lab), n_out)
+            r_ref, m_ref = oracle.replace_mapping(lab, n_out)
+            assert np.array_equal(rep.cpu().numpy(), r_ref) and np.array_equal(mp.cpu().numpy(), m_ref)
+        with pytest.raises(pk.PicassoError):
+            ctx.picasso_replace_mapping(dev(np.array([0, 7, 1], np.int32)), 3)
+    finally:
+        ctx.close()

@@ -465,3 +465,34 @@ def test_a_planted_mistake_would_be_caught(oracle):
     S = Q[u] + Q[v]
     no2 = np.array([_eval_q64(S[e], m[e]) - (S[e, 6:9] @ m[e]) for e in range(E.shape[0])])
     assert np.median(np.abs(no2 - cost)) > 1e-3
+
+
+# ----------------------------------------------------------------------------
+# replace / mapping (Alg. 2, output list; Sec. 3 "Pooling and unpooling")
+# ----------------------------------------------------------------------------
+
+def test_replace_and_mapping_hand_example(oracle):
+    """Seven input vertices in three clusters: the representative is the smallest
+    member; only representatives keep an output index."""
+    cid = np.array([0, 1, 0, 2, 1, 2, 2], np.int32)
+    rep, mp = oracle.replace_mapping(cid, 3)
+    assert rep.tolist() == [0, 1, 0, 3, 1, 3, 3]
+    assert mp.tolist() == [0, 1, -1, 2, -1, -1, -1]
+    with pytest.raises(ValueError):
+        oracle.replace_mapping(np.array([0, 3], np.int32), 3)
+
+
+@pytest.mark.parametrize("absorb", [False, True])
+def test_replace_and_mapping_invariants_on_a_decimation(oracle, absorb):
+    V, F = meshgen.icosphere(4, seed=3)
+    res = oracle.decimate(V, F, V.shape[0] // 7, absorb=absorb)
+    cid, n_out = res["cluster_id"], res["verts"].shape[0]
+    rep, mp = oracle.replace_mapping(cid, n_out)
+    assert np.array_equal(mp[rep], cid)                       # cluster_id = mapping o replace
+    assert np.array_equal(rep[rep], rep)                      # representatives represent themselves
+    assert np.all(rep <= np.arange(V.shape[0]))               # ... and are their cluster's smallest member
+    assert (mp >= 0).sum() == n_out and np.array_equal(np.sort(mp[mp >= 0]), np.arange(n_out))
+    assert np.array_equal(cid[rep], cid)
+    if not absorb:
+        # pairs only: output vertices are numbered in ascending order of their smallest member
+        assert np.all(np.diff(mp[mp >= 0]) == 1)
