@@ -126,8 +126,29 @@ def select_absorb(edge_list, key, n_verts, n_remove):
     return sel.astype(bool), via, n
 
 
+def tie_break(seed, i):
+    f = lib().picasso_oracle_tie_break
+    f.restype = ctypes.c_uint32
+    f.argtypes = [ctypes.c_uint64, ctypes.c_uint32]
+    return int(f(int(seed), int(i)))
+
+
+def select_shuffled(edge_list, key, n_verts, n_remove, seed, absorb=False):
+    """Alg. 2 lines 3-10 (and 11 with absorb) with equal keys visited in the order of tie_break(seed, index)."""
+    edge_list = _i32(edge_list)
+    key = np.ascontiguousarray(key, dtype=np.uint32)
+    sel = np.zeros(edge_list.shape[0], np.uint8)
+    via = np.full(int(n_verts), -1, np.int32)
+    f = lib().picasso_oracle_select_shuffled
+    f.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_uint64,
+                  ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
+    n = f(_p(edge_list), _p(key), edge_list.shape[0], int(n_verts), int(n_remove), int(seed), int(bool(absorb)),
+          _p(sel), _p(via))
+    return sel.astype(bool), via, n
+
+
 def decimate(verts, facets, target_nv, max_rounds=-1, return_quadrics=False, placement=PLACE_MEAN, rcond_min=0.0,
-             absorb=False):
+             absorb=False, shuffle_seed=0):
     """Returns dict(status, verts, facets, cluster_id, rounds[, quadrics])."""
     verts, facets = _f32(verts), _i32(facets).reshape(-1, 3)
     N, F = verts.shape[0], facets.shape[0]
@@ -136,11 +157,11 @@ def decimate(verts, facets, target_nv, max_rounds=-1, return_quadrics=False, pla
     cid = np.zeros(max(N, 1), np.int32)
     qo = np.zeros((max(N, 1), 10), np.float32)
     nv, nf, rounds = ctypes.c_int32(0), ctypes.c_int32(0), ctypes.c_int32(0)
-    if placement != PLACE_MEAN or absorb:
+    if placement != PLACE_MEAN or absorb or shuffle_seed:
         st = lib().picasso_oracle_decimate_opts(
             _p(verts), N, _p(facets), F, int(target_nv), int(max_rounds), int(placement), ctypes.c_float(rcond_min),
-            int(bool(absorb)), _p(vo), _p(fo), _p(cid), ctypes.byref(nv), ctypes.byref(nf), ctypes.byref(rounds),
-            _p(qo))
+            int(bool(absorb)), ctypes.c_uint64(int(shuffle_seed)), _p(vo), _p(fo), _p(cid), ctypes.byref(nv),
+            ctypes.byref(nf), ctypes.byref(rounds), _p(qo))
     else:
         st = lib().picasso_oracle_decimate_rounds(
             _p(verts), N, _p(facets), F, int(target_nv), int(max_rounds), _p(vo), _p(fo), _p(cid),

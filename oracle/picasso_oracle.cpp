@@ -57,6 +57,14 @@
 //    its founding pair's smaller index; its quadric and its mean position are
 //    summed over its members in ascending index order.
 //
+//  * shuffle_seed != 0: the shuffle the paper inserts into the sorting of the
+//    pairs (Sec. 3, footnote; Sec. 5, data augmentation) so that the decimated
+//    mesh varies between epochs.  The paper does not say how; reading: pairs of
+//    equal cost are visited in a seeded pseudo-random order instead of index
+//    order, i.e. the order is ascending (cost key, tie(seed, index)) with tie a
+//    bijection of the 32-bit integers; pairs of different cost keep their
+//    order, so the result stays a greedy clustering by quadric cost.
+//
 // Pins: see tests/test_oracle_*.py (closed forms, brute force, invariants,
 // hand-worked fixtures under tests/golden/).  The whole multi-round pipeline has
 // no printed worked example in the paper (its Fig. 2 carries no numbers):
@@ -154,7 +162,33 @@ struct Opts {
     int placement = 0;        // 0: mean of the pair; 1: -A^-1 b where A has full rank, else the mean
     float rcond_min = 0.0f;   // full rank iff rcond > rcond_min
     int absorb = 0;           // 1: Alg. 2 line 11 under the budget
+    uint64_t shuffle_seed = 0;  // != 0: equal costs in seeded pseudo-random order
 };
+
+// Seeded bijection of the 32-bit integers (every step is invertible: xor with a
+// constant, multiplication by an odd number, xor with a right shift of itself,
+// addition of a constant).  seed = 0 stands for "no shuffle": the identity.
+uint32_t tie_break(uint64_t seed, uint32_t i) {
+    if (seed == 0) return i;
+    uint32_t x = i ^ (uint32_t)seed;
+    x *= 0x9E3779B1u;
+    x ^= x >> 15;
+    x *= 0x85EBCA77u;
+    x ^= x >> 13;
+    x += (uint32_t)(seed >> 32);
+    return x;
+}
+
+// The order in which Alg. 2 line 3 leaves the pairs: ascending (cost key, tie).
+std::vector<int32_t> sorted_pairs(const std::vector<uint32_t>& key, uint64_t seed) {
+    std::vector<int32_t> order(key.size());
+    for (size_t i = 0; i < key.size(); ++i) order[i] = (int32_t)i;
+    std::sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+        if (key[a] != key[b]) return key[a] < key[b];
+        return tie_break(seed, (uint32_t)a) < tie_break(seed, (uint32_t)b);
+    });
+    return order;
+}
 
 // Minimiser of the quadric s = (A, b, c): the solution of A x = -b
 // (supplementary, Eq. "inverse_optimal").  A is a sum of plane quadrics n n^T,
@@ -253,11 +287,9 @@ uint32_t cost_key(float c) {
 // forms a new cluster iff neither end is in a cluster yet and fewer than
 // n_remove pairs have been formed.
 int greedy_pairs(const std::vector<std::pair<int32_t, int32_t>>& E, const std::vector<uint32_t>& key,
-                 int N, int64_t n_remove, std::vector<uint8_t>& selected) {
+                 int N, int64_t n_remove, std::vector<uint8_t>& selected, uint64_t seed = 0) {
     const int nE = (int)E.size();
-    std::vector<int32_t> order(nE);
-    for (int i = 0; i < nE; ++i) order[i] = i;
-    std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return key[a] < key[b]; });
+    const std::vector<int32_t> order = sorted_pairs(key, seed);
     std::vector<uint8_t> in_cluster(N, 0);
     selected.assign(nE, 0);
     int64_t n_r = 0;
@@ -279,11 +311,9 @@ int greedy_pairs(const std::vector<std::pair<int32_t, int32_t>>& E, const std::v
 // founder's cluster (-1 otherwise).  Returns the number of vertices added.
 int absorb_remaining(const std::vector<std::pair<int32_t, int32_t>>& E, const std::vector<uint32_t>& key, int N,
                      int64_t n_remove, int64_t n_r, const std::vector<uint8_t>& selected,
-                     std::vector<int32_t>& via) {
+                     std::vector<int32_t>& via, uint64_t seed = 0) {
     const int nE = (int)E.size();
-    std::vector<int32_t> order(nE);
-    for (int i = 0; i < nE; ++i) order[i] = i;
-    std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return key[a] < key[b]; });
+    const std::vector<int32_t> order = sorted_pairs(key, seed);
     std::vector<uint8_t> founder(N, 0), in_cluster(N, 0);
     for (int e = 0; e < nE; ++e)
         if (selected[e]) founder[E[e].first] = founder[E[e].second] = in_cluster[E[e].first] = in_cluster[E[e].second] = 1;
@@ -325,7 +355,7 @@ int one_round(Mesh& M, int target_nv, std::vector<int32_t>& label, const Opts& o
         key[e] = cost_key(pair_cost(M.Q[u], M.Q[v], &M.pos[3 * (size_t)u], &M.pos[3 * (size_t)v], o));
     }
     std::vector<uint8_t> sel;
-    int n_r = greedy_pairs(E, key, nv, (int64_t)nv - target_nv, sel);
+    int n_r = greedy_pairs(E, key, nv, (int64_t)nv - target_nv, sel, o.shuffle_seed);
     if (n_r == 0) return 0;
 
     // remap[w] = representative of w's cluster (the founding pair's smaller index)
@@ -336,7 +366,7 @@ int one_round(Mesh& M, int target_nv, std::vector<int32_t>& label, const Opts& o
     std::vector<std::vector<int32_t>> members;  // of the clusters line 11 enlarged, ascending; indexed by representative
     if (o.absorb) {
         std::vector<int32_t> via;
-        n_r += absorb_remaining(E, key, nv, (int64_t)nv - target_nv, n_r, sel, via);
+        n_r += absorb_remaining(E, key, nv, (int64_t)nv - target_nv, n_r, sel, via, o.shuffle_seed);
         std::vector<uint8_t> enlarged(nv, 0);
         for (int w = 0; w < nv; ++w) {
             if (via[w] < 0) continue;
@@ -561,7 +591,7 @@ int picasso_oracle_edge_costs_opts(const float* pos, const float* Q, const int32
 
 int picasso_oracle_decimate_opts(const float* verts, int32_t N, const int32_t* facets, int32_t F, int32_t target_nv,
                                  int32_t max_rounds, int32_t placement, float rcond_min, int32_t absorb,
-                                 float* verts_out, int32_t* facets_out, int32_t* cluster_id, int32_t* nv_out,
+                                 uint64_t shuffle_seed, float* verts_out, int32_t* facets_out, int32_t* cluster_id, int32_t* nv_out,
                                  int32_t* nf_out, int32_t* rounds_out, float* quadrics_out) {
     int st = check_inputs(verts, N, facets, F, target_nv);
     if (st < 0) return st;
@@ -571,6 +601,7 @@ int picasso_oracle_decimate_opts(const float* verts, int32_t N, const int32_t* f
     o.placement = placement;
     o.rcond_min = rcond_min;
     o.absorb = absorb;
+    o.shuffle_seed = shuffle_seed;
     Mesh M;
     std::vector<int32_t> label;
     st = decimate(verts, N, facets, F, target_nv, max_rounds, M, label, rounds_out, o);
@@ -587,6 +618,23 @@ int picasso_oracle_decimate_opts(const float* verts, int32_t N, const int32_t* f
 // Alg. 2 lines 3-11 on an explicit edge list with explicit keys: selected[e] = 1
 // for the pairs of lines 5-10, via[w] = index of the pair through which line 11
 // added vertex w to a cluster (-1: not added).  Returns pairs + added vertices.
+uint32_t picasso_oracle_tie_break(uint64_t seed, uint32_t i) { return tie_break(seed, i); }
+
+// The same with the shuffle: pairs of equal key in the order of tie_break(seed, index).
+int picasso_oracle_select_shuffled(const int32_t* edges, const uint32_t* key, int32_t E, int32_t N, int32_t n_remove,
+                                   uint64_t seed, int32_t absorb, uint8_t* selected, int32_t* via) {
+    std::vector<std::pair<int32_t, int32_t>> Ed(E);
+    for (int e = 0; e < E; ++e) Ed[e] = {edges[2 * e], edges[2 * e + 1]};
+    std::vector<uint32_t> k(key, key + E);
+    std::vector<uint8_t> sel;
+    int n = greedy_pairs(Ed, k, N, n_remove, sel, seed);
+    std::vector<int32_t> v(N, -1);
+    if (absorb) n += absorb_remaining(Ed, k, N, n_remove, n, sel, v, seed);
+    std::memcpy(selected, sel.data(), E);
+    std::memcpy(via, v.data(), sizeof(int32_t) * (size_t)N);
+    return n;
+}
+
 int picasso_oracle_select_absorb(const int32_t* edges, const uint32_t* key, int32_t E, int32_t N, int32_t n_remove,
                                  uint8_t* selected, int32_t* via) {
     std::vector<std::pair<int32_t, int32_t>> Ed(E);
