@@ -45,6 +45,8 @@ def main():
                     help="contraction target: the pair's mean (default, the headline path) or the point of "
                          "least quadric error with fallback to the mean")
     ap.add_argument("--rcond-min", type=float, default=1e-3, help="rank threshold of --placement inverse")
+    ap.add_argument("--shuffle-seed", type=int, default=0,
+                    help="seeded order among pairs of equal cost (the paper's augmentation shuffle); 0 = index order")
     ap.add_argument("--absorb", action="store_true",
                     help="apply Alg. 2 line 11 (un-paired vertices join a neighbouring pair's cluster, under the "
                          "budget); the headline path contracts pairs only")
@@ -98,13 +100,15 @@ def main():
     ctx = pk.Context(N, NF, B, device=0)
     stream = torch.cuda.current_stream()
     inverse = args.placement == "inverse"
-    if (inverse or args.absorb) and B > 1 and not args.no_cpu_baseline:
-        sys.exit("bench.py: --placement inverse / --absorb on a batch need --no-cpu-baseline (the oracle's batch "
-                 "entry point runs the default path)")
+    if (inverse or args.absorb or args.shuffle_seed) and B > 1 and not args.no_cpu_baseline:
+        sys.exit("bench.py: --placement inverse / --absorb / --shuffle-seed on a batch need --no-cpu-baseline (the "
+                 "oracle's batch entry point runs the default path)")
     if inverse:
         ctx.set_placement(pk.PICASSO_PLACE_INVERSE, args.rcond_min)
     if args.absorb:
         ctx.set_option(pk.PICASSO_OPT_ABSORB, 1)
+    if args.shuffle_seed:
+        ctx.set_option(pk.PICASSO_OPT_SHUFFLE_SEED, args.shuffle_seed)
 
     def step(stats=None):
         if B == 1:
@@ -173,7 +177,8 @@ def main():
             c0 = time.perf_counter()
             if B == 1:
                 ref = oracle.decimate(V, F, int(target[0]), placement=1 if inverse else 0,
-                                      rcond_min=args.rcond_min if inverse else 0.0, absorb=args.absorb)
+                                      rcond_min=args.rcond_min if inverse else 0.0, absorb=args.absorb,
+                                      shuffle_seed=args.shuffle_seed)
             else:
                 ref = oracle.decimate_batch(V, F, nv_in, nf_in, target)
             times.append(time.perf_counter() - c0)
@@ -232,7 +237,7 @@ def main():
                    "target_nv": int(np.sum(target)), "verts_out": nv_out, "facets_out": nf_out,
                    "rounds": sd["rounds"], "subrounds": sd["subrounds"], "edges": sd["ne"],
                    "placement": args.placement + (f" (rcond_min {args.rcond_min:g})" if inverse else ""),
-                   "line_11": bool(args.absorb)},
+                   "line_11": bool(args.absorb), "shuffle_seed": args.shuffle_seed},
         "paper_context": {"ms": 65.0, "gpu": "RTX 2080 Ti (paper's machine, its own 115,114-vertex mesh)"},
         "event_ms_per_step": round(ev_ms / args.steps, 4),
         "stage_ms": {k: round(sum(r[k] for r in sd["ms_stage"]), 4) for k in pk.binding.STAGE_NAMES},

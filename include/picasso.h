@@ -70,7 +70,7 @@ enum picasso_option {
                                       condition number without saying how or against what).      */
     PICASSO_OPT_RCOND_MIN_BITS = 7,/* that threshold, passed as the bit pattern of a binary32
                                       value (finite, >= 0; default 1e-3)                          */
-    PICASSO_OPT_ABSORB = 8         /* 1: Alg. 2 line 11 (Fig. 2 (c)) is applied in every run of the
+    PICASSO_OPT_ABSORB = 8,        /* 1: Alg. 2 line 11 (Fig. 2 (c)) is applied in every run of the
                                       core algorithm, under the vertex budget: once the pairs
                                       are formed, a vertex in no pair that has an edge to a
                                       paired vertex joins that pair's cluster through its
@@ -80,6 +80,14 @@ enum picasso_option {
                                       mean position are summed over its members in ascending
                                       index order; it is represented by its pair's smaller
                                       index.  0 (default): pairs only.                           */
+    PICASSO_OPT_SHUFFLE_SEED = 9   /* the shuffle inserted into the sorting of the pairs (Sec. 3,
+                                      footnote; Sec. 5, augmentation): with a seed != 0, pairs of
+                                      equal cost are taken in the order of a seeded bijection of
+                                      their 32-bit index (xor with the seed's low word, times
+                                      0x9E3779B1, x ^= x >> 15, times 0x85EBCA77, x ^= x >> 13,
+                                      plus the seed's high word) instead of index order; pairs
+                                      of different cost keep their order.  All 64 bits of the
+                                      value are the seed; 0 (default): index order.              */
 };
 
 #define PICASSO_STATS_ROUNDS 32

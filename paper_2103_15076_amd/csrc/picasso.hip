@@ -85,6 +85,58 @@ __device__ __forceinline__ u32 cost_key(float c) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// Order among pairs of equal cost (Alg. 2 line 3; Sec. 3, footnote on the shuffle inserted into the
+// sorting): by edge index, or with a seed by a seeded bijection of the 32-bit integers applied to
+// the edge index, so that flat regions are clustered differently from epoch to epoch.  Every step
+// of enc() is invertible (xor with a constant, multiplication by an odd number, xor with a right
+// shift of itself, addition of a constant); dec() undoes them in reverse.
+constexpr u32 inverse_mod_2_32(u32 a) {
+    u32 x = a;  // correct to 3 bits for odd a; each step doubles the number of correct bits
+    for (int i = 0; i < 5; ++i) x *= 2u - a * x;
+    return x;
+}
+constexpr u32 TIE_M1 = 0x9E3779B1u, TIE_M2 = 0x85EBCA77u;
+constexpr u32 TIE_M1_INV = inverse_mod_2_32(TIE_M1), TIE_M2_INV = inverse_mod_2_32(TIE_M2);
+static_assert(TIE_M1 * TIE_M1_INV == 1u && TIE_M2 * TIE_M2_INV == 1u, "modular inverses");
+
+struct TieBreak {
+    u32 on, s0, s1;
+    __device__ __forceinline__ u32 enc(u32 e) const {
+        if (!on) return e;
+        u32 x = e ^ s0;
+        x *= TIE_M1;
+        x ^= x >> 15;
+        x *= TIE_M2;
+        x ^= x >> 13;
+        return x + s1;
+    }
+    __device__ __forceinline__ u32 dec(u32 x) const {
+        if (!on) return x;
+        x -= s1;
+        x ^= x >> 13;
+        x ^= x >> 26;
+        x *= TIE_M2_INV;
+        x ^= x >> 15;
+        x ^= x >> 30;
+        x *= TIE_M1_INV;
+        return x ^ s0;
+    }
+    __device__ __forceinline__ u64 priority(u32 cost_key_, int e) const { return ((u64)cost_key_ << 32) | enc((u32)e); }
+};
+
+// The same for the kernels every round runs, where the choice is made at compile time so that
+// the path without shuffle carries no test of it.
+template <bool SHUFFLE>
+__device__ __forceinline__ u64 edge_priority(const TieBreak& tb, u32 cost_key_, int e) {
+    if constexpr (SHUFFLE) return tb.priority(cost_key_, e);
+    return ((u64)cost_key_ << 32) | (u32)e;
+}
+template <bool SHUFFLE>
+__device__ __forceinline__ u32 edge_of_priority(const TieBreak& tb, u64 p) {
+    if constexpr (SHUFFLE) return tb.dec((u32)p);
+    return (u32)p;
+}
+
 // ---------------------------------------------------------------------------
 // S0: vertex quadrics (supplementary: facet quadric Q=(nn^T, dn, d^2); vertex
 // quadric = sum over adjacent facets, here in ascending facet order)
@@ -503,7 +555,7 @@ __device__ __forceinline__ void bid_grouped(u64* __restrict__ vmin, bool on, int
 
 // Writes the distinct edges, their cost keys, and places each edge's first bid
 // (sub-round 0 of the selection) on both of its vertices.
-template <int PLACE>
+template <int PLACE, bool SHUFFLE>
 struct UniqueOutT {
     static constexpr bool WAVE_WIDE = true;
     const u64* keys;
@@ -515,6 +567,7 @@ struct UniqueOutT {
     int vbits;
     MeshTab mt;
     float rcond_min;
+    TieBreak tb;
     __device__ void wave(int i, bool in_range, bool flagged, int e) const {
         bool act = false;
         int u = 0;
@@ -528,7 +581,7 @@ struct UniqueOutT {
             ecost[e] = ck;
             act = mt.active[mesh_of(mt.voff, mt.B, u)] != 0;
             estate[e] = act ? 0 : 1;
-            p = ((u64)ck << 32) | (u32)e;
+            p = edge_priority<SHUFFLE>(tb, ck, e);
             if (act) atomicMin(&vmin0[v], p);
         }
         (void)in_range;
@@ -565,6 +618,7 @@ struct SelArgs {
     int vbits;
     int* host_img;     // pinned host memory, device view: the tail leaves [State][matched] there
     int publish_ints;  // for the host, which then needs no copy of its own before it looks
+    TieBreak tb;       // order among edges of equal cost
 };
 
 // Bids are read with device-scope atomic loads where the same kernel also
@@ -575,25 +629,25 @@ __device__ __forceinline__ u64 load_bid(const u64* p) {
     return *p;
 }
 
-template <bool COHERENT>
+template <bool COHERENT, bool SHUFFLE>
 __device__ __forceinline__ bool vertex_pairs_now(const u64* __restrict__ cur, const u64* __restrict__ ekey, int vbits,
-                                                 int x, u64 mx) {
+                                                 const TieBreak& tb, int x, u64 mx) {
     // The best live edge at x is accepted in this sub-round iff it is also the best at its other end.
     if (mx == VMIN_NONE) return false;  // no bid on x (cannot happen for an end of a live edge)
-    const u64 k = ekey[(u32)mx];
+    const u64 k = ekey[edge_of_priority<SHUFFLE>(tb, mx)];
     const int a = (int)(k >> vbits), b = (int)(k & ((1ull << vbits) - 1ull));
     const int other = (a == x) ? b : a;
     return load_bid<COHERENT>(&cur[other]) == mx;
 }
 
 // One edge of one sub-round.  Returns true if the edge stays live.
-template <bool COHERENT>
+template <bool COHERENT, bool SHUFFLE>
 __device__ __forceinline__ bool subround_edge(const SelArgs& A, const u64* __restrict__ cur, int k, int e, int& u,
                                               int& v, int& m, u64& p, bool& sel) {
     const u64 key = A.ekey[e];
     u = (int)(key >> A.vbits);
     v = (int)(key & ((1ull << A.vbits) - 1ull));
-    p = ((u64)A.ecost[e] << 32) | (u32)e;
+    p = edge_priority<SHUFFLE>(A.tb, A.ecost[e], e);
     m = mesh_of(A.mt.voff, A.mt.B, u);
     sel = false;
     if (k == 0 && !A.mt.active[m]) return false;
@@ -604,8 +658,8 @@ __device__ __forceinline__ bool subround_edge(const SelArgs& A, const u64* __res
         A.mate[v] = u;
         return false;
     }
-    return !(vertex_pairs_now<COHERENT>(cur, A.ekey, A.vbits, u, mu) ||
-             vertex_pairs_now<COHERENT>(cur, A.ekey, A.vbits, v, mv));
+    return !(vertex_pairs_now<COHERENT, SHUFFLE>(cur, A.ekey, A.vbits, A.tb, u, mu) ||
+             vertex_pairs_now<COHERENT, SHUFFLE>(cur, A.ekey, A.vbits, A.tb, v, mv));
 }
 
 // pairs formed, counted per mesh: one atomic per wave and mesh
@@ -640,6 +694,7 @@ __device__ __forceinline__ void count_pairs_lds(int* pairs, bool sel, int m) {
 // their state byte.  No worklist is kept here: appending survivors would need
 // one returning atomic per workgroup on a single counter, and thousands of
 // those queue up for longer than the sub-round itself takes.
+template <bool SHUFFLE>
 __global__ __launch_bounds__(BLOCK) void select_subround_kernel(SelArgs A, int k) {
     const u64* __restrict__ cur = A.vmin[k % 3];
     u64* __restrict__ nxt = A.vmin[(k + 1) % 3];
@@ -652,7 +707,7 @@ __global__ __launch_bounds__(BLOCK) void select_subround_kernel(SelArgs A, int k
         int u = 0, v = 0, m = 0;
         u64 p = 0;
         const bool live_in = (i < n) && A.estate[i] == 0;
-        if (live_in) alive = subround_edge<false>(A, cur, k, (int)i, u, v, m, p, sel);
+        if (live_in) alive = subround_edge<false, SHUFFLE>(A, cur, k, (int)i, u, v, m, p, sel);
         count_pairs(A, sel, m);
         if (alive) {
             atomicMin(&nxt[v], p);
@@ -672,7 +727,7 @@ __global__ __launch_bounds__(BLOCK) void select_subround_kernel(SelArgs A, int k
 // list 64 edges at a time exactly as above.
 constexpr int SPARSE_MIN_EDGES = 1 << 20;  // below this the one-lane-per-edge kernel is at its launch floor anyway
 
-template <int SPARSE_EDGES_PER_LANE>  // 4 while about a third of the edges are live, 16 later
+template <int SPARSE_EDGES_PER_LANE, bool SHUFFLE>  // 4 while about a third of the edges are live, 16 later
 __global__ __launch_bounds__(BLOCK) void select_subround_sparse_kernel(SelArgs A, int k) {
     static_assert(SPARSE_EDGES_PER_LANE == 4 || SPARSE_EDGES_PER_LANE == 16, "one 4- or 16-byte load per lane");
     constexpr int PER_WAVE = 64 * SPARSE_EDGES_PER_LANE;
@@ -724,7 +779,7 @@ __global__ __launch_bounds__(BLOCK) void select_subround_sparse_kernel(SelArgs A
             bool alive = false, sel = false;
             int u = 0, v = 0, m = 0;
             u64 p = 0;
-            if (has) alive = subround_edge<false>(A, cur, k, i, u, v, m, p, sel);
+            if (has) alive = subround_edge<false, SHUFFLE>(A, cur, k, i, u, v, m, p, sel);
             count_pairs(A, sel, m);
             if (alive) {
                 atomicMin(&nxt[v], p);
@@ -810,7 +865,7 @@ __global__ __launch_bounds__(TAIL_THREADS) void select_tail_kernel(SelArgs A) {
     for (int i = tid; i < n; i += TAIL_THREADS) {
         const int e = A.list[i];
         const u64 key = A.ekey[e];
-        L.prio[i] = ((u64)A.ecost[e] << 32) | (u32)e;
+        L.prio[i] = A.tb.priority(A.ecost[e], e);
         L.su[i] = (unsigned short)tail_slot(L.vkey, (int)(key >> A.vbits));
         L.sv[i] = (unsigned short)tail_slot(L.vkey, (int)(key & vmask));
         L.lst[0][i] = (unsigned short)i;
@@ -966,6 +1021,29 @@ struct TruncOutSplit {
     }
 };
 
+// With the seeded tie-break the sorted variant first orders the gathered pairs by their tie-break
+// values (TruncOutTie, 32-bit keys), then gives them their (mesh, cost key) keys in that order
+// (trunc_rekey_kernel) for the stable sort that follows.
+struct TruncOutTie {
+    TieBreak tb;
+    u64* tkey;
+    u32* tval;
+    __device__ void operator()(int e, int pos) const {
+        tkey[pos] = (u64)tb.enc((u32)e);
+        tval[pos] = (u32)e;
+    }
+};
+
+__global__ __launch_bounds__(BLOCK) void trunc_rekey_kernel(const u32* __restrict__ tval, const State* st,
+                                                            const u64* __restrict__ ekey,
+                                                            const u32* __restrict__ ecost, MeshTab mt, int vbits,
+                                                            u64* __restrict__ tkey) {
+    const int i = blockIdx.x * BLOCK + threadIdx.x;
+    if (i >= st->trunc_n) return;
+    const u32 e = tval[i];
+    tkey[i] = ((u64)(u32)mesh_of(mt.voff, mt.B, (int)(ekey[e] >> vbits)) << 32) | (u64)ecost[e];
+}
+
 // Budget for meshes with a moderate number of pairs: no sort.  The gathered pairs of a mesh are a
 // contiguous run in edge order; one workgroup per mesh reads the run's cost keys once, into
 // registers (item r * TRUNC_THREADS + t sits in register r of thread t), finds the cost key of the
@@ -989,8 +1067,9 @@ __device__ __forceinline__ u32 wave_sum_u32(u32 x) {
                  __builtin_amdgcn_readlane(v, 32) + __builtin_amdgcn_readlane(v, 48));
 }
 
-template <int R>
+template <int R, bool SHUFFLE>
 __global__ __launch_bounds__(TRUNC_THREADS) void trunc_block_kernel(u32* __restrict__ tcost,
+                                                                    const u32* __restrict__ tval, TieBreak tb,
                                                                     const int* __restrict__ matched,
                                                                     const int* __restrict__ nrem) {
     constexpr int NW = TRUNC_THREADS / 64;
@@ -1008,6 +1087,7 @@ __global__ __launch_bounds__(TRUNC_THREADS) void trunc_block_kernel(u32* __restr
         if (matched[j] > nrem[j]) before += (u32)matched[j];
     prim::wide_block_exclusive_scan<NW>(before, wsum, s0);
     tcost += s0;
+    tval += s0;
     if (n > R * TRUNC_THREADS) {  // not for this kernel (the host does not launch it so): release nothing
         for (int i = tid; i < n; i += TRUNC_THREADS) tcost[i] = 0u;
         return;
@@ -1044,6 +1124,41 @@ __global__ __launch_bounds__(TRUNC_THREADS) void trunc_block_kernel(u32* __restr
         kk = (u32)keep - (prefix ? count_le(prefix - 1u, 0) : 0u);
     }
     // kk = how many pairs with exactly the key `prefix` stay (the first kk in edge order)
+    if constexpr (SHUFFLE) {
+        // ... the first kk in the order of the seeded tie-break, which is distinct from pair to pair:
+        // the same search once more, on the tie-break values of the pairs with that key
+        u32 tie[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int i = r * TRUNC_THREADS + tid;
+            tie[r] = (i < n && key[r] == prefix) ? tb.enc(tval[i]) : 0xFFFFFFFFu;
+        }
+        auto count_tie_le = [&](u32 x, int slot) -> u32 {
+            u32 c = 0;
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                c += (r * TRUNC_THREADS + tid < n && key[r] == prefix && tie[r] <= x) ? 1u : 0u;
+            c = wave_sum_u32(c);
+            __syncthreads();  // (the sums of the count before this one have been read)
+            if (lane == 0) wsum2[slot][w] = c;
+            __syncthreads();
+            u32 tot = 0;
+#pragma unroll
+            for (int j = 0; j < NW; ++j) tot += wsum2[slot][j];
+            return tot;
+        };
+        u32 t2 = 0;
+        if (kk > 0)
+            for (int bit = 31; bit >= 0; --bit)
+                if (count_tie_le(t2 | ((1u << bit) - 1u), bit & 1) < kk) t2 |= 1u << bit;
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int i = r * TRUNC_THREADS + tid;
+            if (i < n) tcost[i] = (key[r] > prefix || (key[r] == prefix && (kk == 0 || tie[r] > t2))) ? 1u : 0u;
+        }
+        return;
+    }
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const bool eq = (r * TRUNC_THREADS + tid < n) && key[r] == prefix;
@@ -1166,13 +1281,13 @@ __global__ __launch_bounds__(BLOCK) void absorb_begin_kernel(u64* __restrict__ a
 __global__ __launch_bounds__(BLOCK) void absorb_bid_kernel(const u64* __restrict__ ekey, const u32* __restrict__ ecost,
                                                            const State* st, int vbits, const int* __restrict__ mate,
                                                            MeshTab mt, const int* __restrict__ arem,
-                                                           u64* __restrict__ abid) {
+                                                           u64* __restrict__ abid, TieBreak tb) {
     const int n = st->ne;
     for (int e = blockIdx.x * BLOCK + threadIdx.x; e < n; e += gridDim.x * BLOCK) {
         const u64 k = ekey[e];
         const int u = (int)(k >> vbits), v = (int)(k & ((1ull << vbits) - 1ull));
         const int w = joining_end(mate, u, v);
-        if (w >= 0 && arem[mesh_of(mt.voff, mt.B, w)] > 0) atomicMin(&abid[w], ((u64)ecost[e] << 32) | (u32)e);
+        if (w >= 0 && arem[mesh_of(mt.voff, mt.B, w)] > 0) atomicMin(&abid[w], tb.priority(ecost[e], e));
     }
 }
 
@@ -1183,10 +1298,11 @@ struct JoinPred {
     const int* mate;
     const u64* abid;
     int vbits;
+    TieBreak tb;
     __device__ bool operator()(int e) const {
         const u64 k = ekey[e];
         const int w = joining_end(mate, (int)(k >> vbits), (int)(k & ((1ull << vbits) - 1ull)));
-        return w >= 0 && abid[w] == (((u64)ecost[e] << 32) | (u32)e);
+        return w >= 0 && abid[w] == tb.priority(ecost[e], e);
     }
 };
 
@@ -1205,19 +1321,6 @@ struct JoinOverPred {
         if (!jp(e)) return false;
         const int m = mesh_of(mt.voff, mt.B, (int)(jp.ekey[e] >> jp.vbits));
         return acand[m] > arem[m];
-    }
-};
-
-struct JoinOverOut {  // (mesh, cost key) keys for the sorted variant of the budget step
-    const u64* ekey;
-    const u32* ecost;
-    u64* tkey;
-    u32* tval;
-    MeshTab mt;
-    int vbits;
-    __device__ void operator()(int e, int pos) const {
-        tkey[pos] = ((u64)(u32)mesh_of(mt.voff, mt.B, (int)(ekey[e] >> vbits)) << 32) | (u64)ecost[e];
-        tval[pos] = (u32)e;
     }
 };
 
@@ -1251,7 +1354,8 @@ __global__ __launch_bounds__(BLOCK) void absorb_keys_kernel(const int* __restric
                                                             const u64* __restrict__ ekey,
                                                             const u32* __restrict__ ecost, int vbits,
                                                             const int* __restrict__ mate, const u64* __restrict__ abid,
-                                                            int* __restrict__ arep, u64* __restrict__ akey) {
+                                                            int* __restrict__ arep, u64* __restrict__ akey,
+                                                            TieBreak tb) {
     const int i = blockIdx.x * BLOCK + threadIdx.x;
     if (i >= st->absorb_n) return;
     const int e = list[i];
@@ -1259,7 +1363,7 @@ __global__ __launch_bounds__(BLOCK) void absorb_keys_kernel(const int* __restric
     const int u = (int)(k >> vbits), v = (int)(k & ((1ull << vbits) - 1ull));
     const int w = joining_end(mate, u, v);
     u64 out = (vbits >= 32) ? ~0ull : ((1ull << (2 * vbits)) - 1ull);
-    if (w >= 0 && abid[w] == (((u64)ecost[e] << 32) | (u32)e)) {
+    if (w >= 0 && abid[w] == tb.priority(ecost[e], e)) {
         const int o = (w == u) ? v : u;
         const int mo = mate[o];
         const int r = o < mo ? o : mo;
@@ -1658,6 +1762,7 @@ struct picasso_ctx {
     int opt_placement = PLACE_MEAN;
     float opt_rcond_min = 1e-3f;
     int opt_absorb = 0;
+    uint64_t opt_shuffle_seed = 0;  // != 0: pairs of equal cost in the order of the seeded tie-break
     u64* abid = nullptr;   // per vertex: cheapest edge through which it could join a pair's cluster
     int* arep = nullptr;   // per vertex: representative of the cluster it joined, or -1
     int* acand = nullptr;  // per mesh: vertices that could join
@@ -1965,18 +2070,69 @@ int status_from_err_bits(int bits) {
     return PICASSO_OK;
 }
 
+// Budget step: among the edges `over` selects (the formed pairs, or the joining edges of line 11, of
+// the meshes that have more of them than they may use: counts[b] > budgets[b]) each mesh keeps its
+// budgets[b] first ones in ascending (cost key, tie-break) order; the others are released
+// (release_edge<ABSORB>) and counts[] is clamped.  n_over = sum of those meshes' counts, seg_max
+// their largest.
+template <bool ABSORB, class Over>
+int budget_step(picasso_ctx* c, hipStream_t s, Over over, int B, int ne, int vbits, const MeshTab& mt,
+                const TieBreak& tb, long long n_over, int seg_max, int* counts, int* budgets) {
+    if (seg_max <= c->opt_trunc_block_max) {
+        u32* tcost = reinterpret_cast<u32*>(c->key64[0]);
+        TruncOutSplit to{c->ecost, tcost, c->val32[0]};
+        prim::compact(s, over, over, to, &c->st->ne, ne, c->tilesum, &c->st->trunc_n);
+#define PICASSO_TRUNC_BLOCK(R)                                                                                       \
+    do {                                                                                                             \
+        if (tb.on) trunc_block_kernel<R, true><<<B, TRUNC_THREADS, 0, s>>>(tcost, c->val32[0], tb, counts, budgets);  \
+        else trunc_block_kernel<R, false><<<B, TRUNC_THREADS, 0, s>>>(tcost, c->val32[0], tb, counts, budgets);       \
+    } while (0)
+        if (seg_max <= 4 * TRUNC_THREADS) PICASSO_TRUNC_BLOCK(4);
+        else if (seg_max <= 8 * TRUNC_THREADS) PICASSO_TRUNC_BLOCK(8);
+        else if (seg_max <= 16 * TRUNC_THREADS) PICASSO_TRUNC_BLOCK(16);
+        else PICASSO_TRUNC_BLOCK(32);
+#undef PICASSO_TRUNC_BLOCK
+        trunc_release_kernel<ABSORB><<<grid_for(n_over), BLOCK, 0, s>>>(tcost, c->val32[0], c->st, c->ekey, vbits,
+                                                                        c->mate, B, counts, budgets, c->abid);
+        return PICASSO_OK;
+    }
+    u64* k0 = c->key64[0];
+    u64* k1 = c->key64[1];
+    u32* v0 = c->val32[0];
+    u32* v1 = c->val32[1];
+    if (tb.on) {
+        TruncOutTie to{tb, k0, v0};
+        prim::compact(s, over, over, to, &c->st->ne, ne, c->tilesum, &c->st->trunc_n);
+        const int w0 = prim::radix_sort<u64, true>(s, k0, k1, v0, v1, &c->st->trunc_n, (int)n_over, 32, c->sort_sc);
+        if (w0 < 0) return PICASSO_ERR_HIP;
+        if (w0) { std::swap(k0, k1); std::swap(v0, v1); }
+        trunc_rekey_kernel<<<grid_for(n_over), BLOCK, 0, s>>>(v0, c->st, c->ekey, c->ecost, mt, vbits, k0);
+    } else {
+        TruncOut to{c->ekey, c->ecost, k0, v0, mt, vbits};
+        prim::compact(s, over, over, to, &c->st->ne, ne, c->tilesum, &c->st->trunc_n);
+    }
+    const int where = prim::radix_sort<u64, true>(s, k0, k1, v0, v1, &c->st->trunc_n, (int)n_over,
+                                                  32 + (B > 1 ? ceil_log2(B) : 0), c->sort_sc);
+    if (where < 0) return PICASSO_ERR_HIP;
+    trunc_segments_kernel<<<1, 64, 0, s>>>(B, counts, budgets, c->segstart);
+    trunc_apply_kernel<ABSORB><<<grid_for(n_over), BLOCK, 0, s>>>(where ? k1 : k0, where ? v1 : v0, c->st, c->segstart,
+                                                                  budgets, c->ekey, vbits, c->mate, c->abid);
+    trunc_finish_kernel<<<1, BLOCK, 0, s>>>(B, counts, budgets);
+    return PICASSO_OK;
+}
+
 // Alg. 2 line 11 on the device for the round whose pairs are final (see the kernels).  nrem /
 // h_matched: per-mesh budget and pairs kept (host mirrors); h_joined receives the vertices that
 // join per mesh; *akeys the sorted (representative, vertex) keys, st->absorb_n of them.  Waits for
 // the stream once (the per-mesh candidate counts decide whether the budget step is needed).
 int run_absorb(picasso_ctx* c, hipStream_t s, int B, int cur, int vbits, int ne, int nv_total, const MeshTab& mt,
-               const std::vector<int>& nrem, const std::vector<int>& h_matched, std::vector<int>& h_joined,
+               const TieBreak& tb, const std::vector<int>& nrem, const std::vector<int>& h_matched, std::vector<int>& h_joined,
                const u64** akeys) {
     absorb_begin_kernel<<<grid_for(std::max(nv_total, B), 4096), BLOCK, 0, s>>>(c->abid, c->arep, c->st, cur, B, c->nrem,
                                                                               c->matched, c->arem, c->acand);
     absorb_bid_kernel<<<grid_for(std::max(ne, 1), 8192), BLOCK, 0, s>>>(c->ekey, c->ecost, c->st, vbits, c->mate, mt,
-                                                                      c->arem, c->abid);
-    JoinPred jp{c->ekey, c->ecost, c->mate, c->abid, vbits};
+                                                                      c->arem, c->abid, tb);
+    JoinPred jp{c->ekey, c->ecost, c->mate, c->abid, vbits, tb};
     JoinListOut jl{c->list};
     prim::compact(s, jp, jp, jl, &c->st->ne, ne, c->tilesum, &c->st->absorb_n);
     int* host_counts = c->h_pin_dev + HDR_STATE_INTS + c->cap_b;  // (the offsets' slots of the read-back area: free until the end)
@@ -1998,37 +2154,11 @@ int run_absorb(picasso_ctx* c, hipStream_t s, int B, int cur, int vbits, int ne,
     if (n_list == 0) return PICASSO_OK;
     if (n_over > 0) {  // the cheapest `left` candidates of each such mesh stay
         JoinOverPred op{jp, mt, c->acand, c->arem};
-        if (seg_max <= c->opt_trunc_block_max) {
-            u32* tcost = reinterpret_cast<u32*>(c->key64[0]);
-            TruncOutSplit to{c->ecost, tcost, c->val32[0]};
-            prim::compact(s, op, op, to, &c->st->ne, ne, c->tilesum, &c->st->trunc_n);
-            if (seg_max <= 4 * TRUNC_THREADS)
-                trunc_block_kernel<4><<<B, TRUNC_THREADS, 0, s>>>(tcost, c->acand, c->arem);
-            else if (seg_max <= 8 * TRUNC_THREADS)
-                trunc_block_kernel<8><<<B, TRUNC_THREADS, 0, s>>>(tcost, c->acand, c->arem);
-            else if (seg_max <= 16 * TRUNC_THREADS)
-                trunc_block_kernel<16><<<B, TRUNC_THREADS, 0, s>>>(tcost, c->acand, c->arem);
-            else
-                trunc_block_kernel<32><<<B, TRUNC_THREADS, 0, s>>>(tcost, c->acand, c->arem);
-            trunc_release_kernel<true><<<grid_for(n_over), BLOCK, 0, s>>>(tcost, c->val32[0], c->st, c->ekey, vbits,
-                                                                          c->mate, B, c->acand, c->arem, c->abid);
-        } else {
-            JoinOverOut to{c->ekey, c->ecost, c->key64[0], c->val32[0], mt, vbits};
-            prim::compact(s, op, op, to, &c->st->ne, ne, c->tilesum, &c->st->trunc_n);
-            int where = prim::radix_sort<u64, true>(s, c->key64[0], c->key64[1], c->val32[0], c->val32[1],
-                                                    &c->st->trunc_n, (int)n_over, 32 + (B > 1 ? ceil_log2(B) : 0),
-                                                    c->sort_sc);
-            if (where < 0) return PICASSO_ERR_HIP;
-            trunc_segments_kernel<<<1, 64, 0, s>>>(B, c->acand, c->arem, c->segstart);
-            trunc_apply_kernel<true><<<grid_for(n_over), BLOCK, 0, s>>>(where ? c->key64[1] : c->key64[0],
-                                                                        where ? c->val32[1] : c->val32[0], c->st,
-                                                                        c->segstart, c->arem, c->ekey, vbits, c->mate,
-                                                                        c->abid);
-            trunc_finish_kernel<<<1, BLOCK, 0, s>>>(B, c->acand, c->arem);
-        }
+        const int rc = budget_step<true>(c, s, op, B, ne, vbits, mt, tb, n_over, seg_max, c->acand, c->arem);
+        if (rc != PICASSO_OK) return rc;
     }
     absorb_keys_kernel<<<grid_for(n_list), BLOCK, 0, s>>>(c->list, c->st, c->ekey, c->ecost, vbits, c->mate, c->abid,
-                                                         c->arep, c->key64[0]);
+                                                         c->arep, c->key64[0], tb);
     const int where = sort_by_vertex<u64, false>(s, c->key64[0], c->key64[1], nullptr, nullptr, &c->st->absorb_n,
                                                  (int)n_list, 2 * vbits, c->sort_sc, c->hist12);
     if (where < 0) return PICASSO_ERR_HIP;
@@ -2103,6 +2233,7 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
 
     State* hst = reinterpret_cast<State*>(c->h_pin);  // read-back area
     std::vector<int> h_matched(B, 0), h_joined(B, 0);
+    const TieBreak tb{c->opt_shuffle_seed != 0 ? 1u : 0u, (u32)c->opt_shuffle_seed, (u32)(c->opt_shuffle_seed >> 32)};
 
     int cur = 0;        // ping-pong index of vrec / facets / voff / State counts
     int nv_total = N;   // exact (host mirror)
@@ -2124,14 +2255,20 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         }
         const u64 sentinel = (vbits >= 32) ? ~0ull : ((1ull << (2 * vbits)) - 1ull);
         UniquePred up{skeys, sentinel};
+#define PICASSO_UNIQUE(PLACE, SHUFFLE, RCOND)                                                                       \
+    do {                                                                                                             \
+        UniqueOutT<PLACE, SHUFFLE> uo{skeys, c->ekey, c->ecost, c->vrec[cur], c->vmin[0], c->estate, vbits, mt,       \
+                                      RCOND, tb};                                                                    \
+        prim::compact_scatter(s, up, uo, &c->st->nh, H, c->tilesum, &c->st->ne);                                     \
+    } while (0)
         if (c->opt_placement == PLACE_INVERSE) {
-            UniqueOutT<PLACE_INVERSE> uo{skeys, c->ekey, c->ecost, c->vrec[cur], c->vmin[0], c->estate, vbits, mt,
-                                         c->opt_rcond_min};
-            prim::compact_scatter(s, up, uo, &c->st->nh, H, c->tilesum, &c->st->ne);
+            if (tb.on) PICASSO_UNIQUE(PLACE_INVERSE, true, c->opt_rcond_min);
+            else PICASSO_UNIQUE(PLACE_INVERSE, false, c->opt_rcond_min);
         } else {
-            UniqueOutT<PLACE_MEAN> uo{skeys, c->ekey, c->ecost, c->vrec[cur], c->vmin[0], c->estate, vbits, mt, 0.0f};
-            prim::compact_scatter(s, up, uo, &c->st->nh, H, c->tilesum, &c->st->ne);
+            if (tb.on) PICASSO_UNIQUE(PLACE_MEAN, true, 0.0f);
+            else PICASSO_UNIQUE(PLACE_MEAN, false, 0.0f);
         }
+#undef PICASSO_UNIQUE
         tm.end();
 
         // ---- S3: selection sub-rounds
@@ -2148,6 +2285,7 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         sa.vbits = vbits;
         sa.host_img = c->h_pin_dev;
         sa.publish_ints = HDR_STATE_INTS + B;
+        sa.tb = tb;
         int sel_k = 0;
         // Grid-wide sub-rounds while many edges are live (the live count falls about 3x per
         // sub-round), then the live edges are gathered and one workgroup finishes; the host
@@ -2166,12 +2304,17 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
             for (long long l = live_est; l > TAIL_MAX; ++wide) l = l * 10 / decay_x10[std::min(wide, 5)];
             wide = std::min<int>(wide, (int)std::max<int64_t>(1, c->opt_subround_batch));
             for (int j = 0; j < wide; ++j) {
-                if (sel_k + j == 1 && ne_bound >= SPARSE_MIN_EDGES)
-                    select_subround_sparse_kernel<4><<<(ne_bound + BLOCK * 4 - 1) / (BLOCK * 4), BLOCK, 0, s>>>(sa, sel_k + j);
-                else if (sel_k + j > 1 && ne_bound >= SPARSE_MIN_EDGES)
-                    select_subround_sparse_kernel<16><<<(ne_bound + BLOCK * 16 - 1) / (BLOCK * 16), BLOCK, 0, s>>>(sa, sel_k + j);
-                else
-                    select_subround_kernel<<<grid_for(ne_bound, 1 << 16), BLOCK, 0, s>>>(sa, sel_k + j);
+                const int g4 = (ne_bound + BLOCK * 4 - 1) / (BLOCK * 4), g16 = (ne_bound + BLOCK * 16 - 1) / (BLOCK * 16);
+                if (sel_k + j == 1 && ne_bound >= SPARSE_MIN_EDGES) {
+                    if (tb.on) select_subround_sparse_kernel<4, true><<<g4, BLOCK, 0, s>>>(sa, sel_k + j);
+                    else select_subround_sparse_kernel<4, false><<<g4, BLOCK, 0, s>>>(sa, sel_k + j);
+                } else if (sel_k + j > 1 && ne_bound >= SPARSE_MIN_EDGES) {
+                    if (tb.on) select_subround_sparse_kernel<16, true><<<g16, BLOCK, 0, s>>>(sa, sel_k + j);
+                    else select_subround_sparse_kernel<16, false><<<g16, BLOCK, 0, s>>>(sa, sel_k + j);
+                } else {
+                    if (tb.on) select_subround_kernel<true><<<grid_for(ne_bound, 1 << 16), BLOCK, 0, s>>>(sa, sel_k + j);
+                    else select_subround_kernel<false><<<grid_for(ne_bound, 1 << 16), BLOCK, 0, s>>>(sa, sel_k + j);
+                }
             }
             sel_k += wide;
             LivePred lp{c->estate};
@@ -2218,37 +2361,10 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
             }
             n_sel += h_matched[b];
         }
-        if (need_trunc && seg_max <= c->opt_trunc_block_max) {
-            const int ne = hst->ne;
+        if (need_trunc) {
             TruncPred tp{c->ekey, c->mate, mt, vbits};
-            u32* tcost = reinterpret_cast<u32*>(c->key64[0]);
-            TruncOutSplit to{c->ecost, tcost, c->val32[0]};
-            prim::compact(s, tp, tp, to, nullptr, ne, c->tilesum, &c->st->trunc_n);
-            if (seg_max <= 4 * TRUNC_THREADS)
-                trunc_block_kernel<4><<<B, TRUNC_THREADS, 0, s>>>(tcost, c->matched, c->nrem);
-            else if (seg_max <= 8 * TRUNC_THREADS)
-                trunc_block_kernel<8><<<B, TRUNC_THREADS, 0, s>>>(tcost, c->matched, c->nrem);
-            else if (seg_max <= 16 * TRUNC_THREADS)
-                trunc_block_kernel<16><<<B, TRUNC_THREADS, 0, s>>>(tcost, c->matched, c->nrem);
-            else
-                trunc_block_kernel<32><<<B, TRUNC_THREADS, 0, s>>>(tcost, c->matched, c->nrem);
-            trunc_release_kernel<false><<<grid_for(n_trunc), BLOCK, 0, s>>>(tcost, c->val32[0], c->st, c->ekey, vbits,
-                                                                            c->mate, B, c->matched, c->nrem, nullptr);
-        } else if (need_trunc) {
-            const int ne = hst->ne;
-            TruncPred tp{c->ekey, c->mate, mt, vbits};
-            TruncOut to{c->ekey, c->ecost, c->key64[0], c->val32[0], mt, vbits};
-            prim::compact(s, tp, tp, to, nullptr, ne, c->tilesum, &c->st->trunc_n);
-            int where = prim::radix_sort<u64, true>(s, c->key64[0], c->key64[1], c->val32[0], c->val32[1],
-                                                    &c->st->trunc_n, (int)n_trunc, 32 + (B > 1 ? ceil_log2(B) : 0),
-                                                    c->sort_sc);
-            if (where < 0) return PICASSO_ERR_HIP;
-            trunc_segments_kernel<<<1, 64, 0, s>>>(B, c->matched, c->nrem, c->segstart);
-            trunc_apply_kernel<false><<<grid_for(n_trunc), BLOCK, 0, s>>>(where ? c->key64[1] : c->key64[0],
-                                                                          where ? c->val32[1] : c->val32[0], c->st,
-                                                                          c->segstart, c->nrem, c->ekey, vbits, c->mate,
-                                                                          nullptr);
-            trunc_finish_kernel<<<1, BLOCK, 0, s>>>(B, c->matched, c->nrem);
+            rc = budget_step<false>(c, s, tp, B, hst->ne, vbits, mt, tb, n_trunc, seg_max, c->matched, c->nrem);
+            if (rc != PICASSO_OK) return rc;
         }
 
         // ---- Alg. 2 line 11 (option): un-paired vertices join a neighbouring pair's cluster while budget is left
@@ -2258,7 +2374,7 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         bool budget_left = false;
         for (int b = 0; b < B; ++b) budget_left |= (h_matched[b] > 0 && nrem[b] > h_matched[b]);
         if (c->opt_absorb && budget_left) {
-            rc = run_absorb(c, s, B, cur, vbits, hst->ne, nv_total, mt, nrem, h_matched, h_joined, &akeys);
+            rc = run_absorb(c, s, B, cur, vbits, hst->ne, nv_total, mt, tb, nrem, h_matched, h_joined, &akeys);
             if (rc != PICASSO_OK) return rc;
             for (int b = 0; b < B; ++b) n_joined += h_joined[b];
         }
@@ -2455,6 +2571,9 @@ int picasso_set_option(picasso_ctx* c, int option, int64_t value) {
             if (value < 0) return PICASSO_ERR_INVALID_ARG;
             c->opt_trunc_block_max = std::min<int64_t>(value, TRUNC_BLOCK_CAP);
             return PICASSO_OK;
+        case PICASSO_OPT_SHUFFLE_SEED:
+            c->opt_shuffle_seed = (uint64_t)value;
+            return PICASSO_OK;
         case PICASSO_OPT_ABSORB:
             if (value != 0 && value != 1) return PICASSO_ERR_INVALID_ARG;
             c->opt_absorb = (int)value;
@@ -2593,11 +2712,12 @@ int picasso_edge_costs(picasso_ctx* c, void* stream, const float* d_verts, int32
     const u64 sentinel = (vbits >= 32) ? ~0ull : ((1ull << (2 * vbits)) - 1ull);
     UniquePred up{skeys, sentinel};
     if (c->opt_placement == PLACE_INVERSE) {
-        UniqueOutT<PLACE_INVERSE> uo{skeys, c->ekey, c->ecost, c->vrec[0], c->vmin[0], c->estate, vbits, mt,
-                                     c->opt_rcond_min};
+        UniqueOutT<PLACE_INVERSE, false> uo{skeys, c->ekey, c->ecost, c->vrec[0], c->vmin[0], c->estate, vbits, mt,
+                                            c->opt_rcond_min, TieBreak{0u, 0u, 0u}};
         prim::compact_scatter(s, up, uo, &c->st->nh, H, c->tilesum, &c->st->ne);
     } else {
-        UniqueOutT<PLACE_MEAN> uo{skeys, c->ekey, c->ecost, c->vrec[0], c->vmin[0], c->estate, vbits, mt, 0.0f};
+        UniqueOutT<PLACE_MEAN, false> uo{skeys, c->ekey, c->ecost, c->vrec[0], c->vmin[0], c->estate, vbits, mt, 0.0f,
+                                         TieBreak{0u, 0u, 0u}};
         prim::compact_scatter(s, up, uo, &c->st->nh, H, c->tilesum, &c->st->ne);
     }
     export_edges_kernel<<<grid_for(std::max(H, 1)), BLOCK, 0, s>>>(c->ekey, c->ecost, c->st, vbits, d_edges_out,
