@@ -13,7 +13,8 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRCS = [os.path.join(_HERE, "picasso_oracle.cpp"), os.path.join(_HERE, "picasso_pool_oracle.cpp")]
+_SRCS = [os.path.join(_HERE, "picasso_oracle.cpp"), os.path.join(_HERE, "picasso_pool_oracle.cpp"),
+         os.path.join(_HERE, "picasso_conv_oracle.cpp")]
 _LIB = os.path.join(_HERE, "libpicasso_oracle.so")
 _lib = None
 
@@ -255,3 +256,81 @@ def unpool_backward(gx, cluster_id, n_out):
     if st != 0:
         raise ValueError(f"oracle status {st}")
     return gy
+
+
+# ---- mesh convolutions, depth-wise (Sec. 4 "Mesh Convolution"; supplementary, backward propagations); fp64 results
+
+
+def _check(st):
+    if st != 0:
+        raise ValueError(f"oracle status {st}")
+
+
+def facet_geometry(verts, facets):
+    """(normals float64[F,3], areas float64[F])."""
+    verts, facets = _f32(verts), _i32(facets).reshape(-1, 3)
+    F = facets.shape[0]
+    n, a = np.zeros((F, 3)), np.zeros(F)
+    _check(lib().picasso_oracle_facet_geometry(_p(verts), verts.shape[0], _p(facets), F, _p(n), _p(a)))
+    return n, a
+
+
+def facet_levels(areas, foff=None, alpha=1, beta=1):
+    areas = np.ascontiguousarray(areas, np.float64)
+    foff = _i32([0, areas.shape[0]] if foff is None else foff)
+    lev = np.zeros(areas.shape[0], np.int32)
+    _check(lib().picasso_oracle_facet_levels(_p(areas), foff.shape[0] - 1, _p(foff), int(alpha), int(beta), _p(lev)))
+    return lev
+
+
+def fuzzy(normals, mu, inv_var):
+    normals = np.ascontiguousarray(normals, np.float64)
+    mu, inv_var = _f32(mu), _f32(inv_var)
+    T = mu.shape[0]
+    pi = np.zeros((normals.shape[0], T))
+    _check(lib().picasso_oracle_fuzzy(_p(normals), normals.shape[0], _p(mu), _p(inv_var), T, _p(pi)))
+    return pi
+
+
+def v2f_forward(x, facets, level, w):
+    x, facets, level, w = _f32(x), _i32(facets).reshape(-1, 3), _i32(level), _f32(w)
+    N, C = x.shape
+    y = np.zeros((facets.shape[0], C))
+    _check(lib().picasso_oracle_v2f_forward(_p(x), N, C, _p(facets), facets.shape[0], _p(level), _p(w), _p(y)))
+    return y
+
+
+def v2f_backward(gy, x, facets, level, w):
+    gy, x, facets, level, w = _f32(gy), _f32(x), _i32(facets).reshape(-1, 3), _i32(level), _f32(w)
+    N, C = x.shape
+    gx, gw = np.zeros((N, C)), np.zeros((3, C))
+    _check(lib().picasso_oracle_v2f_backward(_p(gy), _p(x), N, C, _p(facets), facets.shape[0], _p(level), _p(w),
+                                             _p(gx), _p(gw)))
+    return gx, gw
+
+
+def f2v_forward(y, pi, w, facets, n_verts):
+    y, pi, w, facets = _f32(y), _f32(pi), _f32(w), _i32(facets).reshape(-1, 3)
+    F, C = y.shape
+    T = pi.shape[1]
+    x = np.zeros((int(n_verts), C))
+    _check(lib().picasso_oracle_f2v_forward(_p(y), F, C, _p(pi), T, _p(w), _p(facets), int(n_verts), _p(x)))
+    return x
+
+
+def f2v_backward(gx, y, pi, w, facets):
+    gx, y, pi, w, facets = _f32(gx), _f32(y), _f32(pi), _f32(w), _i32(facets).reshape(-1, 3)
+    F, C = y.shape
+    T = pi.shape[1]
+    gy, gw, gpi = np.zeros((F, C)), np.zeros((T, C)), np.zeros((F, T))
+    _check(lib().picasso_oracle_f2v_backward(_p(gx), _p(y), F, C, _p(pi), T, _p(w), _p(facets), gx.shape[0], _p(gy),
+                                             _p(gw), _p(gpi)))
+    return gy, gw, gpi
+
+
+def vertex_corner_csr(facets, n_verts):
+    facets = _i32(facets).reshape(-1, 3)
+    off = np.zeros(int(n_verts) + 1, np.int32)
+    cor = np.zeros(max(1, 3 * facets.shape[0]), np.int32)
+    _check(lib().picasso_oracle_vertex_corner_csr(_p(facets), facets.shape[0], int(n_verts), _p(off), _p(cor)))
+    return off, cor[: 3 * facets.shape[0]]
