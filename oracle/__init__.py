@@ -267,16 +267,16 @@ def _check(st):
 
 
 def facet_geometry(verts, facets):
-    """(normals float64[F,3], areas float64[F])."""
+    """(normals float32[F,3], areas float32[F])."""
     verts, facets = _f32(verts), _i32(facets).reshape(-1, 3)
     F = facets.shape[0]
-    n, a = np.zeros((F, 3)), np.zeros(F)
+    n, a = np.zeros((F, 3), np.float32), np.zeros(F, np.float32)
     _check(lib().picasso_oracle_facet_geometry(_p(verts), verts.shape[0], _p(facets), F, _p(n), _p(a)))
     return n, a
 
 
 def facet_levels(areas, foff=None, alpha=1, beta=1):
-    areas = np.ascontiguousarray(areas, np.float64)
+    areas = _f32(areas)
     foff = _i32([0, areas.shape[0]] if foff is None else foff)
     lev = np.zeros(areas.shape[0], np.int32)
     _check(lib().picasso_oracle_facet_levels(_p(areas), foff.shape[0] - 1, _p(foff), int(alpha), int(beta), _p(lev)))
@@ -284,7 +284,7 @@ def facet_levels(areas, foff=None, alpha=1, beta=1):
 
 
 def fuzzy(normals, mu, inv_var):
-    normals = np.ascontiguousarray(normals, np.float64)
+    normals = _f32(normals)
     mu, inv_var = _f32(mu), _f32(inv_var)
     T = mu.shape[0]
     pi = np.zeros((normals.shape[0], T))

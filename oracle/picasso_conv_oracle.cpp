@@ -62,38 +62,44 @@ int check_facets(const int32_t* facets, int32_t F, int32_t N) {
 extern "C" {
 
 // Unit normal and area of every facet (Sec. 4, first paragraph); a facet of zero
-// area gets the zero normal.
-int picasso_oracle_facet_geometry(const float* verts, int32_t N, const int32_t* facets, int32_t F, double* normals,
-                                  double* areas) {
+// area gets the zero normal.  The area decides an integer (the level below), so
+// this is computed in binary32, every operation rounded once, in the order
+// written -- the precision and order the kernel uses.
+int picasso_oracle_facet_geometry(const float* verts, int32_t N, const int32_t* facets, int32_t F, float* normals,
+                                  float* areas) {
     if (!verts || !facets || !normals || !areas) return ERR_INVALID_ARG;
     if (check_facets(facets, F, N) != OK) return ERR_BAD_INDEX;
     for (int f = 0; f < F; ++f) {
         const float* p0 = verts + 3 * (size_t)facets[3 * f];
         const float* p1 = verts + 3 * (size_t)facets[3 * f + 1];
         const float* p2 = verts + 3 * (size_t)facets[3 * f + 2];
-        const double a[3] = {(double)p1[0] - p0[0], (double)p1[1] - p0[1], (double)p1[2] - p0[2]};
-        const double b[3] = {(double)p2[0] - p0[0], (double)p2[1] - p0[1], (double)p2[2] - p0[2]};
-        const double n[3] = {a[1] * b[2] - a[2] * b[1], a[2] * b[0] - a[0] * b[2], a[0] * b[1] - a[1] * b[0]};
-        const double len = std::sqrt(n[0] * n[0] + n[1] * n[1] + n[2] * n[2]);
-        areas[f] = 0.5 * len;
-        for (int k = 0; k < 3; ++k) normals[3 * (size_t)f + k] = len > 0.0 ? n[k] / len : 0.0;
+        const float ax = p1[0] - p0[0], ay = p1[1] - p0[1], az = p1[2] - p0[2];
+        const float bx = p2[0] - p0[0], by = p2[1] - p0[1], bz = p2[2] - p0[2];
+        const float nx = ay * bz - az * by;
+        const float ny = az * bx - ax * bz;
+        const float nz = ax * by - ay * bx;
+        const float len = std::sqrt((nx * nx + ny * ny) + nz * nz);
+        areas[f] = 0.5f * len;
+        normals[3 * (size_t)f] = len > 0.0f ? nx / len : 0.0f;
+        normals[3 * (size_t)f + 1] = len > 0.0f ? ny / len : 0.0f;
+        normals[3 * (size_t)f + 2] = len > 0.0f ? nz / len : 0.0f;
     }
     return OK;
 }
 
 // Eq. "interpolate_num": level k of every facet from its area; foff[B+1] = facet
-// offsets of the meshes of a batch (A_min, A_max are per mesh).
-int picasso_oracle_facet_levels(const double* areas, int32_t B, const int32_t* foff, int32_t alpha, int32_t beta,
+// offsets of the meshes of a batch (A_min, A_max are per mesh).  binary32 as above.
+int picasso_oracle_facet_levels(const float* areas, int32_t B, const int32_t* foff, int32_t alpha, int32_t beta,
                                 int32_t* level) {
     if (!areas || !foff || !level || B < 1 || alpha < 0 || beta < 1) return ERR_INVALID_ARG;
     for (int b = 0; b < B; ++b) {
-        double amin = INFINITY, amax = -INFINITY;
+        float amin = INFINITY, amax = -INFINITY;
         for (int f = foff[b]; f < foff[b + 1]; ++f) {
-            amin = std::fmin(amin, areas[f]);
-            amax = std::fmax(amax, areas[f]);
+            if (areas[f] < amin) amin = areas[f];
+            if (areas[f] > amax) amax = areas[f];
         }
         for (int f = foff[b]; f < foff[b + 1]; ++f) {
-            const double ratio = amax > amin ? (areas[f] - amin) / (amax - amin) : 0.0;
+            const float ratio = amax > amin ? (areas[f] - amin) / (amax - amin) : 0.0f;
             level[f] = (int)std::floor(ratio) * alpha + beta;
         }
     }
@@ -102,7 +108,7 @@ int picasso_oracle_facet_levels(const double* areas, int32_t B, const int32_t* f
 
 // Fuzzy coefficients pi[F,T] of the facets from their normals (Sec. 4.2, the two
 // equations for z_it and pi_it).
-int picasso_oracle_fuzzy(const double* normals, int32_t F, const float* mu, const float* inv_var, int32_t T,
+int picasso_oracle_fuzzy(const float* normals, int32_t F, const float* mu, const float* inv_var, int32_t T,
                          double* pi) {
     if (!normals || !mu || !inv_var || !pi || T < 1) return ERR_INVALID_ARG;
     std::vector<double> e(T);
@@ -111,7 +117,7 @@ int picasso_oracle_fuzzy(const double* normals, int32_t F, const float* mu, cons
         for (int t = 0; t < T; ++t) {
             double z = 0.0;
             for (int k = 0; k < 3; ++k) {
-                const double d = normals[3 * (size_t)f + k] - (double)mu[3 * t + k];
+                const double d = (double)normals[3 * (size_t)f + k] - (double)mu[3 * t + k];
                 z += d * d * (double)inv_var[t];
             }
             e[t] = std::exp(-z);

@@ -156,11 +156,11 @@ def test_facet_geometry_levels_and_fuzzy_coefficients(oracle):
     Vs, Fs = meshgen.icosphere(2, seed=3)
     ns, _ = oracle.facet_geometry(Vs, Fs)
     pi = oracle.fuzzy(ns, mu, inv_var)
-    z = ((ns[:, None, :] - mu[None].astype(float)) ** 2).sum(-1) * inv_var[None].astype(float)
+    z = ((ns.astype(float)[:, None, :] - mu[None].astype(float)) ** 2).sum(-1) * inv_var[None].astype(float)
     np.testing.assert_allclose(pi, softmax(-z, axis=1), rtol=1e-12, atol=1e-15)
     np.testing.assert_allclose(pi.sum(1), 1.0, rtol=1e-12)
     # a normal on a mean with a narrow component is claimed by it
-    p = oracle.fuzzy(np.array([[0.0, 0.0, 1.0]]), mu, np.full(6, 50.0, np.float32))
+    p = oracle.fuzzy(np.array([[0.0, 0.0, 1.0]], np.float32), mu, np.full(6, 50.0, np.float32))
     assert p[0, 4] > 0.999999
 
 
@@ -175,3 +175,15 @@ def test_vertex_corner_csr(oracle):
     for v in range(0, V.shape[0], 11):
         mine = cor[off[v]:off[v + 1]]
         assert np.all(flat[mine] == v) and np.all(np.diff(mine) > 0) and len(mine) == (flat == v).sum()
+
+
+def test_facet_geometry_against_numpy_fp64(oracle):
+    V, F = meshgen.icosphere(3, seed=5, jitter=0.05)
+    n, a = oracle.facet_geometry(V, F)
+    P = V.astype(float)[F]
+    cr = np.cross(P[:, 1] - P[:, 0], P[:, 2] - P[:, 0])
+    ln = np.linalg.norm(cr, axis=1)
+    np.testing.assert_allclose(a, 0.5 * ln, rtol=1e-5)
+    np.testing.assert_allclose(n, cr / ln[:, None], atol=1e-5)
+    lev = oracle.facet_levels(a)
+    assert (lev == 2).sum() == (a == a.max()).sum() and set(lev.tolist()) == {1, 2}
