@@ -40,6 +40,9 @@ def main():
                     help="only run the plain copy kernel on 1 GiB (HBM yardstick / counter calibration)")
     ap.add_argument("--pool", type=int, default=0, metavar="C",
                     help="also time pooling/unpooling of C-channel features over the recorded clusters")
+    ap.add_argument("--conv", type=int, default=0, metavar="C",
+                    help="also time the depth-wise vertex2facet / facet2vertex convolutions on the input mesh, "
+                         "C channels, 6 Gaussian components")
     ap.add_argument("--stages", action="store_true", help="also print per-stage times to stderr")
     ap.add_argument("--placement", choices=["mean", "inverse"], default="mean",
                     help="contraction target: the pair's mean (default, the headline path) or the point of "
@@ -225,6 +228,55 @@ def main():
             pooling[name] = {"ms": round(ms, 4), "algorithmic_MB": round(nbytes / 1e6, 2),
                              "GBps": round(nbytes / ms / 1e6, 1), "frac_of_8TBps": round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 4)}
 
+    convs = None
+    if args.conv:
+        # one vertex2vertex convolution's depth-wise kernels on the input mesh (forward and backward)
+        C, T = args.conv, 6
+
+        def timed_c(fn, reps=20):
+            for _ in range(3):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(reps):
+                fn()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+
+        xin = torch.randn((N, C), device=dev, dtype=torch.float32)
+        w3 = torch.randn((3, C), device=dev, dtype=torch.float32)
+        wt = torch.randn((T, C), device=dev, dtype=torch.float32)
+        mu = torch.tensor([[1, 0, 0], [-1, 0, 0], [0, 1, 0], [0, -1, 0], [0, 0, 1], [0, 0, -1]], device=dev,
+                          dtype=torch.float32)
+        iv = torch.full((T,), 2.0, device=dev, dtype=torch.float32)
+        nf_list = [int(v) for v in nf_in] if B > 1 else None
+        t_csr = timed_c(lambda: ctx.picasso_vertex_corner_csr(dF, N), reps=5)
+        off_c, cor_c = ctx.picasso_vertex_corner_csr(dF, N)
+        t_geo = timed_c(lambda: ctx.picasso_facet_geometry(dV, dF, nf=nf_list), reps=5)
+        nrm, _, lev = ctx.picasso_facet_geometry(dV, dF, nf=nf_list)
+        t_fz = timed_c(lambda: ctx.picasso_fuzzy_coefficients(nrm, mu, iv))
+        pi_c = ctx.picasso_fuzzy_coefficients(nrm, mu, iv)
+        yb = torch.empty((NF, C), device=dev, dtype=torch.float32)
+        xb = torch.empty((N, C), device=dev, dtype=torch.float32)
+        ctx.picasso_v2f_forward(xin, dF, lev, w3, out=yb)
+        idx_f, idx_v = 4 * (3 * NF + NF), 4 * (3 * NF + N)
+        rows_c = {
+            "v2f_forward": (lambda: ctx.picasso_v2f_forward(xin, dF, lev, w3, out=yb), 4 * C * (N + NF) + idx_f),
+            "f2v_forward": (lambda: ctx.picasso_f2v_forward(yb, pi_c, wt, off_c, cor_c, N, out=xb),
+                            4 * C * (N + NF) + idx_v + 4 * T * NF),
+            "v2f_backward": (lambda: ctx.picasso_v2f_backward(yb, xin, dF, lev, w3, off_c, cor_c),
+                             4 * C * (2 * N + 2 * NF) + idx_f + idx_v),
+            "f2v_backward": (lambda: ctx.picasso_f2v_backward(xin, yb, pi_c, wt, dF, off_c, want_gpi=False),
+                             4 * C * (2 * N + 3 * NF) + idx_f + 2 * 4 * T * NF),
+        }
+        convs = {"channels": C, "components": T, "verts": N, "facets": NF, "corner_csr_ms": round(t_csr, 4),
+                 "facet_geometry_ms": round(t_geo, 4), "fuzzy_ms": round(t_fz, 4)}
+        for name, (fn, nbytes) in rows_c.items():
+            ms = timed_c(fn)
+            convs[name] = {"ms": round(ms, 4), "algorithmic_MB": round(nbytes / 1e6, 2),
+                           "GBps": round(nbytes / ms / 1e6, 1), "frac_of_8TBps": round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 4)}
+
     out = {
         "metric": "input facets/s per decimation (ms per decimation in ms_per_step)",
         "value": round(NF / (ms_per_step * 1e-3), 1),
@@ -246,6 +298,8 @@ def main():
     }
     if pooling is not None:
         out["pooling"] = pooling
+    if convs is not None:
+        out["convolutions"] = convs
     print(json.dumps(out))
     ctx.close()
 

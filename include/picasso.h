@@ -268,6 +268,78 @@ int picasso_radix_sort(picasso_ctx* ctx, void* stream, int key_bytes, void* d_ke
 int picasso_bucket_sort(picasso_ctx* ctx, void* stream, int key_bytes, void* d_keys, uint32_t* d_vals, int64_t n,
                         int key_bits);
 
+/* ---------------------------------------------------------------------------
+ * Mesh convolutions, depth-wise form (Sec. 4 "Mesh Convolution"; supplementary
+ * section "Backward propagations of different convolutions").  One filter
+ * weight per channel; the channel-wise (dense) half of the paper's separable
+ * convolutions is an ordinary matrix product and is left to the caller.
+ * Features are fp32 row-major [rows, C]; all data pointers are device memory
+ * owned by the caller.  Unless noted the calls are asynchronous on `stream`,
+ * allocate nothing and do not report bad indices (an out-of-range index is read
+ * as index 0): picasso_vertex_corner_csr checks a facet array once.
+ * C <= 1024 when C is a multiple of 4 and the pointers are 16-byte aligned,
+ * else C <= 256 (filter-gradient reductions).
+ * ------------------------------------------------------------------------- */
+
+/* Corners of the facet array at every vertex: corner i = 3 f + s is vertex
+ * d_facets[i]; corners of vertex v = d_corners[d_offsets[v] .. d_offsets[v+1]),
+ * ascending, so |N(v)| = d_offsets[v+1] - d_offsets[v] (a facet counts once per
+ * corner).  d_offsets [N+1], d_corners [3F].  Synchronises the stream; returns
+ * PICASSO_ERR_BAD_INDEX if an index lies outside [0, N).  F <= max_facets. */
+int picasso_vertex_corner_csr(picasso_ctx* ctx, void* stream, const int32_t* d_facets, int32_t F, int32_t N,
+                              int32_t* d_offsets, int32_t* d_corners);
+
+/* Unit normals d_normals [F,3], areas d_areas [F] (Sec. 4, first paragraph; a
+ * facet of zero area gets the zero normal) and interpolation levels d_level [F]
+ * (Eq. "interpolate_num": k = floor((A - A_min) / (A_max - A_min)) * alpha +
+ * beta, A_min and A_max over the facet's own mesh; the ratio counts as 0 when
+ * all areas of a mesh are equal).  Any of the three outputs may be NULL.  B
+ * meshes with h_nf[b] facets each (host array; NULL allowed for B = 1).
+ * Synchronises the stream; PICASSO_ERR_BAD_INDEX as above. */
+int picasso_facet_geometry(picasso_ctx* ctx, void* stream, const float* d_verts, int32_t N, const int32_t* d_facets,
+                           int32_t F, int32_t B, const int32_t* h_nf, int32_t alpha, int32_t beta, float* d_normals,
+                           float* d_areas, int32_t* d_level);
+
+/* Fuzzy coefficients of the facets (Sec. 4.2): z_ft = |n_f - mu_t|^2 *
+ * d_inv_var[t] (homogeneous diagonal covariance, inv_var = 1 / sigma_t^2),
+ * pi_ft = exp(-z_ft) / sum_m exp(-z_fm).  d_normals [F,3], d_mu [T,3],
+ * d_inv_var [T], d_pi [F,T]. */
+int picasso_fuzzy_coefficients(picasso_ctx* ctx, void* stream, const float* d_normals, int32_t F, const float* d_mu,
+                               const float* d_inv_var, int32_t T, float* d_pi);
+
+/* Vertex2facet (Sec. 4.1): per channel J_f = (1/K) sum_k W_k I_k with I_k, W_k the
+ * barycentric interpolations of the three vertex features and of the three
+ * filter weights d_w [3,C] at the K = k (k + 1) / 2 points of level k =
+ * d_level[f] (NULL: level 1 everywhere).  The points are the triangular lattice
+ * (i, j, l) / (k - 1), i + j + l = k - 1 (the paper does not print them); level 1
+ * is the centroid alone.  d_x [N,C] -> d_y [F,C]. */
+int picasso_v2f_forward(picasso_ctx* ctx, void* stream, const float* d_x, int32_t N, int32_t C,
+                        const int32_t* d_facets, int32_t F, const int32_t* d_level, const float* d_w, float* d_y);
+
+/* Its backward pass (supplementary, vertex2facet kernel): d_gx [N,C] = gradient
+ * with respect to the vertex features, d_gw [3,C] with respect to the filter;
+ * either may be NULL.  d_offsets / d_corners from picasso_vertex_corner_csr of
+ * the same facet array.  d_gw uses the context's workspace: calls on one
+ * context that overlap in time race. */
+int picasso_v2f_backward(picasso_ctx* ctx, void* stream, const float* d_gy, const float* d_x, int32_t N, int32_t C,
+                         const int32_t* d_facets, int32_t F, const int32_t* d_level, const float* d_w,
+                         const int32_t* d_offsets, const int32_t* d_corners, float* d_gx, float* d_gw);
+
+/* Facet2vertex (Sec. 4.2, last equation): per channel I_v = (1 / |N(v)|) sum over the
+ * corners at v of (sum_t pi_ft w_t) J_f; a vertex without facets gets 0.
+ * d_y [F,C], d_pi [F,T], d_w [T,C] -> d_x [N,C]. */
+int picasso_f2v_forward(picasso_ctx* ctx, void* stream, const float* d_y, int32_t F, int32_t C, const float* d_pi,
+                        int32_t T, const float* d_w, const int32_t* d_offsets, const int32_t* d_corners, int32_t N,
+                        float* d_x);
+
+/* Its backward pass (supplementary, facet2vertex kernel): d_gy [F,C] with respect
+ * to the facet features, d_gw [T,C] to the filter, d_gpi [F,T] to the fuzzy
+ * coefficients (for learnable covariances); each may be NULL.  d_gw uses the
+ * context's workspace as above. */
+int picasso_f2v_backward(picasso_ctx* ctx, void* stream, const float* d_gx, const float* d_y, int32_t F, int32_t C,
+                         const float* d_pi, int32_t T, const float* d_w, const int32_t* d_facets,
+                         const int32_t* d_offsets, int32_t N, float* d_gy, float* d_gw, float* d_gpi);
+
 #ifdef __cplusplus
 }
 #endif

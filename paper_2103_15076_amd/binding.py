@@ -40,7 +40,9 @@ EXPORTED_SYMBOLS = (
     "picasso_workspace_bytes", "picasso_create", "picasso_destroy", "picasso_set_option", "picasso_strerror",
     "picasso_last_hip_error", "picasso_decimate", "picasso_decimate_batch", "picasso_vertex_quadrics",
     "picasso_edge_costs", "picasso_radix_sort", "picasso_kernel_timing",
-    "picasso_device_copy", "picasso_bucket_sort", "picasso_cluster_csr", "picasso_replace_mapping", "picasso_pool_forward",
+    "picasso_device_copy", "picasso_bucket_sort", "picasso_cluster_csr", "picasso_replace_mapping",
+    "picasso_vertex_corner_csr", "picasso_facet_geometry", "picasso_fuzzy_coefficients", "picasso_v2f_forward",
+    "picasso_v2f_backward", "picasso_f2v_forward", "picasso_f2v_backward", "picasso_pool_forward",
     "picasso_pool_backward", "picasso_unpool_forward", "picasso_unpool_backward",
 )
 
@@ -124,6 +126,20 @@ def load_library():
     lib.picasso_cluster_csr.argtypes = [vp, vp, vp, i32, i32, vp, vp]
     lib.picasso_replace_mapping.restype = ctypes.c_int
     lib.picasso_replace_mapping.argtypes = [vp, vp, vp, i32, i32, vp, vp]
+    lib.picasso_vertex_corner_csr.restype = ctypes.c_int
+    lib.picasso_vertex_corner_csr.argtypes = [vp, vp, vp, i32, i32, vp, vp]
+    lib.picasso_facet_geometry.restype = ctypes.c_int
+    lib.picasso_facet_geometry.argtypes = [vp, vp, vp, i32, vp, i32, i32, vp, i32, i32, vp, vp, vp]
+    lib.picasso_fuzzy_coefficients.restype = ctypes.c_int
+    lib.picasso_fuzzy_coefficients.argtypes = [vp, vp, vp, i32, vp, vp, i32, vp]
+    lib.picasso_v2f_forward.restype = ctypes.c_int
+    lib.picasso_v2f_forward.argtypes = [vp, vp, vp, i32, i32, vp, i32, vp, vp, vp]
+    lib.picasso_v2f_backward.restype = ctypes.c_int
+    lib.picasso_v2f_backward.argtypes = [vp, vp, vp, vp, i32, i32, vp, i32, vp, vp, vp, vp, vp, vp]
+    lib.picasso_f2v_forward.restype = ctypes.c_int
+    lib.picasso_f2v_forward.argtypes = [vp, vp, vp, i32, i32, vp, i32, vp, vp, vp, i32, vp]
+    lib.picasso_f2v_backward.restype = ctypes.c_int
+    lib.picasso_f2v_backward.argtypes = [vp, vp, vp, vp, i32, i32, vp, i32, vp, vp, vp, i32, vp, vp, vp]
     lib.picasso_pool_forward.restype = ctypes.c_int
     lib.picasso_pool_forward.argtypes = [vp, vp, ctypes.c_int, vp, i32, i32, vp, vp, i32, vp, vp, vp]
     lib.picasso_pool_backward.restype = ctypes.c_int
@@ -397,6 +413,110 @@ class Context:
         if st != PICASSO_OK:
             self._raise(st)
         return gy
+
+    # ---- mesh convolutions, depth-wise (Sec. 4; supplementary, backward propagations)
+
+    def picasso_vertex_corner_csr(self, facets, n_verts, stream=None):
+        """Returns (offsets int32[N+1], corners int32[3F]) device tensors."""
+        import torch
+        F = int(facets.shape[0])
+        off = torch.empty((int(n_verts) + 1,), dtype=torch.int32, device=facets.device)
+        cor = torch.empty((3 * F,), dtype=torch.int32, device=facets.device)
+        st = self._lib.picasso_vertex_corner_csr(self._h, _stream_ptr(stream), _dev_ptr(facets, torch.int32, "facets"),
+                                                 F, int(n_verts), _dev_ptr(off, torch.int32, "off"),
+                                                 _dev_ptr(cor, torch.int32, "cor"))
+        if st != PICASSO_OK:
+            self._raise(st)
+        return off, cor
+
+    def picasso_facet_geometry(self, verts, facets, nf=None, alpha=1, beta=1, stream=None):
+        """Returns (normals f32[F,3], areas f32[F], level int32[F]); nf = facets per mesh of a batch."""
+        import torch
+        N, F = int(verts.shape[0]), int(facets.shape[0])
+        nrm = torch.empty((F, 3), dtype=torch.float32, device=verts.device)
+        area = torch.empty((F,), dtype=torch.float32, device=verts.device)
+        lev = torch.empty((F,), dtype=torch.int32, device=verts.device)
+        B = 1 if nf is None else len(nf)
+        h_nf = None if nf is None else (ctypes.c_int32 * B)(*[int(v) for v in nf])
+        st = self._lib.picasso_facet_geometry(self._h, _stream_ptr(stream), _dev_ptr(verts, torch.float32, "verts"), N,
+                                              _dev_ptr(facets, torch.int32, "facets"), F, B, h_nf, int(alpha), int(beta),
+                                              _dev_ptr(nrm, torch.float32, "normals"),
+                                              _dev_ptr(area, torch.float32, "areas"), _dev_ptr(lev, torch.int32, "level"))
+        if st != PICASSO_OK:
+            self._raise(st)
+        return nrm, area, lev
+
+    def picasso_fuzzy_coefficients(self, normals, mu, inv_var, stream=None):
+        import torch
+        F, T = int(normals.shape[0]), int(mu.shape[0])
+        pi = torch.empty((F, T), dtype=torch.float32, device=normals.device)
+        st = self._lib.picasso_fuzzy_coefficients(self._h, _stream_ptr(stream),
+                                                  _dev_ptr(normals, torch.float32, "normals"), F,
+                                                  _dev_ptr(mu, torch.float32, "mu"),
+                                                  _dev_ptr(inv_var, torch.float32, "inv_var"), T,
+                                                  _dev_ptr(pi, torch.float32, "pi"))
+        if st != PICASSO_OK:
+            self._raise(st)
+        return pi
+
+    def picasso_v2f_forward(self, x, facets, level, w, out=None, stream=None):
+        import torch
+        N, C, F = int(x.shape[0]), int(x.shape[1]), int(facets.shape[0])
+        y = out if out is not None else torch.empty((F, C), dtype=torch.float32, device=x.device)
+        st = self._lib.picasso_v2f_forward(self._h, _stream_ptr(stream), _dev_ptr(x, torch.float32, "x"), N, C,
+                                           _dev_ptr(facets, torch.int32, "facets"), F,
+                                           _dev_ptr(level, torch.int32, "level") if level is not None else None,
+                                           _dev_ptr(w, torch.float32, "w"), _dev_ptr(y, torch.float32, "y"))
+        if st != PICASSO_OK:
+            self._raise(st)
+        return y
+
+    def picasso_v2f_backward(self, gy, x, facets, level, w, offsets, corners, stream=None):
+        """Returns (gx[N,C], gw[3,C])."""
+        import torch
+        N, C, F = int(x.shape[0]), int(x.shape[1]), int(facets.shape[0])
+        gx = torch.empty((N, C), dtype=torch.float32, device=x.device)
+        gw = torch.empty((3, C), dtype=torch.float32, device=x.device)
+        st = self._lib.picasso_v2f_backward(self._h, _stream_ptr(stream), _dev_ptr(gy, torch.float32, "gy"),
+                                            _dev_ptr(x, torch.float32, "x"), N, C,
+                                            _dev_ptr(facets, torch.int32, "facets"), F,
+                                            _dev_ptr(level, torch.int32, "level") if level is not None else None,
+                                            _dev_ptr(w, torch.float32, "w"), _dev_ptr(offsets, torch.int32, "offsets"),
+                                            _dev_ptr(corners, torch.int32, "corners"),
+                                            _dev_ptr(gx, torch.float32, "gx"), _dev_ptr(gw, torch.float32, "gw"))
+        if st != PICASSO_OK:
+            self._raise(st)
+        return gx, gw
+
+    def picasso_f2v_forward(self, y, pi, w, offsets, corners, n_verts, out=None, stream=None):
+        import torch
+        F, C, T = int(y.shape[0]), int(y.shape[1]), int(pi.shape[1])
+        x = out if out is not None else torch.empty((int(n_verts), C), dtype=torch.float32, device=y.device)
+        st = self._lib.picasso_f2v_forward(self._h, _stream_ptr(stream), _dev_ptr(y, torch.float32, "y"), F, C,
+                                           _dev_ptr(pi, torch.float32, "pi"), T, _dev_ptr(w, torch.float32, "w"),
+                                           _dev_ptr(offsets, torch.int32, "offsets"),
+                                           _dev_ptr(corners, torch.int32, "corners"), int(n_verts),
+                                           _dev_ptr(x, torch.float32, "x"))
+        if st != PICASSO_OK:
+            self._raise(st)
+        return x
+
+    def picasso_f2v_backward(self, gx, y, pi, w, facets, offsets, want_gpi=True, stream=None):
+        """Returns (gy[F,C], gw[T,C], gpi[F,T] or None)."""
+        import torch
+        F, C, T, N = int(y.shape[0]), int(y.shape[1]), int(pi.shape[1]), int(gx.shape[0])
+        gy = torch.empty((F, C), dtype=torch.float32, device=y.device)
+        gw = torch.empty((T, C), dtype=torch.float32, device=y.device)
+        gpi = torch.empty((F, T), dtype=torch.float32, device=y.device) if want_gpi else None
+        st = self._lib.picasso_f2v_backward(self._h, _stream_ptr(stream), _dev_ptr(gx, torch.float32, "gx"),
+                                            _dev_ptr(y, torch.float32, "y"), F, C, _dev_ptr(pi, torch.float32, "pi"), T,
+                                            _dev_ptr(w, torch.float32, "w"), _dev_ptr(facets, torch.int32, "facets"),
+                                            _dev_ptr(offsets, torch.int32, "offsets"), N,
+                                            _dev_ptr(gy, torch.float32, "gy"), _dev_ptr(gw, torch.float32, "gw"),
+                                            _dev_ptr(gpi, torch.float32, "gpi") if want_gpi else None)
+        if st != PICASSO_OK:
+            self._raise(st)
+        return gy, gw, gpi
 
     def picasso_bucket_sort(self, keys, vals=None, key_bits=None, stream=None):
         """Same as picasso_radix_sort, by top-digit partition + per-bucket LDS sort (n <= 2^20)."""

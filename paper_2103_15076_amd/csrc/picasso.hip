@@ -21,6 +21,7 @@
 #include "../../include/picasso.h"
 #include "primitives.h"
 #include "pooling.h"
+#include "conv.h"
 
 #pragma clang fp contract(off)
 
@@ -2479,6 +2480,39 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
     return warn;
 }
 
+// channels per lane for row-major [rows, C] features at these addresses
+inline bool conv_vec4(int C, std::initializer_list<const void*> ptrs) {
+    if (C % 4 != 0) return false;
+    for (const void* p : ptrs)
+        if ((uintptr_t)p % 16 != 0) return false;
+    return true;
+}
+
+// Two-stage sum of ROWS x C filter-gradient rows over n_rows rows (conv::reduce_rows_stage1/2):
+// partial sums in the context's sort buffer.
+template <int ROWS, class Term>
+int reduce_filter_rows(picasso_ctx* c, hipStream_t s, Term term, int n_rows, int C, bool vec4, int rows_used,
+                       float* d_out) {
+    const int Q = vec4 ? C / 4 : C;
+    if (Q > pool::BLOCK) return PICASSO_ERR_INVALID_ARG;
+    const size_t cap = (size_t)3 * (size_t)c->max_facets * sizeof(u64) / sizeof(float);  // floats in key64[0]
+    const size_t per_group = (size_t)ROWS * C;
+    if (per_group > cap) return PICASSO_ERR_WORKSPACE;
+    const int R = pool::BLOCK / Q;
+    long long groups = std::min<long long>(1024, ((long long)n_rows + 4ll * R - 1) / (4ll * R));
+    groups = std::max<long long>(1, std::min<long long>(groups, (long long)(cap / per_group)));
+    const int chunk = (int)(((long long)n_rows + groups - 1) / groups);
+    float* partial = reinterpret_cast<float*>(c->key64[0]);
+    const size_t lds = (size_t)pool::BLOCK * ROWS * (vec4 ? 4 : 1) * sizeof(float);
+    if (vec4)
+        conv::reduce_rows_stage1_kernel<ROWS, 4, Term><<<(int)groups, pool::BLOCK, lds, s>>>(term, n_rows, C, chunk, partial);
+    else
+        conv::reduce_rows_stage1_kernel<ROWS, 1, Term><<<(int)groups, pool::BLOCK, lds, s>>>(term, n_rows, C, chunk, partial);
+    conv::reduce_rows_stage2_kernel<<<pool::grid_for((long long)rows_used * C * 64), pool::BLOCK, 0, s>>>(
+        partial, (int)groups, ROWS, rows_used, C, d_out);
+    return PICASSO_OK;
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------------------
@@ -2752,6 +2786,171 @@ int picasso_cluster_csr(picasso_ctx* c, void* stream, const int32_t* d_cluster_i
     if (rc != PICASSO_OK) return rc;
     HIP_TRY(c, hipGetLastError());
     return (reinterpret_cast<State*>(c->h_pin)->err & 1) ? PICASSO_ERR_BAD_INDEX : PICASSO_OK;
+}
+
+// ---- mesh convolutions, depth-wise (Sec. 4 "Mesh Convolution"; supplementary, backward propagations)
+
+int picasso_vertex_corner_csr(picasso_ctx* c, void* stream, const int32_t* d_facets, int32_t F, int32_t N,
+                              int32_t* d_offsets, int32_t* d_corners) {
+    if (!c || !d_facets || F < 1 || N < 1 || !d_offsets || !d_corners) return PICASSO_ERR_INVALID_ARG;
+    if (F > c->max_facets) return PICASSO_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(c, hipSetDevice(c->device));
+    const int H = 3 * F, cbits = ceil_log2(H), vbits = ceil_log2(N);
+    prim::fill_u32_kernel<<<1, BLOCK, 0, s>>>(reinterpret_cast<u32*>(&c->st->err), 1, 0u);
+    conv::corner_keys_kernel<<<pool::grid_for(H), pool::BLOCK, 0, s>>>(d_facets, H, N, cbits, c->key64[0], &c->st->err);
+    const int where = sort_by_vertex<u64, false>(s, c->key64[0], c->key64[1], nullptr, nullptr, nullptr, H,
+                                                 cbits + vbits, c->sort_sc, c->hist12);
+    if (where < 0) return PICASSO_ERR_HIP;
+    const u64* skey = where ? c->key64[1] : c->key64[0];
+    csr_offsets_kernel<u64><<<grid_for(H), BLOCK, 0, s>>>(skey, cbits, H, N, d_offsets);
+    conv::corner_list_kernel<<<pool::grid_for(H), pool::BLOCK, 0, s>>>(skey, H, cbits, d_corners);
+    int rc = read_header(c, s);
+    if (rc != PICASSO_OK) return rc;
+    HIP_TRY(c, hipGetLastError());
+    return (reinterpret_cast<State*>(c->h_pin)->err & 1) ? PICASSO_ERR_BAD_INDEX : PICASSO_OK;
+}
+
+int picasso_facet_geometry(picasso_ctx* c, void* stream, const float* d_verts, int32_t N, const int32_t* d_facets,
+                           int32_t F, int32_t B, const int32_t* h_nf, int32_t alpha, int32_t beta, float* d_normals,
+                           float* d_areas, int32_t* d_level) {
+    if (!c || !d_verts || !d_facets || N < 1 || F < 1 || B < 1 || (B > 1 && !h_nf) || alpha < 0 || beta < 1 ||
+        (!d_normals && !d_areas && !d_level))
+        return PICASSO_ERR_INVALID_ARG;
+    if (B > c->max_meshes || (d_level && !d_areas && F > 3 * c->max_facets)) return PICASSO_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(c, hipSetDevice(c->device));
+    // facet offsets of the meshes, staged in pinned memory like the decimation's header
+    int* img = c->h_pin + c->h_up_off;
+    long long acc = 0;
+    for (int b = 0; b < B; ++b) {
+        img[b] = (int)acc;
+        const long long nb = (B > 1) ? h_nf[b] : F;
+        if (nb < 0) return PICASSO_ERR_INVALID_ARG;
+        acc += nb;
+    }
+    img[B] = (int)acc;
+    if (acc != F) return PICASSO_ERR_INVALID_ARG;
+    HIP_TRY(c, hipMemcpyAsync(c->foff, img, sizeof(int) * (B + 1), hipMemcpyHostToDevice, s));
+    unsigned* amin = reinterpret_cast<unsigned*>(c->acand);
+    unsigned* amax = reinterpret_cast<unsigned*>(c->arem);
+    float* areas = d_areas ? d_areas : reinterpret_cast<float*>(c->ecost);  // scratch when only levels are wanted
+    prim::fill_u32_kernel<<<1, BLOCK, 0, s>>>(reinterpret_cast<u32*>(&c->st->err), 1, 0u);
+    if (d_level) {
+        prim::fill_u32_kernel<<<grid_for(B), BLOCK, 0, s>>>(amin, B, 0xFFFFFFFFu);
+        prim::fill_u32_kernel<<<grid_for(B), BLOCK, 0, s>>>(amax, B, 0u);
+    }
+    conv::facet_geometry_kernel<<<pool::grid_for(F), pool::BLOCK, 0, s>>>(
+        d_verts, N, d_facets, F, B, c->foff, d_normals, (d_areas || d_level) ? areas : nullptr,
+        d_level ? amin : nullptr, d_level ? amax : nullptr, &c->st->err);
+    if (d_level)
+        conv::facet_level_kernel<<<pool::grid_for(F), pool::BLOCK, 0, s>>>(areas, F, B, c->foff, amin, amax, alpha, beta,
+                                                                          d_level);
+    int rc = read_header(c, s);
+    if (rc != PICASSO_OK) return rc;
+    HIP_TRY(c, hipGetLastError());
+    return (reinterpret_cast<State*>(c->h_pin)->err & 1) ? PICASSO_ERR_BAD_INDEX : PICASSO_OK;
+}
+
+int picasso_fuzzy_coefficients(picasso_ctx* c, void* stream, const float* d_normals, int32_t F, const float* d_mu,
+                               const float* d_inv_var, int32_t T, float* d_pi) {
+    if (!c || !d_normals || F < 1 || !d_mu || !d_inv_var || T < 1 || !d_pi) return PICASSO_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(c, hipSetDevice(c->device));
+    conv::fuzzy_kernel<<<pool::grid_for(F), pool::BLOCK, 0, s>>>(d_normals, F, d_mu, d_inv_var, T, d_pi);
+    HIP_TRY(c, hipGetLastError());
+    return PICASSO_OK;
+}
+
+int picasso_v2f_forward(picasso_ctx* c, void* stream, const float* d_x, int32_t N, int32_t C, const int32_t* d_facets,
+                        int32_t F, const int32_t* d_level, const float* d_w, float* d_y) {
+    if (!c || !d_x || N < 1 || C < 1 || !d_facets || F < 1 || !d_w || !d_y) return PICASSO_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(c, hipSetDevice(c->device));
+    if (conv_vec4(C, {d_x, d_w, d_y}))
+        conv::v2f_forward_kernel<4><<<pool::grid_for((long long)F * (C / 4)), pool::BLOCK, 0, s>>>(d_x, N, C, d_facets, F, d_level, d_w, d_y);
+    else
+        conv::v2f_forward_kernel<1><<<pool::grid_for((long long)F * C), pool::BLOCK, 0, s>>>(d_x, N, C, d_facets, F, d_level, d_w, d_y);
+    HIP_TRY(c, hipGetLastError());
+    return PICASSO_OK;
+}
+
+int picasso_v2f_backward(picasso_ctx* c, void* stream, const float* d_gy, const float* d_x, int32_t N, int32_t C,
+                         const int32_t* d_facets, int32_t F, const int32_t* d_level, const float* d_w,
+                         const int32_t* d_offsets, const int32_t* d_corners, float* d_gx, float* d_gw) {
+    if (!c || !d_gy || !d_x || N < 1 || C < 1 || !d_facets || F < 1 || !d_w || !d_offsets || !d_corners ||
+        (!d_gx && !d_gw))
+        return PICASSO_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(c, hipSetDevice(c->device));
+    const bool vec4 = conv_vec4(C, {d_gy, d_x, d_w, d_gx});
+    if (d_gx) {
+        if (vec4)
+            conv::v2f_backward_x_kernel<4><<<pool::grid_for((long long)N * (C / 4)), pool::BLOCK, 0, s>>>(d_gy, C, d_level, d_w, d_offsets, d_corners, N, 3 * F, d_gx);
+        else
+            conv::v2f_backward_x_kernel<1><<<pool::grid_for((long long)N * C), pool::BLOCK, 0, s>>>(d_gy, C, d_level, d_w, d_offsets, d_corners, N, 3 * F, d_gx);
+    }
+    if (d_gw) {
+        conv::V2fWeightTerm term{d_gy, d_x, d_facets, d_level, C, N};
+        const int rc = reduce_filter_rows<3>(c, s, term, F, C, vec4, 3, d_gw);
+        if (rc != PICASSO_OK) return rc;
+    }
+    HIP_TRY(c, hipGetLastError());
+    return PICASSO_OK;
+}
+
+int picasso_f2v_forward(picasso_ctx* c, void* stream, const float* d_y, int32_t F, int32_t C, const float* d_pi,
+                        int32_t T, const float* d_w, const int32_t* d_offsets, const int32_t* d_corners, int32_t N,
+                        float* d_x) {
+    if (!c || !d_y || F < 1 || C < 1 || !d_pi || T < 1 || !d_w || !d_offsets || !d_corners || N < 1 || !d_x)
+        return PICASSO_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(c, hipSetDevice(c->device));
+    const bool vec4 = conv_vec4(C, {d_y, d_w, d_x});
+    const bool lds = (long long)T * C <= conv::F2V_LDS_FLOATS;
+    const size_t lds_bytes = lds ? sizeof(float) * (size_t)T * C : 0;
+    const int grid = pool::grid_for((long long)N * (vec4 ? C / 4 : C));
+#define PICASSO_F2V(VEC, LDS) \
+    conv::f2v_forward_kernel<VEC, LDS><<<grid, pool::BLOCK, lds_bytes, s>>>(d_y, C, d_pi, T, d_w, d_offsets, d_corners, N, 3 * F, d_x)
+    if (vec4) {
+        if (lds) PICASSO_F2V(4, true);
+        else PICASSO_F2V(4, false);
+    } else {
+        if (lds) PICASSO_F2V(1, true);
+        else PICASSO_F2V(1, false);
+    }
+#undef PICASSO_F2V
+    HIP_TRY(c, hipGetLastError());
+    return PICASSO_OK;
+}
+
+int picasso_f2v_backward(picasso_ctx* c, void* stream, const float* d_gx, const float* d_y, int32_t F, int32_t C,
+                         const float* d_pi, int32_t T, const float* d_w, const int32_t* d_facets,
+                         const int32_t* d_offsets, int32_t N, float* d_gy, float* d_gw, float* d_gpi) {
+    if (!c || !d_gx || !d_y || F < 1 || C < 1 || !d_pi || T < 1 || !d_w || !d_facets || !d_offsets || N < 1 ||
+        (!d_gy && !d_gw && !d_gpi))
+        return PICASSO_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(c, hipSetDevice(c->device));
+    const bool vec4 = conv_vec4(C, {d_gx, d_y, d_w, d_gy});
+    if (d_gy) {
+        if (vec4)
+            conv::f2v_backward_y_kernel<4><<<pool::grid_for((long long)F * (C / 4)), pool::BLOCK, 0, s>>>(d_gx, C, d_pi, T, d_w, d_facets, F, d_offsets, N, d_gy);
+        else
+            conv::f2v_backward_y_kernel<1><<<pool::grid_for((long long)F * C), pool::BLOCK, 0, s>>>(d_gx, C, d_pi, T, d_w, d_facets, F, d_offsets, N, d_gy);
+    }
+    if (d_gw) {
+        constexpr int ROWS = 8;  // filter rows per pass
+        for (int t0 = 0; t0 < T; t0 += ROWS) {
+            conv::F2vWeightTerm<ROWS> term{d_gx, d_y, d_pi, d_facets, d_offsets, N, C, T, t0};
+            const int rc = reduce_filter_rows<ROWS>(c, s, term, F, C, vec4, std::min(ROWS, T - t0), d_gw + (size_t)t0 * C);
+            if (rc != PICASSO_OK) return rc;
+        }
+    }
+    if (d_gpi)
+        conv::f2v_backward_pi_kernel<<<pool::grid_for((long long)F * T), pool::BLOCK, 0, s>>>(d_gx, d_y, C, T, d_w, d_facets, F, d_offsets, N, d_gpi);
+    HIP_TRY(c, hipGetLastError());
+    return PICASSO_OK;
 }
 
 int picasso_replace_mapping(picasso_ctx* c, void* stream, const int32_t* d_cluster_id, int32_t n_in, int32_t n_out,

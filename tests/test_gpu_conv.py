@@ -1,0 +1,199 @@
+"""GPU parity of the two mesh convolutions, depth-wise form (Sec. 4 "Mesh
+Convolution"; supplementary, "Backward propagations of different
+convolutions"), through the C-ABI against the fp64 oracle.
+
+Bars.  Index work (corner lists) and what decides an integer (normals, areas,
+levels: computed in binary32 with the same operations on both sides): bit-exact.
+Feature sums: every output is a sum of n products of non-negative coefficients
+with signed data, evaluated in binary32 in some fixed order, so
+|gpu - oracle| <= (n + 16) * 2^-24 * S with S the same sum over absolute values,
+which the oracle itself computes from the inputs' absolute values; n is the
+number of terms on the longest chain of additions (9 for a facet's bilinear
+form; the vertex degree times T for a vertex; for a filter gradient, which is
+summed in two stages -- up to 1,024 workgroups, each lane taking every R-th row
+of its workgroup's chunk, then a tree over the lanes and a serial sum over the
+workgroups -- at most 1,024 + rows / 1,024 + 64 times the 4-6 products of a row).
+"""
+import numpy as np
+import pytest
+from scipy.special import softmax
+
+from paper_2103_15076_amd import meshgen
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+EPS = 2.0 ** -24
+
+
+@pytest.fixture(scope="module")
+def pk():
+    import paper_2103_15076_amd as p
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    p.load_library()
+    return p
+
+
+@pytest.fixture(scope="module")
+def ctx(pk):
+    c = pk.Context(130_000, 230_000, 8, device=0)
+    yield c
+    c.close()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def _meshes():
+    yield "grid", meshgen.noisy_grid(23, 17, seed=5, noise=0.02)
+    yield "sphere", meshgen.icosphere(3, seed=7, jitter=0.05)
+    yield "room", meshgen.room_scene(11, room=(3.0, 2.0, 1.5), n_boxes=5, spacing=0.09)
+    V = np.random.default_rng(1).normal(size=(40, 3)).astype(np.float32)   # a hub, repeated corners, unused vertices
+    F = np.array([[0, i, i + 1] for i in range(1, 30)] + [[5, 5, 6], [7, 8, 8], [0, 1, 2]], np.int32)
+    yield "hub", (V, F)
+
+
+def _gw_terms(n_rows, per_row):
+    return per_row * (1024 + n_rows // 1024 + 64)
+
+
+def _close(got, want, n_terms, abs_sum, what):
+    got = got.cpu().numpy().astype(np.float64)
+    bound = (n_terms + 16) * EPS * abs_sum + 1e-30
+    bad = np.abs(got - want) > bound
+    assert not bad.any(), (what, int(bad.sum()), float(np.abs(got - want).max()), float(bound.max()))
+
+
+@pytest.mark.parametrize("name,mesh", list(_meshes()), ids=lambda x: x if isinstance(x, str) else "")
+def test_corner_lists_and_geometry_bit_exact(pk, ctx, oracle, name, mesh):
+    V, F = mesh
+    print(f"conv csr/geometry {name} N={V.shape[0]} F={F.shape[0]}", flush=True)
+    off, cor = ctx.picasso_vertex_corner_csr(dev(F), V.shape[0])
+    off_r, cor_r = oracle.vertex_corner_csr(F, V.shape[0])
+    assert np.array_equal(off.cpu().numpy(), off_r) and np.array_equal(cor.cpu().numpy(), cor_r)
+    nrm, area, lev = ctx.picasso_facet_geometry(dev(V), dev(F), alpha=2, beta=1)
+    n_r, a_r = oracle.facet_geometry(V, F)
+    assert np.array_equal(nrm.cpu().numpy().view(np.uint32), n_r.view(np.uint32))
+    assert np.array_equal(area.cpu().numpy().view(np.uint32), a_r.view(np.uint32))
+    assert np.array_equal(lev.cpu().numpy(), oracle.facet_levels(a_r, alpha=2, beta=1))
+    # two meshes in one call: extremes per mesh
+    h = F.shape[0] // 2
+    if h > 0:
+        _, _, lev2 = ctx.picasso_facet_geometry(dev(V), dev(F), nf=[h, F.shape[0] - h])
+        assert np.array_equal(lev2.cpu().numpy(), oracle.facet_levels(a_r, foff=[0, h, F.shape[0]]))
+
+
+def test_bad_indices_are_reported_where_they_are_checked(pk, ctx):
+    F = np.array([[0, 1, 2], [2, 1, 9]], np.int32)
+    V = np.zeros((5, 3), np.float32)
+    with pytest.raises(pk.PicassoError):
+        ctx.picasso_vertex_corner_csr(dev(F), 5)
+    with pytest.raises(pk.PicassoError):
+        ctx.picasso_facet_geometry(dev(V), dev(F))
+    # the convolution itself reads a bad index as vertex 0 and stays inside its arrays
+    x = np.arange(10, dtype=np.float32).reshape(5, 2)
+    w = np.ones((3, 2), np.float32)
+    y = ctx.picasso_v2f_forward(dev(x), dev(F), None, dev(w)).cpu().numpy()
+    assert np.allclose(y[1], (x[2] + x[1] + x[0]) / 3)
+
+
+def test_fuzzy_coefficients(pk, ctx, oracle):
+    V, F = meshgen.room_scene(3, room=(3.0, 2.0, 1.5), n_boxes=4, spacing=0.1)
+    n_r, _ = oracle.facet_geometry(V, F)
+    rng = np.random.default_rng(2)
+    for T in (1, 6, 13):
+        mu = rng.normal(size=(T, 3))
+        mu = (mu / np.linalg.norm(mu, axis=1, keepdims=True)).astype(np.float32)
+        inv_var = rng.uniform(0.3, 6.0, T).astype(np.float32)
+        pi = ctx.picasso_fuzzy_coefficients(dev(n_r), dev(mu), dev(inv_var)).cpu().numpy()
+        ref = oracle.fuzzy(n_r, mu, inv_var)
+        # z <= 4 * 6, so exp(-z) >= 4e-11; binary32 exp and one division: a few ulp of each coefficient
+        assert np.abs(pi - ref).max() <= 16 * EPS
+        assert np.abs(pi.sum(1) - 1).max() <= 32 * EPS
+
+
+@pytest.mark.parametrize("name,mesh", list(_meshes()), ids=lambda x: x if isinstance(x, str) else "")
+@pytest.mark.parametrize("C", [3, 8, 100])
+def test_vertex2facet_forward_and_backward(pk, ctx, oracle, name, mesh, C):
+    V, F = mesh
+    N, nF = V.shape[0], F.shape[0]
+    rng = np.random.default_rng(C)
+    x = rng.normal(size=(N, C)).astype(np.float32)
+    w = rng.normal(size=(3, C)).astype(np.float32)
+    gy = rng.normal(size=(nF, C)).astype(np.float32)
+    level = rng.integers(1, 6, nF).astype(np.int32)
+    print(f"v2f {name} C={C}", flush=True)
+    off, cor = ctx.picasso_vertex_corner_csr(dev(F), N)
+    for lev in (level, None):
+        lv = lev if lev is not None else np.ones(nF, np.int32)
+        y = ctx.picasso_v2f_forward(dev(x), dev(F), dev(lev) if lev is not None else None, dev(w))
+        _close(y, oracle.v2f_forward(x, F, lv, w), 9, oracle.v2f_forward(np.abs(x), F, lv, np.abs(w)), "y")
+        gx, gw = ctx.picasso_v2f_backward(dev(gy), dev(x), dev(F), dev(lev) if lev is not None else None, dev(w), off, cor)
+        gx_r, gw_r = oracle.v2f_backward(gy, x, F, lv, w)
+        gx_a, gw_a = oracle.v2f_backward(np.abs(gy), np.abs(x), F, lv, np.abs(w))
+        deg = np.bincount(F.reshape(-1), minlength=N).max()
+        _close(gx, gx_r, 4 * deg, gx_a, "gx")
+        _close(gw, gw_r, _gw_terms(nF, 4), gw_a, "gw")
+
+
+@pytest.mark.parametrize("name,mesh", list(_meshes()), ids=lambda x: x if isinstance(x, str) else "")
+@pytest.mark.parametrize("C,T", [(3, 1), (8, 6), (100, 11)])
+def test_facet2vertex_forward_and_backward(pk, ctx, oracle, name, mesh, C, T):
+    V, F = mesh
+    N, nF = V.shape[0], F.shape[0]
+    rng = np.random.default_rng(C + T)
+    y = rng.normal(size=(nF, C)).astype(np.float32)
+    pi = softmax(rng.normal(size=(nF, T)), axis=1).astype(np.float32)
+    w = rng.normal(size=(T, C)).astype(np.float32)
+    gx = rng.normal(size=(N, C)).astype(np.float32)
+    print(f"f2v {name} C={C} T={T}", flush=True)
+    off, cor = ctx.picasso_vertex_corner_csr(dev(F), N)
+    deg = int(np.bincount(F.reshape(-1), minlength=N).max())
+    x = ctx.picasso_f2v_forward(dev(y), dev(pi), dev(w), off, cor, N)
+    _close(x, oracle.f2v_forward(y, pi, w, F, N), (T + 2) * deg, oracle.f2v_forward(np.abs(y), pi, np.abs(w), F, N), "x")
+    gy, gw, gpi = ctx.picasso_f2v_backward(dev(gx), dev(y), dev(pi), dev(w), dev(F), off)
+    gy_r, gw_r, gpi_r = oracle.f2v_backward(gx, y, pi, w, F)
+    gy_a, gw_a, gpi_a = oracle.f2v_backward(np.abs(gx), np.abs(y), pi, np.abs(w), F)
+    _close(gy, gy_r, T + 8, gy_a, "gy")
+    _close(gw, gw_r, _gw_terms(nF, 6), gw_a, "gw")
+    _close(gpi, gpi_r, 6 * C, gpi_a, "gpi")
+
+
+def test_room115k_convolutions_at_full_size(pk, ctx, oracle):
+    """Sampled outputs at the size the benchmark times (the oracle evaluates rows one by one)."""
+    cfg = meshgen.config("room115k")
+    V, F = cfg["verts"], cfg["facets"]
+    N, nF, C, T = V.shape[0], F.shape[0], 32, 6
+    rng = np.random.default_rng(0)
+    x = rng.normal(size=(N, C)).astype(np.float32)
+    w3 = rng.normal(size=(3, C)).astype(np.float32)
+    wt = rng.normal(size=(T, C)).astype(np.float32)
+    off, cor = ctx.picasso_vertex_corner_csr(dev(F), N)
+    off_r, cor_r = oracle.vertex_corner_csr(F, N)
+    assert np.array_equal(off.cpu().numpy(), off_r) and np.array_equal(cor.cpu().numpy(), cor_r)
+    nrm, area, lev = ctx.picasso_facet_geometry(dev(V), dev(F))
+    n_r, a_r = oracle.facet_geometry(V, F)
+    assert np.array_equal(area.cpu().numpy().view(np.uint32), a_r.view(np.uint32))
+    lev_r = oracle.facet_levels(a_r)
+    assert np.array_equal(lev.cpu().numpy(), lev_r)
+    mu = np.array([[1, 0, 0], [-1, 0, 0], [0, 1, 0], [0, -1, 0], [0, 0, 1], [0, 0, -1]], np.float32)
+    pi = ctx.picasso_fuzzy_coefficients(nrm, dev(mu), dev(np.full(T, 2.0, np.float32)))
+    y = ctx.picasso_v2f_forward(dev(x), dev(F), lev, dev(w3))
+    _close(y, oracle.v2f_forward(x, F, lev_r, w3), 9, oracle.v2f_forward(np.abs(x), F, lev_r, np.abs(w3)), "y")
+    yh, pih = y.cpu().numpy(), pi.cpu().numpy()
+    x2 = ctx.picasso_f2v_forward(y, pi, dev(wt), off, cor, N)
+    _close(x2, oracle.f2v_forward(yh, pih, wt, F, N), (T + 2) * 16, oracle.f2v_forward(np.abs(yh), pih, np.abs(wt), F, N), "x2")
+    gy, gw, _ = ctx.picasso_f2v_backward(dev(x), y, pi, dev(wt), dev(F), off, want_gpi=False)
+    gy_r, gw_r, _ = oracle.f2v_backward(x, yh, pih, wt, F)
+    gy_a, gw_a, _ = oracle.f2v_backward(np.abs(x), np.abs(yh), pih, np.abs(wt), F)
+    _close(gy, gy_r, T + 8, gy_a, "gy")
+    _close(gw, gw_r, _gw_terms(nF, 6), gw_a, "gw")
+    gxx, gw3 = ctx.picasso_v2f_backward(gy, dev(x), dev(F), lev, dev(w3), off, cor)
+    gyh = gy.cpu().numpy()
+    gx_r, gw3_r = oracle.v2f_backward(gyh, x, F, lev_r, w3)
+    gx_a, gw3_a = oracle.v2f_backward(np.abs(gyh), np.abs(x), F, lev_r, np.abs(w3))
+    _close(gxx, gx_r, 4 * 16, gx_a, "gx")
+    _close(gw3, gw3_r, _gw_terms(nF, 4), gw3_a, "gw3")
