@@ -147,3 +147,33 @@ def test_switching_the_option_off_restores_the_default_path(pk, ctx, oracle):
     finally:
         ctx.set_option(pk.PICASSO_OPT_ABSORB, 1)
     _same(st, vo, fo, cid, oracle.decimate(V, F, target))
+
+
+def test_batch_of_16_rooms_with_line_11(pk, oracle):
+    """The 16-mesh batch of the benchmark, first level: per-mesh candidate counts, budgets left and
+    the budget step of line 11 at scale, against the oracle mesh by mesh."""
+    c = meshgen.config("batch16x60k")
+    V, F, nv, nf = c["verts"], c["facets"], c["nv"], c["nf"]
+    ctx = pk.Context(V.shape[0], F.shape[0], 16, device=0)
+    try:
+        ctx.set_option(pk.PICASSO_OPT_ABSORB, 1)
+        tg = (nv.astype(np.int64) * 4 // 10).astype(np.int32)
+        print(f"line11 batch16: N={V.shape[0]} F={F.shape[0]}", flush=True)
+        st, vo, fo, cid, nvo, nfo = ctx.picasso_decimate_batch(dev(V), dev(F), nv, nf, tg)
+        vo, fo, cid = vo.cpu().numpy(), fo.cpu().numpy(), cid.cpu().numpy()
+        voff = np.concatenate([[0], np.cumsum(nv)])
+        foff = np.concatenate([[0], np.cumsum(nf)])
+        v0 = f0 = 0
+        for i in range(16):
+            Vi = V[voff[i]:voff[i + 1]]
+            Fi = F[foff[i]:foff[i + 1]] - voff[i]
+            ref = oracle.decimate(Vi, Fi, int(tg[i]), absorb=True)
+            assert int(nvo[i]) == ref["verts"].shape[0] == int(tg[i]) and int(nfo[i]) == ref["facets"].shape[0], i
+            assert np.array_equal(vo[v0:v0 + nvo[i]].view(np.uint32), ref["verts"].view(np.uint32)), i
+            assert np.array_equal(fo[f0:f0 + nfo[i]], ref["facets"] + v0), i
+            assert np.array_equal(cid[voff[i]:voff[i + 1]], ref["cluster_id"] + v0), i
+            v0 += int(nvo[i])
+            f0 += int(nfo[i])
+        assert st == 0
+    finally:
+        ctx.close()

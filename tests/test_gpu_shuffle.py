@@ -119,3 +119,32 @@ def test_seed_zero_is_the_default_path(pk, ctx, oracle):
     V, F = meshgen.flat_grid(33, 18, spacing=0.5)
     st, vo, fo, cid = _run(pk, ctx, 0, lambda: ctx.picasso_decimate(dev(V), dev(F), V.shape[0] // 4))
     _same(st, vo, fo, cid, oracle.decimate(V, F, V.shape[0] // 4))
+
+
+def test_batch_with_shuffle_meets_every_budget_and_is_reproducible(pk, ctx):
+    """With several meshes in a batch the tie-break runs over the batch's edge numbering, so there is
+    no per-mesh reference; what must hold: every mesh meets its budget exactly, the clusters of a
+    mesh stay inside it, the same seed gives the same bytes, another seed other clusters."""
+    parts = [meshgen.flat_grid(21, 17, spacing=0.25), meshgen.noisy_grid(30, 22, seed=1),
+             meshgen.flat_grid(15, 15, spacing=0.5), meshgen.icosphere(3, seed=2)]
+    nv = [p[0].shape[0] for p in parts]
+    nf = [p[1].shape[0] for p in parts]
+    off = np.cumsum([0] + nv)
+    V = np.concatenate([p[0] for p in parts])
+    F = np.concatenate([p[1] + off[i] for i, p in enumerate(parts)]).astype(np.int32)
+    tg = [nv[0] // 3, nv[1] // 2, nv[2] // 4, nv[3] // 5]
+    runs = {}
+    for seed in (11, 11, 12):
+        for absorb in (0, 1):
+            st, vo, fo, cid, nvo, nfo = _run(pk, ctx, seed, lambda: ctx.picasso_decimate_batch(dev(V), dev(F), nv, nf, tg), absorb)
+            assert st == 0 and nvo.tolist() == tg
+            cid = cid.cpu().numpy()
+            oo = np.cumsum([0] + tg)
+            for i in range(4):
+                part = cid[off[i]:off[i + 1]]
+                assert part.min() == oo[i] and part.max() == oo[i + 1] - 1 and np.unique(part).size == tg[i]
+            key = (seed, absorb)
+            if key in runs:
+                assert np.array_equal(runs[key][0], cid) and np.array_equal(runs[key][1], vo.cpu().numpy())
+            runs[key] = (cid, vo.cpu().numpy())
+    assert not np.array_equal(runs[(11, 0)][0], runs[(12, 0)][0])
