@@ -2488,6 +2488,13 @@ inline bool conv_vec4(int C, std::initializer_list<const void*> ptrs) {
     return true;
 }
 
+// 8 channels per lane where there are enough of them: indices, levels and fuzzy coefficients are then
+// read half as often per channel
+inline int conv_vec(int C, std::initializer_list<const void*> ptrs) {
+    if (!conv_vec4(C, ptrs)) return 1;
+    return (C % 8 == 0 && C >= 32) ? 8 : 4;
+}
+
 // Two-stage sum of ROWS x C filter-gradient rows over n_rows rows (conv::reduce_rows_stage1/2):
 // partial sums in the context's sort buffer.
 template <int ROWS, class Term>
@@ -2867,7 +2874,10 @@ int picasso_v2f_forward(picasso_ctx* c, void* stream, const float* d_x, int32_t 
     if (!c || !d_x || N < 1 || C < 1 || !d_facets || F < 1 || !d_w || !d_y) return PICASSO_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
     HIP_TRY(c, hipSetDevice(c->device));
-    if (conv_vec4(C, {d_x, d_w, d_y}))
+    const int vec = conv_vec(C, {d_x, d_w, d_y});
+    if (vec == 8)
+        conv::v2f_forward_kernel<8><<<pool::grid_for((long long)F * (C / 8)), pool::BLOCK, 0, s>>>(d_x, N, C, d_facets, F, d_level, d_w, d_y);
+    else if (vec == 4)
         conv::v2f_forward_kernel<4><<<pool::grid_for((long long)F * (C / 4)), pool::BLOCK, 0, s>>>(d_x, N, C, d_facets, F, d_level, d_w, d_y);
     else
         conv::v2f_forward_kernel<1><<<pool::grid_for((long long)F * C), pool::BLOCK, 0, s>>>(d_x, N, C, d_facets, F, d_level, d_w, d_y);
@@ -2885,7 +2895,9 @@ int picasso_v2f_backward(picasso_ctx* c, void* stream, const float* d_gy, const 
     HIP_TRY(c, hipSetDevice(c->device));
     const bool vec4 = conv_vec4(C, {d_gy, d_x, d_w, d_gx});
     if (d_gx) {
-        if (vec4)
+        if (conv_vec(C, {d_gy, d_w, d_gx}) == 8)
+            conv::v2f_backward_x_kernel<8><<<pool::grid_for((long long)N * (C / 8)), pool::BLOCK, 0, s>>>(d_gy, C, d_level, d_w, d_offsets, d_corners, N, 3 * F, d_gx);
+        else if (vec4)
             conv::v2f_backward_x_kernel<4><<<pool::grid_for((long long)N * (C / 4)), pool::BLOCK, 0, s>>>(d_gy, C, d_level, d_w, d_offsets, d_corners, N, 3 * F, d_gx);
         else
             conv::v2f_backward_x_kernel<1><<<pool::grid_for((long long)N * C), pool::BLOCK, 0, s>>>(d_gy, C, d_level, d_w, d_offsets, d_corners, N, 3 * F, d_gx);
@@ -2909,10 +2921,14 @@ int picasso_f2v_forward(picasso_ctx* c, void* stream, const float* d_y, int32_t 
     const bool vec4 = conv_vec4(C, {d_y, d_w, d_x});
     const bool lds = (long long)T * C <= conv::F2V_LDS_FLOATS;
     const size_t lds_bytes = lds ? sizeof(float) * (size_t)T * C : 0;
-    const int grid = pool::grid_for((long long)N * (vec4 ? C / 4 : C));
+    const bool vec8 = conv_vec(C, {d_y, d_w, d_x}) == 8;
+    const int grid = pool::grid_for((long long)N * (vec8 ? C / 8 : (vec4 ? C / 4 : C)));
 #define PICASSO_F2V(VEC, LDS) \
     conv::f2v_forward_kernel<VEC, LDS><<<grid, pool::BLOCK, lds_bytes, s>>>(d_y, C, d_pi, T, d_w, d_offsets, d_corners, N, 3 * F, d_x)
-    if (vec4) {
+    if (vec8) {
+        if (lds) PICASSO_F2V(8, true);
+        else PICASSO_F2V(8, false);
+    } else if (vec4) {
         if (lds) PICASSO_F2V(4, true);
         else PICASSO_F2V(4, false);
     } else {
@@ -2934,7 +2950,9 @@ int picasso_f2v_backward(picasso_ctx* c, void* stream, const float* d_gx, const 
     HIP_TRY(c, hipSetDevice(c->device));
     const bool vec4 = conv_vec4(C, {d_gx, d_y, d_w, d_gy});
     if (d_gy) {
-        if (vec4)
+        if (conv_vec(C, {d_gx, d_w, d_gy}) == 8)
+            conv::f2v_backward_y_kernel<8><<<pool::grid_for((long long)F * (C / 8)), pool::BLOCK, 0, s>>>(d_gx, C, d_pi, T, d_w, d_facets, F, d_offsets, N, d_gy);
+        else if (vec4)
             conv::f2v_backward_y_kernel<4><<<pool::grid_for((long long)F * (C / 4)), pool::BLOCK, 0, s>>>(d_gx, C, d_pi, T, d_w, d_facets, F, d_offsets, N, d_gy);
         else
             conv::f2v_backward_y_kernel<1><<<pool::grid_for((long long)F * C), pool::BLOCK, 0, s>>>(d_gx, C, d_pi, T, d_w, d_facets, F, d_offsets, N, d_gy);

@@ -29,6 +29,10 @@ __device__ __forceinline__ Pack<VEC> load_pack(const float* __restrict__ p) {
     if (VEC == 4) {
         const float4 t = *reinterpret_cast<const float4*>(p);
         r.v[0] = t.x; r.v[1 % VEC] = t.y; r.v[2 % VEC] = t.z; r.v[3 % VEC] = t.w;
+    } else if (VEC == 8) {
+        const float4 t = *reinterpret_cast<const float4*>(p), u = *reinterpret_cast<const float4*>(p + 4);
+        r.v[0] = t.x; r.v[1 % VEC] = t.y; r.v[2 % VEC] = t.z; r.v[3 % VEC] = t.w;
+        r.v[4 % VEC] = u.x; r.v[5 % VEC] = u.y; r.v[6 % VEC] = u.z; r.v[7 % VEC] = u.w;
     } else {
 #pragma unroll
         for (int k = 0; k < VEC; ++k) r.v[k] = p[k];
@@ -40,6 +44,9 @@ template <int VEC>
 __device__ __forceinline__ void store_pack(float* __restrict__ p, const Pack<VEC>& r) {
     if (VEC == 4) {
         *reinterpret_cast<float4*>(p) = make_float4(r.v[0], r.v[1 % VEC], r.v[2 % VEC], r.v[3 % VEC]);
+    } else if (VEC == 8) {
+        *reinterpret_cast<float4*>(p) = make_float4(r.v[0], r.v[1 % VEC], r.v[2 % VEC], r.v[3 % VEC]);
+        *reinterpret_cast<float4*>(p + 4) = make_float4(r.v[4 % VEC], r.v[5 % VEC], r.v[6 % VEC], r.v[7 % VEC]);
     } else {
 #pragma unroll
         for (int k = 0; k < VEC; ++k) p[k] = r.v[k];
