@@ -2331,9 +2331,6 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
             }
             sel_k = hst->sel_k;
             const int live = hst->live[0];
-            if (getenv("PICASSO_DEBUG"))
-                fprintf(stderr, "[picasso] round %d: wide=%d sel_k=%d live=%d ne=%d est=%lld\n", round, wide, sel_k, live,
-                        hst->ne, live_est);
             if (live == 0) break;
             live_est = live;
         }
