@@ -177,3 +177,39 @@ def test_batch_of_16_rooms_with_line_11(pk, oracle):
         assert st == 0
     finally:
         ctx.close()
+
+
+def test_many_tiny_meshes_with_line_11(pk, oracle):
+    """1,100 tiny meshes with budgets of every kind: per-mesh candidate counts by binary search over
+    a long mesh table, budget left of 0 in many meshes, one budget workgroup per mesh."""
+    rng = np.random.default_rng(9)
+    parts = []
+    for k in range(1100):
+        nx, ny = int(rng.integers(3, 7)), int(rng.integers(3, 7))
+        parts.append(meshgen.noisy_grid(nx, ny, seed=1000 + k))
+    nv = [p[0].shape[0] for p in parts]
+    nf = [p[1].shape[0] for p in parts]
+    off = np.cumsum([0] + nv)
+    V = np.concatenate([p[0] for p in parts])
+    F = np.concatenate([p[1] + off[i] for i, p in enumerate(parts)]).astype(np.int32)
+    tg = [max(2, int(n * f)) for n, f in zip(nv, rng.uniform(0.2, 1.0, size=len(nv)))]
+    c = pk.Context(V.shape[0], F.shape[0], len(parts), device=0)
+    try:
+        c.set_option(pk.PICASSO_OPT_ABSORB, 1)
+        print(f"line11 batch of {len(parts)}: N={V.shape[0]} F={F.shape[0]}", flush=True)
+        st, vo, fo, cid, nvo, nfo = c.picasso_decimate_batch(dev(V), dev(F), nv, nf, tg)
+        vo, fo, cid = vo.cpu().numpy(), fo.cpu().numpy(), cid.cpu().numpy()
+        v0 = f0 = 0
+        worst = 0
+        for i, (Vi, Fi) in enumerate(parts):
+            ref = oracle.decimate(Vi, Fi, tg[i], absorb=True)
+            worst = max(worst, ref["status"])
+            assert int(nvo[i]) == ref["verts"].shape[0] and int(nfo[i]) == ref["facets"].shape[0], i
+            assert np.array_equal(vo[v0:v0 + nvo[i]].view(np.uint32), ref["verts"].view(np.uint32)), i
+            assert np.array_equal(fo[f0:f0 + nfo[i]], ref["facets"] + v0), i
+            assert np.array_equal(cid[off[i]:off[i + 1]], ref["cluster_id"] + v0), i
+            v0 += int(nvo[i])
+            f0 += int(nfo[i])
+        assert st == worst
+    finally:
+        c.close()
