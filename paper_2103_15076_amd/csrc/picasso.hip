@@ -1261,7 +1261,7 @@ __global__ void trunc_finish_kernel(int B, int* __restrict__ matched, const int*
 // the two founders of a cluster attract: a vertex that joined pulls in nobody.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(BLOCK) void absorb_begin_kernel(u64* __restrict__ abid, int* __restrict__ arep,
-                                                             const State* st, int cur, int B,
+                                                             int* __restrict__ acnt, const State* st, int cur, int B,
                                                              const int* __restrict__ nrem,
                                                              const int* __restrict__ matched, int* __restrict__ arem,
                                                              int* __restrict__ acand) {
@@ -1271,6 +1271,7 @@ __global__ __launch_bounds__(BLOCK) void absorb_begin_kernel(u64* __restrict__ a
     for (int w = g; w < nv; w += stride) {
         abid[w] = ABID_NONE;
         arep[w] = -1;
+        acnt[w] = 0;
     }
     for (int b = g; b < B; b += stride) {
         const int left = nrem[b] - matched[b];
@@ -1335,6 +1336,10 @@ __global__ __launch_bounds__(BLOCK) void absorb_count_kernel(const int* __restri
     for (int b = threadIdx.x; b < B; b += BLOCK) {
         int pos[2];
         for (int side = 0; side < 2; ++side) {
+            if (b + side == 0 || b + side == B) {  // the ends of the list need no search
+                pos[side] = (b + side == 0) ? 0 : n;
+                continue;
+            }
             const int v0 = voff[b + side];
             int lo = 0, hi = n;  // first listed edge whose lower vertex is at or past v0
             while (lo < hi) {
@@ -1355,8 +1360,8 @@ __global__ __launch_bounds__(BLOCK) void absorb_keys_kernel(const int* __restric
                                                             const u64* __restrict__ ekey,
                                                             const u32* __restrict__ ecost, int vbits,
                                                             const int* __restrict__ mate, const u64* __restrict__ abid,
-                                                            int* __restrict__ arep, u64* __restrict__ akey,
-                                                            TieBreak tb) {
+                                                            int* __restrict__ arep, int* __restrict__ acnt,
+                                                            u64* __restrict__ akey, TieBreak tb) {
     const int i = blockIdx.x * BLOCK + threadIdx.x;
     if (i >= st->absorb_n) return;
     const int e = list[i];
@@ -1369,6 +1374,7 @@ __global__ __launch_bounds__(BLOCK) void absorb_keys_kernel(const int* __restric
         const int mo = mate[o];
         const int r = o < mo ? o : mo;
         arep[w] = r;
+        atomicAdd(&acnt[r], 1);  // (so that representatives nobody joined need not look)
         out = ((u64)(u32)r << vbits) | (u64)(u32)w;
     }
     akey[i] = out;
@@ -1407,8 +1413,8 @@ __global__ __launch_bounds__(BLOCK) void contract_kernel(const VRec* __restrict_
                                                          const int* __restrict__ voff_cur, int* __restrict__ voff_nxt,
                                                          int* __restrict__ htab, int hsize,
                                                          u32* __restrict__ msd_hist, float rcond_min,
-                                                         const int* __restrict__ arep, const u64* __restrict__ akey,
-                                                         int vbits) {
+                                                         const int* __restrict__ arep, const int* __restrict__ acnt,
+                                                         const u64* __restrict__ akey, int vbits) {
     const int nv = st->nv[cur];
     const int stride = gridDim.x * BLOCK;
     const int g = blockIdx.x * BLOCK + threadIdx.x;
@@ -1433,7 +1439,7 @@ __global__ __launch_bounds__(BLOCK) void contract_kernel(const VRec* __restrict_
         float4 r0 = a[0], r1 = a[1], r2 = a[2], r3 = a[3];
         if (m >= 0) {
             int j = 0, jend = 0;  // this cluster's part of akey
-            if (ABSORB) {
+            if (ABSORB && acnt[w] > 0) {
                 const int n = st->absorb_n;
                 const u64 first = (u64)(u32)w << vbits;
                 int lo = 0, hi = n;
@@ -1441,8 +1447,8 @@ __global__ __launch_bounds__(BLOCK) void contract_kernel(const VRec* __restrict_
                     const int mid = (lo + hi) >> 1;
                     if (akey[mid] >= first) hi = mid; else lo = mid + 1;
                 }
-                j = jend = lo;
-                while (jend < n && (int)(akey[jend] >> vbits) == w) ++jend;
+                j = lo;
+                jend = min(lo + acnt[w], n);
             }
             if (!ABSORB || j == jend) {
                 const float4* b = reinterpret_cast<const float4*>(&vin[m]);
@@ -1766,6 +1772,7 @@ struct picasso_ctx {
     uint64_t opt_shuffle_seed = 0;  // != 0: pairs of equal cost in the order of the seeded tie-break
     u64* abid = nullptr;   // per vertex: cheapest edge through which it could join a pair's cluster
     int* arep = nullptr;   // per vertex: representative of the cluster it joined, or -1
+    int* acnt = nullptr;   // per vertex: how many vertices joined the cluster it represents
     int* acand = nullptr;  // per mesh: vertices that could join
     int* arem = nullptr;   // per mesh: budget left after the pairs
     int64_t kt_calls = 0;           // decimate calls since the option was set
@@ -1863,6 +1870,7 @@ size_t carve(picasso_ctx* c, char* base, int64_t N, int64_t F, int32_t B) {
     x->mslots = cv.take<int>(b * MATCH_SLOTS * MATCH_PAD);
     x->abid = cv.take<u64>(n);
     x->arep = cv.take<int>(n);
+    x->acnt = cv.take<int>(n);
     x->acand = cv.take<int>(b);
     x->arem = cv.take<int>(b);
     return cv.off;
@@ -2129,7 +2137,7 @@ int budget_step(picasso_ctx* c, hipStream_t s, Over over, int B, int ne, int vbi
 int run_absorb(picasso_ctx* c, hipStream_t s, int B, int cur, int vbits, int ne, int nv_total, const MeshTab& mt,
                const TieBreak& tb, const std::vector<int>& nrem, const std::vector<int>& h_matched, std::vector<int>& h_joined,
                const u64** akeys) {
-    absorb_begin_kernel<<<grid_for(std::max(nv_total, B), 4096), BLOCK, 0, s>>>(c->abid, c->arep, c->st, cur, B, c->nrem,
+    absorb_begin_kernel<<<grid_for(std::max(nv_total, B), 4096), BLOCK, 0, s>>>(c->abid, c->arep, c->acnt, c->st, cur, B, c->nrem,
                                                                               c->matched, c->arem, c->acand);
     absorb_bid_kernel<<<grid_for(std::max(ne, 1), 8192), BLOCK, 0, s>>>(c->ekey, c->ecost, c->st, vbits, c->mate, mt,
                                                                       c->arem, c->abid, tb);
@@ -2159,7 +2167,7 @@ int run_absorb(picasso_ctx* c, hipStream_t s, int B, int cur, int vbits, int ne,
         if (rc != PICASSO_OK) return rc;
     }
     absorb_keys_kernel<<<grid_for(n_list), BLOCK, 0, s>>>(c->list, c->st, c->ekey, c->ecost, vbits, c->mate, c->abid,
-                                                         c->arep, c->key64[0], tb);
+                                                         c->arep, c->acnt, c->key64[0], tb);
     const int where = sort_by_vertex<u64, false>(s, c->key64[0], c->key64[1], nullptr, nullptr, &c->st->absorb_n,
                                                  (int)n_list, 2 * vbits, c->sort_sc, c->hist12);
     if (where < 0) return PICASSO_ERR_HIP;
@@ -2405,7 +2413,7 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
 #define PICASSO_CONTRACT(PLACE, ABSORB, RCOND)                                                                       \
     contract_kernel<PLACE, ABSORB><<<cgrid, BLOCK, 0, s>>>(c->vrec[cur], c->vrec[nxt], c->mate, c->newid, c->vmap,    \
                                                            c->st, cur, B, c->voff[cur], c->voff[nxt], c->htab,        \
-                                                           (int)hsize, c->hist12, RCOND, c->arep, akeys, vbits)
+                                                           (int)hsize, c->hist12, RCOND, c->arep, c->acnt, akeys, vbits)
         if (c->opt_placement == PLACE_INVERSE) {
             if (n_joined > 0) PICASSO_CONTRACT(PLACE_INVERSE, true, c->opt_rcond_min);
             else PICASSO_CONTRACT(PLACE_INVERSE, false, c->opt_rcond_min);
