@@ -57,8 +57,8 @@ def main():
                     help="keep the first round's edge sort on the caller's stream (PICASSO_OPT_OVERLAP = 0)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build measures ONE GPU only (the path shards by mesh; see DESIGN.md); "
-              "run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build measures ONE GPU only (the path shards by mesh: with more GPUs every rank "
+              "would decimate its own meshes, with no exchange); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
