@@ -1,12 +1,8 @@
-// picasso.hip -- round-based QEM mesh decimation for gfx950 behind the C-ABI of
-// include/picasso.h.  Follows Algorithm 2 of the Picasso paper (Sec. 3) and
-// the quadric equations of its supplementary section "Quadric error
-// computation"; the greedy grouping that the paper leaves on the CPU
-// (Alg. 2 lines 3-10) is done here on the GPU by a parallel construction of
-// the same matching.
-//
-// All fp32 arithmetic is written as single IEEE operations in a fixed order
-// and compiled without contraction, so that results are reproducible to the bit.
+// picasso.hip -- host side of the library behind the C-ABI of include/picasso.h:
+// the context and its workspace, the round loop of the decimation (Algorithm 2
+// of the Picasso paper, Sec. 3; kernels in decimate_kernels.h), and the entry
+// points, including those of pooling (pooling.h) and the mesh convolutions
+// (conv.h).
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
@@ -20,1670 +16,13 @@
 
 #include "../../include/picasso.h"
 #include "primitives.h"
+#include "decimate_kernels.h"
 #include "pooling.h"
 #include "conv.h"
 
 #pragma clang fp contract(off)
 
-using prim::u32;
-using prim::u64;
-
 namespace {
-
-constexpr int BLOCK = prim::BLOCK;
-constexpr u64 VMIN_NONE = ~0ull;
-
-// ---------------------------------------------------------------------------
-// Device-resident bookkeeping
-// ---------------------------------------------------------------------------
-struct State {
-    int err;       // bit0: bad facet index, bit1: non-finite coordinate
-    int nv[2];     // vertex count, ping-pong by round parity
-    int nf[2];     // facet count, ping-pong
-    int nh;        // 3 * nf of the current round (half-edge keys to sort)
-    int ne;        // distinct edges of the current round
-    int live[3];   // worklist lengths of the selection sub-rounds (rotating)
-    int trunc_n;   // matched edges entering the budget truncation
-    int sel_k;     // sub-round index the selection has reached (buffer rotation phase)
-    int absorb_n;  // edges through which an un-paired vertex would join a pair's cluster (Alg. 2 line 11)
-    int pad[3];
-};
-
-// One vertex = 64 bytes: position and the 10 quadric coefficients.
-struct __attribute__((aligned(16))) VRec {
-    float x, y, z, w0;
-    float a00, a01, a02, a11;
-    float a12, a22, b0, b1;
-    float b2, c, w1, w2;
-};
-
-constexpr int MATCH_SLOTS = 32;
-constexpr int MATCH_PAD = 32;  // ints: one 128-byte line per slot
-
-struct MeshTab {       // per-mesh tables, all device pointers, B entries (+1 for offsets)
-    int B;
-    const int* voff;   // [B+1] current vertex offsets
-    const int* target; // [B]
-    const int* active; // [B] mesh takes part in this round
-    const int* nrem;   // [B] pairs still to contract (budget of Alg. 2 line 4)
-    int* matched;      // [B] pairs formed this round
-    int* mslots;       // [B][MATCH_SLOTS][MATCH_PAD] partial pair counts, spread over cache lines so that
-                       // the counting atomics of thousands of waves do not queue on one address
-};
-
-__device__ __forceinline__ int mesh_of(const int* __restrict__ voff, int B, int v) {
-    if (B <= 1) return 0;
-    int lo = 0, hi = B;  // invariant: voff[lo] <= v < voff[hi]
-    while (hi - lo > 1) {
-        int mid = (lo + hi) >> 1;
-        if (voff[mid] <= v) lo = mid; else hi = mid;
-    }
-    return lo;
-}
-
-__device__ __forceinline__ u32 cost_key(float c) {
-    u32 u = __float_as_uint(c);
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
-// Order among pairs of equal cost (Alg. 2 line 3; Sec. 3, footnote on the shuffle inserted into the
-// sorting): by edge index, or with a seed by a seeded bijection of the 32-bit integers applied to
-// the edge index, so that flat regions are clustered differently from epoch to epoch.  Every step
-// of enc() is invertible (xor with a constant, multiplication by an odd number, xor with a right
-// shift of itself, addition of a constant); dec() undoes them in reverse.
-constexpr u32 inverse_mod_2_32(u32 a) {
-    u32 x = a;  // correct to 3 bits for odd a; each step doubles the number of correct bits
-    for (int i = 0; i < 5; ++i) x *= 2u - a * x;
-    return x;
-}
-constexpr u32 TIE_M1 = 0x9E3779B1u, TIE_M2 = 0x85EBCA77u;
-constexpr u32 TIE_M1_INV = inverse_mod_2_32(TIE_M1), TIE_M2_INV = inverse_mod_2_32(TIE_M2);
-static_assert(TIE_M1 * TIE_M1_INV == 1u && TIE_M2 * TIE_M2_INV == 1u, "modular inverses");
-
-struct TieBreak {
-    u32 on, s0, s1;
-    __device__ __forceinline__ u32 enc(u32 e) const {
-        if (!on) return e;
-        u32 x = e ^ s0;
-        x *= TIE_M1;
-        x ^= x >> 15;
-        x *= TIE_M2;
-        x ^= x >> 13;
-        return x + s1;
-    }
-    __device__ __forceinline__ u32 dec(u32 x) const {
-        if (!on) return x;
-        x -= s1;
-        x ^= x >> 13;
-        x ^= x >> 26;
-        x *= TIE_M2_INV;
-        x ^= x >> 15;
-        x ^= x >> 30;
-        x *= TIE_M1_INV;
-        return x ^ s0;
-    }
-    __device__ __forceinline__ u64 priority(u32 cost_key_, int e) const { return ((u64)cost_key_ << 32) | enc((u32)e); }
-};
-
-// The same for the kernels every round runs, where the choice is made at compile time so that
-// the path without shuffle carries no test of it.
-template <bool SHUFFLE>
-__device__ __forceinline__ u64 edge_priority(const TieBreak& tb, u32 cost_key_, int e) {
-    if constexpr (SHUFFLE) return tb.priority(cost_key_, e);
-    return ((u64)cost_key_ << 32) | (u32)e;
-}
-template <bool SHUFFLE>
-__device__ __forceinline__ u32 edge_of_priority(const TieBreak& tb, u64 p) {
-    if constexpr (SHUFFLE) return tb.dec((u32)p);
-    return (u32)p;
-}
-
-// ---------------------------------------------------------------------------
-// S0: vertex quadrics (supplementary: facet quadric Q=(nn^T, dn, d^2); vertex
-// quadric = sum over adjacent facets, here in ascending facet order)
-// ---------------------------------------------------------------------------
-
-// Validates and copies the inputs into the workspace; emits the (vertex,
-// incidence) pairs whose stable sort is the vertex->facet CSR.
-enum { COUNT_NONE = 0, COUNT_SMALL = 1, COUNT_LARGE = 2 };
-
-// Incidence key of corner i of the facet array: (vertex << fbits) | facet.
-struct IncidenceKeys {
-    const int* fcur;
-    int fbits;
-    __device__ __forceinline__ u64 operator()(long long i) const {
-        return ((u64)(u32)fcur[i] << fbits) | (u64)(u32)(i / 3);
-    }
-};
-
-// Edge key of corner i of the facet array: the side from corner i to the facet's next corner as
-// (lower vertex << vbits) | higher vertex; a side with equal ends gets the all-ones key.
-struct EdgeKeys {
-    const int* fcur;
-    int vbits;
-    u64 sentinel;
-    __device__ __forceinline__ u64 operator()(long long i) const {
-        const long long f = i / 3;
-        const int sl = (int)(i - 3 * f);
-        const int a = fcur[i], b = fcur[3 * f + (sl == 2 ? 0 : sl + 1)];
-        const int lo = min(a, b), hi = max(a, b);
-        return (lo == hi) ? sentinel : (((u64)(u32)lo << vbits) | (u64)(u32)hi);
-    }
-};
-
-// Incidence keys for S0: (vertex << fbits) | facet, one per facet corner, so that sorting the keys
-// alone lists every vertex's facets in ascending facet order.  With COUNT_SMALL / COUNT_LARGE the
-// kernel also adds the keys' top 8- / 12-bit digits (bits [ishift, ...)) to ihist, the histogram
-// that the sort of the keys starts from (zero on entry; see quadric_reduce_kernel); that sort makes
-// the keys again from the validated facet array (IncidenceKeys), so they are written out (ikey)
-// only for a sort that needs them in memory.
-template <int COUNT>
-__global__ __launch_bounds__(BLOCK) void init_kernel(const float* __restrict__ verts, int N,
-                                                     const int* __restrict__ facets, int F, int B,
-                                                     const int* __restrict__ voff, const int* __restrict__ foff,
-                                                     VRec* __restrict__ vrec, int* __restrict__ cid,
-                                                     int* __restrict__ fcur, u64* __restrict__ ikey, int fbits,
-                                                     int ishift, u32* __restrict__ ihist, State* st,
-                                                     u32* __restrict__ msd_hist, int s0_follows) {
-    constexpr int RADIX = COUNT == COUNT_LARGE ? (1 << prim::BUCKET_LARGE_MSD_BITS) : (1 << prim::BUCKET_MSD_BITS);
-    __shared__ u32 hist[COUNT != COUNT_NONE ? RADIX : 1];
-    const int stride = gridDim.x * BLOCK;
-    const int g = blockIdx.x * BLOCK + threadIdx.x;
-    // the edge-key sort's digit counts and cursors start every round at zero (see edge_keys_kernel)
-    for (int i = g; i < 2 * prim::MSD_HIST_WORDS; i += stride) msd_hist[i] = 0;
-    if constexpr (COUNT != COUNT_NONE) {
-        for (int i = threadIdx.x; i < RADIX; i += BLOCK) hist[i] = 0;
-        __syncthreads();
-    }
-    int err = 0;
-    for (int w = g; w < N; w += stride) {
-        float x = verts[3 * (size_t)w], y = verts[3 * (size_t)w + 1], z = verts[3 * (size_t)w + 2];
-        if (!(isfinite(x) && isfinite(y) && isfinite(z))) err |= 2;
-        if (!s0_follows) {  // (else quadric_reduce_kernel writes the whole record)
-            VRec r;
-            r.x = x; r.y = y; r.z = z; r.w0 = 0.f;
-            r.a00 = r.a01 = r.a02 = r.a11 = r.a12 = r.a22 = r.b0 = r.b1 = r.b2 = r.c = r.w1 = r.w2 = 0.f;
-            vrec[w] = r;
-        }
-        cid[w] = w;
-    }
-    for (int f0 = blockIdx.x * BLOCK; f0 < F; f0 += stride) {  // (whole waves, for the ballots below)
-        const int f = f0 + threadIdx.x;
-        const bool ok = f < F;
-        int lo = 0, hi = 0;
-        if (ok) {
-            const int m = mesh_of(foff, B, f);
-            lo = voff[m];
-            hi = voff[m + 1];
-        }
-#pragma unroll
-        for (int c = 0; c < 3; ++c) {
-            u64 k = 0;
-            if (ok) {
-                int a = facets[3 * (size_t)f + c];
-                if (a < lo || a >= hi) { err |= 1; a = lo; }
-                fcur[3 * (size_t)f + c] = a;
-                k = ((u64)(u32)a << fbits) | (u64)(u32)f;
-                if (ikey) ikey[3 * (size_t)f + c] = k;
-            }
-            if constexpr (COUNT != COUNT_NONE) {
-                // neighbouring facets mostly refer to vertices with the same leading bits: a wave
-                // whose keys all have one digit counts itself with a single LDS atomic
-                const u32 d = (u32)(k >> ishift) & (u32)(RADIX - 1);
-                const u64 on = __ballot(ok);
-                if (on != 0) {
-                    const u32 d0 = (u32)__builtin_amdgcn_readfirstlane((int)d);
-                    if (__ballot(ok && d == d0) == on) {
-                        if (ok && (on & prim::lanemask_lt()) == 0) atomicAdd(&hist[d0], (u32)__popcll(on));
-                    } else if (ok) {
-                        atomicAdd(&hist[d], 1u);
-                    }
-                }
-            }
-        }
-    }
-    if constexpr (COUNT != COUNT_NONE) {
-        __syncthreads();
-        for (int i = threadIdx.x; i < RADIX; i += BLOCK) {
-            const u32 c = hist[i];
-            if (c) atomicAdd(&ihist[i], c);
-        }
-    }
-    if (err) atomicOr(&st->err, err);
-}
-
-// off[v] = first position of row v = key >> fbits in the sorted keys (CSR row starts)
-template <typename K>
-__global__ __launch_bounds__(BLOCK) void csr_offsets_kernel(const K* __restrict__ skey, int fbits, int H, int N,
-                                                            int* __restrict__ off) {
-    const int i = blockIdx.x * BLOCK + threadIdx.x;
-    if (i >= H) return;
-    const int k = (int)(skey[i] >> fbits);
-    const int kp = i ? (int)(skey[i - 1] >> fbits) : -1;
-    for (int v = kp + 1; v <= k; ++v) off[v] = i;
-    if (i == H - 1)
-        for (int v = k + 1; v <= N; ++v) off[v] = H;
-}
-
-struct Quadric10 {
-    float q[10];
-};
-
-// Positions come from the caller's packed [N,3] array (12-byte stride), not from the 64-byte
-// vertex records: the three gathers per incidence then touch five times fewer cache lines.
-__device__ __forceinline__ Quadric10 facet_quadric(const float* __restrict__ verts, int i0, int i1, int i2) {
-    Quadric10 Q;
-#pragma unroll
-    for (int k = 0; k < 10; ++k) Q.q[k] = 0.0f;
-    if (i0 == i1 || i1 == i2 || i0 == i2) return Q;
-    const float3 p0 = make_float3(verts[3 * (size_t)i0], verts[3 * (size_t)i0 + 1], verts[3 * (size_t)i0 + 2]);
-    const float3 p1 = make_float3(verts[3 * (size_t)i1], verts[3 * (size_t)i1 + 1], verts[3 * (size_t)i1 + 2]);
-    const float3 p2 = make_float3(verts[3 * (size_t)i2], verts[3 * (size_t)i2 + 1], verts[3 * (size_t)i2 + 2]);
-    float ax = p1.x - p0.x, ay = p1.y - p0.y, az = p1.z - p0.z;
-    float bx = p2.x - p0.x, by = p2.y - p0.y, bz = p2.z - p0.z;
-    float nx = ay * bz - az * by;
-    float ny = az * bx - ax * bz;
-    float nz = ax * by - ay * bx;
-    float len = sqrtf((nx * nx + ny * ny) + nz * nz);
-    if (len == 0.0f) return Q;
-    nx = nx / len;
-    ny = ny / len;
-    nz = nz / len;
-    float d = -((nx * p0.x + ny * p0.y) + nz * p0.z);
-    Q.q[0] = nx * nx; Q.q[1] = nx * ny; Q.q[2] = nx * nz;
-    Q.q[3] = ny * ny; Q.q[4] = ny * nz; Q.q[5] = nz * nz;
-    Q.q[6] = d * nx;  Q.q[7] = d * ny;  Q.q[8] = d * nz;
-    Q.q[9] = d * d;
-    return Q;
-}
-
-// Ordered segmented reduction: one lane per vertex walks its CSR row in
-// ascending incidence order and adds the facet quadrics left to right.
-__global__ __launch_bounds__(BLOCK) void quadric_reduce_kernel(VRec* __restrict__ vrec,
-                                                               const float* __restrict__ verts, int N,
-                                                               const int* __restrict__ fcur,
-                                                               const int* __restrict__ off,
-                                                               const u64* __restrict__ inc, int fbits,
-                                                               u32* __restrict__ ihist) {
-    const int w = blockIdx.x * BLOCK + threadIdx.x;
-    // last kernel of S0: the incidence sort's digit counts and cursors go back to zero for the next call
-    for (int i = w; i < 2 * prim::MSD_HIST_WORDS; i += gridDim.x * BLOCK) ihist[i] = 0;
-    if (w >= N) return;
-    float acc[10];
-#pragma unroll
-    for (int k = 0; k < 10; ++k) acc[k] = 0.0f;
-    if (off) {
-        const int s = off[w], e = off[w + 1];
-        for (int j = s; j < e; ++j) {
-            const int f = (int)(inc[j] & ((1ull << fbits) - 1ull));
-            const Quadric10 Q = facet_quadric(verts, fcur[3 * (size_t)f], fcur[3 * (size_t)f + 1], fcur[3 * (size_t)f + 2]);
-#pragma unroll
-            for (int k = 0; k < 10; ++k) acc[k] = acc[k] + Q.q[k];
-        }
-    }
-    float4* r = reinterpret_cast<float4*>(&vrec[w]);
-    r[0] = make_float4(verts[3 * (size_t)w], verts[3 * (size_t)w + 1], verts[3 * (size_t)w + 2], 0.f);
-    r[1] = make_float4(acc[0], acc[1], acc[2], acc[3]);
-    r[2] = make_float4(acc[4], acc[5], acc[6], acc[7]);
-    r[3] = make_float4(acc[8], acc[9], 0.f, 0.f);
-}
-
-// ---------------------------------------------------------------------------
-// Round set-up
-// ---------------------------------------------------------------------------
-struct RoundTab {
-    int B;
-    const int* voff;
-    const int* target;
-    int* active;
-    int* stuck;
-    int* nrem;
-    int* matched;
-    int* mslots;
-    int first_round;
-};
-
-// Per-mesh budgets and the round's counters, by one workgroup.
-__device__ __forceinline__ void round_begin_block(const RoundTab& R, int cur, State* st) {
-    for (int i = threadIdx.x; i < R.B * MATCH_SLOTS; i += blockDim.x) R.mslots[(size_t)i * MATCH_PAD] = 0;
-    for (int b = threadIdx.x; b < R.B; b += blockDim.x) {
-        const int nvb = R.voff[b + 1] - R.voff[b];
-        if (!R.first_round && R.active[b] && R.matched[b] == 0) R.stuck[b] = 1;
-        const int act = (nvb > R.target[b]) && !R.stuck[b];
-        R.active[b] = act;
-        R.nrem[b] = act ? nvb - R.target[b] : 0;
-        R.matched[b] = 0;
-    }
-    if (threadIdx.x == 0) {
-        st->nh = 3 * st->nf[cur];
-        st->ne = 0;
-        st->live[0] = 0;
-        st->live[1] = 0;
-        st->live[2] = 0;
-        st->trunc_n = 0;
-        st->sel_k = 0;
-        st->absorb_n = 0;
-    }
-}
-
-// ---------------------------------------------------------------------------
-// S1: candidate pairs = distinct mesh edges (Alg. 2 line 1)
-//
-// First kernel of a round: the round's set-up (block 0), the per-vertex selection state, and one
-// 64-bit key (lower vertex, higher vertex) per half-edge, key i for corner i of the facet array.
-// With COUNT_SMALL / COUNT_LARGE the kernel also adds the keys' top 8- / 12-bit digits to the
-// histogram that the sort of the keys starts from (prim::bucket_sort / prim::bucket_sort_large
-// with `counted`; zeroed beforehand), so the sort needs no counting pass of its own.
-// ---------------------------------------------------------------------------
-template <int COUNT>
-__global__ __launch_bounds__(BLOCK) void edge_keys_kernel(const int* __restrict__ fcur, State* st, int cur, int vbits,
-                                                          u64* __restrict__ keys, u64* __restrict__ vmin0,
-                                                          u64* __restrict__ vmin1, int* __restrict__ mate,
-                                                          RoundTab R, int shift, u32* __restrict__ msd_hist) {
-    constexpr int ITEMS = COUNT == COUNT_LARGE ? prim::SORT_ITEMS_BIG : prim::SORT_ITEMS_SMALL;
-    constexpr int TILE = BLOCK * ITEMS;
-    constexpr int RADIX = COUNT == COUNT_LARGE ? (1 << prim::BUCKET_LARGE_MSD_BITS) : (1 << prim::BUCKET_MSD_BITS);
-    __shared__ u32 hist[COUNT != COUNT_NONE ? RADIX : 1];
-    const int nf = st->nf[cur], nv = st->nv[cur];
-    const long long n = 3ll * nf;
-    const int stride = gridDim.x * BLOCK;
-    const int t = threadIdx.x, g = blockIdx.x * BLOCK + t;
-    const u64 sentinel = (vbits >= 32) ? ~0ull : ((1ull << (2 * vbits)) - 1ull);
-    for (int w = g; w < nv; w += stride) {
-        vmin0[w] = VMIN_NONE;
-        vmin1[w] = VMIN_NONE;
-        mate[w] = -1;
-    }
-    if (blockIdx.x == 0) round_begin_block(R, cur, st);
-    for (long long tile = blockIdx.x; tile * TILE < n; tile += gridDim.x) {
-        if constexpr (COUNT != COUNT_NONE) {
-            for (int i = t; i < RADIX; i += BLOCK) hist[i] = 0;
-            __syncthreads();
-        }
-#pragma unroll 4
-        for (int i = 0; i < ITEMS; ++i) {
-            const long long idx = tile * TILE + (long long)i * BLOCK + t;
-            const bool ok = idx < n;
-            u64 k = 0;
-            if (ok) {
-                k = EdgeKeys{fcur, vbits, sentinel}(idx);
-                if (keys) keys[idx] = k;  // (the counted sorts make the keys again from fcur)
-            }
-            if constexpr (COUNT != COUNT_NONE) {
-                // the lower vertices of neighbouring corners mostly share their leading bits: a wave
-                // whose keys all have one digit counts itself with a single LDS atomic
-                const u32 d = (u32)(k >> shift) & (u32)(RADIX - 1);
-                const u64 on = __ballot(ok);
-                if (on != 0) {
-                    const u32 d0 = (u32)__builtin_amdgcn_readfirstlane((int)d);
-                    if (__ballot(ok && d == d0) == on) {
-                        if (ok && (on & prim::lanemask_lt()) == 0) atomicAdd(&hist[d0], (u32)__popcll(on));
-                    } else if (ok) {
-                        atomicAdd(&hist[d], 1u);
-                    }
-                }
-            }
-        }
-        if constexpr (COUNT != COUNT_NONE) {
-            __syncthreads();
-            for (int i = t; i < RADIX; i += BLOCK) {
-                const u32 c = hist[i];
-                if (c) atomicAdd(&msd_hist[i], c);
-            }
-            __syncthreads();
-        }
-    }
-}
-
-struct UniquePred {
-    const u64* keys;
-    u64 sentinel;
-    __device__ bool operator()(int i) const {
-        const u64 k = keys[i];
-        return k != sentinel && (i == 0 || k != keys[i - 1]);
-    }
-};
-
-// Where a pair is contracted to.
-enum { PLACE_MEAN = 0, PLACE_INVERSE = 1 };
-
-// Point of least quadric error, the solution of A x = -b (supplementary,
-// inverse placement equation), for a positive semi-definite A = sum of n n^T.
-// The three axes are eliminated in the order of the largest remaining diagonal
-// entry (P A P^T = L D L^T); A counts as of full rank when all three pivots are
-// positive and the last exceeds rcond_min times the first, their ratio standing
-// for the reciprocal condition number.  Returns false, leaving (x, y, z) as
-// they are, when A is not of full rank or the solution is not finite.
-__device__ __forceinline__ bool quadric_minimiser(float a00, float a01, float a02, float a11, float a12, float a22,
-                                                  float b0, float b1, float b2, float rcond_min, float& x, float& y,
-                                                  float& z) {
-    float r0 = -b0, r1 = -b1, r2 = -b2, t;
-    int first = 0;
-    float top = a00;
-    if (a11 > top) { first = 1; top = a11; }
-    if (a22 > top) { first = 2; top = a22; }
-    if (first == 1) {  // axes 0 and 1 change places
-        t = a00; a00 = a11; a11 = t;
-        t = a02; a02 = a12; a12 = t;
-        t = r0; r0 = r1; r1 = t;
-    } else if (first == 2) {  // axes 0 and 2 change places
-        t = a00; a00 = a22; a22 = t;
-        t = a01; a01 = a12; a12 = t;
-        t = r0; r0 = r2; r2 = t;
-    }
-    const float d1 = a00;
-    if (!(d1 > 0.0f)) return false;
-    float l1 = a01 / d1, l2 = a02 / d1;
-    float s11 = a11 - (a01 * a01) / d1;
-    const float s12 = a12 - (a01 * a02) / d1;
-    float s22 = a22 - (a02 * a02) / d1;
-    const bool flip = s22 > s11;  // the larger entry of the remaining block goes next
-    if (flip) {
-        t = s11; s11 = s22; s22 = t;
-        t = l1; l1 = l2; l2 = t;
-        t = r1; r1 = r2; r2 = t;
-    }
-    const float d2 = s11;
-    if (!(d2 > 0.0f)) return false;
-    const float l3 = s12 / d2;
-    const float d3 = s22 - l3 * s12;
-    if (!(d3 > 0.0f) || !(d3 > rcond_min * d1)) return false;
-    const float y1 = r1 - l1 * r0;
-    const float y2 = (r2 - l2 * r0) - l3 * y1;
-    float w2 = y2 / d3;
-    float w1 = y1 / d2 - l3 * w2;
-    float w0 = (r0 / d1 - l1 * w1) - l2 * w2;
-    if (flip) { t = w1; w1 = w2; w2 = t; }
-    if (first == 1) { t = w0; w0 = w1; w1 = t; }
-    else if (first == 2) { t = w0; w0 = w2; w2 = t; }
-    if (!isfinite(w0) || !isfinite(w1) || !isfinite(w2)) return false;
-    x = w0; y = w1; z = w2;
-    return true;
-}
-
-// S2: cost of a pair = quadric error of the summed quadric at the point the
-// pair would be contracted to: the pair's mean, or with PLACE_INVERSE the point
-// of least error where the quadric has one (Alg. 2 line 2; supplementary
-// Q(x) = x^T A x + 2 b^T x + c and the two placement equations).
-template <int PLACE>
-__device__ __forceinline__ float pair_cost(const VRec* __restrict__ vrec, int u, int v, float rcond_min) {
-    const float4* ru = reinterpret_cast<const float4*>(&vrec[u]);
-    const float4* rv = reinterpret_cast<const float4*>(&vrec[v]);
-    const float4 u0 = ru[0], u1 = ru[1], u2 = ru[2], u3 = ru[3];
-    const float4 v0 = rv[0], v1 = rv[1], v2 = rv[2], v3 = rv[3];
-    const float a00 = u1.x + v1.x, a01 = u1.y + v1.y, a02 = u1.z + v1.z, a11 = u1.w + v1.w;
-    const float a12 = u2.x + v2.x, a22 = u2.y + v2.y, b0 = u2.z + v2.z, b1 = u2.w + v2.w;
-    const float b2 = u3.x + v3.x, c = u3.y + v3.y;
-    float mx = (u0.x + v0.x) * 0.5f;
-    float my = (u0.y + v0.y) * 0.5f;
-    float mz = (u0.z + v0.z) * 0.5f;
-    if (PLACE == PLACE_INVERSE) quadric_minimiser(a00, a01, a02, a11, a12, a22, b0, b1, b2, rcond_min, mx, my, mz);
-    const float t0 = (a00 * mx + a01 * my) + a02 * mz;
-    const float t1 = (a01 * mx + a11 * my) + a12 * mz;
-    const float t2 = (a02 * mx + a12 * my) + a22 * mz;
-    const float xAx = (mx * t0 + my * t1) + mz * t2;
-    const float bx = (b0 * mx + b1 * my) + b2 * mz;
-    return (xAx + 2.0f * bx) + c;
-}
-
-// Bids of the lanes of one wave on their vertices x, where lanes with equal x are neighbours among
-// the lanes that bid (edges are sorted by their lower vertex, so that end of consecutive edges is
-// often the same vertex).  Atomics of one wave on one address are served one after the other, so
-// each such group first takes the minimum of its priorities across lanes and its last lane issues
-// the group's single atomicMin.  Every lane of the wave must call this.
-__device__ __forceinline__ void bid_grouped(u64* __restrict__ vmin, bool on, int x, u64 p) {
-    const int lane = prim::lane_id();
-    const u64 ab = __ballot(on);
-    if (ab == 0) return;
-    const u64 lt = prim::lanemask_lt();
-    const u64 below = ab & lt;
-    const int prev = below ? 63 - __clzll((long long)below) : lane;
-    const int xprev = __shfl(x, prev, 64);
-    const bool head = on && (below == 0 || xprev != x);
-    const u64 hb = __ballot(head);
-    const u64 hle = hb & (lt | (1ull << lane));
-    const int dist = hle ? lane - (63 - __clzll((long long)hle)) : 0;  // lanes back to the group's head
-    u64 q = on ? p : ~0ull;
-    for (int d = 1; d < 64; d <<= 1) {
-        if (!__any(dist >= d)) break;
-        const u64 o = __shfl_up(q, d, 64);
-        if (dist >= d) q = (o < q) ? o : q;
-    }
-    const u64 above = ab & ~(lt | (1ull << lane));
-    const bool tail = on && (above == 0 || ((hb >> (__ffsll((long long)above) - 1)) & 1ull));
-    if (tail) atomicMin(&vmin[x], q);
-}
-
-// Writes the distinct edges, their cost keys, and places each edge's first bid
-// (sub-round 0 of the selection) on both of its vertices.
-template <int PLACE, bool SHUFFLE>
-struct UniqueOutT {
-    static constexpr bool WAVE_WIDE = true;
-    const u64* keys;
-    u64* ekey;
-    u32* ecost;
-    const VRec* vrec;
-    u64* vmin0;
-    unsigned char* estate;
-    int vbits;
-    MeshTab mt;
-    float rcond_min;
-    TieBreak tb;
-    __device__ void wave(int i, bool in_range, bool flagged, int e) const {
-        bool act = false;
-        int u = 0;
-        u64 p = 0;
-        if (flagged) {
-            const u64 k = keys[i];
-            u = (int)(k >> vbits);
-            const int v = (int)(k & ((1ull << vbits) - 1ull));
-            ekey[e] = k;
-            const u32 ck = cost_key(pair_cost<PLACE>(vrec, u, v, rcond_min));
-            ecost[e] = ck;
-            act = mt.active[mesh_of(mt.voff, mt.B, u)] != 0;
-            estate[e] = act ? 0 : 1;
-            p = edge_priority<SHUFFLE>(tb, ck, e);
-            if (act) atomicMin(&vmin0[v], p);
-        }
-        (void)in_range;
-        bid_grouped(vmin0, act, u, p);
-    }
-};
-
-// ---------------------------------------------------------------------------
-// S3: greedy disjoint grouping of Alg. 2 lines 3-10, computed in parallel.
-//
-// Priority of edge e = (cost key, e) packed in 64 bits; the sequential loop of
-// the paper visits edges in ascending priority.  An edge is LIVE while neither
-// end is paired.  A live edge whose priority is the minimum among the live
-// edges at BOTH ends is exactly one the sequential loop accepts, so every
-// sub-round accepts all such edges at once, retires the edges touching newly
-// paired vertices, and lets the survivors bid again.  vmin buffers rotate:
-// sub-round k reads bids in vmin[k%3], places the survivors' bids in
-// vmin[(k+1)%3] and clears their slots in vmin[(k+2)%3].
-// ---------------------------------------------------------------------------
-constexpr int SEL_ITEMS = 1;
-constexpr int SEL_TILE = BLOCK * SEL_ITEMS;
-constexpr int TAIL_THREADS = 1024;
-constexpr int TAIL_MAX = 3584;  // live edges the single-workgroup tail takes over (sized by its LDS state)
-
-struct SelArgs {
-    const u64* ekey;
-    const u32* ecost;
-    u64* vmin[3];
-    int* mate;
-    int* list;              // live edges gathered for the tail
-    unsigned char* estate;  // per edge: 0 = live, 1 = retired (paired, or an end was paired)
-    State* st;
-    MeshTab mt;
-    int vbits;
-    int* host_img;     // pinned host memory, device view: the tail leaves [State][matched] there
-    int publish_ints;  // for the host, which then needs no copy of its own before it looks
-    TieBreak tb;       // order among edges of equal cost
-};
-
-// Bids are read with device-scope atomic loads where the same kernel also
-// changes them (the tail), with plain loads otherwise.
-template <bool COHERENT>
-__device__ __forceinline__ u64 load_bid(const u64* p) {
-    if (COHERENT) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return *p;
-}
-
-template <bool COHERENT, bool SHUFFLE>
-__device__ __forceinline__ bool vertex_pairs_now(const u64* __restrict__ cur, const u64* __restrict__ ekey, int vbits,
-                                                 const TieBreak& tb, int x, u64 mx) {
-    // The best live edge at x is accepted in this sub-round iff it is also the best at its other end.
-    if (mx == VMIN_NONE) return false;  // no bid on x (cannot happen for an end of a live edge)
-    const u64 k = ekey[edge_of_priority<SHUFFLE>(tb, mx)];
-    const int a = (int)(k >> vbits), b = (int)(k & ((1ull << vbits) - 1ull));
-    const int other = (a == x) ? b : a;
-    return load_bid<COHERENT>(&cur[other]) == mx;
-}
-
-// One edge of one sub-round.  Returns true if the edge stays live.
-template <bool COHERENT, bool SHUFFLE>
-__device__ __forceinline__ bool subround_edge(const SelArgs& A, const u64* __restrict__ cur, int k, int e, int& u,
-                                              int& v, int& m, u64& p, bool& sel) {
-    const u64 key = A.ekey[e];
-    u = (int)(key >> A.vbits);
-    v = (int)(key & ((1ull << A.vbits) - 1ull));
-    p = edge_priority<SHUFFLE>(A.tb, A.ecost[e], e);
-    m = mesh_of(A.mt.voff, A.mt.B, u);
-    sel = false;
-    if (k == 0 && !A.mt.active[m]) return false;
-    const u64 mu = load_bid<COHERENT>(&cur[u]), mv = load_bid<COHERENT>(&cur[v]);
-    if (mu == p && mv == p) {
-        sel = true;
-        A.mate[u] = v;
-        A.mate[v] = u;
-        return false;
-    }
-    return !(vertex_pairs_now<COHERENT, SHUFFLE>(cur, A.ekey, A.vbits, A.tb, u, mu) ||
-             vertex_pairs_now<COHERENT, SHUFFLE>(cur, A.ekey, A.vbits, A.tb, v, mv));
-}
-
-// pairs formed, counted per mesh: one atomic per wave and mesh
-__device__ __forceinline__ void count_pairs(const SelArgs& A, bool sel, int m) {
-    const int lane = prim::lane_id();
-    u64 sb = __ballot(sel);
-    while (sb) {
-        const int leader = __ffsll((long long)sb) - 1;
-        const int m0 = __shfl(m, leader, 64);
-        const u64 same = __ballot(sel && m == m0);
-        if (lane == leader)
-            atomicAdd(&A.mt.mslots[((size_t)m0 * MATCH_SLOTS + (blockIdx.x & (MATCH_SLOTS - 1))) * MATCH_PAD],
-                      (int)__popcll(same));
-        sb &= ~same;
-    }
-}
-
-// The same into an LDS array (one workgroup's own tally).
-__device__ __forceinline__ void count_pairs_lds(int* pairs, bool sel, int m) {
-    const int lane = prim::lane_id();
-    u64 sb = __ballot(sel);
-    while (sb) {
-        const int leader = __ffsll((long long)sb) - 1;
-        const int m0 = __shfl(m, leader, 64);
-        const u64 same = __ballot(sel && m == m0);
-        if (lane == leader) atomicAdd(&pairs[m0], (int)__popcll(same));
-        sb &= ~same;
-    }
-}
-
-// Grid-wide sub-round over ALL edges of the round; retired edges are skipped by
-// their state byte.  No worklist is kept here: appending survivors would need
-// one returning atomic per workgroup on a single counter, and thousands of
-// those queue up for longer than the sub-round itself takes.
-template <bool SHUFFLE>
-__global__ __launch_bounds__(BLOCK) void select_subround_kernel(SelArgs A, int k) {
-    const u64* __restrict__ cur = A.vmin[k % 3];
-    u64* __restrict__ nxt = A.vmin[(k + 1) % 3];
-    u64* __restrict__ rst = A.vmin[(k + 2) % 3];
-    const int n = A.st->ne;
-    if (blockIdx.x == 0 && threadIdx.x == 0) A.st->sel_k = k + 1;
-    for (long long base = (long long)blockIdx.x * BLOCK; base < n; base += (long long)gridDim.x * BLOCK) {
-        const long long i = base + threadIdx.x;
-        bool alive = false, sel = false;
-        int u = 0, v = 0, m = 0;
-        u64 p = 0;
-        const bool live_in = (i < n) && A.estate[i] == 0;
-        if (live_in) alive = subround_edge<false, SHUFFLE>(A, cur, k, (int)i, u, v, m, p, sel);
-        count_pairs(A, sel, m);
-        if (alive) {
-            atomicMin(&nxt[v], p);
-            rst[u] = VMIN_NONE;
-            rst[v] = VMIN_NONE;
-        } else if (live_in) {
-            A.estate[i] = 1;
-        }
-        bid_grouped(nxt, alive, u, p);
-    }
-}
-
-// The same sub-round for large rounds once most edges are retired (every sub-round but the
-// first).  One lane per edge would then spend a wave, and a trip to memory, on every 64 state
-// bytes; here a lane reads the state of 16 consecutive edges at once, the wave lists its live
-// edges in LDS in ascending order (1024 edges per wave), and the lanes then work through that
-// list 64 edges at a time exactly as above.
-constexpr int SPARSE_MIN_EDGES = 1 << 20;  // below this the one-lane-per-edge kernel is at its launch floor anyway
-
-template <int SPARSE_EDGES_PER_LANE, bool SHUFFLE>  // 4 while about a third of the edges are live, 16 later
-__global__ __launch_bounds__(BLOCK) void select_subround_sparse_kernel(SelArgs A, int k) {
-    static_assert(SPARSE_EDGES_PER_LANE == 4 || SPARSE_EDGES_PER_LANE == 16, "one 4- or 16-byte load per lane");
-    constexpr int PER_WAVE = 64 * SPARSE_EDGES_PER_LANE;
-    __shared__ int slist[prim::WAVES][PER_WAVE];
-    const u64* __restrict__ cur = A.vmin[k % 3];
-    u64* __restrict__ nxt = A.vmin[(k + 1) % 3];
-    u64* __restrict__ rst = A.vmin[(k + 2) % 3];
-    const int n = A.st->ne;
-    if (blockIdx.x == 0 && threadIdx.x == 0) A.st->sel_k = k + 1;
-    const int lane = prim::lane_id(), w = prim::wave_id();
-    int* list = slist[w];
-    for (long long cbase = ((long long)blockIdx.x * prim::WAVES + w) * PER_WAVE; cbase < n;
-         cbase += (long long)gridDim.x * prim::WAVES * PER_WAVE) {
-        const long long b0 = cbase + (long long)lane * SPARSE_EDGES_PER_LANE;
-        u32 sw[4] = {0x01010101u, 0x01010101u, 0x01010101u, 0x01010101u};  // "retired" beyond the end
-        if (b0 + SPARSE_EDGES_PER_LANE <= n) {
-            if constexpr (SPARSE_EDGES_PER_LANE == 16) {
-                const uint4 q = *reinterpret_cast<const uint4*>(A.estate + b0);
-                sw[0] = q.x; sw[1] = q.y; sw[2] = q.z; sw[3] = q.w;
-            } else {
-                sw[0] = *reinterpret_cast<const u32*>(A.estate + b0);
-            }
-        } else {
-            for (int j = 0; j < SPARSE_EDGES_PER_LANE; ++j)
-                if (b0 + j < n && A.estate[b0 + j] == 0) sw[j >> 2] &= ~(0xFFu << (8 * (j & 3)));
-        }
-        u32 livebits = 0;
-#pragma unroll
-        for (int j = 0; j < SPARSE_EDGES_PER_LANE; ++j)
-            if (((sw[j >> 2] >> (8 * (j & 3))) & 0xFFu) == 0) livebits |= 1u << j;
-        const int c = __popc(livebits);
-        int incl = c;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const int o = __shfl_up(incl, d, 64);
-            if (lane >= d) incl += o;
-        }
-        const int total = __shfl(incl, 63, 64);
-        int pos = incl - c;
-        while (livebits) {
-            const int j = __ffs((int)livebits) - 1;
-            livebits &= livebits - 1;
-            list[pos++] = (int)(b0 + j);
-        }
-        __builtin_amdgcn_wave_barrier();  // (a wave's LDS operations complete in order)
-        for (int q = 0; q < total; q += 64) {
-            const bool has = q + lane < total;
-            const int i = has ? list[q + lane] : 0;
-            bool alive = false, sel = false;
-            int u = 0, v = 0, m = 0;
-            u64 p = 0;
-            if (has) alive = subround_edge<false, SHUFFLE>(A, cur, k, i, u, v, m, p, sel);
-            count_pairs(A, sel, m);
-            if (alive) {
-                atomicMin(&nxt[v], p);
-                rst[u] = VMIN_NONE;
-                rst[v] = VMIN_NONE;
-            } else if (has) {
-                A.estate[i] = 1;
-            }
-            bid_grouped(nxt, alive, u, p);
-        }
-        __builtin_amdgcn_wave_barrier();
-    }
-}
-
-struct LivePred {
-    const unsigned char* estate;
-    __device__ bool operator()(int e) const { return estate[e] == 0; }
-};
-
-struct LiveOut {
-    int* list;
-    __device__ void operator()(int e, int pos) const { list[pos] = e; }
-};
-
-// Tail: once few edges are live, one workgroup finishes the matching with all
-// of its state in LDS: the live edges' priorities, a hash map from the (at
-// most 2 x TAIL_MAX) vertices they touch to LDS slots, and one 64-bit bid per
-// slot.  A sub-round then costs four workgroup barriers instead of a kernel
-// launch and several trips to memory.  The live count falls in every
-// sub-round (the best live edge is always accepted), so the loop ends.
-// A slot's bid doubles as its "paired" mark (TAIL_PAIRED is below every real
-// priority: a finite cost never has cost key 0).
-constexpr int TAIL_SLOTS = 8192;  // power of two, >= 2 * TAIL_MAX
-constexpr int TAIL_LDS_MESHES = 1024;
-constexpr u64 TAIL_PAIRED = 0ull;
-
-struct TailLds {
-    u64 prio[TAIL_MAX];
-    u64 bid[TAIL_SLOTS];
-    int vkey[TAIL_SLOTS];
-    unsigned short su[TAIL_MAX], sv[TAIL_MAX];
-    unsigned short lst[2][TAIL_MAX];
-    int cnt[2];
-    int pairs[TAIL_LDS_MESHES];  // pairs this kernel formed, per mesh (batches of up to this many meshes)
-};
-
-__device__ __forceinline__ int tail_slot(int* vkey, int v) {
-    u32 h = ((u32)v * 0x9E3779B1u) >> 19;  // 13 bits
-    for (;;) {
-        const int old = atomicCAS(&vkey[h], -1, v);
-        if (old == -1 || old == v) return (int)h;
-        h = (h + 1) & (TAIL_SLOTS - 1);
-    }
-}
-
-// The round's counters and pair counts, written straight into the host's pinned memory (read at
-// the L2, where this kernel's own stores to them already are).
-__device__ __forceinline__ void tail_publish(const SelArgs& A, int tid) {
-    const int* hdr = reinterpret_cast<const int*>(A.st);
-    for (int i = tid; i < A.publish_ints; i += TAIL_THREADS)
-        A.host_img[i] = __hip_atomic_load(&hdr[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-__global__ __launch_bounds__(TAIL_THREADS) void select_tail_kernel(SelArgs A) {
-    __shared__ TailLds L;
-    int n = A.st->live[0];     // live edges, gathered into A.list just before this kernel
-    const int tid = threadIdx.x, lane = prim::lane_id();
-    if (n > TAIL_MAX) {        // too many: the host runs more grid-wide sub-rounds
-        tail_publish(A, tid);
-        return;
-    }
-    const u64 lt = prim::lanemask_lt();
-    const u64 vmask = (1ull << A.vbits) - 1ull;
-
-    // Up to TAIL_LDS_MESHES meshes, the pairs formed here are tallied in LDS and added to the earlier
-    // kernels' counters at the end; that way nothing this kernel writes to memory is read back by
-    // it, and it needs no device-wide fence (which costs several microseconds here).
-    const bool lds_pairs = A.mt.B <= TAIL_LDS_MESHES;
-    if (lds_pairs)
-        for (int b = tid; b < A.mt.B; b += TAIL_THREADS) L.pairs[b] = 0;
-    for (int h = tid; h < TAIL_SLOTS; h += TAIL_THREADS) L.vkey[h] = -1;
-    __syncthreads();
-    for (int i = tid; i < n; i += TAIL_THREADS) {
-        const int e = A.list[i];
-        const u64 key = A.ekey[e];
-        L.prio[i] = A.tb.priority(A.ecost[e], e);
-        L.su[i] = (unsigned short)tail_slot(L.vkey, (int)(key >> A.vbits));
-        L.sv[i] = (unsigned short)tail_slot(L.vkey, (int)(key & vmask));
-        L.lst[0][i] = (unsigned short)i;
-    }
-    int side = 0;
-    __syncthreads();
-
-    while (n > 0) {
-        const int padded = (n + 63) & ~63;  // whole waves run each step so that the ballots are uniform
-        // clear the bids of every vertex that still has a live edge
-        for (int j = tid; j < n; j += TAIL_THREADS) {
-            const int i = L.lst[side][j];
-            L.bid[L.su[i]] = VMIN_NONE;
-            L.bid[L.sv[i]] = VMIN_NONE;
-        }
-        if (tid == 0) L.cnt[side ^ 1] = 0;
-        __syncthreads();
-        for (int j = tid; j < n; j += TAIL_THREADS) {
-            const int i = L.lst[side][j];
-            atomicMin(&L.bid[L.su[i]], L.prio[i]);
-            atomicMin(&L.bid[L.sv[i]], L.prio[i]);
-        }
-        __syncthreads();
-        // accept the edges that hold the best bid at both ends
-        bool mine[(TAIL_MAX + TAIL_THREADS - 1) / TAIL_THREADS];
-        int q = 0;
-        for (int j = tid; j < padded; j += TAIL_THREADS, ++q) {
-            bool sel = false;
-            int m = 0;
-            if (j < n) {
-                const int i = L.lst[side][j];
-                const u64 p = L.prio[i];
-                sel = (L.bid[L.su[i]] == p) && (L.bid[L.sv[i]] == p);
-                if (sel) {
-                    const int u = L.vkey[L.su[i]], v = L.vkey[L.sv[i]];
-                    A.mate[u] = v;
-                    A.mate[v] = u;
-                    m = mesh_of(A.mt.voff, A.mt.B, u);
-                }
-            }
-            mine[q] = sel;
-            if (lds_pairs) count_pairs_lds(L.pairs, sel, m);
-            else count_pairs(A, sel, m);
-        }
-        __syncthreads();
-        q = 0;
-        for (int j = tid; j < n; j += TAIL_THREADS, ++q)
-            if (mine[q]) {
-                const int i = L.lst[side][j];
-                L.bid[L.su[i]] = TAIL_PAIRED;
-                L.bid[L.sv[i]] = TAIL_PAIRED;
-            }
-        __syncthreads();
-        // keep the edges whose ends are both still free
-        for (int j = tid; j < padded; j += TAIL_THREADS) {
-            bool alive = false;
-            int i = 0;
-            if (j < n) {
-                i = L.lst[side][j];
-                alive = (L.bid[L.su[i]] != TAIL_PAIRED) && (L.bid[L.sv[i]] != TAIL_PAIRED);
-            }
-            const u64 ab = __ballot(alive);
-            if (ab) {
-                int wbase = 0;
-                if (lane == 0) wbase = atomicAdd(&L.cnt[side ^ 1], (int)__popcll(ab));
-                wbase = __shfl(wbase, 0, 64);
-                if (alive) L.lst[side ^ 1][wbase + (int)__popcll(ab & lt)] = (unsigned short)i;
-            }
-        }
-        __syncthreads();
-        side ^= 1;
-        n = L.cnt[side];
-        __syncthreads();
-    }
-
-    static_assert(MATCH_SLOTS == 32, "a mesh's slots fill half a wave");
-    constexpr int STATE_INTS = (int)(sizeof(State) / sizeof(int));
-    if (!lds_pairs) {
-        __threadfence();  // the pair counts added above are at the L2 before they are summed
-        __syncthreads();
-    }
-    // one lane per counter slot (a mesh's MATCH_SLOTS slots sit in neighbouring lanes), so that the
-    // loads are in flight together; whole waves run each step for the shuffles
-    for (int base = 0; base < A.mt.B * MATCH_SLOTS; base += TAIL_THREADS) {
-        const int idx = base + tid;
-        const bool ok = idx < A.mt.B * MATCH_SLOTS;
-        int sum = 0;
-        if (ok) sum = __hip_atomic_load(&A.mt.mslots[(size_t)idx * MATCH_PAD], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-        for (int d = MATCH_SLOTS / 2; d > 0; d >>= 1) sum += __shfl_xor(sum, d, 64);
-        if (ok && (idx & (MATCH_SLOTS - 1)) == 0) {
-            const int b = idx / MATCH_SLOTS;
-            if (lds_pairs) sum += L.pairs[b];
-            A.mt.matched[b] = sum;
-            if (lds_pairs && STATE_INTS + b < A.publish_ints) A.host_img[STATE_INTS + b] = sum;
-        }
-    }
-    if (tid == 0) A.st->live[0] = 0;
-    if (lds_pairs) {
-        // the host's copy of the counters: everything but live[0] was written by earlier kernels
-        constexpr int LIVE0 = (int)(offsetof(State, live) / sizeof(int));
-        const int* hdr = reinterpret_cast<const int*>(A.st);
-        if (tid < STATE_INTS && tid < A.publish_ints) A.host_img[tid] = (tid == LIVE0) ? 0 : hdr[tid];
-    } else {
-        __threadfence();
-        __syncthreads();
-        tail_publish(A, tid);
-    }
-}
-
-// ---------------------------------------------------------------------------
-// S2b + budget (Alg. 2 lines 3-4, 6): when a mesh formed more pairs than it may
-// remove, only its n_rem pairs of smallest (cost, edge index) stay.  The pairs
-// are gathered in edge order, sorted stably by (mesh, cost key), and the tail
-// of each mesh's run is released.
-// ---------------------------------------------------------------------------
-struct TruncPred {
-    const u64* ekey;
-    const int* mate;
-    MeshTab mt;
-    int vbits;
-    __device__ bool operator()(int e) const {
-        const u64 k = ekey[e];
-        const int u = (int)(k >> vbits), v = (int)(k & ((1ull << vbits) - 1ull));
-        if (mate[u] != v) return false;
-        const int m = mesh_of(mt.voff, mt.B, u);
-        return mt.matched[m] > mt.nrem[m];
-    }
-};
-
-struct TruncOut {
-    const u64* ekey;
-    const u32* ecost;
-    u64* tkey;
-    u32* tval;
-    MeshTab mt;
-    int vbits;
-    __device__ void operator()(int e, int pos) const {
-        const int u = (int)(ekey[e] >> vbits);
-        tkey[pos] = ((u64)(u32)mesh_of(mt.voff, mt.B, u) << 32) | (u64)ecost[e];
-        tval[pos] = (u32)e;
-    }
-};
-
-// The same gather for the one-workgroup-per-mesh selection below: cost keys and edges apart.
-struct TruncOutSplit {
-    const u32* ecost;
-    u32* tcost;
-    u32* tval;
-    __device__ void operator()(int e, int pos) const {
-        tcost[pos] = ecost[e];
-        tval[pos] = (u32)e;
-    }
-};
-
-// With the seeded tie-break the sorted variant first orders the gathered pairs by their tie-break
-// values (TruncOutTie, 32-bit keys), then gives them their (mesh, cost key) keys in that order
-// (trunc_rekey_kernel) for the stable sort that follows.
-struct TruncOutTie {
-    TieBreak tb;
-    u64* tkey;
-    u32* tval;
-    __device__ void operator()(int e, int pos) const {
-        tkey[pos] = (u64)tb.enc((u32)e);
-        tval[pos] = (u32)e;
-    }
-};
-
-__global__ __launch_bounds__(BLOCK) void trunc_rekey_kernel(const u32* __restrict__ tval, const State* st,
-                                                            const u64* __restrict__ ekey,
-                                                            const u32* __restrict__ ecost, MeshTab mt, int vbits,
-                                                            u64* __restrict__ tkey) {
-    const int i = blockIdx.x * BLOCK + threadIdx.x;
-    if (i >= st->trunc_n) return;
-    const u32 e = tval[i];
-    tkey[i] = ((u64)(u32)mesh_of(mt.voff, mt.B, (int)(ekey[e] >> vbits)) << 32) | (u64)ecost[e];
-}
-
-// Budget for meshes with a moderate number of pairs: no sort.  The gathered pairs of a mesh are a
-// contiguous run in edge order; one workgroup per mesh reads the run's cost keys once, into
-// registers (item r * TRUNC_THREADS + t sits in register r of thread t), finds the cost key of the
-// nrem-th smallest (cost key, edge) by a bitwise search on "how many keys are <= x" (a compare
-// and an add per key and bit), and flags every pair above that key and, among the pairs with
-// exactly that key, all but the first ones in edge order.  A wide kernel then releases the
-// flagged pairs.  One compute unit does the whole search, so runs longer than TRUNC_BLOCK_CAP go
-// to the sort instead.
-constexpr int TRUNC_THREADS = 1024;
-constexpr int TRUNC_REGS_MAX = 32;
-constexpr int TRUNC_BLOCK_CAP = TRUNC_THREADS * TRUNC_REGS_MAX;
-
-// Sum over the 64 lanes of a wave (all active), the same value returned to every lane.
-__device__ __forceinline__ u32 wave_sum_u32(u32 x) {
-    int v = (int)x;
-    v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, true);   // quad_perm [1,0,3,2]
-    v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, true);   // quad_perm [2,3,0,1]
-    v += __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, true);  // row_half_mirror
-    v += __builtin_amdgcn_update_dpp(0, v, 0x140, 0xF, 0xF, true);  // row_mirror: each row of 16 holds its sum
-    return (u32)(__builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) +
-                 __builtin_amdgcn_readlane(v, 32) + __builtin_amdgcn_readlane(v, 48));
-}
-
-template <int R, bool SHUFFLE>
-__global__ __launch_bounds__(TRUNC_THREADS) void trunc_block_kernel(u32* __restrict__ tcost,
-                                                                    const u32* __restrict__ tval, TieBreak tb,
-                                                                    const int* __restrict__ matched,
-                                                                    const int* __restrict__ nrem) {
-    constexpr int NW = TRUNC_THREADS / 64;
-    __shared__ u32 wsum[NW];
-    __shared__ u32 wsum2[2][NW];
-    __shared__ u32 cnt[R * NW];
-    const int b = blockIdx.x;
-    const int n = matched[b], keep = nrem[b];
-    if (n <= keep) return;
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const u64 lt = prim::lanemask_lt();
-
-    u32 before = 0, s0;  // pairs gathered for meshes in front of this one
-    for (int j = tid; j < b; j += TRUNC_THREADS)
-        if (matched[j] > nrem[j]) before += (u32)matched[j];
-    prim::wide_block_exclusive_scan<NW>(before, wsum, s0);
-    tcost += s0;
-    tval += s0;
-    if (n > R * TRUNC_THREADS) {  // not for this kernel (the host does not launch it so): release nothing
-        for (int i = tid; i < n; i += TRUNC_THREADS) tcost[i] = 0u;
-        return;
-    }
-
-    u32 key[R];  // empty slots hold the largest key
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const int i = r * TRUNC_THREADS + tid;
-        key[r] = i < n ? tcost[i] : 0xFFFFFFFFu;
-    }
-
-    // Number of the run's keys <= x, known to every thread after one barrier (`slot` alternates so
-    // that the next count does not overwrite sums that are still being read).
-    auto count_le = [&](u32 x, int slot) -> u32 {
-        u32 c = 0;
-#pragma unroll
-        for (int r = 0; r < R; ++r) c += (key[r] <= x) ? 1u : 0u;
-        c = wave_sum_u32(c);
-        if (lane == 0) wsum2[slot][w] = c;
-        __syncthreads();
-        u32 tot = 0;
-#pragma unroll
-        for (int j = 0; j < NW; ++j) tot += wsum2[slot][j];
-        return tot < (u32)n ? tot : (u32)n;  // (empty slots count when x is the largest key)
-    };
-
-    // prefix = smallest key x with at least `keep` keys <= x, found bit by bit from the top
-    u32 prefix = 0, kk = 0;
-    if (keep > 0) {
-        for (int bit = 31; bit >= 0; --bit)
-            if (count_le(prefix | ((1u << bit) - 1u), bit & 1) < (u32)keep) prefix |= 1u << bit;
-        __syncthreads();
-        kk = (u32)keep - (prefix ? count_le(prefix - 1u, 0) : 0u);
-    }
-    // kk = how many pairs with exactly the key `prefix` stay (the first kk in edge order)
-    if constexpr (SHUFFLE) {
-        // ... the first kk in the order of the seeded tie-break, which is distinct from pair to pair:
-        // the same search once more, on the tie-break values of the pairs with that key
-        u32 tie[R];
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int i = r * TRUNC_THREADS + tid;
-            tie[r] = (i < n && key[r] == prefix) ? tb.enc(tval[i]) : 0xFFFFFFFFu;
-        }
-        auto count_tie_le = [&](u32 x, int slot) -> u32 {
-            u32 c = 0;
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-                c += (r * TRUNC_THREADS + tid < n && key[r] == prefix && tie[r] <= x) ? 1u : 0u;
-            c = wave_sum_u32(c);
-            __syncthreads();  // (the sums of the count before this one have been read)
-            if (lane == 0) wsum2[slot][w] = c;
-            __syncthreads();
-            u32 tot = 0;
-#pragma unroll
-            for (int j = 0; j < NW; ++j) tot += wsum2[slot][j];
-            return tot;
-        };
-        u32 t2 = 0;
-        if (kk > 0)
-            for (int bit = 31; bit >= 0; --bit)
-                if (count_tie_le(t2 | ((1u << bit) - 1u), bit & 1) < kk) t2 |= 1u << bit;
-        __syncthreads();
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int i = r * TRUNC_THREADS + tid;
-            if (i < n) tcost[i] = (key[r] > prefix || (key[r] == prefix && (kk == 0 || tie[r] > t2))) ? 1u : 0u;
-        }
-        return;
-    }
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const bool eq = (r * TRUNC_THREADS + tid < n) && key[r] == prefix;
-        const u64 eb = __ballot(eq);
-        if (lane == 0) cnt[r * NW + w] = (u32)__popcll(eb);
-    }
-    __syncthreads();
-    {
-        const u32 v = tid < R * NW ? cnt[tid] : 0u;
-        u32 tot;
-        const u32 ex = prim::wide_block_exclusive_scan<NW>(v, wsum, tot);
-        if (tid < R * NW) cnt[tid] = ex;  // equal keys in front of wave w's part of row r
-    }
-    __syncthreads();
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const int i = r * TRUNC_THREADS + tid;
-        const bool valid = i < n;
-        const bool eq = valid && key[r] == prefix, gt = valid && key[r] > prefix;
-        const u64 eb = __ballot(eq);
-        const u32 rank = cnt[r * NW + w] + (u32)__popcll(eb & lt);
-        if (valid) tcost[i] = (gt || (eq && rank >= kk)) ? 1u : 0u;  // the key's slot now holds the flag
-    }
-}
-
-constexpr u64 ABID_NONE = ~0ull;
-
-// The end of an edge that line 11 of Alg. 2 could add to the other end's cluster: the un-paired
-// one when exactly one end is paired, else -1.
-__device__ __forceinline__ int joining_end(const int* __restrict__ mate, int u, int v) {
-    const bool pu = mate[u] >= 0, pv = mate[v] >= 0;
-    return pu == pv ? -1 : (pu ? v : u);
-}
-
-// Gives up what the budget does not cover: a pair is dissolved (ABSORB = false), or the vertex
-// that would have joined through the edge stays on its own (ABSORB = true: its bid is withdrawn).
-template <bool ABSORB>
-__device__ __forceinline__ void release_edge(u64 k, int vbits, int* __restrict__ mate, u64* __restrict__ abid) {
-    const int u = (int)(k >> vbits), v = (int)(k & ((1ull << vbits) - 1ull));
-    if (ABSORB) {
-        const int w = joining_end(mate, u, v);
-        if (w >= 0) abid[w] = ABID_NONE;
-    } else {
-        mate[u] = -1;
-        mate[v] = -1;
-    }
-}
-
-// Releases the flagged pairs; block 0 also clamps the pair counts of the meshes to their budgets.
-template <bool ABSORB>
-__global__ __launch_bounds__(BLOCK) void trunc_release_kernel(const u32* __restrict__ tflag,
-                                                              const u32* __restrict__ tval, const State* st,
-                                                              const u64* __restrict__ ekey, int vbits,
-                                                              int* __restrict__ mate, int B, int* __restrict__ matched,
-                                                              const int* __restrict__ nrem, u64* __restrict__ abid) {
-    const int i = blockIdx.x * BLOCK + threadIdx.x;
-    if (i < st->trunc_n && tflag[i]) release_edge<ABSORB>(ekey[tval[i]], vbits, mate, abid);
-    if (blockIdx.x == 0)
-        for (int b = threadIdx.x; b < B; b += BLOCK)
-            if (matched[b] > nrem[b]) matched[b] = nrem[b];
-}
-
-// segstart[b] = number of gathered pairs that belong to meshes before b
-__global__ void trunc_segments_kernel(int B, const int* __restrict__ matched, const int* __restrict__ nrem,
-                                      int* __restrict__ segstart) {
-    if (threadIdx.x == 0 && blockIdx.x == 0) {
-        int run = 0;
-        for (int b = 0; b < B; ++b) {
-            segstart[b] = run;
-            if (matched[b] > nrem[b]) run += matched[b];
-        }
-    }
-}
-
-template <bool ABSORB>
-__global__ __launch_bounds__(BLOCK) void trunc_apply_kernel(const u64* __restrict__ tkey, const u32* __restrict__ tval,
-                                                            const State* st, const int* __restrict__ segstart,
-                                                            const int* __restrict__ nrem,
-                                                            const u64* __restrict__ ekey, int vbits,
-                                                            int* __restrict__ mate, u64* __restrict__ abid) {
-    const int i = blockIdx.x * BLOCK + threadIdx.x;
-    if (i >= st->trunc_n) return;
-    const int m = (int)(tkey[i] >> 32);
-    if (i - segstart[m] >= nrem[m]) release_edge<ABSORB>(ekey[tval[i]], vbits, mate, abid);
-}
-
-__global__ void trunc_finish_kernel(int B, int* __restrict__ matched, const int* __restrict__ nrem) {
-    for (int b = threadIdx.x; b < B; b += blockDim.x)
-        if (matched[b] > nrem[b]) matched[b] = nrem[b];
-}
-
-// ---------------------------------------------------------------------------
-// Alg. 2 line 11 (option), under the vertex budget: after the pairs are final,
-// an un-paired vertex next to a paired one joins that pair's cluster through
-// its cheapest such edge (cost key, edge index) -- the first the sequential
-// walk over the sorted pairs would reach.  Every joining vertex has its own
-// edge, so the priorities are distinct; where a mesh has more candidates than
-// budget left, the cheapest stay (the same machinery as for the pairs).  Only
-// the two founders of a cluster attract: a vertex that joined pulls in nobody.
-// ---------------------------------------------------------------------------
-__global__ __launch_bounds__(BLOCK) void absorb_begin_kernel(u64* __restrict__ abid, int* __restrict__ arep,
-                                                             int* __restrict__ acnt, const State* st, int cur, int B,
-                                                             const int* __restrict__ nrem,
-                                                             const int* __restrict__ matched, int* __restrict__ arem,
-                                                             int* __restrict__ acand) {
-    const int nv = st->nv[cur];
-    const int stride = gridDim.x * BLOCK;
-    const int g = blockIdx.x * BLOCK + threadIdx.x;
-    for (int w = g; w < nv; w += stride) {
-        abid[w] = ABID_NONE;
-        arep[w] = -1;
-        acnt[w] = 0;
-    }
-    for (int b = g; b < B; b += stride) {
-        const int left = nrem[b] - matched[b];
-        arem[b] = (matched[b] > 0 && left > 0) ? left : 0;  // budget left once the pairs are formed
-        acand[b] = 0;
-    }
-}
-
-__global__ __launch_bounds__(BLOCK) void absorb_bid_kernel(const u64* __restrict__ ekey, const u32* __restrict__ ecost,
-                                                           const State* st, int vbits, const int* __restrict__ mate,
-                                                           MeshTab mt, const int* __restrict__ arem,
-                                                           u64* __restrict__ abid, TieBreak tb) {
-    const int n = st->ne;
-    for (int e = blockIdx.x * BLOCK + threadIdx.x; e < n; e += gridDim.x * BLOCK) {
-        const u64 k = ekey[e];
-        const int u = (int)(k >> vbits), v = (int)(k & ((1ull << vbits) - 1ull));
-        const int w = joining_end(mate, u, v);
-        if (w >= 0 && arem[mesh_of(mt.voff, mt.B, w)] > 0) atomicMin(&abid[w], tb.priority(ecost[e], e));
-    }
-}
-
-// Edge e is the one through which its un-paired end joins (its bid stands at that vertex).
-struct JoinPred {
-    const u64* ekey;
-    const u32* ecost;
-    const int* mate;
-    const u64* abid;
-    int vbits;
-    TieBreak tb;
-    __device__ bool operator()(int e) const {
-        const u64 k = ekey[e];
-        const int w = joining_end(mate, (int)(k >> vbits), (int)(k & ((1ull << vbits) - 1ull)));
-        return w >= 0 && abid[w] == tb.priority(ecost[e], e);
-    }
-};
-
-struct JoinListOut {
-    int* list;
-    __device__ void operator()(int e, int pos) const { list[pos] = e; }
-};
-
-// ... and its mesh has more such edges than budget left.
-struct JoinOverPred {
-    JoinPred jp;
-    MeshTab mt;
-    const int* acand;
-    const int* arem;
-    __device__ bool operator()(int e) const {
-        if (!jp(e)) return false;
-        const int m = mesh_of(mt.voff, mt.B, (int)(jp.ekey[e] >> jp.vbits));
-        return acand[m] > arem[m];
-    }
-};
-
-// The joining edges are listed in edge order, hence by mesh: acand[b] = how many belong to mesh b.
-// Also written to host memory (`host_out`), which the host reads after waiting for the stream.
-__global__ __launch_bounds__(BLOCK) void absorb_count_kernel(const int* __restrict__ list, const State* st,
-                                                             const u64* __restrict__ ekey, int vbits, int B,
-                                                             const int* __restrict__ voff, int* __restrict__ acand,
-                                                             int* __restrict__ host_out) {
-    const int n = st->absorb_n;
-    for (int b = threadIdx.x; b < B; b += BLOCK) {
-        int pos[2];
-        for (int side = 0; side < 2; ++side) {
-            if (b + side == 0 || b + side == B) {  // the ends of the list need no search
-                pos[side] = (b + side == 0) ? 0 : n;
-                continue;
-            }
-            const int v0 = voff[b + side];
-            int lo = 0, hi = n;  // first listed edge whose lower vertex is at or past v0
-            while (lo < hi) {
-                const int mid = (lo + hi) >> 1;
-                if ((int)(ekey[list[mid]] >> vbits) >= v0) hi = mid; else lo = mid + 1;
-            }
-            pos[side] = lo;
-        }
-        acand[b] = pos[1] - pos[0];
-        host_out[b] = pos[1] - pos[0];
-    }
-}
-
-// For every listed edge that still stands: the joining vertex records its cluster's representative
-// (the founding pair's smaller index) and emits the key (representative, vertex); withdrawn ones
-// emit the all-ones key, which sorts behind every real one.
-__global__ __launch_bounds__(BLOCK) void absorb_keys_kernel(const int* __restrict__ list, const State* st,
-                                                            const u64* __restrict__ ekey,
-                                                            const u32* __restrict__ ecost, int vbits,
-                                                            const int* __restrict__ mate, const u64* __restrict__ abid,
-                                                            int* __restrict__ arep, int* __restrict__ acnt,
-                                                            u64* __restrict__ akey, TieBreak tb) {
-    const int i = blockIdx.x * BLOCK + threadIdx.x;
-    if (i >= st->absorb_n) return;
-    const int e = list[i];
-    const u64 k = ekey[e];
-    const int u = (int)(k >> vbits), v = (int)(k & ((1ull << vbits) - 1ull));
-    const int w = joining_end(mate, u, v);
-    u64 out = (vbits >= 32) ? ~0ull : ((1ull << (2 * vbits)) - 1ull);
-    if (w >= 0 && abid[w] == tb.priority(ecost[e], e)) {
-        const int o = (w == u) ? v : u;
-        const int mo = mate[o];
-        const int r = o < mo ? o : mo;
-        arep[w] = r;
-        atomicAdd(&acnt[r], 1);  // (so that representatives nobody joined need not look)
-        out = ((u64)(u32)r << vbits) | (u64)(u32)w;
-    }
-    akey[i] = out;
-}
-
-// ---------------------------------------------------------------------------
-// S4 + S6: contraction (Alg. 2 lines 12-16) and survivor renumbering
-// ---------------------------------------------------------------------------
-template <bool ABSORB>
-struct AlivePredT {
-    const int* mate;
-    const int* arep;
-    __device__ bool operator()(int w) const {
-        const int m = mate[w];
-        if (m >= 0 && m < w) return false;  // the larger index of a pair is replaced by the smaller
-        return !(ABSORB && arep[w] >= 0);   // as is a vertex that joined a pair's cluster
-    }
-};
-
-struct AliveOut {
-    int* newid;
-    __device__ void operator()(int w, int pos) const { newid[w] = pos; }
-};
-
-// Survivors move to their new slot; a pair's representative takes the summed
-// quadric and the pair's target position (the mean; with PLACE_INVERSE the
-// point of least error where there is one).  With ABSORB a cluster may have
-// more members than its pair: `akey` lists (representative, member) in
-// ascending order for the vertices that joined, and quadric and position are
-// summed over all members in ascending index order, the position sum divided
-// by their number.  vmap[w] = output slot of w's cluster.
-template <int PLACE, bool ABSORB>
-__global__ __launch_bounds__(BLOCK) void contract_kernel(const VRec* __restrict__ vin, VRec* __restrict__ vout,
-                                                         const int* __restrict__ mate, const int* __restrict__ newid,
-                                                         int* __restrict__ vmap, const State* st, int cur, int B,
-                                                         const int* __restrict__ voff_cur, int* __restrict__ voff_nxt,
-                                                         int* __restrict__ htab, int hsize,
-                                                         u32* __restrict__ msd_hist, float rcond_min,
-                                                         const int* __restrict__ arep, const int* __restrict__ acnt,
-                                                         const u64* __restrict__ akey, int vbits) {
-    const int nv = st->nv[cur];
-    const int stride = gridDim.x * BLOCK;
-    const int g = blockIdx.x * BLOCK + threadIdx.x;
-    // this round's edge keys are long sorted: their digit counts and cursors go back to zero for the next round
-    for (int i = g; i < 2 * prim::MSD_HIST_WORDS; i += stride) msd_hist[i] = 0;
-    for (int w = g; w < nv; w += stride) {
-        const int m = mate[w];
-        if (m >= 0 && m < w) {
-            vmap[w] = newid[m];
-            continue;
-        }
-        if (ABSORB) {
-            const int r = arep[w];
-            if (r >= 0) {
-                vmap[w] = newid[r];
-                continue;
-            }
-        }
-        const int nw = newid[w];
-        vmap[w] = nw;
-        const float4* a = reinterpret_cast<const float4*>(&vin[w]);
-        float4 r0 = a[0], r1 = a[1], r2 = a[2], r3 = a[3];
-        if (m >= 0) {
-            int j = 0, jend = 0;  // this cluster's part of akey
-            if (ABSORB && acnt[w] > 0) {
-                const int n = st->absorb_n;
-                const u64 first = (u64)(u32)w << vbits;
-                int lo = 0, hi = n;
-                while (lo < hi) {
-                    const int mid = (lo + hi) >> 1;
-                    if (akey[mid] >= first) hi = mid; else lo = mid + 1;
-                }
-                j = lo;
-                jend = min(lo + acnt[w], n);
-            }
-            if (!ABSORB || j == jend) {
-                const float4* b = reinterpret_cast<const float4*>(&vin[m]);
-                const float4 s0 = b[0], s1 = b[1], s2 = b[2], s3 = b[3];
-                r0.x = (r0.x + s0.x) * 0.5f; r0.y = (r0.y + s0.y) * 0.5f; r0.z = (r0.z + s0.z) * 0.5f;
-                r1.x = r1.x + s1.x; r1.y = r1.y + s1.y; r1.z = r1.z + s1.z; r1.w = r1.w + s1.w;
-                r2.x = r2.x + s2.x; r2.y = r2.y + s2.y; r2.z = r2.z + s2.z; r2.w = r2.w + s2.w;
-                r3.x = r3.x + s3.x; r3.y = r3.y + s3.y;
-            } else {
-                // merge w < m with the ascending list of joined vertices
-                const u64 low = (1ull << vbits) - 1ull;
-                bool done_w = false, done_m = false;
-                int cnt = 0;
-                while (!done_w || !done_m || j < jend) {
-                    int x = 0x7FFFFFFF, from = -1;
-                    if (!done_w) { x = w; from = 0; }
-                    else if (!done_m) { x = m; from = 1; }
-                    if (j < jend) {
-                        const int y = (int)(akey[j] & low);
-                        if (y < x) { x = y; from = 2; }
-                    }
-                    if (from == 0) done_w = true;
-                    else if (from == 1) done_m = true;
-                    else ++j;
-                    const float4* b = reinterpret_cast<const float4*>(&vin[x]);
-                    const float4 s0 = b[0], s1 = b[1], s2 = b[2], s3 = b[3];
-                    if (cnt == 0) {
-                        r0 = s0; r1 = s1; r2 = s2; r3 = s3;
-                    } else {
-                        r0.x = r0.x + s0.x; r0.y = r0.y + s0.y; r0.z = r0.z + s0.z;
-                        r1.x = r1.x + s1.x; r1.y = r1.y + s1.y; r1.z = r1.z + s1.z; r1.w = r1.w + s1.w;
-                        r2.x = r2.x + s2.x; r2.y = r2.y + s2.y; r2.z = r2.z + s2.z; r2.w = r2.w + s2.w;
-                        r3.x = r3.x + s3.x; r3.y = r3.y + s3.y;
-                    }
-                    ++cnt;
-                }
-                const float k = (float)cnt;
-                r0.x = r0.x / k; r0.y = r0.y / k; r0.z = r0.z / k;
-                r0.w = 0.f; r3.z = 0.f; r3.w = 0.f;
-            }
-            if (PLACE == PLACE_INVERSE)
-                quadric_minimiser(r1.x, r1.y, r1.z, r1.w, r2.x, r2.y, r2.z, r2.w, r3.x, rcond_min, r0.x, r0.y, r0.z);
-        }
-        float4* o = reinterpret_cast<float4*>(&vout[nw]);
-        o[0] = r0; o[1] = r1; o[2] = r2; o[3] = r3;
-    }
-    // a mesh's first vertex always survives when only pairs are contracted (a removed vertex has a
-    // smaller partner in its own mesh); one that joined a cluster may not, and then the mesh starts
-    // at its first survivor (every cluster has one)
-    for (int b = g; b <= B; b += stride) {
-        int nb = st->nv[cur ^ 1];
-        if (b < B) {
-            int w = voff_cur[b];
-            if (ABSORB)
-                while (w + 1 < voff_cur[b + 1] && arep[w] >= 0) ++w;
-            nb = newid[w];
-        }
-        voff_nxt[b] = nb;
-    }
-    for (int h = g; h < hsize; h += stride) htab[h] = -1;
-}
-
-// ---------------------------------------------------------------------------
-// S5: facet re-indexing, removal of collapsed and repeated facets, compaction
-// ---------------------------------------------------------------------------
-__device__ __forceinline__ void sort3(int& a, int& b, int& c) {
-    int t;
-    if (a > b) { t = a; a = b; b = t; }
-    if (b > c) { t = b; b = c; c = t; }
-    if (a > b) { t = a; a = b; b = t; }
-}
-
-__device__ __forceinline__ u32 hash3(int a, int b, int c) {
-    u32 h = (u32)a * 0x9E3779B1u;
-    h ^= (u32)b * 0x85EBCA77u + (h << 6) + (h >> 2);
-    h ^= (u32)c * 0xC2B2AE3Du + (h << 6) + (h >> 2);
-    h ^= h >> 15;
-    h *= 0x2C1B3C6Du;
-    h ^= h >> 12;
-    return h;
-}
-
-// Re-indexes every facet and enters the non-collapsed ones into an open-
-// addressing table keyed by the unordered vertex triple.  A slot stores a
-// facet index; the slot's identity is that facet's triple, and among equal
-// triples the slot converges to the smallest facet index (atomicMin), so the
-// survivor does not depend on the order in which lanes arrive.
-constexpr int FSLOT_KEEP = -1, FSLOT_DROP = -2;
-
-__global__ __launch_bounds__(BLOCK) void facet_insert_kernel(const int* __restrict__ fcur, int* __restrict__ fmap,
-                                                             const int* __restrict__ vmap, const State* st, int cur,
-                                                             int* __restrict__ htab, u32 hmask, MeshTab mt,
-                                                             const int* __restrict__ voff_cur,
-                                                             int* __restrict__ cid, int n_orig,
-                                                             int* __restrict__ fslot) {
-    const int nf = st->nf[cur];
-    const int stride = gridDim.x * BLOCK;
-    const int g = blockIdx.x * BLOCK + threadIdx.x;
-    for (int f = g; f < nf; f += stride) {
-        const int a0 = fcur[3 * (size_t)f], b0 = fcur[3 * (size_t)f + 1], c0 = fcur[3 * (size_t)f + 2];
-        const int a = vmap[a0], b = vmap[b0], c = vmap[c0];
-        fmap[3 * (size_t)f] = a;
-        fmap[3 * (size_t)f + 1] = b;
-        fmap[3 * (size_t)f + 2] = c;
-        // fslot[f]: the table slot that decides about the facet (it survives iff the slot ends up
-        // holding f), or FSLOT_KEEP / FSLOT_DROP where no slot is involved
-        if (!mt.active[mesh_of(voff_cur, mt.B, a0)]) {  // mesh sits this round out: facets kept as they are
-            fslot[f] = FSLOT_KEEP;
-            continue;
-        }
-        if (a == b || b == c || a == c) {
-            fslot[f] = FSLOT_DROP;
-            continue;
-        }
-        int x = a, y = b, z = c;
-        sort3(x, y, z);
-        u32 h = hash3(x, y, z) & hmask;
-        for (;;) {
-            const int old = atomicCAS(&htab[h], -1, f);
-            if (old == -1) break;
-            if (old == f) break;
-            int p = vmap[fcur[3 * (size_t)old]], q = vmap[fcur[3 * (size_t)old + 1]], r = vmap[fcur[3 * (size_t)old + 2]];
-            sort3(p, q, r);
-            if (p == x && q == y && r == z) {
-                atomicMin(&htab[h], f);
-                break;
-            }
-            h = (h + 1) & hmask;
-        }
-        fslot[f] = (int)h;
-    }
-    for (int o = g; o < n_orig; o += stride) cid[o] = vmap[cid[o]];
-}
-
-// keep[f] = 1 iff the facet survives: not collapsed and the first of its triple (the slot that
-// facet_insert_kernel left for it holds the smallest facet index of the triple).
-struct FacetKeepPred {
-    const int* fslot;
-    const int* htab;
-    unsigned char* keep;
-    __device__ bool operator()(int f) const {
-        const int h = fslot[f];
-        const bool k = h >= 0 ? htab[h] == f : h == FSLOT_KEEP;
-        keep[f] = k ? 1 : 0;
-        return k;
-    }
-};
-
-struct FlagPred {
-    const unsigned char* keep;
-    __device__ bool operator()(int f) const { return keep[f] != 0; }
-};
-
-struct FacetOut {
-    const int* fmap;
-    int* fnxt;
-    __device__ void operator()(int f, int pos) const {
-        fnxt[3 * (size_t)pos] = fmap[3 * (size_t)f];
-        fnxt[3 * (size_t)pos + 1] = fmap[3 * (size_t)f + 1];
-        fnxt[3 * (size_t)pos + 2] = fmap[3 * (size_t)f + 2];
-    }
-};
-
-// ---------------------------------------------------------------------------
-// Results
-// ---------------------------------------------------------------------------
-__global__ __launch_bounds__(BLOCK) void copy_out_kernel(const VRec* __restrict__ vrec, const int* __restrict__ fcur,
-                                                         const int* __restrict__ cid, const State* st, int cur,
-                                                         int n_orig, float* __restrict__ verts_out,
-                                                         int* __restrict__ facets_out, int* __restrict__ cid_out,
-                                                         int B, const int* __restrict__ voff,
-                                                         int* __restrict__ foff_out) {
-    const int nv = st->nv[cur], nf = st->nf[cur];
-    const int stride = gridDim.x * BLOCK;
-    const int g = blockIdx.x * BLOCK + threadIdx.x;
-    for (int w = g; w < nv; w += stride) {
-        const float4 p = *reinterpret_cast<const float4*>(&vrec[w]);
-        verts_out[3 * (size_t)w] = p.x;
-        verts_out[3 * (size_t)w + 1] = p.y;
-        verts_out[3 * (size_t)w + 2] = p.z;
-    }
-    for (long long i = g; i < 3ll * nf; i += stride) facets_out[i] = fcur[i];
-    for (int o = g; o < n_orig; o += stride) cid_out[o] = cid[o];
-    // facets stay grouped by mesh: first facet whose leading vertex is at or past the mesh's first vertex
-    for (int b = g; b <= B; b += stride) {
-        int lo = 0, hi = nf;
-        if (b == B) lo = nf;
-        else {
-            const int v0 = voff[b];
-            while (lo < hi) {
-                const int mid = (lo + hi) >> 1;
-                if (fcur[3 * (size_t)mid] >= v0) hi = mid; else lo = mid + 1;
-            }
-        }
-        foff_out[b] = lo;
-    }
-}
-
-// Plain streaming copy, 16 bytes per lane per step: the yardstick for the
-// achievable HBM rate and for calibrating the profiler's byte counters.
-__global__ __launch_bounds__(BLOCK) void copy_kernel(const float4* __restrict__ src, float4* __restrict__ dst,
-                                                     size_t n16) {
-    const size_t stride = (size_t)gridDim.x * BLOCK;
-    for (size_t i = (size_t)blockIdx.x * BLOCK + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
-}
-
-__global__ __launch_bounds__(BLOCK) void export_quadrics_kernel(const VRec* __restrict__ vrec, int N,
-                                                                float* __restrict__ out) {
-    const int w = blockIdx.x * BLOCK + threadIdx.x;
-    if (w >= N) return;
-    const float4* r = reinterpret_cast<const float4*>(&vrec[w]);
-    const float4 r1 = r[1], r2 = r[2], r3 = r[3];
-    float* o = out + 10 * (size_t)w;
-    o[0] = r1.x; o[1] = r1.y; o[2] = r1.z; o[3] = r1.w;
-    o[4] = r2.x; o[5] = r2.y; o[6] = r2.z; o[7] = r2.w;
-    o[8] = r3.x; o[9] = r3.y;
-}
-
-__global__ __launch_bounds__(BLOCK) void export_edges_kernel(const u64* __restrict__ ekey, const u32* __restrict__ ecost,
-                                                             const State* st, int vbits, int* __restrict__ edges,
-                                                             float* __restrict__ cost) {
-    const int e = blockIdx.x * BLOCK + threadIdx.x;
-    if (e >= st->ne) return;
-    const u64 k = ekey[e];
-    edges[2 * (size_t)e] = (int)(k >> vbits);
-    edges[2 * (size_t)e + 1] = (int)(k & ((1ull << vbits) - 1ull));
-    const u32 ck = ecost[e];
-    cost[e] = __uint_as_float((ck & 0x80000000u) ? (ck & 0x7FFFFFFFu) : ~ck);
-}
-
-inline int ceil_log2(long long n) {
-    int b = 0;
-    while ((1ll << b) < n) ++b;
-    return b < 1 ? 1 : b;
-}
 
 inline int grid_for(long long n, int cap = 0x7FFFFFFF) {
     long long g = (n + BLOCK - 1) / BLOCK;
