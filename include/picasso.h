@@ -2,7 +2,10 @@
  *
  * Implements the round-based QEM decimation of the Picasso paper
  * (Sec. 3, Algorithm 2 "Fast GPU-accelerated mesh simplification";
- * supplementary section "Quadric error computation").  Every step runs in
+ * supplementary section "Quadric error computation"), and around it the
+ * operators the paper defines on its results: pooling and unpooling over the
+ * vertex clusters (Sec. 3), the replace / mapping tensors, and the
+ * vertex2facet / facet2vertex convolutions (Sec. 4).  Every step runs in
  * hand-written HIP kernels; there is no CPU fallback.
  *
  * Conventions for every call
@@ -106,7 +109,7 @@ typedef struct picasso_stats {
     int32_t nv[PICASSO_STATS_ROUNDS];        /* vertices entering round r                           */
     int32_t nf[PICASSO_STATS_ROUNDS];        /* facets entering round r                             */
     int32_t ne[PICASSO_STATS_ROUNDS];        /* distinct edges in round r                           */
-    int32_t nsel[PICASSO_STATS_ROUNDS];      /* pairs contracted in round r                         */
+    int32_t nsel[PICASSO_STATS_ROUNDS];      /* vertices removed in round r (pairs; + joiners of line 11) */
     int32_t subrounds[PICASSO_STATS_ROUNDS]; /* selection sub-rounds launched in round r            */
     float ms_stage[PICASSO_STATS_ROUNDS][PICASSO_ST_COUNT];
     float ms_total;                          /* whole call, hipEvents on `stream`                   */
