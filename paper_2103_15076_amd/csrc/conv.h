@@ -28,6 +28,19 @@ using pool::store_pack;
 // cannot reach outside the arrays: it is read as index 0.
 __device__ __forceinline__ int in_range_or_zero(int i, int n) { return ((unsigned)i < (unsigned)n) ? i : 0; }
 
+// Workgroups are handed to the 8 accelerator dies in turn, and each die has its own L2.  The facet
+// rows that neighbouring vertices gather overlap (mesh numbering has locality), so the facet2vertex
+// forward kernel deals its work out in 8 contiguous parts, one per die: workgroup b works as
+// number (b % 8) * (G / 8) + b / 8 of a grid of G workgroups, G a multiple of 8 (xcd_grid).
+__device__ __forceinline__ long long xcd_block() {
+    const unsigned g8 = gridDim.x >> 3;
+    return (long long)(blockIdx.x & 7u) * g8 + (blockIdx.x >> 3);
+}
+inline int xcd_grid(long long threads) {
+    const long long g = (threads + BLOCK - 1) / BLOCK;
+    return (int)((g + 7) / 8 * 8 > 0 ? (g + 7) / 8 * 8 : 8);
+}
+
 // ---------------------------------------------------------------------------
 // Facet geometry: unit normal, area (Sec. 4, first paragraph) and the level k
 // of Eq. "interpolate_num", k = floor((A - A_min) / (A_max - A_min)) * alpha +
@@ -380,7 +393,7 @@ __global__ __launch_bounds__(BLOCK) void f2v_forward_kernel(const float* __restr
     }
     const float* wsrc = W_IN_LDS ? wl : w;
     const int Q = C / VEC;
-    const long long idx = (long long)blockIdx.x * BLOCK + threadIdx.x;
+    const long long idx = xcd_block() * BLOCK + threadIdx.x;
     const int v = (int)(idx / Q), q = (int)(idx % Q);
     if (v >= N) return;
     const size_t co = (size_t)q * VEC;

@@ -1266,7 +1266,7 @@ int picasso_f2v_forward(picasso_ctx* c, void* stream, const float* d_y, int32_t 
     const bool lds = (long long)T * C <= conv::F2V_LDS_FLOATS;
     const size_t lds_bytes = lds ? sizeof(float) * (size_t)T * C : 0;
     const bool vec8 = conv_vec(C, {d_y, d_w, d_x}) == 8;
-    const int grid = pool::grid_for((long long)N * (vec8 ? C / 8 : (vec4 ? C / 4 : C)));
+    const int grid = conv::xcd_grid((long long)N * (vec8 ? C / 8 : (vec4 ? C / 4 : C)));
 #define PICASSO_F2V(VEC, LDS) \
     conv::f2v_forward_kernel<VEC, LDS><<<grid, pool::BLOCK, lds_bytes, s>>>(d_y, C, d_pi, T, d_w, d_offsets, d_corners, N, 3 * F, d_x)
     if (vec8) {
