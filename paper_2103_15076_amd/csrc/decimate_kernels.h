@@ -295,9 +295,10 @@ __global__ __launch_bounds__(BLOCK) void quadric_reduce_kernel(VRec* __restrict_
                                                                const int* __restrict__ off,
                                                                const u64* __restrict__ inc, int fbits,
                                                                u32* __restrict__ ihist) {
-    const int w = blockIdx.x * BLOCK + threadIdx.x;
+    // workgroups go to the 8 dies in turn; each die (its own L2) takes one contiguous eighth of the vertices
+    const int w = (int)(((long long)(blockIdx.x & 7u) * (gridDim.x >> 3) + (blockIdx.x >> 3)) * BLOCK + threadIdx.x);
     // last kernel of S0: the incidence sort's digit counts and cursors go back to zero for the next call
-    for (int i = w; i < 2 * prim::MSD_HIST_WORDS; i += gridDim.x * BLOCK) ihist[i] = 0;
+    for (int i = blockIdx.x * BLOCK + threadIdx.x; i < 2 * prim::MSD_HIST_WORDS; i += gridDim.x * BLOCK) ihist[i] = 0;
     if (w >= N) return;
     float acc[10];
 #pragma unroll

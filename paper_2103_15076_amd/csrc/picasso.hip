@@ -364,10 +364,10 @@ int run_vertex_quadrics(picasso_ctx* c, hipStream_t s, const float* d_verts, int
         if (where < 0) return PICASSO_ERR_HIP;
         const u64* skey = where ? c->s0_key[1] : c->s0_key[0];
         csr_offsets_kernel<u64><<<grid_for(H), BLOCK, 0, s>>>(skey, fbits, H, N, c->csr_off);
-        quadric_reduce_kernel<<<grid_for(N), BLOCK, 0, s>>>(c->vrec[0], d_verts, N, c->fbuf[0], c->csr_off, skey, fbits,
+        quadric_reduce_kernel<<<(grid_for(N) + 7) / 8 * 8, BLOCK, 0, s>>>(c->vrec[0], d_verts, N, c->fbuf[0], c->csr_off, skey, fbits,
                                                             c->hist12_s0);
     } else {
-        quadric_reduce_kernel<<<grid_for(N), BLOCK, 0, s>>>(c->vrec[0], d_verts, N, c->fbuf[0], nullptr, nullptr, 0,
+        quadric_reduce_kernel<<<(grid_for(N) + 7) / 8 * 8, BLOCK, 0, s>>>(c->vrec[0], d_verts, N, c->fbuf[0], nullptr, nullptr, 0,
                                                             c->hist12_s0);
     }
     return PICASSO_OK;
