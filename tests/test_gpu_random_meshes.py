@@ -83,3 +83,50 @@ def test_random_meshes_and_options(oracle, chunk):
             assert np.array_equal(vo.cpu().numpy().view(np.uint32), ref["verts"].view(np.uint32))
     finally:
         ctx.close()
+
+
+@pytest.mark.parametrize("chunk", range(4))
+def test_random_batches_against_the_meshes_one_by_one(oracle, chunk):
+    """Batches of 2-7 random meshes (line 11 and inverse placement at random; the shuffle has no
+    per-mesh reference in a batch): every mesh's block of the outputs equals the oracle run on that
+    mesh alone."""
+    import paper_2103_15076_amd as pk
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    rng = np.random.default_rng(2000 + chunk)
+    ctx = pk.Context(8192, 32768, 8, device=0)
+    try:
+        for case in range(25):
+            B = int(rng.integers(2, 8))
+            parts = [_random_mesh(rng) for _ in range(B)]
+            nv = [p[0].shape[0] for p in parts]
+            nf = [p[1].shape[0] for p in parts]
+            off = np.cumsum([0] + nv)
+            V = np.concatenate([p[0] for p in parts])
+            F = np.concatenate([p[1].reshape(-1, 3) + off[i] for i, p in enumerate(parts)]).astype(np.int32)
+            tg = [int(rng.integers(1, n + 2)) for n in nv]
+            absorb = bool(rng.integers(0, 2))
+            inverse = bool(rng.integers(0, 2))
+            block_max = int(rng.choice([0, 1 << 15]))
+            print(f"random batch chunk={chunk} case={case} nv={nv} nf={nf} tg={tg} absorb={absorb} inverse={inverse} "
+                  f"block_max={block_max}", flush=True)
+            ctx.set_option(pk.PICASSO_OPT_ABSORB, int(absorb))
+            ctx.set_placement(pk.PICASSO_PLACE_INVERSE if inverse else pk.PICASSO_PLACE_MEAN, 1e-3)
+            ctx.set_option(pk.PICASSO_OPT_TRUNC_BLOCK_MAX, block_max)
+            Fd = dev(F) if F.shape[0] else torch.empty((0, 3), dtype=torch.int32, device="cuda:0")
+            st, vo, fo, cid, nvo, nfo = ctx.picasso_decimate_batch(dev(V), Fd, nv, nf, tg)
+            vo, fo, cid = vo.cpu().numpy(), fo.cpu().numpy().reshape(-1, 3), cid.cpu().numpy()
+            v0 = f0 = 0
+            worst = 0
+            for i, (Vi, Fi) in enumerate(parts):
+                ref = oracle.decimate(Vi, Fi, tg[i], absorb=absorb, placement=int(inverse), rcond_min=1e-3)
+                worst = max(worst, ref["status"])
+                assert int(nvo[i]) == ref["verts"].shape[0] and int(nfo[i]) == ref["facets"].shape[0], i
+                assert np.array_equal(vo[v0:v0 + nvo[i]].view(np.uint32), ref["verts"].view(np.uint32)), i
+                assert np.array_equal(fo[f0:f0 + nfo[i]], ref["facets"].reshape(-1, 3) + v0), i
+                assert np.array_equal(cid[off[i]:off[i + 1]], ref["cluster_id"] + v0), i
+                v0 += int(nvo[i])
+                f0 += int(nfo[i])
+            assert st == worst
+    finally:
+        ctx.close()
