@@ -190,3 +190,32 @@ def test_members_are_summed_in_ascending_index_order(oracle):
         assert not np.array_equal((rev / np.float32(6.0)).astype(np.float32), want)
     else:
         pytest.fail(f"expected a single cluster, got {res['cluster_id']}")
+
+
+def test_output_numbering_follows_the_founding_pairs(oracle):
+    """Output vertices are numbered in ascending order of their representative, which for a cluster
+    is its founding pair's smaller index even when a vertex that joined has a smaller one.  The
+    numbering is rebuilt here from the stage-level result (pairs and joining edges) and compared
+    with the whole run's cluster_id; a flat lattice with a seeded tie order makes joiners with
+    small indices common."""
+    V, F = meshgen.flat_grid(12, 9, spacing=1.0)
+    N = V.shape[0]
+    E = oracle.edges(F)
+    _, key = oracle.edge_costs(V, oracle.vertex_quadrics(V, F), E)
+    seen_small_joiner = False
+    for seed in (3, 4, 5, 6):
+        target = N // 3
+        sel, via, removed = oracle.select_shuffled(E, key, N, N - target, seed, absorb=True)
+        rep = np.arange(N)
+        for e in np.nonzero(sel)[0]:
+            rep[E[e, 1]] = E[e, 0]
+        for w in np.nonzero(via >= 0)[0]:
+            a, b = E[via[w]]
+            rep[w] = rep[b if w == a else a]
+            seen_small_joiner |= bool(w < rep[w])
+        order = np.unique(rep)                      # ascending representatives
+        want = np.searchsorted(order, rep)
+        got = oracle.decimate(V, F, target, max_rounds=1, absorb=True, shuffle_seed=seed)
+        assert np.array_equal(got["cluster_id"], want)
+        assert got["verts"].shape[0] == N - removed
+    assert seen_small_joiner
