@@ -500,3 +500,21 @@ def test_config_batch_hierarchy(ctx, oracle):
         assert np.array_equal(vo.cpu().numpy().view(np.uint32), ref["verts"].view(np.uint32))
         V, F, nv, nf = ref["verts"], ref["facets"], ref["nv"], ref["nf"]
         dV, dF = vo.clone(), fo.clone()
+
+
+def test_contexts_can_be_created_and_destroyed_many_times(pk):
+    """Every context owns device memory, pinned memory, a stream and events: 300 create / use /
+    destroy cycles must leave the device's free memory where it was."""
+    V, F = meshgen.noisy_grid(12, 12, seed=1)
+    dV, dF = dev(V), dev(F)
+    torch.cuda.synchronize()
+    free0, _ = torch.cuda.mem_get_info()
+    for i in range(300):
+        c = pk.Context(50_000, 100_000, 4, device=0)
+        if i % 50 == 0:
+            st, vo, fo, cid = c.picasso_decimate(dV, dF, 40)
+            assert st == 0 and vo.shape[0] == 40
+        c.close()
+    torch.cuda.synchronize()
+    free1, _ = torch.cuda.mem_get_info()
+    assert free0 - free1 < 64 << 20, (free0, free1)
