@@ -518,3 +518,29 @@ def test_contexts_can_be_created_and_destroyed_many_times(pk):
     torch.cuda.synchronize()
     free1, _ = torch.cuda.mem_get_info()
     assert free0 - free1 < 64 << 20, (free0, free1)
+
+
+def test_on_a_stream_of_the_callers(pk, ctx, oracle):
+    """The calls run on the stream they are given: inputs produced on a side stream just before the
+    call are seen, outputs are complete when the call returns (it waits for that stream), and work
+    queued on the same stream afterwards sees them."""
+    V, F = meshgen.icosphere(4, seed=7, jitter=0.05)
+    target = V.shape[0] // 4
+    ref = oracle.decimate(V, F, target)
+    side = torch.cuda.Stream()
+    hV, hF = torch.from_numpy(V).pin_memory(), torch.from_numpy(F).pin_memory()
+    with torch.cuda.stream(side):
+        dV = hV.to("cuda:0", non_blocking=True)
+        dF = hF.to("cuda:0", non_blocking=True)
+        st, vo, fo, cid = ctx.picasso_decimate(dV, dF, target, stream=side)
+        doubled = vo * 2.0
+    assert_same_result(st, vo, fo, cid, ref)
+    side.synchronize()
+    assert np.array_equal(doubled.cpu().numpy(), ref["verts"] * np.float32(2.0))
+    # larger input: the first round's edge sort runs on the context's own stream beside the caller's
+    c = meshgen.config("scene1p2m")
+    V2, F2, t2 = c["verts"], c["facets"], int(c["target"][0])
+    with torch.cuda.stream(side):
+        d2, f2 = dev(V2), dev(F2)
+        st, vo, fo, cid = ctx.picasso_decimate(d2, f2, t2, stream=side)
+    assert_same_result(st, vo, fo, cid, oracle.decimate(V2, F2, t2))
