@@ -197,3 +197,35 @@ def test_room115k_convolutions_at_full_size(pk, ctx, oracle):
     gx_a, gw3_a = oracle.v2f_backward(np.abs(gyh), np.abs(x), F, lev_r, np.abs(w3))
     _close(gxx, gx_r, 4 * 16, gx_a, "gx")
     _close(gw3, gw3_r, _gw_terms(nF, 4), gw3_a, "gw3")
+
+
+def test_features_at_addresses_that_are_not_16_byte_aligned(pk, ctx, oracle):
+    """A channel count that is a multiple of 4 with feature arrays starting 4 bytes off a 16-byte
+    boundary: the entry points must fall back to one channel per lane."""
+    V, F = meshgen.icosphere(3, seed=7, jitter=0.05)
+    N, nF, C, T = V.shape[0], F.shape[0], 8, 3
+    rng = np.random.default_rng(5)
+    x = rng.normal(size=(N, C)).astype(np.float32)
+    w = rng.normal(size=(3, C)).astype(np.float32)
+    wt = rng.normal(size=(T, C)).astype(np.float32)
+    pi = softmax(rng.normal(size=(nF, T)), axis=1).astype(np.float32)
+
+    def off_by_one(a):
+        buf = torch.empty(a.size + 1, dtype=torch.float32, device="cuda:0")
+        view = buf[1:].view(*a.shape)
+        view.copy_(torch.from_numpy(a))
+        assert view.data_ptr() % 16 == 4 and view.is_contiguous()
+        return view
+
+    lev = np.ones(nF, np.int32)
+    y = ctx.picasso_v2f_forward(off_by_one(x), dev(F), None, dev(w))
+    _close(y, oracle.v2f_forward(x, F, lev, w), 9, oracle.v2f_forward(np.abs(x), F, lev, np.abs(w)), "y")
+    off, cor = ctx.picasso_vertex_corner_csr(dev(F), N)
+    yh = y.cpu().numpy()
+    x2 = ctx.picasso_f2v_forward(off_by_one(yh), dev(pi), dev(wt), off, cor, N)
+    _close(x2, oracle.f2v_forward(yh, pi, wt, F, N), (T + 2) * 8, oracle.f2v_forward(np.abs(yh), pi, np.abs(wt), F, N), "x2")
+    gx, gw = ctx.picasso_v2f_backward(off_by_one(yh), off_by_one(x), dev(F), None, dev(w), off, cor)
+    gx_r, gw_r = oracle.v2f_backward(yh, x, F, lev, w)
+    gx_a, gw_a = oracle.v2f_backward(np.abs(yh), np.abs(x), F, lev, np.abs(w))
+    _close(gx, gx_r, 4 * 8, gx_a, "gx")
+    _close(gw, gw_r, _gw_terms(nF, 4), gw_a, "gw")
