@@ -334,3 +334,19 @@ def vertex_corner_csr(facets, n_verts):
     cor = np.zeros(max(1, 3 * facets.shape[0]), np.int32)
     _check(lib().picasso_oracle_vertex_corner_csr(_p(facets), facets.shape[0], int(n_verts), _p(off), _p(cor)))
     return off, cor[: 3 * facets.shape[0]]
+
+
+def f2f_forward(tex, bary, poff, w):
+    tex, bary, poff, w = _f32(tex), _f32(bary), _i32(poff), _f32(w)
+    F, C = poff.shape[0] - 1, tex.shape[1]
+    y = np.zeros((F, C))
+    _check(lib().picasso_oracle_f2f_forward(_p(tex), _p(bary), _p(poff), F, C, _p(w), _p(y)))
+    return y
+
+
+def f2f_backward(gy, tex, bary, poff, w):
+    gy, tex, bary, poff, w = _f32(gy), _f32(tex), _f32(bary), _i32(poff), _f32(w)
+    F, C = poff.shape[0] - 1, tex.shape[1]
+    gtex, gw = np.zeros(tex.shape), np.zeros((3, C))
+    _check(lib().picasso_oracle_f2f_backward(_p(gy), _p(tex), _p(bary), _p(poff), F, C, _p(w), _p(gtex), _p(gw)))
+    return gtex, gw

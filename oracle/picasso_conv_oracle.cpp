@@ -1,8 +1,9 @@
 // picasso_conv_oracle.cpp -- TEST INFRASTRUCTURE, NOT THE PRODUCT.
 //
-// Plain fp64 statements of the two mesh convolutions of the Picasso paper
-// (Sec. 4 "Mesh Convolution": vertex2facet with barycentric interpolation,
-// facet2vertex with Gaussian-mixture fuzzy coefficients; supplementary section
+// Plain fp64 statements of the mesh convolutions of the Picasso paper
+// (Sec. 4 "Mesh Convolution": vertex2facet with barycentric interpolation, its
+// facet2facet variant for textured meshes, facet2vertex with Gaussian-mixture
+// fuzzy coefficients; supplementary section
 // "Backward propagations of different convolutions"), in their depth-wise
 // form: one filter weight per channel (Sec. 4, last paragraph splits every
 // convolution into a depth-wise and a channel-wise operation; the channel-wise
@@ -241,6 +242,54 @@ int picasso_oracle_f2v_backward(const float* gx, const float* y, int32_t F, int3
                 }
             }
         }
+    return OK;
+}
+
+// Facet2facet, depth-wise (Sec. 4.1, paragraph "Facet2Facet convolution"): every facet
+// carries Gamma_f texture points with features of their own, so only the filter is
+// interpolated: W_k = sum_s xi_ks w_s at the point's barycentric coordinates, and
+// J_f = (1 / Gamma_f) sum_k W_k T_k as in the vertex2facet equation.  tex [P,C], bary [P,3],
+// poff [F+1] (points of facet f = poff[f] .. poff[f+1]), w [3,C], y [F,C]; a facet without
+// points gets 0.  The coordinates come with the rendered mesh (the paper does not say how
+// the points are placed).
+int picasso_oracle_f2f_forward(const float* tex, const float* bary, const int32_t* poff, int32_t F, int32_t C,
+                               const float* w, double* y) {
+    if (!tex || !bary || !poff || !w || !y || C < 1) return ERR_INVALID_ARG;
+    for (int f = 0; f < F; ++f) {
+        const int g = poff[f + 1] - poff[f];
+        if (g < 0) return ERR_INVALID_ARG;
+        for (int c = 0; c < C; ++c) {
+            double acc = 0.0;
+            for (int k = poff[f]; k < poff[f + 1]; ++k) {
+                double Wk = 0.0;
+                for (int s = 0; s < 3; ++s) Wk += (double)bary[3 * (size_t)k + s] * (double)w[s * C + c];
+                acc += Wk * (double)tex[(size_t)k * C + c];
+            }
+            y[(size_t)f * C + c] = g > 0 ? acc / g : 0.0;
+        }
+    }
+    return OK;
+}
+
+// Its backward pass (the supplementary notes that it mirrors the vertex2facet one):
+// dJ/dT_k = W_k / Gamma, dJ/dw_s = (1 / Gamma) sum_k xi_ks T_k.  gtex [P,C], gw [3,C].
+int picasso_oracle_f2f_backward(const float* gy, const float* tex, const float* bary, const int32_t* poff, int32_t F,
+                                int32_t C, const float* w, double* gtex, double* gw) {
+    if (!gy || !tex || !bary || !poff || !w || !gtex || !gw || C < 1) return ERR_INVALID_ARG;
+    for (int i = 0; i < 3 * C; ++i) gw[i] = 0.0;
+    for (int f = 0; f < F; ++f) {
+        const int g = poff[f + 1] - poff[f];
+        if (g < 0) return ERR_INVALID_ARG;
+        for (int k = poff[f]; k < poff[f + 1]; ++k)
+            for (int c = 0; c < C; ++c) {
+                double Wk = 0.0;
+                for (int s = 0; s < 3; ++s) Wk += (double)bary[3 * (size_t)k + s] * (double)w[s * C + c];
+                gtex[(size_t)k * C + c] = (double)gy[(size_t)f * C + c] * Wk / g;
+                for (int s = 0; s < 3; ++s)
+                    gw[s * C + c] += (double)gy[(size_t)f * C + c] * (double)bary[3 * (size_t)k + s] *
+                                     (double)tex[(size_t)k * C + c] / g;
+            }
+    }
     return OK;
 }
 

@@ -187,3 +187,48 @@ def test_facet_geometry_against_numpy_fp64(oracle):
     np.testing.assert_allclose(n, cr / ln[:, None], atol=1e-5)
     lev = oracle.facet_levels(a)
     assert (lev == 2).sum() == (a == a.max()).sum() and set(lev.tolist()) == {1, 2}
+
+
+def _textured(rng, F, x, max_level=4):
+    """Texture points of every facet = the lattice of a random level, their features = the
+    barycentric interpolation of the vertex features (what vertex2facet interpolates itself)."""
+    level = rng.integers(1, max_level + 1, F.shape[0]).astype(np.int32)
+    bary = [_lattice(int(k)) for k in level]
+    poff = np.concatenate([[0], np.cumsum([b.shape[0] for b in bary])]).astype(np.int32)
+    tex = np.concatenate([b @ x.astype(float)[F[f]] for f, b in enumerate(bary)])
+    return level, np.concatenate(bary).astype(np.float32), poff, tex.astype(np.float32)
+
+
+def test_f2f_on_interpolated_textures_is_vertex2facet(oracle):
+    """Facet2facet differs from vertex2facet only in that the points' features are given: fed with
+    the features vertex2facet would interpolate, at the same points, it must give the same facet
+    features (up to the fp32 rounding of the stored textures)."""
+    rng = np.random.default_rng(7)
+    V, F = meshgen.icosphere(2, seed=None)
+    x = rng.normal(size=(V.shape[0], 5)).astype(np.float32)
+    w = rng.normal(size=(3, 5)).astype(np.float32)
+    level, bary, poff, tex = _textured(rng, F, x)
+    got = oracle.f2f_forward(tex, bary, poff, w)
+    want = oracle.v2f_forward(x, F, level, w)
+    np.testing.assert_allclose(got, want, rtol=0, atol=2e-6)
+    # a facet without points gets 0; one point with weight w gives w . xi times its feature
+    y = oracle.f2f_forward(np.array([[2.0, 3.0]], np.float32), np.array([[0.5, 0.25, 0.25]], np.float32), [0, 0, 1],
+                           np.array([[1, 1], [2, 4], [4, 8]], np.float32))
+    assert y.tolist() == [[0.0, 0.0], [2.0 * 2.0, 3.0 * 3.5]]
+
+
+def test_f2f_backward_is_the_gradient_and_the_adjoint(oracle):
+    rng = np.random.default_rng(8)
+    V, F = meshgen.icosphere(1, seed=None)
+    C = 3
+    x = rng.normal(size=(V.shape[0], C)).astype(np.float32)
+    w = rng.normal(size=(3, C)).astype(np.float32)
+    _, bary, poff, tex = _textured(rng, F, x, max_level=3)
+    tex = (tex + rng.normal(size=tex.shape)).astype(np.float32)   # textures of their own
+    gy = rng.normal(size=(F.shape[0], C)).astype(np.float32)
+    gtex, gw = oracle.f2f_backward(gy, tex, bary, poff, w)
+    loss = lambda tt, ww: float((oracle.f2f_forward(tt, bary, poff, ww) * gy).sum())
+    np.testing.assert_allclose(gtex, _fd(lambda a: loss(a, w), tex), rtol=2e-4, atol=2e-4)
+    np.testing.assert_allclose(gw, _fd(lambda a: loss(tex, a), w), rtol=2e-4, atol=2e-4)
+    assert loss(tex, w) == pytest.approx(float((gtex * tex).sum()), rel=1e-6)
+    assert loss(tex, w) == pytest.approx(float((gw * w).sum()), rel=1e-6)
