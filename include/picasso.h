@@ -328,6 +328,23 @@ int picasso_v2f_backward(picasso_ctx* ctx, void* stream, const float* d_gy, cons
                          const int32_t* d_facets, int32_t F, const int32_t* d_level, const float* d_w,
                          const int32_t* d_offsets, const int32_t* d_corners, float* d_gx, float* d_gw);
 
+/* Facet2facet (Sec. 4.1, for meshes rendered with textures): facet f carries the
+ * texture points d_poff[f] .. d_poff[f+1] (d_poff [F+1], P points in all) with
+ * features d_tex [P,C] and barycentric coordinates d_bary [P,3] that come with
+ * the rendering; only the filter d_w [3,C] is interpolated, W_k = sum_s xi_ks w_s,
+ * and J_f = (1 / Gamma_f) sum_k W_k T_k per channel (0 for a facet without
+ * points).  d_y [F,C].  Offsets outside [0, P] are clipped. */
+int picasso_f2f_forward(picasso_ctx* ctx, void* stream, const float* d_tex, const float* d_bary,
+                        const int32_t* d_poff, int32_t F, int32_t P, int32_t C, const float* d_w, float* d_y);
+
+/* Its backward pass (the supplementary refers to the vertex2facet kernel for it):
+ * d_gtex [P,C] with respect to the texture features (rows of points that belong
+ * to no facet are left untouched), d_gw [3,C] with respect to the filter; either
+ * may be NULL.  d_gw uses the context's workspace as above. */
+int picasso_f2f_backward(picasso_ctx* ctx, void* stream, const float* d_gy, const float* d_tex, const float* d_bary,
+                         const int32_t* d_poff, int32_t F, int32_t P, int32_t C, const float* d_w, float* d_gtex,
+                         float* d_gw);
+
 /* Facet2vertex (Sec. 4.2, last equation): per channel I_v = (1 / |N(v)|) sum over the
  * corners at v of (sum_t pi_ft w_t) J_f; a vertex without facets gets 0.
  * d_y [F,C], d_pi [F,T], d_w [T,C] -> d_x [N,C]. */

@@ -42,7 +42,8 @@ EXPORTED_SYMBOLS = (
     "picasso_edge_costs", "picasso_radix_sort", "picasso_kernel_timing",
     "picasso_device_copy", "picasso_bucket_sort", "picasso_cluster_csr", "picasso_replace_mapping",
     "picasso_vertex_corner_csr", "picasso_facet_geometry", "picasso_fuzzy_coefficients", "picasso_v2f_forward",
-    "picasso_v2f_backward", "picasso_f2v_forward", "picasso_f2v_backward", "picasso_pool_forward",
+    "picasso_v2f_backward", "picasso_f2f_forward", "picasso_f2f_backward", "picasso_f2v_forward",
+    "picasso_f2v_backward", "picasso_pool_forward",
     "picasso_pool_backward", "picasso_unpool_forward", "picasso_unpool_backward",
 )
 
@@ -136,6 +137,10 @@ def load_library():
     lib.picasso_v2f_forward.argtypes = [vp, vp, vp, i32, i32, vp, i32, vp, vp, vp]
     lib.picasso_v2f_backward.restype = ctypes.c_int
     lib.picasso_v2f_backward.argtypes = [vp, vp, vp, vp, i32, i32, vp, i32, vp, vp, vp, vp, vp, vp]
+    lib.picasso_f2f_forward.restype = ctypes.c_int
+    lib.picasso_f2f_forward.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, vp, vp]
+    lib.picasso_f2f_backward.restype = ctypes.c_int
+    lib.picasso_f2f_backward.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp]
     lib.picasso_f2v_forward.restype = ctypes.c_int
     lib.picasso_f2v_forward.argtypes = [vp, vp, vp, i32, i32, vp, i32, vp, vp, vp, i32, vp]
     lib.picasso_f2v_backward.restype = ctypes.c_int
@@ -487,6 +492,32 @@ class Context:
         if st != PICASSO_OK:
             self._raise(st)
         return gx, gw
+
+    def picasso_f2f_forward(self, tex, bary, poff, w, stream=None):
+        import torch
+        P, C, F = int(tex.shape[0]), int(tex.shape[1]), int(poff.shape[0]) - 1
+        y = torch.empty((F, C), dtype=torch.float32, device=tex.device)
+        st = self._lib.picasso_f2f_forward(self._h, _stream_ptr(stream), _dev_ptr(tex, torch.float32, "tex"),
+                                           _dev_ptr(bary, torch.float32, "bary"), _dev_ptr(poff, torch.int32, "poff"),
+                                           F, P, C, _dev_ptr(w, torch.float32, "w"), _dev_ptr(y, torch.float32, "y"))
+        if st != PICASSO_OK:
+            self._raise(st)
+        return y
+
+    def picasso_f2f_backward(self, gy, tex, bary, poff, w, stream=None):
+        """Returns (gtex[P,C], gw[3,C])."""
+        import torch
+        P, C, F = int(tex.shape[0]), int(tex.shape[1]), int(poff.shape[0]) - 1
+        gtex = torch.zeros((P, C), dtype=torch.float32, device=tex.device)
+        gw = torch.empty((3, C), dtype=torch.float32, device=tex.device)
+        st = self._lib.picasso_f2f_backward(self._h, _stream_ptr(stream), _dev_ptr(gy, torch.float32, "gy"),
+                                            _dev_ptr(tex, torch.float32, "tex"), _dev_ptr(bary, torch.float32, "bary"),
+                                            _dev_ptr(poff, torch.int32, "poff"), F, P, C,
+                                            _dev_ptr(w, torch.float32, "w"), _dev_ptr(gtex, torch.float32, "gtex"),
+                                            _dev_ptr(gw, torch.float32, "gw"))
+        if st != PICASSO_OK:
+            self._raise(st)
+        return gtex, gw
 
     def picasso_f2v_forward(self, y, pi, w, offsets, corners, n_verts, out=None, stream=None):
         import torch

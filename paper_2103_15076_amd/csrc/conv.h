@@ -357,6 +357,109 @@ struct V2fWeightTerm {
 };
 
 // ---------------------------------------------------------------------------
+// Facet2facet (Sec. 4.1, for meshes rendered with textures): every facet has
+// Gamma_f texture points with features of their own and barycentric coordinates;
+// only the filter is interpolated, W_k = sum_s xi_ks w_s, and J_f = (1 / Gamma_f)
+// sum_k W_k T_k.  Points of facet f = poff[f] .. poff[f+1]; tex [P,C], bary [P,3].
+// One lane owns VEC channels of one facet and walks the facet's points in order.
+// ---------------------------------------------------------------------------
+template <int VEC>
+__device__ __forceinline__ Pack<VEC> point_filter(const float* __restrict__ bary, const Pack<VEC>* ws, int k) {
+    const float x0 = bary[3 * (size_t)k], x1 = bary[3 * (size_t)k + 1], x2 = bary[3 * (size_t)k + 2];
+    Pack<VEC> wk;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) wk.v[i] = (x0 * ws[0].v[i] + x1 * ws[1].v[i]) + x2 * ws[2].v[i];
+    return wk;
+}
+
+template <int VEC>
+__global__ __launch_bounds__(BLOCK) void f2f_forward_kernel(const float* __restrict__ tex,
+                                                            const float* __restrict__ bary,
+                                                            const int* __restrict__ poff, int F, int P, int C,
+                                                            const float* __restrict__ w, float* __restrict__ y) {
+    const int Q = C / VEC;
+    const long long idx = (long long)blockIdx.x * BLOCK + threadIdx.x;
+    const int f = (int)(idx / Q), q = (int)(idx % Q);
+    if (f >= F) return;
+    const size_t co = (size_t)q * VEC;
+    Pack<VEC> ws[3], acc;
+#pragma unroll
+    for (int s = 0; s < 3; ++s) ws[s] = load_pack<VEC>(w + (size_t)s * C + co);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) acc.v[i] = 0.0f;
+    const int kb = max(poff[f], 0), ke = min(poff[f + 1], P);
+    for (int k = kb; k < ke; ++k) {
+        const Pack<VEC> wk = point_filter<VEC>(bary, ws, k);
+        const Pack<VEC> t = load_pack<VEC>(tex + (size_t)k * C + co);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc.v[i] = acc.v[i] + wk.v[i] * t.v[i];
+    }
+    const float g = (float)(ke - kb);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) acc.v[i] = (ke > kb) ? acc.v[i] / g : 0.0f;
+    store_pack<VEC>(y + (size_t)f * C + co, acc);
+}
+
+// dJ/dT_k = W_k / Gamma_f, times the facet's incoming gradient: the same walk, one row written per point.
+template <int VEC>
+__global__ __launch_bounds__(BLOCK) void f2f_backward_tex_kernel(const float* __restrict__ gy,
+                                                                 const float* __restrict__ bary,
+                                                                 const int* __restrict__ poff, int F, int P, int C,
+                                                                 const float* __restrict__ w,
+                                                                 float* __restrict__ gtex) {
+    const int Q = C / VEC;
+    const long long idx = (long long)blockIdx.x * BLOCK + threadIdx.x;
+    const int f = (int)(idx / Q), q = (int)(idx % Q);
+    if (f >= F) return;
+    const size_t co = (size_t)q * VEC;
+    Pack<VEC> ws[3];
+#pragma unroll
+    for (int s = 0; s < 3; ++s) ws[s] = load_pack<VEC>(w + (size_t)s * C + co);
+    const Pack<VEC> g = load_pack<VEC>(gy + (size_t)f * C + co);
+    const int kb = max(poff[f], 0), ke = min(poff[f + 1], P);
+    const float n = (float)(ke - kb);
+    for (int k = kb; k < ke; ++k) {
+        Pack<VEC> wk = point_filter<VEC>(bary, ws, k);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) wk.v[i] = (g.v[i] * wk.v[i]) / n;
+        store_pack<VEC>(gtex + (size_t)k * C + co, wk);
+    }
+}
+
+// dJ/dw_s = (1 / Gamma_f) sum_k xi_ks T_k, times the incoming gradient: the three rows of gw.
+struct F2fWeightTerm {
+    const float* gy;
+    const float* tex;
+    const float* bary;
+    const int* poff;
+    int C, P;
+    template <int VEC>
+    __device__ __forceinline__ void add(int f, int q, float* acc) const {
+        const size_t co = (size_t)q * VEC;
+        const int kb = max(poff[f], 0), ke = min(poff[f + 1], P);
+        if (ke <= kb) return;
+        const Pack<VEC> g = load_pack<VEC>(gy + (size_t)f * C + co);
+        float m[3 * VEC];
+#pragma unroll
+        for (int i = 0; i < 3 * VEC; ++i) m[i] = 0.0f;
+        for (int k = kb; k < ke; ++k) {
+            const Pack<VEC> t = load_pack<VEC>(tex + (size_t)k * C + co);
+#pragma unroll
+            for (int s = 0; s < 3; ++s) {
+                const float x = bary[3 * (size_t)k + s];
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) m[s * VEC + i] = m[s * VEC + i] + x * t.v[i];
+            }
+        }
+        const float n = (float)(ke - kb);
+#pragma unroll
+        for (int s = 0; s < 3; ++s)
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[s * VEC + i] = acc[s * VEC + i] + (g.v[i] * m[s * VEC + i]) / n;
+    }
+};
+
+// ---------------------------------------------------------------------------
 // Facet2vertex (Sec. 4.2): I_v = (1 / |N(v)|) sum_{f in N(v)} (sum_t pi_ft w_t) J_f,
 // N(v) = the corners at v in ascending order.
 // ---------------------------------------------------------------------------

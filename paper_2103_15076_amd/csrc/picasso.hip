@@ -1255,6 +1255,42 @@ int picasso_v2f_backward(picasso_ctx* c, void* stream, const float* d_gy, const 
     return PICASSO_OK;
 }
 
+int picasso_f2f_forward(picasso_ctx* c, void* stream, const float* d_tex, const float* d_bary, const int32_t* d_poff,
+                        int32_t F, int32_t P, int32_t C, const float* d_w, float* d_y) {
+    if (!c || !d_tex || !d_bary || !d_poff || F < 1 || P < 0 || C < 1 || !d_w || !d_y) return PICASSO_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(c, hipSetDevice(c->device));
+    if (conv_vec4(C, {d_tex, d_w, d_y}))
+        conv::f2f_forward_kernel<4><<<pool::grid_for((long long)F * (C / 4)), pool::BLOCK, 0, s>>>(d_tex, d_bary, d_poff, F, P, C, d_w, d_y);
+    else
+        conv::f2f_forward_kernel<1><<<pool::grid_for((long long)F * C), pool::BLOCK, 0, s>>>(d_tex, d_bary, d_poff, F, P, C, d_w, d_y);
+    HIP_TRY(c, hipGetLastError());
+    return PICASSO_OK;
+}
+
+int picasso_f2f_backward(picasso_ctx* c, void* stream, const float* d_gy, const float* d_tex, const float* d_bary,
+                         const int32_t* d_poff, int32_t F, int32_t P, int32_t C, const float* d_w, float* d_gtex,
+                         float* d_gw) {
+    if (!c || !d_gy || !d_tex || !d_bary || !d_poff || F < 1 || P < 0 || C < 1 || !d_w || (!d_gtex && !d_gw))
+        return PICASSO_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(c, hipSetDevice(c->device));
+    const bool vec4 = conv_vec4(C, {d_gy, d_tex, d_w, d_gtex});
+    if (d_gtex) {
+        if (vec4)
+            conv::f2f_backward_tex_kernel<4><<<pool::grid_for((long long)F * (C / 4)), pool::BLOCK, 0, s>>>(d_gy, d_bary, d_poff, F, P, C, d_w, d_gtex);
+        else
+            conv::f2f_backward_tex_kernel<1><<<pool::grid_for((long long)F * C), pool::BLOCK, 0, s>>>(d_gy, d_bary, d_poff, F, P, C, d_w, d_gtex);
+    }
+    if (d_gw) {
+        conv::F2fWeightTerm term{d_gy, d_tex, d_bary, d_poff, C, P};
+        const int rc = reduce_filter_rows<3>(c, s, term, F, C, vec4, 3, d_gw);
+        if (rc != PICASSO_OK) return rc;
+    }
+    HIP_TRY(c, hipGetLastError());
+    return PICASSO_OK;
+}
+
 int picasso_f2v_forward(picasso_ctx* c, void* stream, const float* d_y, int32_t F, int32_t C, const float* d_pi,
                         int32_t T, const float* d_w, const int32_t* d_offsets, const int32_t* d_corners, int32_t N,
                         float* d_x) {

@@ -229,3 +229,51 @@ def test_features_at_addresses_that_are_not_16_byte_aligned(pk, ctx, oracle):
     gx_a, gw_a = oracle.v2f_backward(np.abs(yh), np.abs(x), F, lev, np.abs(w))
     _close(gx, gx_r, 4 * 8, gx_a, "gx")
     _close(gw, gw_r, _gw_terms(nF, 4), gw_a, "gw")
+
+
+@pytest.mark.parametrize("C", [3, 16])
+def test_facet2facet_forward_and_backward(pk, ctx, oracle, C):
+    """Texture points per facet: 0 to 40 of them at random barycentric coordinates with features of
+    their own; the facet feature is a sum of Gamma terms (3 products each)."""
+    rng = np.random.default_rng(C)
+    nF = 3000
+    gamma = rng.integers(0, 41, nF)
+    gamma[:5] = [0, 1, 2, 40, 0]
+    poff = np.concatenate([[0], np.cumsum(gamma)]).astype(np.int32)
+    P = int(poff[-1])
+    bary = rng.dirichlet(np.ones(3), size=P).astype(np.float32)
+    tex = rng.normal(size=(P, C)).astype(np.float32)
+    w = rng.normal(size=(3, C)).astype(np.float32)
+    gy = rng.normal(size=(nF, C)).astype(np.float32)
+    y = ctx.picasso_f2f_forward(dev(tex), dev(bary), dev(poff), dev(w))
+    _close(y, oracle.f2f_forward(tex, bary, poff, w), 4 * 40, oracle.f2f_forward(np.abs(tex), bary, poff, np.abs(w)), "y")
+    assert np.all(y.cpu().numpy()[gamma == 0] == 0)
+    gtex, gw = ctx.picasso_f2f_backward(dev(gy), dev(tex), dev(bary), dev(poff), dev(w))
+    gt_r, gw_r = oracle.f2f_backward(gy, tex, bary, poff, w)
+    gt_a, gw_a = oracle.f2f_backward(np.abs(gy), np.abs(tex), bary, poff, np.abs(w))
+    _close(gtex, gt_r, 8, gt_a, "gtex")
+    _close(gw, gw_r, _gw_terms(nF, 4 * 40), gw_a, "gw")
+
+
+def test_facet2facet_on_interpolated_textures_equals_vertex2facet(pk, ctx, oracle):
+    """The two facet convolutions differ only in where the points' features come from."""
+    rng = np.random.default_rng(3)
+    V, F = meshgen.icosphere(4, seed=2)
+    C = 8
+    x = rng.normal(size=(V.shape[0], C)).astype(np.float32)
+    w = rng.normal(size=(3, C)).astype(np.float32)
+    level = rng.integers(1, 5, F.shape[0]).astype(np.int32)
+
+    def lattice(k):
+        if k == 1:
+            return np.array([[1 / 3, 1 / 3, 1 / 3]])
+        return np.array([(i, j, k - 1 - i - j) for i in range(k) for j in range(k - i)], float) / (k - 1)
+
+    bary = [lattice(int(k)) for k in level]
+    poff = np.concatenate([[0], np.cumsum([b.shape[0] for b in bary])]).astype(np.int32)
+    tex = np.concatenate([b @ x.astype(float)[F[f]] for f, b in enumerate(bary)]).astype(np.float32)
+    bary = np.concatenate(bary).astype(np.float32)
+    a = ctx.picasso_f2f_forward(dev(tex), dev(bary), dev(poff), dev(w)).cpu().numpy()
+    b = ctx.picasso_v2f_forward(dev(x), dev(F), dev(level), dev(w)).cpu().numpy()
+    scale = oracle.v2f_forward(np.abs(x), F, level, np.abs(w))
+    assert np.all(np.abs(a - b) <= 64 * EPS * scale + 1e-30)
