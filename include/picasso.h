@@ -5,7 +5,7 @@
  * supplementary section "Quadric error computation"), and around it the
  * operators the paper defines on its results: pooling and unpooling over the
  * vertex clusters (Sec. 3), the replace / mapping tensors, and the
- * vertex2facet / facet2vertex convolutions (Sec. 4).  Every step runs in
+ * vertex2facet / facet2facet / facet2vertex convolutions (Sec. 4).  Every step runs in
  * hand-written HIP kernels; there is no CPU fallback.
  *
  * Conventions for every call
