@@ -544,3 +544,17 @@ def test_on_a_stream_of_the_callers(pk, ctx, oracle):
         d2, f2 = dev(V2), dev(F2)
         st, vo, fo, cid = ctx.picasso_decimate(d2, f2, t2, stream=side)
     assert_same_result(st, vo, fo, cid, oracle.decimate(V2, F2, t2))
+
+
+@pytest.mark.parametrize("w,h,what", [
+    (419, 419, "just below 2^20 half-edges: 256-bucket sort, one lane per edge in every sub-round"),
+    (420, 419, "just above 2^20 half-edges: 4096-bucket sort, sparse sub-rounds"),
+    (363, 362, "just below 2^18 facets: one stream"),
+    (364, 363, "just above 2^18 facets: the first round's edge sort on the second stream"),
+])
+def test_sizes_on_either_side_of_the_path_switches(ctx, oracle, w, h, what):
+    V, F = meshgen.noisy_grid(w, h, seed=w + h, noise=0.004)
+    target = V.shape[0] // 3
+    print(f"switch {w}x{h}: N={V.shape[0]} F={F.shape[0]} 3F={3 * F.shape[0]} ({what})", flush=True)
+    st, vo, fo, cid = ctx.picasso_decimate(dev(V), dev(F), target)
+    assert_same_result(st, vo, fo, cid, oracle.decimate(V, F, target))
