@@ -558,3 +558,20 @@ def test_sizes_on_either_side_of_the_path_switches(ctx, oracle, w, h, what):
     print(f"switch {w}x{h}: N={V.shape[0]} F={F.shape[0]} 3F={3 * F.shape[0]} ({what})", flush=True)
     st, vo, fo, cid = ctx.picasso_decimate(dev(V), dev(F), target)
     assert_same_result(st, vo, fo, cid, oracle.decimate(V, F, target))
+
+
+@pytest.mark.parametrize("w,keys_per_lane", [(64, 4), (120, 8), (168, 16), (240, 32)])
+def test_every_width_of_the_per_mesh_budget_search(ctx, oracle, w, keys_per_lane):
+    """One run that forms about 0.45 N pairs and may keep a few hundred, or all but a few: the
+    search kernel holds 4, 8, 16 or 32 cost keys per lane depending on how many pairs formed."""
+    V, F = meshgen.noisy_grid(w, w, seed=w, noise=0.01)
+    N = V.shape[0]
+    E = oracle.edges(F)
+    _, key = oracle.edge_costs(V, oracle.vertex_quadrics(V, F), E)
+    _, pairs = oracle.select(E, key, N, N)
+    assert (keys_per_lane // 2) * 1024 < pairs <= keys_per_lane * 1024 or keys_per_lane == 4, pairs
+    for keep in (300, pairs - 7):
+        print(f"budget search w={w}: {pairs} pairs formed, {keep} kept", flush=True)
+        st, vo, fo, cid = ctx.picasso_decimate(dev(V), dev(F), N - keep)
+        assert_same_result(st, vo, fo, cid, oracle.decimate(V, F, N - keep))
+        assert vo.shape[0] == N - keep
