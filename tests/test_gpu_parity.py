@@ -575,3 +575,19 @@ def test_every_width_of_the_per_mesh_budget_search(ctx, oracle, w, keys_per_lane
         st, vo, fo, cid = ctx.picasso_decimate(dev(V), dev(F), N - keep)
         assert_same_result(st, vo, fo, cid, oracle.decimate(V, F, N - keep))
         assert vo.shape[0] == N - keep
+
+
+@pytest.mark.parametrize("batch", [1, 2])
+def test_few_sub_rounds_between_looks_of_the_host(pk, ctx, oracle, batch):
+    """With only one or two grid-wide sub-rounds per batch the single-workgroup tail finds more live
+    edges than it can take, hands back, and the host queues further batches: same result."""
+    ctx.set_option(pk.PICASSO_OPT_SUBROUND_BATCH, batch)
+    try:
+        for name, (V, F) in list(_small_meshes()) + [("room115k", (meshgen.config("room115k")["verts"],
+                                                                 meshgen.config("room115k")["facets"]))]:
+            target = V.shape[0] // 3
+            print(f"sub-round batch {batch}: {name}", flush=True)
+            st, vo, fo, cid = ctx.picasso_decimate(dev(V), dev(F), target)
+            assert_same_result(st, vo, fo, cid, oracle.decimate(V, F, target))
+    finally:
+        ctx.set_option(pk.PICASSO_OPT_SUBROUND_BATCH, 16)
