@@ -591,3 +591,34 @@ def test_few_sub_rounds_between_looks_of_the_host(pk, ctx, oracle, batch):
             assert_same_result(st, vo, fo, cid, oracle.decimate(V, F, target))
     finally:
         ctx.set_option(pk.PICASSO_OPT_SUBROUND_BATCH, 16)
+
+
+def test_statistics_and_timing_options_do_not_change_the_result(pk, ctx, oracle):
+    """The per-round statistics agree with the oracle's bookkeeping; stage events and the kernel's
+    launch events are measurement only."""
+    V, F = meshgen.icosphere(5, seed=3)
+    N, target = V.shape[0], V.shape[0] // 6
+    ref = oracle.decimate(V, F, target)
+    for stage, every in ((0, 0), (1, 0), (0, 1), (1, 2)):
+        ctx.set_option(pk.PICASSO_OPT_STAGE_TIMING, stage)
+        ctx.set_option(pk.PICASSO_OPT_KERNEL_TIMING, every)
+        try:
+            ctx.picasso_kernel_timing(reset=True)
+            st_ = pk.picasso_stats()
+            for _ in range(3):
+                st, vo, fo, cid = ctx.picasso_decimate(dev(V), dev(F), target, stats=st_)
+                assert_same_result(st, vo, fo, cid, ref)
+            d = st_.as_dict()
+            assert d["rounds"] == ref["rounds"] and d["nv_out"] == target and d["nf_out"] == ref["facets"].shape[0]
+            assert d["nv"][0] == N and d["nf"][0] == F.shape[0] and d["ne"][0] == oracle.edges(F).shape[0]
+            assert all(d["nv"][r + 1] == d["nv"][r] - d["nsel"][r] for r in range(d["rounds"] - 1))
+            assert d["nv"][-1] - d["nsel"][-1] == target and d["ms_total"] > 0
+            if stage:
+                assert sum(sum(r.values()) for r in d["ms_stage"]) > 0
+            kt = ctx.picasso_kernel_timing(reset=True)
+            assert (kt["launches"] > 0) == (every > 0)
+            if every:
+                assert kt["ms_total"] > 0 and kt["bytes_total"] > 0
+        finally:
+            ctx.set_option(pk.PICASSO_OPT_STAGE_TIMING, 0)
+            ctx.set_option(pk.PICASSO_OPT_KERNEL_TIMING, 0)
