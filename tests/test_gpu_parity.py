@@ -622,3 +622,30 @@ def test_statistics_and_timing_options_do_not_change_the_result(pk, ctx, oracle)
         finally:
             ctx.set_option(pk.PICASSO_OPT_STAGE_TIMING, 0)
             ctx.set_option(pk.PICASSO_OPT_KERNEL_TIMING, 0)
+
+
+def test_vertices_of_medium_degree(ctx, oracle):
+    """Cones whose apex has 17 to 130 facets: per-vertex groups of the sorts between the register
+    network (up to 16 keys), the in-place insertion (up to 64) and the radix fallback beyond."""
+    rng = np.random.default_rng(4)
+    Vs, Fs = [], []
+    base = 0
+    for d in (3, 15, 16, 17, 31, 32, 33, 63, 64, 65, 96, 130) * 3:
+        ang = np.linspace(0.0, 2.0 * np.pi, d, endpoint=False)
+        ring = np.stack([np.cos(ang), np.sin(ang), np.zeros(d)], axis=1) * rng.uniform(0.5, 2.0)
+        apex = np.array([[0.0, 0.0, rng.uniform(0.2, 1.5)]])
+        P = np.concatenate([apex, ring]) + rng.normal(scale=0.01, size=(d + 1, 3)) + rng.uniform(-50, 50, size=(1, 3))
+        tri = np.array([[0, 1 + i, 1 + (i + 1) % d] for i in range(d)])
+        Vs.append(P.astype(np.float32))
+        Fs.append(tri + base)
+        base += d + 1
+    V = np.concatenate(Vs)
+    F = np.concatenate(Fs).astype(np.int32)
+    Q = ctx.picasso_vertex_quadrics(dev(V), dev(F)).cpu().numpy()
+    assert np.array_equal(Q.view(np.uint32), oracle.vertex_quadrics(V, F).view(np.uint32))
+    E, cost = ctx.picasso_edge_costs(dev(V), dev(F))
+    assert np.array_equal(E.cpu().numpy(), oracle.edges(F))
+    for frac in (0.7, 0.3):
+        target = int(V.shape[0] * frac)
+        st, vo, fo, cid = ctx.picasso_decimate(dev(V), dev(F), target)
+        assert_same_result(st, vo, fo, cid, oracle.decimate(V, F, target))
