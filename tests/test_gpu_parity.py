@@ -639,8 +639,14 @@ def test_vertices_of_medium_degree(ctx, oracle):
         Vs.append(P.astype(np.float32))
         Fs.append(tri + base)
         base += d + 1
+    # The cones come first (low indices) in a mesh of about 2^17 vertices: then the sorts' per-bucket
+    # radix pass ends exactly at the lower vertex's bits, and an apex's edges (facets) form one group.
+    room = meshgen.config("room115k")
+    Vs.append(room["verts"])
+    Fs.append(room["facets"] + base)
     V = np.concatenate(Vs)
     F = np.concatenate(Fs).astype(np.int32)
+    assert 1 << 16 < V.shape[0] <= 1 << 17
     Q = ctx.picasso_vertex_quadrics(dev(V), dev(F)).cpu().numpy()
     assert np.array_equal(Q.view(np.uint32), oracle.vertex_quadrics(V, F).view(np.uint32))
     E, cost = ctx.picasso_edge_costs(dev(V), dev(F))
