@@ -18,7 +18,9 @@
  *   - A context owns its scratch workspace, a small pinned host buffer that its
  *     kernels write counters into, and one internal stream of default priority;
  *     it is bound to one device, which the calls make current; calls on one
- *     context must not overlap in time.  Inputs are never modified.
+ *     context must not overlap in time.  Contexts share no state: different
+ *     contexts may be used from different host threads at the same time.
+ *     Inputs are never modified.
  *   - Nothing is allocated inside the decimate calls.
  */
 #ifndef PICASSO_H

@@ -655,3 +655,54 @@ def test_vertices_of_medium_degree(ctx, oracle):
         target = int(V.shape[0] * frac)
         st, vo, fo, cid = ctx.picasso_decimate(dev(V), dev(F), target)
         assert_same_result(st, vo, fo, cid, oracle.decimate(V, F, target))
+
+
+def test_two_contexts_on_two_host_threads(pk, oracle):
+    """Contexts share nothing: two host threads, each with a context, a stream and options of its
+    own, decimate different meshes at the same time and each result matches the oracle's."""
+    import threading
+    room = meshgen.config("room115k")
+    jobs = [
+        dict(V=room["verts"], F=room["facets"], target=int(room["target"][0]), opts={}),
+        dict(V=None, F=None, target=None, opts=dict(placement=1, rcond_min=1e-3, absorb=True, shuffle_seed=77)),
+    ]
+    jobs[1]["V"], jobs[1]["F"] = meshgen.icosphere(6, seed=2, jitter=0.05)
+    jobs[1]["target"] = jobs[1]["V"].shape[0] // 5
+    for j in jobs:
+        j["ref"] = oracle.decimate(j["V"], j["F"], j["target"], **j["opts"])
+        j["ctx"] = pk.Context(200_000, 400_000, 4, device=0)
+        j["stream"] = torch.cuda.Stream()
+        j["dV"], j["dF"] = dev(j["V"]), dev(j["F"])
+        j["out"], j["err"] = [], None
+    c1 = jobs[1]["ctx"]
+    c1.set_placement(pk.PICASSO_PLACE_INVERSE, 1e-3)
+    c1.set_option(pk.PICASSO_OPT_ABSORB, 1)
+    c1.set_option(pk.PICASSO_OPT_SHUFFLE_SEED, 77)
+    torch.cuda.synchronize()
+    start = threading.Barrier(2)
+
+    def work(j):
+        try:
+            with torch.cuda.stream(j["stream"]):
+                start.wait(timeout=30)
+                for _ in range(20):
+                    j["out"].append(j["ctx"].picasso_decimate(j["dV"], j["dF"], j["target"], stream=j["stream"]))
+        except Exception as e:  # noqa: BLE001 -- reported by the main thread below
+            j["err"] = e
+
+    threads = [threading.Thread(target=work, args=(j,)) for j in jobs]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=100)
+        assert not t.is_alive()
+    torch.cuda.synchronize()
+    try:
+        for j in jobs:
+            assert j["err"] is None, j["err"]
+            assert len(j["out"]) == 20
+            for st, vo, fo, cid in j["out"]:
+                assert_same_result(st, vo, fo, cid, j["ref"])
+    finally:
+        for j in jobs:
+            j["ctx"].close()

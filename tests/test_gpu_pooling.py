@@ -122,6 +122,46 @@ def test_empty_clusters_ties_and_unaligned_channels(pk, ctx, oracle):
     assert not yw.any()
 
 
+def test_features_at_addresses_that_are_not_16_byte_aligned(pk, ctx, oracle):
+    """C a multiple of 4 with feature arrays 4 bytes off a 16-byte boundary: one channel per lane is
+    used instead of four; sums run in the same order either way, so the results are bit-identical
+    to those from aligned arrays."""
+    rng = np.random.default_rng(21)
+    n_in, n_out, C = 3001, 700, 8
+    cid = _clusters(rng, n_in, n_out)
+    x = rng.normal(size=(n_in, C)).astype(np.float32)
+    g = rng.normal(size=(n_out, C)).astype(np.float32)
+    w = rng.uniform(0.1, 2.0, size=n_in).astype(np.float32)
+
+    def off_by_one(a):
+        buf = torch.empty(a.size + 1, dtype=torch.float32, device="cuda:0")
+        view = buf[1:].view(*a.shape)
+        view.copy_(torch.from_numpy(a))
+        assert view.data_ptr() % 16 == 4 and view.is_contiguous()
+        return view
+
+    dcid, dw = dev(cid), dev(w)
+    off, mem = ctx.picasso_cluster_csr(dcid, n_out)
+    for mode in (pk.PICASSO_POOL_AVG, pk.PICASSO_POOL_SUM, pk.PICASSO_POOL_WEIGHTED):
+        a = ctx.picasso_pool_forward(mode, dev(x), off, mem, weight=dw).cpu().numpy()
+        b = ctx.picasso_pool_forward(mode, off_by_one(x), off, mem, weight=dw).cpu().numpy()
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), mode
+        a = ctx.picasso_pool_backward(mode, dev(g), dcid, off, mem, weight=dw).cpu().numpy()
+        b = ctx.picasso_pool_backward(mode, off_by_one(g), dcid, off, mem, weight=dw).cpu().numpy()
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), mode
+    y, arg = ctx.picasso_pool_forward(pk.PICASSO_POOL_MAX, off_by_one(x), off, mem)
+    ry, rarg = oracle.pool_forward(oracle.POOL_MAX, x, cid, n_out)
+    assert np.array_equal(y.cpu().numpy().view(np.uint32), ry.view(np.uint32)) and np.array_equal(arg.cpu().numpy(), rarg)
+    gx = ctx.picasso_pool_backward(pk.PICASSO_POOL_MAX, off_by_one(g), dcid, off, mem, argmax=arg).cpu().numpy()
+    assert np.array_equal(gx.view(np.uint32), oracle.pool_backward(oracle.POOL_MAX, g, cid, n_in, argmax=rarg).view(np.uint32))
+    up = ctx.picasso_unpool_forward(off_by_one(g), dcid).cpu().numpy()
+    assert np.array_equal(up.view(np.uint32), oracle.unpool_forward(g, cid).view(np.uint32))
+    ya = ctx.picasso_pool_forward(pk.PICASSO_POOL_AVG, off_by_one(x), off, mem).cpu().numpy()
+    sizes = np.bincount(cid, minlength=n_out).astype(np.float64)
+    ref = oracle.pool_forward(oracle.POOL_AVG, x, cid, n_out)
+    assert np.all(np.abs(ya.astype(np.float64) - ref) <= _sum_bound(np.abs(x), cid, n_out, sizes) + U * np.abs(ref))
+
+
 def test_bad_cluster_ids_are_rejected(pk, ctx):
     cid = np.array([0, 1, 5, 2], np.int32)
     with pytest.raises(pk.PicassoError) as e:
