@@ -706,3 +706,19 @@ def test_two_contexts_on_two_host_threads(pk, oracle):
     finally:
         for j in jobs:
             j["ctx"].close()
+
+
+def test_ten_million_vertices(pk, oracle):
+    """10.2 M vertices, 20.5 M facets, 61 M half-edges (a 6 GiB workspace): every index that is
+    multiplied by a record size goes beyond 2^31 bytes, the sorts run as plain radix passes over
+    tens of thousands of tiles.  About 15 s of oracle time."""
+    V, F = meshgen.noisy_grid(3200, 3200, seed=5, noise=0.004)
+    target = V.shape[0] // 4
+    print(f"large mesh: N={V.shape[0]} F={F.shape[0]} -> {target}", flush=True)
+    c = pk.Context(V.shape[0], F.shape[0], 1, device=0)
+    try:
+        st, vo, fo, cid = c.picasso_decimate(dev(V), dev(F), target)
+        print("decimated; oracle running", flush=True)
+        assert_same_result(st, vo, fo, cid, oracle.decimate(V, F, target))
+    finally:
+        c.close()
