@@ -11,6 +11,8 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "primitives.h"
 
 #pragma clang fp contract(off)
@@ -1040,13 +1042,17 @@ __global__ __launch_bounds__(BLOCK) void trunc_rekey_kernel(const u32* __restric
 // contiguous run in edge order; one workgroup per mesh reads the run's cost keys once, into
 // registers (item r * TRUNC_THREADS + t sits in register r of thread t), finds the cost key of the
 // nrem-th smallest (cost key, edge) by a bitwise search on "how many keys are <= x" (a compare
-// and an add per key and bit), and flags every pair above that key and, among the pairs with
-// exactly that key, all but the first ones in edge order.  A wide kernel then releases the
+// and an add per key and bit; the keys that share the bits decided so far are dealt out again
+// once they are few, and in the end one wave decides the remaining bits without barriers), and
+// flags every pair
+// above that key and, among the pairs with exactly that key, all but the first ones in edge order.  A wide kernel then releases the
 // flagged pairs.  One compute unit does the whole search, so runs longer than TRUNC_BLOCK_CAP go
 // to the sort instead.
 constexpr int TRUNC_THREADS = 1024;
 constexpr int TRUNC_REGS_MAX = 32;
 constexpr int TRUNC_BLOCK_CAP = TRUNC_THREADS * TRUNC_REGS_MAX;
+constexpr int TRUNC_NARROW_BLOCK = 4 * TRUNC_THREADS;  // candidates that are dealt out again, 4 to a thread
+constexpr int TRUNC_NARROW_WAVE = 4 * 64;              // candidates that one wave takes over, 4 to a lane
 
 // Sum over the 64 lanes of a wave (all active), the same value returned to every lane.
 __device__ __forceinline__ u32 wave_sum_u32(u32 x) {
@@ -1068,6 +1074,8 @@ __global__ __launch_bounds__(TRUNC_THREADS) void trunc_block_kernel(u32* __restr
     __shared__ u32 wsum[NW];
     __shared__ u32 wsum2[2][NW];
     __shared__ u32 cnt[R * NW];
+    __shared__ u32 cbuf[TRUNC_NARROW_BLOCK];
+    __shared__ u32 found[2];
     const int b = blockIdx.x;
     const int n = matched[b], keep = nrem[b];
     if (n <= keep) return;
@@ -1092,33 +1100,162 @@ __global__ __launch_bounds__(TRUNC_THREADS) void trunc_block_kernel(u32* __restr
         key[r] = i < n ? tcost[i] : 0xFFFFFFFFu;
     }
 
-    // Number of the run's keys <= x, known to every thread after one barrier (`slot` alternates so
-    // that the next count does not overwrite sums that are still being read).
-    auto count_le = [&](u32 x, int slot) -> u32 {
+    // Number of values <= x among the RR that every thread holds, known to every thread after one
+    // barrier (`slot` alternates so that the next count does not overwrite sums still being read).
+    auto count_le = [&](const auto& a, auto rr, u32 x, int slot) -> u32 {
+        constexpr int RR = decltype(rr)::value;
         u32 c = 0;
 #pragma unroll
-        for (int r = 0; r < R; ++r) c += (key[r] <= x) ? 1u : 0u;
+        for (int r = 0; r < RR; ++r) c += (a[r] <= x) ? 1u : 0u;
         c = wave_sum_u32(c);
         if (lane == 0) wsum2[slot][w] = c;
         __syncthreads();
         u32 tot = 0;
 #pragma unroll
         for (int j = 0; j < NW; ++j) tot += wsum2[slot][j];
-        return tot < (u32)n ? tot : (u32)n;  // (empty slots count when x is the largest key)
+        return tot;
+    };
+    // One wave alone finishes a search over at most TRUNC_NARROW_WAVE values held in `cbuf` (the
+    // first `m` entries): the smallest x whose low bits (`bit` and below) extend `pre` such that at
+    // least `want` values are <= x, `outside` values that are not in `cbuf` being below every
+    // candidate.  Returns x and how many values are < x; no barriers, 4 compares per lane and bit.
+    auto wave_search = [&](u32 m, u32 pre, int bit, u32 outside, u32 want, u32& less_out) -> u32 {
+        u32 less = outside;  // values < pre: those outside `cbuf`, then the candidates passed over
+        u32 ck[TRUNC_NARROW_WAVE / 64];
+#pragma unroll
+        for (int j = 0; j < TRUNC_NARROW_WAVE / 64; ++j) ck[j] = (u32)(j * 64 + lane) < m ? cbuf[j * 64 + lane] : 0xFFFFFFFFu;
+        for (; bit >= 0; --bit) {
+            const u32 x = pre | ((1u << bit) - 1u);
+            u32 c = 0;
+#pragma unroll
+            for (int j = 0; j < TRUNC_NARROW_WAVE / 64; ++j) c += (u32)__popcll(__ballot(ck[j] <= x));
+            c = outside + (c < m ? c : m);  // (the empty places count when x is the largest value)
+            if (c < want) {
+                pre |= 1u << bit;
+                less = c;
+            }
+        }
+        less_out = less;
+        return pre;
+    };
+    // Those of the RR values a thread holds that satisfy `is_cand` go to consecutive places of
+    // `cbuf`; returns how many there are in the workgroup (the caller knows that they fit).
+    auto gather_candidates = [&](auto rr, auto is_cand, auto value_of) -> u32 {
+        constexpr int RR = decltype(rr)::value;
+        u32 mc = 0;
+#pragma unroll
+        for (int r = 0; r < RR; ++r) mc += is_cand(r) ? 1u : 0u;
+        u32 m;
+        u32 at = prim::wide_block_exclusive_scan<NW>(mc, wsum, m);
+#pragma unroll
+        for (int r = 0; r < RR; ++r)
+            if (is_cand(r) && at < (u32)TRUNC_NARROW_BLOCK) cbuf[at++] = value_of(r);
+        __syncthreads();
+        return m;
     };
 
-    // prefix = smallest key x with at least `keep` keys <= x, found bit by bit from the top
+    // prefix = smallest key x with at least `keep` keys <= x, found bit by bit from the top.
+    // below = keys < prefix, upper = keys <= prefix | (undecided bits all set): upper - below keys
+    // share the bits decided so far.  Once there are at most TRUNC_NARROW_BLOCK of them they are
+    // dealt out again, 4 to a thread; once at most TRUNC_NARROW_WAVE, one wave takes them and
+    // finishes alone.
     u32 prefix = 0, kk = 0;
     if (keep > 0) {
-        for (int bit = 31; bit >= 0; --bit)
-            if (count_le(prefix | ((1u << bit) - 1u), bit & 1) < (u32)keep) prefix |= 1u << bit;
-        __syncthreads();
-        kk = (u32)keep - (prefix ? count_le(prefix - 1u, 0) : 0u);
+        u32 below = 0, upper = (u32)n;
+        int bit = 31;
+        // steps over the values in `a` (of which `valid` are real, `outside` more lie below them all)
+        auto steps = [&](const auto& a, auto rr, u32 valid, u32 outside, u32 until) {
+            while (bit >= 0 && upper - below > until) {
+                u32 c = count_le(a, rr, prefix | ((1u << bit) - 1u), bit & 1);
+                c = outside + (c < valid ? c : valid);  // (empty slots count when x is the largest key)
+                if (c < (u32)keep) {
+                    prefix |= 1u << bit;
+                    below = c;
+                } else {
+                    upper = c;
+                }
+                --bit;
+            }
+        };
+        auto finish_in_one_wave = [&](auto rr, auto is_cand, auto value_of) {
+            const u32 outside = below;
+            const u32 m = gather_candidates(rr, is_cand, value_of);
+            if (w == 0) {
+                u32 less;
+                const u32 x = wave_search(m, prefix, bit, outside, (u32)keep, less);
+                if (lane == 0) {
+                    found[0] = x;
+                    found[1] = less;
+                }
+            }
+            __syncthreads();
+            prefix = found[0];
+            below = found[1];
+        };
+        const auto all_r = std::integral_constant<int, R>{};
+        const auto four = std::integral_constant<int, 4>{};
+        auto decided_mask = [&]() -> u32 { return bit == 31 ? 0u : ~0u << (bit + 1); };
+        steps(key, all_r, (u32)n, 0u, R > 4 ? (u32)TRUNC_NARROW_BLOCK : (u32)TRUNC_NARROW_WAVE);
+        if (R > 4 && bit >= 0 && upper - below > (u32)TRUNC_NARROW_WAVE) {
+            const u32 decided = decided_mask(), outside = below;
+            const u32 m = gather_candidates(
+                all_r, [&](int r) { return r * TRUNC_THREADS + tid < n && (key[r] & decided) == prefix; },
+                [&](int r) { return key[r]; });
+            u32 k4[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) k4[j] = (u32)(j * TRUNC_THREADS + tid) < m ? cbuf[j * TRUNC_THREADS + tid] : 0xFFFFFFFFu;
+            steps(k4, four, m, outside, (u32)TRUNC_NARROW_WAVE);
+            if (bit >= 0) {
+                const u32 d2 = decided_mask();
+                finish_in_one_wave(
+                    four, [&](int j) { return (u32)(j * TRUNC_THREADS + tid) < m && (k4[j] & d2) == prefix; },
+                    [&](int j) { return k4[j]; });
+            }
+        } else if (bit >= 0) {
+            const u32 decided = decided_mask();
+            finish_in_one_wave(
+                all_r, [&](int r) { return r * TRUNC_THREADS + tid < n && (key[r] & decided) == prefix; },
+                [&](int r) { return key[r]; });
+        }
+        kk = (u32)keep - below;
     }
     // kk = how many pairs with exactly the key `prefix` stay (the first kk in edge order)
     if constexpr (SHUFFLE) {
         // ... the first kk in the order of the seeded tie-break, which is distinct from pair to pair:
         // the same search once more, on the tie-break values of the pairs with that key
+        u32 neq = 0;
+#pragma unroll
+        for (int r = 0; r < R; ++r) neq += (r * TRUNC_THREADS + tid < n && key[r] == prefix) ? 1u : 0u;
+        {
+            u32 tot;
+            (void)prim::wide_block_exclusive_scan<NW>(neq, wsum, tot);
+            neq = tot;
+        }
+        if (neq <= (u32)TRUNC_NARROW_WAVE) {  // the usual case: few pairs share the threshold's cost key
+            u32 t2 = 0;
+            if (kk > 0) {
+                const u32 m = gather_candidates(
+                    std::integral_constant<int, R>{},
+                    [&](int r) { return r * TRUNC_THREADS + tid < n && key[r] == prefix; },
+                    [&](int r) { return tb.enc(tval[r * TRUNC_THREADS + tid]); });
+                if (w == 0) {
+                    u32 less;
+                    const u32 x = wave_search(m, 0u, 31, 0u, kk, less);
+                    if (lane == 0) found[0] = x;
+                }
+                __syncthreads();
+                t2 = found[0];
+            }
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int i = r * TRUNC_THREADS + tid;
+                if (i < n) {
+                    const bool out = key[r] > prefix || (key[r] == prefix && (kk == 0 || tb.enc(tval[i]) > t2));
+                    tcost[i] = out ? 1u : 0u;
+                }
+            }
+            return;
+        }
         u32 tie[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) {

@@ -148,3 +148,20 @@ def test_batch_with_shuffle_meets_every_budget_and_is_reproducible(pk, ctx):
                 assert np.array_equal(runs[key][0], cid) and np.array_equal(runs[key][1], vo.cpu().numpy())
             runs[key] = (cid, vo.cpu().numpy())
     assert not np.array_equal(runs[(11, 0)][0], runs[(12, 0)][0])
+
+
+@pytest.mark.parametrize("seed", [0, 77])
+@pytest.mark.parametrize("absorb", [0, 1])
+def test_budget_ends_inside_thousands_of_equal_costs(pk, ctx, oracle, seed, absorb):
+    """A flat lattice (every cost is exactly zero) beside a jittered one: the budget step has to pick
+    1,500 and then 5,000 of many thousands of pairs with one and the same cost key, more than the
+    search hands to a single wave, by edge order (seed 0) or by the seeded tie-break."""
+    Va, Fa = meshgen.flat_grid(150, 120, spacing=0.1)
+    Vb, Fb = meshgen.noisy_grid(60, 50, seed=3, noise=0.02)
+    V = np.concatenate([Va, Vb + np.float32(40.0)])
+    F = np.concatenate([Fa, Fb + Va.shape[0]]).astype(np.int32)
+    for drop in (1500, 5000, 9000):
+        target = V.shape[0] - drop
+        print(f"equal costs: N={V.shape[0]} target={target} seed={seed} absorb={absorb}", flush=True)
+        st, vo, fo, cid = _run(pk, ctx, seed, lambda: ctx.picasso_decimate(dev(V), dev(F), target), absorb)
+        _same(st, vo, fo, cid, oracle.decimate(V, F, target, shuffle_seed=seed, absorb=bool(absorb)))
