@@ -14,7 +14,9 @@
  *   - return 0 = OK, >0 = warning, <0 = error (see picasso_status).
  *     On error no output buffer has been written.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  The
- *     decimate calls synchronise that stream before they return.
+ *     decimate calls return when everything they queued on that stream has been
+ *     done: all outputs are complete (they wait for their last kernel, see
+ *     PICASSO_OPT_HOST_POLL).
  *   - A context owns its scratch workspace, a small pinned host buffer that its
  *     kernels write counters into, and one internal stream of default priority;
  *     it is bound to one device, which the calls make current; calls on one
@@ -85,7 +87,7 @@ enum picasso_option {
                                       mean position are summed over its members in ascending
                                       index order; it is represented by its pair's smaller
                                       index.  0 (default): pairs only.                           */
-    PICASSO_OPT_SHUFFLE_SEED = 9   /* the shuffle inserted into the sorting of the pairs (Sec. 3,
+    PICASSO_OPT_SHUFFLE_SEED = 9,  /* the shuffle inserted into the sorting of the pairs (Sec. 3,
                                       footnote; Sec. 5, augmentation): with a seed != 0, pairs of
                                       equal cost are taken in the order of a seeded bijection of
                                       their 32-bit index (xor with the seed's low word, times
@@ -93,6 +95,12 @@ enum picasso_option {
                                       plus the seed's high word) instead of index order; pairs
                                       of different cost keep their order.  All 64 bits of the
                                       value are the seed; 0 (default): index order.              */
+    PICASSO_OPT_HOST_POLL = 10     /* 1 (default): where a decimate call has to wait for the device
+                                      (once per round, and at its end) the host watches a sequence
+                                      number that the last kernel stores in the context's pinned
+                                      host memory after its results (it gives up after 20 ms and
+                                      synchronises the stream); 0: it synchronises the stream.
+                                      The results are the same either way.                       */
 };
 
 #define PICASSO_STATS_ROUNDS 32

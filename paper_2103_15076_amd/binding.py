@@ -30,6 +30,7 @@ PICASSO_OPT_PLACEMENT = 6
 PICASSO_OPT_RCOND_MIN_BITS = 7
 PICASSO_OPT_ABSORB = 8
 PICASSO_OPT_SHUFFLE_SEED = 9
+PICASSO_OPT_HOST_POLL = 10
 PICASSO_PLACE_MEAN, PICASSO_PLACE_INVERSE = 0, 1
 
 PICASSO_STATS_ROUNDS = 32

@@ -600,6 +600,22 @@ constexpr int SEL_TILE = BLOCK * SEL_ITEMS;
 constexpr int TAIL_THREADS = 1024;
 constexpr int TAIL_MAX = 3584;  // live edges the single-workgroup tail takes over (sized by its LDS state)
 
+// A word in the context's pinned host memory and the number to store there: the last kernel
+// before a look of the host stores it once its results are written, so that the host may watch
+// that word instead of waiting for the stream.
+struct HostSignal {
+    int* word;
+    int seq;
+};
+
+// By every thread of the (single) workgroup, as its last act: the workgroup's stores, to host
+// memory as well, are complete before one thread stores the sequence number.
+__device__ __forceinline__ void signal_host(const HostSignal& h, int tid) {
+    __threadfence_system();
+    __syncthreads();
+    if (tid == 0) __hip_atomic_store(h.word, h.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
 struct SelArgs {
     const u64* ekey;
     const u32* ecost;
@@ -613,6 +629,7 @@ struct SelArgs {
     int* host_img;     // pinned host memory, device view: the tail leaves [State][matched] there
     int publish_ints;  // for the host, which then needs no copy of its own before it looks
     TieBreak tb;       // order among edges of equal cost
+    HostSignal done;   // stored by the tail once everything above is written
 };
 
 // Bids are read with device-scope atomic loads where the same kernel also
@@ -843,6 +860,7 @@ __global__ __launch_bounds__(TAIL_THREADS) void select_tail_kernel(SelArgs A) {
     const int tid = threadIdx.x, lane = prim::lane_id();
     if (n > TAIL_MAX) {        // too many: the host runs more grid-wide sub-rounds
         tail_publish(A, tid);
+        signal_host(A.done, tid);
         return;
     }
     const u64 lt = prim::lanemask_lt();
@@ -968,6 +986,7 @@ __global__ __launch_bounds__(TAIL_THREADS) void select_tail_kernel(SelArgs A) {
         __syncthreads();
         tail_publish(A, tid);
     }
+    signal_host(A.done, tid);
 }
 
 // ---------------------------------------------------------------------------
@@ -1455,11 +1474,11 @@ struct JoinOverPred {
 };
 
 // The joining edges are listed in edge order, hence by mesh: acand[b] = how many belong to mesh b.
-// Also written to host memory (`host_out`), which the host reads after waiting for the stream.
+// Also written to host memory (`host_out`), which the host reads once `done` tells it to.
 __global__ __launch_bounds__(BLOCK) void absorb_count_kernel(const int* __restrict__ list, const State* st,
                                                              const u64* __restrict__ ekey, int vbits, int B,
                                                              const int* __restrict__ voff, int* __restrict__ acand,
-                                                             int* __restrict__ host_out) {
+                                                             int* __restrict__ host_out, HostSignal done) {
     const int n = st->absorb_n;
     for (int b = threadIdx.x; b < B; b += BLOCK) {
         int pos[2];
@@ -1479,6 +1498,7 @@ __global__ __launch_bounds__(BLOCK) void absorb_count_kernel(const int* __restri
         acand[b] = pos[1] - pos[0];
         host_out[b] = pos[1] - pos[0];
     }
+    signal_host(done, threadIdx.x);
 }
 
 // For every listed edge that still stands: the joining vertex records its cluster's representative
@@ -1743,6 +1763,14 @@ struct FacetOut {
 // ---------------------------------------------------------------------------
 // Results
 // ---------------------------------------------------------------------------
+// The call's last kernel, one workgroup: the header's first n ints ([State][matched][foff_out])
+// copied to the host's read-back area, then the host is told.
+__global__ __launch_bounds__(BLOCK) void publish_header_kernel(const int* __restrict__ hdr, int n,
+                                                               int* __restrict__ host_img, HostSignal done) {
+    for (int i = threadIdx.x; i < n; i += BLOCK) host_img[i] = hdr[i];
+    signal_host(done, threadIdx.x);
+}
+
 __global__ __launch_bounds__(BLOCK) void copy_out_kernel(const VRec* __restrict__ vrec, const int* __restrict__ fcur,
                                                          const int* __restrict__ cid, const State* st, int cur,
                                                          int n_orig, float* __restrict__ verts_out,

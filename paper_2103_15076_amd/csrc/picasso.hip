@@ -11,6 +11,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <chrono>
 #include <new>
 #include <vector>
 
@@ -100,6 +101,9 @@ struct picasso_ctx {
     int* h_pin_dev = nullptr;  // the same memory as the device addresses it
     size_t h_up_off = 0;
     size_t h_pin_ints = 0;
+    size_t h_seq_off = 0;  // the word that kernels store a sequence number in for the host (a cache line of its own)
+    int host_seq = 0;      // the last sequence number handed out
+    int opt_poll = 1;      // the host watches that word instead of waiting for the stream
     hipEvent_t ev[2 * PICASSO_STATS_ROUNDS * PICASSO_ST_COUNT + 4];
     int n_ev = 0;
     hipEvent_t ev_total[2];
@@ -404,6 +408,30 @@ int upload_header(picasso_ctx* c, hipStream_t s, int B, const int32_t* nv_in, co
     return PICASSO_OK;
 }
 
+// The signal for the next kernel after which the host looks at the read-back area.
+HostSignal next_signal(picasso_ctx* c) { return HostSignal{c->h_pin_dev + c->h_seq_off, ++c->host_seq}; }
+
+// Waits until the kernel that was given `sig` has written its results to the pinned read-back
+// area.  That kernel stores the sequence number after them (system-scope release), so the host
+// watches the word: it sees it some microseconds before a stream synchronisation would return,
+// and everything queued on the stream before that kernel is complete by then as well.  Falls back
+// to the stream synchronisation when the word has not changed after a while (or when switched
+// off), which also brings any launch error to light.
+hipError_t wait_for_signal(picasso_ctx* c, hipStream_t s, const HostSignal& sig) {
+    if (c->opt_poll) {
+        const int* word = c->h_pin + c->h_seq_off;
+        const auto t0 = std::chrono::steady_clock::now();
+        for (long spins = 1;; ++spins) {
+            if (__atomic_load_n(word, __ATOMIC_ACQUIRE) == sig.seq) return hipSuccess;
+            if ((spins & 1023) == 0 && std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(20)) break;
+#if defined(__x86_64__)
+            __builtin_ia32_pause();
+#endif
+        }
+    }
+    return hipStreamSynchronize(s);
+}
+
 // One copy of [State][matched][foff_out] to the pinned read-back area, then waits for the stream.
 int read_header(picasso_ctx* c, hipStream_t s) {
     const int n = HDR_STATE_INTS + 2 * c->cap_b + 1;
@@ -484,8 +512,10 @@ int run_absorb(picasso_ctx* c, hipStream_t s, int B, int cur, int vbits, int ne,
     JoinListOut jl{c->list};
     prim::compact(s, jp, jp, jl, &c->st->ne, ne, c->tilesum, &c->st->absorb_n);
     int* host_counts = c->h_pin_dev + HDR_STATE_INTS + c->cap_b;  // (the offsets' slots of the read-back area: free until the end)
-    absorb_count_kernel<<<1, BLOCK, 0, s>>>(c->list, c->st, c->ekey, vbits, B, c->voff[cur], c->acand, host_counts);
-    HIP_TRY(c, hipStreamSynchronize(s));
+    const HostSignal counted = next_signal(c);
+    absorb_count_kernel<<<1, BLOCK, 0, s>>>(c->list, c->st, c->ekey, vbits, B, c->voff[cur], c->acand, host_counts,
+                                            counted);
+    HIP_TRY(c, wait_for_signal(c, s, counted));
     const int* h_cand = c->h_pin + HDR_STATE_INTS + c->cap_b;
     long long n_list = 0, n_over = 0;
     int seg_max = 0;
@@ -668,9 +698,10 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
             LivePred lp{c->estate};
             LiveOut lo{c->list};
             prim::compact(s, lp, lp, lo, &c->st->ne, ne_bound, c->tilesum, &c->st->live[0]);
+            sa.done = next_signal(c);
             select_tail_kernel<<<1, TAIL_THREADS, 0, s>>>(sa);
             launched += wide + 3;
-            HIP_TRY(c, hipStreamSynchronize(s));  // the tail has left [State][matched] in the read-back area
+            HIP_TRY(c, wait_for_signal(c, s, sa.done));  // the tail has left [State][matched] in the read-back area
             if (!validated) {
                 const int st_err = status_from_err_bits(hst->err);
                 if (st_err != PICASSO_OK) return st_err;
@@ -791,8 +822,13 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         c->vrec[cur], c->fbuf[cur], c->cid, c->st, cur, N, d_verts_out, d_facets_out, d_cluster_id, B, c->voff[cur],
         c->foff_out);
     if (stats) HIP_TRY(c, hipEventRecord(c->ev_total[1], s));
-    rc = read_header(c, s);
-    if (rc != PICASSO_OK) return rc;
+    {
+        const HostSignal finished = next_signal(c);
+        publish_header_kernel<<<1, BLOCK, 0, s>>>(c->hdr, HDR_STATE_INTS + 2 * c->cap_b + 1, c->h_pin_dev, finished);
+        HIP_TRY(c, wait_for_signal(c, s, finished));
+        // the events of the measurement options are read below: those need the stream itself to be idle
+        if (stats || c->kt.nrec > 0) HIP_TRY(c, hipStreamSynchronize(s));
+    }
     HIP_TRY(c, hipGetLastError());
     const int* h_foff = c->h_pin + HDR_STATE_INTS + c->cap_b;
 
@@ -892,7 +928,8 @@ int picasso_create(picasso_ctx** out, int device, int64_t max_verts, int64_t max
     carve(c, c->ws, max_verts, max_facets, max_meshes);
     c->cap_b = max_meshes;
     c->h_up_off = (size_t)HDR_STATE_INTS + 2 * (size_t)max_meshes + 16;
-    c->h_pin_ints = c->h_up_off + HDR_STATE_INTS + 8 * (size_t)max_meshes + 16;
+    c->h_seq_off = (c->h_up_off + HDR_STATE_INTS + 8 * (size_t)max_meshes + 16 + 31) / 32 * 32;
+    c->h_pin_ints = c->h_seq_off + 32;
     if (hipHostMalloc((void**)&c->h_pin, c->h_pin_ints * sizeof(int), hipHostMallocDefault) != hipSuccess) {
         (void)hipFree(c->ws);
         delete c;
@@ -958,6 +995,10 @@ int picasso_set_option(picasso_ctx* c, int option, int64_t value) {
             return PICASSO_OK;
         case PICASSO_OPT_SHUFFLE_SEED:
             c->opt_shuffle_seed = (uint64_t)value;
+            return PICASSO_OK;
+        case PICASSO_OPT_HOST_POLL:
+            if (value != 0 && value != 1) return PICASSO_ERR_INVALID_ARG;
+            c->opt_poll = (int)value;
             return PICASSO_OK;
         case PICASSO_OPT_ABSORB:
             if (value != 0 && value != 1) return PICASSO_ERR_INVALID_ARG;

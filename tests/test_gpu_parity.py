@@ -722,3 +722,23 @@ def test_ten_million_vertices(pk, oracle):
         assert_same_result(st, vo, fo, cid, oracle.decimate(V, F, target))
     finally:
         c.close()
+
+
+def test_host_wait_by_stream_synchronisation_or_by_watching_pinned_memory(pk, ctx, oracle):
+    """PICASSO_OPT_HOST_POLL only changes how the host learns that a round's selection is done."""
+    V, F = meshgen.icosphere(5, seed=11, jitter=0.05)
+    target = V.shape[0] // 7
+    ref = oracle.decimate(V, F, target)
+    b = meshgen.config("grid64")
+    for poll in (0, 1, 0, 1):
+        ctx.set_option(pk.PICASSO_OPT_HOST_POLL, poll)
+        try:
+            for _ in range(5):
+                st, vo, fo, cid = ctx.picasso_decimate(dev(V), dev(F), target)
+                assert_same_result(st, vo, fo, cid, ref)
+            st, vo, fo, cid = ctx.picasso_decimate(dev(b["verts"]), dev(b["facets"]), int(b["target"][0]))
+            assert_same_result(st, vo, fo, cid, oracle.decimate(b["verts"], b["facets"], int(b["target"][0])))
+        finally:
+            ctx.set_option(pk.PICASSO_OPT_HOST_POLL, 1)
+    with pytest.raises(pk.PicassoError):
+        ctx.set_option(pk.PICASSO_OPT_HOST_POLL, 2)
