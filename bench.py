@@ -53,6 +53,9 @@ def main():
     ap.add_argument("--absorb", action="store_true",
                     help="apply Alg. 2 line 11 (un-paired vertices join a neighbouring pair's cluster, under the "
                          "budget); the headline path contracts pairs only")
+    ap.add_argument("--stream-sync", action="store_true",
+                    help="the host waits by synchronising the stream (PICASSO_OPT_HOST_POLL = 0) instead of "
+                         "watching the word its last kernel writes to pinned memory")
     ap.add_argument("--single-stream", action="store_true",
                     help="keep the first round's edge sort on the caller's stream (PICASSO_OPT_OVERLAP = 0)")
     args = ap.parse_args()
@@ -112,6 +115,8 @@ def main():
         ctx.set_option(pk.PICASSO_OPT_ABSORB, 1)
     if args.shuffle_seed:
         ctx.set_option(pk.PICASSO_OPT_SHUFFLE_SEED, args.shuffle_seed)
+    if args.stream_sync:
+        ctx.set_option(pk.PICASSO_OPT_HOST_POLL, 0)
 
     def step(stats=None):
         if B == 1:
@@ -289,7 +294,8 @@ def main():
                    "target_nv": int(np.sum(target)), "verts_out": nv_out, "facets_out": nf_out,
                    "rounds": sd["rounds"], "subrounds": sd["subrounds"], "edges": sd["ne"],
                    "placement": args.placement + (f" (rcond_min {args.rcond_min:g})" if inverse else ""),
-                   "line_11": bool(args.absorb), "shuffle_seed": args.shuffle_seed},
+                   "line_11": bool(args.absorb), "shuffle_seed": args.shuffle_seed,
+                   "host_wait": "stream synchronisation" if args.stream_sync else "pinned-memory sequence number"},
         "paper_context": {"ms": 65.0, "gpu": "RTX 2080 Ti (paper's machine, its own 115,114-vertex mesh)"},
         "event_ms_per_step": round(ev_ms / args.steps, 4),
         "stage_ms": {k: round(sum(r[k] for r in sd["ms_stage"]), 4) for k in pk.binding.STAGE_NAMES},

@@ -826,8 +826,10 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         const HostSignal finished = next_signal(c);
         publish_header_kernel<<<1, BLOCK, 0, s>>>(c->hdr, HDR_STATE_INTS + 2 * c->cap_b + 1, c->h_pin_dev, finished);
         HIP_TRY(c, wait_for_signal(c, s, finished));
-        // the events of the measurement options are read below: those need the stream itself to be idle
-        if (stats || c->kt.nrec > 0) HIP_TRY(c, hipStreamSynchronize(s));
+        // the events of the measurement options are read below; all were recorded before that kernel,
+        // so waiting for the last of them returns at once and leaves every one of them readable
+        if (stats) HIP_TRY(c, hipEventSynchronize(c->ev_total[1]));
+        else if (c->kt.nrec > 0) HIP_TRY(c, hipEventSynchronize(c->kt_pool[c->kt.recs[c->kt.nrec - 1].e1]));
     }
     HIP_TRY(c, hipGetLastError());
     const int* h_foff = c->h_pin + HDR_STATE_INTS + c->cap_b;
