@@ -409,7 +409,11 @@ int upload_header(picasso_ctx* c, hipStream_t s, int B, const int32_t* nv_in, co
 }
 
 // The signal for the next kernel after which the host looks at the read-back area.
-HostSignal next_signal(picasso_ctx* c) { return HostSignal{c->h_pin_dev + c->h_seq_off, ++c->host_seq}; }
+// (The number wraps around after 2^32 signals; only equality with the last one stored matters.)
+HostSignal next_signal(picasso_ctx* c) {
+    c->host_seq = (int)((unsigned)c->host_seq + 1u);
+    return HostSignal{c->h_pin_dev + c->h_seq_off, c->host_seq};
+}
 
 // Waits until the kernel that was given `sig` has written its results to the pinned read-back
 // area.  That kernel stores the sequence number after them (system-scope release), so the host
