@@ -207,7 +207,8 @@ enum picasso_pool_mode {
  * an input vertex index (the cluster's smallest member), d_mapping[v] = output
  * index of v if v is that representative, else -1, so that
  * d_cluster_id[v] == d_mapping[d_replace[v]].  Device pointers of n_in ints
- * each, owned by the caller.  Synchronises the stream; returns
+ * each, owned by the caller.  Waits for its work on the stream (as the decimate
+ * calls do); returns
  * PICASSO_ERR_BAD_INDEX (outputs then unspecified) if an id lies outside
  * [0, n_out).  n_out <= max_verts of the context. */
 int picasso_replace_mapping(picasso_ctx* ctx, void* stream, const int32_t* d_cluster_id, int32_t n_in, int32_t n_out,
@@ -215,7 +216,8 @@ int picasso_replace_mapping(picasso_ctx* ctx, void* stream, const int32_t* d_clu
 
 /* Member lists of the clusters: d_offsets [n_out+1], d_members [n_in] (members of
  * cluster c = d_members[d_offsets[c] .. d_offsets[c+1]), ascending).  Built with a
- * stable radix sort of (cluster_id, vertex).  Synchronises the stream; returns
+ * stable radix sort of (cluster_id, vertex).  Waits for its work on the stream (as
+ * the decimate calls do); returns
  * PICASSO_ERR_BAD_INDEX if an id lies outside [0, n_out).  n_in <= 3*max_facets
  * and n_out <= max_verts of the context. */
 int picasso_cluster_csr(picasso_ctx* ctx, void* stream, const int32_t* d_cluster_id, int32_t n_in, int32_t n_out,
@@ -249,14 +251,14 @@ int picasso_unpool_backward(picasso_ctx* ctx, void* stream, const float* d_gx, i
  * d_quadrics_out [N,10] = a00 a01 a02 a11 a12 a22 b0 b1 b2 c, each the
  * left-to-right fp32 sum over adjacent facets in ascending facet order
  * (vertex->facet lists by a sort of packed (vertex, facet) keys, then an
- * ordered segmented reduction).  Synchronises the stream. */
+ * ordered segmented reduction).  Waits for its work on the stream. */
 int picasso_vertex_quadrics(picasso_ctx* ctx, void* stream, const float* d_verts, int32_t N, const int32_t* d_facets,
                             int32_t F, float* d_quadrics_out);
 
 /* Distinct edges of the input mesh in ascending (lo,hi) order (Alg. 2 line 1)
  * and the cost of each (Alg. 2 line 2) from the vertex quadrics above.
  * d_edges_out (capacity 3F*2 ints), d_cost_out (capacity 3F floats); the number
- * of edges goes to the host scalar h_ne_out.  Synchronises the stream. */
+ * of edges goes to the host scalar h_ne_out.  Waits for its work on the stream. */
 int picasso_edge_costs(picasso_ctx* ctx, void* stream, const float* d_verts, int32_t N, const int32_t* d_facets,
                        int32_t F, int32_t* d_edges_out, float* d_cost_out, int32_t* h_ne_out);
 
@@ -297,7 +299,8 @@ int picasso_bucket_sort(picasso_ctx* ctx, void* stream, int key_bytes, void* d_k
 /* Corners of the facet array at every vertex: corner i = 3 f + s is vertex
  * d_facets[i]; corners of vertex v = d_corners[d_offsets[v] .. d_offsets[v+1]),
  * ascending, so |N(v)| = d_offsets[v+1] - d_offsets[v] (a facet counts once per
- * corner).  d_offsets [N+1], d_corners [3F].  Synchronises the stream; returns
+ * corner).  d_offsets [N+1], d_corners [3F].  Waits for its work on the stream (as
+ * the decimate calls do); returns
  * PICASSO_ERR_BAD_INDEX if an index lies outside [0, N).  F <= max_facets. */
 int picasso_vertex_corner_csr(picasso_ctx* ctx, void* stream, const int32_t* d_facets, int32_t F, int32_t N,
                               int32_t* d_offsets, int32_t* d_corners);
@@ -308,7 +311,7 @@ int picasso_vertex_corner_csr(picasso_ctx* ctx, void* stream, const int32_t* d_f
  * beta, A_min and A_max over the facet's own mesh; the ratio counts as 0 when
  * all areas of a mesh are equal).  Any of the three outputs may be NULL.  B
  * meshes with h_nf[b] facets each (host array; NULL allowed for B = 1).
- * Synchronises the stream; PICASSO_ERR_BAD_INDEX as above. */
+ * Waits for its work on the stream; PICASSO_ERR_BAD_INDEX as above. */
 int picasso_facet_geometry(picasso_ctx* ctx, void* stream, const float* d_verts, int32_t N, const int32_t* d_facets,
                            int32_t F, int32_t B, const int32_t* h_nf, int32_t alpha, int32_t beta, float* d_normals,
                            float* d_areas, int32_t* d_level);

@@ -436,11 +436,12 @@ hipError_t wait_for_signal(picasso_ctx* c, hipStream_t s, const HostSignal& sig)
     return hipStreamSynchronize(s);
 }
 
-// One copy of [State][matched][foff_out] to the pinned read-back area, then waits for the stream.
+// [State][matched][foff_out] brought to the pinned read-back area by a one-workgroup kernel that then
+// tells the host; returns when the host has them (and everything queued before has been executed).
 int read_header(picasso_ctx* c, hipStream_t s) {
-    const int n = HDR_STATE_INTS + 2 * c->cap_b + 1;
-    HIP_TRY(c, hipMemcpyAsync(c->h_pin, c->hdr, sizeof(int) * n, hipMemcpyDeviceToHost, s));
-    HIP_TRY(c, hipStreamSynchronize(s));
+    const HostSignal done = next_signal(c);
+    publish_header_kernel<<<1, BLOCK, 0, s>>>(c->hdr, HDR_STATE_INTS + 2 * c->cap_b + 1, c->h_pin_dev, done);
+    HIP_TRY(c, wait_for_signal(c, s, done));
     return PICASSO_OK;
 }
 
@@ -826,15 +827,12 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         c->vrec[cur], c->fbuf[cur], c->cid, c->st, cur, N, d_verts_out, d_facets_out, d_cluster_id, B, c->voff[cur],
         c->foff_out);
     if (stats) HIP_TRY(c, hipEventRecord(c->ev_total[1], s));
-    {
-        const HostSignal finished = next_signal(c);
-        publish_header_kernel<<<1, BLOCK, 0, s>>>(c->hdr, HDR_STATE_INTS + 2 * c->cap_b + 1, c->h_pin_dev, finished);
-        HIP_TRY(c, wait_for_signal(c, s, finished));
-        // the events of the measurement options are read below; all were recorded before that kernel,
-        // so waiting for the last of them returns at once and leaves every one of them readable
-        if (stats) HIP_TRY(c, hipEventSynchronize(c->ev_total[1]));
-        else if (c->kt.nrec > 0) HIP_TRY(c, hipEventSynchronize(c->kt_pool[c->kt.recs[c->kt.nrec - 1].e1]));
-    }
+    rc = read_header(c, s);
+    if (rc != PICASSO_OK) return rc;
+    // the events of the measurement options are read below; all were recorded before the last kernel,
+    // so waiting for the last of them returns at once and leaves every one of them readable
+    if (stats) HIP_TRY(c, hipEventSynchronize(c->ev_total[1]));
+    else if (c->kt.nrec > 0) HIP_TRY(c, hipEventSynchronize(c->kt_pool[c->kt.recs[c->kt.nrec - 1].e1]));
     HIP_TRY(c, hipGetLastError());
     const int* h_foff = c->h_pin + HDR_STATE_INTS + c->cap_b;
 
