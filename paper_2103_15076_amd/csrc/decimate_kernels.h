@@ -608,10 +608,11 @@ struct HostSignal {
     int seq;
 };
 
-// By every thread of the (single) workgroup, as its last act: the workgroup's stores, to host
-// memory as well, are complete before one thread stores the sequence number.
-__device__ __forceinline__ void signal_host(const HostSignal& h, int tid) {
-    __threadfence_system();
+// By every thread of the (single) workgroup, as its last act: the workgroup's stores to host
+// memory are complete before one thread stores the sequence number.  `wrote`: this thread has
+// stored something the host will read (only those threads need the fence, which is not cheap).
+__device__ __forceinline__ void signal_host(const HostSignal& h, int tid, bool wrote) {
+    if (wrote) __threadfence_system();
     __syncthreads();
     if (tid == 0) __hip_atomic_store(h.word, h.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
 }
@@ -860,7 +861,7 @@ __global__ __launch_bounds__(TAIL_THREADS) void select_tail_kernel(SelArgs A) {
     const int tid = threadIdx.x, lane = prim::lane_id();
     if (n > TAIL_MAX) {        // too many: the host runs more grid-wide sub-rounds
         tail_publish(A, tid);
-        signal_host(A.done, tid);
+        signal_host(A.done, tid, tid < A.publish_ints);
         return;
     }
     const u64 lt = prim::lanemask_lt();
@@ -986,7 +987,7 @@ __global__ __launch_bounds__(TAIL_THREADS) void select_tail_kernel(SelArgs A) {
         __syncthreads();
         tail_publish(A, tid);
     }
-    signal_host(A.done, tid);
+    signal_host(A.done, tid, tid < A.publish_ints || ((tid & (MATCH_SLOTS - 1)) == 0 && lds_pairs));
 }
 
 // ---------------------------------------------------------------------------
@@ -1498,7 +1499,7 @@ __global__ __launch_bounds__(BLOCK) void absorb_count_kernel(const int* __restri
         acand[b] = pos[1] - pos[0];
         host_out[b] = pos[1] - pos[0];
     }
-    signal_host(done, threadIdx.x);
+    signal_host(done, threadIdx.x, (int)threadIdx.x < B);
 }
 
 // For every listed edge that still stands: the joining vertex records its cluster's representative
@@ -1768,7 +1769,7 @@ struct FacetOut {
 __global__ __launch_bounds__(BLOCK) void publish_header_kernel(const int* __restrict__ hdr, int n,
                                                                int* __restrict__ host_img, HostSignal done) {
     for (int i = threadIdx.x; i < n; i += BLOCK) host_img[i] = hdr[i];
-    signal_host(done, threadIdx.x);
+    signal_host(done, threadIdx.x, (int)threadIdx.x < n);
 }
 
 __global__ __launch_bounds__(BLOCK) void copy_out_kernel(const VRec* __restrict__ vrec, const int* __restrict__ fcur,
