@@ -95,12 +95,18 @@ enum picasso_option {
                                       plus the seed's high word) instead of index order; pairs
                                       of different cost keep their order.  All 64 bits of the
                                       value are the seed; 0 (default): index order.              */
-    PICASSO_OPT_HOST_POLL = 10     /* 1 (default): where a decimate call has to wait for the device
+    PICASSO_OPT_HOST_POLL = 10,    /* 1 (default): where a decimate call has to wait for the device
                                       (once per round, and at its end) the host watches a sequence
                                       number that the last kernel stores in the context's pinned
                                       host memory after its results (it gives up after 20 ms and
                                       synchronises the stream); 0: it synchronises the stream.
                                       The results are the same either way.                       */
+    PICASSO_OPT_LAUNCH_AHEAD = 11  /* 1 (default): in a round in which no mesh can form more pairs
+                                      than its budget allows (2 * (vertices - target) >= vertices)
+                                      the contraction and facet kernels are queued behind the
+                                      selection before the host has looked at its outcome; they do
+                                      nothing if the selection turns out to need more passes.
+                                      0: they are queued after the look.  Same results.          */
 };
 
 #define PICASSO_STATS_ROUNDS 32

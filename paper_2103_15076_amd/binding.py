@@ -31,6 +31,7 @@ PICASSO_OPT_RCOND_MIN_BITS = 7
 PICASSO_OPT_ABSORB = 8
 PICASSO_OPT_SHUFFLE_SEED = 9
 PICASSO_OPT_HOST_POLL = 10
+PICASSO_OPT_LAUNCH_AHEAD = 11
 PICASSO_PLACE_MEAN, PICASSO_PLACE_INVERSE = 0, 1
 
 PICASSO_STATS_ROUNDS = 32

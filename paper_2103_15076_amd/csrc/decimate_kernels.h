@@ -38,7 +38,9 @@ struct State {
     int trunc_n;   // matched edges entering the budget truncation
     int sel_k;     // sub-round index the selection has reached (buffer rotation phase)
     int absorb_n;  // edges through which an un-paired vertex would join a pair's cluster (Alg. 2 line 11)
-    int pad[3];
+    // Written by every selection tail for kernels that the host queued behind it before looking
+    // (they run only if the tail finished the matching): 1 / nv / nf of the round then, else zeros.
+    int go, guard_nv, guard_nf;
 };
 
 // One vertex = 64 bytes: position and the 10 quadric coefficients.
@@ -631,6 +633,7 @@ struct SelArgs {
     int publish_ints;  // for the host, which then needs no copy of its own before it looks
     TieBreak tb;       // order among edges of equal cost
     HostSignal done;   // stored by the tail once everything above is written
+    int cur;           // which of the ping-pong vertex / facet counts belong to this round
 };
 
 // Bids are read with device-scope atomic loads where the same kernel also
@@ -851,8 +854,17 @@ __device__ __forceinline__ int tail_slot(int* vkey, int v) {
 // the L2, where this kernel's own stores to them already are).
 __device__ __forceinline__ void tail_publish(const SelArgs& A, int tid) {
     const int* hdr = reinterpret_cast<const int*>(A.st);
+    constexpr int GO0 = (int)(offsetof(State, go) / sizeof(int)), STATE_INTS = (int)(sizeof(State) / sizeof(int));
     for (int i = tid; i < A.publish_ints; i += TAIL_THREADS)
-        A.host_img[i] = __hip_atomic_load(&hdr[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (i < GO0 || i >= STATE_INTS)  // (the guard fields are for the device only; the tail is writing them)
+            A.host_img[i] = __hip_atomic_load(&hdr[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// What the kernels queued behind the tail go by (see State).
+__device__ __forceinline__ void tail_set_guard(const SelArgs& A, bool finished) {
+    A.st->go = finished ? 1 : 0;
+    A.st->guard_nv = finished ? A.st->nv[A.cur] : 0;
+    A.st->guard_nf = finished ? A.st->nf[A.cur] : 0;
 }
 
 __global__ __launch_bounds__(TAIL_THREADS) void select_tail_kernel(SelArgs A) {
@@ -860,6 +872,7 @@ __global__ __launch_bounds__(TAIL_THREADS) void select_tail_kernel(SelArgs A) {
     int n = A.st->live[0];     // live edges, gathered into A.list just before this kernel
     const int tid = threadIdx.x, lane = prim::lane_id();
     if (n > TAIL_MAX) {        // too many: the host runs more grid-wide sub-rounds
+        if (tid == 0) tail_set_guard(A, false);
         tail_publish(A, tid);
         signal_host(A.done, tid, tid < A.publish_ints);
         return;
@@ -976,12 +989,15 @@ __global__ __launch_bounds__(TAIL_THREADS) void select_tail_kernel(SelArgs A) {
             if (lds_pairs && STATE_INTS + b < A.publish_ints) A.host_img[STATE_INTS + b] = sum;
         }
     }
-    if (tid == 0) A.st->live[0] = 0;
+    if (tid == 0) {
+        A.st->live[0] = 0;
+        tail_set_guard(A, true);
+    }
     if (lds_pairs) {
         // the host's copy of the counters: everything but live[0] was written by earlier kernels
-        constexpr int LIVE0 = (int)(offsetof(State, live) / sizeof(int));
+        constexpr int LIVE0 = (int)(offsetof(State, live) / sizeof(int)), GO0 = (int)(offsetof(State, go) / sizeof(int));
         const int* hdr = reinterpret_cast<const int*>(A.st);
-        if (tid < STATE_INTS && tid < A.publish_ints) A.host_img[tid] = (tid == LIVE0) ? 0 : hdr[tid];
+        if (tid < GO0 && tid < A.publish_ints) A.host_img[tid] = (tid == LIVE0) ? 0 : hdr[tid];
     } else {
         __threadfence();
         __syncthreads();
@@ -1563,7 +1579,9 @@ __global__ __launch_bounds__(BLOCK) void contract_kernel(const VRec* __restrict_
                                                          int* __restrict__ htab, int hsize,
                                                          u32* __restrict__ msd_hist, float rcond_min,
                                                          const int* __restrict__ arep, const int* __restrict__ acnt,
-                                                         const u64* __restrict__ akey, int vbits) {
+                                                         const u64* __restrict__ akey, int vbits,
+                                                         const int* __restrict__ guard) {
+    if (guard && *guard == 0) return;  // queued ahead of the host's look, and the selection was not finished
     const int nv = st->nv[cur];
     const int stride = gridDim.x * BLOCK;
     const int g = blockIdx.x * BLOCK + threadIdx.x;
@@ -1692,7 +1710,8 @@ __global__ __launch_bounds__(BLOCK) void facet_insert_kernel(const int* __restri
                                                              int* __restrict__ htab, u32 hmask, MeshTab mt,
                                                              const int* __restrict__ voff_cur,
                                                              int* __restrict__ cid, int n_orig,
-                                                             int* __restrict__ fslot) {
+                                                             int* __restrict__ fslot, const int* __restrict__ guard) {
+    if (guard && *guard == 0) return;  // (as in contract_kernel)
     const int nf = st->nf[cur];
     const int stride = gridDim.x * BLOCK;
     const int g = blockIdx.x * BLOCK + threadIdx.x;

@@ -104,6 +104,7 @@ struct picasso_ctx {
     size_t h_seq_off = 0;  // the word that kernels store a sequence number in for the host (a cache line of its own)
     int host_seq = 0;      // the last sequence number handed out
     int opt_poll = 1;      // the host watches that word instead of waiting for the stream
+    int opt_ahead = 1;     // a round's contraction and facet kernels are queued before the host has looked
     hipEvent_t ev[2 * PICASSO_STATS_ROUNDS * PICASSO_ST_COUNT + 4];
     int n_ev = 0;
     hipEvent_t ev_total[2];
@@ -654,9 +655,60 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
 #undef PICASSO_UNIQUE
         tm.end();
 
+        // The kernels after the selection.  `guarded`: queued behind the selection tail before the host
+        // has looked; they then go by what the tail leaves in State (go, guard_nv, guard_nf) and do
+        // nothing unless it finished the matching.
+        auto issue_contract = [&](int nf_cap, int n_joined, const u64* akeys, bool guarded) {
+            const int nxt = cur ^ 1;
+            const int* guard = guarded ? &c->st->go : nullptr;
+            const int* n_ptr = guarded ? &c->st->guard_nv : nullptr;
+            AliveOut ao{c->newid};
+            if (n_joined > 0) {
+                AlivePredT<true> ap{c->mate, c->arep};
+                prim::compact(s, ap, ap, ao, n_ptr, nv_total, c->tilesum, &c->st->nv[nxt]);
+            } else {
+                AlivePredT<false> ap{c->mate, nullptr};
+                prim::compact(s, ap, ap, ao, n_ptr, nv_total, c->tilesum, &c->st->nv[nxt]);
+            }
+            const size_t hsize = next_pow2((size_t)2 * std::max(nf_cap, 1));
+            const int cgrid = grid_for(std::max<long long>(nv_total, (long long)hsize), 8192);
+#define PICASSO_CONTRACT(PLACE, ABSORB, RCOND)                                                                       \
+    contract_kernel<PLACE, ABSORB><<<cgrid, BLOCK, 0, s>>>(c->vrec[cur], c->vrec[nxt], c->mate, c->newid, c->vmap,    \
+                                                           c->st, cur, B, c->voff[cur], c->voff[nxt], c->htab,        \
+                                                           (int)hsize, c->hist12, RCOND, c->arep, c->acnt, akeys,     \
+                                                           vbits, guard)
+            if (c->opt_placement == PLACE_INVERSE) {
+                if (n_joined > 0) PICASSO_CONTRACT(PLACE_INVERSE, true, c->opt_rcond_min);
+                else PICASSO_CONTRACT(PLACE_INVERSE, false, c->opt_rcond_min);
+            } else {
+                if (n_joined > 0) PICASSO_CONTRACT(PLACE_MEAN, true, 0.0f);
+                else PICASSO_CONTRACT(PLACE_MEAN, false, 0.0f);
+            }
+#undef PICASSO_CONTRACT
+        };
+        auto issue_facets = [&](int nf_cap, bool guarded) {
+            const int nxt = cur ^ 1;
+            const size_t hsize = next_pow2((size_t)2 * std::max(nf_cap, 1));
+            facet_insert_kernel<<<grid_for(std::max(nf_cap, N), 8192), BLOCK, 0, s>>>(
+                c->fbuf[cur], c->fmap, c->vmap, c->st, cur, c->htab, (u32)(hsize - 1), mt, c->voff[cur], c->cid, N,
+                c->fslot, guarded ? &c->st->go : nullptr);
+            FacetKeepPred kp{c->fslot, c->htab, c->keep};
+            FlagPred fp{c->keep};
+            FacetOut fo{c->fmap, c->fbuf[nxt]};
+            prim::compact(s, kp, fp, fo, guarded ? &c->st->guard_nf : &c->st->nf[cur], nf_cap, c->tilesum, &c->st->nf[nxt]);
+        };
+        // Where no mesh can form more pairs than its budget allows (a matching pairs at most half the
+        // vertices) and nothing else has to be decided after the selection, those kernels are queued
+        // right behind the tail: the device does not idle while the host looks.
+        bool ahead_ok = !c->opt_absorb && !stats && c->opt_ahead;
+        for (int b = 0; b < B && ahead_ok; ++b)
+            if (act[b] && 2ll * nrem[b] < nvb[b]) ahead_ok = false;
+        bool ahead = false;  // the kernels are queued and the tail has finished the matching
+
         // ---- S3: selection sub-rounds
         tm.begin(round, PICASSO_ST_SELECT);
         SelArgs sa;
+        sa.cur = cur;
         sa.ekey = c->ekey;
         sa.ecost = c->ecost;
         for (int i = 0; i < 3; ++i) sa.vmin[i] = c->vmin[i];
@@ -706,6 +758,10 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
             sa.done = next_signal(c);
             select_tail_kernel<<<1, TAIL_THREADS, 0, s>>>(sa);
             launched += wide + 3;
+            if (ahead_ok) {
+                issue_contract(nf_bound, 0, nullptr, true);
+                issue_facets(nf_bound, true);
+            }
             HIP_TRY(c, wait_for_signal(c, s, sa.done));  // the tail has left [State][matched] in the read-back area
             if (!validated) {
                 const int st_err = status_from_err_bits(hst->err);
@@ -714,7 +770,10 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
             }
             sel_k = hst->sel_k;
             const int live = hst->live[0];
-            if (live == 0) break;
+            if (live == 0) {
+                ahead = ahead_ok;
+                break;
+            }
             live_est = live;
         }
         for (int b = 0; b < B; ++b) h_matched[b] = c->h_pin[HDR_STATE_INTS + b];
@@ -742,6 +801,7 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
             }
             n_sel += h_matched[b];
         }
+        if (need_trunc && ahead) return PICASSO_ERR_HIP;  // (cannot happen: a matching pairs at most half the vertices)
         if (need_trunc) {
             TruncPred tp{c->ekey, c->mate, mt, vbits};
             rc = budget_step<false>(c, s, tp, B, hst->ne, vbits, mt, tb, n_trunc, seg_max, c->matched, c->nrem);
@@ -772,43 +832,17 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
             break;
         }
 
-        // ---- S4 + S6: contraction and renumbering
-        tm.begin(round, PICASSO_ST_CONTRACT);
+        // ---- S4 + S6: contraction and renumbering; S5: facets (already queued behind the tail, and run,
+        // where `ahead` is set)
         const int nxt = cur ^ 1;
-        AliveOut ao{c->newid};
-        if (n_joined > 0) {
-            AlivePredT<true> ap{c->mate, c->arep};
-            prim::compact(s, ap, ap, ao, nullptr, nv_total, c->tilesum, &c->st->nv[nxt]);
-        } else {
-            AlivePredT<false> ap{c->mate, nullptr};
-            prim::compact(s, ap, ap, ao, nullptr, nv_total, c->tilesum, &c->st->nv[nxt]);
+        if (!ahead) {
+            tm.begin(round, PICASSO_ST_CONTRACT);
+            issue_contract(nf_bound, n_joined, akeys, false);
+            tm.end();
+            tm.begin(round, PICASSO_ST_FACETS);
+            issue_facets(nf_bound, false);
+            tm.end();
         }
-        const size_t hsize = next_pow2((size_t)2 * std::max(nf_bound, 1));
-        const int cgrid = grid_for(std::max<long long>(nv_total, (long long)hsize), 8192);
-#define PICASSO_CONTRACT(PLACE, ABSORB, RCOND)                                                                       \
-    contract_kernel<PLACE, ABSORB><<<cgrid, BLOCK, 0, s>>>(c->vrec[cur], c->vrec[nxt], c->mate, c->newid, c->vmap,    \
-                                                           c->st, cur, B, c->voff[cur], c->voff[nxt], c->htab,        \
-                                                           (int)hsize, c->hist12, RCOND, c->arep, c->acnt, akeys, vbits)
-        if (c->opt_placement == PLACE_INVERSE) {
-            if (n_joined > 0) PICASSO_CONTRACT(PLACE_INVERSE, true, c->opt_rcond_min);
-            else PICASSO_CONTRACT(PLACE_INVERSE, false, c->opt_rcond_min);
-        } else {
-            if (n_joined > 0) PICASSO_CONTRACT(PLACE_MEAN, true, 0.0f);
-            else PICASSO_CONTRACT(PLACE_MEAN, false, 0.0f);
-        }
-#undef PICASSO_CONTRACT
-        tm.end();
-
-        // ---- S5: facets
-        tm.begin(round, PICASSO_ST_FACETS);
-        facet_insert_kernel<<<grid_for(std::max(nf_bound, N), 8192), BLOCK, 0, s>>>(
-            c->fbuf[cur], c->fmap, c->vmap, c->st, cur, c->htab, (u32)(hsize - 1), mt, c->voff[cur], c->cid, N,
-            c->fslot);
-        FacetKeepPred kp{c->fslot, c->htab, c->keep};
-        FlagPred fp{c->keep};
-        FacetOut fo{c->fmap, c->fbuf[nxt]};
-        prim::compact(s, kp, fp, fo, &c->st->nf[cur], nf_bound, c->tilesum, &c->st->nf[nxt]);
-        tm.end();
 
         nv_total -= n_sel + n_joined;
         cur = nxt;
@@ -1003,6 +1037,10 @@ int picasso_set_option(picasso_ctx* c, int option, int64_t value) {
         case PICASSO_OPT_HOST_POLL:
             if (value != 0 && value != 1) return PICASSO_ERR_INVALID_ARG;
             c->opt_poll = (int)value;
+            return PICASSO_OK;
+        case PICASSO_OPT_LAUNCH_AHEAD:
+            if (value != 0 && value != 1) return PICASSO_ERR_INVALID_ARG;
+            c->opt_ahead = (int)value;
             return PICASSO_OK;
         case PICASSO_OPT_ABSORB:
             if (value != 0 && value != 1) return PICASSO_ERR_INVALID_ARG;

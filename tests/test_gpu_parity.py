@@ -742,3 +742,33 @@ def test_host_wait_by_stream_synchronisation_or_by_watching_pinned_memory(pk, ct
             ctx.set_option(pk.PICASSO_OPT_HOST_POLL, 1)
     with pytest.raises(pk.PicassoError):
         ctx.set_option(pk.PICASSO_OPT_HOST_POLL, 2)
+
+
+@pytest.mark.parametrize("batch", [1, 16])
+def test_kernels_queued_ahead_of_the_hosts_look(pk, ctx, oracle, batch):
+    """PICASSO_OPT_LAUNCH_AHEAD: in rounds whose budget cannot bind, the contraction and facet kernels
+    are queued behind the selection before the host knows its outcome.  With one sub-round per
+    batch the selection is not finished at the first look, so the queued kernels must do nothing and
+    be queued again; results equal the oracle's either way, on a single mesh and on a batch."""
+    V, F = meshgen.icosphere(5, seed=13, jitter=0.05)
+    target = V.shape[0] // 9                      # four rounds, the first three far from the budget
+    ref = oracle.decimate(V, F, target)
+    assert ref["rounds"] >= 3
+    c5 = meshgen.config("batch16x60k")
+    nv, nf, tg = c5["nv"][:3], c5["nf"][:3], c5["target"][:3]
+    Vb, Fb = c5["verts"][: nv.sum()], c5["facets"][: nf.sum()]
+    refb = oracle.decimate_batch(Vb, Fb, nv, nf, tg)
+    ctx.set_option(pk.PICASSO_OPT_SUBROUND_BATCH, batch)
+    try:
+        for ahead in (1, 0, 1):
+            ctx.set_option(pk.PICASSO_OPT_LAUNCH_AHEAD, ahead)
+            st, vo, fo, cid = ctx.picasso_decimate(dev(V), dev(F), target)
+            assert_same_result(st, vo, fo, cid, ref)
+            st, vo, fo, cid, nvo, nfo = ctx.picasso_decimate_batch(dev(Vb), dev(Fb), nv, nf, tg)
+            assert st == refb["status"]
+            assert np.array_equal(cid.cpu().numpy(), refb["cluster_id"])
+            assert np.array_equal(fo.cpu().numpy(), refb["facets"])
+            assert np.array_equal(vo.cpu().numpy().view(np.uint32), refb["verts"].view(np.uint32))
+    finally:
+        ctx.set_option(pk.PICASSO_OPT_LAUNCH_AHEAD, 1)
+        ctx.set_option(pk.PICASSO_OPT_SUBROUND_BATCH, 16)
