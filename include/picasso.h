@@ -101,12 +101,14 @@ enum picasso_option {
                                       host memory after its results (it gives up after 20 ms and
                                       synchronises the stream); 0: it synchronises the stream.
                                       The results are the same either way.                       */
-    PICASSO_OPT_LAUNCH_AHEAD = 11  /* 1 (default): in a round in which no mesh can form more pairs
-                                      than its budget allows (2 * (vertices - target) >= vertices)
-                                      the contraction and facet kernels are queued behind the
-                                      selection before the host has looked at its outcome; they do
-                                      nothing if the selection turns out to need more passes.
-                                      0: they are queued after the look.  Same results.          */
+    PICASSO_OPT_LAUNCH_AHEAD = 11  /* 1 (default): for inputs of up to 2^20 facets, in a round in
+                                      which the outcome of the selection decides nothing but
+                                      counts (no mesh can exceed its budget, or some mesh surely
+                                      will and the per-mesh budget step can take it), the kernels
+                                      that follow the selection are queued behind it before the
+                                      host has looked; they do nothing if the selection turns out
+                                      to need more passes.  0: queued after the look.  Same
+                                      results.                                                   */
 };
 
 #define PICASSO_STATS_ROUNDS 32

@@ -39,8 +39,8 @@ struct State {
     int sel_k;     // sub-round index the selection has reached (buffer rotation phase)
     int absorb_n;  // edges through which an un-paired vertex would join a pair's cluster (Alg. 2 line 11)
     // Written by every selection tail for kernels that the host queued behind it before looking
-    // (they run only if the tail finished the matching): 1 / nv / nf of the round then, else zeros.
-    int go, guard_nv, guard_nf;
+    // (they run only if the tail finished the matching): 1 / nv / nf / ne of the round then, else zeros.
+    int go, guard_nv, guard_nf, guard_ne;
 };
 
 // One vertex = 64 bytes: position and the 10 quadric coefficients.
@@ -865,6 +865,7 @@ __device__ __forceinline__ void tail_set_guard(const SelArgs& A, bool finished) 
     A.st->go = finished ? 1 : 0;
     A.st->guard_nv = finished ? A.st->nv[A.cur] : 0;
     A.st->guard_nf = finished ? A.st->nf[A.cur] : 0;
+    A.st->guard_ne = finished ? A.st->ne : 0;
 }
 
 __global__ __launch_bounds__(TAIL_THREADS) void select_tail_kernel(SelArgs A) {
@@ -1105,7 +1106,9 @@ template <int R, bool SHUFFLE>
 __global__ __launch_bounds__(TRUNC_THREADS) void trunc_block_kernel(u32* __restrict__ tcost,
                                                                     const u32* __restrict__ tval, TieBreak tb,
                                                                     const int* __restrict__ matched,
-                                                                    const int* __restrict__ nrem) {
+                                                                    const int* __restrict__ nrem,
+                                                                    const int* __restrict__ guard) {
+    if (guard && *guard == 0) return;  // queued ahead of the host's look, and the selection was not finished
     constexpr int NW = TRUNC_THREADS / 64;
     __shared__ u32 wsum[NW];
     __shared__ u32 wsum2[2][NW];
@@ -1378,7 +1381,9 @@ __global__ __launch_bounds__(BLOCK) void trunc_release_kernel(const u32* __restr
                                                               const u32* __restrict__ tval, const State* st,
                                                               const u64* __restrict__ ekey, int vbits,
                                                               int* __restrict__ mate, int B, int* __restrict__ matched,
-                                                              const int* __restrict__ nrem, u64* __restrict__ abid) {
+                                                              const int* __restrict__ nrem, u64* __restrict__ abid,
+                                                              const int* __restrict__ guard) {
+    if (guard && *guard == 0) return;  // (as in trunc_block_kernel)
     const int i = blockIdx.x * BLOCK + threadIdx.x;
     if (i < st->trunc_n && tflag[i]) release_edge<ABSORB>(ekey[tval[i]], vbits, mate, abid);
     if (blockIdx.x == 0)

@@ -457,17 +457,24 @@ int status_from_err_bits(int bits) {
 // budgets[b] first ones in ascending (cost key, tie-break) order; the others are released
 // (release_edge<ABSORB>) and counts[] is clamped.  n_over = sum of those meshes' counts, seg_max
 // their largest.
+// `guarded` (per-mesh search only, i.e. seg_max <= the context's limit for it): queued behind the
+// selection tail before the host has looked; ne, n_over and seg_max are then upper bounds and the
+// kernels do nothing unless the tail finished the matching.
 template <bool ABSORB, class Over>
 int budget_step(picasso_ctx* c, hipStream_t s, Over over, int B, int ne, int vbits, const MeshTab& mt,
-                const TieBreak& tb, long long n_over, int seg_max, int* counts, int* budgets) {
+                const TieBreak& tb, long long n_over, int seg_max, int* counts, int* budgets, bool guarded = false) {
+    if (guarded && seg_max > c->opt_trunc_block_max) return PICASSO_ERR_INVALID_ARG;
     if (seg_max <= c->opt_trunc_block_max) {
+        const int* guard = guarded ? &c->st->go : nullptr;
         u32* tcost = reinterpret_cast<u32*>(c->key64[0]);
         TruncOutSplit to{c->ecost, tcost, c->val32[0]};
-        prim::compact(s, over, over, to, &c->st->ne, ne, c->tilesum, &c->st->trunc_n);
+        prim::compact(s, over, over, to, guarded ? &c->st->guard_ne : &c->st->ne, ne, c->tilesum, &c->st->trunc_n);
 #define PICASSO_TRUNC_BLOCK(R)                                                                                       \
     do {                                                                                                             \
-        if (tb.on) trunc_block_kernel<R, true><<<B, TRUNC_THREADS, 0, s>>>(tcost, c->val32[0], tb, counts, budgets);  \
-        else trunc_block_kernel<R, false><<<B, TRUNC_THREADS, 0, s>>>(tcost, c->val32[0], tb, counts, budgets);       \
+        if (tb.on)                                                                                                   \
+            trunc_block_kernel<R, true><<<B, TRUNC_THREADS, 0, s>>>(tcost, c->val32[0], tb, counts, budgets, guard);  \
+        else                                                                                                         \
+            trunc_block_kernel<R, false><<<B, TRUNC_THREADS, 0, s>>>(tcost, c->val32[0], tb, counts, budgets, guard); \
     } while (0)
         if (seg_max <= 4 * TRUNC_THREADS) PICASSO_TRUNC_BLOCK(4);
         else if (seg_max <= 8 * TRUNC_THREADS) PICASSO_TRUNC_BLOCK(8);
@@ -475,7 +482,7 @@ int budget_step(picasso_ctx* c, hipStream_t s, Over over, int B, int ne, int vbi
         else PICASSO_TRUNC_BLOCK(32);
 #undef PICASSO_TRUNC_BLOCK
         trunc_release_kernel<ABSORB><<<grid_for(n_over), BLOCK, 0, s>>>(tcost, c->val32[0], c->st, c->ekey, vbits,
-                                                                        c->mate, B, counts, budgets, c->abid);
+                                                                        c->mate, B, counts, budgets, c->abid, guard);
         return PICASSO_OK;
     }
     u64* k0 = c->key64[0];
@@ -700,9 +707,28 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         // Where no mesh can form more pairs than its budget allows (a matching pairs at most half the
         // vertices) and nothing else has to be decided after the selection, those kernels are queued
         // right behind the tail: the device does not idle while the host looks.
-        bool ahead_ok = !c->opt_absorb && !stats && c->opt_ahead;
-        for (int b = 0; b < B && ahead_ok; ++b)
-            if (act[b] && 2ll * nrem[b] < nvb[b]) ahead_ok = false;
+        // Where the budget will bind (a mesh has to stop below 40 % of its vertices; a matching on these
+        // meshes pairs 85-95 % of them) and the per-mesh search can take every such mesh, the budget step
+        // is queued there too, in front of them: it finds on the device which meshes are over their
+        // budgets, and does nothing where none is.  In between (40-50 %) nothing is queued ahead.
+        // Queued ahead, the kernels are sized by the facet bound of the round before (twice the hash
+        // table to clear, twice the tiles), which costs more than the idling from about a million facets.
+        constexpr int AHEAD_MAX_FACETS = 1 << 20;
+        bool ahead_ok = !c->opt_absorb && !stats && c->opt_ahead && nf_bound <= AHEAD_MAX_FACETS;
+        bool ahead_budget = false;
+        long long over_bound = 0;  // pairs of the meshes that may exceed their budgets, at most
+        int seg_bound = 0;         // ... of the largest of them
+        if (ahead_ok) {
+            bool likely = false;
+            for (int b = 0; b < B; ++b)
+                if (act[b] && 2ll * nrem[b] < nvb[b]) {
+                    over_bound += nvb[b] / 2;
+                    seg_bound = std::max(seg_bound, nvb[b] / 2);
+                    likely |= 5ll * nrem[b] < 2ll * nvb[b];
+                }
+            ahead_budget = seg_bound > 0;
+            if (ahead_budget && !(likely && seg_bound <= c->opt_trunc_block_max)) ahead_ok = false;
+        }
         bool ahead = false;  // the kernels are queued and the tail has finished the matching
 
         // ---- S3: selection sub-rounds
@@ -759,6 +785,12 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
             select_tail_kernel<<<1, TAIL_THREADS, 0, s>>>(sa);
             launched += wide + 3;
             if (ahead_ok) {
+                if (ahead_budget) {
+                    TruncPred tp{c->ekey, c->mate, mt, vbits};
+                    rc = budget_step<false>(c, s, tp, B, ne_bound, vbits, mt, tb, over_bound, seg_bound, c->matched,
+                                            c->nrem, true);
+                    if (rc != PICASSO_OK) return rc;
+                }
                 issue_contract(nf_bound, 0, nullptr, true);
                 issue_facets(nf_bound, true);
             }
@@ -801,8 +833,8 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
             }
             n_sel += h_matched[b];
         }
-        if (need_trunc && ahead) return PICASSO_ERR_HIP;  // (cannot happen: a matching pairs at most half the vertices)
-        if (need_trunc) {
+        if (need_trunc && ahead && !ahead_budget) return PICASSO_ERR_HIP;  // (cannot happen: a matching pairs at most half the vertices)
+        if (need_trunc && !ahead) {
             TruncPred tp{c->ekey, c->mate, mt, vbits};
             rc = budget_step<false>(c, s, tp, B, hst->ne, vbits, mt, tb, n_trunc, seg_max, c->matched, c->nrem);
             if (rc != PICASSO_OK) return rc;
