@@ -632,7 +632,6 @@ struct SelArgs {
     int* host_img;     // pinned host memory, device view: the tail leaves [State][matched] there
     int publish_ints;  // for the host, which then needs no copy of its own before it looks
     TieBreak tb;       // order among edges of equal cost
-    HostSignal done;   // stored by the tail once everything above is written
     int cur;           // which of the ping-pong vertex / facet counts belong to this round
 };
 
@@ -875,7 +874,6 @@ __global__ __launch_bounds__(TAIL_THREADS) void select_tail_kernel(SelArgs A) {
     if (n > TAIL_MAX) {        // too many: the host runs more grid-wide sub-rounds
         if (tid == 0) tail_set_guard(A, false);
         tail_publish(A, tid);
-        signal_host(A.done, tid, tid < A.publish_ints);
         return;
     }
     const u64 lt = prim::lanemask_lt();
@@ -1004,7 +1002,25 @@ __global__ __launch_bounds__(TAIL_THREADS) void select_tail_kernel(SelArgs A) {
         __syncthreads();
         tail_publish(A, tid);
     }
-    signal_host(A.done, tid, tid < A.publish_ints || ((tid & (MATCH_SLOTS - 1)) == 0 && lds_pairs));
+}
+
+// The selection tail does not tell the host itself (a system-scope fence inside it, with the pairs it
+// has just written still in the cache, costs more than a launch): the kernel after it on the stream
+// does, as its first act.  Everything the kernels before that one have written, to host memory as
+// well, is complete when it starts.  Either the first of the kernels queued ahead of the host's
+// look (through the counting predicate's on_start) ...
+template <class Pred>
+struct SignalingPred {
+    Pred pred;
+    HostSignal done;
+    __device__ void on_start() const {
+        if (done.word) __hip_atomic_store(done.word, done.seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+    __device__ bool operator()(int i) const { return pred(i); }
+};
+// ... or a kernel of its own.
+__global__ void signal_kernel(HostSignal done) {
+    if (threadIdx.x == 0) __hip_atomic_store(done.word, done.seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
 // ---------------------------------------------------------------------------

@@ -459,16 +459,19 @@ int status_from_err_bits(int bits) {
 // their largest.
 // `guarded` (per-mesh search only, i.e. seg_max <= the context's limit for it): queued behind the
 // selection tail before the host has looked; ne, n_over and seg_max are then upper bounds and the
-// kernels do nothing unless the tail finished the matching.
+// kernels do nothing unless the tail finished the matching; `tell` is stored by the first of them.
 template <bool ABSORB, class Over>
 int budget_step(picasso_ctx* c, hipStream_t s, Over over, int B, int ne, int vbits, const MeshTab& mt,
-                const TieBreak& tb, long long n_over, int seg_max, int* counts, int* budgets, bool guarded = false) {
+                const TieBreak& tb, long long n_over, int seg_max, int* counts, int* budgets, bool guarded = false,
+                HostSignal tell = HostSignal{nullptr, 0}) {
     if (guarded && seg_max > c->opt_trunc_block_max) return PICASSO_ERR_INVALID_ARG;
     if (seg_max <= c->opt_trunc_block_max) {
         const int* guard = guarded ? &c->st->go : nullptr;
         u32* tcost = reinterpret_cast<u32*>(c->key64[0]);
         TruncOutSplit to{c->ecost, tcost, c->val32[0]};
-        prim::compact(s, over, over, to, guarded ? &c->st->guard_ne : &c->st->ne, ne, c->tilesum, &c->st->trunc_n);
+        // (`tell`: the first kernel also tells the host that the selection tail in front of it is done)
+        SignalingPred<Over> first{over, tell};
+        prim::compact(s, first, over, to, guarded ? &c->st->guard_ne : &c->st->ne, ne, c->tilesum, &c->st->trunc_n);
 #define PICASSO_TRUNC_BLOCK(R)                                                                                       \
     do {                                                                                                             \
         if (tb.on)                                                                                                   \
@@ -665,7 +668,7 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         // The kernels after the selection.  `guarded`: queued behind the selection tail before the host
         // has looked; they then go by what the tail leaves in State (go, guard_nv, guard_nf) and do
         // nothing unless it finished the matching.
-        auto issue_contract = [&](int nf_cap, int n_joined, const u64* akeys, bool guarded) {
+        auto issue_contract = [&](int nf_cap, int n_joined, const u64* akeys, bool guarded, HostSignal tell) {
             const int nxt = cur ^ 1;
             const int* guard = guarded ? &c->st->go : nullptr;
             const int* n_ptr = guarded ? &c->st->guard_nv : nullptr;
@@ -675,7 +678,8 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
                 prim::compact(s, ap, ap, ao, n_ptr, nv_total, c->tilesum, &c->st->nv[nxt]);
             } else {
                 AlivePredT<false> ap{c->mate, nullptr};
-                prim::compact(s, ap, ap, ao, n_ptr, nv_total, c->tilesum, &c->st->nv[nxt]);
+                SignalingPred<AlivePredT<false>> first{ap, tell};  // (`tell.word` may be null: nothing to tell)
+                prim::compact(s, first, ap, ao, n_ptr, nv_total, c->tilesum, &c->st->nv[nxt]);
             }
             const size_t hsize = next_pow2((size_t)2 * std::max(nf_cap, 1));
             const int cgrid = grid_for(std::max<long long>(nv_total, (long long)hsize), 8192);
@@ -781,20 +785,24 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
             LivePred lp{c->estate};
             LiveOut lo{c->list};
             prim::compact(s, lp, lp, lo, &c->st->ne, ne_bound, c->tilesum, &c->st->live[0]);
-            sa.done = next_signal(c);
             select_tail_kernel<<<1, TAIL_THREADS, 0, s>>>(sa);
             launched += wide + 3;
+            // the kernel behind the tail tells the host that the tail's results are in the read-back area
+            const HostSignal tail_done = next_signal(c);
+            const HostSignal nothing{nullptr, 0};
             if (ahead_ok) {
                 if (ahead_budget) {
                     TruncPred tp{c->ekey, c->mate, mt, vbits};
                     rc = budget_step<false>(c, s, tp, B, ne_bound, vbits, mt, tb, over_bound, seg_bound, c->matched,
-                                            c->nrem, true);
+                                            c->nrem, true, tail_done);
                     if (rc != PICASSO_OK) return rc;
                 }
-                issue_contract(nf_bound, 0, nullptr, true);
+                issue_contract(nf_bound, 0, nullptr, true, ahead_budget ? nothing : tail_done);
                 issue_facets(nf_bound, true);
+            } else {
+                signal_kernel<<<1, 64, 0, s>>>(tail_done);
             }
-            HIP_TRY(c, wait_for_signal(c, s, sa.done));  // the tail has left [State][matched] in the read-back area
+            HIP_TRY(c, wait_for_signal(c, s, tail_done));  // [State][matched] are in the read-back area
             if (!validated) {
                 const int st_err = status_from_err_bits(hst->err);
                 if (st_err != PICASSO_OK) return st_err;
@@ -869,7 +877,7 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         const int nxt = cur ^ 1;
         if (!ahead) {
             tm.begin(round, PICASSO_ST_CONTRACT);
-            issue_contract(nf_bound, n_joined, akeys, false);
+            issue_contract(nf_bound, n_joined, akeys, false, HostSignal{nullptr, 0});
             tm.end();
             tm.begin(round, PICASSO_ST_FACETS);
             issue_facets(nf_bound, false);

@@ -1031,11 +1031,22 @@ inline int compact_tilesum_capacity(long long n_cap) {
     return (big > COMPACT_MAX_SUMMED_TILES ? big : COMPACT_MAX_SUMMED_TILES) + 1;
 }
 
+// A counting predicate may provide `void on_start() const`: one thread of the count kernel calls it
+// before anything else, whatever the number of items (used to tell the host that the kernels in
+// front of this one on the stream are done).
+template <class P, class = void>
+struct pred_has_on_start : std::false_type {};
+template <class P>
+struct pred_has_on_start<P, std::void_t<decltype(std::declval<const P&>().on_start())>> : std::true_type {};
+
 template <class Pred, int CHUNKS>
 __global__ __launch_bounds__(BLOCK) void tile_count_kernel(Pred pred, const int* n_ptr, int n_host,
                                                            int* __restrict__ tilesum) {
     constexpr int CTILE = BLOCK * CHUNKS;
     __shared__ u32 smem[WAVES];
+    if constexpr (pred_has_on_start<Pred>::value) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) pred.on_start();
+    }
     const int n = load_count(n_ptr, n_host);
     const long long base = (long long)blockIdx.x * CTILE;
     if (base >= n) return;
