@@ -2,7 +2,8 @@
 oracle: random point sets with random facet lists (repeated triples, facets
 with repeated corners, vertices no facet uses, several components), lattice
 patches with random holes, random budgets, and random settings of the three
-options (Alg. 2 line 11, inverse placement, seeded shuffle).  Integer outputs
+options (Alg. 2 line 11, inverse placement, seeded shuffle) and of the options
+that only change how the host drives a round.  Integer outputs
 bit-exact, positions bit-identical.
 """
 import numpy as np
@@ -64,8 +65,13 @@ def test_random_meshes_and_options(oracle, chunk):
             seed = int(rng.choice([0, 0, 1 + int(rng.integers(0, 1 << 40))]))
             max_rounds = int(rng.choice([-1, -1, 1, 2]))
             block_max = int(rng.choice([0, 1 << 15]))
+            sub_batch, ahead, poll = int(rng.choice([1, 2, 16])), int(rng.integers(0, 2)), int(rng.integers(0, 2))
             print(f"random chunk={chunk} case={case} N={N} F={F.shape[0]} target={target} absorb={absorb} "
-                  f"inverse={inverse} thr={thr} seed={seed} max_rounds={max_rounds} block_max={block_max}", flush=True)
+                  f"inverse={inverse} thr={thr} seed={seed} max_rounds={max_rounds} block_max={block_max} "
+                  f"sub_batch={sub_batch} ahead={ahead} poll={poll}", flush=True)
+            ctx.set_option(pk.PICASSO_OPT_SUBROUND_BATCH, sub_batch)   # (how the host drives the round: no effect
+            ctx.set_option(pk.PICASSO_OPT_LAUNCH_AHEAD, ahead)         #  on the result)
+            ctx.set_option(pk.PICASSO_OPT_HOST_POLL, poll)
             ctx.set_option(pk.PICASSO_OPT_ABSORB, int(absorb))
             ctx.set_placement(pk.PICASSO_PLACE_INVERSE if inverse else pk.PICASSO_PLACE_MEAN, thr)
             ctx.set_option(pk.PICASSO_OPT_SHUFFLE_SEED, seed)
