@@ -1209,53 +1209,59 @@ __global__ __launch_bounds__(TRUNC_THREADS) void trunc_block_kernel(u32* __restr
         return m;
     };
 
-    // prefix = smallest key x with at least `keep` keys <= x, found bit by bit from the top.
-    // below = keys < prefix, upper = keys <= prefix | (undecided bits all set): upper - below keys
-    // share the bits decided so far.  Once there are at most TRUNC_NARROW_BLOCK of them they are
-    // dealt out again, 4 to a thread; once at most TRUNC_NARROW_WAVE, one wave takes them and
-    // finishes alone.
-    u32 prefix = 0, kk = 0;
-    if (keep > 0) {
-        u32 below = 0, upper = (u32)n;
-        int bit = 31;
-        // steps over the values in `a` (of which `valid` are real, `outside` more lie below them all)
-        auto steps = [&](const auto& a, auto rr, u32 valid, u32 outside, u32 until) {
-            while (bit >= 0 && upper - below > until) {
-                u32 c = count_le(a, rr, prefix | ((1u << bit) - 1u), bit & 1);
-                c = outside + (c < valid ? c : valid);  // (empty slots count when x is the largest key)
-                if (c < (u32)keep) {
-                    prefix |= 1u << bit;
-                    below = c;
-                } else {
-                    upper = c;
-                }
-                --bit;
+    // The search: the smallest x with at least `want` of the values a[] <= x, bit by bit from the
+    // top.  Every thread holds R values, `valid` of them in the workgroup are real (is_real(r)), the
+    // others hold the largest value.  below = values < prefix, upper = values <= prefix | (undecided
+    // bits all set): upper - below values share the bits decided so far.  Once there are at most
+    // TRUNC_NARROW_BLOCK of them they are dealt out again, 4 to a thread; once at most
+    // TRUNC_NARROW_WAVE, one wave takes them and finishes alone.  Leaves x in `prefix` and the
+    // number of values < x in `below`.
+    u32 prefix = 0, below = 0, upper = 0, want = 0;
+    int bit = -1;
+    // steps over the values in `a` (of which `real` are real, `outside` more lie below them all)
+    auto steps = [&](const auto& a, auto rr, u32 real, u32 outside, u32 until) {
+        while (bit >= 0 && upper - below > until) {
+            u32 c = count_le(a, rr, prefix | ((1u << bit) - 1u), bit & 1);
+            c = outside + (c < real ? c : real);  // (the other slots count when x is the largest value)
+            if (c < want) {
+                prefix |= 1u << bit;
+                below = c;
+            } else {
+                upper = c;
             }
-        };
-        auto finish_in_one_wave = [&](auto rr, auto is_cand, auto value_of) {
-            const u32 outside = below;
-            const u32 m = gather_candidates(rr, is_cand, value_of);
-            if (w == 0) {
-                u32 less;
-                const u32 x = wave_search(m, prefix, bit, outside, (u32)keep, less);
-                if (lane == 0) {
-                    found[0] = x;
-                    found[1] = less;
-                }
+            --bit;
+        }
+    };
+    auto finish_in_one_wave = [&](auto rr, auto is_cand, auto value_of) {
+        const u32 outside = below;
+        const u32 m = gather_candidates(rr, is_cand, value_of);
+        if (w == 0) {
+            u32 less;
+            const u32 x = wave_search(m, prefix, bit, outside, want, less);
+            if (lane == 0) {
+                found[0] = x;
+                found[1] = less;
             }
-            __syncthreads();
-            prefix = found[0];
-            below = found[1];
-        };
+        }
+        __syncthreads();
+        prefix = found[0];
+        below = found[1];
+    };
+    auto search = [&](const auto& a, auto is_real, u32 valid, u32 want_) {
         const auto all_r = std::integral_constant<int, R>{};
         const auto four = std::integral_constant<int, 4>{};
         auto decided_mask = [&]() -> u32 { return bit == 31 ? 0u : ~0u << (bit + 1); };
-        steps(key, all_r, (u32)n, 0u, R > 4 ? (u32)TRUNC_NARROW_BLOCK : (u32)TRUNC_NARROW_WAVE);
+        prefix = 0;
+        below = 0;
+        upper = valid;
+        want = want_;
+        bit = 31;
+        __syncthreads();  // (a search before this one has finished with the shared arrays)
+        steps(a, all_r, valid, 0u, R > 4 ? (u32)TRUNC_NARROW_BLOCK : (u32)TRUNC_NARROW_WAVE);
         if (R > 4 && bit >= 0 && upper - below > (u32)TRUNC_NARROW_WAVE) {
             const u32 decided = decided_mask(), outside = below;
             const u32 m = gather_candidates(
-                all_r, [&](int r) { return r * TRUNC_THREADS + tid < n && (key[r] & decided) == prefix; },
-                [&](int r) { return key[r]; });
+                all_r, [&](int r) { return is_real(r) && (a[r] & decided) == prefix; }, [&](int r) { return a[r]; });
             u32 k4[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) k4[j] = (u32)(j * TRUNC_THREADS + tid) < m ? cbuf[j * TRUNC_THREADS + tid] : 0xFFFFFFFFu;
@@ -1269,83 +1275,49 @@ __global__ __launch_bounds__(TRUNC_THREADS) void trunc_block_kernel(u32* __restr
         } else if (bit >= 0) {
             const u32 decided = decided_mask();
             finish_in_one_wave(
-                all_r, [&](int r) { return r * TRUNC_THREADS + tid < n && (key[r] & decided) == prefix; },
-                [&](int r) { return key[r]; });
+                all_r, [&](int r) { return is_real(r) && (a[r] & decided) == prefix; }, [&](int r) { return a[r]; });
         }
+    };
+
+    // the cost key of the keep-th smallest pair, and how many pairs with exactly that key stay
+    u32 kk = 0;
+    if (keep > 0) {
+        search(key, [&](int r) { return r * TRUNC_THREADS + tid < n; }, (u32)n, (u32)keep);
         kk = (u32)keep - below;
     }
-    // kk = how many pairs with exactly the key `prefix` stay (the first kk in edge order)
+    const u32 kprefix = prefix;
     if constexpr (SHUFFLE) {
         // ... the first kk in the order of the seeded tie-break, which is distinct from pair to pair:
         // the same search once more, on the tie-break values of the pairs with that key
+        u32 tie[R];
         u32 neq = 0;
 #pragma unroll
-        for (int r = 0; r < R; ++r) neq += (r * TRUNC_THREADS + tid < n && key[r] == prefix) ? 1u : 0u;
+        for (int r = 0; r < R; ++r) {
+            const int i = r * TRUNC_THREADS + tid;
+            const bool eq = i < n && key[r] == kprefix;
+            tie[r] = eq ? tb.enc(tval[i]) : 0xFFFFFFFFu;
+            neq += eq ? 1u : 0u;
+        }
         {
             u32 tot;
             (void)prim::wide_block_exclusive_scan<NW>(neq, wsum, tot);
             neq = tot;
         }
-        if (neq <= (u32)TRUNC_NARROW_WAVE) {  // the usual case: few pairs share the threshold's cost key
-            u32 t2 = 0;
-            if (kk > 0) {
-                const u32 m = gather_candidates(
-                    std::integral_constant<int, R>{},
-                    [&](int r) { return r * TRUNC_THREADS + tid < n && key[r] == prefix; },
-                    [&](int r) { return tb.enc(tval[r * TRUNC_THREADS + tid]); });
-                if (w == 0) {
-                    u32 less;
-                    const u32 x = wave_search(m, 0u, 31, 0u, kk, less);
-                    if (lane == 0) found[0] = x;
-                }
-                __syncthreads();
-                t2 = found[0];
-            }
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                const int i = r * TRUNC_THREADS + tid;
-                if (i < n) {
-                    const bool out = key[r] > prefix || (key[r] == prefix && (kk == 0 || tb.enc(tval[i]) > t2));
-                    tcost[i] = out ? 1u : 0u;
-                }
-            }
-            return;
-        }
-        u32 tie[R];
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int i = r * TRUNC_THREADS + tid;
-            tie[r] = (i < n && key[r] == prefix) ? tb.enc(tval[i]) : 0xFFFFFFFFu;
-        }
-        auto count_tie_le = [&](u32 x, int slot) -> u32 {
-            u32 c = 0;
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-                c += (r * TRUNC_THREADS + tid < n && key[r] == prefix && tie[r] <= x) ? 1u : 0u;
-            c = wave_sum_u32(c);
-            __syncthreads();  // (the sums of the count before this one have been read)
-            if (lane == 0) wsum2[slot][w] = c;
-            __syncthreads();
-            u32 tot = 0;
-#pragma unroll
-            for (int j = 0; j < NW; ++j) tot += wsum2[slot][j];
-            return tot;
-        };
         u32 t2 = 0;
-        if (kk > 0)
-            for (int bit = 31; bit >= 0; --bit)
-                if (count_tie_le(t2 | ((1u << bit) - 1u), bit & 1) < kk) t2 |= 1u << bit;
-        __syncthreads();
+        if (kk > 0) {
+            search(tie, [&](int r) { return r * TRUNC_THREADS + tid < n && key[r] == kprefix; }, neq, kk);
+            t2 = prefix;
+        }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int i = r * TRUNC_THREADS + tid;
-            if (i < n) tcost[i] = (key[r] > prefix || (key[r] == prefix && (kk == 0 || tie[r] > t2))) ? 1u : 0u;
+            if (i < n) tcost[i] = (key[r] > kprefix || (key[r] == kprefix && (kk == 0 || tie[r] > t2))) ? 1u : 0u;
         }
         return;
     }
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        const bool eq = (r * TRUNC_THREADS + tid < n) && key[r] == prefix;
+        const bool eq = (r * TRUNC_THREADS + tid < n) && key[r] == kprefix;
         const u64 eb = __ballot(eq);
         if (lane == 0) cnt[r * NW + w] = (u32)__popcll(eb);
     }
@@ -1361,7 +1333,7 @@ __global__ __launch_bounds__(TRUNC_THREADS) void trunc_block_kernel(u32* __restr
     for (int r = 0; r < R; ++r) {
         const int i = r * TRUNC_THREADS + tid;
         const bool valid = i < n;
-        const bool eq = valid && key[r] == prefix, gt = valid && key[r] > prefix;
+        const bool eq = valid && key[r] == kprefix, gt = valid && key[r] > kprefix;
         const u64 eb = __ballot(eq);
         const u32 rank = cnt[r * NW + w] + (u32)__popcll(eb & lt);
         if (valid) tcost[i] = (gt || (eq && rank >= kk)) ? 1u : 0u;  // the key's slot now holds the flag
