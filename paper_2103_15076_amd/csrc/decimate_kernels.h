@@ -633,6 +633,9 @@ struct SelArgs {
     int publish_ints;  // for the host, which then needs no copy of its own before it looks
     TieBreak tb;       // order among edges of equal cost
     int cur;           // which of the ping-pong vertex / facet counts belong to this round
+    int* tile_live;    // not null (last grid-wide sub-round before the tail, one edge per lane and no
+                       // striding): workgroup b leaves here how many of its edges stay live, which is
+                       // the count pass of the gather that follows
 };
 
 // Bids are read with device-scope atomic loads where the same kernel also
@@ -715,9 +718,11 @@ __global__ __launch_bounds__(BLOCK) void select_subround_kernel(SelArgs A, int k
     u64* __restrict__ rst = A.vmin[(k + 2) % 3];
     const int n = A.st->ne;
     if (blockIdx.x == 0 && threadIdx.x == 0) A.st->sel_k = k + 1;
+    bool alive = false;
     for (long long base = (long long)blockIdx.x * BLOCK; base < n; base += (long long)gridDim.x * BLOCK) {
         const long long i = base + threadIdx.x;
-        bool alive = false, sel = false;
+        bool sel = false;
+        alive = false;
         int u = 0, v = 0, m = 0;
         u64 p = 0;
         const bool live_in = (i < n) && A.estate[i] == 0;
@@ -731,6 +736,18 @@ __global__ __launch_bounds__(BLOCK) void select_subround_kernel(SelArgs A, int k
             A.estate[i] = 1;
         }
         bid_grouped(nxt, alive, u, p);
+    }
+    if (A.tile_live) {  // (the host has made the grid cover every edge in one step)
+        __shared__ int wave_live[BLOCK / 64];
+        const u64 b = __ballot(alive);
+        if (prim::lane_id() == 0) wave_live[prim::wave_id()] = (int)__popcll(b);
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int tot = 0;
+#pragma unroll
+            for (int j = 0; j < BLOCK / 64; ++j) tot += wave_live[j];
+            A.tile_live[blockIdx.x] = tot;
+        }
     }
 }
 

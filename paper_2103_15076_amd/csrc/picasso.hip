@@ -768,7 +768,13 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
             int wide = 0;
             for (long long l = live_est; l > TAIL_MAX; ++wide) l = l * 10 / decay_x10[std::min(wide, 5)];
             wide = std::min<int>(wide, (int)std::max<int64_t>(1, c->opt_subround_batch));
+            // Below the sparse kernels' range the last of these sub-rounds has one lane per edge and as
+            // many workgroups as the gather has tiles: it counts its surviving edges for the gather.
+            // (wide == 0: so few edges that the tail takes them all from the start)
+            const bool counts_live = wide > 0 && ne_bound < SPARSE_MIN_EDGES && prim::compact_chunks_for(ne_bound) == 1 &&
+                                     grid_for(ne_bound, 1 << 16) == prim::compact_tiles(std::max(ne_bound, 1), 1);
             for (int j = 0; j < wide; ++j) {
+                sa.tile_live = (counts_live && j == wide - 1) ? c->tilesum : nullptr;
                 const int g4 = (ne_bound + BLOCK * 4 - 1) / (BLOCK * 4), g16 = (ne_bound + BLOCK * 16 - 1) / (BLOCK * 16);
                 if (sel_k + j == 1 && ne_bound >= SPARSE_MIN_EDGES) {
                     if (tb.on) select_subround_sparse_kernel<4, true><<<g4, BLOCK, 0, s>>>(sa, sel_k + j);
@@ -784,7 +790,8 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
             sel_k += wide;
             LivePred lp{c->estate};
             LiveOut lo{c->list};
-            prim::compact(s, lp, lp, lo, &c->st->ne, ne_bound, c->tilesum, &c->st->live[0]);
+            if (counts_live) prim::compact_scatter(s, lp, lo, &c->st->ne, ne_bound, c->tilesum, &c->st->live[0]);
+            else prim::compact(s, lp, lp, lo, &c->st->ne, ne_bound, c->tilesum, &c->st->live[0]);
             select_tail_kernel<<<1, TAIL_THREADS, 0, s>>>(sa);
             launched += wide + 3;
             // the kernel behind the tail tells the host that the tail's results are in the read-back area
