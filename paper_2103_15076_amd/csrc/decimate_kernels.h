@@ -1725,6 +1725,9 @@ __global__ __launch_bounds__(BLOCK) void facet_insert_kernel(const int* __restri
     const int nf = st->nf[cur];
     const int stride = gridDim.x * BLOCK;
     const int g = blockIdx.x * BLOCK + threadIdx.x;
+    // (the label of this thread's first original vertex is asked for now, so that it arrives while the
+    // facet is being worked on; it is composed with the new numbering at the end)
+    const int first_label = g < n_orig ? cid[g] : 0;
     for (int f = g; f < nf; f += stride) {
         const int a0 = fcur[3 * (size_t)f], b0 = fcur[3 * (size_t)f + 1], c0 = fcur[3 * (size_t)f + 2];
         const int a = vmap[a0], b = vmap[b0], c = vmap[c0];
@@ -1758,7 +1761,8 @@ __global__ __launch_bounds__(BLOCK) void facet_insert_kernel(const int* __restri
         }
         fslot[f] = (int)h;
     }
-    for (int o = g; o < n_orig; o += stride) cid[o] = vmap[cid[o]];
+    if (g < n_orig) cid[g] = vmap[first_label];
+    for (int o = g + stride; o < n_orig; o += stride) cid[o] = vmap[cid[o]];
 }
 
 // keep[f] = 1 iff the facet survives: not collapsed and the first of its triple (the slot that
