@@ -101,7 +101,7 @@ enum picasso_option {
                                       host memory after its results (it gives up after 20 ms and
                                       synchronises the stream); 0: it synchronises the stream.
                                       The results are the same either way.                       */
-    PICASSO_OPT_LAUNCH_AHEAD = 11  /* 1 (default): for inputs of up to 2^20 facets, in a round in
+    PICASSO_OPT_LAUNCH_AHEAD = 11  /* 1 (default): in a round of at most 2^20 facets in
                                       which the outcome of the selection decides nothing but
                                       counts (no mesh can exceed its budget, or some mesh surely
                                       will and the per-mesh budget step can take it), the kernels
