@@ -95,12 +95,13 @@ enum picasso_option {
                                       plus the seed's high word) instead of index order; pairs
                                       of different cost keep their order.  All 64 bits of the
                                       value are the seed; 0 (default): index order.              */
-    PICASSO_OPT_HOST_POLL = 10,    /* 1 (default): where a decimate call has to wait for the device
-                                      (once per round, and at its end) the host watches a sequence
-                                      number that the last kernel stores in the context's pinned
-                                      host memory after its results (it gives up after 20 ms and
-                                      synchronises the stream); 0: it synchronises the stream.
-                                      The results are the same either way.                       */
+    PICASSO_OPT_HOST_POLL = 10,    /* where a decimate call has to wait for the device (once per
+                                      round, and at its end) the host watches a sequence number
+                                      that a kernel stores in the context's pinned host memory
+                                      after its results, for at most this many microseconds, and
+                                      synchronises the stream if it has not come by then.  1
+                                      (default) = 20,000 us; 0 = synchronise the stream at once;
+                                      at most 10,000,000.  The results are the same either way.  */
     PICASSO_OPT_LAUNCH_AHEAD = 11  /* 1 (default): in a round of at most 2^20 facets in
                                       which the outcome of the selection decides nothing but
                                       counts (no mesh can exceed its budget, or some mesh surely

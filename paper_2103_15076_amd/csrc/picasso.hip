@@ -103,7 +103,7 @@ struct picasso_ctx {
     size_t h_pin_ints = 0;
     size_t h_seq_off = 0;  // the word that kernels store a sequence number in for the host (a cache line of its own)
     int host_seq = 0;      // the last sequence number handed out
-    int opt_poll = 1;      // the host watches that word instead of waiting for the stream
+    int64_t opt_poll_us = 20000;  // for how long the host watches that word before it waits for the stream instead (0: not at all)
     int opt_ahead = 1;     // a round's contraction and facet kernels are queued before the host has looked
     hipEvent_t ev[2 * PICASSO_STATS_ROUNDS * PICASSO_ST_COUNT + 4];
     int n_ev = 0;
@@ -420,15 +420,17 @@ HostSignal next_signal(picasso_ctx* c) {
 // area.  That kernel stores the sequence number after them (system-scope release), so the host
 // watches the word: it sees it some microseconds before a stream synchronisation would return,
 // and everything queued on the stream before that kernel is complete by then as well.  Falls back
-// to the stream synchronisation when the word has not changed after a while (or when switched
-// off), which also brings any launch error to light.
+// to the stream synchronisation when the word has not changed within the context's limit (20 ms
+// unless set otherwise; 0 = do not watch at all), which also brings any launch error to light.
 hipError_t wait_for_signal(picasso_ctx* c, hipStream_t s, const HostSignal& sig) {
-    if (c->opt_poll) {
+    if (c->opt_poll_us > 0) {
         const int* word = c->h_pin + c->h_seq_off;
         const auto t0 = std::chrono::steady_clock::now();
+        const auto limit = std::chrono::microseconds(c->opt_poll_us);
+        const long check_every = c->opt_poll_us >= 1000 ? 1023 : 15;  // (the clock is read every so many looks)
         for (long spins = 1;; ++spins) {
             if (__atomic_load_n(word, __ATOMIC_ACQUIRE) == sig.seq) return hipSuccess;
-            if ((spins & 1023) == 0 && std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(20)) break;
+            if ((spins & check_every) == 0 && std::chrono::steady_clock::now() - t0 > limit) break;
 #if defined(__x86_64__)
             __builtin_ia32_pause();
 #endif
@@ -1082,8 +1084,8 @@ int picasso_set_option(picasso_ctx* c, int option, int64_t value) {
             c->opt_shuffle_seed = (uint64_t)value;
             return PICASSO_OK;
         case PICASSO_OPT_HOST_POLL:
-            if (value != 0 && value != 1) return PICASSO_ERR_INVALID_ARG;
-            c->opt_poll = (int)value;
+            if (value < 0 || value > 10000000) return PICASSO_ERR_INVALID_ARG;
+            c->opt_poll_us = value == 1 ? 20000 : value;
             return PICASSO_OK;
         case PICASSO_OPT_LAUNCH_AHEAD:
             if (value != 0 && value != 1) return PICASSO_ERR_INVALID_ARG;

@@ -730,7 +730,7 @@ def test_host_wait_by_stream_synchronisation_or_by_watching_pinned_memory(pk, ct
     target = V.shape[0] // 7
     ref = oracle.decimate(V, F, target)
     b = meshgen.config("grid64")
-    for poll in (0, 1, 0, 1):
+    for poll in (0, 1, 2, 0, 50, 1):   # 2 and 50 us: the watch gives up and the stream is synchronised instead
         ctx.set_option(pk.PICASSO_OPT_HOST_POLL, poll)
         try:
             for _ in range(5):
@@ -741,7 +741,7 @@ def test_host_wait_by_stream_synchronisation_or_by_watching_pinned_memory(pk, ct
         finally:
             ctx.set_option(pk.PICASSO_OPT_HOST_POLL, 1)
     with pytest.raises(pk.PicassoError):
-        ctx.set_option(pk.PICASSO_OPT_HOST_POLL, 2)
+        ctx.set_option(pk.PICASSO_OPT_HOST_POLL, -1)
 
 
 @pytest.mark.parametrize("batch", [1, 16])

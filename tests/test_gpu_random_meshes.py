@@ -65,7 +65,7 @@ def test_random_meshes_and_options(oracle, chunk):
             seed = int(rng.choice([0, 0, 1 + int(rng.integers(0, 1 << 40))]))
             max_rounds = int(rng.choice([-1, -1, 1, 2]))
             block_max = int(rng.choice([0, 1 << 15]))
-            sub_batch, ahead, poll = int(rng.choice([1, 2, 16])), int(rng.integers(0, 2)), int(rng.integers(0, 2))
+            sub_batch, ahead, poll = int(rng.choice([1, 2, 16])), int(rng.integers(0, 2)), int(rng.choice([0, 1, 3]))
             print(f"random chunk={chunk} case={case} N={N} F={F.shape[0]} target={target} absorb={absorb} "
                   f"inverse={inverse} thr={thr} seed={seed} max_rounds={max_rounds} block_max={block_max} "
                   f"sub_batch={sub_batch} ahead={ahead} poll={poll}", flush=True)
