@@ -1023,21 +1023,22 @@ __global__ __launch_bounds__(TAIL_THREADS) void select_tail_kernel(SelArgs A) {
 
 // The selection tail does not tell the host itself (a system-scope fence inside it, with the pairs it
 // has just written still in the cache, costs more than a launch): the kernel after it on the stream
-// does, as its first act.  Everything the kernels before that one have written, to host memory as
-// well, is complete when it starts.  Either the first of the kernels queued ahead of the host's
+// does, as its first act, with a release store at system scope: what the kernels before that one
+// have written is visible to it when it starts, so the release carries those writes along (there
+// is next to nothing left in the cache to write back then, so it costs nothing measurable).  Either the first of the kernels queued ahead of the host's
 // look (through the counting predicate's on_start) ...
 template <class Pred>
 struct SignalingPred {
     Pred pred;
     HostSignal done;
     __device__ void on_start() const {
-        if (done.word) __hip_atomic_store(done.word, done.seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        if (done.word) __hip_atomic_store(done.word, done.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
     }
     __device__ bool operator()(int i) const { return pred(i); }
 };
 // ... or a kernel of its own.
 __global__ void signal_kernel(HostSignal done) {
-    if (threadIdx.x == 0) __hip_atomic_store(done.word, done.seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    if (threadIdx.x == 0) __hip_atomic_store(done.word, done.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
 // ---------------------------------------------------------------------------
