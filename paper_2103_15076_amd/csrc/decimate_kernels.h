@@ -165,6 +165,17 @@ struct EdgeKeys {
     }
 };
 
+// A single mesh's header (State and the per-mesh tables) written by init_kernel itself instead of
+// a copy from the host in front of it: everything zero except the counts, the mesh's vertex and
+// facet ranges and its target.  State::err is left alone (other workgroups of the same kernel flag
+// errors there): it is zero between calls.  hdr == nullptr: the header has been uploaded.
+struct HeaderInit {
+    int* hdr;
+    int total;                           // ints in the header
+    int at_voff0, at_foff, at_target;    // where the tables start
+    int N, F, target;
+};
+
 // Incidence keys for S0: (vertex << fbits) | facet, one per facet corner, so that sorting the keys
 // alone lists every vertex's facets in ascending facet order.  With COUNT_SMALL / COUNT_LARGE the
 // kernel also adds the keys' top 8- / 12-bit digits (bits [ishift, ...)) to ihist, the histogram
@@ -178,11 +189,24 @@ __global__ __launch_bounds__(BLOCK) void init_kernel(const float* __restrict__ v
                                                      VRec* __restrict__ vrec, int* __restrict__ cid,
                                                      int* __restrict__ fcur, u64* __restrict__ ikey, int fbits,
                                                      int ishift, u32* __restrict__ ihist, State* st,
-                                                     u32* __restrict__ msd_hist, int s0_follows) {
+                                                     u32* __restrict__ msd_hist, int s0_follows, HeaderInit init) {
     constexpr int RADIX = COUNT == COUNT_LARGE ? (1 << prim::BUCKET_LARGE_MSD_BITS) : (1 << prim::BUCKET_MSD_BITS);
     __shared__ u32 hist[COUNT != COUNT_NONE ? RADIX : 1];
     const int stride = gridDim.x * BLOCK;
     const int g = blockIdx.x * BLOCK + threadIdx.x;
+    const bool single = init.hdr != nullptr;  // one mesh, whose ranges are [0, N) and [0, F): the tables are not read here
+    if (single && blockIdx.x == 0) {
+        constexpr int ERR = (int)(offsetof(State, err) / sizeof(int));
+        constexpr int NV0 = (int)(offsetof(State, nv) / sizeof(int)), NF0 = (int)(offsetof(State, nf) / sizeof(int));
+        for (int i = threadIdx.x; i < init.total; i += BLOCK) {
+            if (i == ERR) continue;
+            int v = 0;
+            if (i == NV0 || i == init.at_voff0 + 1) v = init.N;
+            else if (i == NF0 || i == init.at_foff + 1) v = init.F;
+            else if (i == init.at_target) v = init.target;
+            init.hdr[i] = v;
+        }
+    }
     // the edge-key sort's digit counts and cursors start every round at zero (see edge_keys_kernel)
     for (int i = g; i < 2 * prim::MSD_HIST_WORDS; i += stride) msd_hist[i] = 0;
     if constexpr (COUNT != COUNT_NONE) {
@@ -206,9 +230,13 @@ __global__ __launch_bounds__(BLOCK) void init_kernel(const float* __restrict__ v
         const bool ok = f < F;
         int lo = 0, hi = 0;
         if (ok) {
-            const int m = mesh_of(foff, B, f);
-            lo = voff[m];
-            hi = voff[m + 1];
+            if (single) {
+                hi = N;
+            } else {
+                const int m = mesh_of(foff, B, f);
+                lo = voff[m];
+                hi = voff[m + 1];
+            }
         }
 #pragma unroll
         for (int c = 0; c < 3; ++c) {
@@ -1800,9 +1828,11 @@ struct FacetOut {
 // ---------------------------------------------------------------------------
 // The call's last kernel, one workgroup: the header's first n ints ([State][matched][foff_out])
 // copied to the host's read-back area, then the host is told.
-__global__ __launch_bounds__(BLOCK) void publish_header_kernel(const int* __restrict__ hdr, int n,
+__global__ __launch_bounds__(BLOCK) void publish_header_kernel(int* __restrict__ hdr, int n,
                                                                int* __restrict__ host_img, HostSignal done) {
     for (int i = threadIdx.x; i < n; i += BLOCK) host_img[i] = hdr[i];
+    // (the error flags are zero between calls: a single mesh's next call does not upload a header)
+    if (threadIdx.x == 0) hdr[offsetof(State, err) / sizeof(int)] = 0;
     signal_host(done, threadIdx.x, (int)threadIdx.x < n);
 }
 

@@ -333,7 +333,7 @@ inline int incidence_key_bits(int N, int F) { return ceil_log2(N) + incidence_fb
 
 // The validating kernel, instantiated for the sort the incidence keys go to.
 int launch_init(picasso_ctx* c, hipStream_t s, const float* d_verts, int N, const int32_t* d_facets, int F, int B,
-                bool with_keys) {
+                bool with_keys, HeaderInit init = HeaderInit{nullptr, 0, 0, 0, 0, 0, 0, 0}) {
     const int fbits = incidence_fbits(F), kb = incidence_key_bits(N, F);
     const int how = with_keys ? sort_by_vertex_path(3ll * F, kb) : COUNT_NONE;
     // only a sort that cannot make the keys itself (the plain LSD fallback) needs them written out
@@ -343,16 +343,16 @@ int launch_init(picasso_ctx* c, hipStream_t s, const float* d_verts, int N, cons
     if (how == COUNT_SMALL)
         init_kernel<COUNT_SMALL><<<grid, BLOCK, 0, s>>>(d_verts, N, d_facets, F, B, c->voff[0], c->foff, c->vrec[0],
                                                         c->cid, c->fbuf[0], ikey, fbits, prim::bucket_sort_low_bits(kb),
-                                                        c->hist12_s0, c->st, c->hist12, s0);
+                                                        c->hist12_s0, c->st, c->hist12, s0, init);
     else if (how == COUNT_LARGE)
         init_kernel<COUNT_LARGE><<<grid, BLOCK, 0, s>>>(d_verts, N, d_facets, F, B, c->voff[0], c->foff, c->vrec[0],
                                                         c->cid, c->fbuf[0], ikey, fbits,
                                                         kb - prim::BUCKET_LARGE_MSD_BITS, c->hist12_s0, c->st, c->hist12,
-                                                        s0);
+                                                        s0, init);
     else
         init_kernel<COUNT_NONE><<<grid, BLOCK, 0, s>>>(d_verts, N, d_facets, F, B, c->voff[0], c->foff, c->vrec[0],
                                                        c->cid, c->fbuf[0], ikey, fbits, 0, nullptr, c->st, c->hist12,
-                                                       s0);
+                                                       s0, init);
     return hipGetLastError() == hipSuccess ? PICASSO_OK : PICASSO_ERR_HIP;
 }
 
@@ -379,8 +379,9 @@ int run_vertex_quadrics(picasso_ctx* c, hipStream_t s, const float* d_verts, int
 }
 
 // Fills the pinned image of the header (State + per-mesh tables) and sends it with one copy.
+// `by_kernel`: only the checks; the first kernel writes the header itself (a single mesh, see HeaderInit).
 int upload_header(picasso_ctx* c, hipStream_t s, int B, const int32_t* nv_in, const int32_t* nf_in,
-                  const int32_t* target, int64_t* N_out, int64_t* F_out) {
+                  const int32_t* target, int64_t* N_out, int64_t* F_out, bool by_kernel = false) {
     const int cb = c->cap_b;
     int* img = c->h_pin + c->h_up_off;
     const int total = HDR_STATE_INTS + 8 * cb + 3;
@@ -405,7 +406,7 @@ int upload_header(picasso_ctx* c, hipStream_t s, int B, const int32_t* nv_in, co
     h->nf[0] = (int)facc;
     *N_out = nacc;
     *F_out = facc;
-    HIP_TRY(c, hipMemcpyAsync(c->hdr, img, sizeof(int) * total, hipMemcpyHostToDevice, s));
+    if (!by_kernel) HIP_TRY(c, hipMemcpyAsync(c->hdr, img, sizeof(int) * total, hipMemcpyHostToDevice, s));
     return PICASSO_OK;
 }
 
@@ -575,10 +576,15 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
     if (stats) memset(stats, 0, sizeof(*stats));
 
     int64_t N64 = 0, F64 = 0;
-    int rc = upload_header(c, s, B, nv_in, nf_in, target_nv, &N64, &F64);
+    const bool header_by_kernel = B == 1;  // one mesh: no copy in front of the first kernel
+    int rc = upload_header(c, s, B, nv_in, nf_in, target_nv, &N64, &F64, header_by_kernel);
     if (rc != PICASSO_OK) return rc;
     if (F64 > 0 && !d_facets) return PICASSO_ERR_INVALID_ARG;
     const int N = (int)N64, F = (int)F64;
+    HeaderInit hinit{nullptr, 0, 0, 0, 0, 0, 0, 0};
+    if (header_by_kernel)
+        hinit = HeaderInit{c->hdr, HDR_STATE_INTS + 8 * c->cap_b + 3, (int)(c->voff[0] - c->hdr), (int)(c->foff - c->hdr),
+                           (int)(c->target - c->hdr), N, F, target_nv[0]};
 
     c->n_ev = 0;
     c->kt.pool = c->kt_pool;
@@ -611,7 +617,7 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
     const u64* skeys = nullptr;
     const bool overlap = work && c->opt_overlap && c->side && !tm.on && F >= OVERLAP_MIN_FACETS;
     tm.begin(0, PICASSO_ST_QUADRICS);
-    rc = launch_init(c, s, d_verts, N, d_facets, F, B, work);
+    rc = launch_init(c, s, d_verts, N, d_facets, F, B, work, hinit);
     if (rc != PICASSO_OK) return rc;
     if (overlap) {
         HIP_TRY(c, hipEventRecord(c->ev_fork, s));
@@ -814,7 +820,10 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
             HIP_TRY(c, wait_for_signal(c, s, tail_done));  // [State][matched] are in the read-back area
             if (!validated) {
                 const int st_err = status_from_err_bits(hst->err);
-                if (st_err != PICASSO_OK) return st_err;
+                if (st_err != PICASSO_OK) {  // (the flags go back to zero for the next call, see HeaderInit)
+                    prim::fill_u32_kernel<<<1, BLOCK, 0, s>>>(reinterpret_cast<u32*>(&c->st->err), 1, 0u);
+                    return st_err;
+                }
                 validated = true;
             }
             sel_k = hst->sel_k;
@@ -1023,8 +1032,10 @@ int picasso_create(picasso_ctx** out, int device, int64_t max_verts, int64_t max
         return PICASSO_ERR_HIP;
     }
     memset(c->h_pin, 0, c->h_pin_ints * sizeof(int));
-    // the incidence sort's digit counts start at zero; every S0 leaves them at zero again
-    if (hipMemset(c->hist12_s0, 0, sizeof(u32) * 2 * prim::MSD_HIST_WORDS) != hipSuccess) {
+    // the incidence sort's digit counts start at zero; every S0 leaves them at zero again.  So do the
+    // header's error flags (see HeaderInit).
+    if (hipMemset(c->hist12_s0, 0, sizeof(u32) * 2 * prim::MSD_HIST_WORDS) != hipSuccess ||
+        hipMemset(c->hdr, 0, sizeof(int) * (HDR_STATE_INTS + 8 * (size_t)max_meshes + 3)) != hipSuccess) {
         (void)hipHostFree(c->h_pin);
         (void)hipFree(c->ws);
         delete c;
