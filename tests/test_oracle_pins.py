@@ -401,16 +401,92 @@ def test_zero_rounds_and_budget_unmet(oracle):
     assert r["status"] == oracle.WARN_BUDGET_UNMET and r["verts"].shape[0] == 7 and r["facets"].shape[0] == 0
 
 
+def _first_copies(facets_in, cid):
+    """What the reading on coinciding facets says, written out with a python set:
+    facets re-indexed through cluster_id; those with a repeated index dropped; of the
+    facets with one unordered triple the first in list order kept, as it is wound."""
+    seen, out = set(), []
+    for a, b, c in cid[np.asarray(facets_in).reshape(-1, 3)].tolist():
+        if a == b or b == c or a == c:
+            continue
+        k = tuple(sorted((a, b, c)))
+        if k in seen:
+            continue
+        seen.add(k)
+        out.append([a, b, c])
+    return out
+
+
+def test_hand_worked_facet_soup_keeps_first_copy_with_its_winding(oracle):
+    """Planar soup followed by hand (tests/golden/duplicate_facets_hand.json): a triple
+    given twice and once reversed, two facets that coincide with opposite windings only
+    after the contraction, far apart in the list, and repeated-index facets.  The
+    output list is compared entry by entry: order and winding both count."""
+    fx = json.load(open(os.path.join(GOLD, "duplicate_facets_hand.json")))
+    V = np.asarray(fx["verts"], np.float32)
+    F = np.asarray(fx["facets"], np.int32)
+    assert oracle.edges(F).tolist() == fx["edges"]
+    Q = oracle.vertex_quadrics(V, F)
+    cost, _ = oracle.edge_costs(V, Q, oracle.edges(F))
+    assert not cost.view(np.uint32).any()                    # all +0: pairs are visited in index order
+    for case in fx["cases"]:
+        r = oracle.decimate(V, F, case["target"])
+        assert r["status"] == 0 and r["rounds"] == case["rounds"]
+        assert r["verts"].tolist() == case["verts_out"]
+        assert r["facets"].reshape(-1, 3).tolist() == case["facets_out"]
+        assert r["cluster_id"].tolist() == case["cluster_id"]
+
+
 def test_duplicate_and_degenerate_input_facets(oracle):
-    """First copy of a repeated triple survives with its winding, also when the
-    later copy is wound the other way; repeated-index facets are dropped."""
+    """First copy of a repeated triple survives with its winding and in its place, also
+    when the later copy is wound the other way; repeated-index facets are dropped.
+    One contraction forces a clean-up pass; the expected list is rebuilt from the input
+    list and the cluster map with a python set."""
     V = np.array([[0, 0, 0], [1, 0, 0], [0, 1, 0], [1, 1, 0.3], [2, 2, 1]], np.float32)
     F = np.array([[0, 1, 2], [2, 1, 0], [1, 3, 2], [1, 2, 0], [3, 3, 2], [1, 3, 2]], np.int32)
-    r = oracle.decimate(V, F, 4)   # one contraction: forces a clean-up pass
+    r = oracle.decimate(V, F, 4)
     fo = r["facets"].reshape(-1, 3)
+    assert fo.tolist() == _first_copies(F, r["cluster_id"])
     s = np.sort(fo, 1)
     assert np.unique(s, axis=0).shape[0] == s.shape[0]
     assert np.all((fo[:, 0] != fo[:, 1]) & (fo[:, 1] != fo[:, 2]) & (fo[:, 0] != fo[:, 2]))
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_facet_soups_keep_first_copies_in_order(oracle, seed):
+    """Random soups full of repeated, reversed and collapsed facets, one and several
+    runs: the output facets are exactly the first copies, in input order, wound as given."""
+    rng = np.random.default_rng(900 + seed)
+    nv = int(rng.integers(8, 30))
+    V = rng.normal(size=(nv, 3)).astype(np.float32)
+    F = rng.integers(0, nv, size=(int(rng.integers(10, 90)), 3)).astype(np.int32)
+    F = np.concatenate([F, F[rng.integers(0, F.shape[0], 12)][:, ::-1], F[rng.integers(0, F.shape[0], 12)][:, [1, 2, 0]]])
+    F = np.ascontiguousarray(F[rng.permutation(F.shape[0])])
+    for target, max_rounds in ((nv - 1, -1), (max(2, nv // 2), 1), (max(2, nv // 4), -1)):
+        r = oracle.decimate(V, F, target, max_rounds=max_rounds)
+        if r["rounds"] == 0:
+            continue
+        assert r["facets"].reshape(-1, 3).tolist() == _first_copies(F, r["cluster_id"])
+
+
+def test_hand_worked_fan_two_runs_mean_of_current_positions(oracle):
+    """Planar fan followed by hand over two runs (tests/golden/fan_two_runs_hand.json):
+    the second run merges a two-vertex cluster with a single vertex, where the mean of
+    the two current positions (0.5,-2,0) differs from the centroid of the three
+    original vertices (2/3,-8/3,0); quadrics are carried as sums."""
+    fx = json.load(open(os.path.join(GOLD, "fan_two_runs_hand.json")))
+    V = np.asarray(fx["verts"], np.float32)
+    F = np.asarray(fx["facets"], np.int32)
+    assert oracle.edges(F).tolist() == fx["edges"]
+    assert oracle.vertex_quadrics(V, F)[:, 5].tolist() == fx["vertex_a22"]
+    for case in fx["cases"]:
+        r = oracle.decimate(V, F, case["target"], max_rounds=case["max_rounds"], return_quadrics=True)
+        assert r["status"] == 0 and r["rounds"] == case["rounds"]
+        assert r["verts"].tolist() == case["verts_out"]
+        assert r["facets"].reshape(-1, 3).tolist() == case["facets_out"]
+        assert r["cluster_id"].tolist() == case["cluster_id"]
+        assert r["quadrics"][:, 5].tolist() == case["a22_out"]
+        assert not r["quadrics"][:, [0, 1, 2, 3, 4, 6, 7, 8, 9]].any()
 
 
 def test_error_codes(oracle):
