@@ -223,6 +223,30 @@ enum picasso_pool_mode {
 int picasso_replace_mapping(picasso_ctx* ctx, void* stream, const int32_t* d_cluster_id, int32_t n_in, int32_t n_out,
                             int32_t* d_replace, int32_t* d_mapping);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): picasso_replace_mapping
+ * without a context.  The one scratch array the two kernels need (the smallest
+ * member of every cluster, n_out ints, and an error flag) lives in a static
+ * device array inside the library, so n_out <= PICASSO_STATIC_MAX_CLUSTERS
+ * (16 MiB per device, held until the process ends); a larger n_out returns
+ * PICASSO_ERR_WORKSPACE and nothing is queued.  The call allocates nothing
+ * (no hipMalloc / hipFree, no allocating library routine), creates no stream or
+ * event, does not wait and uses no pinned host memory: it queues three kernels
+ * on `stream` of `device` (0 <= device < 64) and returns.  Instead of a status
+ * that would need a wait, the last kernel stores PICASSO_OK or
+ * PICASSO_ERR_BAD_INDEX (an id outside [0, n_out); d_replace / d_mapping then
+ * unspecified) in the device word d_status; the return value covers the
+ * argument checks and launch errors only.  d_replace, d_mapping [n_in],
+ * d_status [1]: device memory owned by the caller; same results as
+ * picasso_replace_mapping.  The array's address is looked up once per device
+ * on the first call there (make that call outside graph capture).  Every call
+ * on a device uses that device's one array: calls that overlap in time on one
+ * device (other streams, other host threads) race and must be ordered by the
+ * caller. */
+#define PICASSO_STATIC_MAX_CLUSTERS (1 << 22)
+int picasso_replace_mapping_static(int device, void* stream, const int32_t* d_cluster_id, int32_t n_in, int32_t n_out,
+                                   int32_t* d_replace, int32_t* d_mapping, int32_t* d_status);
+
 /* Member lists of the clusters: d_offsets [n_out+1], d_members [n_in] (members of
  * cluster c = d_members[d_offsets[c] .. d_offsets[c+1]), ascending).  Built with a
  * stable radix sort of (cluster_id, vertex).  Waits for its work on the stream (as

@@ -8,6 +8,7 @@ raises if the library is missing (there is no CPU fallback).
 from . import meshgen  # noqa: F401
 from .binding import (  # noqa: F401
     Context, PicassoError, load_library, picasso_stats, picasso_strerror, picasso_workspace_bytes, picasso_device_copy,
+    picasso_replace_mapping_static, PICASSO_STATIC_MAX_CLUSTERS,
     PICASSO_OK, PICASSO_WARN_BUDGET_UNMET, PICASSO_ERR_INVALID_ARG, PICASSO_ERR_BAD_INDEX,
     PICASSO_ERR_NONFINITE, PICASSO_ERR_WORKSPACE, PICASSO_ERR_HIP,
     PICASSO_OPT_MAX_ROUNDS, PICASSO_OPT_STAGE_TIMING, PICASSO_OPT_SUBROUND_BATCH, PICASSO_OPT_KERNEL_TIMING, PICASSO_OPT_OVERLAP, PICASSO_OPT_TRUNC_BLOCK_MAX,

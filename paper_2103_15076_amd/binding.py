@@ -43,6 +43,7 @@ EXPORTED_SYMBOLS = (
     "picasso_last_hip_error", "picasso_decimate", "picasso_decimate_batch", "picasso_vertex_quadrics",
     "picasso_edge_costs", "picasso_radix_sort", "picasso_kernel_timing",
     "picasso_device_copy", "picasso_bucket_sort", "picasso_cluster_csr", "picasso_replace_mapping",
+    "picasso_replace_mapping_static",
     "picasso_vertex_corner_csr", "picasso_facet_geometry", "picasso_fuzzy_coefficients", "picasso_v2f_forward",
     "picasso_v2f_backward", "picasso_f2f_forward", "picasso_f2f_backward", "picasso_f2v_forward",
     "picasso_f2v_backward", "picasso_pool_forward",
@@ -129,6 +130,8 @@ def load_library():
     lib.picasso_cluster_csr.argtypes = [vp, vp, vp, i32, i32, vp, vp]
     lib.picasso_replace_mapping.restype = ctypes.c_int
     lib.picasso_replace_mapping.argtypes = [vp, vp, vp, i32, i32, vp, vp]
+    lib.picasso_replace_mapping_static.restype = ctypes.c_int
+    lib.picasso_replace_mapping_static.argtypes = [ctypes.c_int, vp, vp, i32, i32, vp, vp, vp]
     lib.picasso_vertex_corner_csr.restype = ctypes.c_int
     lib.picasso_vertex_corner_csr.argtypes = [vp, vp, vp, i32, i32, vp, vp]
     lib.picasso_facet_geometry.restype = ctypes.c_int
@@ -192,6 +195,21 @@ def picasso_device_copy(dst, src, stream=None):
                                             ctypes.c_void_p(src.data_ptr()), nbytes)
     if st != PICASSO_OK:
         raise PicassoError(st, picasso_strerror(st))
+
+
+PICASSO_STATIC_MAX_CLUSTERS = 1 << 22
+
+
+def picasso_replace_mapping_static(cluster_id, n_out, replace, mapping, status, device=0, stream=None):
+    """picasso_replace_mapping for callers that cannot allocate: no context; every tensor, outputs
+    (replace, mapping int32[n_in], status int32[1]) included, comes from the caller; asynchronous.
+    Returns the call's own status (argument checks and launch errors); the bad-index verdict is left
+    in ``status`` on the device."""
+    import torch
+    return int(load_library().picasso_replace_mapping_static(
+        int(device), _stream_ptr(stream), _dev_ptr(cluster_id, torch.int32, "cluster_id"), int(cluster_id.shape[0]),
+        int(n_out), _dev_ptr(replace, torch.int32, "replace"), _dev_ptr(mapping, torch.int32, "mapping"),
+        _dev_ptr(status, torch.int32, "status")))
 
 
 class Context:

@@ -11,6 +11,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <atomic>
 #include <chrono>
 #include <new>
 #include <vector>
@@ -998,6 +999,16 @@ int reduce_filter_rows(picasso_ctx* c, hipStream_t s, Term term, int n_rows, int
 
 }  // namespace
 
+// Scratch of picasso_replace_mapping_static (the entry point for callers that cannot allocate):
+// the smallest member of every cluster, then (a cache line further) the bad-index flag.  In host
+// code this name is only a handle for hipGetSymbolAddress; kernels get the looked-up address.
+static __device__ __align__(256) int scratch[PICASSO_STATIC_MAX_CLUSTERS + 64];
+
+namespace {
+constexpr int STATIC_MAX_DEVICES = 64;
+std::atomic<int*> scratch_ptr[STATIC_MAX_DEVICES];  // per device: where its copy of `scratch` lies (null: not looked up yet)
+}  // namespace
+
 // ---------------------------------------------------------------------------
 // C-ABI
 // ---------------------------------------------------------------------------
@@ -1510,6 +1521,34 @@ int picasso_replace_mapping(picasso_ctx* c, void* stream, const int32_t* d_clust
     if (rc != PICASSO_OK) return rc;
     HIP_TRY(c, hipGetLastError());
     return (reinterpret_cast<State*>(c->h_pin)->err & 1) ? PICASSO_ERR_BAD_INDEX : PICASSO_OK;
+}
+
+int picasso_replace_mapping_static(int device, void* stream, const int32_t* d_cluster_id, int32_t n_in, int32_t n_out,
+                                   int32_t* d_replace, int32_t* d_mapping, int32_t* d_status) {
+    if (device < 0 || device >= STATIC_MAX_DEVICES || !d_cluster_id || n_in < 1 || n_out < 1 || !d_replace ||
+        !d_mapping || !d_status)
+        return PICASSO_ERR_INVALID_ARG;
+    if (n_out > PICASSO_STATIC_MAX_CLUSTERS) return PICASSO_ERR_WORKSPACE;
+    if (hipSetDevice(device) != hipSuccess) return PICASSO_ERR_HIP;
+    // every device holds its own copy of the array at its own address: looked up once per device, with
+    // that device current; from here on only that address is used, never the array's name
+    int* ptr = scratch_ptr[device].load(std::memory_order_acquire);
+    if (!ptr) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return PICASSO_ERR_HIP;
+        ptr = static_cast<int*>(p);
+        scratch_ptr[device].store(ptr, std::memory_order_release);
+    }
+    hipStream_t s = (hipStream_t)stream;
+    int* first = ptr;
+    int* flag = ptr + PICASSO_STATIC_MAX_CLUSTERS;
+    // the array keeps the last call's contents: what this call reads starts from its own fill
+    // (a kernel, not a memset command, so that the call can be recorded into a graph)
+    pool::static_begin_kernel<<<pool::grid_for(n_out), pool::BLOCK, 0, s>>>(first, n_out, flag);
+    pool::cluster_first_kernel<<<pool::grid_for(n_in), pool::BLOCK, 0, s>>>(d_cluster_id, n_in, n_out, first, flag);
+    pool::replace_mapping_status_kernel<<<pool::grid_for(n_in), pool::BLOCK, 0, s>>>(
+        d_cluster_id, n_in, n_out, first, flag, d_replace, d_mapping, d_status, PICASSO_OK, PICASSO_ERR_BAD_INDEX);
+    return hipGetLastError() == hipSuccess ? PICASSO_OK : PICASSO_ERR_HIP;
 }
 
 int picasso_pool_forward(picasso_ctx* c, void* stream, int mode, const float* d_x, int32_t n_in, int32_t C,

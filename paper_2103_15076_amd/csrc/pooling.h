@@ -195,6 +195,30 @@ __global__ __launch_bounds__(BLOCK) void replace_mapping_kernel(const int* __res
     mapping[v] = (r == v) ? c : -1;
 }
 
+// The two kernels in front of and behind cluster_first_kernel when the table of first members is the
+// library's static array (picasso_replace_mapping_static): the fill, which also clears the flag, and
+// replace_mapping_kernel's work plus the status word for the caller.
+__global__ __launch_bounds__(BLOCK) void static_begin_kernel(int* __restrict__ first, int n_out, int* __restrict__ flag) {
+    const int i = blockIdx.x * BLOCK + threadIdx.x;
+    if (i < n_out) first[i] = 0x7FFFFFFF;
+    if (i == 0) *flag = 0;
+}
+
+__global__ __launch_bounds__(BLOCK) void replace_mapping_status_kernel(const int* __restrict__ cid, int n_in, int n_out,
+                                                                       const int* __restrict__ first,
+                                                                       const int* __restrict__ flag,
+                                                                       int* __restrict__ replace, int* __restrict__ mapping,
+                                                                       int* __restrict__ status, int ok, int bad) {
+    const int v = blockIdx.x * BLOCK + threadIdx.x;
+    if (v == 0) *status = (*flag != 0) ? bad : ok;
+    if (v >= n_in) return;
+    const int c = cid[v];
+    if (c < 0 || c >= n_out) return;
+    const int r = first[c];
+    replace[v] = r;
+    mapping[v] = (r == v) ? c : -1;
+}
+
 inline int grid_for(long long n) { return (int)((n + BLOCK - 1) / BLOCK > 0 ? (n + BLOCK - 1) / BLOCK : 1); }
 
 template <int VEC>

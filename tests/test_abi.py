@@ -68,6 +68,13 @@ def test_host_side_argument_checks_need_no_device(lib):
     assert lib.picasso_create(ctypes.byref(h), 0, 10, (1 << 29) + 1, 1) == pk.PICASSO_ERR_INVALID_ARG
     assert lib.picasso_create(ctypes.byref(h), 0, 1 << 31, 10, 1) == pk.PICASSO_ERR_INVALID_ARG
     assert lib.picasso_device_copy(None, None, None, 16) == pk.PICASSO_ERR_INVALID_ARG
+    # the entry point without a context checks its arguments and its size limit before it touches a device
+    one = ctypes.c_void_p(16)
+    f = lib.picasso_replace_mapping_static
+    assert f(0, None, None, 4, 4, one, one, one) == pk.PICASSO_ERR_INVALID_ARG
+    assert f(0, None, one, 4, 4, one, one, None) == pk.PICASSO_ERR_INVALID_ARG
+    assert f(64, None, one, 4, 4, one, one, one) == pk.PICASSO_ERR_INVALID_ARG
+    assert f(0, None, one, 4, pk.PICASSO_STATIC_MAX_CLUSTERS + 1, one, one, one) == pk.PICASSO_ERR_WORKSPACE
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
