@@ -165,6 +165,29 @@ struct EdgeKeys {
     }
 };
 
+// Plane of a facet as (unit normal, d) with n . x + d = 0 (supplementary, facet quadric equation);
+// a facet of zero area or with a repeated index gets the zero plane, hence the zero quadric.
+// Positions come from the caller's packed [N,3] array.
+__device__ __forceinline__ float4 facet_plane(const float* __restrict__ verts, int i0, int i1, int i2) {
+    const float4 none = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    if (i0 == i1 || i1 == i2 || i0 == i2) return none;
+    const float3 p0 = make_float3(verts[3 * (size_t)i0], verts[3 * (size_t)i0 + 1], verts[3 * (size_t)i0 + 2]);
+    const float3 p1 = make_float3(verts[3 * (size_t)i1], verts[3 * (size_t)i1 + 1], verts[3 * (size_t)i1 + 2]);
+    const float3 p2 = make_float3(verts[3 * (size_t)i2], verts[3 * (size_t)i2 + 1], verts[3 * (size_t)i2 + 2]);
+    float ax = p1.x - p0.x, ay = p1.y - p0.y, az = p1.z - p0.z;
+    float bx = p2.x - p0.x, by = p2.y - p0.y, bz = p2.z - p0.z;
+    float nx = ay * bz - az * by;
+    float ny = az * bx - ax * bz;
+    float nz = ax * by - ay * bx;
+    float len = sqrtf((nx * nx + ny * ny) + nz * nz);
+    if (len == 0.0f) return none;
+    nx = nx / len;
+    ny = ny / len;
+    nz = nz / len;
+    const float d = -((nx * p0.x + ny * p0.y) + nz * p0.z);
+    return make_float4(nx, ny, nz, d);
+}
+
 // A single mesh's header (State and the per-mesh tables) written by init_kernel itself instead of
 // a copy from the host in front of it: everything zero except the counts, the mesh's vertex and
 // facet ranges and its target.  State::err is left alone (other workgroups of the same kernel flag
@@ -179,7 +202,7 @@ struct HeaderInit {
 // Incidence keys for S0: (vertex << fbits) | facet, one per facet corner, so that sorting the keys
 // alone lists every vertex's facets in ascending facet order.  With COUNT_SMALL / COUNT_LARGE the
 // kernel also adds the keys' top 8- / 12-bit digits (bits [ishift, ...)) to ihist, the histogram
-// that the sort of the keys starts from (zero on entry; see quadric_reduce_kernel); that sort makes
+// that the sort of the keys starts from (zero on entry; see quadric_rows_kernel); that sort makes
 // the keys again from the validated facet array (IncidenceKeys), so they are written out (ikey)
 // only for a sort that needs them in memory.
 template <int COUNT>
@@ -189,7 +212,8 @@ __global__ __launch_bounds__(BLOCK) void init_kernel(const float* __restrict__ v
                                                      VRec* __restrict__ vrec, int* __restrict__ cid,
                                                      int* __restrict__ fcur, u64* __restrict__ ikey, int fbits,
                                                      int ishift, u32* __restrict__ ihist, State* st,
-                                                     u32* __restrict__ msd_hist, int s0_follows, HeaderInit init) {
+                                                     u32* __restrict__ msd_hist, int s0_follows, HeaderInit init,
+                                                     float4* __restrict__ planes) {
     constexpr int RADIX = COUNT == COUNT_LARGE ? (1 << prim::BUCKET_LARGE_MSD_BITS) : (1 << prim::BUCKET_MSD_BITS);
     __shared__ u32 hist[COUNT != COUNT_NONE ? RADIX : 1];
     const int stride = gridDim.x * BLOCK;
@@ -217,7 +241,7 @@ __global__ __launch_bounds__(BLOCK) void init_kernel(const float* __restrict__ v
     for (int w = g; w < N; w += stride) {
         float x = verts[3 * (size_t)w], y = verts[3 * (size_t)w + 1], z = verts[3 * (size_t)w + 2];
         if (!(isfinite(x) && isfinite(y) && isfinite(z))) err |= 2;
-        if (!s0_follows) {  // (else quadric_reduce_kernel writes the whole record)
+        if (!s0_follows) {  // (else quadric_rows_kernel writes the whole record)
             VRec r;
             r.x = x; r.y = y; r.z = z; r.w0 = 0.f;
             r.a00 = r.a01 = r.a02 = r.a11 = r.a12 = r.a22 = r.b0 = r.b1 = r.b2 = r.c = r.w1 = r.w2 = 0.f;
@@ -238,6 +262,7 @@ __global__ __launch_bounds__(BLOCK) void init_kernel(const float* __restrict__ v
                 hi = voff[m + 1];
             }
         }
+        int corner[3] = {0, 0, 0};
 #pragma unroll
         for (int c = 0; c < 3; ++c) {
             u64 k = 0;
@@ -245,6 +270,7 @@ __global__ __launch_bounds__(BLOCK) void init_kernel(const float* __restrict__ v
                 int a = facets[3 * (size_t)f + c];
                 if (a < lo || a >= hi) { err |= 1; a = lo; }
                 fcur[3 * (size_t)f + c] = a;
+                corner[c] = a;
                 k = ((u64)(u32)a << fbits) | (u64)(u32)f;
                 if (ikey) ikey[3 * (size_t)f + c] = k;
             }
@@ -263,6 +289,8 @@ __global__ __launch_bounds__(BLOCK) void init_kernel(const float* __restrict__ v
                 }
             }
         }
+        // the facet's plane, once per facet, for the vertex quadrics that S0 sums from it
+        if (planes && ok) planes[f] = facet_plane(verts, corner[0], corner[1], corner[2]);
     }
     if constexpr (COUNT != COUNT_NONE) {
         __syncthreads();
@@ -287,68 +315,130 @@ __global__ __launch_bounds__(BLOCK) void csr_offsets_kernel(const K* __restrict_
         for (int v = k + 1; v <= N; ++v) off[v] = H;
 }
 
-struct Quadric10 {
-    float q[10];
-};
+// Ordered segmented reduction over the sorted incidence keys (vertex << fbits | facet): the keys of
+// one vertex are consecutive and ascend in facet index, which is the order of the sum.  A
+// workgroup takes a tile of the keys; every lane fetches the planes of its share of the tile's
+// incidences into LDS (16 bytes gathered per incidence, all of a tile's gathers in flight together:
+// the plane was computed once per facet by init_kernel); the positions where a new vertex starts
+// are listed, and every such row goes to one lane, which adds up the facets' quadrics
+// Q = (n n^T, d n, d^2) left to right and writes the vertex's whole 64-byte record, position
+// included.  A row that runs past the end of its tile is followed into the next one (whose first
+// keys are then no row start).  Vertices without any facet appear in no key: the row of the next
+// vertex that has one notes the run of them in front of it (the last row also the run behind it),
+// and the workgroup writes their records (zero quadric) together.
+constexpr int QR_ITEMS = 4;
+constexpr int QR_TILE = BLOCK * QR_ITEMS;
+constexpr int QR_GAPS = 64;  // runs of facet-less vertices a tile lists (further ones are written by the lane that meets them)
 
-// Positions come from the caller's packed [N,3] array (12-byte stride), not from the 64-byte
-// vertex records: the three gathers per incidence then touch five times fewer cache lines.
-__device__ __forceinline__ Quadric10 facet_quadric(const float* __restrict__ verts, int i0, int i1, int i2) {
-    Quadric10 Q;
-#pragma unroll
-    for (int k = 0; k < 10; ++k) Q.q[k] = 0.0f;
-    if (i0 == i1 || i1 == i2 || i0 == i2) return Q;
-    const float3 p0 = make_float3(verts[3 * (size_t)i0], verts[3 * (size_t)i0 + 1], verts[3 * (size_t)i0 + 2]);
-    const float3 p1 = make_float3(verts[3 * (size_t)i1], verts[3 * (size_t)i1 + 1], verts[3 * (size_t)i1 + 2]);
-    const float3 p2 = make_float3(verts[3 * (size_t)i2], verts[3 * (size_t)i2 + 1], verts[3 * (size_t)i2 + 2]);
-    float ax = p1.x - p0.x, ay = p1.y - p0.y, az = p1.z - p0.z;
-    float bx = p2.x - p0.x, by = p2.y - p0.y, bz = p2.z - p0.z;
-    float nx = ay * bz - az * by;
-    float ny = az * bx - ax * bz;
-    float nz = ax * by - ay * bx;
-    float len = sqrtf((nx * nx + ny * ny) + nz * nz);
-    if (len == 0.0f) return Q;
-    nx = nx / len;
-    ny = ny / len;
-    nz = nz / len;
-    float d = -((nx * p0.x + ny * p0.y) + nz * p0.z);
-    Q.q[0] = nx * nx; Q.q[1] = nx * ny; Q.q[2] = nx * nz;
-    Q.q[3] = ny * ny; Q.q[4] = ny * nz; Q.q[5] = nz * nz;
-    Q.q[6] = d * nx;  Q.q[7] = d * ny;  Q.q[8] = d * nz;
-    Q.q[9] = d * d;
-    return Q;
-}
-
-// Ordered segmented reduction: one lane per vertex walks its CSR row in
-// ascending incidence order and adds the facet quadrics left to right.
-__global__ __launch_bounds__(BLOCK) void quadric_reduce_kernel(VRec* __restrict__ vrec,
-                                                               const float* __restrict__ verts, int N,
-                                                               const int* __restrict__ fcur,
-                                                               const int* __restrict__ off,
-                                                               const u64* __restrict__ inc, int fbits,
-                                                               u32* __restrict__ ihist) {
-    // workgroups go to the 8 dies in turn; each die (its own L2) takes one contiguous eighth of the vertices
-    const int w = (int)(((long long)(blockIdx.x & 7u) * (gridDim.x >> 3) + (blockIdx.x >> 3)) * BLOCK + threadIdx.x);
-    // last kernel of S0: the incidence sort's digit counts and cursors go back to zero for the next call
-    for (int i = blockIdx.x * BLOCK + threadIdx.x; i < 2 * prim::MSD_HIST_WORDS; i += gridDim.x * BLOCK) ihist[i] = 0;
-    if (w >= N) return;
-    float acc[10];
-#pragma unroll
-    for (int k = 0; k < 10; ++k) acc[k] = 0.0f;
-    if (off) {
-        const int s = off[w], e = off[w + 1];
-        for (int j = s; j < e; ++j) {
-            const int f = (int)(inc[j] & ((1ull << fbits) - 1ull));
-            const Quadric10 Q = facet_quadric(verts, fcur[3 * (size_t)f], fcur[3 * (size_t)f + 1], fcur[3 * (size_t)f + 2]);
-#pragma unroll
-            for (int k = 0; k < 10; ++k) acc[k] = acc[k] + Q.q[k];
-        }
-    }
-    float4* r = reinterpret_cast<float4*>(&vrec[w]);
-    r[0] = make_float4(verts[3 * (size_t)w], verts[3 * (size_t)w + 1], verts[3 * (size_t)w + 2], 0.f);
+__device__ __forceinline__ void write_vertex_record(VRec* __restrict__ vrec, const float* __restrict__ verts, int v,
+                                                    const float (&acc)[10]) {
+    float4* r = reinterpret_cast<float4*>(&vrec[v]);
+    r[0] = make_float4(verts[3 * (size_t)v], verts[3 * (size_t)v + 1], verts[3 * (size_t)v + 2], 0.f);
     r[1] = make_float4(acc[0], acc[1], acc[2], acc[3]);
     r[2] = make_float4(acc[4], acc[5], acc[6], acc[7]);
     r[3] = make_float4(acc[8], acc[9], 0.f, 0.f);
+}
+
+// acc += the quadric of the plane (n, d), coefficient by coefficient
+__device__ __forceinline__ void add_plane_quadric(float (&acc)[10], const float4 pl) {
+    const float q0 = pl.x * pl.x, q1 = pl.x * pl.y, q2 = pl.x * pl.z, q3 = pl.y * pl.y, q4 = pl.y * pl.z;
+    const float q5 = pl.z * pl.z, q6 = pl.w * pl.x, q7 = pl.w * pl.y, q8 = pl.w * pl.z, q9 = pl.w * pl.w;
+    acc[0] = acc[0] + q0; acc[1] = acc[1] + q1; acc[2] = acc[2] + q2; acc[3] = acc[3] + q3;
+    acc[4] = acc[4] + q4; acc[5] = acc[5] + q5; acc[6] = acc[6] + q6; acc[7] = acc[7] + q7;
+    acc[8] = acc[8] + q8; acc[9] = acc[9] + q9;
+}
+
+__global__ __launch_bounds__(BLOCK) void quadric_rows_kernel(VRec* __restrict__ vrec, const float* __restrict__ verts,
+                                                             int N, const float4* __restrict__ planes,
+                                                             const u64* __restrict__ inc, int H, int fbits,
+                                                             u32* __restrict__ ihist) {
+    __shared__ float4 splane[QR_TILE];         // plane of the facet of the key at position base + i
+    __shared__ int svert[QR_TILE + 1];         // svert[i + 1] = vertex of that key; svert[0] = of the key in front of the tile (-1: none)
+    __shared__ unsigned short hpos[QR_TILE];   // positions (within the tile) where a vertex's row starts, ascending
+    __shared__ u32 smem[prim::WAVES];
+    __shared__ int gap[2 * QR_GAPS];           // runs [first, end) of vertices without facets met by this tile's rows
+    __shared__ int n_gaps;
+    const int t = threadIdx.x;
+    // last kernel of S0: the incidence sort's digit counts and cursors go back to zero for the next call
+    for (int i = blockIdx.x * BLOCK + t; i < 2 * prim::MSD_HIST_WORDS; i += gridDim.x * BLOCK) ihist[i] = 0;
+    const float zero[10] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (H <= 0) {  // no facets at all: every vertex gets the zero quadric
+        for (int v = blockIdx.x * BLOCK + t; v < N; v += gridDim.x * BLOCK) write_vertex_record(vrec, verts, v, zero);
+        return;
+    }
+    // workgroups go to the 8 dies in turn; each die (its own L2) takes one contiguous eighth of the tiles
+    const long long tile = (long long)(blockIdx.x & 7u) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const long long base = tile * QR_TILE;
+    if (base >= H) return;
+    const int tile_n = (int)((long long)H - base < QR_TILE ? (long long)H - base : QR_TILE);
+    const u64 fmask = (1ull << fbits) - 1ull;
+#pragma unroll
+    for (int j = 0; j < QR_ITEMS; ++j) {
+        const int i = j * BLOCK + t;
+        if (i < tile_n) {
+            const u64 key = inc[base + i];
+            svert[i + 1] = (int)(key >> fbits);
+            splane[i] = planes[(size_t)(key & fmask)];
+        }
+    }
+    if (t == 0) {
+        svert[0] = base > 0 ? (int)(inc[base - 1] >> fbits) : -1;
+        n_gaps = 0;
+    }
+    __syncthreads();
+    // thread t looks at positions t * QR_ITEMS .. + QR_ITEMS - 1, so that the list of starts is in order
+    u32 mine = 0;
+    int cnt = 0;
+#pragma unroll
+    for (int j = 0; j < QR_ITEMS; ++j) {
+        const int i = t * QR_ITEMS + j;
+        if (i < tile_n && svert[i + 1] != svert[i]) {
+            mine |= 1u << j;
+            ++cnt;
+        }
+    }
+    u32 n_rows;
+    u32 at = prim::block_exclusive_scan((u32)cnt, smem, n_rows);
+#pragma unroll
+    for (int j = 0; j < QR_ITEMS; ++j)
+        if (mine & (1u << j)) hpos[at++] = (unsigned short)(t * QR_ITEMS + j);
+    __syncthreads();
+    auto note_gap = [&](int first, int end) {
+        const int slot = atomicAdd(&n_gaps, 1);
+        if (slot < QR_GAPS) {
+            gap[2 * slot] = first;
+            gap[2 * slot + 1] = end;
+        } else {
+            for (int g = first; g < end; ++g) write_vertex_record(vrec, verts, g, zero);
+        }
+    };
+    for (int r = t; r < (int)n_rows; r += BLOCK) {
+        const int hp = hpos[r];
+        const int row_end = r + 1 < (int)n_rows ? (int)hpos[r + 1] : tile_n;  // (within the tile)
+        const int v = svert[hp + 1];
+        const int pv = svert[hp];  // vertices between the row in front of this one and this one have no facet
+        if (pv + 1 < v) note_gap(pv + 1, v);
+        float acc[10];
+#pragma unroll
+        for (int k = 0; k < 10; ++k) acc[k] = 0.0f;
+        for (int j = hp; j < row_end; ++j) add_plane_quadric(acc, splane[j]);
+        bool last_of_all = false;
+        if (row_end == tile_n) {  // the tile's last row may go on in the next tile
+            long long j = base + tile_n;
+            for (; j < H; ++j) {
+                const u64 key = inc[j];
+                if ((int)(key >> fbits) != v) break;
+                add_plane_quadric(acc, planes[(size_t)(key & fmask)]);
+            }
+            last_of_all = j >= H;
+        }
+        write_vertex_record(vrec, verts, v, acc);
+        if (last_of_all && v + 1 < N) note_gap(v + 1, N);  // the vertices behind the last row have no facet either
+    }
+    __syncthreads();
+    const int ng = n_gaps < QR_GAPS ? n_gaps : QR_GAPS;
+    for (int i = 0; i < ng; ++i)
+        for (int g = gap[2 * i] + t; g < gap[2 * i + 1]; g += BLOCK) write_vertex_record(vrec, verts, g, zero);
 }
 
 // ---------------------------------------------------------------------------

@@ -271,7 +271,7 @@ inline int sort_by_vertex_path(long long n_max, int key_bits) {
     return COUNT_NONE;
 }
 
-template <typename K, bool HAS_VAL, int LARGE_KEYS_ONLY_ITEMS = 8, class Src = prim::ArrayKeys<K>>
+template <typename K, bool HAS_VAL, class Src = prim::ArrayKeys<K>>
 int sort_by_vertex(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_ptr, int n_max, int key_bits,
                    const prim::SortScratch& sc, u32* hist12, prim::LaunchTimer* lt = nullptr, int tag = 0,
                    bool counted = false, const Src* src = nullptr) {
@@ -280,7 +280,7 @@ int sort_by_vertex(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_p
         return prim::bucket_sort<K, HAS_VAL, Src>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc, lt, tag, counted,
                                                   hist12, src);
     if (how == COUNT_LARGE)
-        return prim::bucket_sort_large<K, HAS_VAL, LARGE_KEYS_ONLY_ITEMS, Src>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits,
+        return prim::bucket_sort_large<K, HAS_VAL, Src>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits,
                                                                                sc, hist12, lt, tag, counted, src);
     return prim::radix_sort<K, HAS_VAL>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc, lt, tag);
 }
@@ -314,7 +314,7 @@ int issue_edge_prefix(picasso_ctx* c, hipStream_t st_, int B, int round_, int cu
     const u64 sentinel_ = (vbits_ >= 32) ? ~0ull : ((1ull << (2 * vbits_)) - 1ull);
     if (H_ > 0) {
         const EdgeKeys src{c->fbuf[cur_], vbits_, sentinel_};  // (the counted sorts read the keys from here)
-        int where = sort_by_vertex<u64, false, 8, EdgeKeys>(st_, c->key64[0], c->key64[1], nullptr, nullptr, &c->st->nh,
+        int where = sort_by_vertex<u64, false, EdgeKeys>(st_, c->key64[0], c->key64[1], nullptr, nullptr, &c->st->nh,
                                                             H_, 2 * vbits_, c->sort_sc, c->hist12,
                                                             c->kt_this_call ? &c->kt : nullptr, round_, counted, &src);
         if (where < 0) return PICASSO_ERR_HIP;
@@ -332,6 +332,10 @@ constexpr int64_t OVERLAP_MIN_FACETS = 1 << 18;
 inline int incidence_fbits(int F) { return ceil_log2(std::max(F, 1)); }
 inline int incidence_key_bits(int N, int F) { return ceil_log2(N) + incidence_fbits(F); }
 
+// Where init_kernel leaves the facets' planes for S0: the edge-key array, which nothing else uses
+// before the first round's costs are computed (24 bytes per facet there, 16 needed).
+inline float4* facet_planes(picasso_ctx* c) { return reinterpret_cast<float4*>(c->ekey); }
+
 // The validating kernel, instantiated for the sort the incidence keys go to.
 int launch_init(picasso_ctx* c, hipStream_t s, const float* d_verts, int N, const int32_t* d_facets, int F, int B,
                 bool with_keys, HeaderInit init = HeaderInit{nullptr, 0, 0, 0, 0, 0, 0, 0}) {
@@ -340,20 +344,21 @@ int launch_init(picasso_ctx* c, hipStream_t s, const float* d_verts, int N, cons
     // only a sort that cannot make the keys itself (the plain LSD fallback) needs them written out
     u64* ikey = (with_keys && how == COUNT_NONE) ? c->s0_key[0] : nullptr;
     const int s0 = with_keys ? 1 : 0;
+    float4* planes = with_keys ? facet_planes(c) : nullptr;
     const int grid = grid_for(std::max(N, F), 4096);
     if (how == COUNT_SMALL)
         init_kernel<COUNT_SMALL><<<grid, BLOCK, 0, s>>>(d_verts, N, d_facets, F, B, c->voff[0], c->foff, c->vrec[0],
                                                         c->cid, c->fbuf[0], ikey, fbits, prim::bucket_sort_low_bits(kb),
-                                                        c->hist12_s0, c->st, c->hist12, s0, init);
+                                                        c->hist12_s0, c->st, c->hist12, s0, init, planes);
     else if (how == COUNT_LARGE)
         init_kernel<COUNT_LARGE><<<grid, BLOCK, 0, s>>>(d_verts, N, d_facets, F, B, c->voff[0], c->foff, c->vrec[0],
                                                         c->cid, c->fbuf[0], ikey, fbits,
                                                         kb - prim::BUCKET_LARGE_MSD_BITS, c->hist12_s0, c->st, c->hist12,
-                                                        s0, init);
+                                                        s0, init, planes);
     else
         init_kernel<COUNT_NONE><<<grid, BLOCK, 0, s>>>(d_verts, N, d_facets, F, B, c->voff[0], c->foff, c->vrec[0],
                                                        c->cid, c->fbuf[0], ikey, fbits, 0, nullptr, c->st, c->hist12,
-                                                       s0, init);
+                                                       s0, init, planes);
     return hipGetLastError() == hipSuccess ? PICASSO_OK : PICASSO_ERR_HIP;
 }
 
@@ -364,17 +369,17 @@ int run_vertex_quadrics(picasso_ctx* c, hipStream_t s, const float* d_verts, int
     if (F > 0) {
         const bool counted = sort_by_vertex_path(H, kb) != COUNT_NONE;
         const IncidenceKeys src{c->fbuf[0], fbits};  // (the counted sorts read the keys from here)
-        int where = sort_by_vertex<u64, false, 16, IncidenceKeys>(s, c->s0_key[0], c->s0_key[1], nullptr, nullptr,
+        int where = sort_by_vertex<u64, false, IncidenceKeys>(s, c->s0_key[0], c->s0_key[1], nullptr, nullptr,
                                                                   nullptr, H, kb, c->sort_sc_s0, c->hist12_s0, nullptr,
                                                                   0, counted, &src);
         if (where < 0) return PICASSO_ERR_HIP;
         const u64* skey = where ? c->s0_key[1] : c->s0_key[0];
-        csr_offsets_kernel<u64><<<grid_for(H), BLOCK, 0, s>>>(skey, fbits, H, N, c->csr_off);
-        quadric_reduce_kernel<<<(grid_for(N) + 7) / 8 * 8, BLOCK, 0, s>>>(c->vrec[0], d_verts, N, c->fbuf[0], c->csr_off, skey, fbits,
-                                                            c->hist12_s0);
+        const int tiles = (H + QR_TILE - 1) / QR_TILE;
+        quadric_rows_kernel<<<(tiles + 7) / 8 * 8, BLOCK, 0, s>>>(c->vrec[0], d_verts, N, facet_planes(c), skey, H, fbits,
+                                                                 c->hist12_s0);
     } else {
-        quadric_reduce_kernel<<<(grid_for(N) + 7) / 8 * 8, BLOCK, 0, s>>>(c->vrec[0], d_verts, N, c->fbuf[0], nullptr, nullptr, 0,
-                                                            c->hist12_s0);
+        quadric_rows_kernel<<<grid_for(N, 4096), BLOCK, 0, s>>>(c->vrec[0], d_verts, N, nullptr, nullptr, 0, 0,
+                                                               c->hist12_s0);
     }
     return PICASSO_OK;
 }

@@ -347,6 +347,9 @@ constexpr int BUCKET_THREADS_256 = 1024;  // 256 buckets: 8 keys per lane, up to
 constexpr int BUCKET_THREADS_4096 = 512;  // 4096 buckets: up to 4096 keys (8 per lane), or 8192 key-value
                                           // pairs (16 per lane: vertex incidences run to ~6 per vertex and
                                           // vertex ids need not fill their bit range, so those buckets run fuller)
+// keys without values (bucket_keys_kernel): lanes and keys per lane of a bucket's workgroup
+constexpr int BUCKET_KEYS_THREADS_256 = 512, BUCKET_KEYS_ITEMS_256 = 16;   // 256 buckets: up to 8192 keys in LDS
+constexpr int BUCKET_KEYS_THREADS_4096 = 256, BUCKET_KEYS_ITEMS_4096 = 16;  // 4096 buckets: up to 4096 keys in LDS
 constexpr int BUCKET_MSD_BITS = 8;
 constexpr long long BUCKET_SORT_MAX_KEYS = 1ll << 20;  // average bucket <= half of what LDS holds
 
@@ -520,7 +523,7 @@ template <typename K, bool HAS_VAL, int BUCKET_THREADS, int BUCKET_ITEMS, typena
 __device__ __forceinline__ void bucket_sort_one(const int bkt, K* __restrict__ kin, K* __restrict__ kout,
                                                 u32* __restrict__ vin, u32* __restrict__ vout,
                                                 const u32* __restrict__ totals, const u32* __restrict__ starts,
-                                                int low_bits, int only_above, int leave_above) {
+                                                int low_bits) {
     constexpr int BUCKET_WAVES = BUCKET_THREADS / 64;
     constexpr int BUCKET_CAP = BUCKET_THREADS * BUCKET_ITEMS;  // keys of one bucket held in LDS
     constexpr int RMAX = 1 << BUCKET_GROUP_BITS;
@@ -534,8 +537,7 @@ __device__ __forceinline__ void bucket_sort_one(const int bkt, K* __restrict__ k
 
     // start of this bucket = sum of the counts of the buckets before it (given, or summed here)
     const int cnt = (int)totals[bkt];
-    // (a second launch with more keys per lane, hence fewer workgroups per compute unit, may take the long buckets)
-    if (cnt == 0 || cnt <= only_above || cnt > leave_above) return;
+    if (cnt == 0) return;
     u32 start;
     if (starts) {  // (the partition kernel has left them)
         start = starts[bkt];
@@ -678,47 +680,288 @@ __device__ __forceinline__ void bucket_sort_one(const int bkt, K* __restrict__ k
     }
 }
 
-// A launch with one workgroup per bucket takes every bucket; a smaller grid walks over the buckets
-// (used for the few long buckets, selected by only_above, whose variant fits one workgroup per
-// compute unit: a full grid of workgroups that only look and leave would queue up behind that).
-template <typename K, bool HAS_VAL, int BUCKET_THREADS, int BUCKET_ITEMS, bool WALK = false, typename LK = K>
+template <typename K, bool HAS_VAL, int BUCKET_THREADS, int BUCKET_ITEMS, typename LK = K>
 __global__ __launch_bounds__(BUCKET_THREADS) void bucket_sort_kernel(K* __restrict__ kin, K* __restrict__ kout,
                                                                      u32* __restrict__ vin, u32* __restrict__ vout,
                                                                      const u32* __restrict__ totals, int nbuckets,
-                                                                     int low_bits, const u32* __restrict__ starts = nullptr,
-                                                                     int only_above = 0, int leave_above = 0x7FFFFFFF) {
-    if constexpr (WALK) {
-        // every wave looks at the sizes of the workgroup's next 64 buckets at once (same loads, same
-        // ballot in every wave), and the workgroup then visits only those it has to sort
-        for (int base = blockIdx.x; base < nbuckets; base += 64 * gridDim.x) {
-            const int mine = base + lane_id() * (int)gridDim.x;
-            const int c = mine < nbuckets ? (int)totals[mine] : 0;
-            u64 todo = __ballot(c > 0 && c > only_above && c <= leave_above);
-            while (todo) {
-                const int j = __ffsll((long long)todo) - 1;
-                todo &= todo - 1;
-                bucket_sort_one<K, HAS_VAL, BUCKET_THREADS, BUCKET_ITEMS, LK>(base + j * (int)gridDim.x, kin, kout, vin,
-                                                                              vout, totals, starts, low_bits,
-                                                                              only_above, leave_above);
+                                                                     int low_bits, const u32* __restrict__ starts = nullptr) {
+    (void)nbuckets;
+    bucket_sort_one<K, HAS_VAL, BUCKET_THREADS, BUCKET_ITEMS, LK>((int)blockIdx.x, kin, kout, vin, vout, totals, starts,
+                                                                  low_bits);
+}
+
+// ---------------------------------------------------------------------------
+// The per-bucket kernel for keys WITHOUT values (the sorts of the decimation path: incidence keys
+// and edge keys).  Equal keys are indistinguishable, so nothing has to be stable:
+//   1. the keys of the bucket are read once; each takes its place in its group (the keys that agree
+//      on the top 9 of the bucket's low bits: with vertex-pair keys the half-edges of one lower
+//      vertex) from one returning LDS atomic on the group's counter;
+//   2. one scan of the (up to 512) group counters gives the groups' first positions;
+//   3. one lane per group sorts its group on the whole key in registers with a sorting network of
+//      minimal size for 4, 6, 8, 12 or 16 keys (a wave runs every size that occurs among its 64
+//      groups, so the sizes are graded finely), by insertion up to 64 keys;
+//   4. the bucket is written out in order; optionally the number of distinct keys in it (the
+//      all-ones `sentinel` not counted) is left in nunique[bucket] for a compaction that follows.
+// A bucket with a group of more than 64 keys (a vertex of very high degree) is sorted as a whole by
+// a bitonic network over the LDS array; a bucket beyond the LDS capacity takes the slow
+// global-memory route of bucket_sort_oversize.  Workgroups are small (256 lanes for the 4096-bucket
+// sorts) so that eight of them share a compute unit and cover each other's barriers.
+// ---------------------------------------------------------------------------
+#define PRIM_CE(a, b)                       \
+    {                                       \
+        const K x_ = k[a], y_ = k[b];       \
+        const bool s_ = y_ < x_;            \
+        k[a] = s_ ? y_ : x_;                \
+        k[b] = s_ ? x_ : y_;                \
+    }
+
+// Sorting networks of 5, 12, 19, 39 and 60 comparators (the smallest known for these sizes; each was
+// checked on all 2^G inputs of zeros and ones).
+template <typename K, int G>
+__device__ __forceinline__ void network_sort_regs(K (&k)[G]) {
+    if constexpr (G == 4) {
+        PRIM_CE(0, 2) PRIM_CE(1, 3) PRIM_CE(0, 1) PRIM_CE(2, 3) PRIM_CE(1, 2)
+    } else if constexpr (G == 6) {
+        PRIM_CE(0, 5) PRIM_CE(1, 3) PRIM_CE(2, 4) PRIM_CE(1, 2) PRIM_CE(3, 4) PRIM_CE(0, 3) PRIM_CE(2, 5) PRIM_CE(0, 1)
+        PRIM_CE(2, 3) PRIM_CE(4, 5) PRIM_CE(1, 2) PRIM_CE(3, 4)
+    } else if constexpr (G == 8) {
+        PRIM_CE(0, 2) PRIM_CE(1, 3) PRIM_CE(4, 6) PRIM_CE(5, 7) PRIM_CE(0, 4) PRIM_CE(1, 5) PRIM_CE(2, 6) PRIM_CE(3, 7)
+        PRIM_CE(0, 1) PRIM_CE(2, 3) PRIM_CE(4, 5) PRIM_CE(6, 7) PRIM_CE(2, 4) PRIM_CE(3, 5) PRIM_CE(1, 4) PRIM_CE(3, 6)
+        PRIM_CE(1, 2) PRIM_CE(3, 4) PRIM_CE(5, 6)
+    } else if constexpr (G == 12) {
+        PRIM_CE(0, 8) PRIM_CE(1, 7) PRIM_CE(2, 6) PRIM_CE(3, 11) PRIM_CE(4, 10) PRIM_CE(5, 9) PRIM_CE(0, 1) PRIM_CE(2, 5)
+        PRIM_CE(3, 4) PRIM_CE(6, 9) PRIM_CE(7, 8) PRIM_CE(10, 11) PRIM_CE(0, 2) PRIM_CE(1, 6) PRIM_CE(5, 10) PRIM_CE(9, 11)
+        PRIM_CE(0, 3) PRIM_CE(1, 2) PRIM_CE(4, 6) PRIM_CE(5, 7) PRIM_CE(8, 11) PRIM_CE(9, 10) PRIM_CE(1, 4) PRIM_CE(3, 5)
+        PRIM_CE(6, 8) PRIM_CE(7, 10) PRIM_CE(1, 3) PRIM_CE(2, 5) PRIM_CE(6, 9) PRIM_CE(8, 10) PRIM_CE(2, 3) PRIM_CE(4, 5)
+        PRIM_CE(6, 7) PRIM_CE(8, 9) PRIM_CE(4, 6) PRIM_CE(5, 7) PRIM_CE(3, 4) PRIM_CE(5, 6) PRIM_CE(7, 8)
+    } else {
+        static_assert(G == 16, "network sizes: 4, 6, 8, 12, 16");
+        PRIM_CE(0, 13) PRIM_CE(1, 12) PRIM_CE(2, 15) PRIM_CE(3, 14) PRIM_CE(4, 8) PRIM_CE(5, 6) PRIM_CE(7, 11) PRIM_CE(9, 10)
+        PRIM_CE(0, 5) PRIM_CE(1, 7) PRIM_CE(2, 9) PRIM_CE(3, 4) PRIM_CE(6, 13) PRIM_CE(8, 14) PRIM_CE(10, 15) PRIM_CE(11, 12)
+        PRIM_CE(0, 1) PRIM_CE(2, 3) PRIM_CE(4, 5) PRIM_CE(6, 8) PRIM_CE(7, 9) PRIM_CE(10, 11) PRIM_CE(12, 13) PRIM_CE(14, 15)
+        PRIM_CE(0, 2) PRIM_CE(1, 3) PRIM_CE(4, 10) PRIM_CE(5, 11) PRIM_CE(6, 7) PRIM_CE(8, 9) PRIM_CE(12, 14) PRIM_CE(13, 15)
+        PRIM_CE(1, 2) PRIM_CE(3, 12) PRIM_CE(4, 6) PRIM_CE(5, 7) PRIM_CE(8, 10) PRIM_CE(9, 11) PRIM_CE(13, 14) PRIM_CE(1, 4)
+        PRIM_CE(2, 6) PRIM_CE(5, 8) PRIM_CE(7, 10) PRIM_CE(9, 13) PRIM_CE(11, 14) PRIM_CE(2, 4) PRIM_CE(3, 6) PRIM_CE(9, 12)
+        PRIM_CE(11, 13) PRIM_CE(3, 5) PRIM_CE(6, 8) PRIM_CE(7, 9) PRIM_CE(10, 12) PRIM_CE(3, 4) PRIM_CE(5, 6) PRIM_CE(7, 8)
+        PRIM_CE(9, 10) PRIM_CE(11, 12) PRIM_CE(6, 7) PRIM_CE(8, 9)
+    }
+}
+#undef PRIM_CE
+
+// The g <= G keys at [gs, gs + g) of an LDS array sorted by one lane (empty places hold the largest key).
+template <typename K, int G>
+__device__ __forceinline__ void group_sort_lds(K* skey, int gs, int g) {
+    K k[G];
+#pragma unroll
+    for (int j = 0; j < G; ++j) k[j] = j < g ? skey[gs + j] : (K) ~(K)0;
+    network_sort_regs<K, G>(k);
+#pragma unroll
+    for (int j = 0; j < G; ++j)
+        if (j < g) skey[gs + j] = k[j];
+}
+
+template <typename K, typename LK, int THREADS, int ITEMS, bool COUNT_UNIQUE>
+__global__ __launch_bounds__(THREADS) void bucket_keys_kernel(K* __restrict__ kin, K* __restrict__ kout,
+                                                              const u32* __restrict__ totals,
+                                                              const u32* __restrict__ starts, int low_bits, K sentinel,
+                                                              u32* __restrict__ nunique) {
+    constexpr int NW = THREADS / 64;
+    constexpr int CAP = THREADS * ITEMS;
+    constexpr int RMAX = 1 << BUCKET_GROUP_BITS;
+    constexpr int PER = RMAX / THREADS > 0 ? RMAX / THREADS : 1;  // group counters per thread in the scan
+    static_assert((CAP & (CAP - 1)) == 0, "the whole-bucket network pads to a power of two within the LDS array");
+    static_assert(THREADS >= 64 && THREADS % 64 == 0 && (THREADS >= RMAX || RMAX % THREADS == 0), "whole counters per thread");
+    __shared__ LK skey[CAP];
+    __shared__ u32 gcnt[RMAX];
+    __shared__ u32 gstart[RMAX + 1];
+    __shared__ u32 smem[NW];
+    __shared__ u32 nlong;
+    const int t = threadIdx.x, lane = lane_id(), w = wave_id();
+    const int bkt = (int)blockIdx.x;
+    const int cnt = (int)totals[bkt];
+    if (cnt == 0) {
+        if (COUNT_UNIQUE && t == 0) nunique[bkt] = 0;
+        return;
+    }
+    const u32 start = starts[bkt];
+    kin += start;
+    kout += start;
+
+    // number of distinct keys, from the threads' partial counts
+    auto publish_unique = [&](u32 uc) {
+#pragma unroll
+        for (int d = 32; d > 0; d >>= 1) uc += __shfl_xor(uc, d, 64);
+        __syncthreads();
+        if (lane == 0) smem[w] = uc;
+        __syncthreads();
+        if (t == 0) {
+            u32 tot = 0;
+            for (int j = 0; j < NW; ++j) tot += smem[j];
+            nunique[bkt] = tot;
+        }
+    };
+
+    if (cnt > CAP) {  // beyond the LDS array: pass by pass through global memory
+        bucket_sort_oversize<K, false, THREADS>(kout, kin, nullptr, nullptr, cnt, low_bits, gcnt, smem);
+        if constexpr (COUNT_UNIQUE) {
+            __threadfence();
+            __syncthreads();
+            u32 uc = 0;
+            for (int i = t; i < cnt; i += THREADS) {
+                const K k = coherent_load(&kout[i]);
+                uc += (k != sentinel && (i == 0 || coherent_load(&kout[i - 1]) != k)) ? 1u : 0u;
+            }
+            publish_unique(uc);
+        }
+        return;
+    }
+    if (low_bits <= 0) {  // nothing below the bucket's digit: all keys equal
+        for (int i = t; i < cnt; i += THREADS) kout[i] = kin[i];
+        if (COUNT_UNIQUE && t == 0) nunique[bkt] = kin[0] != sentinel ? 1u : 0u;
+        return;
+    }
+
+    const int gbits = low_bits < BUCKET_GROUP_BITS ? low_bits : BUCKET_GROUP_BITS;
+    const int rest = low_bits - gbits;
+    const u32 R = 1u << gbits, dmask = R - 1;
+    for (int i = t; i < (int)R; i += THREADS) gcnt[i] = 0;
+    if (t == 0) nlong = 0;
+    const int items = (cnt + THREADS - 1) / THREADS;  // <= ITEMS, the same in every thread
+    LK key[ITEMS];
+    u32 pos[ITEMS];
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        key[i] = (LK)0;
+        pos[i] = 0;
+        if (i < items) {
+            const int idx = i * THREADS + t;
+            if (idx < cnt) key[i] = (LK)kin[idx];
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i)
+        if (i < items && i * THREADS + t < cnt) pos[i] = atomicAdd(&gcnt[digit_of<LK>(key[i], rest, dmask)], 1u);
+    __syncthreads();
+    u32 c[PER], sum = 0, tot;
+    int too_long = 0;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+        const u32 d = (u32)(t * PER + j);
+        c[j] = d < R ? gcnt[d] : 0u;
+        sum += c[j];
+        too_long |= c[j] > (u32)BUCKET_GROUP_MAX ? 1 : 0;
+    }
+    u32 run = wide_block_exclusive_scan<NW>(sum, smem, tot);
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+        const u32 d = (u32)(t * PER + j);
+        if (d < R) gstart[d] = run;
+        run += c[j];
+    }
+    if (t == 0) gstart[R] = (u32)cnt;
+    const int any_long = __syncthreads_or(too_long);
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i)
+        if (i < items && i * THREADS + t < cnt) skey[gstart[digit_of<LK>(key[i], rest, dmask)] + pos[i]] = key[i];
+    __syncthreads();
+    if (rest > 0 && !any_long) {
+        for (int gi = t; gi < (int)R; gi += THREADS) {
+            const int gs = (int)gstart[gi];
+            const int g = (int)gstart[gi + 1] - gs;
+            if (g > 16) {  // listed for the waves (the counters are no longer needed: the list goes there)
+                gcnt[atomicAdd(&nlong, 1u)] = (u32)gi;
+            } else if (g > 12) {
+                group_sort_lds<LK, 16>(skey, gs, g);
+            } else if (g > 8) {
+                group_sort_lds<LK, 12>(skey, gs, g);
+            } else if (g > 6) {
+                group_sort_lds<LK, 8>(skey, gs, g);
+            } else if (g > 4) {
+                group_sort_lds<LK, 6>(skey, gs, g);
+            } else if (g > 1) {
+                group_sort_lds<LK, 4>(skey, gs, g);
+            }
+        }
+        __syncthreads();
+        // groups of 17 to 64 keys: a wave takes a group, one lane per key; a key's place is the number of
+        // keys of the group that go before it (every lane reads the same address, one read after the
+        // other with nothing waiting in between, where an insertion sort by one lane would wait for
+        // LDS at every step)
+        const int n_long = (int)nlong;
+        if (n_long > 0) {
+            for (int li = w; li < n_long; li += NW) {
+                const int gi = (int)gcnt[li];
+                const int gs = (int)gstart[gi];
+                const int g = (int)gstart[gi + 1] - gs;
+                const LK k = lane < g ? skey[gs + lane] : (LK)0;
+                int r = 0;
+                for (int i = 0; i < g; ++i) {
+                    const LK o = skey[gs + i];
+                    r += (o < k || (o == k && i < lane)) ? 1 : 0;
+                }
+                __builtin_amdgcn_wave_barrier();  // (a wave's LDS operations complete in order)
+                if (lane < g) skey[gs + r] = k;
+            }
+            __syncthreads();
+        }
+    } else if (rest > 0) {
+        // some group is longer still: the whole bucket through a bitonic network, padded to a power of two
+        int P = 64;
+        while (P < cnt) P <<= 1;
+        for (int i = cnt + t; i < P; i += THREADS) skey[i] = (LK) ~(LK)0;
+        __syncthreads();
+        for (int size = 2; size <= P; size <<= 1) {
+            for (int stride = size >> 1; stride > 0; stride >>= 1) {
+                for (int q = t; q < P / 2; q += THREADS) {
+                    const int i = 2 * q - (q & (stride - 1)), l = i + stride;
+                    const bool up = (i & size) == 0;
+                    const LK a = skey[i], b = skey[l];
+                    if ((a > b) == up) {
+                        skey[i] = b;
+                        skey[l] = a;
+                    }
+                }
                 __syncthreads();
             }
         }
-    } else {
-        bucket_sort_one<K, HAS_VAL, BUCKET_THREADS, BUCKET_ITEMS, LK>((int)blockIdx.x, kin, kout, vin, vout, totals,
-                                                                      starts, low_bits, only_above, leave_above);
     }
+    K upper = 0;
+    if constexpr (sizeof(LK) < sizeof(K)) upper = (K)(u32)bkt << low_bits;
+    u32 uc = 0;
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        if (i < items) {
+            const int idx = i * THREADS + t;
+            if (idx < cnt) {
+                const LK k = skey[idx];
+                const K full = upper | (K)k;
+                kout[idx] = full;
+                if constexpr (COUNT_UNIQUE) uc += (full != sentinel && (idx == 0 || skey[idx - 1] != k)) ? 1u : 0u;
+            }
+        }
+    }
+    if constexpr (COUNT_UNIQUE) publish_unique(uc);
 }
 
-// Launch of the keys-only bucket kernel with the narrowest in-LDS key type that holds low_bits bits.
-template <typename K, int BUCKET_THREADS, int BUCKET_ITEMS, bool WALK>
-inline void launch_bucket_keys(int grid, hipStream_t s, K* kin, K* kout, const u32* totals, int nbuckets, int low_bits,
-                               const u32* starts, int only_above = 0, int leave_above = 0x7FFFFFFF) {
-    if (sizeof(K) == 8 && low_bits <= 32)
-        bucket_sort_kernel<K, false, BUCKET_THREADS, BUCKET_ITEMS, WALK, u32><<<grid, BUCKET_THREADS, 0, s>>>(
-            kin, kout, nullptr, nullptr, totals, nbuckets, low_bits, starts, only_above, leave_above);
+// Launch of that kernel, one workgroup per bucket, with the narrowest in-LDS key type that holds low_bits
+// bits.  nunique == nullptr: no counting.
+template <typename K, int THREADS, int ITEMS>
+inline void launch_bucket_keys_kernel(int nbuckets, hipStream_t s, K* kin, K* kout, const u32* totals, int low_bits,
+                                      const u32* starts, K sentinel = (K)0, u32* nunique = nullptr) {
+    if constexpr (sizeof(K) == 8) {
+        if (low_bits <= 32) {
+            if (nunique)
+                bucket_keys_kernel<K, u32, THREADS, ITEMS, true><<<nbuckets, THREADS, 0, s>>>(kin, kout, totals, starts, low_bits, sentinel, nunique);
+            else
+                bucket_keys_kernel<K, u32, THREADS, ITEMS, false><<<nbuckets, THREADS, 0, s>>>(kin, kout, totals, starts, low_bits, sentinel, nunique);
+            return;
+        }
+    }
+    if (nunique)
+        bucket_keys_kernel<K, K, THREADS, ITEMS, true><<<nbuckets, THREADS, 0, s>>>(kin, kout, totals, starts, low_bits, sentinel, nunique);
     else
-        bucket_sort_kernel<K, false, BUCKET_THREADS, BUCKET_ITEMS, WALK, K><<<grid, BUCKET_THREADS, 0, s>>>(
-            kin, kout, nullptr, nullptr, totals, nbuckets, low_bits, starts, only_above, leave_above);
+        bucket_keys_kernel<K, K, THREADS, ITEMS, false><<<nbuckets, THREADS, 0, s>>>(kin, kout, totals, starts, low_bits, sentinel, nunique);
 }
 
 // Histogram of the top RBITS-bit digit (bits [shift, shift + RBITS)) over the whole input, added
@@ -878,7 +1121,7 @@ inline int bucket_sort(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int*
             else
                 msd_scatter_kernel<K, BUCKET_MSD_BITS, SORT_ITEMS_SMALL, ArrayKeys<K>><<<tiles, BLOCK, 0, s>>>(ArrayKeys<K>{k0}, k1, n_ptr, n_max, low, msd_hist, cursor, starts);
             const bool timed = lt && lt->begin(s, tag);
-            launch_bucket_keys<K, BUCKET_THREADS_256, 8, false>(1 << msd, s, k1, k0, msd_hist, 1 << msd, low, starts);
+            launch_bucket_keys_kernel<K, BUCKET_KEYS_THREADS_256, BUCKET_KEYS_ITEMS_256>(1 << msd, s, k1, k0, msd_hist, low, starts);
             if (timed) lt->end(s);
             if (hipGetLastError() != hipSuccess) return -1;
             return 0;
@@ -950,8 +1193,7 @@ __global__ __launch_bounds__(BLOCK) void top_digit_histogram_kernel(const K* __r
 
 // Result is in (k1, v1): returns 1 (keys with values), or in k0: returns 0 (keys only); <0 on a
 // launch error.  hist12 holds 3 * MSD_HIST_WORDS words (counts, cursors, first positions).
-template <typename K, bool HAS_VAL, int KEYS_ONLY_ITEMS = 8,  // keys per lane of the bucket kernel without values
-          class Src = ArrayKeys<K>>
+template <typename K, bool HAS_VAL, class Src = ArrayKeys<K>>
 inline int bucket_sort_large(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_ptr, int n_max, int key_bits,
                              const SortScratch& sc, u32* hist12, LaunchTimer* lt = nullptr, int tag = 0,
                              bool counted = false, const Src* src = nullptr) {
@@ -971,14 +1213,7 @@ inline int bucket_sort_large(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, cons
         else
             msd_scatter_kernel<K, BUCKET_LARGE_MSD_BITS, SORT_ITEMS_BIG, ArrayKeys<K>><<<tiles, BLOCK, 0, s>>>(ArrayKeys<K>{k0}, k1, n_ptr, n_max, low, hist12, cursor, starts);
         const bool timed = lt && lt->begin(s, tag);
-        if constexpr (KEYS_ONLY_ITEMS > 8) {
-            // buckets of up to 4096 keys at three workgroups per compute unit, longer ones separately
-            constexpr int CAP8 = BUCKET_THREADS_4096 * 8;
-            launch_bucket_keys<K, BUCKET_THREADS_4096, 8, false>(R, s, k1, k0, hist12, R, low, starts, 0, CAP8);
-            launch_bucket_keys<K, BUCKET_THREADS_4096, KEYS_ONLY_ITEMS, true>(256, s, k1, k0, hist12, R, low, starts, CAP8);
-        } else {
-            launch_bucket_keys<K, BUCKET_THREADS_4096, KEYS_ONLY_ITEMS, false>(R, s, k1, k0, hist12, R, low, starts);
-        }
+        launch_bucket_keys_kernel<K, BUCKET_KEYS_THREADS_4096, BUCKET_KEYS_ITEMS_4096>(R, s, k1, k0, hist12, low, starts);
         if (timed) lt->end(s);
         if (hipGetLastError() != hipSuccess) return -1;
         return 0;
