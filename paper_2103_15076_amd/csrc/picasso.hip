@@ -271,17 +271,19 @@ inline int sort_by_vertex_path(long long n_max, int key_bits) {
     return COUNT_NONE;
 }
 
+// `uq` (keys without values, bucket sorts only): the sort also does the count pass of the compaction
+// that keeps one of every run of equal keys.
 template <typename K, bool HAS_VAL, class Src = prim::ArrayKeys<K>>
 int sort_by_vertex(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_ptr, int n_max, int key_bits,
                    const prim::SortScratch& sc, u32* hist12, prim::LaunchTimer* lt = nullptr, int tag = 0,
-                   bool counted = false, const Src* src = nullptr) {
+                   bool counted = false, const Src* src = nullptr, const prim::UniqueCount<K>* uq = nullptr) {
     const int how = sort_by_vertex_path(n_max, key_bits);
     if (how == COUNT_SMALL)
         return prim::bucket_sort<K, HAS_VAL, Src>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc, lt, tag, counted,
-                                                  hist12, src);
+                                                  hist12, src, uq);
     if (how == COUNT_LARGE)
-        return prim::bucket_sort_large<K, HAS_VAL, Src>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits,
-                                                                               sc, hist12, lt, tag, counted, src);
+        return prim::bucket_sort_large<K, HAS_VAL, Src>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc, hist12, lt, tag,
+                                                        counted, src, uq);
     return prim::radix_sort<K, HAS_VAL>(s, k0, k1, v0, v1, n_ptr, n_max, key_bits, sc, lt, tag);
 }
 
@@ -312,16 +314,31 @@ int issue_edge_prefix(picasso_ctx* c, hipStream_t st_, int B, int round_, int cu
             c->fbuf[cur_], c->st, cur_, vbits_, c->key64[0], c->vmin[0], c->vmin[1], c->mate, rt, 0, nullptr);
     skeys = c->key64[0];
     const u64 sentinel_ = (vbits_ >= 32) ? ~0ull : ((1ull << (2 * vbits_)) - 1ull);
+    bool counted_firsts = false;  // the sort has left the unique step's tile counts
     if (H_ > 0) {
         const EdgeKeys src{c->fbuf[cur_], vbits_, sentinel_};  // (the counted sorts read the keys from here)
+        // the bucket sorts also count, per tile of the compaction that follows, the keys that differ from
+        // the key in front of them: the count pass of the unique step
+        prim::UniqueCount<u64> uq;
+        if (counted) {
+            const int chunks = prim::compact_chunks_for(H_);
+            uq.tilesum = c->tilesum;
+            uq.tiles = prim::compact_tiles(H_, chunks);
+            uq.tile_shift = ceil_log2((long long)BLOCK * chunks);
+            uq.sentinel = sentinel_;
+            counted_firsts = true;
+        }
         int where = sort_by_vertex<u64, false, EdgeKeys>(st_, c->key64[0], c->key64[1], nullptr, nullptr, &c->st->nh,
-                                                            H_, 2 * vbits_, c->sort_sc, c->hist12,
-                                                            c->kt_this_call ? &c->kt : nullptr, round_, counted, &src);
+                                                         H_, 2 * vbits_, c->sort_sc, c->hist12,
+                                                         c->kt_this_call ? &c->kt : nullptr, round_, counted, &src,
+                                                         counted ? &uq : nullptr);
         if (where < 0) return PICASSO_ERR_HIP;
         skeys = where ? c->key64[1] : c->key64[0];
     }
-    UniquePred up_{skeys, sentinel_};
-    prim::compact_count(st_, up_, &c->st->nh, H_, c->tilesum);
+    if (!counted_firsts) {
+        UniquePred up_{skeys, sentinel_};
+        prim::compact_count(st_, up_, &c->st->nh, H_, c->tilesum);
+    }
     *skeys_out = skeys;
     return PICASSO_OK;
 }

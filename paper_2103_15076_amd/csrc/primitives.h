@@ -700,8 +700,11 @@ __global__ __launch_bounds__(BUCKET_THREADS) void bucket_sort_kernel(K* __restri
 //   3. one lane per group sorts its group on the whole key in registers with a sorting network of
 //      minimal size for 4, 6, 8, 12 or 16 keys (a wave runs every size that occurs among its 64
 //      groups, so the sizes are graded finely), by insertion up to 64 keys;
-//   4. the bucket is written out in order; optionally the number of distinct keys in it (the
-//      all-ones `sentinel` not counted) is left in nunique[bucket] for a compaction that follows.
+//   4. the bucket is written out in order; optionally (COUNT_UNIQUE) the kernel also does the count
+//      pass of the compaction that keeps the first of every run of equal keys (the all-ones
+//      `sentinel` not counted): it adds, per tile of 2^tile_shift positions of the whole output, the
+//      number of such keys to tilesum[tile] (zero on entry), which is what tile_count_kernel would
+//      leave there.
 // A bucket with a group of more than 64 keys (a vertex of very high degree) is sorted as a whole by
 // a bitonic network over the LDS array; a bucket beyond the LDS capacity takes the slow
 // global-memory route of bucket_sort_oversize.  Workgroups are small (256 lanes for the 4096-bucket
@@ -764,7 +767,7 @@ template <typename K, typename LK, int THREADS, int ITEMS, bool COUNT_UNIQUE>
 __global__ __launch_bounds__(THREADS) void bucket_keys_kernel(K* __restrict__ kin, K* __restrict__ kout,
                                                               const u32* __restrict__ totals,
                                                               const u32* __restrict__ starts, int low_bits, K sentinel,
-                                                              u32* __restrict__ nunique) {
+                                                              int* __restrict__ tilesum, int tile_shift) {
     constexpr int NW = THREADS / 64;
     constexpr int CAP = THREADS * ITEMS;
     constexpr int RMAX = 1 << BUCKET_GROUP_BITS;
@@ -776,28 +779,38 @@ __global__ __launch_bounds__(THREADS) void bucket_keys_kernel(K* __restrict__ ki
     __shared__ u32 gstart[RMAX + 1];
     __shared__ u32 smem[NW];
     __shared__ u32 nlong;
+    constexpr int TALLY = (CAP >> 8) + 2;  // tiles (of at least 256 positions) that CAP consecutive positions can touch
+    static_assert(TALLY <= THREADS, "one thread per tile of the tally");
+    __shared__ int tcnt[COUNT_UNIQUE ? TALLY : 1];
     const int t = threadIdx.x, lane = lane_id(), w = wave_id();
     const int bkt = (int)blockIdx.x;
     const int cnt = (int)totals[bkt];
-    if (cnt == 0) {
-        if (COUNT_UNIQUE && t == 0) nunique[bkt] = 0;
-        return;
-    }
+    if (cnt == 0) return;
     const u32 start = starts[bkt];
     kin += start;
     kout += start;
 
-    // number of distinct keys, from the threads' partial counts
-    auto publish_unique = [&](u32 uc) {
-#pragma unroll
-        for (int d = 32; d > 0; d >>= 1) uc += __shfl_xor(uc, d, 64);
-        __syncthreads();
-        if (lane == 0) smem[w] = uc;
-        __syncthreads();
-        if (t == 0) {
-            u32 tot = 0;
-            for (int j = 0; j < NW; ++j) tot += smem[j];
-            nunique[bkt] = tot;
+    // By every lane of a wave together: the wave's lanes hold the output positions start + idx0 + lane
+    // (idx0 the same in all lanes), `first` says whether a lane's key is the first of its run; the
+    // counts go to the one or two tiles the 64 positions lie in: to the workgroup's tally in LDS
+    // (`tally`), or straight to memory.
+    const u32 tile0 = COUNT_UNIQUE ? start >> tile_shift : 0u;  // first tile this bucket's range touches
+    auto count_firsts = [&](int idx0, bool first, int* tally) {
+        const u64 bal = __ballot(first);
+        if (bal == 0) return;
+        const u32 p0 = start + (u32)idx0;
+        const u32 tile_a = p0 >> tile_shift, tile_b = (p0 + 63u) >> tile_shift;
+        const u32 in_a = ((tile_a + 1u) << tile_shift) - p0;  // positions of the wave that lie in its first tile
+        const u64 mask_a = in_a >= 64u ? ~0ull : ((1ull << in_a) - 1ull);
+        if (lane == 0) {
+            const int ca = (int)__popcll(bal & mask_a), cb = (int)__popcll(bal & ~mask_a);
+            if (tally) {
+                if (ca) atomicAdd(&tally[tile_a - tile0], ca);
+                if (cb) atomicAdd(&tally[tile_b - tile0], cb);
+            } else {
+                if (ca) atomicAdd(&tilesum[tile_a], ca);
+                if (cb) atomicAdd(&tilesum[tile_b], cb);
+            }
         }
     };
 
@@ -806,18 +819,23 @@ __global__ __launch_bounds__(THREADS) void bucket_keys_kernel(K* __restrict__ ki
         if constexpr (COUNT_UNIQUE) {
             __threadfence();
             __syncthreads();
-            u32 uc = 0;
-            for (int i = t; i < cnt; i += THREADS) {
-                const K k = coherent_load(&kout[i]);
-                uc += (k != sentinel && (i == 0 || coherent_load(&kout[i - 1]) != k)) ? 1u : 0u;
+            for (int i0 = w * 64; i0 < cnt; i0 += THREADS) {  // (whole waves, for the ballot)
+                const int i = i0 + lane;
+                bool first = false;
+                if (i < cnt) {
+                    const K k = coherent_load(&kout[i]);
+                    first = k != sentinel && (i == 0 || coherent_load(&kout[i - 1]) != k);
+                }
+                count_firsts(i0, first, nullptr);
             }
-            publish_unique(uc);
         }
         return;
     }
     if (low_bits <= 0) {  // nothing below the bucket's digit: all keys equal
         for (int i = t; i < cnt; i += THREADS) kout[i] = kin[i];
-        if (COUNT_UNIQUE && t == 0) nunique[bkt] = kin[0] != sentinel ? 1u : 0u;
+        if constexpr (COUNT_UNIQUE) {
+            if (w == 0) count_firsts(0, lane == 0 && kin[0] != sentinel, nullptr);
+        }
         return;
     }
 
@@ -826,6 +844,9 @@ __global__ __launch_bounds__(THREADS) void bucket_keys_kernel(K* __restrict__ ki
     const u32 R = 1u << gbits, dmask = R - 1;
     for (int i = t; i < (int)R; i += THREADS) gcnt[i] = 0;
     if (t == 0) nlong = 0;
+    if constexpr (COUNT_UNIQUE) {
+        if (t < TALLY) tcnt[t] = 0;
+    }
     const int items = (cnt + THREADS - 1) / THREADS;  // <= ITEMS, the same in every thread
     LK key[ITEMS];
     u32 pos[ITEMS];
@@ -928,41 +949,65 @@ __global__ __launch_bounds__(THREADS) void bucket_keys_kernel(K* __restrict__ ki
     }
     K upper = 0;
     if constexpr (sizeof(LK) < sizeof(K)) upper = (K)(u32)bkt << low_bits;
-    u32 uc = 0;
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) {
         if (i < items) {
             const int idx = i * THREADS + t;
+            bool first = false;
             if (idx < cnt) {
                 const LK k = skey[idx];
                 const K full = upper | (K)k;
                 kout[idx] = full;
-                if constexpr (COUNT_UNIQUE) uc += (full != sentinel && (idx == 0 || skey[idx - 1] != k)) ? 1u : 0u;
+                if constexpr (COUNT_UNIQUE) first = full != sentinel && (idx == 0 || skey[idx - 1] != k);
             }
+            if constexpr (COUNT_UNIQUE) count_firsts(i * THREADS + w * 64, first, tcnt);
         }
     }
-    if constexpr (COUNT_UNIQUE) publish_unique(uc);
+    if constexpr (COUNT_UNIQUE) {
+        // A tile that lies wholly inside this bucket's range gets its count from this workgroup alone (a
+        // plain store); the range's first and last tile may be shared with the neighbouring buckets.
+        __syncthreads();
+        const u32 last_tile = (start + (u32)cnt - 1u) >> tile_shift;
+        if ((u32)t <= last_tile - tile0) {
+            const u32 tile = tile0 + (u32)t;
+            const int v = tcnt[t];
+            const bool inside = (tile << tile_shift) >= start && ((tile + 1u) << tile_shift) <= start + (u32)cnt;
+            if (inside) tilesum[tile] = v;
+            else if (v) atomicAdd(&tilesum[tile], v);
+        }
+    }
 }
 
 // Launch of that kernel, one workgroup per bucket, with the narrowest in-LDS key type that holds low_bits
-// bits.  nunique == nullptr: no counting.
+// bits.  tilesum == nullptr: no counting.
 template <typename K, int THREADS, int ITEMS>
 inline void launch_bucket_keys_kernel(int nbuckets, hipStream_t s, K* kin, K* kout, const u32* totals, int low_bits,
-                                      const u32* starts, K sentinel = (K)0, u32* nunique = nullptr) {
+                                      const u32* starts, K sentinel = (K)0, int* tilesum = nullptr, int tile_shift = 0) {
     if constexpr (sizeof(K) == 8) {
         if (low_bits <= 32) {
-            if (nunique)
-                bucket_keys_kernel<K, u32, THREADS, ITEMS, true><<<nbuckets, THREADS, 0, s>>>(kin, kout, totals, starts, low_bits, sentinel, nunique);
+            if (tilesum)
+                bucket_keys_kernel<K, u32, THREADS, ITEMS, true><<<nbuckets, THREADS, 0, s>>>(kin, kout, totals, starts, low_bits, sentinel, tilesum, tile_shift);
             else
-                bucket_keys_kernel<K, u32, THREADS, ITEMS, false><<<nbuckets, THREADS, 0, s>>>(kin, kout, totals, starts, low_bits, sentinel, nunique);
+                bucket_keys_kernel<K, u32, THREADS, ITEMS, false><<<nbuckets, THREADS, 0, s>>>(kin, kout, totals, starts, low_bits, sentinel, tilesum, tile_shift);
             return;
         }
     }
-    if (nunique)
-        bucket_keys_kernel<K, K, THREADS, ITEMS, true><<<nbuckets, THREADS, 0, s>>>(kin, kout, totals, starts, low_bits, sentinel, nunique);
+    if (tilesum)
+        bucket_keys_kernel<K, K, THREADS, ITEMS, true><<<nbuckets, THREADS, 0, s>>>(kin, kout, totals, starts, low_bits, sentinel, tilesum, tile_shift);
     else
-        bucket_keys_kernel<K, K, THREADS, ITEMS, false><<<nbuckets, THREADS, 0, s>>>(kin, kout, totals, starts, low_bits, sentinel, nunique);
+        bucket_keys_kernel<K, K, THREADS, ITEMS, false><<<nbuckets, THREADS, 0, s>>>(kin, kout, totals, starts, low_bits, sentinel, tilesum, tile_shift);
 }
+
+// What a keys-only bucket sort may do for the compaction that follows it (see bucket_keys_kernel):
+// the count pass of "keep the first of every run of equal keys, `sentinel` excepted" with tiles of
+// 2^tile_shift positions; the partition kernel zeroes tilesum[0, tiles).  tilesum == nullptr: nothing.
+template <typename K>
+struct UniqueCount {
+    int* tilesum = nullptr;
+    int tile_shift = 0;
+    int tiles = 0;
+    K sentinel = (K)0;
+};
 
 // Histogram of the top RBITS-bit digit (bits [shift, shift + RBITS)) over the whole input, added
 // to `hist` (which starts at zero); tiles of BLOCK * ITEMS keys.
@@ -1011,9 +1056,12 @@ template <typename K, int RBITS, int ITEMS, class Src>
 __global__ __launch_bounds__(BLOCK) void msd_scatter_kernel(Src kin, K* __restrict__ kout,
                                                             const int* n_ptr, int n_host, int shift,
                                                             const u32* __restrict__ hist, u32* __restrict__ cursor,
-                                                            u32* __restrict__ starts) {
+                                                            u32* __restrict__ starts, int* __restrict__ zero = nullptr,
+                                                            int n_zero = 0) {
     constexpr int R = 1 << RBITS;
     constexpr int PER = R / BLOCK;  // digits per thread in the scan of the ranges' first positions
+    // (an array that the kernel after this one adds to: zeroed here, by all workgroups together)
+    for (int i = blockIdx.x * BLOCK + threadIdx.x; i < n_zero; i += gridDim.x * BLOCK) zero[i] = 0;
     static_assert(R % BLOCK == 0, "whole digits per thread");
     constexpr int TILE = BLOCK * ITEMS;
     __shared__ u32 h[R];  // per digit: this tile's count, then where the tile's keys of that digit go
@@ -1102,7 +1150,7 @@ __global__ __launch_bounds__(BLOCK) void fill_u32_kernel(u32* __restrict__ p, in
 template <typename K, bool HAS_VAL, class Src = ArrayKeys<K>>
 inline int bucket_sort(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_ptr, int n_max, int key_bits,
                        const SortScratch& sc, LaunchTimer* lt = nullptr, int tag = 0, bool counted = false,
-                       u32* msd_hist = nullptr, const Src* src = nullptr) {
+                       u32* msd_hist = nullptr, const Src* src = nullptr, const UniqueCount<K>* uq = nullptr) {
     if (n_max <= 0 || key_bits <= 0) return 0;
     const int msd = bucket_sort_msd_bits(key_bits);
     const int low = key_bits - msd;
@@ -1116,12 +1164,14 @@ inline int bucket_sort(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int*
                 msd_histogram_kernel<K, BUCKET_MSD_BITS, SORT_ITEMS_SMALL><<<tiles, BLOCK, 0, s>>>(k0, n_ptr, n_max, msd_hist, low);
             }
             u32* starts = msd_hist + 2 * MSD_HIST_WORDS;
+            const UniqueCount<K> none{};
+            const UniqueCount<K>& u = uq ? *uq : none;
             if (src && counted)
-                msd_scatter_kernel<K, BUCKET_MSD_BITS, SORT_ITEMS_SMALL, Src><<<tiles, BLOCK, 0, s>>>(*src, k1, n_ptr, n_max, low, msd_hist, cursor, starts);
+                msd_scatter_kernel<K, BUCKET_MSD_BITS, SORT_ITEMS_SMALL, Src><<<tiles, BLOCK, 0, s>>>(*src, k1, n_ptr, n_max, low, msd_hist, cursor, starts, u.tilesum, u.tiles);
             else
-                msd_scatter_kernel<K, BUCKET_MSD_BITS, SORT_ITEMS_SMALL, ArrayKeys<K>><<<tiles, BLOCK, 0, s>>>(ArrayKeys<K>{k0}, k1, n_ptr, n_max, low, msd_hist, cursor, starts);
+                msd_scatter_kernel<K, BUCKET_MSD_BITS, SORT_ITEMS_SMALL, ArrayKeys<K>><<<tiles, BLOCK, 0, s>>>(ArrayKeys<K>{k0}, k1, n_ptr, n_max, low, msd_hist, cursor, starts, u.tilesum, u.tiles);
             const bool timed = lt && lt->begin(s, tag);
-            launch_bucket_keys_kernel<K, BUCKET_KEYS_THREADS_256, BUCKET_KEYS_ITEMS_256>(1 << msd, s, k1, k0, msd_hist, low, starts);
+            launch_bucket_keys_kernel<K, BUCKET_KEYS_THREADS_256, BUCKET_KEYS_ITEMS_256>(1 << msd, s, k1, k0, msd_hist, low, starts, u.sentinel, u.tilesum, u.tile_shift);
             if (timed) lt->end(s);
             if (hipGetLastError() != hipSuccess) return -1;
             return 0;
@@ -1196,7 +1246,7 @@ __global__ __launch_bounds__(BLOCK) void top_digit_histogram_kernel(const K* __r
 template <typename K, bool HAS_VAL, class Src = ArrayKeys<K>>
 inline int bucket_sort_large(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, const int* n_ptr, int n_max, int key_bits,
                              const SortScratch& sc, u32* hist12, LaunchTimer* lt = nullptr, int tag = 0,
-                             bool counted = false, const Src* src = nullptr) {
+                             bool counted = false, const Src* src = nullptr, const UniqueCount<K>* uq = nullptr) {
     constexpr int R = 1 << BUCKET_LARGE_MSD_BITS;
     const int low = key_bits - BUCKET_LARGE_MSD_BITS;
     const int tiles = sort_tiles(n_max, SORT_ITEMS_BIG);
@@ -1208,12 +1258,14 @@ inline int bucket_sort_large(hipStream_t s, K* k0, K* k1, u32* v0, u32* v1, cons
             msd_histogram_kernel<K, BUCKET_LARGE_MSD_BITS, SORT_ITEMS_BIG><<<tiles, BLOCK, 0, s>>>(k0, n_ptr, n_max, hist12, low);
         }
         u32* starts = hist12 + 2 * MSD_HIST_WORDS;
+        const UniqueCount<K> none{};
+        const UniqueCount<K>& u = uq ? *uq : none;
         if (src && counted)
-            msd_scatter_kernel<K, BUCKET_LARGE_MSD_BITS, SORT_ITEMS_BIG, Src><<<tiles, BLOCK, 0, s>>>(*src, k1, n_ptr, n_max, low, hist12, cursor, starts);
+            msd_scatter_kernel<K, BUCKET_LARGE_MSD_BITS, SORT_ITEMS_BIG, Src><<<tiles, BLOCK, 0, s>>>(*src, k1, n_ptr, n_max, low, hist12, cursor, starts, u.tilesum, u.tiles);
         else
-            msd_scatter_kernel<K, BUCKET_LARGE_MSD_BITS, SORT_ITEMS_BIG, ArrayKeys<K>><<<tiles, BLOCK, 0, s>>>(ArrayKeys<K>{k0}, k1, n_ptr, n_max, low, hist12, cursor, starts);
+            msd_scatter_kernel<K, BUCKET_LARGE_MSD_BITS, SORT_ITEMS_BIG, ArrayKeys<K>><<<tiles, BLOCK, 0, s>>>(ArrayKeys<K>{k0}, k1, n_ptr, n_max, low, hist12, cursor, starts, u.tilesum, u.tiles);
         const bool timed = lt && lt->begin(s, tag);
-        launch_bucket_keys_kernel<K, BUCKET_KEYS_THREADS_4096, BUCKET_KEYS_ITEMS_4096>(R, s, k1, k0, hist12, low, starts);
+        launch_bucket_keys_kernel<K, BUCKET_KEYS_THREADS_4096, BUCKET_KEYS_ITEMS_4096>(R, s, k1, k0, hist12, low, starts, u.sentinel, u.tilesum, u.tile_shift);
         if (timed) lt->end(s);
         if (hipGetLastError() != hipSuccess) return -1;
         return 0;
