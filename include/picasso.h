@@ -44,7 +44,9 @@ enum picasso_status {
     PICASSO_ERR_BAD_INDEX = -2,    /* facet index outside [0,N) (batched: outside its own mesh)     */
     PICASSO_ERR_NONFINITE = -3,    /* NaN or Inf vertex coordinate                                  */
     PICASSO_ERR_WORKSPACE = -4,    /* input larger than the context was created for                 */
-    PICASSO_ERR_HIP = -5           /* HIP runtime error (see picasso_last_hip_error)                */
+    PICASSO_ERR_HIP = -5,          /* HIP runtime error (see picasso_last_hip_error)                */
+    PICASSO_ERR_INTERNAL = -6      /* a kernel met sizes that its launch does not take: a defect of
+                                      the library, never of the input; outputs unspecified          */
 };
 
 enum picasso_option {
@@ -102,7 +104,7 @@ enum picasso_option {
                                       synchronises the stream if it has not come by then.  1
                                       (default) = 20,000 us; 0 = synchronise the stream at once;
                                       at most 10,000,000.  The results are the same either way.  */
-    PICASSO_OPT_LAUNCH_AHEAD = 11  /* 1 (default): in a round of at most 2^20 facets in
+    PICASSO_OPT_LAUNCH_AHEAD = 11, /* 1 (default): in a round of at most 2^20 facets in
                                       which the outcome of the selection decides nothing but
                                       counts (no mesh can exceed its budget, or some mesh surely
                                       will and the per-mesh budget step can take it), the kernels
@@ -110,6 +112,12 @@ enum picasso_option {
                                       host has looked; they do nothing if the selection turns out
                                       to need more passes.  0: queued after the look.  Same
                                       results.                                                   */
+    PICASSO_OPT_TRUNC_WIDTH = 12   /* test hook for the per-mesh budget step: 0 (default) = its
+                                      workgroups hold 4, 8, 16 or 32 cost keys per lane (x 1024
+                                      lanes) as the largest mesh needs; 4, 8, 16 or 32 = always
+                                      that many, so that a mesh with more pairs than fit makes
+                                      the kernel report it and the call return
+                                      PICASSO_ERR_INTERNAL instead of a wrong budget.            */
 };
 
 #define PICASSO_STATS_ROUNDS 32
@@ -324,9 +332,7 @@ int picasso_bucket_sort(picasso_ctx* ctx, void* stream, int key_bytes, void* d_k
  * Features are fp32 row-major [rows, C]; all data pointers are device memory
  * owned by the caller.  Unless noted the calls are asynchronous on `stream`,
  * allocate nothing and do not report bad indices (an out-of-range index is read
- * as index 0): picasso_vertex_corner_csr checks a facet array once.
- * C <= 1024 when C is a multiple of 4 and the pointers are 16-byte aligned,
- * else C <= 256 (filter-gradient reductions).
+ * as index 0): picasso_vertex_corner_csr checks a facet array once.  Any C >= 1.
  * ------------------------------------------------------------------------- */
 
 /* Corners of the facet array at every vertex: corner i = 3 f + s is vertex

@@ -10,8 +10,8 @@ from .binding import (  # noqa: F401
     Context, PicassoError, load_library, picasso_stats, picasso_strerror, picasso_workspace_bytes, picasso_device_copy,
     picasso_replace_mapping_static, PICASSO_STATIC_MAX_CLUSTERS,
     PICASSO_OK, PICASSO_WARN_BUDGET_UNMET, PICASSO_ERR_INVALID_ARG, PICASSO_ERR_BAD_INDEX,
-    PICASSO_ERR_NONFINITE, PICASSO_ERR_WORKSPACE, PICASSO_ERR_HIP,
+    PICASSO_ERR_NONFINITE, PICASSO_ERR_WORKSPACE, PICASSO_ERR_HIP, PICASSO_ERR_INTERNAL,
     PICASSO_OPT_MAX_ROUNDS, PICASSO_OPT_STAGE_TIMING, PICASSO_OPT_SUBROUND_BATCH, PICASSO_OPT_KERNEL_TIMING, PICASSO_OPT_OVERLAP, PICASSO_OPT_TRUNC_BLOCK_MAX,
-    PICASSO_OPT_PLACEMENT, PICASSO_OPT_RCOND_MIN_BITS, PICASSO_OPT_ABSORB, PICASSO_OPT_SHUFFLE_SEED, PICASSO_OPT_HOST_POLL, PICASSO_OPT_LAUNCH_AHEAD, PICASSO_PLACE_MEAN, PICASSO_PLACE_INVERSE,
+    PICASSO_OPT_PLACEMENT, PICASSO_OPT_RCOND_MIN_BITS, PICASSO_OPT_ABSORB, PICASSO_OPT_SHUFFLE_SEED, PICASSO_OPT_HOST_POLL, PICASSO_OPT_LAUNCH_AHEAD, PICASSO_OPT_TRUNC_WIDTH, PICASSO_PLACE_MEAN, PICASSO_PLACE_INVERSE,
     PICASSO_POOL_AVG, PICASSO_POOL_MAX, PICASSO_POOL_WEIGHTED, PICASSO_POOL_SUM,
 )

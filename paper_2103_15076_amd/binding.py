@@ -19,6 +19,7 @@ PICASSO_ERR_BAD_INDEX = -2
 PICASSO_ERR_NONFINITE = -3
 PICASSO_ERR_WORKSPACE = -4
 PICASSO_ERR_HIP = -5
+PICASSO_ERR_INTERNAL = -6
 
 PICASSO_OPT_MAX_ROUNDS = 0
 PICASSO_OPT_STAGE_TIMING = 1
@@ -32,6 +33,7 @@ PICASSO_OPT_ABSORB = 8
 PICASSO_OPT_SHUFFLE_SEED = 9
 PICASSO_OPT_HOST_POLL = 10
 PICASSO_OPT_LAUNCH_AHEAD = 11
+PICASSO_OPT_TRUNC_WIDTH = 12
 PICASSO_PLACE_MEAN, PICASSO_PLACE_INVERSE = 0, 1
 
 PICASSO_STATS_ROUNDS = 32

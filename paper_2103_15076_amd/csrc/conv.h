@@ -270,16 +270,17 @@ __global__ __launch_bounds__(BLOCK) void v2f_backward_x_kernel(const float* __re
 // Filter gradients: a sum over all rows (facets) of ROWS values per channel, in
 // two fixed stages.  Stage 1: workgroup g sums the rows [g * chunk, (g + 1) *
 // chunk); lane (r, q) of it takes every R-th row of the chunk for channel pack
-// q, then the R lanes of a pack are summed in LDS in a fixed tree.  Stage 2
+// q (a launch covers up to BLOCK packs), then the R lanes of a pack are summed in LDS in a fixed tree.  Stage 2
 // adds the workgroups' partial sums in ascending order.
 // ---------------------------------------------------------------------------
 template <int ROWS, int VEC, class Term>
 __global__ __launch_bounds__(BLOCK) void reduce_rows_stage1_kernel(Term term, int n_rows, int C, int chunk,
-                                                                   float* __restrict__ partial) {
+                                                                   float* __restrict__ partial, int q0, int Q) {
     extern __shared__ float lds[];  // [BLOCK][ROWS * VEC]
-    const int Q = C / VEC;          // host guarantees Q <= BLOCK
+    // this launch takes the channel packs q0 .. q0 + Q - 1, Q <= BLOCK (the host makes as many launches as
+    // the channels need)
     const int R = BLOCK / Q;
-    const int r = threadIdx.x / Q, q = threadIdx.x % Q;
+    const int r = threadIdx.x / Q, q = q0 + threadIdx.x % Q;
     float acc[ROWS * VEC];
 #pragma unroll
     for (int k = 0; k < ROWS * VEC; ++k) acc[k] = 0.0f;

@@ -24,12 +24,13 @@ namespace {
 
 constexpr int BLOCK = prim::BLOCK;
 constexpr u64 VMIN_NONE = ~0ull;
+constexpr int ERR_BIT_BAD_INDEX = 1, ERR_BIT_NONFINITE = 2, ERR_BIT_INTERNAL = 4;  // State::err
 
 // ---------------------------------------------------------------------------
 // Device-resident bookkeeping
 // ---------------------------------------------------------------------------
 struct State {
-    int err;       // bit0: bad facet index, bit1: non-finite coordinate
+    int err;       // bit0: bad facet index, bit1: non-finite coordinate, bit2: a kernel was launched for sizes it does not take
     int nv[2];     // vertex count, ping-pong by round parity
     int nf[2];     // facet count, ping-pong
     int nh;        // 3 * nf of the current round (half-edge keys to sort)
@@ -749,6 +750,8 @@ struct SelArgs {
     int vbits;
     int* host_img;     // pinned host memory, device view: the tail leaves [State][matched] there
     int publish_ints;  // for the host, which then needs no copy of its own before it looks
+    int* host_check;   // ... and, behind them, the number that the kernel after it will store in the
+    int host_seq;      // sequence word (the host compares the two before it trusts what it reads)
     TieBreak tb;       // order among edges of equal cost
     int cur;           // which of the ping-pong vertex / facet counts belong to this round
     int* tile_live;    // not null (last grid-wide sub-round before the tail, one edge per lane and no
@@ -984,6 +987,19 @@ __device__ __forceinline__ int tail_slot(int* vkey, int v) {
     }
 }
 
+// A word for the host: stored at system scope (not left in a cache of the device), so that it is in
+// host memory when the kernel has ended.
+__device__ __forceinline__ void host_store(int* p, int v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+// By every thread of the tail, after its last store for the host: once all of them are issued, the
+// copy of the sequence number follows them.
+__device__ __forceinline__ void tail_mark_published(const SelArgs& A, int tid) {
+    __syncthreads();
+    if (tid == 0) host_store(A.host_check, A.host_seq);
+}
+
 // The round's counters and pair counts, written straight into the host's pinned memory (read at
 // the L2, where this kernel's own stores to them already are).
 __device__ __forceinline__ void tail_publish(const SelArgs& A, int tid) {
@@ -991,7 +1007,7 @@ __device__ __forceinline__ void tail_publish(const SelArgs& A, int tid) {
     constexpr int GO0 = (int)(offsetof(State, go) / sizeof(int)), STATE_INTS = (int)(sizeof(State) / sizeof(int));
     for (int i = tid; i < A.publish_ints; i += TAIL_THREADS)
         if (i < GO0 || i >= STATE_INTS)  // (the guard fields are for the device only; the tail is writing them)
-            A.host_img[i] = __hip_atomic_load(&hdr[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            host_store(&A.host_img[i], __hip_atomic_load(&hdr[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
 }
 
 // What the kernels queued behind the tail go by (see State).
@@ -1009,6 +1025,7 @@ __global__ __launch_bounds__(TAIL_THREADS) void select_tail_kernel(SelArgs A) {
     if (n > TAIL_MAX) {        // too many: the host runs more grid-wide sub-rounds
         if (tid == 0) tail_set_guard(A, false);
         tail_publish(A, tid);
+        tail_mark_published(A, tid);
         return;
     }
     const u64 lt = prim::lanemask_lt();
@@ -1120,7 +1137,7 @@ __global__ __launch_bounds__(TAIL_THREADS) void select_tail_kernel(SelArgs A) {
             const int b = idx / MATCH_SLOTS;
             if (lds_pairs) sum += L.pairs[b];
             A.mt.matched[b] = sum;
-            if (lds_pairs && STATE_INTS + b < A.publish_ints) A.host_img[STATE_INTS + b] = sum;
+            if (lds_pairs && STATE_INTS + b < A.publish_ints) host_store(&A.host_img[STATE_INTS + b], sum);
         }
     }
     if (tid == 0) {
@@ -1131,12 +1148,13 @@ __global__ __launch_bounds__(TAIL_THREADS) void select_tail_kernel(SelArgs A) {
         // the host's copy of the counters: everything but live[0] was written by earlier kernels
         constexpr int LIVE0 = (int)(offsetof(State, live) / sizeof(int)), GO0 = (int)(offsetof(State, go) / sizeof(int));
         const int* hdr = reinterpret_cast<const int*>(A.st);
-        if (tid < GO0 && tid < A.publish_ints) A.host_img[tid] = (tid == LIVE0) ? 0 : hdr[tid];
+        if (tid < GO0 && tid < A.publish_ints) host_store(&A.host_img[tid], (tid == LIVE0) ? 0 : hdr[tid]);
     } else {
         __threadfence();
         __syncthreads();
         tail_publish(A, tid);
     }
+    tail_mark_published(A, tid);
 }
 
 // The selection tail does not tell the host itself (a system-scope fence inside it, with the pairs it
@@ -1259,7 +1277,7 @@ __global__ __launch_bounds__(TRUNC_THREADS) void trunc_block_kernel(u32* __restr
                                                                     const u32* __restrict__ tval, TieBreak tb,
                                                                     const int* __restrict__ matched,
                                                                     const int* __restrict__ nrem,
-                                                                    const int* __restrict__ guard) {
+                                                                    const int* __restrict__ guard, State* st) {
     if (guard && *guard == 0) return;  // queued ahead of the host's look, and the selection was not finished
     constexpr int NW = TRUNC_THREADS / 64;
     __shared__ u32 wsum[NW];
@@ -1279,8 +1297,11 @@ __global__ __launch_bounds__(TRUNC_THREADS) void trunc_block_kernel(u32* __restr
     prim::wide_block_exclusive_scan<NW>(before, wsum, s0);
     tcost += s0;
     tval += s0;
-    if (n > R * TRUNC_THREADS) {  // not for this kernel (the host does not launch it so): release nothing
+    if (n > R * TRUNC_THREADS) {
+        // More pairs than this instance holds: the host never launches it so.  Nothing is released, and
+        // the call is made to fail (ERR_BIT_INTERNAL) instead of returning a budget that was not applied.
         for (int i = tid; i < n; i += TRUNC_THREADS) tcost[i] = 0u;
+        if (tid == 0) atomicOr(&st->err, ERR_BIT_INTERNAL);
         return;
     }
 

@@ -14,7 +14,6 @@
 #include <atomic>
 #include <chrono>
 #include <new>
-#include <vector>
 
 #include "../../include/picasso.h"
 #include "primitives.h"
@@ -40,6 +39,9 @@ inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 // ---------------------------------------------------------------------------
 // Context
 // ---------------------------------------------------------------------------
+constexpr int NF_ROUND_CAP = 64;  // rounds whose facet counts a call notes for the kernel-timing totals
+struct StageRec { int round, stage, e0, e1; };
+
 struct picasso_ctx {
     int device = 0;
     int64_t max_verts = 0, max_facets = 0;
@@ -106,6 +108,7 @@ struct picasso_ctx {
     int host_seq = 0;      // the last sequence number handed out
     int64_t opt_poll_us = 20000;  // for how long the host watches that word before it waits for the stream instead (0: not at all)
     int opt_ahead = 1;     // a round's contraction and facet kernels are queued before the host has looked
+    int opt_trunc_width = 0;  // test hook: keys per lane of the per-mesh budget search (0: as the sizes need)
     hipEvent_t ev[2 * PICASSO_STATS_ROUNDS * PICASSO_ST_COUNT + 4];
     int n_ev = 0;
     hipEvent_t ev_total[2];
@@ -127,11 +130,18 @@ struct picasso_ctx {
     prim::LaunchTimer kt;
     int64_t kt_launches = 0;
     double kt_ms = 0.0, kt_bytes = 0.0;
+    // host mirrors of the per-mesh state of a decimate call (6 x max_meshes ints, allocated with the
+    // context: the calls themselves allocate nothing, on the host either)
+    int* h_mesh = nullptr;
+    int nf_round[NF_ROUND_CAP];  // facets entering each round of the current call
+    int n_rounds_noted = 0;
+    StageRec st_recs[PICASSO_STATS_ROUNDS * PICASSO_ST_COUNT + 2];
 };
 
 namespace {
 
 constexpr int HDR_STATE_INTS = (int)(sizeof(State) / sizeof(int));
+constexpr int SEQ_CHECK_WORD = 16;  // within the sequence word's 32-int area: the selection tail's copy of the number (a cache line further)
 
 struct Carver {
     size_t off = 0;
@@ -235,25 +245,26 @@ struct StageTimer {
     picasso_ctx* c;
     hipStream_t s;
     bool on;
-    struct Rec { int round, stage, e0, e1; };
-    std::vector<Rec> recs;
+    int n_recs = 0;  // records in c->st_recs
     int open = -1;
     void begin(int round, int stage) {
-        if (!on || c->n_ev + 2 > (int)(sizeof(c->ev) / sizeof(c->ev[0]))) return;
-        Rec r{round, stage, c->n_ev, c->n_ev + 1};
+        constexpr int cap = (int)(sizeof(c->st_recs) / sizeof(c->st_recs[0]));
+        if (!on || n_recs >= cap || c->n_ev + 2 > (int)(sizeof(c->ev) / sizeof(c->ev[0]))) return;
+        const StageRec r{round, stage, c->n_ev, c->n_ev + 1};
         c->n_ev += 2;
         (void)hipEventRecord(c->ev[r.e0], s);
-        recs.push_back(r);
-        open = (int)recs.size() - 1;
+        c->st_recs[n_recs] = r;
+        open = n_recs++;
     }
     void end() {
         if (!on || open < 0) return;
-        (void)hipEventRecord(c->ev[recs[open].e1], s);
+        (void)hipEventRecord(c->ev[c->st_recs[open].e1], s);
         open = -1;
     }
     void collect(picasso_stats* stats) {
         if (!on || !stats) return;
-        for (const Rec& r : recs) {
+        for (int i = 0; i < n_recs; ++i) {
+            const StageRec& r = c->st_recs[i];
             float ms = 0.f;
             if (hipEventElapsedTime(&ms, c->ev[r.e0], c->ev[r.e1]) == hipSuccess && r.round < PICASSO_STATS_ROUNDS)
                 stats->ms_stage[r.round][r.stage] += ms;
@@ -473,8 +484,9 @@ int read_header(picasso_ctx* c, hipStream_t s) {
 }
 
 int status_from_err_bits(int bits) {
-    if (bits & 1) return PICASSO_ERR_BAD_INDEX;
-    if (bits & 2) return PICASSO_ERR_NONFINITE;
+    if (bits & ERR_BIT_INTERNAL) return PICASSO_ERR_INTERNAL;
+    if (bits & ERR_BIT_BAD_INDEX) return PICASSO_ERR_BAD_INDEX;
+    if (bits & ERR_BIT_NONFINITE) return PICASSO_ERR_NONFINITE;
     return PICASSO_OK;
 }
 
@@ -501,13 +513,17 @@ int budget_step(picasso_ctx* c, hipStream_t s, Over over, int B, int ne, int vbi
 #define PICASSO_TRUNC_BLOCK(R)                                                                                       \
     do {                                                                                                             \
         if (tb.on)                                                                                                   \
-            trunc_block_kernel<R, true><<<B, TRUNC_THREADS, 0, s>>>(tcost, c->val32[0], tb, counts, budgets, guard);  \
+            trunc_block_kernel<R, true><<<B, TRUNC_THREADS, 0, s>>>(tcost, c->val32[0], tb, counts, budgets, guard,   \
+                                                                    c->st);                                          \
         else                                                                                                         \
-            trunc_block_kernel<R, false><<<B, TRUNC_THREADS, 0, s>>>(tcost, c->val32[0], tb, counts, budgets, guard); \
+            trunc_block_kernel<R, false><<<B, TRUNC_THREADS, 0, s>>>(tcost, c->val32[0], tb, counts, budgets, guard,  \
+                                                                     c->st);                                         \
     } while (0)
-        if (seg_max <= 4 * TRUNC_THREADS) PICASSO_TRUNC_BLOCK(4);
-        else if (seg_max <= 8 * TRUNC_THREADS) PICASSO_TRUNC_BLOCK(8);
-        else if (seg_max <= 16 * TRUNC_THREADS) PICASSO_TRUNC_BLOCK(16);
+        // keys per lane: what the largest mesh needs (or what the test hook says)
+        const int width = c->opt_trunc_width ? c->opt_trunc_width : (seg_max + TRUNC_THREADS - 1) / TRUNC_THREADS;
+        if (width <= 4) PICASSO_TRUNC_BLOCK(4);
+        else if (width <= 8) PICASSO_TRUNC_BLOCK(8);
+        else if (width <= 16) PICASSO_TRUNC_BLOCK(16);
         else PICASSO_TRUNC_BLOCK(32);
 #undef PICASSO_TRUNC_BLOCK
         trunc_release_kernel<ABSORB><<<grid_for(n_over), BLOCK, 0, s>>>(tcost, c->val32[0], c->st, c->ekey, vbits,
@@ -544,8 +560,7 @@ int budget_step(picasso_ctx* c, hipStream_t s, Over over, int B, int ne, int vbi
 // join per mesh; *akeys the sorted (representative, vertex) keys, st->absorb_n of them.  Waits for
 // the stream once (the per-mesh candidate counts decide whether the budget step is needed).
 int run_absorb(picasso_ctx* c, hipStream_t s, int B, int cur, int vbits, int ne, int nv_total, const MeshTab& mt,
-               const TieBreak& tb, const std::vector<int>& nrem, const std::vector<int>& h_matched, std::vector<int>& h_joined,
-               const u64** akeys) {
+               const TieBreak& tb, const int* nrem, const int* h_matched, int* h_joined, const u64** akeys) {
     absorb_begin_kernel<<<grid_for(std::max(nv_total, B), 4096), BLOCK, 0, s>>>(c->abid, c->arep, c->acnt, c->st, cur, B, c->nrem,
                                                                               c->matched, c->arem, c->acand);
     absorb_bid_kernel<<<grid_for(std::max(ne, 1), 8192), BLOCK, 0, s>>>(c->ekey, c->ecost, c->st, vbits, c->mate, mt,
@@ -616,12 +631,21 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
     c->kt.used = 0;
     c->kt.nrec = 0;
     c->kt_this_call = c->opt_kernel_timing > 0 && (c->kt_calls++ % c->opt_kernel_timing) == 0;
-    std::vector<int> nf_round;
-    StageTimer tm{c, s, c->opt_stage_timing != 0 && stats != nullptr, {}, -1};
+    c->n_rounds_noted = 0;
+    StageTimer tm{c, s, c->opt_stage_timing != 0 && stats != nullptr};
     if (stats) HIP_TRY(c, hipEventRecord(c->ev_total[0], s));  // (an event costs queue time: only when asked for)
 
     // host mirror of the per-mesh vertex counts
-    std::vector<int> nvb(nv_in, nv_in + B), stuck(B, 0), act(B, 0), nrem(B, 0);
+    int* const nvb = c->h_mesh;
+    int* const stuck = nvb + c->max_meshes;
+    int* const act = stuck + c->max_meshes;
+    int* const nrem = act + c->max_meshes;
+    int* const h_matched = nrem + c->max_meshes;
+    int* const h_joined = h_matched + c->max_meshes;
+    for (int b = 0; b < B; ++b) {
+        nvb[b] = nv_in[b];
+        stuck[b] = act[b] = nrem[b] = h_matched[b] = h_joined[b] = 0;
+    }
     auto any_active = [&]() {
         bool any = false;
         for (int b = 0; b < B; ++b) {
@@ -657,7 +681,6 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
     tm.end();
 
     State* hst = reinterpret_cast<State*>(c->h_pin);  // read-back area
-    std::vector<int> h_matched(B, 0), h_joined(B, 0);
     const TieBreak tb{c->opt_shuffle_seed != 0 ? 1u : 0u, (u32)c->opt_shuffle_seed, (u32)(c->opt_shuffle_seed >> 32)};
 
     int cur = 0;        // ping-pong index of vrec / facets / voff / State counts
@@ -781,6 +804,7 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         sa.vbits = vbits;
         sa.host_img = c->h_pin_dev;
         sa.publish_ints = HDR_STATE_INTS + B;
+        sa.host_check = c->h_pin_dev + c->h_seq_off + SEQ_CHECK_WORD;
         sa.tb = tb;
         int sel_k = 0;
         // Grid-wide sub-rounds while many edges are live (the live count falls about 3x per
@@ -823,10 +847,11 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
             LiveOut lo{c->list};
             if (counts_live) prim::compact_scatter(s, lp, lo, &c->st->ne, ne_bound, c->tilesum, &c->st->live[0]);
             else prim::compact(s, lp, lp, lo, &c->st->ne, ne_bound, c->tilesum, &c->st->live[0]);
-            select_tail_kernel<<<1, TAIL_THREADS, 0, s>>>(sa);
-            launched += wide + 3;
             // the kernel behind the tail tells the host that the tail's results are in the read-back area
             const HostSignal tail_done = next_signal(c);
+            sa.host_seq = tail_done.seq;
+            select_tail_kernel<<<1, TAIL_THREADS, 0, s>>>(sa);
+            launched += wide + 3;
             const HostSignal nothing{nullptr, 0};
             if (ahead_ok) {
                 if (ahead_budget) {
@@ -841,6 +866,16 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
                 signal_kernel<<<1, 64, 0, s>>>(tail_done);
             }
             HIP_TRY(c, wait_for_signal(c, s, tail_done));  // [State][matched] are in the read-back area
+            // The tail stored its counters at system scope and, after them, its own copy of the number
+            // that the kernel behind it has just stored; should that copy not be there yet, what the
+            // host would read is not to be trusted: wait for the stream, after which everything is.
+            if (__atomic_load_n(c->h_pin + c->h_seq_off + SEQ_CHECK_WORD, __ATOMIC_ACQUIRE) != tail_done.seq) {
+                HIP_TRY(c, hipStreamSynchronize(s));
+                if (c->h_pin[c->h_seq_off + SEQ_CHECK_WORD] != tail_done.seq) {
+                    snprintf(c->hip_err, sizeof(c->hip_err), "the selection's results did not reach host memory");
+                    return PICASSO_ERR_HIP;
+                }
+            }
             if (!validated) {
                 const int st_err = status_from_err_bits(hst->err);
                 if (st_err != PICASSO_OK) {  // (the flags go back to zero for the next call, see HeaderInit)
@@ -848,6 +883,10 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
                     return st_err;
                 }
                 validated = true;
+            }
+            if (hst->err & ERR_BIT_INTERNAL) {  // a kernel of the round before has refused its sizes
+                prim::fill_u32_kernel<<<1, BLOCK, 0, s>>>(reinterpret_cast<u32*>(&c->st->err), 1, 0u);
+                return PICASSO_ERR_INTERNAL;
             }
             sel_k = hst->sel_k;
             const int live = hst->live[0];
@@ -859,7 +898,7 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         }
         for (int b = 0; b < B; ++b) h_matched[b] = c->h_pin[HDR_STATE_INTS + b];
         nf_bound = std::min(nf_bound, hst->nf[cur]);
-        nf_round.push_back(hst->nf[cur]);
+        if (c->n_rounds_noted < NF_ROUND_CAP) c->nf_round[c->n_rounds_noted++] = hst->nf[cur];
         ne_prev = hst->ne;
         nv_prev = nv_total;
         if (stats && round < PICASSO_STATS_ROUNDS) {
@@ -892,7 +931,7 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         // ---- Alg. 2 line 11 (option): un-paired vertices join a neighbouring pair's cluster while budget is left
         int n_joined = 0;
         const u64* akeys = nullptr;
-        std::fill(h_joined.begin(), h_joined.end(), 0);
+        for (int b = 0; b < B; ++b) h_joined[b] = 0;
         bool budget_left = false;
         for (int b = 0; b < B; ++b) budget_left |= (h_matched[b] > 0 && nrem[b] > h_matched[b]);
         if (c->opt_absorb && budget_left) {
@@ -944,6 +983,7 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
     if (stats) HIP_TRY(c, hipEventRecord(c->ev_total[1], s));
     rc = read_header(c, s);
     if (rc != PICASSO_OK) return rc;
+    if (hst->err & ERR_BIT_INTERNAL) return PICASSO_ERR_INTERNAL;  // (the publishing kernel has cleared the flag)
     // the events of the measurement options are read below; all were recorded before the last kernel,
     // so waiting for the last of them returns at once and leaves every one of them readable
     if (stats) HIP_TRY(c, hipEventSynchronize(c->ev_total[1]));
@@ -955,10 +995,10 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
     for (int i = 0; i < c->kt.nrec; ++i) {
         const prim::LaunchTimer::Rec& r = c->kt.recs[i];
         float ms = 0.f;
-        if (r.tag < (int)nf_round.size() && hipEventElapsedTime(&ms, c->kt_pool[r.e0], c->kt_pool[r.e1]) == hipSuccess) {
+        if (r.tag < c->n_rounds_noted && hipEventElapsedTime(&ms, c->kt_pool[r.e0], c->kt_pool[r.e1]) == hipSuccess) {
             c->kt_launches += 1;
             c->kt_ms += ms;
-            c->kt_bytes += 16.0 * 3.0 * (double)nf_round[r.tag];
+            c->kt_bytes += 16.0 * 3.0 * (double)c->nf_round[r.tag];
         }
     }
 
@@ -999,21 +1039,23 @@ inline int conv_vec(int C, std::initializer_list<const void*> ptrs) {
 template <int ROWS, class Term>
 int reduce_filter_rows(picasso_ctx* c, hipStream_t s, Term term, int n_rows, int C, bool vec4, int rows_used,
                        float* d_out) {
-    const int Q = vec4 ? C / 4 : C;
-    if (Q > pool::BLOCK) return PICASSO_ERR_INVALID_ARG;
+    const int Q = vec4 ? C / 4 : C;  // channel packs; a stage-1 launch takes up to pool::BLOCK of them
     const size_t cap = (size_t)3 * (size_t)c->max_facets * sizeof(u64) / sizeof(float);  // floats in key64[0]
     const size_t per_group = (size_t)ROWS * C;
     if (per_group > cap) return PICASSO_ERR_WORKSPACE;
-    const int R = pool::BLOCK / Q;
+    const int R = pool::BLOCK / std::min(Q, pool::BLOCK);
     long long groups = std::min<long long>(1024, ((long long)n_rows + 4ll * R - 1) / (4ll * R));
     groups = std::max<long long>(1, std::min<long long>(groups, (long long)(cap / per_group)));
     const int chunk = (int)(((long long)n_rows + groups - 1) / groups);
     float* partial = reinterpret_cast<float*>(c->key64[0]);
     const size_t lds = (size_t)pool::BLOCK * ROWS * (vec4 ? 4 : 1) * sizeof(float);
-    if (vec4)
-        conv::reduce_rows_stage1_kernel<ROWS, 4, Term><<<(int)groups, pool::BLOCK, lds, s>>>(term, n_rows, C, chunk, partial);
-    else
-        conv::reduce_rows_stage1_kernel<ROWS, 1, Term><<<(int)groups, pool::BLOCK, lds, s>>>(term, n_rows, C, chunk, partial);
+    for (int q0 = 0; q0 < Q; q0 += pool::BLOCK) {
+        const int qn = std::min(pool::BLOCK, Q - q0);
+        if (vec4)
+            conv::reduce_rows_stage1_kernel<ROWS, 4, Term><<<(int)groups, pool::BLOCK, lds, s>>>(term, n_rows, C, chunk, partial, q0, qn);
+        else
+            conv::reduce_rows_stage1_kernel<ROWS, 1, Term><<<(int)groups, pool::BLOCK, lds, s>>>(term, n_rows, C, chunk, partial, q0, qn);
+    }
     conv::reduce_rows_stage2_kernel<<<pool::grid_for((long long)rows_used * C * 64), pool::BLOCK, 0, s>>>(
         partial, (int)groups, ROWS, rows_used, C, d_out);
     return PICASSO_OK;
@@ -1056,11 +1098,19 @@ int picasso_create(picasso_ctx** out, int device, int64_t max_verts, int64_t max
     if (hipMalloc((void**)&c->ws, c->ws_bytes) != hipSuccess) { delete c; return PICASSO_ERR_HIP; }
     carve(c, c->ws, max_verts, max_facets, max_meshes);
     c->cap_b = max_meshes;
+    c->h_mesh = new (std::nothrow) int[6 * (size_t)max_meshes];
+    if (!c->h_mesh) {
+        (void)hipFree(c->ws);
+        delete c;
+        return PICASSO_ERR_HIP;
+    }
     c->h_up_off = (size_t)HDR_STATE_INTS + 2 * (size_t)max_meshes + 16;
     c->h_seq_off = (c->h_up_off + HDR_STATE_INTS + 8 * (size_t)max_meshes + 16 + 31) / 32 * 32;
     c->h_pin_ints = c->h_seq_off + 32;
-    if (hipHostMalloc((void**)&c->h_pin, c->h_pin_ints * sizeof(int), hipHostMallocDefault) != hipSuccess) {
+    // (mapped into the device's address space and coherent with it: kernels store there what the host reads while they run)
+    if (hipHostMalloc((void**)&c->h_pin, c->h_pin_ints * sizeof(int), hipHostMallocMapped | hipHostMallocCoherent) != hipSuccess) {
         (void)hipFree(c->ws);
+        delete[] c->h_mesh;
         delete c;
         return PICASSO_ERR_HIP;
     }
@@ -1071,12 +1121,14 @@ int picasso_create(picasso_ctx** out, int device, int64_t max_verts, int64_t max
         hipMemset(c->hdr, 0, sizeof(int) * (HDR_STATE_INTS + 8 * (size_t)max_meshes + 3)) != hipSuccess) {
         (void)hipHostFree(c->h_pin);
         (void)hipFree(c->ws);
+        delete[] c->h_mesh;
         delete c;
         return PICASSO_ERR_HIP;
     }
     if (hipHostGetDevicePointer((void**)&c->h_pin_dev, c->h_pin, 0) != hipSuccess) {
         (void)hipHostFree(c->h_pin);
         (void)hipFree(c->ws);
+        delete[] c->h_mesh;
         delete c;
         return PICASSO_ERR_HIP;
     }
@@ -1106,6 +1158,7 @@ void picasso_destroy(picasso_ctx* c) {
     if (c->ev_join) (void)hipEventDestroy(c->ev_join);
     if (c->h_pin) (void)hipHostFree(c->h_pin);
     if (c->ws) (void)hipFree(c->ws);
+    delete[] c->h_mesh;
     delete c;
 }
 
@@ -1134,6 +1187,10 @@ int picasso_set_option(picasso_ctx* c, int option, int64_t value) {
         case PICASSO_OPT_LAUNCH_AHEAD:
             if (value != 0 && value != 1) return PICASSO_ERR_INVALID_ARG;
             c->opt_ahead = (int)value;
+            return PICASSO_OK;
+        case PICASSO_OPT_TRUNC_WIDTH:
+            if (value != 0 && value != 4 && value != 8 && value != 16 && value != 32) return PICASSO_ERR_INVALID_ARG;
+            c->opt_trunc_width = (int)value;
             return PICASSO_OK;
         case PICASSO_OPT_ABSORB:
             if (value != 0 && value != 1) return PICASSO_ERR_INVALID_ARG;
@@ -1169,6 +1226,7 @@ const char* picasso_strerror(int status) {
         case PICASSO_ERR_NONFINITE: return "non-finite vertex coordinate";
         case PICASSO_ERR_WORKSPACE: return "input exceeds the capacity the context was created with";
         case PICASSO_ERR_HIP: return "HIP runtime error";
+        case PICASSO_ERR_INTERNAL: return "internal error: a kernel met sizes that its launch does not take";
         default: return "unknown status";
     }
 }

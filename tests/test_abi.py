@@ -37,7 +37,7 @@ def test_every_declared_symbol_is_exported(lib):
 def test_status_strings(lib):
     import paper_2103_15076_amd as pk
     seen = set()
-    for st in (0, 1, -1, -2, -3, -4, -5):
+    for st in (0, 1, -1, -2, -3, -4, -5, -6):
         s = pk.picasso_strerror(st)
         assert s and s not in seen
         seen.add(s)

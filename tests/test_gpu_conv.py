@@ -277,3 +277,28 @@ def test_facet2facet_on_interpolated_textures_equals_vertex2facet(pk, ctx, oracl
     b = ctx.picasso_v2f_forward(dev(x), dev(F), dev(level), dev(w)).cpu().numpy()
     scale = oracle.v2f_forward(np.abs(x), F, level, np.abs(w))
     assert np.all(np.abs(a - b) <= 64 * EPS * scale + 1e-30)
+
+
+@pytest.mark.parametrize("C", [300, 1028, 2052])
+def test_filter_gradients_with_many_channels(pk, ctx, oracle, C):
+    """Channel counts beyond what one launch of the filter-gradient reduction covers (256 channel packs: 300
+    channels one at a time, 1,028 and 2,052 four at a time): forward and backward accept the same C."""
+    V, F = meshgen.noisy_grid(23, 17, seed=5, noise=0.02)
+    N, nF, T = V.shape[0], F.shape[0], 3
+    rng = np.random.default_rng(C)
+    x = rng.normal(size=(N, C)).astype(np.float32)
+    w3 = rng.normal(size=(3, C)).astype(np.float32)
+    wt = rng.normal(size=(T, C)).astype(np.float32)
+    gy = rng.normal(size=(nF, C)).astype(np.float32)
+    pi = softmax(rng.normal(size=(nF, T)), axis=1).astype(np.float32)
+    lev = np.ones(nF, np.int32)
+    print(f"wide filter gradients C={C}", flush=True)
+    off, cor = ctx.picasso_vertex_corner_csr(dev(F), N)
+    _, gw = ctx.picasso_v2f_backward(dev(gy), dev(x), dev(F), None, dev(w3), off, cor)
+    _, gw_r = oracle.v2f_backward(gy, x, F, lev, w3)
+    _, gw_a = oracle.v2f_backward(np.abs(gy), np.abs(x), F, lev, np.abs(w3))
+    _close(gw, gw_r, _gw_terms(nF, 4), gw_a, "gw (v2f)")
+    _, gw2, _ = ctx.picasso_f2v_backward(dev(x), dev(gy), dev(pi), dev(wt), dev(F), off, want_gpi=False)
+    _, gw2_r, _ = oracle.f2v_backward(x, gy, pi, wt, F)
+    _, gw2_a, _ = oracle.f2v_backward(np.abs(x), np.abs(gy), pi, np.abs(wt), F)
+    _close(gw2, gw2_r, _gw_terms(nF, 6), gw2_a, "gw (f2v)")

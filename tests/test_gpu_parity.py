@@ -795,3 +795,27 @@ def test_hand_worked_fixtures_on_the_gpu(pk, ctx, fixture):
         assert vo.cpu().numpy().tolist() == case["verts_out"]
         assert fo.cpu().numpy().reshape(-1, 3).tolist() == case["facets_out"]
         assert cid.cpu().numpy().tolist() == case["cluster_id"]
+
+
+def test_budget_search_refuses_sizes_it_was_not_launched_for(pk, ctx, oracle):
+    """The per-mesh budget step holds 4, 8, 16 or 32 cost keys per lane of a 1024-lane workgroup.  Forced
+    (test hook) to 4 on a mesh that forms more than 4096 pairs, the kernel must make the call fail with
+    PICASSO_ERR_INTERNAL rather than return with the budget not applied; the context stays usable."""
+    V, F = meshgen.noisy_grid(130, 120, seed=17)          # 15,600 vertices: about 7,000 pairs per round
+    target = int(V.shape[0] * 0.62)                       # the budget binds in the first round
+    ctx.set_option(pk.PICASSO_OPT_TRUNC_WIDTH, 4)
+    try:
+        print("budget search, width forced to 4", flush=True)
+        with pytest.raises(pk.PicassoError) as ei:
+            ctx.picasso_decimate(dev(V), dev(F), target)
+        assert ei.value.status == pk.PICASSO_ERR_INTERNAL
+        # a mesh that fits the forced width is unaffected
+        Vs, Fs = meshgen.noisy_grid(40, 40, seed=3)
+        st, vo, fo, cid = ctx.picasso_decimate(dev(Vs), dev(Fs), 1000)
+        assert_same_result(st, vo, fo, cid, oracle.decimate(Vs, Fs, 1000))
+    finally:
+        ctx.set_option(pk.PICASSO_OPT_TRUNC_WIDTH, 0)
+    st, vo, fo, cid = ctx.picasso_decimate(dev(V), dev(F), target)
+    assert_same_result(st, vo, fo, cid, oracle.decimate(V, F, target))
+    with pytest.raises(pk.PicassoError):
+        ctx.set_option(pk.PICASSO_OPT_TRUNC_WIDTH, 5)
