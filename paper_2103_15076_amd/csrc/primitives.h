@@ -706,8 +706,10 @@ __global__ __launch_bounds__(BUCKET_THREADS) void bucket_sort_kernel(K* __restri
 //      number of such keys to tilesum[tile] (zero on entry), which is what tile_count_kernel would
 //      leave there.
 // A bucket with a group of more than 64 keys (a vertex of very high degree) is sorted as a whole by
-// a bitonic network over the LDS array; a bucket beyond the LDS capacity takes the slow
-// global-memory route of bucket_sort_oversize.  Workgroups are small (256 lanes for the 4096-bucket
+// a bitonic network over the LDS array.  A bucket beyond the LDS capacity (uneven vertex numbering:
+// up to 16 times the capacity) is sorted in parts, runs of whole groups that fit, each read out of the
+// bucket by the workgroup; if it also has a group of more than 64 keys, or is larger still, it
+// takes the slow global-memory route of bucket_sort_oversize.  Workgroups are small (256 lanes for the 4096-bucket
 // sorts) so that eight of them share a compute unit and cover each other's barriers.
 // ---------------------------------------------------------------------------
 #define PRIM_CE(a, b)                       \
@@ -814,7 +816,119 @@ __global__ __launch_bounds__(THREADS) void bucket_keys_kernel(K* __restrict__ ki
         }
     };
 
-    if (cnt > CAP) {  // beyond the LDS array: pass by pass through global memory
+    const int gbits = low_bits < BUCKET_GROUP_BITS ? (low_bits > 0 ? low_bits : 0) : BUCKET_GROUP_BITS;
+    const int rest = low_bits - gbits;
+    const u32 R = 1u << gbits, dmask = R - 1;
+    K upper = 0;  // what the keys of this bucket share above their low_bits bits
+    if constexpr (sizeof(LK) < sizeof(K)) upper = (K)(u32)bkt << low_bits;
+
+    // The groups g0 .. g1 - 1, whose keys lie at [gstart[g] - gstart[g0], ...) of the LDS array, each sorted on
+    // the whole key: one lane per group of up to 16 keys (a sorting network), then a wave per longer group.
+    // By the whole workgroup; no group may exceed 64 keys; uses gcnt (as the list of long groups) and nlong.
+    auto sort_groups = [&](int g0, int g1) {
+        const int lds0 = (int)gstart[g0];
+        if (t == 0) nlong = 0;
+        __syncthreads();
+        for (int gi = g0 + t; gi < g1; gi += THREADS) {
+            const int gs = (int)gstart[gi] - lds0;
+            const int g = (int)gstart[gi + 1] - (int)gstart[gi];
+            if (g > 16) {  // listed for the waves (the counters are no longer needed: the list goes there)
+                gcnt[atomicAdd(&nlong, 1u)] = (u32)gi;
+            } else if (g > 12) {
+                group_sort_lds<LK, 16>(skey, gs, g);
+            } else if (g > 8) {
+                group_sort_lds<LK, 12>(skey, gs, g);
+            } else if (g > 6) {
+                group_sort_lds<LK, 8>(skey, gs, g);
+            } else if (g > 4) {
+                group_sort_lds<LK, 6>(skey, gs, g);
+            } else if (g > 1) {
+                group_sort_lds<LK, 4>(skey, gs, g);
+            }
+        }
+        __syncthreads();
+        // groups of 17 to 64 keys: a wave takes a group, one lane per key; a key's place is the number of
+        // keys of the group that go before it (every lane reads the same address, one read after the
+        // other with nothing waiting in between, where an insertion sort by one lane would wait for
+        // LDS at every step)
+        const int n_long = (int)nlong;
+        if (n_long > 0) {
+            for (int li = w; li < n_long; li += NW) {
+                const int gi = (int)gcnt[li];
+                const int gs = (int)gstart[gi] - lds0;
+                const int g = (int)gstart[gi + 1] - (int)gstart[gi];
+                const LK k = lane < g ? skey[gs + lane] : (LK)0;
+                int r = 0;
+                for (int i = 0; i < g; ++i) {
+                    const LK o = skey[gs + i];
+                    r += (o < k || (o == k && i < lane)) ? 1 : 0;
+                }
+                __builtin_amdgcn_wave_barrier();  // (a wave's LDS operations complete in order)
+                if (lane < g) skey[gs + r] = k;
+            }
+            __syncthreads();
+        }
+    };
+
+    if (cnt > CAP && low_bits > 0) {
+        // More keys than the LDS array holds.  If no group is long, the bucket is sorted in parts: runs of
+        // whole groups of at most CAP keys each, every part fetched from the bucket (which is read once per
+        // part, and once more for the groups' sizes) and sorted like a bucket that fits.
+        for (int i = t; i < (int)R; i += THREADS) gcnt[i] = 0;
+        __syncthreads();
+        for (int i = t; i < cnt; i += THREADS) atomicAdd(&gcnt[digit_of<LK>((LK)kin[i], rest, dmask)], 1u);
+        __syncthreads();
+        u32 c[PER], sum = 0, tot;
+        int too_long = 0;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const u32 d = (u32)(t * PER + j);
+            c[j] = d < R ? gcnt[d] : 0u;
+            sum += c[j];
+            too_long |= c[j] > (u32)BUCKET_GROUP_MAX ? 1 : 0;
+        }
+        u32 run = wide_block_exclusive_scan<NW>(sum, smem, tot);
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const u32 d = (u32)(t * PER + j);
+            if (d < R) gstart[d] = run;
+            run += c[j];
+        }
+        if (t == 0) gstart[R] = (u32)cnt;
+        if (!__syncthreads_or(too_long) && rest > 0 && cnt <= 16 * CAP) {
+            for (int g0 = 0; g0 < (int)R;) {
+                int g1 = g0 + 1;  // (a group has at most 64 keys: at least one fits)
+                while (g1 < (int)R && gstart[g1 + 1] - gstart[g0] <= (u32)CAP) ++g1;
+                const int part0 = (int)gstart[g0], part_n = (int)gstart[g1] - part0;
+                if (part_n > 0) {
+                    for (int i = g0 + t; i < g1; i += THREADS) gcnt[i] = 0;
+                    __syncthreads();
+                    for (int i = t; i < cnt; i += THREADS) {
+                        const LK k = (LK)kin[i];
+                        const int d = (int)digit_of<LK>(k, rest, dmask);
+                        if (d >= g0 && d < g1) skey[gstart[d] - (u32)part0 + atomicAdd(&gcnt[d], 1u)] = k;
+                    }
+                    __syncthreads();
+                    sort_groups(g0, g1);
+                    for (int i0 = w * 64; i0 < part_n; i0 += THREADS) {  // (whole waves, for the ballot)
+                        const int i = i0 + lane;
+                        bool first = false;
+                        if (i < part_n) {
+                            const LK k = skey[i];
+                            const K full = upper | (K)k;
+                            kout[part0 + i] = full;
+                            if constexpr (COUNT_UNIQUE) first = full != sentinel && (i == 0 || skey[i - 1] != k);
+                        }
+                        if constexpr (COUNT_UNIQUE) count_firsts(part0 + i0, first, nullptr);
+                    }
+                    __syncthreads();
+                }
+                g0 = g1;
+            }
+            return;
+        }
+    }
+    if (cnt > CAP) {  // ... else pass by pass through global memory
         bucket_sort_oversize<K, false, THREADS>(kout, kin, nullptr, nullptr, cnt, low_bits, gcnt, smem);
         if constexpr (COUNT_UNIQUE) {
             __threadfence();
@@ -839,11 +953,7 @@ __global__ __launch_bounds__(THREADS) void bucket_keys_kernel(K* __restrict__ ki
         return;
     }
 
-    const int gbits = low_bits < BUCKET_GROUP_BITS ? low_bits : BUCKET_GROUP_BITS;
-    const int rest = low_bits - gbits;
-    const u32 R = 1u << gbits, dmask = R - 1;
     for (int i = t; i < (int)R; i += THREADS) gcnt[i] = 0;
-    if (t == 0) nlong = 0;
     if constexpr (COUNT_UNIQUE) {
         if (t < TALLY) tcnt[t] = 0;
     }
@@ -887,45 +997,7 @@ __global__ __launch_bounds__(THREADS) void bucket_keys_kernel(K* __restrict__ ki
         if (i < items && i * THREADS + t < cnt) skey[gstart[digit_of<LK>(key[i], rest, dmask)] + pos[i]] = key[i];
     __syncthreads();
     if (rest > 0 && !any_long) {
-        for (int gi = t; gi < (int)R; gi += THREADS) {
-            const int gs = (int)gstart[gi];
-            const int g = (int)gstart[gi + 1] - gs;
-            if (g > 16) {  // listed for the waves (the counters are no longer needed: the list goes there)
-                gcnt[atomicAdd(&nlong, 1u)] = (u32)gi;
-            } else if (g > 12) {
-                group_sort_lds<LK, 16>(skey, gs, g);
-            } else if (g > 8) {
-                group_sort_lds<LK, 12>(skey, gs, g);
-            } else if (g > 6) {
-                group_sort_lds<LK, 8>(skey, gs, g);
-            } else if (g > 4) {
-                group_sort_lds<LK, 6>(skey, gs, g);
-            } else if (g > 1) {
-                group_sort_lds<LK, 4>(skey, gs, g);
-            }
-        }
-        __syncthreads();
-        // groups of 17 to 64 keys: a wave takes a group, one lane per key; a key's place is the number of
-        // keys of the group that go before it (every lane reads the same address, one read after the
-        // other with nothing waiting in between, where an insertion sort by one lane would wait for
-        // LDS at every step)
-        const int n_long = (int)nlong;
-        if (n_long > 0) {
-            for (int li = w; li < n_long; li += NW) {
-                const int gi = (int)gcnt[li];
-                const int gs = (int)gstart[gi];
-                const int g = (int)gstart[gi + 1] - gs;
-                const LK k = lane < g ? skey[gs + lane] : (LK)0;
-                int r = 0;
-                for (int i = 0; i < g; ++i) {
-                    const LK o = skey[gs + i];
-                    r += (o < k || (o == k && i < lane)) ? 1 : 0;
-                }
-                __builtin_amdgcn_wave_barrier();  // (a wave's LDS operations complete in order)
-                if (lane < g) skey[gs + r] = k;
-            }
-            __syncthreads();
-        }
+        sort_groups(0, (int)R);
     } else if (rest > 0) {
         // some group is longer still: the whole bucket through a bitonic network, padded to a power of two
         int P = 64;
@@ -947,8 +1019,6 @@ __global__ __launch_bounds__(THREADS) void bucket_keys_kernel(K* __restrict__ ki
             }
         }
     }
-    K upper = 0;
-    if constexpr (sizeof(LK) < sizeof(K)) upper = (K)(u32)bkt << low_bits;
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) {
         if (i < items) {

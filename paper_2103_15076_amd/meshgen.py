@@ -105,54 +105,82 @@ def icosphere(level: int = 6, seed: int | None = 1002, jitter: float = 0.01):
     return np.ascontiguousarray(v.astype(np.float32)), np.ascontiguousarray(f.astype(np.int32))
 
 
-def _rect_patch(origin, eu, ev, lu, lv, h):
-    """Regular lattice over the rectangle origin + s*eu + t*ev, s in [0,lu], t in [0,lv]."""
-    nu = max(2, int(np.ceil(lu / h)) + 1)
-    nv = max(2, int(np.ceil(lv / h)) + 1)
-    s = np.linspace(0.0, lu, nu)
-    t = np.linspace(0.0, lv, nv)
-    S, T = np.meshgrid(s, t, indexing="xy")
-    p = origin[None, :] + S.ravel()[:, None] * eu[None, :] + T.ravel()[:, None] * ev[None, :]
-    return p, grid_patch(nu, nv)
+def _cells(length, h):
+    """Lattice cells along an edge of this length at spacing about h."""
+    return max(1, int(np.ceil(length / h)))
 
 
-def _box_faces(lo, size, with_bottom):
-    """The axis-aligned rectangles bounding a box: (origin, eu, ev, lu, lv) each."""
-    x0, y0, z0 = lo
-    sx, sy, sz = size
-    ex, ey, ez = np.eye(3)
-    faces = [
-        (np.array([x0, y0, z0 + sz]), ex, ey, sx, sy),            # top
-        (np.array([x0, y0, z0]), ex, ez, sx, sz),                 # y = y0
-        (np.array([x0, y0 + sy, z0]), ex, ez, sx, sz),            # y = y0+sy
-        (np.array([x0, y0, z0]), ey, ez, sy, sz),                 # x = x0
-        (np.array([x0 + sx, y0, z0]), ey, ez, sy, sz),            # x = x0+sx
-    ]
-    if with_bottom:
-        faces.append((np.array([x0, y0, z0]), ex, ey, sx, sy))
-    return faces
+def _box_surface(lo, size, h, with_bottom):
+    """Lattice over the faces of an axis-aligned box, welded along the box's edges: every face is a
+    regular patch (cells split like ``grid_patch``), and lattice points shared by two or three faces
+    are one vertex.  Faces: top, y = y0, y = y1, x = x0, x = x1 and, with ``with_bottom``, the bottom.
+    Vertices are numbered in the order in which the faces first reach them.
+    Returns (points float64[n,3], facets int64[m,3])."""
+    n = [_cells(size[d], h) for d in range(3)]
+    ax = [np.linspace(0.0, size[d], n[d] + 1) + lo[d] for d in range(3)]
+    specs = [(2, n[2]), (1, 0), (1, n[1]), (0, 0), (0, n[0])] + ([(2, 0)] if with_bottom else [])
+    ijk, tris, base = [], [], 0
+    for d, val in specs:
+        u, v = [a for a in range(3) if a != d]
+        nu, nv = n[u] + 1, n[v] + 1
+        I, J = np.meshgrid(np.arange(nu), np.arange(nv), indexing="xy")
+        idx = np.zeros((I.size, 3), np.int64)
+        idx[:, u] = I.ravel()
+        idx[:, v] = J.ravel()
+        idx[:, d] = val
+        ijk.append(idx)
+        tris.append(grid_patch(nu, nv) + base)
+        base += I.size
+    ijk = np.concatenate(ijk, axis=0)
+    tris = np.concatenate(tris, axis=0)
+    key = (ijk[:, 0] * (n[1] + 1) + ijk[:, 1]) * (n[2] + 1) + ijk[:, 2]
+    _, first, inv = np.unique(key, return_index=True, return_inverse=True)
+    order = np.argsort(first, kind="stable")      # distinct points in order of first appearance
+    rank = np.empty_like(order)
+    rank[order] = np.arange(order.size)
+    pick = ijk[first[order]]
+    pts = np.stack([ax[0][pick[:, 0]], ax[1][pick[:, 1]], ax[2][pick[:, 2]]], axis=1)
+    return pts, rank[inv.reshape(-1)][tris]
 
 
-def room_scene(seed: int, room=(10.0, 8.0, 3.0), n_boxes: int = 40, spacing: float = 0.07,
-               jitter: float = 0.003):
-    """Box room (floor, ceiling, 4 walls) plus ``n_boxes`` axis-aligned furniture
-    boxes (sizes U(0.3, 2.0) m per axis, standing on the floor).  Every
-    rectangle is an independent lattice patch (patches are not welded, so the
-    mesh has open boundaries and many components, like scanned rooms);
-    per-coordinate vertex jitter N(0, jitter).
-    """
+def _box_surface_counts(size, h, with_bottom):
+    """(vertices, facets) of ``_box_surface`` without building it."""
+    a, b, c = (_cells(size[d], h) + 1 for d in range(3))
+    nv = 2 * (a * b + a * c + b * c) - 4 * (a + b + c) + 8
+    nf = 4 * ((a - 1) * (b - 1) + (a - 1) * (c - 1) + (b - 1) * (c - 1))
+    if not with_bottom:
+        nv -= (a - 2) * (b - 2)
+        nf -= 2 * (a - 1) * (b - 1)
+    return nv, nf
+
+
+def _scene_boxes(seed, room, n_boxes):
+    """The room and its furniture: (rng, [(lo, size, with_bottom)]); the rng goes on to the jitter."""
     rng = np.random.default_rng(seed)
     rx, ry, rz = room
-    rects = _box_faces((0.0, 0.0, 0.0), (rx, ry, rz), with_bottom=True)
+    boxes = [((0.0, 0.0, 0.0), (rx, ry, rz), True)]
     sizes = rng.uniform(0.3, 2.0, size=(n_boxes, 3))
     sizes[:, 2] = np.minimum(sizes[:, 2], rz)
     px = rng.uniform(0.0, 1.0, size=n_boxes) * (rx - sizes[:, 0])
     py = rng.uniform(0.0, 1.0, size=n_boxes) * (ry - sizes[:, 1])
     for k in range(n_boxes):
-        rects += _box_faces((px[k], py[k], 0.0), tuple(sizes[k]), with_bottom=False)
+        boxes.append(((px[k], py[k], 0.0), tuple(sizes[k]), False))
+    return rng, boxes
+
+
+def room_scene(seed: int, room=(10.0, 8.0, 3.0), n_boxes: int = 40, spacing: float = 0.07,
+               jitter: float = 0.003):
+    """Box room (floor, ceiling, 4 walls: a closed surface) plus ``n_boxes`` axis-aligned furniture
+    boxes (sizes U(0.3, 2.0) m per axis, standing on the floor, five faces each, open towards the
+    floor).  The faces of one box are welded along its edges; boxes are not joined to the floor or to
+    each other (separate components, intersecting surfaces, open boundaries: as in scanned rooms).
+    Facets come to about twice the vertices, as in the paper's room meshes.  Per-coordinate vertex
+    jitter N(0, jitter).
+    """
+    rng, boxes = _scene_boxes(seed, room, n_boxes)
     vs, fs, base = [], [], 0
-    for (o, eu, ev, lu, lv) in rects:
-        p, f = _rect_patch(o, eu, ev, lu, lv, spacing)
+    for lo, size, with_bottom in boxes:
+        p, f = _box_surface(lo, size, spacing, with_bottom)
         vs.append(p)
         fs.append(f + base)
         base += p.shape[0]
@@ -163,18 +191,8 @@ def room_scene(seed: int, room=(10.0, 8.0, 3.0), n_boxes: int = 40, spacing: flo
 
 
 def _count_verts(seed, room, n_boxes, h):
-    rng = np.random.default_rng(seed)
-    rx, ry, rz = room
-    dims = [(rx, ry), (rx, rz), (rx, rz), (ry, rz), (ry, rz), (rx, ry)]
-    sizes = rng.uniform(0.3, 2.0, size=(n_boxes, 3))
-    sizes[:, 2] = np.minimum(sizes[:, 2], rz)
-    for k in range(n_boxes):
-        sx, sy, sz = sizes[k]
-        dims += [(sx, sy), (sx, sz), (sx, sz), (sy, sz), (sy, sz)]
-    n = 0
-    for (a, b) in dims:
-        n += max(2, int(np.ceil(a / h)) + 1) * max(2, int(np.ceil(b / h)) + 1)
-    return n
+    _, boxes = _scene_boxes(seed, room, n_boxes)
+    return sum(_box_surface_counts(size, h, with_bottom)[0] for _, size, with_bottom in boxes)
 
 
 def room_scene_sized(seed: int, n_target: int, room=(10.0, 8.0, 3.0), n_boxes: int = 40,

@@ -99,6 +99,12 @@ def _bucket_cases():
     k[:120000] = (np.uint64(5) << np.uint64(24)) | (k[:120000] & np.uint64(0xFFFFFF))   # 120k keys share the top byte
     rng.shuffle(k)
     yield "skewed_oversize", k, 32
+    # one bucket of 256 holds 20,000 keys, more than LDS takes, but spread over its 512 groups (about 40 keys
+    # each): sorted in parts of whole groups
+    k = rng.integers(0, 1 << 34, size=200000, dtype=np.uint64)
+    k[:20000] = (np.uint64(5) << np.uint64(26)) | (k[:20000] & np.uint64((1 << 26) - 1))
+    rng.shuffle(k)
+    yield "oversize_in_parts", k, 34
     k = np.full(30000, (7 << 20) | 12345, np.uint64)   # all equal: one oversize bucket, stability only
     yield "all_equal", k, 28
     yield "full", rng.integers(0, 1 << 40, size=1 << 20, dtype=np.uint64), 40
