@@ -4,7 +4,9 @@
 One "step" = one whole picasso_decimate call (vertex quadrics, then every
 round: edges, costs, selection, contraction, facet clean-up) on the
 115k-vertex synthetic room mesh, decimated to 41,500 vertices (about 36 %),
-inputs resident in HBM.  Prints ONE JSON line.
+inputs resident in HBM.  For the hierarchy workload (batch16x60k) a step is
+the whole ladder: four batched decimations in a row, each to 40 % per mesh.
+Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload room115k]
 """
@@ -19,10 +21,40 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# Bytes per launch of the edge-key sort's main kernel (bucket_sort_kernel<u64>) that crossed the L2-fabric boundary, from two
-# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by the copy-kernel calibration; see
-# profiles/hbm_counters_edge_sort.md.  Offline measurements: null for workloads that were not profiled.
-MEASURED_TRAFFIC_BYTES = {"room115k": 8.07e6, "scene1p2m": 66.3e6}
+
+
+def source_hash():
+    """sha256 over the HIP sources: what the stored HBM-traffic figures are stamped with."""
+    import hashlib
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2103_15076_amd", "csrc")
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".h", ".hip")):
+            h.update(name.encode())
+            h.update(open(os.path.join(d, name), "rb").read())
+    return h.hexdigest()
+
+
+def measured_traffic(workload):
+    """HBM-side bytes per launch of the bracketed kernels from the rocprofv3 --pmc runs summarised in
+    profiles/hbm_traffic.txt ({kernel key: bytes}), or {} when that file was taken with other kernel
+    sources than the ones that are running now (the figures would be stale)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return {}
+    out, ok = {}, False
+    for line in open(path):
+        w = line.split()
+        if not w or w[0].startswith("#"):
+            continue
+        if w[0] == "source_sha256":
+            ok = w[1] == source_hash()
+        elif w[0] == workload and len(w) >= 3:
+            out[w[1]] = float(w[2])
+    return out if ok else {}
+
+
+KERNEL_KEYS = ("sort", "unique_cost", "subround0", "facet_insert", "quadric_rows")
 
 
 def main():
@@ -118,10 +150,35 @@ def main():
     if args.stream_sync:
         ctx.set_option(pk.PICASSO_OPT_HOST_POLL, 0)
 
-    def step(stats=None):
-        if B == 1:
-            return ctx.picasso_decimate(dV, dF, int(target[0]), vo, fo, cid, stats=stats, stream=stream)
-        return ctx.picasso_decimate_batch(dV, dF, nv_in, nf_in, target, vo, fo, cid, stats=stats, stream=stream)
+    levels = int(cfg.get("levels", 1))
+    targets = [np.asarray(target, np.int32)]
+    for _ in range(1, levels):   # every further level keeps 40 % of each mesh's vertices
+        targets.append((targets[-1].astype(np.int64) * 4 // 10).astype(np.int32))
+    lev_out = [(torch.empty((N, 3), dtype=torch.float32, device=dev), torch.empty((NF, 3), dtype=torch.int32, device=dev),
+                torch.empty((N,), dtype=torch.int32, device=dev)) for _ in range(levels - 1)]
+    lev_ev = [torch.cuda.Event(enable_timing=True) for _ in range(levels + 1)]
+
+    def step(stats=None, record=False):
+        """One pass of the whole path: one decimation, or for the hierarchy workload its levels in a row,
+        each level's output mesh being the next level's input.  Returns the last level's result and, per
+        level, (status, verts, facets, cluster ids, nv[B], nf[B])."""
+        if levels == 1:
+            if B == 1:
+                return ctx.picasso_decimate(dV, dF, int(target[0]), vo, fo, cid, stats=stats, stream=stream), None
+            return ctx.picasso_decimate_batch(dV, dF, nv_in, nf_in, target, vo, fo, cid, stats=stats, stream=stream), None
+        per_level = []
+        v_in, f_in, nvs, nfs = dV, dF, nv_in, nf_in
+        if record:
+            lev_ev[0].record(stream)
+        for lv in range(levels):
+            bufs = (vo, fo, cid) if lv == 0 else lev_out[lv - 1]
+            r = ctx.picasso_decimate_batch(v_in, f_in, nvs, nfs, targets[lv], bufs[0], bufs[1],
+                                           bufs[2][: int(v_in.shape[0])], stats=stats if lv == 0 else None, stream=stream)
+            if record:
+                lev_ev[lv + 1].record(stream)
+            per_level.append(r)
+            v_in, f_in, nvs, nfs = r[1], r[2], r[4], r[5]
+        return per_level[-1], per_level
 
     for _ in range(args.warmup):
         step()
@@ -138,12 +195,18 @@ def main():
     ctx.set_option(pk.PICASSO_OPT_KERNEL_TIMING, 0 if args.no_kernel_events else max(1, args.kernel_events_every))
     if args.single_stream:
         ctx.set_option(pk.PICASSO_OPT_OVERLAP, 0)
-    ctx.picasso_kernel_timing(reset=True)
+    for k in range(pk.PICASSO_KERNEL_COUNT):
+        ctx.picasso_kernel_timing(k, reset=True)
     torch.cuda.synchronize()
+    level_ms = [0.0] * levels
     t0 = time.perf_counter()
     ev0.record(stream)
     for _ in range(args.steps):
-        res = step()
+        res, res_levels = step(record=levels > 1)
+        if levels > 1:   # (the host has waited for every level's work; the last event follows it at once)
+            lev_ev[levels].synchronize()
+            for lv in range(levels):
+                level_ms[lv] += lev_ev[lv].elapsed_time(lev_ev[lv + 1])
     ev1.record(stream)
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
@@ -151,7 +214,8 @@ def main():
     ms_per_step = max(wall_ms, ev_ms) / args.steps
     nv_out, nf_out = int(res[1].shape[0]), int(res[2].shape[0])
     gc.enable()
-    kt = ctx.picasso_kernel_timing(reset=True)   # hipEvents around the dominant kernel's launches in every N-th step of the timed region
+    # hipEvents around the largest kernels' launches in every N-th step of the timed region
+    kts = [ctx.picasso_kernel_timing(k, reset=True) for k in range(pk.PICASSO_KERNEL_COUNT)]
 
     # ---- one extra call for the per-round shape and stage times
     st = pk.picasso_stats()
@@ -163,17 +227,23 @@ def main():
     if args.stages:
         print(json.dumps(sd), file=sys.stderr)
 
-    roofline = None
-    if kt["launches"] > 0:
+    # Roofline: every bracketed kernel against the HBM peak (algorithmic bytes per launch / average
+    # launch time); the headline entry is the kernel with the largest share of the step.
+    traffic = measured_traffic(args.workload)
+    by_kernel = []
+    for key, kt in zip(KERNEL_KEYS, kts):
+        if kt["launches"] == 0:
+            continue
         avg_ms = kt["ms_total"] / kt["launches"]
         bytes_per_launch = kt["bytes_total"] / kt["launches"]
         achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "kernel": kt["kernel"], "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5),
-                    "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
-                    "launches_timed": kt["launches"], "events_every_n_steps": max(1, args.kernel_events_every),
-                    "avg_launch_us": round(avg_ms * 1e3, 3),
-                    "algorithmic_bytes_per_launch": int(bytes_per_launch)}
+        by_kernel.append({"bound": "hbm", "kernel": kt["kernel"], "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
+                          "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": traffic.get(key),
+                          "launches_timed": kt["launches"], "events_every_n_steps": max(1, args.kernel_events_every),
+                          "avg_launch_us": round(avg_ms * 1e3, 3), "algorithmic_bytes_per_launch": int(bytes_per_launch),
+                          "event_ms_per_timed_step": round(kt["ms_total"] * max(1, args.kernel_events_every) / args.steps, 4)})
+    by_kernel.sort(key=lambda r: -r["event_ms_per_timed_step"])
+    roofline = by_kernel[0] if by_kernel else None
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
@@ -181,20 +251,32 @@ def main():
         oracle.build()
         times = []
         reps = 5 if N < 500000 else 2
+
+        def oracle_pass():
+            """The same work on one host core: one decimation, or the hierarchy's levels in a row."""
+            if B == 1:
+                return [oracle.decimate(V, F, int(target[0]), placement=1 if inverse else 0,
+                                        rcond_min=args.rcond_min if inverse else 0.0, absorb=args.absorb,
+                                        shuffle_seed=args.shuffle_seed)]
+            outs, v_in, f_in, nvs, nfs = [], V, F, nv_in, nf_in
+            for lv in range(levels):
+                r = oracle.decimate_batch(v_in, f_in, nvs, nfs, targets[lv])
+                outs.append(r)
+                v_in, f_in, nvs, nfs = r["verts"], r["facets"], r["nv"], r["nf"]
+            return outs
+
         for _ in range(reps):
             c0 = time.perf_counter()
-            if B == 1:
-                ref = oracle.decimate(V, F, int(target[0]), placement=1 if inverse else 0,
-                                      rcond_min=args.rcond_min if inverse else 0.0, absorb=args.absorb,
-                                      shuffle_seed=args.shuffle_seed)
-            else:
-                ref = oracle.decimate_batch(V, F, nv_in, nf_in, target)
+            refs = oracle_pass()
             times.append(time.perf_counter() - c0)
         med = float(np.median(times))
-        same = (np.array_equal(res[3].cpu().numpy(), ref["cluster_id"])
-                and np.array_equal(res[2].cpu().numpy(), ref["facets"]))
+        got = res_levels if res_levels is not None else [res]
+        same = all(np.array_equal(g[3].cpu().numpy(), r["cluster_id"]) and np.array_equal(g[2].cpu().numpy(), r["facets"])
+                   and np.array_equal(g[1].cpu().numpy().view(np.uint32), r["verts"].view(np.uint32))
+                   for g, r in zip(got, refs))
+        what = "decimation" if levels == 1 else f"pass over the {levels} levels"
         cpu_baseline = {"value": round(NF / med, 1), "unit": "facets/s", "cores": 1, "kind": "oracle",
-                        "sample": f"the full workload, median of {reps} runs ({med * 1e3:.1f} ms per decimation)",
+                        "sample": f"the full workload, median of {reps} runs ({med * 1e3:.1f} ms per {what})",
                         "ms_per_decimation": round(med * 1e3, 2), "gpu_matches_oracle_bit_exact": bool(same)}
 
     pooling = None
@@ -300,8 +382,18 @@ def main():
         "event_ms_per_step": round(ev_ms / args.steps, 4),
         "stage_ms": {k: round(sum(r[k] for r in sd["ms_stage"]), 4) for k in pk.binding.STAGE_NAMES},
         "roofline": roofline,
+        "roofline_by_kernel": by_kernel,
         "cpu_baseline": cpu_baseline,
     }
+    if levels > 1:
+        # the hierarchy: per-level time (hipEvents between the levels of every timed step) and sizes
+        out["levels"] = [{"level": lv + 1, "ms": round(level_ms[lv] / args.steps, 4),
+                          "verts_in": int(np.sum(nv_in)) if lv == 0 else int(res_levels[lv - 1][1].shape[0]),
+                          "facets_in": NF if lv == 0 else int(res_levels[lv - 1][2].shape[0]),
+                          "verts_out": int(res_levels[lv][1].shape[0]), "facets_out": int(res_levels[lv][2].shape[0])}
+                         for lv in range(levels)]
+        out["config"]["levels"] = levels
+        out["config"]["stage_ms_and_rounds_are_of"] = "level 1" 
     if pooling is not None:
         out["pooling"] = pooling
     if convs is not None:

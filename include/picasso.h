@@ -54,7 +54,7 @@ enum picasso_option {
     PICASSO_OPT_STAGE_TIMING = 1,  /* 1: fill picasso_stats.ms_stage with hipEvent times (slower)    */
     PICASSO_OPT_SUBROUND_BATCH = 2,/* selection sub-rounds launched between two host checks         */
     PICASSO_OPT_KERNEL_TIMING = 3, /* N > 0: in every N-th decimate call from now on, bracket the
-                                      launches of the edge-key sort's main kernel with hipEvents
+                                      launches of the path's largest kernels with hipEvents
                                       (see picasso_kernel_timing); an event pair costs several
                                       microseconds of queue time per launch; 0: off                */
     PICASSO_OPT_OVERLAP = 4,       /* 1 (default): for inputs of 2^18 facets or more, the first
@@ -156,14 +156,37 @@ int picasso_set_option(picasso_ctx* ctx, int option, int64_t value);
 const char* picasso_strerror(int status);
 const char* picasso_last_hip_error(picasso_ctx* ctx);
 
-/* Totals gathered while PICASSO_OPT_KERNEL_TIMING is on, over all decimate
- * calls since the last reset: launches of the main streaming kernel of the
- * 64-bit edge-key sort (Alg. 2 line 1) -- the per-bucket sort kernel, or the
- * scatter passes when an input beyond 2^23 keys falls back to plain LSD --,
- * their summed hipEvent time, and their summed algorithmic bytes (each launch
- * reads and writes every 8-byte key once: 16 bytes x 3 x facets of that
- * round).  Host pointers, may be NULL.  reset != 0 clears the totals. */
-int picasso_kernel_timing(picasso_ctx* ctx, int reset, int64_t* launches, double* ms_total, double* bytes_total);
+/* Kernels whose launches PICASSO_OPT_KERNEL_TIMING brackets with hipEvents, and the algorithmic
+ * bytes a launch of each is charged with (what the step has to move at least, from the sizes of the
+ * round it runs in: nv vertices, nf facets, H = 3 nf half-edges, E distinct edges; N, F = the call's
+ * input sizes):
+ *   SORT          per-bucket kernel of the 64-bit edge-key sort (Alg. 2 line 1; the scatter passes
+ *                 when an input beyond 2^23 keys falls back to plain radix passes): every 8-byte
+ *                 key read and written once, 16 H.
+ *   UNIQUE_COST   distinct edges, their costs (Alg. 2 line 2) and first bids: 8 H (sorted keys
+ *                 read) + 13 E (edge key, cost key, state written) + 64 nv (every vertex record
+ *                 read once) + 8 nv (one bid word per vertex).
+ *   SUBROUND0     first grid-wide sub-round of the selection (Alg. 2 lines 3-10): 13 E read, E
+ *                 written (edge states), 3 x 8 nv (bids read, next bids written, third array cleared).
+ *   FACET_INSERT  facets re-indexed and entered into the hash set, cluster labels composed:
+ *                 12 nf read + 12 nf re-indexed + 4 nf deciding slot + 4 nf table slot + 4 nv
+ *                 (vertex map) + 8 N (labels read and written).
+ *   QUADRIC_ROWS  vertex quadrics summed from the facets' planes (supplementary, vertex quadric
+ *                 equation): 8 x 3F sorted incidences + 16 F planes + 12 N positions + 64 N records. */
+enum picasso_timed_kernel {
+    PICASSO_KERNEL_SORT = 0,
+    PICASSO_KERNEL_UNIQUE_COST = 1,
+    PICASSO_KERNEL_SUBROUND0 = 2,
+    PICASSO_KERNEL_FACET_INSERT = 3,
+    PICASSO_KERNEL_QUADRIC_ROWS = 4,
+    PICASSO_KERNEL_COUNT = 5
+};
+
+/* Totals gathered for `kernel` while PICASSO_OPT_KERNEL_TIMING is on, over all decimate calls
+ * since the last reset: launches, their summed hipEvent time, their summed algorithmic bytes.
+ * Host pointers, may be NULL.  reset != 0 clears that kernel's totals afterwards. */
+int picasso_kernel_timing(picasso_ctx* ctx, int kernel, int reset, int64_t* launches, double* ms_total,
+                          double* bytes_total);
 
 /* Alg. 2 repeated until the vertex budget is met (Sec. 3: "running the core
  * algorithm multiple times").

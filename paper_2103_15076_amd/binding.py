@@ -36,6 +36,16 @@ PICASSO_OPT_LAUNCH_AHEAD = 11
 PICASSO_OPT_TRUNC_WIDTH = 12
 PICASSO_PLACE_MEAN, PICASSO_PLACE_INVERSE = 0, 1
 
+(PICASSO_KERNEL_SORT, PICASSO_KERNEL_UNIQUE_COST, PICASSO_KERNEL_SUBROUND0, PICASSO_KERNEL_FACET_INSERT,
+ PICASSO_KERNEL_QUADRIC_ROWS, PICASSO_KERNEL_COUNT) = range(6)
+TIMED_KERNEL_NAMES = (
+    "bucket_keys_kernel<u64> (edge-key sort, per-bucket LDS sort)",
+    "tile_scatter_kernel<UniquePred, UniqueOut> (distinct edges, costs, first bids)",
+    "select_subround_kernel (first sub-round of the selection)",
+    "facet_insert_kernel (facet hash set, label compose)",
+    "quadric_rows_kernel (vertex quadrics from facet planes)",
+)
+
 PICASSO_STATS_ROUNDS = 32
 PICASSO_ST_COUNT = 8
 STAGE_NAMES = ("quadrics", "edges", "select", "contract", "facets")
@@ -122,8 +132,8 @@ def load_library():
     lib.picasso_edge_costs.restype = ctypes.c_int
     lib.picasso_edge_costs.argtypes = [vp, vp, vp, i32, vp, i32, vp, vp, ctypes.POINTER(i32)]
     lib.picasso_kernel_timing.restype = ctypes.c_int
-    lib.picasso_kernel_timing.argtypes = [vp, ctypes.c_int, ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double),
-                                          ctypes.POINTER(ctypes.c_double)]
+    lib.picasso_kernel_timing.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(i64),
+                                          ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
     lib.picasso_device_copy.restype = ctypes.c_int
     lib.picasso_device_copy.argtypes = [vp, vp, vp, ctypes.c_size_t]
     lib.picasso_radix_sort.restype = ctypes.c_int
@@ -254,12 +264,14 @@ class Context:
         self.set_option(PICASSO_OPT_RCOND_MIN_BITS, struct.unpack("<I", struct.pack("<f", float(rcond_min)))[0])
         self.set_option(PICASSO_OPT_PLACEMENT, placement)
 
-    def picasso_kernel_timing(self, reset=False):
-        """Totals for the edge-key sort's main kernel while PICASSO_OPT_KERNEL_TIMING is on."""
+    def picasso_kernel_timing(self, kernel, reset=False):
+        """Totals for one of the bracketed kernels (PICASSO_KERNEL_*) while PICASSO_OPT_KERNEL_TIMING is on."""
         n, ms, by = ctypes.c_int64(0), ctypes.c_double(0.0), ctypes.c_double(0.0)
-        self._lib.picasso_kernel_timing(self._h, int(bool(reset)), ctypes.byref(n), ctypes.byref(ms), ctypes.byref(by))
-        return dict(kernel="bucket_sort_kernel<u64> (edge-key sort, per-bucket LDS sort)", launches=n.value, ms_total=ms.value,
-                    bytes_total=by.value)
+        st = self._lib.picasso_kernel_timing(self._h, int(kernel), int(bool(reset)), ctypes.byref(n), ctypes.byref(ms),
+                                             ctypes.byref(by))
+        if st != PICASSO_OK:
+            self._raise(st)
+        return dict(kernel=TIMED_KERNEL_NAMES[int(kernel)], launches=n.value, ms_total=ms.value, bytes_total=by.value)
 
     def last_hip_error(self) -> str:
         return self._lib.picasso_last_hip_error(self._h).decode()

@@ -128,12 +128,14 @@ struct picasso_ctx {
     hipEvent_t kt_pool[512];
     prim::LaunchTimer::Rec kt_recs[256];
     prim::LaunchTimer kt;
-    int64_t kt_launches = 0;
-    double kt_ms = 0.0, kt_bytes = 0.0;
+    int64_t kt_launches[PICASSO_KERNEL_COUNT] = {0};
+    double kt_ms[PICASSO_KERNEL_COUNT] = {0.0}, kt_bytes[PICASSO_KERNEL_COUNT] = {0.0};
     // host mirrors of the per-mesh state of a decimate call (6 x max_meshes ints, allocated with the
     // context: the calls themselves allocate nothing, on the host either)
     int* h_mesh = nullptr;
-    int nf_round[NF_ROUND_CAP];  // facets entering each round of the current call
+    int nf_round[NF_ROUND_CAP];  // facets, vertices, distinct edges of each round of the current call
+    int nv_round[NF_ROUND_CAP];
+    int ne_round[NF_ROUND_CAP];
     int n_rounds_noted = 0;
     StageRec st_recs[PICASSO_STATS_ROUNDS * PICASSO_ST_COUNT + 2];
 };
@@ -272,6 +274,22 @@ struct StageTimer {
     }
 };
 
+// hipEvents around the launches made while this object lives, credited to `kernel` in round `round`
+// (only in the calls that PICASSO_OPT_KERNEL_TIMING picks).
+struct KernelBracket {
+    picasso_ctx* c;
+    hipStream_t s;
+    bool on;
+    KernelBracket(picasso_ctx* c_, hipStream_t s_, int kernel, int round, bool wanted = true) : c(c_), s(s_) {
+        on = wanted && c->kt_this_call && round < 0xFF && c->kt.begin(s, (kernel << 8) | round);
+    }
+    ~KernelBracket() {
+        if (on) c->kt.end(s);
+    }
+    KernelBracket(const KernelBracket&) = delete;
+    KernelBracket& operator=(const KernelBracket&) = delete;
+};
+
 // Sort for keys whose leading bits are vertex ids (evenly spread): bucket sort
 // when the input is small enough for it, plain LSD passes otherwise.
 // which sort sort_by_vertex takes, named by the counting a producer of the keys may do for it
@@ -403,6 +421,7 @@ int run_vertex_quadrics(picasso_ctx* c, hipStream_t s, const float* d_verts, int
         if (where < 0) return PICASSO_ERR_HIP;
         const u64* skey = where ? c->s0_key[1] : c->s0_key[0];
         const int tiles = (H + QR_TILE - 1) / QR_TILE;
+        const KernelBracket timed(c, s, PICASSO_KERNEL_QUADRIC_ROWS, 0);
         quadric_rows_kernel<<<(tiles + 7) / 8 * 8, BLOCK, 0, s>>>(c->vrec[0], d_verts, N, facet_planes(c), skey, H, fbits,
                                                                  c->hist12_s0);
     } else {
@@ -631,6 +650,10 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
     c->kt.used = 0;
     c->kt.nrec = 0;
     c->kt_this_call = c->opt_kernel_timing > 0 && (c->kt_calls++ % c->opt_kernel_timing) == 0;
+    struct TimingScope {  // (no brackets outside this call, however it ends)
+        picasso_ctx* c;
+        ~TimingScope() { c->kt_this_call = false; }
+    } timing_scope{c};
     c->n_rounds_noted = 0;
     StageTimer tm{c, s, c->opt_stage_timing != 0 && stats != nullptr};
     if (stats) HIP_TRY(c, hipEventRecord(c->ev_total[0], s));  // (an event costs queue time: only when asked for)
@@ -707,6 +730,7 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
     do {                                                                                                             \
         UniqueOutT<PLACE, SHUFFLE> uo{skeys, c->ekey, c->ecost, c->vrec[cur], c->vmin[0], c->estate, vbits, mt,       \
                                       RCOND, tb};                                                                    \
+        const KernelBracket timed(c, s, PICASSO_KERNEL_UNIQUE_COST, round);                                          \
         prim::compact_scatter(s, up, uo, &c->st->nh, H, c->tilesum, &c->st->ne);                                     \
     } while (0)
         if (c->opt_placement == PLACE_INVERSE) {
@@ -754,9 +778,12 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         auto issue_facets = [&](int nf_cap, bool guarded) {
             const int nxt = cur ^ 1;
             const size_t hsize = next_pow2((size_t)2 * std::max(nf_cap, 1));
-            facet_insert_kernel<<<grid_for(std::max(nf_cap, N), 8192), BLOCK, 0, s>>>(
-                c->fbuf[cur], c->fmap, c->vmap, c->st, cur, c->htab, (u32)(hsize - 1), mt, c->voff[cur], c->cid, N,
-                c->fslot, guarded ? &c->st->go : nullptr);
+            {
+                const KernelBracket timed(c, s, PICASSO_KERNEL_FACET_INSERT, round);
+                facet_insert_kernel<<<grid_for(std::max(nf_cap, N), 8192), BLOCK, 0, s>>>(
+                    c->fbuf[cur], c->fmap, c->vmap, c->st, cur, c->htab, (u32)(hsize - 1), mt, c->voff[cur], c->cid, N,
+                    c->fslot, guarded ? &c->st->go : nullptr);
+            }
             FacetKeepPred kp{c->fslot, c->htab, c->keep};
             FlagPred fp{c->keep};
             FacetOut fo{c->fmap, c->fbuf[nxt]};
@@ -838,6 +865,7 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
                     if (tb.on) select_subround_sparse_kernel<16, true><<<g16, BLOCK, 0, s>>>(sa, sel_k + j);
                     else select_subround_sparse_kernel<16, false><<<g16, BLOCK, 0, s>>>(sa, sel_k + j);
                 } else {
+                    const KernelBracket timed(c, s, PICASSO_KERNEL_SUBROUND0, round, sel_k + j == 0);  // (the first only)
                     if (tb.on) select_subround_kernel<true><<<grid_for(ne_bound, 1 << 16), BLOCK, 0, s>>>(sa, sel_k + j);
                     else select_subround_kernel<false><<<grid_for(ne_bound, 1 << 16), BLOCK, 0, s>>>(sa, sel_k + j);
                 }
@@ -898,7 +926,12 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         }
         for (int b = 0; b < B; ++b) h_matched[b] = c->h_pin[HDR_STATE_INTS + b];
         nf_bound = std::min(nf_bound, hst->nf[cur]);
-        if (c->n_rounds_noted < NF_ROUND_CAP) c->nf_round[c->n_rounds_noted++] = hst->nf[cur];
+        if (c->n_rounds_noted < NF_ROUND_CAP) {
+            c->nf_round[c->n_rounds_noted] = hst->nf[cur];
+            c->nv_round[c->n_rounds_noted] = nv_total;
+            c->ne_round[c->n_rounds_noted] = hst->ne;
+            ++c->n_rounds_noted;
+        }
         ne_prev = hst->ne;
         nv_prev = nv_total;
         if (stats && round < PICASSO_STATS_ROUNDS) {
@@ -991,14 +1024,25 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
     HIP_TRY(c, hipGetLastError());
     const int* h_foff = c->h_pin + HDR_STATE_INTS + c->cap_b;
 
-    // edge-key sort, main kernel: one read and one write of every 8-byte key per launch
+    // the bracketed kernels: event times and the algorithmic bytes of their rounds (see picasso_timed_kernel)
     for (int i = 0; i < c->kt.nrec; ++i) {
         const prim::LaunchTimer::Rec& r = c->kt.recs[i];
+        const int kernel = r.tag >> 8, rd = r.tag & 0xFF;
         float ms = 0.f;
-        if (r.tag < c->n_rounds_noted && hipEventElapsedTime(&ms, c->kt_pool[r.e0], c->kt_pool[r.e1]) == hipSuccess) {
-            c->kt_launches += 1;
-            c->kt_ms += ms;
-            c->kt_bytes += 16.0 * 3.0 * (double)c->nf_round[r.tag];
+        if (kernel < PICASSO_KERNEL_COUNT && rd < c->n_rounds_noted &&
+            hipEventElapsedTime(&ms, c->kt_pool[r.e0], c->kt_pool[r.e1]) == hipSuccess) {
+            const double nv = c->nv_round[rd], nf = c->nf_round[rd], ne = c->ne_round[rd], H = 3.0 * nf;
+            double bytes = 0.0;
+            switch (kernel) {
+                case PICASSO_KERNEL_SORT: bytes = 16.0 * H; break;
+                case PICASSO_KERNEL_UNIQUE_COST: bytes = 8.0 * H + 13.0 * ne + 72.0 * nv; break;
+                case PICASSO_KERNEL_SUBROUND0: bytes = 14.0 * ne + 24.0 * nv; break;
+                case PICASSO_KERNEL_FACET_INSERT: bytes = 32.0 * nf + 4.0 * nv + 8.0 * (double)N; break;
+                default: bytes = 24.0 * (double)F + 16.0 * (double)F + 76.0 * (double)N; break;  // QUADRIC_ROWS
+            }
+            c->kt_launches[kernel] += 1;
+            c->kt_ms[kernel] += ms;
+            c->kt_bytes[kernel] += bytes;
         }
     }
 
@@ -1233,15 +1277,16 @@ const char* picasso_strerror(int status) {
 
 const char* picasso_last_hip_error(picasso_ctx* c) { return c ? c->hip_err : ""; }
 
-int picasso_kernel_timing(picasso_ctx* c, int reset, int64_t* launches, double* ms_total, double* bytes_total) {
-    if (!c) return PICASSO_ERR_INVALID_ARG;
-    if (launches) *launches = c->kt_launches;
-    if (ms_total) *ms_total = c->kt_ms;
-    if (bytes_total) *bytes_total = c->kt_bytes;
+int picasso_kernel_timing(picasso_ctx* c, int kernel, int reset, int64_t* launches, double* ms_total,
+                          double* bytes_total) {
+    if (!c || kernel < 0 || kernel >= PICASSO_KERNEL_COUNT) return PICASSO_ERR_INVALID_ARG;
+    if (launches) *launches = c->kt_launches[kernel];
+    if (ms_total) *ms_total = c->kt_ms[kernel];
+    if (bytes_total) *bytes_total = c->kt_bytes[kernel];
     if (reset) {
-        c->kt_launches = 0;
-        c->kt_ms = 0.0;
-        c->kt_bytes = 0.0;
+        c->kt_launches[kernel] = 0;
+        c->kt_ms[kernel] = 0.0;
+        c->kt_bytes[kernel] = 0.0;
     }
     return PICASSO_OK;
 }

@@ -609,7 +609,8 @@ def test_statistics_and_timing_options_do_not_change_the_result(pk, ctx, oracle)
         ctx.set_option(pk.PICASSO_OPT_STAGE_TIMING, stage)
         ctx.set_option(pk.PICASSO_OPT_KERNEL_TIMING, every)
         try:
-            ctx.picasso_kernel_timing(reset=True)
+            for k in range(pk.PICASSO_KERNEL_COUNT):
+                ctx.picasso_kernel_timing(k, reset=True)
             st_ = pk.picasso_stats()
             for _ in range(3):
                 st, vo, fo, cid = ctx.picasso_decimate(dev(V), dev(F), target, stats=st_)
@@ -621,10 +622,16 @@ def test_statistics_and_timing_options_do_not_change_the_result(pk, ctx, oracle)
             assert d["nv"][-1] - d["nsel"][-1] == target and d["ms_total"] > 0
             if stage:
                 assert sum(sum(r.values()) for r in d["ms_stage"]) > 0
-            kt = ctx.picasso_kernel_timing(reset=True)
-            assert (kt["launches"] > 0) == (every > 0)
-            if every:
-                assert kt["ms_total"] > 0 and kt["bytes_total"] > 0
+            timed_calls = {0: 0, 1: 3, 2: 2}[every]   # of the three calls above
+            for k in range(pk.PICASSO_KERNEL_COUNT):
+                kt = ctx.picasso_kernel_timing(k, reset=True)
+                per_call = 1 if k == pk.PICASSO_KERNEL_QUADRIC_ROWS else d["rounds"]
+                assert kt["launches"] == timed_calls * per_call, (k, kt)
+                if every:
+                    assert kt["ms_total"] > 0 and kt["bytes_total"] > 0
+                assert ctx.picasso_kernel_timing(k)["launches"] == 0           # the reset took
+            with pytest.raises(pk.PicassoError):
+                ctx.picasso_kernel_timing(pk.PICASSO_KERNEL_COUNT)
         finally:
             ctx.set_option(pk.PICASSO_OPT_STAGE_TIMING, 0)
             ctx.set_option(pk.PICASSO_OPT_KERNEL_TIMING, 0)
