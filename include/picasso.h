@@ -112,12 +112,22 @@ enum picasso_option {
                                       host has looked; they do nothing if the selection turns out
                                       to need more passes.  0: queued after the look.  Same
                                       results.                                                   */
-    PICASSO_OPT_TRUNC_WIDTH = 12   /* test hook for the per-mesh budget step: 0 (default) = its
+    PICASSO_OPT_TRUNC_WIDTH = 12,  /* test hook for the per-mesh budget step: 0 (default) = its
                                       workgroups hold 4, 8, 16 or 32 cost keys per lane (x 1024
                                       lanes) as the largest mesh needs; 4, 8, 16 or 32 = always
                                       that many, so that a mesh with more pairs than fit makes
                                       the kernel report it and the call return
                                       PICASSO_ERR_INTERNAL instead of a wrong budget.            */
+    PICASSO_OPT_DROP_DEGENERATED = 13 /* 1: degenerated vertices are removed (Sec. 3, "Pooling and
+                                      unpooling": the mapping tensor's degenerated-vertex
+                                      information; the paper leaves its definition to code it does
+                                      not print).  An output vertex that no output facet refers
+                                      to (its cluster no longer touches the surface; also an input
+                                      vertex that never did) is dropped at the end of the call:
+                                      the other output vertices keep their order and are
+                                      renumbered, nv_out counts them (it may fall below target_nv),
+                                      and d_cluster_id holds -1 for the input vertices of dropped
+                                      clusters.  0 (default): every cluster stays an output vertex. */
 };
 
 #define PICASSO_STATS_ROUNDS 32
@@ -246,11 +256,12 @@ enum picasso_pool_mode {
  * decimate call's d_cluster_id: d_replace[v] = representative of v's cluster as
  * an input vertex index (the cluster's smallest member), d_mapping[v] = output
  * index of v if v is that representative, else -1, so that
- * d_cluster_id[v] == d_mapping[d_replace[v]].  Device pointers of n_in ints
+ * d_cluster_id[v] == d_mapping[d_replace[v]]; a vertex with cluster id -1 (its cluster was dropped, see
+ * PICASSO_OPT_DROP_DEGENERATED) gets -1 in both.  Device pointers of n_in ints
  * each, owned by the caller.  Waits for its work on the stream (as the decimate
  * calls do); returns
  * PICASSO_ERR_BAD_INDEX (outputs then unspecified) if an id lies outside
- * [0, n_out).  n_out <= max_verts of the context. */
+ * [-1, n_out).  0 <= n_out <= max_verts of the context. */
 int picasso_replace_mapping(picasso_ctx* ctx, void* stream, const int32_t* d_cluster_id, int32_t n_in, int32_t n_out,
                             int32_t* d_replace, int32_t* d_mapping);
 

@@ -148,6 +148,22 @@ def select_shuffled(edge_list, key, n_verts, n_remove, seed, absorb=False):
     return sel.astype(bool), via, n
 
 
+def drop_unreferenced(res, nv=None):
+    """Removes the output vertices that no output facet refers to from a decimate / decimate_batch result
+    (in a copy): cluster ids of dropped clusters become -1; nv = per-mesh vertex counts of a batch."""
+    verts, facets, cid = _f32(res["verts"]).copy(), _i32(res["facets"]).reshape(-1, 3).copy(), _i32(res["cluster_id"]).copy()
+    nvo = _i32([verts.shape[0]] if nv is None else nv).copy()
+    st = lib().picasso_oracle_drop_unreferenced(_p(verts), _p(facets), facets.shape[0], _p(cid), cid.shape[0],
+                                                nvo.shape[0], _p(nvo))
+    if st != 0:
+        raise ValueError(f"oracle status {st}")
+    out = dict(res)
+    out.update(verts=verts[: int(nvo.sum())].copy(), facets=facets, cluster_id=cid)
+    if nv is not None:
+        out["nv"] = nvo
+    return out
+
+
 def decimate(verts, facets, target_nv, max_rounds=-1, return_quadrics=False, placement=PLACE_MEAN, rcond_min=0.0,
              absorb=False, shuffle_seed=0):
     """Returns dict(status, verts, facets, cluster_id, rounds[, quadrics])."""

@@ -656,17 +656,63 @@ int picasso_oracle_select_absorb(const int32_t* edges, const uint32_t* key, int3
 // v's cluster as an INPUT vertex index, the cluster's smallest member;
 // mapping[v] = the output index of v if v is that representative, -1 if v has
 // degenerated into another vertex.  So cluster_id[v] == mapping[replace[v]].
+// A vertex whose cluster was dropped (cluster id -1, see
+// picasso_oracle_drop_unreferenced) gets -1 in both.
 int picasso_oracle_replace_mapping(const int32_t* cluster_id, int32_t n_in, int32_t n_out, int32_t* replace,
                                    int32_t* mapping) {
-    if (!cluster_id || n_in < 1 || n_out < 1 || !replace || !mapping) return ERR_INVALID_ARG;
+    if (!cluster_id || n_in < 1 || n_out < 0 || !replace || !mapping) return ERR_INVALID_ARG;
     for (int v = 0; v < n_in; ++v)
-        if (cluster_id[v] < 0 || cluster_id[v] >= n_out) return ERR_BAD_INDEX;
+        if (cluster_id[v] < -1 || cluster_id[v] >= n_out) return ERR_BAD_INDEX;
     std::vector<int32_t> first(n_out, -1);
     for (int v = 0; v < n_in; ++v)
-        if (first[cluster_id[v]] < 0) first[cluster_id[v]] = v;
+        if (cluster_id[v] >= 0 && first[cluster_id[v]] < 0) first[cluster_id[v]] = v;
     for (int v = 0; v < n_in; ++v) {
+        if (cluster_id[v] < 0) {  // the vertex's cluster has degenerated and was dropped: nothing represents it
+            replace[v] = -1;
+            mapping[v] = -1;
+            continue;
+        }
         replace[v] = first[cluster_id[v]];
         mapping[v] = (replace[v] == v) ? cluster_id[v] : -1;
+    }
+    return OK;
+}
+
+// Degenerated vertices removed (Sec. 3, "Pooling and unpooling": the mapping tensor carries the
+// degenerated-vertex information; the paper leaves the definition to code it does not print).
+// Reading: an output vertex that no output facet refers to has degenerated -- its cluster no longer
+// touches the surface -- and is dropped from the output; the remaining output vertices keep their
+// order and are renumbered; every input vertex of a dropped cluster gets cluster id -1.  Applied to
+// the result of a decimation, in place: verts [sum nv_out, 3], facets [nf, 3], cluster_id [n_in], and
+// the per-mesh vertex counts nv_out [B] of a batch (B = 1 for a single mesh).
+int picasso_oracle_drop_unreferenced(float* verts, int32_t* facets, int32_t nf, int32_t* cluster_id, int32_t n_in,
+                                     int32_t B, int32_t* nv_out) {
+    if (!verts || (nf > 0 && !facets) || !cluster_id || B < 1 || !nv_out) return ERR_INVALID_ARG;
+    int64_t nv = 0;
+    for (int b = 0; b < B; ++b) nv += nv_out[b];
+    std::vector<uint8_t> used((size_t)nv, 0);
+    for (int64_t i = 0; i < 3 * (int64_t)nf; ++i) {
+        if (facets[i] < 0 || facets[i] >= nv) return ERR_BAD_INDEX;
+        used[facets[i]] = 1;
+    }
+    std::vector<int32_t> newid((size_t)nv, -1);
+    int32_t kept = 0;
+    int64_t v = 0;
+    for (int b = 0; b < B; ++b) {
+        int32_t kept_b = 0;
+        for (int32_t k = 0; k < nv_out[b]; ++k, ++v) {
+            if (!used[v]) continue;
+            newid[v] = kept;
+            for (int d = 0; d < 3; ++d) verts[3 * (size_t)kept + d] = verts[3 * (size_t)v + d];
+            ++kept;
+            ++kept_b;
+        }
+        nv_out[b] = kept_b;
+    }
+    for (int64_t i = 0; i < 3 * (int64_t)nf; ++i) facets[i] = newid[facets[i]];
+    for (int32_t o = 0; o < n_in; ++o) {
+        if (cluster_id[o] < 0 || cluster_id[o] >= nv) return ERR_BAD_INDEX;
+        cluster_id[o] = newid[cluster_id[o]];
     }
     return OK;
 }

@@ -39,6 +39,7 @@ struct State {
     int trunc_n;   // matched edges entering the budget truncation
     int sel_k;     // sub-round index the selection has reached (buffer rotation phase)
     int absorb_n;  // edges through which an un-paired vertex would join a pair's cluster (Alg. 2 line 11)
+    int nv_kept;   // output vertices that some output facet refers to (option: degenerated vertices dropped)
     // Written by every selection tail for kernels that the host queued behind it before looking
     // (they run only if the tail finished the matching): 1 / nv / nf / ne of the round then, else zeros.
     int go, guard_nv, guard_nf, guard_ne;
@@ -1947,23 +1948,57 @@ __global__ __launch_bounds__(BLOCK) void publish_header_kernel(int* __restrict__
     signal_host(done, threadIdx.x, (int)threadIdx.x < n);
 }
 
+// Degenerated vertices (option): ref[v] = 1 for every vertex that a facet of the final mesh refers to
+// (ref is cleared beforehand; all writers store the same value).
+__global__ __launch_bounds__(BLOCK) void mark_referenced_kernel(const int* __restrict__ fcur, const State* st, int cur,
+                                                                int* __restrict__ ref) {
+    const long long n = 3ll * st->nf[cur];
+    for (long long i = (long long)blockIdx.x * BLOCK + threadIdx.x; i < n; i += (long long)gridDim.x * BLOCK) ref[fcur[i]] = 1;
+}
+
+struct RefPred {
+    const int* ref;
+    __device__ bool operator()(int v) const { return ref[v] != 0; }
+};
+
+// newid[v] = number of referenced vertices in front of v, for EVERY vertex (so that the count in front
+// of a mesh's first vertex can be read off as well)
+struct RefOut {
+    static constexpr bool WAVE_WIDE = true;
+    int* newid;
+    __device__ void wave(int v, bool in_range, bool flagged, int pos) const {
+        (void)flagged;
+        if (in_range) newid[v] = pos;
+    }
+};
+
+// DROP: only the vertices with ref[v] != 0 go out, at newid[v]; facets and cluster ids follow that
+// numbering, cluster ids of dropped vertices become -1, and kept_per_mesh[b] receives mesh b's count.
+template <bool DROP>
 __global__ __launch_bounds__(BLOCK) void copy_out_kernel(const VRec* __restrict__ vrec, const int* __restrict__ fcur,
                                                          const int* __restrict__ cid, const State* st, int cur,
                                                          int n_orig, float* __restrict__ verts_out,
                                                          int* __restrict__ facets_out, int* __restrict__ cid_out,
                                                          int B, const int* __restrict__ voff,
-                                                         int* __restrict__ foff_out) {
+                                                         int* __restrict__ foff_out, const int* __restrict__ ref,
+                                                         const int* __restrict__ newid,
+                                                         int* __restrict__ kept_per_mesh) {
     const int nv = st->nv[cur], nf = st->nf[cur];
     const int stride = gridDim.x * BLOCK;
     const int g = blockIdx.x * BLOCK + threadIdx.x;
     for (int w = g; w < nv; w += stride) {
+        if (DROP && !ref[w]) continue;
+        const int o = DROP ? newid[w] : w;
         const float4 p = *reinterpret_cast<const float4*>(&vrec[w]);
-        verts_out[3 * (size_t)w] = p.x;
-        verts_out[3 * (size_t)w + 1] = p.y;
-        verts_out[3 * (size_t)w + 2] = p.z;
+        verts_out[3 * (size_t)o] = p.x;
+        verts_out[3 * (size_t)o + 1] = p.y;
+        verts_out[3 * (size_t)o + 2] = p.z;
     }
-    for (long long i = g; i < 3ll * nf; i += stride) facets_out[i] = fcur[i];
-    for (int o = g; o < n_orig; o += stride) cid_out[o] = cid[o];
+    for (long long i = g; i < 3ll * nf; i += stride) facets_out[i] = DROP ? newid[fcur[i]] : fcur[i];
+    for (int o = g; o < n_orig; o += stride) {
+        const int c = cid[o];
+        cid_out[o] = DROP ? (ref[c] ? newid[c] : -1) : c;
+    }
     // facets stay grouped by mesh: first facet whose leading vertex is at or past the mesh's first vertex
     for (int b = g; b <= B; b += stride) {
         int lo = 0, hi = nf;
@@ -1976,6 +2011,11 @@ __global__ __launch_bounds__(BLOCK) void copy_out_kernel(const VRec* __restrict_
             }
         }
         foff_out[b] = lo;
+        if (DROP && b < B) {
+            const int before = voff[b] < nv ? newid[voff[b]] : st->nv_kept;
+            const int upto = voff[b + 1] < nv ? newid[voff[b + 1]] : st->nv_kept;
+            kept_per_mesh[b] = upto - before;
+        }
     }
 }
 

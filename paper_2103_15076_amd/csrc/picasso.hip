@@ -109,6 +109,7 @@ struct picasso_ctx {
     int64_t opt_poll_us = 20000;  // for how long the host watches that word before it waits for the stream instead (0: not at all)
     int opt_ahead = 1;     // a round's contraction and facet kernels are queued before the host has looked
     int opt_trunc_width = 0;  // test hook: keys per lane of the per-mesh budget search (0: as the sizes need)
+    int opt_drop_degenerated = 0;  // output vertices that no output facet refers to are dropped
     hipEvent_t ev[2 * PICASSO_STATS_ROUNDS * PICASSO_ST_COUNT + 4];
     int n_ev = 0;
     hipEvent_t ev_total[2];
@@ -1010,9 +1011,23 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         if (st_err != PICASSO_OK) return st_err;
     }
 
-    copy_out_kernel<<<grid_for(std::max(std::max(N, 3 * nf_bound), 1), 8192), BLOCK, 0, s>>>(
-        c->vrec[cur], c->fbuf[cur], c->cid, c->st, cur, N, d_verts_out, d_facets_out, d_cluster_id, B, c->voff[cur],
-        c->foff_out);
+    const int out_grid = grid_for(std::max(std::max(N, 3 * nf_bound), 1), 8192);
+    if (c->opt_drop_degenerated) {
+        // output vertices that no output facet refers to are dropped: mark, number the others, copy out
+        int* ref = c->mate;  // (free once the rounds are over)
+        prim::fill_u32_kernel<<<grid_for(nv_total), BLOCK, 0, s>>>(reinterpret_cast<u32*>(ref), nv_total, 0u);
+        mark_referenced_kernel<<<grid_for(std::max(3 * nf_bound, 1), 8192), BLOCK, 0, s>>>(c->fbuf[cur], c->st, cur, ref);
+        const RefPred rp{ref};
+        const RefOut ro{c->newid};
+        prim::compact(s, rp, rp, ro, &c->st->nv[cur], nv_total, c->tilesum, &c->st->nv_kept);
+        copy_out_kernel<true><<<out_grid, BLOCK, 0, s>>>(c->vrec[cur], c->fbuf[cur], c->cid, c->st, cur, N, d_verts_out,
+                                                         d_facets_out, d_cluster_id, B, c->voff[cur], c->foff_out, ref,
+                                                         c->newid, c->matched);
+    } else {
+        copy_out_kernel<false><<<out_grid, BLOCK, 0, s>>>(c->vrec[cur], c->fbuf[cur], c->cid, c->st, cur, N, d_verts_out,
+                                                          d_facets_out, d_cluster_id, B, c->voff[cur], c->foff_out,
+                                                          nullptr, nullptr, nullptr);
+    }
     if (stats) HIP_TRY(c, hipEventRecord(c->ev_total[1], s));
     rc = read_header(c, s);
     if (rc != PICASSO_OK) return rc;
@@ -1048,13 +1063,14 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
 
     int warn = PICASSO_OK;
     for (int b = 0; b < B; ++b) {
-        h_nv_out[b] = nvb[b];
+        // (with degenerated vertices dropped, the last kernels have left the meshes' counts where the pair counts were)
+        h_nv_out[b] = c->opt_drop_degenerated ? c->h_pin[HDR_STATE_INTS + b] : nvb[b];
         h_nf_out[b] = h_foff[b + 1] - h_foff[b];
         if (nvb[b] > target_nv[b] && (c->opt_max_rounds < 0 || stuck[b])) warn = PICASSO_WARN_BUDGET_UNMET;
     }
     if (stats) {
         stats->rounds = round;
-        stats->nv_out = hst->nv[cur];
+        stats->nv_out = c->opt_drop_degenerated ? hst->nv_kept : hst->nv[cur];
         stats->nf_out = hst->nf[cur];
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, c->ev_total[0], c->ev_total[1]) == hipSuccess) stats->ms_total = ms;
@@ -1231,6 +1247,10 @@ int picasso_set_option(picasso_ctx* c, int option, int64_t value) {
         case PICASSO_OPT_LAUNCH_AHEAD:
             if (value != 0 && value != 1) return PICASSO_ERR_INVALID_ARG;
             c->opt_ahead = (int)value;
+            return PICASSO_OK;
+        case PICASSO_OPT_DROP_DEGENERATED:
+            if (value != 0 && value != 1) return PICASSO_ERR_INVALID_ARG;
+            c->opt_drop_degenerated = (int)value;
             return PICASSO_OK;
         case PICASSO_OPT_TRUNC_WIDTH:
             if (value != 0 && value != 4 && value != 8 && value != 16 && value != 32) return PICASSO_ERR_INVALID_ARG;
@@ -1632,12 +1652,13 @@ int picasso_f2v_backward(picasso_ctx* c, void* stream, const float* d_gx, const 
 
 int picasso_replace_mapping(picasso_ctx* c, void* stream, const int32_t* d_cluster_id, int32_t n_in, int32_t n_out,
                             int32_t* d_replace, int32_t* d_mapping) {
-    if (!c || !d_cluster_id || n_in < 1 || n_out < 1 || !d_replace || !d_mapping) return PICASSO_ERR_INVALID_ARG;
+    if (!c || !d_cluster_id || n_in < 1 || n_out < 0 || !d_replace || !d_mapping) return PICASSO_ERR_INVALID_ARG;
     if (n_out > c->max_verts) return PICASSO_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     HIP_TRY(c, hipSetDevice(c->device));
     prim::fill_u32_kernel<<<1, BLOCK, 0, s>>>(reinterpret_cast<u32*>(&c->st->err), 1, 0u);
-    prim::fill_u32_kernel<<<grid_for(n_out), BLOCK, 0, s>>>(reinterpret_cast<u32*>(c->newid), n_out, 0x7FFFFFFFu);
+    if (n_out > 0)
+        prim::fill_u32_kernel<<<grid_for(n_out), BLOCK, 0, s>>>(reinterpret_cast<u32*>(c->newid), n_out, 0x7FFFFFFFu);
     pool::cluster_first_kernel<<<pool::grid_for(n_in), pool::BLOCK, 0, s>>>(d_cluster_id, n_in, n_out, c->newid,
                                                                             &c->st->err);
     pool::replace_mapping_kernel<<<pool::grid_for(n_in), pool::BLOCK, 0, s>>>(d_cluster_id, n_in, n_out, c->newid,
@@ -1650,7 +1671,7 @@ int picasso_replace_mapping(picasso_ctx* c, void* stream, const int32_t* d_clust
 
 int picasso_replace_mapping_static(int device, void* stream, const int32_t* d_cluster_id, int32_t n_in, int32_t n_out,
                                    int32_t* d_replace, int32_t* d_mapping, int32_t* d_status) {
-    if (device < 0 || device >= STATIC_MAX_DEVICES || !d_cluster_id || n_in < 1 || n_out < 1 || !d_replace ||
+    if (device < 0 || device >= STATIC_MAX_DEVICES || !d_cluster_id || n_in < 1 || n_out < 0 || !d_replace ||
         !d_mapping || !d_status)
         return PICASSO_ERR_INVALID_ARG;
     if (n_out > PICASSO_STATIC_MAX_CLUSTERS) return PICASSO_ERR_WORKSPACE;

@@ -176,6 +176,7 @@ __global__ __launch_bounds__(BLOCK) void cluster_first_kernel(const int* __restr
     const int v = blockIdx.x * BLOCK + threadIdx.x;
     if (v >= n_in) return;
     const int c = cid[v];
+    if (c == -1) return;  // (the vertex's cluster was dropped: nothing represents it)
     if (c < 0 || c >= n_out) {
         atomicOr(err, 1);
         return;
@@ -189,10 +190,10 @@ __global__ __launch_bounds__(BLOCK) void replace_mapping_kernel(const int* __res
     const int v = blockIdx.x * BLOCK + threadIdx.x;
     if (v >= n_in) return;
     const int c = cid[v];
-    if (c < 0 || c >= n_out) return;  // (flagged by the first pass; the call reports it)
-    const int r = first[c];
+    if (c < -1 || c >= n_out) return;  // (flagged by the first pass; the call reports it)
+    const int r = c >= 0 ? first[c] : -1;
     replace[v] = r;
-    mapping[v] = (r == v) ? c : -1;
+    mapping[v] = (c >= 0 && r == v) ? c : -1;
 }
 
 // The two kernels in front of and behind cluster_first_kernel when the table of first members is the
@@ -213,10 +214,10 @@ __global__ __launch_bounds__(BLOCK) void replace_mapping_status_kernel(const int
     if (v == 0) *status = (*flag != 0) ? bad : ok;
     if (v >= n_in) return;
     const int c = cid[v];
-    if (c < 0 || c >= n_out) return;
-    const int r = first[c];
+    if (c < -1 || c >= n_out) return;
+    const int r = c >= 0 ? first[c] : -1;
     replace[v] = r;
-    mapping[v] = (r == v) ? c : -1;
+    mapping[v] = (c >= 0 && r == v) ? c : -1;
 }
 
 inline int grid_for(long long n) { return (int)((n + BLOCK - 1) / BLOCK > 0 ? (n + BLOCK - 1) / BLOCK : 1); }

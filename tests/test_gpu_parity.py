@@ -832,3 +832,71 @@ def test_budget_search_refuses_sizes_it_was_not_launched_for(pk, ctx, oracle):
     assert_same_result(st, vo, fo, cid, oracle.decimate(V, F, target))
     with pytest.raises(pk.PicassoError):
         ctx.set_option(pk.PICASSO_OPT_TRUNC_WIDTH, 5)
+
+
+def test_degenerated_vertices_dropped(pk, ctx, ctx16k, oracle):
+    """PICASSO_OPT_DROP_DEGENERATED: output vertices that no output facet refers to are dropped; against the
+    hand-worked fixture, and against the oracle's post-processing on soups, a room, a batch and a call
+    that runs zero rounds; replace / mapping (both entry points) take the -1 cluster ids."""
+    import json
+    import os
+    fx = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "drop_degenerated_hand.json")))
+
+    def check(c, V, F, target, ref):
+        st, vo, fo, cid = c.picasso_decimate(dev(V), dev(F), target)
+        assert vo.shape[0] == ref["verts"].shape[0]
+        assert np.array_equal(vo.cpu().numpy().view(np.uint32), ref["verts"].view(np.uint32))
+        assert np.array_equal(fo.cpu().numpy(), ref["facets"]) and np.array_equal(cid.cpu().numpy(), ref["cluster_id"])
+        return cid, vo.shape[0]
+
+    for c in (ctx, ctx16k):
+        c.set_option(pk.PICASSO_OPT_DROP_DEGENERATED, 1)
+    try:
+        V = np.asarray(fx["verts"], np.float32)
+        F = np.asarray(fx["facets"], np.int32)
+        for case in fx["cases"]:
+            print(f"drop degenerated: fixture target={case['target']}", flush=True)
+            st, vo, fo, cid = ctx.picasso_decimate(dev(V), dev(F), case["target"])
+            assert vo.cpu().numpy().tolist() == case["dropped"]["verts_out"]
+            assert fo.cpu().numpy().reshape(-1, 3).tolist() == case["dropped"]["facets_out"]
+            assert cid.cpu().numpy().tolist() == case["dropped"]["cluster_id"]
+            rep, mp = ctx.picasso_replace_mapping(cid, vo.shape[0])
+            assert rep.cpu().numpy().tolist() == case["dropped"]["replace"]
+            assert mp.cpu().numpy().tolist() == case["dropped"]["mapping"]
+            rep2, mp2 = torch.zeros_like(rep), torch.zeros_like(mp)
+            status = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+            assert pk.picasso_replace_mapping_static(cid, vo.shape[0], rep2, mp2, status) == pk.PICASSO_OK
+            torch.cuda.synchronize()
+            assert int(status.item()) == 0 and torch.equal(rep, rep2) and torch.equal(mp, mp2)
+        rng = np.random.default_rng(8)
+        for k in range(6):
+            nv = int(rng.integers(10, 400))
+            V = rng.normal(size=(nv, 3)).astype(np.float32)
+            F = rng.integers(0, max(3, nv * 2 // 3), size=(int(rng.integers(4, 600)), 3)).astype(np.int32)
+            target = max(2, nv // int(rng.integers(2, 6)))
+            print(f"drop degenerated: soup {k} nv={nv} target={target}", flush=True)
+            check(ctx, V, F, target, oracle.drop_unreferenced(oracle.decimate(V, F, target)))
+        V, F = meshgen.room_scene(5, room=(3.0, 2.0, 1.5), n_boxes=6, spacing=0.04)
+        V = np.concatenate([V, rng.normal(size=(100, 3)).astype(np.float32)])          # 100 vertices in no facet
+        for target in (V.shape[0] + 5, V.shape[0] // 3, 50):                            # zero rounds, a few, many
+            print(f"drop degenerated: room N={V.shape[0]} target={target}", flush=True)
+            cid, n_out = check(ctx, V, F, target, oracle.drop_unreferenced(oracle.decimate(V, F, target)))
+            assert int((cid[-100:] == -1).sum()) == 100
+        parts = [meshgen.noisy_grid(30, 22, seed=1), meshgen.icosphere(3, seed=2), meshgen.noisy_grid(12, 12, seed=3)]
+        parts[0] = (np.concatenate([parts[0][0], rng.normal(size=(7, 3)).astype(np.float32)]), parts[0][1])
+        nv = [p[0].shape[0] for p in parts]
+        nf = [p[1].shape[0] for p in parts]
+        off = np.cumsum([0] + nv)
+        V = np.concatenate([p[0] for p in parts])
+        F = np.concatenate([p[1] + off[i] for i, p in enumerate(parts)]).astype(np.int32)
+        tg = [200, 700, 4]
+        print("drop degenerated: batch", flush=True)
+        st, vo, fo, cid, nvo, nfo = ctx16k.picasso_decimate_batch(dev(V), dev(F), nv, nf, tg)
+        rb = oracle.decimate_batch(V, F, nv, nf, tg)
+        ref = oracle.drop_unreferenced(rb, nv=rb["nv"])
+        assert nvo.tolist() == ref["nv"].tolist() and nfo.tolist() == rb["nf"].tolist()
+        assert np.array_equal(vo.cpu().numpy().view(np.uint32), ref["verts"].view(np.uint32))
+        assert np.array_equal(fo.cpu().numpy(), ref["facets"]) and np.array_equal(cid.cpu().numpy(), ref["cluster_id"])
+    finally:
+        for c in (ctx, ctx16k):
+            c.set_option(pk.PICASSO_OPT_DROP_DEGENERATED, 0)

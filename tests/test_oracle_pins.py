@@ -572,3 +572,67 @@ def test_replace_and_mapping_invariants_on_a_decimation(oracle, absorb):
     if not absorb:
         # pairs only: output vertices are numbered in ascending order of their smallest member
         assert np.all(np.diff(mp[mp >= 0]) == 1)
+
+
+# ----------------------------------------------------------------------------
+# degenerated vertices dropped (Sec. 3, "Pooling and unpooling"; Alg. 2 output list)
+# ----------------------------------------------------------------------------
+
+def test_hand_worked_drop_of_degenerated_vertices(oracle):
+    fx = json.load(open(os.path.join(GOLD, "drop_degenerated_hand.json")))
+    V = np.asarray(fx["verts"], np.float32)
+    F = np.asarray(fx["facets"], np.int32)
+    for case in fx["cases"]:
+        r = oracle.decimate(V, F, case["target"])
+        assert r["verts"].tolist() == case["kept"]["verts_out"]
+        assert r["facets"].reshape(-1, 3).tolist() == case["kept"]["facets_out"]
+        assert r["cluster_id"].tolist() == case["kept"]["cluster_id"]
+        d = oracle.drop_unreferenced(r)
+        assert d["verts"].tolist() == case["dropped"]["verts_out"]
+        assert d["facets"].reshape(-1, 3).tolist() == case["dropped"]["facets_out"]
+        assert d["cluster_id"].tolist() == case["dropped"]["cluster_id"]
+        rep, mp = oracle.replace_mapping(d["cluster_id"], d["verts"].shape[0])
+        assert rep.tolist() == case["dropped"]["replace"] and mp.tolist() == case["dropped"]["mapping"]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_drop_of_degenerated_vertices_against_numpy(oracle, seed):
+    """Random soups with unused input vertices and facets that collapse: the kept vertices are exactly those
+    some output facet refers to, in their old order; facets and cluster ids follow the renumbering."""
+    rng = np.random.default_rng(40 + seed)
+    nv = int(rng.integers(10, 60))
+    V = rng.normal(size=(nv, 3)).astype(np.float32)
+    F = rng.integers(0, max(3, nv * 2 // 3), size=(int(rng.integers(4, 50)), 3)).astype(np.int32)   # the upper third unused
+    r = oracle.decimate(V, F, max(2, nv // 3))
+    d = oracle.drop_unreferenced(r)
+    used = np.zeros(r["verts"].shape[0], bool)
+    used[r["facets"].reshape(-1)] = True
+    newid = np.where(used, np.cumsum(used) - 1, -1)
+    assert np.array_equal(d["verts"], r["verts"][used])
+    assert np.array_equal(d["facets"], newid[r["facets"]])
+    assert np.array_equal(d["cluster_id"], newid[r["cluster_id"]])
+    assert d["verts"].shape[0] == int(used.sum())
+
+
+def test_drop_of_degenerated_vertices_in_a_batch_counts_per_mesh(oracle):
+    parts = [meshgen.noisy_grid(6, 5, seed=1), meshgen.icosphere(1, seed=2), meshgen.noisy_grid(4, 4, seed=3)]
+    extra = np.random.default_rng(0).normal(size=(3, 3)).astype(np.float32)       # three unused vertices behind mesh 0
+    parts[0] = (np.concatenate([parts[0][0], extra]), parts[0][1])
+    nv = [p[0].shape[0] for p in parts]
+    nf = [p[1].shape[0] for p in parts]
+    off = np.cumsum([0] + nv)
+    V = np.concatenate([p[0] for p in parts])
+    F = np.concatenate([p[1] + off[i] for i, p in enumerate(parts)]).astype(np.int32)
+    tg = [12, 20, 3]
+    rb = oracle.decimate_batch(V, F, nv, nf, tg)
+    db = oracle.drop_unreferenced(rb, nv=rb["nv"])
+    vo = 0
+    for i, (v, f) in enumerate(parts):
+        d = oracle.drop_unreferenced(oracle.decimate(v, f, tg[i]))
+        n = d["verts"].shape[0]
+        assert db["nv"][i] == n
+        assert np.array_equal(db["verts"][vo:vo + n], d["verts"])
+        cid = d["cluster_id"]
+        assert np.array_equal(db["cluster_id"][off[i]:off[i + 1]], np.where(cid >= 0, cid + vo, -1))
+        vo += n
+    assert db["nv"][0] <= 12 - 3      # the unused vertices of mesh 0 are gone

@@ -62,7 +62,7 @@ def test_static_entry_point_reports_a_bad_index_on_the_device_and_recovers(pk):
     st, _, _, status = _static(pk, torch.from_numpy(bad).to("cuda:0"), 900)
     torch.cuda.synchronize()
     assert st == pk.PICASSO_OK and int(status.item()) == pk.PICASSO_ERR_BAD_INDEX
-    bad[1234] = -1
+    bad[1234] = -2            # (-1 alone is legal: a vertex whose cluster was dropped)
     st, _, _, status = _static(pk, torch.from_numpy(bad).to("cuda:0"), 900)
     torch.cuda.synchronize()
     assert st == pk.PICASSO_OK and int(status.item()) == pk.PICASSO_ERR_BAD_INDEX
@@ -79,7 +79,7 @@ def test_static_entry_point_rejects_what_it_cannot_hold(pk):
     status = torch.zeros(1, dtype=torch.int32, device="cuda:0")
     f = pk.picasso_replace_mapping_static
     assert f(d, pk.PICASSO_STATIC_MAX_CLUSTERS + 1, out, out.clone(), status) == pk.PICASSO_ERR_WORKSPACE
-    assert f(d, 0, out, out.clone(), status) == pk.PICASSO_ERR_INVALID_ARG
+    assert f(d, -1, out, out.clone(), status) == pk.PICASSO_ERR_INVALID_ARG
     assert f(d, 4, out, out.clone(), status, device=64) == pk.PICASSO_ERR_INVALID_ARG
     assert f(d, 4, out, out.clone(), status, device=-1) == pk.PICASSO_ERR_INVALID_ARG
     # the largest table it holds
