@@ -54,7 +54,7 @@ def measured_traffic(workload):
     return out if ok else {}
 
 
-KERNEL_KEYS = ("sort", "unique_cost", "subround0", "facet_insert", "quadric_rows")
+KERNEL_KEYS = ("sort", "unique_cost", "subround0", "facet_insert", "quadric_rows", "sort_incidence")
 
 
 def main():

@@ -56,7 +56,9 @@ enum picasso_option {
     PICASSO_OPT_KERNEL_TIMING = 3, /* N > 0: in every N-th decimate call from now on, bracket the
                                       launches of the path's largest kernels with hipEvents
                                       (see picasso_kernel_timing); an event pair costs several
-                                      microseconds of queue time per launch; 0: off                */
+                                      microseconds of queue time per launch, and such a call keeps
+                                      all its work on `stream` (as with PICASSO_OPT_OVERLAP 0), so
+                                      that a bracketed kernel runs alone on the chip; 0: off       */
     PICASSO_OPT_OVERLAP = 4,       /* 1 (default): for inputs of 2^18 facets or more, the first
                                       round's edge-key sort runs on a stream of the context's own
                                       beside the vertex quadrics and joins `stream` before costs
@@ -182,14 +184,17 @@ const char* picasso_last_hip_error(picasso_ctx* ctx);
  *                 12 nf read + 12 nf re-indexed + 4 nf deciding slot + 4 nf table slot + 4 nv
  *                 (vertex map) + 8 N (labels read and written).
  *   QUADRIC_ROWS  vertex quadrics summed from the facets' planes (supplementary, vertex quadric
- *                 equation): 8 x 3F sorted incidences + 16 F planes + 12 N positions + 64 N records. */
+ *                 equation): 8 x 3F sorted incidences + 16 F planes + 12 N positions + 64 N records.
+ *   SORT_INCIDENCE per-bucket kernel of the sort that brings the 3F (vertex, facet) incidence keys
+ *                 into vertex order for the vertex quadrics (once per call): 16 x 3F. */
 enum picasso_timed_kernel {
     PICASSO_KERNEL_SORT = 0,
     PICASSO_KERNEL_UNIQUE_COST = 1,
     PICASSO_KERNEL_SUBROUND0 = 2,
     PICASSO_KERNEL_FACET_INSERT = 3,
     PICASSO_KERNEL_QUADRIC_ROWS = 4,
-    PICASSO_KERNEL_COUNT = 5
+    PICASSO_KERNEL_SORT_INCIDENCE = 5,
+    PICASSO_KERNEL_COUNT = 6
 };
 
 /* Totals gathered for `kernel` while PICASSO_OPT_KERNEL_TIMING is on, over all decimate calls

@@ -38,13 +38,14 @@ PICASSO_OPT_DROP_DEGENERATED = 13
 PICASSO_PLACE_MEAN, PICASSO_PLACE_INVERSE = 0, 1
 
 (PICASSO_KERNEL_SORT, PICASSO_KERNEL_UNIQUE_COST, PICASSO_KERNEL_SUBROUND0, PICASSO_KERNEL_FACET_INSERT,
- PICASSO_KERNEL_QUADRIC_ROWS, PICASSO_KERNEL_COUNT) = range(6)
+ PICASSO_KERNEL_QUADRIC_ROWS, PICASSO_KERNEL_SORT_INCIDENCE, PICASSO_KERNEL_COUNT) = range(7)
 TIMED_KERNEL_NAMES = (
     "bucket_keys_kernel<u64> (edge-key sort, per-bucket LDS sort)",
     "tile_scatter_kernel<UniquePred, UniqueOut> (distinct edges, costs, first bids)",
     "select_subround_kernel (first sub-round of the selection)",
     "facet_insert_kernel (facet hash set, label compose)",
     "quadric_rows_kernel (vertex quadrics from facet planes)",
+    "bucket_keys_kernel<u64> (incidence-key sort of the vertex quadrics, per-bucket LDS sort)",
 )
 
 PICASSO_STATS_ROUNDS = 32

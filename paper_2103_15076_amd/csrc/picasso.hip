@@ -417,8 +417,9 @@ int run_vertex_quadrics(picasso_ctx* c, hipStream_t s, const float* d_verts, int
         const bool counted = sort_by_vertex_path(H, kb) != COUNT_NONE;
         const IncidenceKeys src{c->fbuf[0], fbits};  // (the counted sorts read the keys from here)
         int where = sort_by_vertex<u64, false, IncidenceKeys>(s, c->s0_key[0], c->s0_key[1], nullptr, nullptr,
-                                                                  nullptr, H, kb, c->sort_sc_s0, c->hist12_s0, nullptr,
-                                                                  0, counted, &src);
+                                                                  nullptr, H, kb, c->sort_sc_s0, c->hist12_s0,
+                                                                  c->kt_this_call ? &c->kt : nullptr,
+                                                                  PICASSO_KERNEL_SORT_INCIDENCE << 8, counted, &src);
         if (where < 0) return PICASSO_ERR_HIP;
         const u64* skey = where ? c->s0_key[1] : c->s0_key[0];
         const int tiles = (H + QR_TILE - 1) / QR_TILE;
@@ -683,10 +684,12 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
 
     // In the first round the vertex quadrics (S0) and the edge keys (S1) depend only on the validated
     // input, not on each other: S1's prefix goes to the context's side stream and joins before the
-    // costs are computed.  (Serial when stage times are being recorded, to keep them attributable.)
+    // costs are computed.  (Serial when stage times are being recorded, to keep them attributable, and in a
+    // call whose kernels are bracketed by events: a bracketed kernel then has the chip to itself, and its
+    // duration is its own.)
     // The fork and join cost about as much as a few small kernels, so small inputs stay on one stream.
     const u64* skeys = nullptr;
-    const bool overlap = work && c->opt_overlap && c->side && !tm.on && F >= OVERLAP_MIN_FACETS;
+    const bool overlap = work && c->opt_overlap && c->side && !tm.on && !c->kt_this_call && F >= OVERLAP_MIN_FACETS;
     tm.begin(0, PICASSO_ST_QUADRICS);
     rc = launch_init(c, s, d_verts, N, d_facets, F, B, work, hinit);
     if (rc != PICASSO_OK) return rc;
@@ -1053,6 +1056,7 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
                 case PICASSO_KERNEL_UNIQUE_COST: bytes = 8.0 * H + 13.0 * ne + 72.0 * nv; break;
                 case PICASSO_KERNEL_SUBROUND0: bytes = 14.0 * ne + 24.0 * nv; break;
                 case PICASSO_KERNEL_FACET_INSERT: bytes = 32.0 * nf + 4.0 * nv + 8.0 * (double)N; break;
+                case PICASSO_KERNEL_SORT_INCIDENCE: bytes = 48.0 * (double)F; break;
                 default: bytes = 24.0 * (double)F + 16.0 * (double)F + 76.0 * (double)N; break;  // QUADRIC_ROWS
             }
             c->kt_launches[kernel] += 1;

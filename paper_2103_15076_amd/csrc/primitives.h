@@ -784,7 +784,8 @@ __global__ __launch_bounds__(THREADS) void bucket_keys_kernel(K* __restrict__ ki
     constexpr int TALLY = (CAP >> 8) + 2;  // tiles (of at least 256 positions) that CAP consecutive positions can touch
     static_assert(TALLY <= THREADS, "one thread per tile of the tally");
     __shared__ int tcnt[COUNT_UNIQUE ? TALLY : 1];
-    const int t = threadIdx.x, lane = lane_id(), w = wave_id();
+    const int t = threadIdx.x, lane = lane_id();
+    const int w = __builtin_amdgcn_readfirstlane(wave_id());  // (in a scalar register: what follows from it is computed once per wave)
     const int bkt = (int)blockIdx.x;
     const int cnt = (int)totals[bkt];
     if (cnt == 0) return;
@@ -876,7 +877,22 @@ __global__ __launch_bounds__(THREADS) void bucket_keys_kernel(K* __restrict__ ki
         // part, and once more for the groups' sizes) and sorted like a bucket that fits.
         for (int i = t; i < (int)R; i += THREADS) gcnt[i] = 0;
         __syncthreads();
-        for (int i = t; i < cnt; i += THREADS) atomicAdd(&gcnt[digit_of<LK>((LK)kin[i], rest, dmask)], 1u);
+        // fn(key) for every key of the bucket; a thread's loads go out ITEMS at a time, so that a pass over
+        // the bucket waits for memory once per CAP keys and not once per key of the thread
+        auto for_each_key = [&](auto fn) {
+            for (int base = 0; base < cnt; base += CAP) {
+                LK kreg[ITEMS];
+#pragma unroll
+                for (int i = 0; i < ITEMS; ++i) {
+                    const int idx = base + i * THREADS + t;
+                    kreg[i] = idx < cnt ? (LK)kin[idx] : (LK)0;
+                }
+#pragma unroll
+                for (int i = 0; i < ITEMS; ++i)
+                    if (base + i * THREADS + t < cnt) fn(kreg[i]);
+            }
+        };
+        for_each_key([&](LK k) { atomicAdd(&gcnt[digit_of<LK>(k, rest, dmask)], 1u); });
         __syncthreads();
         u32 c[PER], sum = 0, tot;
         int too_long = 0;
@@ -897,17 +913,23 @@ __global__ __launch_bounds__(THREADS) void bucket_keys_kernel(K* __restrict__ ki
         if (t == 0) gstart[R] = (u32)cnt;
         if (!__syncthreads_or(too_long) && rest > 0 && cnt <= 16 * CAP) {
             for (int g0 = 0; g0 < (int)R;) {
-                int g1 = g0 + 1;  // (a group has at most 64 keys: at least one fits)
-                while (g1 < (int)R && gstart[g1 + 1] - gstart[g0] <= (u32)CAP) ++g1;
+                // the longest run of whole groups from g0 on with at most CAP keys (a group has at most 64
+                // keys, so at least one fits): gstart ascends, the run's end is found by bisection
+                int g1 = g0 + 1, g_hi = (int)R;
+                const u32 part_end = gstart[g0] + (u32)CAP;
+                while (g1 < g_hi) {
+                    const int mid = (g1 + g_hi + 1) >> 1;
+                    if (gstart[mid] <= part_end) g1 = mid;
+                    else g_hi = mid - 1;
+                }
                 const int part0 = (int)gstart[g0], part_n = (int)gstart[g1] - part0;
                 if (part_n > 0) {
                     for (int i = g0 + t; i < g1; i += THREADS) gcnt[i] = 0;
                     __syncthreads();
-                    for (int i = t; i < cnt; i += THREADS) {
-                        const LK k = (LK)kin[i];
+                    for_each_key([&](LK k) {
                         const int d = (int)digit_of<LK>(k, rest, dmask);
                         if (d >= g0 && d < g1) skey[gstart[d] - (u32)part0 + atomicAdd(&gcnt[d], 1u)] = k;
-                    }
+                    });
                     __syncthreads();
                     sort_groups(g0, g1);
                     for (int i0 = w * 64; i0 < part_n; i0 += THREADS) {  // (whole waves, for the ballot)
