@@ -192,7 +192,7 @@ def main():
 
     # ---- timed region: exactly K steps, hipEvents on the launch stream + wall clock
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    ctx.set_option(pk.PICASSO_OPT_KERNEL_TIMING, 0 if args.no_kernel_events else max(1, args.kernel_events_every))
+    every = max(1, args.kernel_events_every)   # kernel events in every `every`-th step: all calls of such a step
     if args.single_stream:
         ctx.set_option(pk.PICASSO_OPT_OVERLAP, 0)
     for k in range(pk.PICASSO_KERNEL_COUNT):
@@ -201,7 +201,9 @@ def main():
     level_ms = [0.0] * levels
     t0 = time.perf_counter()
     ev0.record(stream)
-    for _ in range(args.steps):
+    for k_step in range(args.steps):
+        if not args.no_kernel_events:
+            ctx.set_option(pk.PICASSO_OPT_KERNEL_TIMING, 1 if k_step % every == 0 else 0)
         res, res_levels = step(record=levels > 1)
         if levels > 1:   # (the host has waited for every level's work; the last event follows it at once)
             lev_ev[levels].synchronize()
@@ -230,6 +232,7 @@ def main():
     # Roofline: every bracketed kernel against the HBM peak (algorithmic bytes per launch / average
     # launch time); the headline entry is the kernel with the largest share of the step.
     traffic = measured_traffic(args.workload)
+    timed_steps = (args.steps + every - 1) // every
     by_kernel = []
     for key, kt in zip(KERNEL_KEYS, kts):
         if kt["launches"] == 0:
@@ -239,9 +242,9 @@ def main():
         achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
         by_kernel.append({"bound": "hbm", "kernel": kt["kernel"], "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                           "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": traffic.get(key),
-                          "launches_timed": kt["launches"], "events_every_n_steps": max(1, args.kernel_events_every),
+                          "launches_timed": kt["launches"], "events_every_n_steps": every,
                           "avg_launch_us": round(avg_ms * 1e3, 3), "algorithmic_bytes_per_launch": int(bytes_per_launch),
-                          "event_ms_per_timed_step": round(kt["ms_total"] * max(1, args.kernel_events_every) / args.steps, 4)})
+                          "event_ms_per_timed_step": round(kt["ms_total"] / timed_steps, 4)})
     by_kernel.sort(key=lambda r: -r["event_ms_per_timed_step"])
     roofline = by_kernel[0] if by_kernel else None
 

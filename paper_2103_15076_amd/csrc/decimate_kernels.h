@@ -277,18 +277,11 @@ __global__ __launch_bounds__(BLOCK) void init_kernel(const float* __restrict__ v
                 if (ikey) ikey[3 * (size_t)f + c] = k;
             }
             if constexpr (COUNT != COUNT_NONE) {
-                // neighbouring facets mostly refer to vertices with the same leading bits: a wave
-                // whose keys all have one digit counts itself with a single LDS atomic
+                // neighbouring facets mostly refer to vertices with the same leading bits: the lanes of a
+                // wave that share a digit count themselves with a single LDS atomic
                 const u32 d = (u32)(k >> ishift) & (u32)(RADIX - 1);
-                const u64 on = __ballot(ok);
-                if (on != 0) {
-                    const u32 d0 = (u32)__builtin_amdgcn_readfirstlane((int)d);
-                    if (__ballot(ok && d == d0) == on) {
-                        if (ok && (on & prim::lanemask_lt()) == 0) atomicAdd(&hist[d0], (u32)__popcll(on));
-                    } else if (ok) {
-                        atomicAdd(&hist[d], 1u);
-                    }
-                }
+                const u64 same = prim::wave_same_digit_lanes(ok, d);
+                if (ok && (same & prim::lanemask_lt()) == 0) atomicAdd(&hist[d], (u32)__popcll(same));
             }
         }
         // the facet's plane, once per facet, for the vertex quadrics that S0 sums from it
@@ -525,18 +518,11 @@ __global__ __launch_bounds__(BLOCK) void edge_keys_kernel(const int* __restrict_
                 if (keys) keys[idx] = k;  // (the counted sorts make the keys again from fcur)
             }
             if constexpr (COUNT != COUNT_NONE) {
-                // the lower vertices of neighbouring corners mostly share their leading bits: a wave
-                // whose keys all have one digit counts itself with a single LDS atomic
+                // the lower vertices of neighbouring corners mostly share their leading bits: the lanes of
+                // a wave that share a digit count themselves with a single LDS atomic
                 const u32 d = (u32)(k >> shift) & (u32)(RADIX - 1);
-                const u64 on = __ballot(ok);
-                if (on != 0) {
-                    const u32 d0 = (u32)__builtin_amdgcn_readfirstlane((int)d);
-                    if (__ballot(ok && d == d0) == on) {
-                        if (ok && (on & prim::lanemask_lt()) == 0) atomicAdd(&hist[d0], (u32)__popcll(on));
-                    } else if (ok) {
-                        atomicAdd(&hist[d], 1u);
-                    }
-                }
+                const u64 same = prim::wave_same_digit_lanes(ok, d);
+                if (ok && (same & prim::lanemask_lt()) == 0) atomicAdd(&hist[d], (u32)__popcll(same));
             }
         }
         if constexpr (COUNT != COUNT_NONE) {
@@ -1849,6 +1835,21 @@ __device__ __forceinline__ u32 hash3(int a, int b, int c) {
     return h;
 }
 
+// Where a triple's search of the table starts: the table follows the vertex numbering (the triple's
+// smallest vertex x, scaled from the round's new vertex count to the number of slots; the same x always
+// gives the same place, which is all the table needs), plus a few bits of the triple's hash.
+// Facets that are neighbours in the mesh are neighbours in the facet list and have nearby smallest
+// vertices, so the lanes that handle them meet in the same cache lines of the table, where a uniform
+// hash would fetch, and later write back, a whole line for nearly every facet (and the keep test
+// that follows reads the table the same way).  Measured at 1.2 M vertices: 3 hash bits are best; with
+// none the facets of one vertex collide, with 6 or 9 the lines are shared by fewer facets.
+constexpr int FACET_HOME_WINDOW_BITS = 3;
+constexpr int FACET_HOME_PROBES = 8;
+__device__ __forceinline__ u32 facet_home(int x, u32 hx, float slots_per_vertex) {
+    const float at = (float)x * slots_per_vertex;  // (below 2^32: x is below the vertex count)
+    return (u32)at + (hx & ((1u << FACET_HOME_WINDOW_BITS) - 1u));
+}
+
 // Re-indexes every facet and enters the non-collapsed ones into an open-
 // addressing table keyed by the unordered vertex triple.  A slot stores a
 // facet index; the slot's identity is that facet's triple, and among equal
@@ -1866,6 +1867,8 @@ __global__ __launch_bounds__(BLOCK) void facet_insert_kernel(const int* __restri
     const int nf = st->nf[cur];
     const int stride = gridDim.x * BLOCK;
     const int g = blockIdx.x * BLOCK + threadIdx.x;
+    const int nv_new = st->nv[cur ^ 1];  // (the renumbering before this kernel has left the count there)
+    const float slots_per_vertex = ((float)hmask + 1.0f) / (float)(nv_new > 0 ? nv_new : 1);
     // (the label of this thread's first original vertex is asked for now, so that it arrives while the
     // facet is being worked on; it is composed with the new numbering at the end)
     const int first_label = g < n_orig ? cid[g] : 0;
@@ -1887,8 +1890,9 @@ __global__ __launch_bounds__(BLOCK) void facet_insert_kernel(const int* __restri
         }
         int x = a, y = b, z = c;
         sort3(x, y, z);
-        u32 h = hash3(x, y, z) & hmask;
-        for (;;) {
+        const u32 hx = hash3(x, y, z);
+        u32 h = facet_home(x, hx, slots_per_vertex) & hmask;
+        for (int probe = 1;; ++probe) {
             const int old = atomicCAS(&htab[h], -1, f);
             if (old == -1) break;
             if (old == f) break;
@@ -1898,7 +1902,9 @@ __global__ __launch_bounds__(BLOCK) void facet_insert_kernel(const int* __restri
                 atomicMin(&htab[h], f);
                 break;
             }
-            h = (h + 1) & hmask;
+            // a few steps along the line, then (a crowded stretch: a vertex with very many facets) on from
+            // a place that the whole triple decides
+            h = (probe == FACET_HOME_PROBES ? hx : h + 1u) & hmask;
         }
         fslot[f] = (int)h;
     }

@@ -19,6 +19,27 @@ __device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & 63); }
 __device__ __forceinline__ int wave_id() { return (int)(threadIdx.x >> 6); }
 __device__ __forceinline__ u64 lanemask_lt() { return (1ull << lane_id()) - 1ull; }
 
+// For a lane with `ok`: the lanes of its wave (itself included) that hold the same digit `d`, worked out
+// for the first WAVE_DIGIT_PEEL distinct digits among the wave's lanes; a lane whose digit comes after
+// those is left alone in its mask.  Lanes without `ok` get 0.  Keys in mesh order mostly bring one to
+// three distinct leading digits into a wave, so one LDS atomic per digit (by the first lane of each
+// mask, adding the mask's population) replaces up to 64 atomics on the same address.  By all lanes.
+constexpr int WAVE_DIGIT_PEEL = 4;
+__device__ __forceinline__ u64 wave_same_digit_lanes(bool ok, u32 d) {
+    u64 rem = __ballot(ok);
+    u64 mine = ok ? (1ull << lane_id()) : 0ull;
+#pragma unroll
+    for (int j = 0; j < WAVE_DIGIT_PEEL; ++j) {
+        if (rem == 0) break;
+        const int lead = __ffsll((long long)rem) - 1;
+        const u32 d0 = (u32)__builtin_amdgcn_readlane((int)d, lead);
+        const u64 m = __ballot(ok && d == d0);
+        if (ok && d == d0) mine = m;
+        rem &= ~m;
+    }
+    return mine;
+}
+
 // Reads a count that lives either on the device (n_ptr) or in the launch arguments.
 __device__ __forceinline__ int load_count(const int* n_ptr, int n_host) { return n_ptr ? *n_ptr : n_host; }
 
@@ -1134,8 +1155,8 @@ __global__ __launch_bounds__(BLOCK) void msd_histogram_kernel(const K* __restric
 // digit's range with one returning atomic per digit it holds, and writes its keys there.  The
 // order of the keys inside a digit's range depends on the order in which tiles arrive, so this is
 // for sorts that then order each range on the whole key; with equal keys indistinguishable the
-// final result does not depend on it.  A wave whose keys share one digit (the common case for
-// keys led by mesh indices) ranks itself with one LDS atomic and writes one contiguous run.
+// final result does not depend on it.  The lanes of a wave whose keys share a digit (keys led by
+// mesh indices bring few distinct digits into a wave) rank themselves with one LDS atomic.
 // A key source gives key i of the input: an array, or a functor that makes the key on the fly (so
 // that keys which are a cheap function of other data need not be written out and read back).
 template <typename K>
@@ -1193,18 +1214,12 @@ __global__ __launch_bounds__(BLOCK) void msd_scatter_kernel(Src kin, K* __restri
         const long long idx = base + (long long)w * (64 * ITEMS) + i * 64 + lane;
         const bool ok = idx < n;
         const u32 d = digit_of<K>(key[i], shift, R - 1);
-        const u64 on = __ballot(ok);
-        rk[i] = 0;
-        if (on == 0) continue;
-        const int lead = __ffsll((long long)on) - 1;
-        const u32 d0 = (u32)__shfl((int)d, lead, 64);
-        if (__ballot(ok && d == d0) == on) {
-            u32 b = 0;
-            if (lane == lead) b = atomicAdd(&h[d0], (u32)__popcll(on));
-            rk[i] = (u32)__shfl((int)b, lead, 64) + (u32)__popcll(on & lt);
-        } else if (ok) {
-            rk[i] = atomicAdd(&h[d], 1u);
-        }
+        // the lanes that share a digit rank themselves with one returning atomic, by the first of them
+        const u64 same = wave_same_digit_lanes(ok, d);
+        u32 b = 0;
+        if (ok && (same & lt) == 0) b = atomicAdd(&h[d], (u32)__popcll(same));
+        b = (u32)__shfl((int)b, ok ? __ffsll((long long)same) - 1 : lane, 64);
+        rk[i] = b + (u32)__popcll(same & lt);
     }
     __syncthreads();
     for (int d = t; d < R; d += BLOCK) {
