@@ -120,7 +120,7 @@ enum picasso_option {
                                       that many, so that a mesh with more pairs than fit makes
                                       the kernel report it and the call return
                                       PICASSO_ERR_INTERNAL instead of a wrong budget.            */
-    PICASSO_OPT_DROP_DEGENERATED = 13 /* 1: degenerated vertices are removed (Sec. 3, "Pooling and
+    PICASSO_OPT_DROP_DEGENERATED = 13, /* 1: degenerated vertices are removed (Sec. 3, "Pooling and
                                       unpooling": the mapping tensor's degenerated-vertex
                                       information; the paper leaves its definition to code it does
                                       not print).  An output vertex that no output facet refers
@@ -130,6 +130,12 @@ enum picasso_option {
                                       renumbered, nv_out counts them (it may fall below target_nv),
                                       and d_cluster_id holds -1 for the input vertices of dropped
                                       clusters.  0 (default): every cluster stays an output vertex. */
+    PICASSO_OPT_TRUNC_SELECT = 14  /* budget step (Alg. 2 lines 3-4 and 6) of a single mesh that
+                                      formed more pairs than PICASSO_OPT_TRUNC_BLOCK_MAX, ties in
+                                      index order: 1 (default) = the cost key at the budget is
+                                      found by three histogram passes over the pairs' cost keys;
+                                      0 = the pairs are sorted, as they are for a batch or with a
+                                      shuffle seed.  Same results.                               */
 };
 
 #define PICASSO_STATS_ROUNDS 32

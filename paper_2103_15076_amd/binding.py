@@ -35,6 +35,7 @@ PICASSO_OPT_HOST_POLL = 10
 PICASSO_OPT_LAUNCH_AHEAD = 11
 PICASSO_OPT_TRUNC_WIDTH = 12
 PICASSO_OPT_DROP_DEGENERATED = 13
+PICASSO_OPT_TRUNC_SELECT = 14
 PICASSO_PLACE_MEAN, PICASSO_PLACE_INVERSE = 0, 1
 
 (PICASSO_KERNEL_SORT, PICASSO_KERNEL_UNIQUE_COST, PICASSO_KERNEL_SUBROUND0, PICASSO_KERNEL_FACET_INSERT,

@@ -361,8 +361,7 @@ __global__ __launch_bounds__(BLOCK) void quadric_rows_kernel(VRec* __restrict__ 
         for (int v = blockIdx.x * BLOCK + t; v < N; v += gridDim.x * BLOCK) write_vertex_record(vrec, verts, v, zero);
         return;
     }
-    // workgroups go to the 8 dies in turn; each die (its own L2) takes one contiguous eighth of the tiles
-    const long long tile = (long long)(blockIdx.x & 7u) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const long long tile = blockIdx.x;
     const long long base = tile * QR_TILE;
     if (base >= H) return;
     const int tile_n = (int)((long long)H - base < QR_TILE ? (long long)H - base : QR_TILE);
@@ -1483,6 +1482,112 @@ __global__ __launch_bounds__(TRUNC_THREADS) void trunc_block_kernel(u32* __restr
         if (valid) tcost[i] = (gt || (eq && rank >= kk)) ? 1u : 0u;  // the key's slot now holds the flag
     }
 }
+
+// ---------------------------------------------------------------------------
+// Budget for ONE long run (a single mesh that formed more pairs than one workgroup's registers hold)
+// without sorting it: the cost key of the nrem-th smallest pair is found digit by digit, from the top,
+// by histograms over the gathered cost keys (tcost, in edge order): three passes of 11, 11 and 10 bits,
+// each a wide kernel that counts the keys which share the digits decided so far, and one small
+// workgroup that picks the digit in which the count crosses nrem.  Then the pairs with exactly that
+// key are ranked in edge order by the atomic-free scan, and every pair above the key, or at the key but
+// beyond the budget, is flagged for trunc_release_kernel, as trunc_block_kernel does it.
+// ---------------------------------------------------------------------------
+constexpr int SELECT_BINS = 1 << 11;
+struct SelectState {
+    u32 prefix;  // the digits decided so far, right-aligned (after the last pass: the threshold key)
+    u32 below;   // keys smaller than every key that starts with `prefix`
+    u32 keep;    // (after the last pass) how many of the pairs with exactly the threshold key stay
+    u32 pad;
+    u32 hist[SELECT_BINS];
+};
+__device__ __forceinline__ int select_shift(int pass) { return pass == 0 ? 21 : (pass == 1 ? 10 : 0); }
+__device__ __forceinline__ int select_bits(int pass) { return pass == 2 ? 10 : 11; }
+
+constexpr int SELECT_ITEMS = 8;
+template <int PASS>
+__global__ __launch_bounds__(BLOCK) void trunc_select_hist_kernel(const u32* __restrict__ tcost, const State* st,
+                                                                  SelectState* __restrict__ S) {
+    __shared__ u32 h[SELECT_BINS];
+    const int n = st->trunc_n;
+    const long long base = (long long)blockIdx.x * (BLOCK * SELECT_ITEMS);
+    if (base >= n) return;
+    const int t = threadIdx.x;
+    for (int i = t; i < SELECT_BINS; i += BLOCK) h[i] = 0;
+    const u32 prefix = PASS == 0 ? 0u : S->prefix;
+    const int shift = select_shift(PASS), bits = select_bits(PASS);
+    __syncthreads();
+    u32 key[SELECT_ITEMS];
+#pragma unroll
+    for (int i = 0; i < SELECT_ITEMS; ++i) {
+        const long long idx = base + (long long)i * BLOCK + t;
+        key[i] = idx < n ? tcost[idx] : 0u;
+    }
+#pragma unroll
+    for (int i = 0; i < SELECT_ITEMS; ++i) {  // (whole waves run every step, for the ballots)
+        const long long idx = base + (long long)i * BLOCK + t;
+        // keys that share the digits decided so far; cost keys cluster, so the lanes of a wave that hold
+        // one digit count themselves with a single LDS atomic
+        const bool ok = idx < n && (PASS == 0 || (key[i] >> (shift + bits)) == prefix);
+        const u32 d = (key[i] >> shift) & ((1u << bits) - 1u);
+        const u64 same = prim::wave_same_digit_lanes(ok, d);
+        if (ok && (same & prim::lanemask_lt()) == 0) atomicAdd(&h[d], (u32)__popcll(same));
+    }
+    __syncthreads();
+    for (int i = t; i < SELECT_BINS; i += BLOCK) {
+        const u32 c = h[i];
+        if (c) atomicAdd(&S->hist[i], c);
+    }
+}
+
+// One workgroup: the digit in which the running count of the histogram reaches the budget; the
+// histogram is left zero for the next pass.
+template <int PASS>
+__global__ __launch_bounds__(BLOCK) void trunc_select_pick_kernel(SelectState* __restrict__ S,
+                                                                  const int* __restrict__ nrem) {
+    constexpr int PER = SELECT_BINS / BLOCK;
+    __shared__ u32 smem[prim::WAVES];
+    const int t = threadIdx.x;
+    const u32 below = PASS == 0 ? 0u : S->below, prefix = PASS == 0 ? 0u : S->prefix;
+    const u32 need = (u32)nrem[0] - below;  // >= 1: the key sought is among those counted
+    u32 c[PER], sum = 0, tot;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+        c[j] = S->hist[t * PER + j];
+        S->hist[t * PER + j] = 0;
+        sum += c[j];
+    }
+    u32 run = prim::block_exclusive_scan(sum, smem, tot);
+    if (run < need && need <= run + sum) {  // (exactly one thread, as tot >= need)
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            if (run < need && need <= run + c[j]) {
+                S->prefix = (prefix << select_bits(PASS)) | (u32)(t * PER + j);
+                S->below = below + run;
+                if (PASS == 2) S->keep = need - run;
+            }
+            run += c[j];
+        }
+    }
+}
+
+struct SelectTiePred {
+    const u32* tcost;
+    const SelectState* S;
+    __device__ bool operator()(int i) const { return tcost[i] == S->prefix; }
+};
+
+// Called for every gathered pair i; `tie`: its key is the threshold key, and `pos` pairs with that key
+// come before it in edge order.  The key's slot then holds the flag (1 = give the pair up).
+struct SelectFlagOut {
+    static constexpr bool WAVE_WIDE = true;
+    u32* tcost;
+    const SelectState* S;
+    __device__ void wave(int i, bool in_range, bool tie, int pos) const {
+        if (!in_range) return;
+        const u32 k = tcost[i];
+        tcost[i] = (k > S->prefix || (tie && (u32)pos >= S->keep)) ? 1u : 0u;
+    }
+};
 
 constexpr u64 ABID_NONE = ~0ull;
 

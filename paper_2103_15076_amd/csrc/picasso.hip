@@ -97,6 +97,7 @@ struct picasso_ctx {
     int* nrem = nullptr;
     int* matched = nullptr;
     int* segstart = nullptr;
+    SelectState* sel_state = nullptr;  // the budget step's radix select (one long run, see budget_step)
     int* mslots = nullptr;
     // pinned host staging
     // pinned host staging: read-back image of the header's front, then the upload image of the whole header
@@ -110,6 +111,7 @@ struct picasso_ctx {
     int opt_ahead = 1;     // a round's contraction and facet kernels are queued before the host has looked
     int opt_trunc_width = 0;  // test hook: keys per lane of the per-mesh budget search (0: as the sizes need)
     int opt_drop_degenerated = 0;  // output vertices that no output facet refers to are dropped
+    int opt_trunc_select = 1;      // a single mesh's long run in the budget step: 1 = radix select, 0 = sort
     hipEvent_t ev[2 * PICASSO_STATS_ROUNDS * PICASSO_ST_COUNT + 4];
     int n_ev = 0;
     hipEvent_t ev_total[2];
@@ -225,6 +227,7 @@ size_t carve(picasso_ctx* c, char* base, int64_t N, int64_t F, int32_t B) {
     x->voff[1] = cv.take<int>(b + 1);
     x->nrem = cv.take<int>(b);
     x->segstart = cv.take<int>(b);
+    x->sel_state = cv.take<SelectState>(1);
     x->mslots = cv.take<int>(b * MATCH_SLOTS * MATCH_PAD);
     x->abid = cv.take<u64>(n);
     x->arep = cv.take<int>(n);
@@ -424,8 +427,8 @@ int run_vertex_quadrics(picasso_ctx* c, hipStream_t s, const float* d_verts, int
         const u64* skey = where ? c->s0_key[1] : c->s0_key[0];
         const int tiles = (H + QR_TILE - 1) / QR_TILE;
         const KernelBracket timed(c, s, PICASSO_KERNEL_QUADRIC_ROWS, 0);
-        quadric_rows_kernel<<<(tiles + 7) / 8 * 8, BLOCK, 0, s>>>(c->vrec[0], d_verts, N, facet_planes(c), skey, H, fbits,
-                                                                 c->hist12_s0);
+        quadric_rows_kernel<<<tiles, BLOCK, 0, s>>>(c->vrec[0], d_verts, N, facet_planes(c), skey, H, fbits,
+                                                    c->hist12_s0);
     } else {
         quadric_rows_kernel<<<grid_for(N, 4096), BLOCK, 0, s>>>(c->vrec[0], d_verts, N, nullptr, nullptr, 0, 0,
                                                                c->hist12_s0);
@@ -550,6 +553,28 @@ int budget_step(picasso_ctx* c, hipStream_t s, Over over, int B, int ne, int vbi
         trunc_release_kernel<ABSORB><<<grid_for(n_over), BLOCK, 0, s>>>(tcost, c->val32[0], c->st, c->ekey, vbits,
                                                                         c->mate, B, counts, budgets, c->abid, guard);
         return PICASSO_OK;
+    }
+    if (B == 1 && !tb.on && c->opt_trunc_select) {
+        // one long run, ties in edge order: no sort, the threshold key is found by three histogram passes
+        u32* tcost = reinterpret_cast<u32*>(c->key64[0]);
+        TruncOutSplit to{c->ecost, tcost, c->val32[0]};
+        prim::compact(s, over, over, to, &c->st->ne, ne, c->tilesum, &c->st->trunc_n);
+        SelectState* S = c->sel_state;
+        constexpr int state_words = (int)(sizeof(SelectState) / sizeof(u32));
+        prim::fill_u32_kernel<<<grid_for(state_words), BLOCK, 0, s>>>(reinterpret_cast<u32*>(S), state_words, 0u);
+        const int hgrid = grid_for((n_over + SELECT_ITEMS - 1) / SELECT_ITEMS);
+        trunc_select_hist_kernel<0><<<hgrid, BLOCK, 0, s>>>(tcost, c->st, S);
+        trunc_select_pick_kernel<0><<<1, BLOCK, 0, s>>>(S, budgets);
+        trunc_select_hist_kernel<1><<<hgrid, BLOCK, 0, s>>>(tcost, c->st, S);
+        trunc_select_pick_kernel<1><<<1, BLOCK, 0, s>>>(S, budgets);
+        trunc_select_hist_kernel<2><<<hgrid, BLOCK, 0, s>>>(tcost, c->st, S);
+        trunc_select_pick_kernel<2><<<1, BLOCK, 0, s>>>(S, budgets);
+        const SelectTiePred tie{tcost, S};
+        const SelectFlagOut flag{tcost, S};
+        prim::compact(s, tie, tie, flag, &c->st->trunc_n, (int)n_over, c->tilesum, nullptr);
+        trunc_release_kernel<ABSORB><<<grid_for(n_over), BLOCK, 0, s>>>(tcost, c->val32[0], c->st, c->ekey, vbits,
+                                                                        c->mate, B, counts, budgets, c->abid, nullptr);
+        return hipGetLastError() == hipSuccess ? PICASSO_OK : PICASSO_ERR_HIP;
     }
     u64* k0 = c->key64[0];
     u64* k1 = c->key64[1];
@@ -1255,6 +1280,10 @@ int picasso_set_option(picasso_ctx* c, int option, int64_t value) {
         case PICASSO_OPT_DROP_DEGENERATED:
             if (value != 0 && value != 1) return PICASSO_ERR_INVALID_ARG;
             c->opt_drop_degenerated = (int)value;
+            return PICASSO_OK;
+        case PICASSO_OPT_TRUNC_SELECT:
+            if (value != 0 && value != 1) return PICASSO_ERR_INVALID_ARG;
+            c->opt_trunc_select = (int)value;
             return PICASSO_OK;
         case PICASSO_OPT_TRUNC_WIDTH:
             if (value != 0 && value != 4 && value != 8 && value != 16 && value != 32) return PICASSO_ERR_INVALID_ARG;

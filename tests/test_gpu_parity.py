@@ -189,12 +189,15 @@ def test_decimate_matches_oracle(pk, ctx, oracle, name, mesh, frac, max_rounds):
     assert_same_result(st, vo, fo, cid, ref)
 
 
-@pytest.mark.parametrize("block_max", [0, 1 << 15], ids=["sorted", "per_mesh_select"])
-def test_budget_step_both_ways(pk, ctx, oracle, block_max):
-    """The last round keeps a mesh's cheapest pairs either by a sort of all gathered pairs or by a
-    per-mesh selection; both against the oracle, on meshes with distinct costs and with nothing but ties,
+@pytest.mark.parametrize("block_max,radix_select", [(0, 0), (0, 1), (1 << 15, 1)],
+                         ids=["sorted", "histogram_passes", "per_mesh_search"])
+def test_budget_step_every_way(pk, ctx, oracle, block_max, radix_select):
+    """The last round keeps a mesh's cheapest pairs by a sort of all gathered pairs, by histogram passes
+    over their cost keys (a single mesh; the batch cases then take the sort) or by a search inside one
+    workgroup per mesh; all against the oracle, on meshes with distinct costs and with nothing but ties,
     alone and in a batch (budgets of 1 pair, of all but 1 pair, and in between)."""
     ctx.set_option(pk.PICASSO_OPT_TRUNC_BLOCK_MAX, block_max)
+    ctx.set_option(pk.PICASSO_OPT_TRUNC_SELECT, radix_select)
     try:
         for name, (V, F) in _small_meshes():
             for frac in (0.9, 0.55):
@@ -219,6 +222,34 @@ def test_budget_step_both_ways(pk, ctx, oracle, block_max):
             assert np.array_equal(cid.cpu().numpy(), ref["cluster_id"])
             assert np.array_equal(fo.cpu().numpy(), ref["facets"])
             assert np.array_equal(vo.cpu().numpy().view(np.uint32), ref["verts"].view(np.uint32))
+    finally:
+        ctx.set_option(pk.PICASSO_OPT_TRUNC_BLOCK_MAX, 1 << 15)
+        ctx.set_option(pk.PICASSO_OPT_TRUNC_SELECT, 1)
+
+
+def test_histogram_passes_of_the_budget_step_on_clustered_and_tied_cost_keys(pk, ctx, oracle):
+    """A single mesh whose last round forms more pairs than the per-mesh search is allowed here: the
+    cost key at the budget is found digit by digit.  Flat lattices (every cost key equal: the budget cuts
+    through one run of ties, in edge order), a lattice with a few creases (two key values), noisy
+    surfaces (keys spread over many leading digits) and the room (keys clustered in a few exponents),
+    each at budgets of 1 pair, about half the pairs, and all but 1."""
+    ctx.set_option(pk.PICASSO_OPT_TRUNC_BLOCK_MAX, 0)
+    try:
+        crease_v, crease_f = meshgen.flat_grid(40, 30, spacing=0.5)
+        crease_v = crease_v.copy()
+        crease_v[::7, 2] += 0.25
+        room_v, room_f = meshgen.room_scene(seed=77, n_boxes=6, spacing=0.25)
+        for name, (V, F) in (("flat", meshgen.flat_grid(64, 48, spacing=0.25)), ("creases", (crease_v, crease_f)),
+                             ("noisy", meshgen.noisy_grid(80, 70, seed=9)), ("sphere", meshgen.icosphere(5, seed=4)),
+                             ("room", (room_v, room_f))):
+            N = V.shape[0]
+            one_round = oracle.decimate(V, F, 1, max_rounds=1)
+            pairs = N - one_round["verts"].shape[0]       # pairs the first round would form without a budget
+            for remove in (1, pairs // 2, pairs - 1):
+                target = N - remove
+                print(f"histogram passes {name} N={N} pairs={pairs} target={target}", flush=True)
+                st, vo, fo, cid = ctx.picasso_decimate(dev(V), dev(F), target)
+                assert_same_result(st, vo, fo, cid, oracle.decimate(V, F, target))
     finally:
         ctx.set_option(pk.PICASSO_OPT_TRUNC_BLOCK_MAX, 1 << 15)
 
