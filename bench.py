@@ -66,8 +66,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="leave out the per-launch hipEvents of the roofline measurement")
-    ap.add_argument("--kernel-events-every", type=int, default=4, metavar="N",
-                    help="bracket the roofline kernel's launches with hipEvents in every N-th timed step (default 4)")
+    ap.add_argument("--kernel-events-every", type=int, default=10, metavar="N",
+                    help="bracket the roofline kernels' launches with hipEvents in every N-th timed step (default 10)")
     ap.add_argument("--copy-calib", action="store_true",
                     help="only run the plain copy kernel on 1 GiB (HBM yardstick / counter calibration)")
     ap.add_argument("--pool", type=int, default=0, metavar="C",

@@ -1178,7 +1178,8 @@ __global__ __launch_bounds__(BLOCK) void msd_scatter_kernel(Src kin, K* __restri
     static_assert(R % BLOCK == 0, "whole digits per thread");
     constexpr int TILE = BLOCK * ITEMS;
     __shared__ u32 h[R];  // per digit: this tile's count, then where the tile's keys of that digit go
-    __shared__ u32 first[R];
+    __shared__ u32 first[R + R / 32];  // (one unused word after every 32: a thread's PER consecutive digits, written by the scan
+                                       // below, then fall into different banks from its neighbours')
     __shared__ u32 smem[WAVES];
     const int n = load_count(n_ptr, n_host);
     const long long base = (long long)blockIdx.x * TILE;
@@ -1203,7 +1204,7 @@ __global__ __launch_bounds__(BLOCK) void msd_scatter_kernel(Src kin, K* __restri
         u32 run = block_exclusive_scan(sum, smem, tot);
 #pragma unroll
         for (int j = 0; j < PER; ++j) {
-            first[t * PER + j] = run;
+            first[(t * PER + j) + ((t * PER + j) >> 5)] = run;
             if (blockIdx.x == 0) starts[t * PER + j] = run;  // for the kernel that sorts the ranges
             run += c[j];
         }
@@ -1224,7 +1225,7 @@ __global__ __launch_bounds__(BLOCK) void msd_scatter_kernel(Src kin, K* __restri
     __syncthreads();
     for (int d = t; d < R; d += BLOCK) {
         const u32 c = h[d];
-        if (c) h[d] = first[d] + atomicAdd(&cursor[d], c);
+        if (c) h[d] = first[d + (d >> 5)] + atomicAdd(&cursor[d], c);
     }
     __syncthreads();
 #pragma unroll
