@@ -729,7 +729,9 @@ struct SelArgs {
     const u32* ecost;
     u64* vmin[3];
     int* mate;
-    int* list;              // live edges gathered for the tail
+    int* list;              // live edges gathered for the tail,
+    const u64* lkey;        // ... their keys
+    const u32* lcost;       // ... and cost keys, in the same order
     unsigned char* estate;  // per edge: 0 = live, 1 = retired (paired, or an end was paired)
     State* st;
     MeshTab mt;
@@ -937,9 +939,19 @@ struct LivePred {
     __device__ bool operator()(int e) const { return estate[e] == 0; }
 };
 
+// The gathered live edges, with their keys and cost keys beside them: the tail then reads three
+// contiguous arrays at once, not the list and then, through it, the edge arrays.
 struct LiveOut {
     int* list;
-    __device__ void operator()(int e, int pos) const { list[pos] = e; }
+    const u64* ekey;
+    const u32* ecost;
+    u64* lkey;
+    u32* lcost;
+    __device__ void operator()(int e, int pos) const {
+        list[pos] = e;
+        lkey[pos] = ekey[e];
+        lcost[pos] = ecost[e];
+    }
 };
 
 // Tail: once few edges are live, one workgroup finishes the matching with all
@@ -1027,8 +1039,8 @@ __global__ __launch_bounds__(TAIL_THREADS) void select_tail_kernel(SelArgs A) {
     __syncthreads();
     for (int i = tid; i < n; i += TAIL_THREADS) {
         const int e = A.list[i];
-        const u64 key = A.ekey[e];
-        L.prio[i] = A.tb.priority(A.ecost[e], e);
+        const u64 key = A.lkey[i];
+        L.prio[i] = A.tb.priority(A.lcost[i], e);
         L.su[i] = (unsigned short)tail_slot(L.vkey, (int)(key >> A.vbits));
         L.sv[i] = (unsigned short)tail_slot(L.vkey, (int)(key & vmask));
         L.lst[0][i] = (unsigned short)i;
@@ -1236,7 +1248,8 @@ __global__ __launch_bounds__(BLOCK) void trunc_rekey_kernel(const u32* __restric
 // registers (item r * TRUNC_THREADS + t sits in register r of thread t), finds the cost key of the
 // nrem-th smallest (cost key, edge) by a bitwise search on "how many keys are <= x" (a compare
 // and an add per key and bit; the keys that share the bits decided so far are dealt out again
-// once they are few, and in the end one wave decides the remaining bits without barriers), and
+// once they are few and then decided 8 bits at a time by counts per digit, and in the end one wave
+// decides the remaining bits without barriers), and
 // flags every pair
 // above that key and, among the pairs with exactly that key, all but the first ones in edge order.  A wide kernel then releases the
 // flagged pairs.  One compute unit does the whole search, so runs longer than TRUNC_BLOCK_CAP go
@@ -1270,7 +1283,8 @@ __global__ __launch_bounds__(TRUNC_THREADS) void trunc_block_kernel(u32* __restr
     __shared__ u32 wsum2[2][NW];
     __shared__ u32 cnt[R * NW];
     __shared__ u32 cbuf[TRUNC_NARROW_BLOCK];
-    __shared__ u32 found[2];
+    __shared__ u32 found[3];
+    __shared__ u32 dhist[256];  // the narrow phase's counts per 8-bit digit
     const int b = blockIdx.x;
     const int n = matched[b], keep = nrem[b];
     if (n <= keep) return;
@@ -1408,7 +1422,40 @@ __global__ __launch_bounds__(TRUNC_THREADS) void trunc_block_kernel(u32* __restr
             u32 k4[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) k4[j] = (u32)(j * TRUNC_THREADS + tid) < m ? cbuf[j * TRUNC_THREADS + tid] : 0xFFFFFFFFu;
-            steps(k4, four, m, outside, (u32)TRUNC_NARROW_WAVE);
+            (void)outside;
+            // ... and decided 8 bits at a time from here on: the candidates that share the decided bits are
+            // counted per digit in LDS (the lanes of a wave that hold one digit with a single atomic: where
+            // many pairs tie at the threshold they all hold the same), and the digit in which the running
+            // count reaches what is still wanted is found by one scan: three barriers per 8 bits instead
+            // of one per bit
+            while (bit >= 0 && upper - below > (u32)TRUNC_NARROW_WAVE) {
+                const int nb = bit >= 7 ? 8 : bit + 1, shift = bit + 1 - nb;
+                const u32 dec = decided_mask();
+                if (tid < 256) dhist[tid] = 0;
+                __syncthreads();
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {  // (whole waves, for the ballots)
+                    const bool ok = (u32)(j * TRUNC_THREADS + tid) < m && (k4[j] & dec) == prefix;
+                    const u32 dg = (k4[j] >> shift) & ((1u << nb) - 1u);
+                    const u64 same = prim::wave_same_digit_lanes(ok, dg);
+                    if (ok && (same & lt) == 0) atomicAdd(&dhist[dg], (u32)__popcll(same));
+                }
+                __syncthreads();
+                const u32 c = tid < 256 ? dhist[tid] : 0u;
+                u32 tot;
+                const u32 run = prim::wide_block_exclusive_scan<NW>(c, wsum, tot);
+                const u32 need = want - below;  // >= 1, and at most the number of candidates
+                if (tid < 256 && run < need && need <= run + c) {
+                    found[0] = (u32)tid;
+                    found[1] = run;
+                    found[2] = c;
+                }
+                __syncthreads();
+                prefix |= found[0] << shift;
+                below += found[1];
+                upper = below + found[2];
+                bit -= nb;
+            }
             if (bit >= 0) {
                 const u32 d2 = decided_mask();
                 finish_in_one_wave(

@@ -854,6 +854,8 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
         for (int i = 0; i < 3; ++i) sa.vmin[i] = c->vmin[i];
         sa.mate = c->mate;
         sa.list = c->list;
+        sa.lkey = c->key64[1];  // (the sort's arrays are free between the unique step and the budget step)
+        sa.lcost = c->val32[1];
         sa.estate = c->estate;
         sa.st = c->st;
         sa.mt = mt;
@@ -901,7 +903,7 @@ int decimate_impl(picasso_ctx* c, hipStream_t s, int B, const float* d_verts, co
             }
             sel_k += wide;
             LivePred lp{c->estate};
-            LiveOut lo{c->list};
+            LiveOut lo{c->list, c->ekey, c->ecost, c->key64[1], c->val32[1]};
             if (counts_live) prim::compact_scatter(s, lp, lo, &c->st->ne, ne_bound, c->tilesum, &c->st->live[0]);
             else prim::compact(s, lp, lp, lo, &c->st->ne, ne_bound, c->tilesum, &c->st->live[0]);
             // the kernel behind the tail tells the host that the tail's results are in the read-back area
