@@ -65,9 +65,11 @@ def test_random_meshes_and_options(oracle, chunk):
             seed = int(rng.choice([0, 0, 1 + int(rng.integers(0, 1 << 40))]))
             max_rounds = int(rng.choice([-1, -1, 1, 2]))
             block_max = int(rng.choice([0, 1 << 15]))
+            radix_select = int(rng.integers(0, 2))
             sub_batch, ahead, poll = int(rng.choice([1, 2, 16])), int(rng.integers(0, 2)), int(rng.choice([0, 1, 3]))
             print(f"random chunk={chunk} case={case} N={N} F={F.shape[0]} target={target} absorb={absorb} "
                   f"inverse={inverse} thr={thr} seed={seed} max_rounds={max_rounds} block_max={block_max} "
+                  f"radix_select={radix_select} "
                   f"sub_batch={sub_batch} ahead={ahead} poll={poll}", flush=True)
             ctx.set_option(pk.PICASSO_OPT_SUBROUND_BATCH, sub_batch)   # (how the host drives the round: no effect
             ctx.set_option(pk.PICASSO_OPT_LAUNCH_AHEAD, ahead)         #  on the result)
@@ -77,6 +79,7 @@ def test_random_meshes_and_options(oracle, chunk):
             ctx.set_option(pk.PICASSO_OPT_SHUFFLE_SEED, seed)
             ctx.set_option(pk.PICASSO_OPT_MAX_ROUNDS, max_rounds)
             ctx.set_option(pk.PICASSO_OPT_TRUNC_BLOCK_MAX, block_max)
+            ctx.set_option(pk.PICASSO_OPT_TRUNC_SELECT, radix_select)
             Fd = dev(F) if F.shape[0] else torch.empty((0, 3), dtype=torch.int32, device="cuda:0")
             st, vo, fo, cid = ctx.picasso_decimate(dev(V), Fd, target)
             ref = oracle.decimate(V, F, target, max_rounds=max_rounds, absorb=absorb, placement=int(inverse),
